@@ -1,0 +1,224 @@
+/*
+ * chn.h -- C ABI of libchn: the array kernels that a define-by-run training step issues to a
+ * NumPy-like GPU array layer, written for AMD MI355X (gfx950).
+ *
+ * The paper (Section "GPU Support by CuPy") describes a GPU ndarray that is a drop-in for
+ * numpy.ndarray -- standard dtypes, transpose, reshape, broadcasting -- on which two kinds of kernels
+ * run, element-wise maps and reductions (Section "Custom CUDA Kernels"), plus dense products backed
+ * by a BLAS.  A training step (Section "On Demand Graph Construction") calls these operation by
+ * operation: forward, then each recorded operation's backward once in reverse order, then the
+ * optimiser.  This header is that operation set as plain C calls.
+ *
+ * Conventions that hold for every call
+ *   - chn_array describes caller-owned DEVICE memory: shape plus BYTE strides (NumPy convention).
+ *     Descriptors live on the host, are read during the call and never retained.
+ *   - Strides must be non-negative multiples of the item size.  Stride 0 is allowed on inputs (a
+ *     broadcast view) and refused on outputs.
+ *   - The library allocates and frees nothing.  Calls that need scratch take a caller-owned device
+ *     workspace `ws` of at least chn_*_workspace_bytes(...) bytes, 256-byte aligned.
+ *   - Every call validates on the host, enqueues its kernels on `stream` (a hipStream_t; NULL = the
+ *     default stream) and returns without synchronising.  Device faults surface at the caller's next
+ *     synchronisation.
+ *   - Return value: CHN_OK or a negative chn_status; chn_last_error() gives a thread-local detail
+ *     string for the most recent failure.  A failing call enqueues nothing.
+ *   - Arrays with zero elements are valid: the call returns CHN_OK and does nothing, except that a
+ *     reduction over an empty axis writes the fold's identity.
+ *   - An output may alias an input only when both descriptors are identical (in-place update);
+ *     partially overlapping views are the caller's responsibility.
+ *   - Index values (labels, token ids) must be in range; the library does not check them on device.
+ */
+#ifndef CHN_H_
+#define CHN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHN_MAX_NDIM 8
+
+typedef enum { CHN_F32 = 0, CHN_BF16 = 1, CHN_I32 = 2, CHN_I64 = 3 } chn_dtype;
+
+typedef struct {
+  void *data;                    /* device pointer, caller-owned                         */
+  int32_t ndim;                  /* 0 .. CHN_MAX_NDIM                                    */
+  int64_t shape[CHN_MAX_NDIM];
+  int64_t strides[CHN_MAX_NDIM]; /* bytes                                                */
+  int32_t dtype;                 /* a chn_dtype                                          */
+} chn_array;
+
+typedef int32_t chn_status;
+enum {
+  CHN_OK = 0,
+  CHN_ERR_NULL = -1,      /* a required pointer is NULL                                  */
+  CHN_ERR_NDIM = -2,      /* ndim out of range or not what the call needs                */
+  CHN_ERR_DTYPE = -3,     /* unsupported or inconsistent dtype combination               */
+  CHN_ERR_SHAPE = -4,     /* not broadcastable / inner dimensions differ / wrong output  */
+  CHN_ERR_STRIDE = -5,    /* negative, misaligned, zero on an output, or unsupported     */
+  CHN_ERR_OP = -6,        /* unknown operation / epilogue code or wrong operand count    */
+  CHN_ERR_AXIS = -7,      /* axis out of range                                           */
+  CHN_ERR_WORKSPACE = -8, /* workspace missing, misaligned or too small                  */
+  CHN_ERR_LAUNCH = -9     /* the HIP runtime refused a launch                            */
+};
+
+typedef void *chn_stream; /* hipStream_t */
+
+/* ---- element-wise map with NumPy broadcasting -------------------------------------------------
+ * Section "Custom CUDA Kernels": an element-wise kernel applies one operation to every element;
+ * the figure "Example of a user-defined kernel" (my_mad, w = x*y + z) is CHN_OP_MAD.  Operands are
+ * right-aligned and size-1 dimensions repeat (Section "GPU Support by CuPy": broadcasting); every
+ * input must broadcast to the shape of `out`.  All inputs share one dtype (F32 or BF16); `out` is F32 or
+ * BF16; arithmetic is fp32; a BF16 store rounds to nearest even.  Any byte strides are accepted
+ * (transposed and sliced views included).  `scalars` is a host array read during the call. */
+typedef enum {
+  CHN_OP_COPY = 0,  /* out = x                      (1 input; also the dtype cast)               */
+  CHN_OP_ADD,       /* x + y                                                                     */
+  CHN_OP_SUB,       /* x - y                                                                     */
+  CHN_OP_MUL,       /* x * y                                                                     */
+  CHN_OP_MAD,       /* x * y + z                    (3 inputs)                                   */
+  CHN_OP_MAD_RELU,  /* max(0, x * y + z)            (3 inputs)                                   */
+  CHN_OP_RELU,      /* max(0, x)                                                                 */
+  CHN_OP_RELU_BWD,  /* gy * [y > 0]                 (inputs gy, y: the forward OUTPUT)           */
+  CHN_OP_GELU,      /* 0.5 x (1 + erf(x / sqrt 2))                                               */
+  CHN_OP_GELU_BWD,  /* gy * (Phi(z) + z phi(z))     (inputs gy, z: the forward input)            */
+  CHN_OP_SCALE,     /* s0 * x                       (1 scalar)                                   */
+  CHN_OP_AXPY,      /* x + s0 * y                   (1 scalar)                                   */
+  CHN_OP_ADD_RELU,  /* max(0, x + y)                (bias + activation)                          */
+  CHN_OP_ADD_GELU,  /* gelu(x + y)                                                               */
+  CHN_OP_FILL,      /* s0                           (0 inputs, 1 scalar)                         */
+  CHN_OP_SIGMOID,   /* 1 / (1 + exp(-x))                                                         */
+  CHN_OP_TANH,      /* tanh(x)                                                                   */
+  CHN_OP_SQRT,      /* sqrt(x)                                                                   */
+  CHN_OP_COUNT_
+} chn_op;
+
+chn_status chn_elementwise_broadcast(int op, int n_in, const chn_array *const *in,
+                                     const chn_array *out, const float *scalars, int n_scalars,
+                                     chn_stream stream);
+
+/* ---- reduction over one axis ------------------------------------------------------------------
+ * Section "Custom CUDA Kernels": a reduction kernel folds elements by a binary operator (sum folds
+ * by +).  `axis` may be negative (NumPy style).  `out` has the input's shape without the axis
+ * (keepdims = 0) or with it set to 1 (keepdims != 0).  Input F32 or BF16, any byte strides;
+ * accumulation is fp32 in a fixed order (bit-reproducible run to run); `out` F32 or BF16.
+ * An empty axis writes 0 (sum) or -inf (max). */
+typedef enum { CHN_REDUCE_SUM = 0, CHN_REDUCE_MAX = 1 } chn_reduce_op;
+
+size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis);
+chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
+                           const chn_array *out, void *ws, size_t ws_bytes, chn_stream stream);
+
+/* ---- dense product ------------------------------------------------------------------------------
+ * C = epilogue(alpha * A B + beta * C).  A (M,K), B (K,N), C (M,N) are 2-d views; a transposed
+ * operand is expressed by its strides, so the fully connected layer of the model-definition figure,
+ * y = x @ W.T + b with W (n_out, n_in), is A = x, B = the (n_in, n_out) view of W with strides
+ * swapped, epilogue CHN_EPI_BIAS.  A and B must each have one unit-stride dimension; C (and
+ * `preact_out`, `aux`) must be row-major (unit stride along N).
+ * dtypes: A,B F32 -> C F32 (fp32 matrix cores); A,B BF16 -> C BF16 or F32 (fp32 accumulation).
+ * Epilogue, applied to v = alpha*acc + beta*C in fp32 before the single final rounding:
+ *   BIAS       v + bias[n]                         bias (N,) F32
+ *   BIAS_RELU  max(0, v + bias[n])
+ *   BIAS_GELU  gelu(v + bias[n]); when preact_out != NULL it receives v + bias[n] (same dtype and
+ *              shape as C) for the backward pass
+ *   RELU_BWD   v * [aux > 0]                       aux (M,N): the retained forward output
+ *   GELU_BWD   v * gelu'(aux)                      aux (M,N): the retained pre-activation
+ * Unused optional arguments are NULL.  beta != 0 reads C before writing it. */
+typedef enum {
+  CHN_EPI_NONE = 0,
+  CHN_EPI_BIAS,
+  CHN_EPI_BIAS_RELU,
+  CHN_EPI_BIAS_GELU,
+  CHN_EPI_RELU_BWD,
+  CHN_EPI_GELU_BWD,
+  CHN_EPI_COUNT_
+} chn_epilogue;
+
+size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const chn_array *C);
+chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, float alpha,
+                    float beta, int epilogue, const chn_array *bias, const chn_array *aux,
+                    const chn_array *preact_out, void *ws, size_t ws_bytes, chn_stream stream);
+
+/* ---- LSTM cell ------------------------------------------------------------------------------------
+ * The paper names LSTMs as a motivating model class (Section "Introduction") and an RNN language
+ * model as an application; it prints no equations, so the cell is the textbook one without
+ * peepholes.  z (B,4H) holds the gate pre-activations x W + h U, gate blocks of width H along the
+ * last axis in the order i, f, g, o; `bias` (4H,) or NULL is added to z.
+ *   i,f,o = sigmoid(z_i,z_f,z_o)  g = tanh(z_g)  c = f*c_prev + i*g  h = o*tanh(c)
+ * c_prev, c, h are (B,H); `gates` (B,4H) or NULL receives the activated i,f,g,o for the backward.
+ * All F32, rows may be pitched (stride[0] free), unit stride along the last axis. */
+chn_status chn_lstm_fwd(const chn_array *z, const chn_array *bias, const chn_array *c_prev,
+                        const chn_array *c, const chn_array *h, const chn_array *gates,
+                        chn_stream stream);
+
+/* Backward from retained OUTPUTS only (Section "Function-wise Local Memory Usage Reduction": an
+ * operation such as tanh can compute its gradient from its output): inputs are the activated
+ * `gates`, c_prev, c, the incoming dh and dc_next (NULL = zero); outputs dz (B,4H), dc_prev (B,H).
+ *   do = dh*tanh(c)  dc = dc_next + dh*o*(1-tanh(c)^2)  di = dc*g  dg = dc*i  df = dc*c_prev
+ *   dc_prev = dc*f   dz_i = di*i(1-i)  dz_f = df*f(1-f)  dz_g = dg*(1-g^2)  dz_o = do*o(1-o) */
+chn_status chn_lstm_bwd(const chn_array *gates, const chn_array *c_prev, const chn_array *c,
+                        const chn_array *dh, const chn_array *dc_next, const chn_array *dz,
+                        const chn_array *dc_prev, chn_stream stream);
+
+/* ---- softmax cross-entropy ------------------------------------------------------------------------
+ * The classifier loss of the paper's MNIST example (Section "API Design"); textbook definition.
+ * logits (N,C) F32 or BF16, row-major; labels (N,) I32 or I64.  Rows whose label equals
+ * `ignore_label` contribute no loss and no gradient and are not counted in N_valid.
+ *   lse_n = max_c z + log sum_c exp(z - max)   loss_n = lse_n - z[n, label_n]
+ *   loss_mean = (1/N_valid) sum_n loss_n       (0 when N_valid = 0)
+ * loss_mean: 0-d (or 1-element) F32.  loss_rows, lse: (N,) F32 or NULL.
+ * Workspace: chn_softmax_ce_workspace_bytes(N). */
+size_t chn_softmax_ce_workspace_bytes(int64_t n_rows);
+chn_status chn_softmax_ce_fwd(const chn_array *logits, const chn_array *labels,
+                              int64_t ignore_label, const chn_array *loss_mean,
+                              const chn_array *loss_rows, const chn_array *lse, void *ws,
+                              size_t ws_bytes, chn_stream stream);
+
+/* dlogits[n,c] = (upstream / N_valid) * (softmax(z)[n,c] - [c == label_n]); ignored rows get 0.
+ * `lse` (N,) F32 from the forward, or NULL to recompute it.  dlogits (N,C) F32 or BF16 and may be
+ * the logits array itself (in place). */
+chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels,
+                              int64_t ignore_label, const chn_array *lse, float upstream,
+                              const chn_array *dlogits, void *ws, size_t ws_bytes,
+                              chn_stream stream);
+
+/* ---- optimiser --------------------------------------------------------------------------------------
+ * Stochastic gradient descent (Section "Background and Motivation" names it as the optimiser of the
+ * run phase): param <- param - lr * grad, no momentum, decay or clipping.  param, grad: F32,
+ * contiguous, same shape.  `lowp_copy` (BF16, same shape, contiguous) or NULL receives the updated
+ * value rounded to nearest even: the working copy of a mixed-precision master weight. */
+chn_status chn_sgd_update(const chn_array *param, const chn_array *grad, float lr,
+                          const chn_array *lowp_copy, chn_stream stream);
+
+/* The same update for `n` tensors (a whole model's parameter set) in as few launches as the kernel
+ * argument space allows (40 tensors per launch).  lowp_copies may be NULL, and so may its entries. */
+chn_status chn_sgd_update_multi(int n, const chn_array *const *params,
+                                const chn_array *const *grads, float lr,
+                                const chn_array *const *lowp_copies, chn_stream stream);
+
+/* ---- embedding ----------------------------------------------------------------------------------------
+ * Array indexing of the ndarray layer (Section "GPU Support by CuPy") as the language model uses it:
+ * out[n,:] = table[ids[n],:] (bit copies), and its gradient
+ * dtable[v,:] = (accumulate ? dtable[v,:] : 0) + sum over n with ids[n] == v of dout[n,:],
+ * summed in increasing n (bit-reproducible).  table/dtable (V,D) F32 or BF16 (fwd) / F32 (bwd),
+ * ids (N,) I32 or I64, out/dout (N,D); row-major with unit inner stride. */
+chn_status chn_embed_fwd(const chn_array *table, const chn_array *ids, const chn_array *out,
+                         chn_stream stream);
+chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_array *dtable,
+                         int accumulate, chn_stream stream);
+
+/* ---- diagnostics ---------------------------------------------------------------------------------------- */
+const char *chn_status_string(chn_status status);
+const char *chn_last_error(void); /* thread-local, valid until the next failing call on the thread */
+int chn_version(void);
+
+/* Host-only query used by tests: which kernel family a call would take, without launching.
+ * Returns a small integer code (>= 0) or a negative chn_status.  Element-wise families:
+ * 0 flat contiguous/row-broadcast, 1 pitched rows, 2 tile-transposed, 3 general strided. */
+int chn_elementwise_plan(int op, int n_in, const chn_array *const *in, const chn_array *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHN_H_ */

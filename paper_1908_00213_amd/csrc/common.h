@@ -1,0 +1,154 @@
+// Internal helpers shared by the libchn translation units (host validation + device utilities).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <cstdarg>
+#include <cstdio>
+
+#include "chn.h"
+
+namespace chn {
+
+// ---- error reporting -------------------------------------------------------------------------
+char *last_error_buffer();  // thread-local, 512 bytes
+
+inline chn_status fail(chn_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(last_error_buffer(), 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define CHN_TRY(expr)                        \
+  do {                                       \
+    chn_status _st = (expr);                 \
+    if (_st != CHN_OK) return _st;           \
+  } while (0)
+
+inline chn_status check_launch(const char *what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(CHN_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+  return CHN_OK;
+}
+
+// ---- descriptor helpers ------------------------------------------------------------------------
+inline int dtype_size(int dt) {
+  switch (dt) {
+    case CHN_F32: return 4;
+    case CHN_BF16: return 2;
+    case CHN_I32: return 4;
+    case CHN_I64: return 8;
+  }
+  return 0;
+}
+
+inline bool is_float(int dt) { return dt == CHN_F32 || dt == CHN_BF16; }
+inline bool is_index(int dt) { return dt == CHN_I32 || dt == CHN_I64; }
+
+inline int64_t numel(const chn_array *a) {
+  int64_t n = 1;
+  for (int d = 0; d < a->ndim; ++d) n *= a->shape[d];
+  return n;
+}
+
+// Checks pointer, ndim, dtype, shape >= 0, strides >= 0 and multiples of the item size.
+// `is_output` additionally refuses zero strides on dimensions longer than 1.
+chn_status validate(const chn_array *a, const char *name, bool is_output);
+
+// True when the view is C-contiguous (dimensions of size 1 may carry any stride).
+bool is_contiguous(const chn_array *a);
+
+// Requires a 2-d view with unit stride along the last axis; returns the row pitch in elements.
+chn_status row_major_2d(const chn_array *a, const char *name, int64_t *rows, int64_t *cols,
+                        int64_t *pitch);
+
+inline hipStream_t as_stream(chn_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline chn_status check_ws(const void *ws, size_t have, size_t need, const char *what) {
+  if (need == 0) return CHN_OK;
+  if (!ws) return fail(CHN_ERR_WORKSPACE, "%s: workspace of %zu bytes required, got NULL", what, need);
+  if (reinterpret_cast<uintptr_t>(ws) % 256)
+    return fail(CHN_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", what);
+  if (have < need)
+    return fail(CHN_ERR_WORKSPACE, "%s: workspace of %zu bytes required, got %zu", what, need, have);
+  return CHN_OK;
+}
+
+// ---- device-side scalar helpers ----------------------------------------------------------------
+#if defined(__HIPCC__)
+typedef uint16_t bf16_raw;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_raw b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Round to nearest, ties to even (NaN stays NaN).
+__device__ __forceinline__ bf16_raw f32_to_bf16(float f) {
+  __bf16 h = static_cast<__bf16>(f);
+  return __builtin_bit_cast(bf16_raw, h);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float *p) { return *p; }
+  static __device__ __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_raw> {
+  static __device__ __forceinline__ float load(const bf16_raw *p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_raw *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// 16-byte vector of T, converted to/from fp32 lanes.
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
+  __device__ __forceinline__ void set(int i, float v) { (&raw.x)[i] = v; }
+};
+template <> struct Vec16<bf16_raw> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_raw *p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void store(bf16_raw *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
+  __device__ __forceinline__ float get(int i) const {
+    uint32_t w = (&raw.x)[i >> 1];
+    return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  __device__ __forceinline__ void set(int i, float v) {
+    uint32_t b = f32_to_bf16(v);
+    uint32_t &w = (&raw.x)[i >> 1];
+    w = (i & 1) ? ((w & 0x0000ffffu) | (b << 16)) : ((w & 0xffff0000u) | b);
+  }
+};
+
+// gelu(x) = x * Phi(x); Phi written with erfc so that the negative tail keeps its relative accuracy.
+__device__ __forceinline__ float gelu_f(float x) {
+  return 0.5f * x * erfcf(-x * 0.70710678118654752440f);
+}
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  float Phi = 0.5f * erfcf(-x * 0.70710678118654752440f);
+  float phi = 0.39894228040143267794f * expf(-0.5f * x * x);
+  return Phi + x * phi;
+}
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// Wave-wide (64 lanes) sum / max by butterfly exchange.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+#endif  // __HIPCC__
+
+}  // namespace chn

@@ -1,0 +1,344 @@
+// chn_reduce_axis: fold + or max over one axis (Section "Custom CUDA Kernels": the reduction kernel).
+//
+// The host turns (view, axis) into one of three shapes of work:
+//   ROW  the reduced axis has unit stride and the kept dimensions merge into one pitched row index:
+//        a group of G lanes (8 / 64 / 256) walks each row with 16-byte loads, folds through wave
+//        butterflies (and LDS across the four waves of a block for G = 256);
+//   COL  the innermost kept dimension has unit stride: (outer O, reduced R, inner I).  Each thread
+//        owns one 16-byte column group, a block is 64 column groups x 4 row lanes, and R is split
+//        over S blocks whose fp32 partial sums land in the caller's workspace and are folded by a
+//        second launch of the same kernel -- no atomics, so results are bit-reproducible;
+//   GEN  anything else: one thread per output element.
+// A transposed 2-d view simply swaps ROW and COL.  HBM-bound: the input is read exactly once.
+#include "common.h"
+
+namespace chn {
+namespace {
+
+template <int OP> __device__ __forceinline__ float fold(float a, float b) {
+  if constexpr (OP == CHN_REDUCE_SUM) return a + b; else return fmaxf(a, b);
+}
+template <int OP> __device__ __forceinline__ float identity() {
+  if constexpr (OP == CHN_REDUCE_SUM) return 0.0f; else return -INFINITY;
+}
+
+enum { KIND_EMPTY = 0, KIND_ROW = 1, KIND_COL = 2, KIND_GEN = 3 };
+
+struct RPlan {
+  int kind = KIND_GEN;
+  int64_t len = 0, total_out = 0;
+  int64_t sR = 0;            // element stride of the reduced axis
+  // kept dimensions after dropping length-1 and merging
+  int nk = 0;
+  int64_t kshape[CHN_MAX_NDIM] = {0}, kstr[CHN_MAX_NDIM] = {0};
+  // COL
+  int64_t O = 1, I = 1, sO = 0;
+  int split = 1;
+  int64_t rows_per_split = 0;
+  bool vec = false;
+  size_t ws_bytes = 0;
+};
+
+constexpr int kColTX = 64, kColTY = 4;
+
+chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
+  CHN_TRY(validate(in, "in", false));
+  if (!is_float(in->dtype)) return fail(CHN_ERR_DTYPE, "reduce: input must be F32 or BF16");
+  if (in->ndim < 1) return fail(CHN_ERR_NDIM, "reduce: input needs at least one dimension");
+  int ax = axis < 0 ? axis + in->ndim : axis;
+  if (ax < 0 || ax >= in->ndim) return fail(CHN_ERR_AXIS, "reduce: axis %d out of range for ndim %d", axis, in->ndim);
+  const int isz = dtype_size(in->dtype);
+  p->len = in->shape[ax];
+  p->sR = p->len > 1 ? in->strides[ax] / isz : 1;
+  p->total_out = 1;
+  int nk = 0;
+  for (int d = 0; d < in->ndim; ++d) {
+    if (d == ax) continue;
+    p->total_out *= in->shape[d];
+    if (in->shape[d] == 1) continue;
+    p->kshape[nk] = in->shape[d];
+    p->kstr[nk] = in->strides[d] / isz;
+    ++nk;
+  }
+  if (p->total_out == 0 || p->len == 0) { p->kind = KIND_EMPTY; p->nk = nk; return CHN_OK; }
+  int w = 0;
+  for (int d = 1; d < nk; ++d) {
+    if (p->kstr[w] == p->kstr[d] * p->kshape[d]) {
+      p->kshape[w] *= p->kshape[d]; p->kstr[w] = p->kstr[d];
+    } else {
+      ++w; p->kshape[w] = p->kshape[d]; p->kstr[w] = p->kstr[d];
+    }
+  }
+  nk = nk == 0 ? 0 : w + 1;
+  p->nk = nk;
+  if ((p->sR == 1 || p->len == 1) && nk <= 1) { p->kind = KIND_ROW; return CHN_OK; }
+  if (nk >= 1 && nk <= 2 && p->kstr[nk - 1] == 1) {
+    p->kind = KIND_COL;
+    p->I = p->kshape[nk - 1];
+    p->O = nk == 2 ? p->kshape[0] : 1;
+    p->sO = nk == 2 ? p->kstr[0] : 0;
+    const int n = 16 / isz;
+    p->vec = reinterpret_cast<uintptr_t>(in->data) % 16 == 0 && p->I % n == 0 && p->sR % n == 0 && p->sO % n == 0;
+    const int64_t cols_per_block = (int64_t)kColTX * (p->vec ? n : 1);
+    const int64_t blocks_xy = ((p->I + cols_per_block - 1) / cols_per_block) * p->O;
+    int64_t s = (2048 + blocks_xy - 1) / blocks_xy;
+    int64_t max_s = p->len / 64;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    if (s > 1024) s = 1024;
+    p->split = (int)s;
+    p->rows_per_split = (p->len + s - 1) / s;
+    p->split = (int)((p->len + p->rows_per_split - 1) / p->rows_per_split);
+    p->ws_bytes = p->split > 1 ? (size_t)p->split * p->O * p->I * sizeof(float) : 0;
+    return CHN_OK;
+  }
+  p->kind = KIND_GEN;
+  return CHN_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename Tout>
+__global__ __launch_bounds__(256) void fill_kernel(Tout *out, int64_t n, float v) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) Elem<Tout>::store(out + i, v);
+}
+
+// ROW: G lanes per row, 256 / G rows per block.
+template <int OP, typename Tin, typename Tout, int G, bool VEC>
+__global__ __launch_bounds__(256) void reduce_row_kernel(const Tin *in, Tout *out, int64_t rows, int64_t len, int64_t pitch) {
+  constexpr int RPB = 256 / G;
+  const int g = threadIdx.x % G;
+  const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / G;
+  float acc[4] = {identity<OP>(), identity<OP>(), identity<OP>(), identity<OP>()};
+  if (row < rows) {
+    const Tin *p = in + row * pitch;
+    if constexpr (VEC) {
+      constexpr int N = Vec16<Tin>::N;
+      const int64_t nvec = len / N;
+      int64_t v = g;
+      for (; v + 3 * G < nvec; v += 4 * G) {
+        Vec16<Tin> x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u].load(p + (v + u * G) * N);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int i = 0; i < N; ++i) acc[u] = fold<OP>(acc[u], x[u].get(i));
+      }
+      for (; v < nvec; v += G) {
+        Vec16<Tin> x;
+        x.load(p + v * N);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[0] = fold<OP>(acc[0], x.get(i));
+      }
+      for (int64_t c = nvec * N + g; c < len; c += G) acc[1] = fold<OP>(acc[1], Elem<Tin>::load(p + c));
+    } else {
+      int64_t c = g;
+      for (; c + 3 * G < len; c += 4 * G) {
+        float x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = Elem<Tin>::load(p + c + u * G);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[u] = fold<OP>(acc[u], x[u]);
+      }
+      for (; c < len; c += G) acc[0] = fold<OP>(acc[0], Elem<Tin>::load(p + c));
+    }
+  }
+  float a = fold<OP>(fold<OP>(acc[0], acc[1]), fold<OP>(acc[2], acc[3]));
+  constexpr int W = G < 64 ? G : 64;
+#pragma unroll
+  for (int o = W / 2; o > 0; o >>= 1) a = fold<OP>(a, __shfl_xor(a, o, 64));
+  if constexpr (G == 256) {
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0 && row < rows)
+      Elem<Tout>::store(out + row, fold<OP>(fold<OP>(part[0], part[1]), fold<OP>(part[2], part[3])));
+  } else {
+    if (g == 0 && row < rows) Elem<Tout>::store(out + row, a);
+  }
+}
+
+// COL: out[o, i] (or partial[s, o, i]) = fold over r in this block's slice of in[o*sO + r*sR + i].
+template <int OP, typename Tin, typename Tout, bool VEC>
+__global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *out, int64_t R, int64_t I, int64_t sO, int64_t sR,
+                                                         int64_t rows_per_split, int64_t out_split_stride) {
+  constexpr int N = VEC ? Vec16<Tin>::N : 1;
+  const int tx = threadIdx.x % kColTX, ty = threadIdx.x / kColTX;
+  const int64_t col = ((int64_t)blockIdx.x * kColTX + tx) * N;
+  const int64_t o = blockIdx.z;
+  const int64_t r_begin = (int64_t)blockIdx.y * rows_per_split;
+  int64_t r_end = r_begin + rows_per_split;
+  if (r_end > R) r_end = R;
+  float acc[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) acc[i] = identity<OP>();
+  if (col < I) {
+    const Tin *p = in + o * sO + col;
+    int64_t r = r_begin + ty;
+    if constexpr (VEC) {
+      for (; r + 3 * kColTY < r_end; r += 4 * kColTY) {
+        Vec16<Tin> x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u].load(p + (r + u * kColTY) * sR);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int i = 0; i < N; ++i) acc[i] = fold<OP>(acc[i], x[u].get(i));
+      }
+      for (; r < r_end; r += kColTY) {
+        Vec16<Tin> x;
+        x.load(p + r * sR);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = fold<OP>(acc[i], x.get(i));
+      }
+    } else {
+      for (; r + 3 * kColTY < r_end; r += 4 * kColTY) {
+        float x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) x[u] = Elem<Tin>::load(p + (r + u * kColTY) * sR);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[0] = fold<OP>(acc[0], x[u]);
+      }
+      for (; r < r_end; r += kColTY) acc[0] = fold<OP>(acc[0], Elem<Tin>::load(p + r * sR));
+    }
+  }
+  __shared__ float part[kColTY][kColTX * N + 1];
+#pragma unroll
+  for (int i = 0; i < N; ++i) part[ty][tx * N + i] = acc[i];
+  __syncthreads();
+  if (ty == 0 && col < I) {
+    Tout *q = out + (int64_t)blockIdx.y * out_split_stride + o * I + col;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      float a = part[0][tx * N + i];
+#pragma unroll
+      for (int y = 1; y < kColTY; ++y) a = fold<OP>(a, part[y][tx * N + i]);
+      Elem<Tout>::store(q + i, a);
+    }
+  }
+}
+
+struct GenArgs {
+  int nk;
+  int64_t kshape[CHN_MAX_NDIM], kstr[CHN_MAX_NDIM];
+  int64_t len, sR, total_out;
+};
+
+template <int OP, typename Tin, typename Tout>
+__global__ __launch_bounds__(256) void reduce_gen_kernel(const Tin *in, Tout *out, GenArgs a) {
+  int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= a.total_out) return;
+  int64_t off = 0, rem = e;
+  for (int d = a.nk - 1; d >= 0; --d) { off += (rem % a.kshape[d]) * a.kstr[d]; rem /= a.kshape[d]; }
+  float acc = identity<OP>();
+  for (int64_t r = 0; r < a.len; ++r) acc = fold<OP>(acc, Elem<Tin>::load(in + off + r * a.sR));
+  Elem<Tout>::store(out + e, acc);
+}
+
+template <int OP, typename Tin, typename Tout>
+chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64_t R, int64_t I, int64_t sO, int64_t sR,
+                      int split, int64_t rps, int64_t split_stride, bool vec, hipStream_t st) {
+  const int n = vec ? 16 / (int)sizeof(Tin) : 1;
+  const int64_t cpb = (int64_t)kColTX * n;
+  dim3 grid((unsigned)((I + cpb - 1) / cpb), (unsigned)split, (unsigned)O);
+  if (O > 65535) return fail(CHN_ERR_SHAPE, "reduce: outer extent %lld too large for the column kernel", (long long)O);
+  if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  (void)p;
+  return check_launch("reduce col");
+}
+
+template <int OP, typename Tin, typename Tout>
+chn_status launch(const RPlan &p, const chn_array *in, const chn_array *out, void *ws, hipStream_t st) {
+  const Tin *src = static_cast<const Tin *>(in->data);
+  Tout *dst = static_cast<Tout *>(out->data);
+  if (p.kind == KIND_ROW) {
+    const int64_t rows = p.nk == 1 ? p.kshape[0] : 1;
+    const int64_t pitch = p.nk == 1 ? p.kstr[0] : 0;
+    const int n = 16 / (int)sizeof(Tin);
+    const bool vec = reinterpret_cast<uintptr_t>(src) % 16 == 0 && pitch % n == 0 && p.len >= 4 * n;
+#define CHN_ROW(G)                                                                                          \
+  do {                                                                                                      \
+    const int64_t blocks = (rows + (256 / G) - 1) / (256 / G);                                              \
+    if (blocks > 0x7fffffff) return fail(CHN_ERR_SHAPE, "reduce: too many rows");                           \
+    if (vec) hipLaunchKernelGGL((reduce_row_kernel<OP, Tin, Tout, G, true>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, rows, p.len, pitch); \
+    else hipLaunchKernelGGL((reduce_row_kernel<OP, Tin, Tout, G, false>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, rows, p.len, pitch);    \
+  } while (0)
+    if (p.len >= 2048 || rows < 512) CHN_ROW(256);
+    else if (p.len > 64) CHN_ROW(64);
+    else CHN_ROW(8);
+#undef CHN_ROW
+    return check_launch("reduce row");
+  }
+  if (p.kind == KIND_COL) {
+    if (p.split == 1)
+      return launch_col<OP, Tin, Tout>(src, dst, p, p.O, p.len, p.I, p.sO, p.sR, 1, p.len, 0, p.vec, st);
+    float *part = static_cast<float *>(ws);
+    const int64_t OI = p.O * p.I;
+    CHN_TRY((launch_col<OP, Tin, float>(src, part, p, p.O, p.len, p.I, p.sO, p.sR, p.split, p.rows_per_split, OI, p.vec, st)));
+    return launch_col<OP, float, Tout>(part, dst, p, 1, p.split, OI, 0, OI, 1, p.split, 0, OI % 4 == 0, st);
+  }
+  GenArgs a{};
+  a.nk = p.nk; a.len = p.len; a.sR = p.sR; a.total_out = p.total_out;
+  for (int d = 0; d < p.nk; ++d) { a.kshape[d] = p.kshape[d]; a.kstr[d] = p.kstr[d]; }
+  const int64_t blocks = (p.total_out + 255) / 256;
+  if (blocks > 0x7fffffff) return fail(CHN_ERR_SHAPE, "reduce: output too large");
+  hipLaunchKernelGGL((reduce_gen_kernel<OP, Tin, Tout>), dim3((unsigned)blocks), dim3(256), 0, st, src, dst, a);
+  return check_launch("reduce general");
+}
+
+template <typename Tin, typename Tout>
+chn_status launch_op(int op, const RPlan &p, const chn_array *in, const chn_array *out, void *ws, hipStream_t st) {
+  if (op == CHN_REDUCE_SUM) return launch<CHN_REDUCE_SUM, Tin, Tout>(p, in, out, ws, st);
+  return launch<CHN_REDUCE_MAX, Tin, Tout>(p, in, out, ws, st);
+}
+
+}  // namespace
+}  // namespace chn
+
+extern "C" {
+
+size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis) {
+  chn::RPlan p;
+  if (chn::make_rplan(in, axis, &p) != CHN_OK) return 0;
+  return p.kind == chn::KIND_COL ? p.ws_bytes : 0;
+}
+
+chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                           void *ws, size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  if (op != CHN_REDUCE_SUM && op != CHN_REDUCE_MAX) return fail(CHN_ERR_OP, "reduce: unknown op %d", op);
+  RPlan p;
+  CHN_TRY(make_rplan(in, axis, &p));
+  CHN_TRY(validate(out, "out", true));
+  if (!is_float(out->dtype)) return fail(CHN_ERR_DTYPE, "reduce: out must be F32 or BF16");
+  const int ax = axis < 0 ? axis + in->ndim : axis;
+  const int ond = keepdims ? in->ndim : in->ndim - 1;
+  if (out->ndim != ond) return fail(CHN_ERR_SHAPE, "reduce: out has ndim %d, expected %d", out->ndim, ond);
+  for (int d = 0, od = 0; d < in->ndim; ++d) {
+    if (d == ax) {
+      if (keepdims) { if (out->shape[od] != 1) return fail(CHN_ERR_SHAPE, "reduce: kept axis must have length 1"); ++od; }
+      continue;
+    }
+    if (out->shape[od] != in->shape[d]) return fail(CHN_ERR_SHAPE, "reduce: out dimension %d has length %lld, expected %lld", od, (long long)out->shape[od], (long long)in->shape[d]);
+    ++od;
+  }
+  if (!is_contiguous(out)) return fail(CHN_ERR_STRIDE, "reduce: out must be contiguous");
+  if (p.total_out == 0) return CHN_OK;
+  hipStream_t st = as_stream(stream);
+  if (p.kind == KIND_EMPTY) {
+    const float v = op == CHN_REDUCE_SUM ? 0.0f : -INFINITY;
+    const unsigned blocks = (unsigned)((p.total_out + 255) / 256);
+    if (out->dtype == CHN_F32) hipLaunchKernelGGL((fill_kernel<float>), dim3(blocks), dim3(256), 0, st, static_cast<float *>(out->data), p.total_out, v);
+    else hipLaunchKernelGGL((fill_kernel<bf16_raw>), dim3(blocks), dim3(256), 0, st, static_cast<bf16_raw *>(out->data), p.total_out, v);
+    return check_launch("reduce fill");
+  }
+  if (p.kind == KIND_COL) CHN_TRY(check_ws(ws, ws_bytes, p.ws_bytes, "reduce"));
+  if (in->dtype == CHN_F32 && out->dtype == CHN_F32) return launch_op<float, float>(op, p, in, out, ws, st);
+  if (in->dtype == CHN_BF16 && out->dtype == CHN_F32) return launch_op<bf16_raw, float>(op, p, in, out, ws, st);
+  if (in->dtype == CHN_BF16 && out->dtype == CHN_BF16) return launch_op<bf16_raw, bf16_raw>(op, p, in, out, ws, st);
+  return launch_op<float, bf16_raw>(op, p, in, out, ws, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,322 @@
+// chn_softmax_ce_fwd / chn_softmax_ce_bwd: row-wise softmax cross-entropy (textbook definition; the
+// paper only names the classification task, Section "API Design").
+//
+// A group of G lanes (8 / 64 / 256 by row length) owns one row.  The forward pass reads the row once
+// with 16-byte loads, keeping a running (max, sum of exp) pair per lane that is merged through wave
+// butterflies (and LDS for G = 256); a second one-block kernel folds the per-row losses into the mean
+// in a fixed order.  The backward pass reads the row (twice when the log-sum-exp was not retained:
+// the second read comes from L2) and writes the gradient once.  HBM-bound for wide rows.
+#include "common.h"
+
+namespace chn {
+namespace {
+
+struct MS { float m, s; };  // running max and sum of exp(x - m)
+
+__device__ __forceinline__ MS ms_merge(MS a, MS b) {
+  const float m = fmaxf(a.m, b.m);
+  if (m == -INFINITY) return MS{m, 0.0f};
+  return MS{m, a.s * expf(a.m - m) + b.s * expf(b.m - m)};
+}
+
+template <int G>
+__device__ __forceinline__ MS group_merge(MS v, MS *smem /* [4] per block, G==256 only */) {
+  constexpr int W = G < 64 ? G : 64;
+#pragma unroll
+  for (int o = W / 2; o > 0; o >>= 1) {
+    MS other{__shfl_xor(v.m, o, 64), __shfl_xor(v.s, o, 64)};
+    v = ms_merge(v, other);
+  }
+  if constexpr (G == 256) {
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = ms_merge(ms_merge(smem[0], smem[1]), ms_merge(smem[2], smem[3]));
+    __syncthreads();
+  }
+  return v;
+}
+
+// Running (max, sum exp) of one row slice owned by lane g of G.
+template <typename T, int G, bool VEC>
+__device__ __forceinline__ MS row_scan(const T *p, int64_t C, int g) {
+  MS acc{-INFINITY, 0.0f};
+  if constexpr (VEC) {
+    constexpr int N = Vec16<T>::N;
+    const int64_t nvec = C / N;
+    for (int64_t v = g; v < nvec; v += G) {
+      Vec16<T> x;
+      x.load(p + v * N);
+      float mx = x.get(0);
+#pragma unroll
+      for (int i = 1; i < N; ++i) mx = fmaxf(mx, x.get(i));
+      const float m = fmaxf(acc.m, mx);
+      float s = acc.s * expf(acc.m - m);
+#pragma unroll
+      for (int i = 0; i < N; ++i) s += expf(x.get(i) - m);
+      acc = MS{m, s};
+    }
+    for (int64_t c = nvec * N + g; c < C; c += G) {
+      const float x = Elem<T>::load(p + c);
+      const float m = fmaxf(acc.m, x);
+      acc = MS{m, acc.s * expf(acc.m - m) + expf(x - m)};
+    }
+  } else {
+    for (int64_t c = g; c < C; c += G) {
+      const float x = Elem<T>::load(p + c);
+      const float m = fmaxf(acc.m, x);
+      acc = MS{m, acc.s * expf(acc.m - m) + expf(x - m)};
+    }
+  }
+  return acc;
+}
+
+template <typename T, typename L, int G, bool VEC>
+__global__ __launch_bounds__(256) void sce_fwd_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
+                                                      int64_t ignore, float *loss_rows, float *lse_out) {
+  __shared__ MS smem[4];
+  const int g = threadIdx.x % G;
+  int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+  const bool live = row < N;
+  if (!live) row = N - 1;  // keep every lane in the collectives; results are discarded
+  const T *p = z + row * pitch;
+  MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
+  if (g == 0 && live) {
+    const float lse = v.m + logf(v.s);
+    const int64_t t = (int64_t)labels[row];
+    if (lse_out) lse_out[row] = lse;
+    loss_rows[row] = t == ignore ? 0.0f : lse - Elem<T>::load(p + t);
+  }
+}
+
+// loss_mean = sum of loss_rows over valid rows / number of valid rows, fixed order.
+template <typename L>
+__global__ __launch_bounds__(1024) void sce_mean_kernel(const float *loss_rows, const L *labels, int64_t N, int64_t ignore,
+                                                        float *loss_mean) {
+  __shared__ float ssum[16];
+  __shared__ int scnt[16];
+  float s = 0.0f;
+  int cnt = 0;
+  for (int64_t n = threadIdx.x; n < N; n += 1024)
+    if ((int64_t)labels[n] != ignore) { s += loss_rows[n]; ++cnt; }
+  s = wave_sum(s);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if ((threadIdx.x & 63) == 0) { ssum[threadIdx.x >> 6] = s; scnt[threadIdx.x >> 6] = cnt; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.0f;
+    int c = 0;
+    for (int w = 0; w < 16; ++w) { t += ssum[w]; c += scnt[w]; }
+    *loss_mean = c > 0 ? t / (float)c : 0.0f;
+  }
+}
+
+// scale = upstream / N_valid (0 when no row is valid)
+template <typename L>
+__global__ __launch_bounds__(1024) void sce_scale_kernel(const L *labels, int64_t N, int64_t ignore, float upstream, float *scale) {
+  __shared__ int scnt[16];
+  int cnt = 0;
+  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += ((int64_t)labels[n] != ignore) ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if ((threadIdx.x & 63) == 0) scnt[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int c = 0;
+    for (int w = 0; w < 16; ++w) c += scnt[w];
+    *scale = c > 0 ? upstream / (float)c : 0.0f;
+  }
+}
+
+template <typename T, typename TO, typename L, int G, bool VEC>
+__global__ __launch_bounds__(256) void sce_bwd_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
+                                                      int64_t ignore, const float *lse_in, const float *scale_ptr,
+                                                      TO *dz, int64_t dpitch) {
+  __shared__ MS smem[4];
+  const int g = threadIdx.x % G;
+  int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+  const bool live = row < N;
+  if (!live) row = N - 1;
+  const T *p = z + row * pitch;
+  float lse;
+  if (lse_in) {
+    lse = lse_in[row];
+  } else {
+    MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
+    lse = v.m + logf(v.s);
+  }
+  if (!live) return;
+  const int64_t t = (int64_t)labels[row];
+  const float scale = t == ignore ? 0.0f : *scale_ptr;
+  TO *q = dz + row * dpitch;
+  if constexpr (VEC) {
+    constexpr int NI = Vec16<T>::N, NO = Vec16<TO>::N;
+    constexpr int E = NI > NO ? NI : NO;  // elements per step: whole 16-byte vectors on both sides
+    const int64_t nstep = C / E;
+    for (int64_t v = g; v < nstep; v += G) {
+      Vec16<T> x[E / NI];
+      Vec16<TO> y[E / NO];
+#pragma unroll
+      for (int i = 0; i < E / NI; ++i) x[i].load(p + v * E + i * NI);
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int64_t c = v * E + i;
+        float pr = scale == 0.0f ? 0.0f : expf(x[i / NI].get(i % NI) - lse);
+        y[i / NO].set(i % NO, scale * (pr - (c == t ? 1.0f : 0.0f)));
+      }
+#pragma unroll
+      for (int i = 0; i < E / NO; ++i) y[i].store(q + v * E + i * NO);
+    }
+    for (int64_t c = nstep * E + g; c < C; c += G) {
+      float pr = scale == 0.0f ? 0.0f : expf(Elem<T>::load(p + c) - lse);
+      Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
+    }
+  } else {
+    for (int64_t c = g; c < C; c += G) {
+      float pr = scale == 0.0f ? 0.0f : expf(Elem<T>::load(p + c) - lse);
+      Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
+    }
+  }
+}
+
+struct Common {
+  int64_t N = 0, C = 0, pitch = 0;
+  int G = 256;
+  bool vec = false;
+};
+
+chn_status check_common(const chn_array *logits, const chn_array *labels, Common *c) {
+  CHN_TRY(validate(logits, "logits", false));
+  CHN_TRY(validate(labels, "labels", false));
+  if (!is_float(logits->dtype)) return fail(CHN_ERR_DTYPE, "softmax_ce: logits must be F32 or BF16");
+  if (!is_index(labels->dtype)) return fail(CHN_ERR_DTYPE, "softmax_ce: labels must be I32 or I64");
+  CHN_TRY(row_major_2d(logits, "logits", &c->N, &c->C, &c->pitch));
+  if (labels->ndim != 1 || labels->shape[0] != c->N)
+    return fail(CHN_ERR_SHAPE, "softmax_ce: labels must have shape (%lld,)", (long long)c->N);
+  if (!is_contiguous(labels)) return fail(CHN_ERR_STRIDE, "softmax_ce: labels must be contiguous");
+  if (c->N > 0 && c->C == 0) return fail(CHN_ERR_SHAPE, "softmax_ce: zero classes");
+  c->G = c->C >= 2048 ? 256 : (c->C > 32 ? 64 : 8);
+  const int n = 16 / dtype_size(logits->dtype);
+  c->vec = reinterpret_cast<uintptr_t>(logits->data) % 16 == 0 && c->pitch % n == 0;
+  return CHN_OK;
+}
+
+chn_status check_rows_f32(const chn_array *a, const char *name, int64_t N) {
+  CHN_TRY(validate(a, name, true));
+  if (a->dtype != CHN_F32) return fail(CHN_ERR_DTYPE, "softmax_ce: %s must be F32", name);
+  if (a->ndim != 1 || a->shape[0] != N) return fail(CHN_ERR_SHAPE, "softmax_ce: %s must have shape (%lld,)", name, (long long)N);
+  if (!is_contiguous(a)) return fail(CHN_ERR_STRIDE, "softmax_ce: %s must be contiguous", name);
+  return CHN_OK;
+}
+
+inline size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
+template <typename T, typename L>
+void launch_fwd(const Common &c, const chn_array *logits, const chn_array *labels, int64_t ignore, float *rows, float *lse, hipStream_t st) {
+  const T *z = static_cast<const T *>(logits->data);
+  const L *t = static_cast<const L *>(labels->data);
+#define CHN_FWD(G, V) hipLaunchKernelGGL((sce_fwd_kernel<T, L, G, V>), dim3((unsigned)((c.N + 256 / G - 1) / (256 / G))), dim3(256), 0, st, z, c.pitch, t, c.N, c.C, ignore, rows, lse)
+  if (c.G == 256) { if (c.vec) CHN_FWD(256, true); else CHN_FWD(256, false); }
+  else if (c.G == 64) { if (c.vec) CHN_FWD(64, true); else CHN_FWD(64, false); }
+  else CHN_FWD(8, false);
+#undef CHN_FWD
+}
+
+template <typename T, typename TO, typename L>
+void launch_bwd(const Common &c, const chn_array *logits, const chn_array *labels, int64_t ignore, const float *lse,
+                const float *scale, const chn_array *dl, int64_t dpitch, bool vec, hipStream_t st) {
+  const T *z = static_cast<const T *>(logits->data);
+  const L *t = static_cast<const L *>(labels->data);
+  TO *d = static_cast<TO *>(dl->data);
+#define CHN_BWD(G, V) hipLaunchKernelGGL((sce_bwd_kernel<T, TO, L, G, V>), dim3((unsigned)((c.N + 256 / G - 1) / (256 / G))), dim3(256), 0, st, z, c.pitch, t, c.N, c.C, ignore, lse, scale, d, dpitch)
+  if (c.G == 256) { if (vec) CHN_BWD(256, true); else CHN_BWD(256, false); }
+  else if (c.G == 64) { if (vec) CHN_BWD(64, true); else CHN_BWD(64, false); }
+  else CHN_BWD(8, false);
+#undef CHN_BWD
+}
+
+}  // namespace
+}  // namespace chn
+
+extern "C" {
+
+size_t chn_softmax_ce_workspace_bytes(int64_t n_rows) {
+  if (n_rows < 0) n_rows = 0;
+  return 256 + chn::round256((size_t)n_rows * sizeof(float));
+}
+
+chn_status chn_softmax_ce_fwd(const chn_array *logits, const chn_array *labels, int64_t ignore_label,
+                              const chn_array *loss_mean, const chn_array *loss_rows,
+                              const chn_array *lse, void *ws, size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  Common c;
+  CHN_TRY(check_common(logits, labels, &c));
+  CHN_TRY(validate(loss_mean, "loss_mean", true));
+  if (loss_mean->dtype != CHN_F32 || numel(loss_mean) != 1)
+    return fail(CHN_ERR_SHAPE, "softmax_ce: loss_mean must be a single F32 value");
+  if (loss_rows) CHN_TRY(check_rows_f32(loss_rows, "loss_rows", c.N));
+  if (lse) CHN_TRY(check_rows_f32(lse, "lse", c.N));
+  float *rows = loss_rows ? static_cast<float *>(loss_rows->data) : nullptr;
+  if (!rows && c.N > 0) {
+    CHN_TRY(check_ws(ws, ws_bytes, chn_softmax_ce_workspace_bytes(c.N), "softmax_ce_fwd"));
+    rows = reinterpret_cast<float *>(static_cast<char *>(ws) + 256);
+  }
+  hipStream_t st = as_stream(stream);
+  if (c.N > 0) {
+    float *l = lse ? static_cast<float *>(lse->data) : nullptr;
+    const bool i32 = labels->dtype == CHN_I32;
+    if (logits->dtype == CHN_F32) {
+      if (i32) launch_fwd<float, int32_t>(c, logits, labels, ignore_label, rows, l, st);
+      else launch_fwd<float, int64_t>(c, logits, labels, ignore_label, rows, l, st);
+    } else {
+      if (i32) launch_fwd<bf16_raw, int32_t>(c, logits, labels, ignore_label, rows, l, st);
+      else launch_fwd<bf16_raw, int64_t>(c, logits, labels, ignore_label, rows, l, st);
+    }
+    CHN_TRY(check_launch("softmax_ce_fwd rows"));
+  }
+  float *lm = static_cast<float *>(loss_mean->data);
+  if (labels->dtype == CHN_I32)
+    hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, ignore_label, lm);
+  else
+    hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, ignore_label, lm);
+  return check_launch("softmax_ce_fwd mean");
+}
+
+chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels, int64_t ignore_label,
+                              const chn_array *lse, float upstream, const chn_array *dlogits,
+                              void *ws, size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  Common c;
+  CHN_TRY(check_common(logits, labels, &c));
+  CHN_TRY(validate(dlogits, "dlogits", true));
+  if (!is_float(dlogits->dtype)) return fail(CHN_ERR_DTYPE, "softmax_ce: dlogits must be F32 or BF16");
+  int64_t dn, dc, dpitch;
+  CHN_TRY(row_major_2d(dlogits, "dlogits", &dn, &dc, &dpitch));
+  if (dn != c.N || dc != c.C) return fail(CHN_ERR_SHAPE, "softmax_ce: dlogits must have the logits' shape");
+  if (lse) CHN_TRY(check_rows_f32(lse, "lse", c.N));
+  if (c.N == 0) return CHN_OK;
+  CHN_TRY(check_ws(ws, ws_bytes, 256, "softmax_ce_bwd"));
+  float *scale = static_cast<float *>(ws);
+  hipStream_t st = as_stream(stream);
+  const bool i32 = labels->dtype == CHN_I32;
+  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  CHN_TRY(check_launch("softmax_ce_bwd scale"));
+  const int no = 16 / dtype_size(dlogits->dtype);
+  const bool vec = c.vec && reinterpret_cast<uintptr_t>(dlogits->data) % 16 == 0 && dpitch % no == 0;
+  const float *l = lse ? static_cast<const float *>(lse->data) : nullptr;
+  const bool zin32 = logits->dtype == CHN_F32, zout32 = dlogits->dtype == CHN_F32;
+#define CHN_GO(T, TO)                                                                                        \
+  do {                                                                                                       \
+    if (i32) launch_bwd<T, TO, int32_t>(c, logits, labels, ignore_label, l, scale, dlogits, dpitch, vec, st); \
+    else launch_bwd<T, TO, int64_t>(c, logits, labels, ignore_label, l, scale, dlogits, dpitch, vec, st);     \
+  } while (0)
+  if (zin32 && zout32) CHN_GO(float, float);
+  else if (zin32 && !zout32) CHN_GO(float, bf16_raw);
+  else if (!zin32 && zout32) CHN_GO(bf16_raw, float);
+  else CHN_GO(bf16_raw, bf16_raw);
+#undef CHN_GO
+  return check_launch("softmax_ce_bwd rows");
+}
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+"""CPU-side checks of the C ABI: the built library loads, exports every symbol the header declares,
+and rejects malformed descriptors on the host before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1908_00213_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 4096  # fake, aligned, non-NULL device address: validation never dereferences it
+
+
+def _call_ew(op, ins, out, scalars=None):
+    sc = None if scalars is None else (C.c_float * len(scalars))(*scalars)
+    return B.lib().chn_elementwise_broadcast(op, len(ins), B._ptrs(ins), C.byref(out), sc,
+                                             0 if scalars is None else len(scalars), None)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "chn.h")).read()
+    declared = set(re.findall(r"\b(chn_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.chn_version() >= 100
+    assert L.chn_status_string(0) == b"ok" and L.chn_status_string(-4) == b"shape mismatch"
+
+
+def test_elementwise_validation():
+    f = lambda shape, strides, dt=B.F32, p=P: B.raw_desc(p, shape, strides, dt)
+    a = f((4, 5), (20, 4))
+    assert _call_ew(B.OP["add"], [a, f((4, 3), (12, 4))], a) == -4            # not broadcastable
+    assert b"length 3" in B.lib().chn_last_error()
+    assert _call_ew(B.OP["add"], [a], a) == -6                               # wrong arity
+    assert _call_ew(99, [a], a) == -6
+    assert _call_ew(B.OP["add"], [a, f((4, 5), (20, 4), B.BF16)], a) == -3    # mixed input dtypes
+    assert _call_ew(B.OP["add"], [a, a], f((4, 5), (20, 4), B.I32)) == -3
+    assert _call_ew(B.OP["add"], [a, a], f((4, 5), (0, 4))) == -5             # zero stride on output
+    assert _call_ew(B.OP["add"], [a, f((4, 5), (-20, 4))], a) == -5           # negative stride
+    assert _call_ew(B.OP["add"], [a, f((4, 5), (20, 2))], a) == -5            # stride not multiple of item
+    assert _call_ew(B.OP["add"], [a, f((4, 5), (20, 4), p=0)], a) == -1       # NULL data
+    assert _call_ew(B.OP["scale"], [a], a) == -6                             # missing scalar
+    bad = f((4, 5), (20, 4)); bad.ndim = 9
+    assert _call_ew(B.OP["copy"], [bad], a) == -2
+    assert _call_ew(B.OP["copy"], [f((2, 4, 5), (80, 20, 4))], a) == -4       # input has more dims than out
+    # zero-size arrays are fine and launch nothing
+    z = f((0, 5), (20, 4))
+    assert _call_ew(B.OP["add"], [z, z], z) == 0
+
+
+def test_elementwise_plan_families():
+    L = B.lib()
+    f = lambda shape, strides, dt=B.F32: B.raw_desc(P, shape, strides, dt)
+    plan = lambda op, ins, out: L.chn_elementwise_plan(B.OP[op], len(ins), B._ptrs(ins), C.byref(out))
+    n = 64
+    full = f((n, n), (4 * n, 4))
+    assert plan("mad_relu", [full, full, f((1, n), (4 * n, 4))], full) == 0      # contiguous + row broadcast
+    assert plan("add", [full, f((n,), (4,))], full) == 0                         # bias
+    assert plan("add", [full, f((), ())], full) == 0                             # scalar
+    assert plan("add", [full, f((n, 1), (4, 4))], full) == 1                     # column broadcast
+    assert plan("add", [f((n, n), (8 * n, 4)), full], full) == 1                 # pitched rows
+    assert plan("mad_relu", [f((n, n), (4, 4 * n)), full, f((1, n), (4 * n, 4))], full) == 2   # transposed a
+    assert plan("copy", [f((n, n), (8 * n, 8))], full) == 3                      # inner stride 2
+    # 4-d contiguous collapses to flat; permuted collapses to a 2-d transpose
+    c4 = f((2, 3, 4, 8), (384, 128, 32, 4))
+    assert plan("relu", [c4], c4) == 0
+    assert plan("relu", [f((6, 32), (4, 24))], f((6, 32), (128, 4))) == 2
+    # misaligned base pointer cannot use 16-byte vectors
+    mis = B.raw_desc(P + 4, (n, n), (4 * n, 4), B.F32)
+    assert plan("relu", [mis], full) == 1
+
+
+def test_reduce_gemm_and_layer_validation():
+    L = B.lib()
+    f = lambda shape, strides, dt=B.F32, p=P: B.raw_desc(p, shape, strides, dt)
+    x = f((8, 16), (64, 4))
+    r = lambda op, a, ax, keep, out: L.chn_reduce_axis(op, C.byref(a), ax, keep, C.byref(out), None, 0, None)
+    assert r(0, x, 2, 0, f((8,), (4,))) == -7
+    assert r(0, x, -3, 0, f((8,), (4,))) == -7
+    assert r(0, x, 1, 0, f((16,), (4,))) == -4
+    assert r(0, x, 1, 1, f((8,), (4,))) == -4
+    assert r(7, x, 1, 0, f((8,), (4,))) == -6
+    assert r(0, x, 1, 0, f((8,), (8,))) == -5                 # out must be contiguous
+    big = f((8192, 8192), (4 * 8192, 4))
+    need = L.chn_reduce_axis_workspace_bytes(C.byref(big), 0)
+    assert need > 0 and L.chn_reduce_axis_workspace_bytes(C.byref(big), 1) == 0
+    assert r(0, big, 0, 0, f((8192,), (4,))) == -8            # workspace required but missing
+    g = lambda A, Bm, Cm, epi=0, bias=None, aux=None, pre=None: L.chn_gemm(
+        C.byref(A), C.byref(Bm), C.byref(Cm), 1.0, 0.0, epi, None if bias is None else C.byref(bias),
+        None if aux is None else C.byref(aux), None if pre is None else C.byref(pre), None, 0, None)
+    A, Bm, Cm = f((8, 16), (64, 4)), f((16, 4), (16, 4)), f((8, 4), (16, 4))
+    assert g(A, f((15, 4), (16, 4)), Cm) == -4
+    assert g(A, Bm, f((8, 5), (20, 4))) == -4
+    assert g(A, f((16, 4), (16, 4), B.BF16), Cm) == -3
+    assert g(A, Bm, f((8, 4), (8, 2), B.BF16)) == -3          # fp32 operands need an fp32 C
+    assert g(f((8, 16), (128, 8)), Bm, Cm) == -5              # no unit-stride dimension
+    assert g(A, Bm, f((8, 4), (4, 32))) == -5                 # C must be row-major
+    assert g(A, Bm, Cm, 1) == -1                              # bias epilogue without bias
+    assert g(A, Bm, Cm, 1, f((5,), (4,))) == -4
+    assert g(A, Bm, Cm, 4) == -1                              # aux missing
+    assert g(A, Bm, Cm, 0, None, None, Cm) == -6              # preact_out without BIAS_GELU
+    assert g(A, Bm, Cm, 17) == -6
+    z, c = f((4, 32), (128, 4)), f((4, 8), (32, 4))
+    assert L.chn_lstm_fwd(C.byref(f((4, 31), (124, 4))), None, C.byref(c), C.byref(c), C.byref(c), None, None) == -4
+    assert L.chn_lstm_fwd(C.byref(z), C.byref(f((31,), (4,))), C.byref(c), C.byref(c), C.byref(c), None, None) == -4
+    lab = f((4,), (4,), B.I32)
+    one = f((), (), B.F32)
+    assert L.chn_softmax_ce_fwd(C.byref(c), C.byref(f((5,), (4,), B.I32)), -1, C.byref(one), None, None, None, 0, None) == -4
+    assert L.chn_softmax_ce_fwd(C.byref(c), C.byref(f((4,), (4,), B.F32)), -1, C.byref(one), None, None, None, 0, None) == -3
+    assert L.chn_softmax_ce_fwd(C.byref(c), C.byref(lab), -1, C.byref(one), None, None, None, 0, None) == -8
+    assert L.chn_softmax_ce_workspace_bytes(1000) >= 4256
+    assert L.chn_sgd_update(C.byref(c), C.byref(z), 0.1, None, None) == -4
+    assert L.chn_sgd_update(C.byref(c), C.byref(f((4, 8), (64, 4))), 0.1, None, None) == -5
+    assert L.chn_sgd_update(C.byref(c), C.byref(c), 0.1, C.byref(c), None) == -3
+    assert L.chn_embed_fwd(C.byref(c), C.byref(f((3,), (4,), B.F32)), C.byref(f((3, 8), (32, 4))), None) == -3
+    assert L.chn_embed_fwd(C.byref(c), C.byref(f((3,), (4,), B.I32)), C.byref(f((3, 7), (28, 4))), None) == -4

@@ -1,0 +1,133 @@
+"""GPU parity of chn_gemm against the CPU oracle: all four operand layouts, both dtypes, the three
+tile sizes, ragged edges in M, N and K, misaligned leading dimensions, alpha/beta and every epilogue.
+Exact small-integer inputs must match bit for bit (fp32 accumulation of integers below 2^24 is exact
+in any order)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_1908_00213_amd import binding as B
+from tests.util import TOL_BF16, TOL_SUM, bf16r, check, dev, empty, host
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(213_1908)
+
+
+def rnd(shape, dt="f32", scale=1.0):
+    a = (RNG.standard_normal(size=shape) * scale).astype(np.float32)
+    return bf16r(a) if dt == "bf16" else a
+
+
+def operands(M, N, K, layout, dt, gen=rnd):
+    """Returns (A_np, B_np, A_dev, B_dev): A (M,K), B (K,N) views with the requested unit strides.
+    layout[0]: 'n' A row-major (unit stride along K), 't' A stored transposed (unit stride along M);
+    layout[1]: 'n' B row-major (unit stride along N), 't' B stored transposed (unit stride along K)."""
+    if layout[0] == "n":
+        a = gen((M, K), dt); A_np, A_dev = a, dev(a, dt)
+    else:
+        a = gen((K, M), dt); A_np, A_dev = a.T, dev(a, dt).t()
+    if layout[1] == "n":
+        b = gen((K, N), dt); B_np, B_dev = b, dev(b, dt)
+    else:
+        b = gen((N, K), dt); B_np, B_dev = b.T, dev(b, dt).t()
+    return A_np, B_np, A_dev, B_dev
+
+
+SHAPES = [(64, 64, 64), (100, 70, 50), (257, 129, 100), (130, 300, 650), (32, 10, 100), (10, 1000, 33),
+          (600, 520, 96), (1, 1, 1), (5, 7, 3)]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn", "tt"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_gemm_layouts(dt, layout, shape):
+    M, N, K = shape
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
+    out = B.gemm(Ad, Bd, empty((M, N)))
+    ref = O.gemm(A, Bm)
+    S = O.gemm(np.abs(A), np.abs(Bm))
+    check(host(out), ref, TOL_BF16 if dt == "bf16" else TOL_SUM, S, "gemm %s %s" % (layout, dt))
+    if dt == "bf16":
+        # bf16 inputs are exact, the accumulator is fp32: the fp32 result meets the fp32 bar too
+        check(host(out), ref, TOL_SUM, S, "gemm bf16-in fp32-out")
+        outb = B.gemm(Ad, Bd, empty((M, N), "bf16"))
+        check(host(outb), ref, TOL_BF16, S, "gemm bf16 out")
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("shape", [(2100, 2060, 200), (1050, 1100, 136), (300, 200, 4100)])
+def test_gemm_big_tiles_exact_integers(dt, layout, shape):
+    # sizes that select the 256x256 and 128x128 macro tiles, with ragged edges in every dimension
+    M, N, K = shape
+    gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gen)
+    out = host(B.gemm(Ad, Bd, empty((M, N))))
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)       # exact in fp64; the oracle is pinned to it
+    rows = RNG.integers(0, M, 24)
+    assert np.array_equal(O.gemm(A[rows], Bm), ref[rows])
+    assert np.array_equal(out, ref)
+
+
+def test_gemm_identity_and_ones():
+    x = rnd((200, 96))
+    assert np.array_equal(host(B.gemm(dev(x), dev(np.eye(96, dtype=np.float32)), empty((200, 96)))), x)
+    o = host(B.gemm(dev(np.ones((70, 650), np.float32)), dev(np.ones((650, 90), np.float32)), empty((70, 90))))
+    assert np.all(o == 650.0)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_gemm_alpha_beta_and_epilogues(dt):
+    M, N, K = 150, 200, 90
+    tol = TOL_BF16 if dt == "bf16" else TOL_SUM
+    cdt = dt
+    A, Bm, Ad, Bd = operands(M, N, K, "nt", dt)
+    C0 = rnd((M, N), cdt)
+    S = O.gemm(np.abs(A), np.abs(Bm))
+    Cd = dev(C0, cdt)
+    B.gemm(Ad, Bd, Cd, alpha=0.5, beta=-2.0)
+    check(host(Cd), O.gemm(A, Bm, C0, 0.5, -2.0), tol, 0.5 * S + 2 * np.abs(C0), "alpha beta")
+    bias = rnd((N,))
+    v = O.elementwise("add", [O.gemm(A, Bm), bias])
+    Sb = S + np.abs(bias)
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias", bias=dev(bias))
+    check(host(out), v, tol, Sb, "bias")
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_relu", bias=dev(bias))
+    check(host(out), O.elementwise("relu", [v]), tol, Sb, "bias_relu")
+    pre = empty((M, N), cdt)
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_gelu", bias=dev(bias), preact_out=pre)
+    check(host(pre), v, tol, Sb, "preact")
+    check(host(out), O.elementwise("gelu", [v]), tol, Sb, "bias_gelu")
+    out2 = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_gelu", bias=dev(bias))
+    assert torch.equal(out.view(torch.int16 if cdt == "bf16" else torch.int32), out2.view(torch.int16 if cdt == "bf16" else torch.int32))
+    aux = rnd((M, N), cdt)
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="relu_bwd", aux=dev(aux, cdt))
+    check(host(out), O.elementwise("relu_bwd", [O.gemm(A, Bm), aux]), tol, S, "relu_bwd")
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="gelu_bwd", aux=dev(aux, cdt))
+    check(host(out), O.elementwise("gelu_bwd", [O.gemm(A, Bm), aux]), tol, S * 1.2, "gelu_bwd")
+    # accumulate into a row block of a larger buffer (how the recurrent step adds h U to x W)
+    big = rnd((3 * M, N))
+    bd = dev(big)
+    if dt == "f32":
+        B.gemm(Ad, Bd, bd[M:2 * M], beta=1.0)
+        want = big.astype(np.float64); want[M:2 * M] += O.gemm(A, Bm)
+        check(host(bd), want, tol, np.concatenate([np.zeros((M, N)), S + np.abs(big[M:2 * M]), np.zeros((M, N))]), "beta=1 slice")
+
+
+def test_gemm_misaligned_leading_dimensions():
+    # K = 650 fp32: rows are 8-byte but not 16-byte aligned; K = 651: 4-byte only; bf16 K = 325: 2-byte
+    for dt, K in (("f32", 650), ("f32", 651), ("bf16", 652), ("bf16", 325)):
+        M, N = 140, 90
+        for layout in ("nt", "nn", "tn"):
+            A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
+            out = B.gemm(Ad, Bd, empty((M, N)))
+            check(host(out), O.gemm(A, Bm), TOL_SUM, O.gemm(np.abs(A), np.abs(Bm)), "misaligned %s %d %s" % (dt, K, layout))
+    # operands that are column slices of wider buffers (leading dimension > extent)
+    a = rnd((100, 300)); b = rnd((80, 300))
+    out = B.gemm(dev(a)[:, 4:204], dev(b)[:, 8:208].t(), empty((100, 80)))
+    check(host(out), O.gemm(a[:, 4:204], b[:, 8:208].T), TOL_SUM, O.gemm(np.abs(a[:, 4:204]), np.abs(b[:, 8:208].T)), "sliced")
+    # empty problems
+    B.gemm(empty((0, 5)), empty((5, 7)), empty((0, 7)))
+    z = B.gemm(empty((4, 0)), empty((0, 7)), dev(rnd((4, 7))))
+    assert np.all(host(z) == 0)

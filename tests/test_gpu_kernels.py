@@ -1,0 +1,360 @@
+"""GPU parity: every C-ABI call against the CPU oracle, element by element, on seeded inputs at sizes
+that span several tiles plus a ragged tail, with the edge cases each call has."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_1908_00213_amd import binding as B
+from tests.util import TOL_BF16, TOL_EW, TOL_SUM, bf16r, check, dev, empty, host, ws
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(1908_00213)
+
+
+def rnd(shape, dt="f32", lo=-1.0, hi=1.0):
+    a = RNG.uniform(lo, hi, size=shape).astype(np.float32)
+    return bf16r(a) if dt == "bf16" else a
+
+
+def tol_for(dt_in, dt_out, base):
+    return TOL_BF16 if "bf16" in (dt_in, dt_out) else base
+
+
+# ------------------------------------------------------------------------------------ element-wise
+@pytest.mark.parametrize("dt_in,dt_out", [("f32", "f32"), ("bf16", "bf16"), ("f32", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("shape", [(300, 520), (257, 1031), (3, 5), (1, 1)])
+def test_mad_relu_row_broadcast(dt_in, dt_out, shape):
+    a, b, c = rnd(shape, dt_in), rnd(shape, dt_in), rnd((1, shape[1]), dt_in)
+    out = empty(shape, dt_out)
+    assert B.elementwise_plan("mad_relu", [dev(a, dt_in), dev(b, dt_in), dev(c, dt_in)], out) == 0
+    B.elementwise_broadcast("mad_relu", [dev(a, dt_in), dev(b, dt_in), dev(c, dt_in)], out)
+    ref = O.elementwise("mad_relu", [a, b, c])
+    S = O.elementwise("mad", [np.abs(a), np.abs(b), np.abs(c)])
+    check(host(out), ref, tol_for(dt_in, dt_out, TOL_EW), S, "mad_relu")
+    if dt_out == "f32" and dt_in == "f32":
+        # fused multiply-add differs from the oracle's fp64 only by the final rounding
+        assert np.max(np.abs(host(out) - ref)) <= 2.0 ** -23 * 2
+
+
+OPS1 = ["copy", "relu", "gelu", "sigmoid", "tanh"]
+OPS2 = ["add", "sub", "mul", "relu_bwd", "gelu_bwd", "add_relu", "add_gelu"]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_every_op_flat(dt):
+    shape = (129, 77)
+    x, y, z = rnd(shape, dt, -4, 4), rnd(shape, dt, -4, 4), rnd(shape, dt, -4, 4)
+    tol = tol_for(dt, dt, TOL_EW)
+    for op in OPS1:
+        out = B.elementwise_broadcast(op, [dev(x, dt)], empty(shape, dt))
+        S = np.abs(x) if op == "gelu" else None
+        check(host(out), O.elementwise(op, [x]), tol, S, op)
+    for op in OPS2:
+        out = B.elementwise_broadcast(op, [dev(x, dt), dev(y, dt)], empty(shape, dt))
+        S = {"add": np.abs(x) + np.abs(y), "sub": np.abs(x) + np.abs(y), "add_relu": np.abs(x) + np.abs(y),
+             "add_gelu": np.abs(x) + np.abs(y), "gelu_bwd": np.abs(x) * (1 + np.abs(y))}.get(op)
+        check(host(out), O.elementwise(op, [x, y]), tol, S, op)
+    out = B.elementwise_broadcast("mad", [dev(x, dt), dev(y, dt), dev(z, dt)], empty(shape, dt))
+    check(host(out), O.elementwise("mad", [x, y, z]), tol, np.abs(x * y) + np.abs(z), "mad")
+    out = B.elementwise_broadcast("scale", [dev(x, dt)], empty(shape, dt), scalars=[-2.5])
+    check(host(out), O.elementwise("scale", [x], scalars=[-2.5]), tol, None, "scale")
+    out = B.elementwise_broadcast("axpy", [dev(x, dt), dev(y, dt)], empty(shape, dt), scalars=[0.375])
+    check(host(out), O.elementwise("axpy", [x, y], scalars=[0.375]), tol, np.abs(x) + np.abs(y), "axpy")
+    out = B.elementwise_broadcast("fill", [], empty(shape, dt), scalars=[1.5])
+    assert np.all(host(out) == 1.5)
+    xp = np.abs(x)
+    out = B.elementwise_broadcast("sqrt", [dev(xp, dt)], empty(shape, dt))
+    check(host(out), O.elementwise("sqrt", [xp]), tol, None, "sqrt")
+
+
+def test_paper_examples_on_gpu():
+    # figure "Examples using NumPy and CuPy": the norm of [1, 2]; figure "user-defined kernel": x*y+z
+    x = dev(np.array([1.0, 2.0], dtype=np.float32))
+    sq = B.elementwise_broadcast("mul", [x, x], empty((2,)))
+    s = B.reduce_axis("sum", sq, 0, empty(()))
+    assert float(s.cpu()) == 5.0
+    n = B.elementwise_broadcast("sqrt", [s], empty(()))
+    assert abs(float(n.cpu()) - 5 ** 0.5) < 2e-7
+    rows = np.array([[1, 2, 3, 5], [-2, 4, 1, -7], [0.5, 0.25, -0.125, 0], [3, -3, 9, 0], [-1.5, -2, 0.5, 3.5]], dtype=np.float32)
+    w = B.elementwise_broadcast("mad", [dev(rows[:, 0].copy()), dev(rows[:, 1].copy()), dev(rows[:, 2].copy())], empty((5,)))
+    assert np.array_equal(host(w), rows[:, 3])
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_broadcast_patterns(dt):
+    tol = tol_for(dt, dt, TOL_EW)
+    cases = [
+        [(70, 130), (70, 130), (130,)],          # bias, aligned period? 130 is not a vector multiple
+        [(70, 136), (70, 136), (136,)],          # aligned period
+        [(70, 10), (70, 10), (10,)],             # period shorter than... a tiny class count
+        [(70, 130), (70, 1), (1, 130)],          # column broadcast x row broadcast
+        [(6, 1, 50), (1, 7, 1), (7, 50)],        # 3-d mixed
+        [(5, 6, 7, 8), (8,), ()],                # scalar operand
+        [(33,), (1,), (33,)],
+    ]
+    for shapes in cases:
+        xs = [rnd(s, dt) for s in shapes]
+        ref = O.elementwise("mad", xs)
+        out = B.elementwise_broadcast("mad", [dev(x, dt) for x in xs], empty(ref.shape, dt))
+        S = O.elementwise("mad", [np.abs(x) for x in xs])
+        check(host(out), ref, tol, S, str(shapes))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(200, 330), (64, 64), (65, 63), (1000, 7)])
+def test_transposed_view(dt, shape):
+    r, c = shape
+    a_store = rnd((c, r), dt)                 # a is the transpose view of a contiguous (c, r) buffer
+    b, cc = rnd((r, c), dt), rnd((1, c), dt)
+    a_dev = dev(a_store, dt).t()
+    assert a_dev.stride() == (1, r)
+    out = empty((r, c), dt)
+    fam = B.elementwise_plan("mad_relu", [a_dev, dev(b, dt), dev(cc, dt)], out)
+    assert fam == 2
+    B.elementwise_broadcast("mad_relu", [a_dev, dev(b, dt), dev(cc, dt)], out)
+    ref = O.elementwise("mad_relu", [a_store.T, b, cc])
+    S = O.elementwise("mad", [np.abs(a_store.T), np.abs(b), np.abs(cc)])
+    check(host(out), ref, tol_for(dt, dt, TOL_EW), S, "transposed")
+    # bit-equal to the same call on a materialised transpose
+    out2 = B.elementwise_broadcast("mad_relu", [dev(np.ascontiguousarray(a_store.T), dt), dev(b, dt), dev(cc, dt)], empty((r, c), dt))
+    assert torch.equal(out.view(torch.int16 if dt == "bf16" else torch.int32), out2.view(torch.int16 if dt == "bf16" else torch.int32))
+
+
+def test_strided_views_and_inplace():
+    big = rnd((40, 50))
+    d = dev(big)
+    v = d[3:37:2, 5:47:3]                      # general strides
+    assert B.elementwise_plan("relu", [v], empty(tuple(v.shape))) == 3
+    out = B.elementwise_broadcast("relu", [v], empty(tuple(v.shape)))
+    check(host(out), O.elementwise("relu", [big[3:37:2, 5:47:3]]), TOL_EW, None, "strided")
+    p = d[:, 8:40]                             # pitched rows
+    assert B.elementwise_plan("scale", [p], p) == 1
+    B.elementwise_broadcast("scale", [p], p, scalars=[2.0])   # in place on a view
+    want = big.copy(); want[:, 8:40] *= 2
+    assert np.array_equal(host(d), want)
+    # output written through a transposed view
+    o = empty((50, 40)).t()
+    B.elementwise_broadcast("copy", [dev(big)], o)
+    assert np.array_equal(host(o), big)
+    # zero-size
+    z = empty((0, 7))
+    B.elementwise_broadcast("add", [z, z], z)
+
+
+def test_elementwise_large_flat_tail():
+    n = 4 * 1024 * 1024 + 3                    # several blocks and a ragged tail
+    x, y = rnd((n,)), rnd((n,))
+    out = B.elementwise_broadcast("add", [dev(x), dev(y)], empty((n,)))
+    assert np.array_equal(host(out), (x + y).astype(np.float64))      # fp32 add is correctly rounded
+
+
+# ------------------------------------------------------------------------------------ reductions
+def _reduce(op, x_np, x_dev, axis, dt_out="f32", keep=False):
+    need = B.reduce_axis_workspace_bytes(x_dev, axis)
+    ref = O.reduce_axis(op, x_np, axis, keep)
+    out = B.reduce_axis(op, x_dev, axis, empty(ref.shape, dt_out), keep, ws(need) if need else None)
+    return host(out), ref
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(513, 1030), (4100, 260), (32, 100), (1024, 10), (7, 4099), (1, 50), (50, 1), (2500, 3)])
+def test_reduce_2d_both_axes(dt, shape):
+    x = rnd(shape, dt)
+    tol = tol_for(dt, "f32", TOL_SUM)
+    for axis in (0, 1, -1):
+        got, ref = _reduce("sum", x, dev(x, dt), axis)
+        check(got, ref, tol, O.reduce_axis("sum", np.abs(x), axis), "sum axis %d" % axis)
+        got, ref = _reduce("max", x, dev(x, dt), axis)
+        assert np.array_equal(got, ref)
+    # transposed views swap the two kernels and must give the same sums
+    xt = dev(x, dt).t()
+    got, ref = _reduce("sum", x.T, xt, 0)
+    check(got, ref, tol, O.reduce_axis("sum", np.abs(x.T), 0), "sum T axis 0")
+    got, ref = _reduce("sum", x.T, xt, 1, keep=True)
+    check(got, ref, tol, O.reduce_axis("sum", np.abs(x.T), 1, True), "sum T axis 1 keepdims")
+
+
+def test_reduce_exact_integers_bit_equal():
+    for dt in ("f32", "bf16"):
+        x = RNG.integers(-4, 5, size=(2050, 1500)).astype(np.float32)
+        for axis in (0, 1):
+            got, ref = _reduce("sum", x, dev(x, dt), axis)
+            assert np.array_equal(got, ref)
+    assert np.array_equal(_reduce("sum", np.ones((777, 33), np.float32), dev(np.ones((777, 33), np.float32)), 0)[0], np.full(33, 777.0))
+
+
+def test_reduce_nd_keepdims_bf16_out_empty_and_deterministic():
+    x = rnd((6, 70, 40))
+    for axis in (0, 1, 2):
+        got, ref = _reduce("sum", x, dev(x), axis, keep=(axis == 1))
+        check(got, ref, TOL_SUM, O.reduce_axis("sum", np.abs(x), axis, axis == 1), "3-d axis %d" % axis)
+    v = dev(x)[:, ::2, 1:39]                    # general strided view
+    got, ref = _reduce("sum", x[:, ::2, 1:39], v, 1)
+    check(got, ref, TOL_SUM, O.reduce_axis("sum", np.abs(x[:, ::2, 1:39]), 1), "strided view")
+    got, ref = _reduce("sum", x, dev(x), 2, dt_out="bf16")
+    check(got, ref, TOL_BF16, None, "bf16 out")
+    e = empty((5, 0))
+    out = B.reduce_axis("sum", e, 1, empty((5,)))
+    assert np.all(host(out) == 0)
+    out = B.reduce_axis("max", e, 1, empty((5,)))
+    assert np.all(host(out) == -np.inf)
+    B.reduce_axis("sum", e, 0, empty((0,)))
+    big = rnd((3000, 700))
+    d = dev(big)
+    need = B.reduce_axis_workspace_bytes(d, 0)
+    assert need > 0
+    a = B.reduce_axis("sum", d, 0, empty((700,)), ws=ws(need))
+    b = B.reduce_axis("sum", d, 0, empty((700,)), ws=ws(need))
+    assert torch.equal(a, b)                   # fixed summation order: bit-reproducible
+    s0 = host(a).sum()
+    s1 = host(B.reduce_axis("sum", d, 1, empty((3000,)))).sum()
+    assert abs(s0 - s1) <= 1e-4 * np.abs(big).sum()
+
+
+# ------------------------------------------------------------------------------------ softmax CE
+@pytest.mark.parametrize("N,Cn,dt,lab", [(37, 10, "f32", np.int32), (300, 1000, "f32", np.int64), (70, 4100, "f32", np.int32),
+                                         (129, 1000, "bf16", np.int32), (33, 2051, "bf16", np.int64), (5, 33, "f32", np.int32)])
+def test_softmax_ce(N, Cn, dt, lab):
+    z = rnd((N, Cn), dt, -6, 6)
+    t = RNG.integers(0, Cn, size=(N,)).astype(lab)
+    t[::7] = -1
+    zd, td = dev(z, dt), dev(t)
+    loss, rows, lse = empty(()), empty((N,)), empty((N,))
+    w = ws(B.softmax_ce_workspace_bytes(N))
+    B.softmax_ce_fwd(zd, td, loss, rows, lse, ws=w)
+    rl, rrows, rlse, nv = O.softmax_ce_fwd(z, t)
+    check(host(lse), rlse, TOL_EW * 10, None, "lse")
+    check(host(rows), rrows, TOL_SUM, np.abs(rlse), "loss rows")
+    assert np.all(host(rows)[t == -1] == 0)
+    check(host(loss), np.array(rl), TOL_SUM, None, "loss mean")
+    # without optional outputs the mean is identical
+    loss2 = B.softmax_ce_fwd(zd, td, empty(()), ws=w)
+    assert torch.equal(loss, loss2)
+    ref = O.softmax_ce_bwd(z, t, -1, 1.5)
+    for out_dt in ("f32", "bf16"):
+        for use_lse in (True, False):
+            dz = B.softmax_ce_bwd(zd, td, empty((N, Cn), out_dt), lse if use_lse else None, 1.5, ws=w)
+            check(host(dz), ref, tol_for(dt, out_dt, TOL_EW * 10), 1.5 / nv, "dlogits")
+            assert np.all(host(dz)[t == -1] == 0)
+    g = host(B.softmax_ce_bwd(zd, td, empty((N, Cn)), lse, 1.0, ws=w))
+    assert np.max(np.abs(g.sum(axis=1))) < 1e-6                       # each row of the gradient sums to 0
+    # one-hot position is exact: the only negative entry of a row sits at its label
+    valid = np.where(t != -1)[0]
+    assert np.array_equal(np.argmin(g[valid], axis=1), t[valid])
+    if dt == "f32":                                                    # in place
+        zc = zd.clone()
+        B.softmax_ce_bwd(zc, td, zc, None, 1.5, ws=w)
+        check(host(zc), ref, TOL_EW * 10, 1.5 / nv, "in place")
+
+
+def test_softmax_ce_closed_forms():
+    for Cn in (10, 1000, 10000):
+        z = np.zeros((4, Cn), dtype=np.float32)
+        t = np.array([0, Cn - 1, 5, 7], dtype=np.int32)
+        w = ws(B.softmax_ce_workspace_bytes(4))
+        loss = B.softmax_ce_fwd(dev(z), dev(t), empty(()), ws=w)
+        assert abs(float(loss.cpu()) - np.log(Cn)) < 1e-5 * np.log(Cn)
+        dz = host(B.softmax_ce_bwd(dev(z), dev(t), empty((4, Cn)), ws=w))
+        want = np.full((4, Cn), 0.25 / Cn); want[np.arange(4), t] -= 0.25
+        check(dz, want, TOL_EW, None, "uniform")
+    # all rows ignored
+    z = rnd((6, 50)); t = np.full(6, -1, np.int32)
+    w = ws(B.softmax_ce_workspace_bytes(6))
+    assert float(B.softmax_ce_fwd(dev(z), dev(t), empty(()), ws=w).cpu()) == 0.0
+    assert np.all(host(B.softmax_ce_bwd(dev(z), dev(t), empty((6, 50)), ws=w)) == 0)
+
+
+# ------------------------------------------------------------------------------------ LSTM cell
+@pytest.mark.parametrize("Bn,H", [(128, 650), (3, 5), (17, 129)])
+def test_lstm_cell(Bn, H):
+    z, bias, cp = rnd((Bn, 4 * H), lo=-3, hi=3), rnd((4 * H,)), rnd((Bn, H), lo=-2, hi=2)
+    c, h, g = empty((Bn, H)), empty((Bn, H)), empty((Bn, 4 * H))
+    B.lstm_fwd(dev(z), dev(bias), dev(cp), c, h, g)
+    rc, rh, rg = O.lstm_fwd(z, bias, cp)
+    check(host(g), rg, TOL_EW, None, "gates")
+    check(host(c), rc, TOL_EW, np.abs(rc) + 1, "c")
+    check(host(h), rh, TOL_EW * 2, None, "h")
+    c2, h2 = empty((Bn, H)), empty((Bn, H))
+    B.lstm_fwd(dev(z + bias), None, dev(cp), c2, h2, None)          # bias is just added to z
+    check(host(c2), rc, TOL_EW, np.abs(rc) + 1, "c no-bias")
+    dh, dcn = rnd((Bn, H)), rnd((Bn, H))
+    # teacher-forced: the backward gets the GPU forward's own retained outputs
+    gh, ch = host(g), host(c)
+    dz, dcp = empty((Bn, 4 * H)), empty((Bn, H))
+    B.lstm_bwd(g, dev(cp), c, dev(dh), dev(dcn), dz, dcp)
+    rdz, rdcp = O.lstm_bwd(gh, cp, ch, dh, dcn)
+    check(host(dz), rdz, TOL_EW, 1e-3 + np.abs(rdz), "dz")
+    check(host(dcp), rdcp, TOL_EW, 1e-3, "dc_prev")
+    B.lstm_bwd(g, dev(cp), c, dev(dh), None, dz, dcp)
+    rdz0, rdcp0 = O.lstm_bwd(gh, cp, ch, dh, None)
+    check(host(dz), rdz0, TOL_EW, 1e-3 + np.abs(rdz0), "dz no dc_next")
+    # pitched rows: z is a row block of a larger time-major buffer
+    zz = dev(np.concatenate([z, z], axis=1))[:, :4 * H]
+    c3, h3 = empty((Bn, H)), empty((Bn, H))
+    B.lstm_fwd(zz, dev(bias), dev(cp), c3, h3, None)
+    assert torch.equal(c3, c) and torch.equal(h3, h)
+
+
+def test_lstm_zero_preactivation_closed_form():
+    cp = rnd((4, 8))
+    c, h, g = empty((4, 8)), empty((4, 8)), empty((4, 32))
+    B.lstm_fwd(dev(np.zeros((4, 32), np.float32)), None, dev(cp), c, h, g)
+    assert np.array_equal(host(c), 0.5 * cp.astype(np.float64))
+    check(host(h), 0.5 * np.tanh(0.5 * cp.astype(np.float64)), TOL_EW, None, "h")
+    assert np.array_equal(host(g)[:, :8], np.full((4, 8), 0.5)) and np.all(host(g)[:, 16:24] == 0)
+
+
+# ------------------------------------------------------------------------------------ SGD
+def test_sgd():
+    for n in (89610 // 9, 1000 * 784, 7, 4096 * 4 + 5):
+        p, g = rnd((n,)), rnd((n,))
+        pd, lp = dev(p), empty((n,), "bf16")
+        B.sgd_update(pd, dev(g), 0.01, lp)
+        ref = O.sgd_update(p, g, np.float32(0.01))
+        check(host(pd), ref, TOL_EW, np.abs(p), "sgd")
+        assert np.array_equal(host(lp), O.round_bf16(host(pd)))       # working copy = RNE of the new master
+    p = rnd((300, 70))
+    pd = dev(p)
+    B.sgd_update(pd, dev(rnd((300, 70))), 0.0)
+    assert np.array_equal(host(pd), p)
+    B.sgd_update(pd, dev(np.ones((300, 70), np.float32)), 0.25)
+    assert np.array_equal(host(pd), (p - np.float32(0.25)).astype(np.float64))
+    # multi-tensor form equals the single calls bit for bit
+    shapes = [(100, 784), (100,), (10, 100), (10,), (0,), (3, 3)] * 9        # > 40 tensors: two launches
+    ps, gs = [rnd(s) for s in shapes], [rnd(s) for s in shapes]
+    a = [dev(x) for x in ps]; b = [dev(x) for x in ps]; gd = [dev(x) for x in gs]
+    lows = [empty(s, "bf16") if i % 2 == 0 else None for i, s in enumerate(shapes)]
+    B.sgd_update_multi(a, gd, 0.05, lows)
+    for x, g_ in zip(b, gd):
+        B.sgd_update(x, g_, 0.05)
+    for x, y, l in zip(a, b, lows):
+        assert torch.equal(x, y)
+        if l is not None:
+            assert np.array_equal(host(l), O.round_bf16(host(x)))
+
+
+# ------------------------------------------------------------------------------------ embedding
+@pytest.mark.parametrize("V,D,N,idt", [(1000, 650, 500, np.int32), (50, 7, 300, np.int64), (10, 1100, 20, np.int32)])
+def test_embedding(V, D, N, idt):
+    E = rnd((V, D))
+    ids = RNG.integers(0, V, size=(N,)).astype(idt)
+    ids[:5] = ids[0]                              # guaranteed collisions
+    out = B.embed_fwd(dev(E), dev(ids), empty((N, D)))
+    assert np.array_equal(host(out), O.embed_fwd(E, ids))                    # bit copies
+    Eb = bf16r(E)
+    outb = B.embed_fwd(dev(Eb, "bf16"), dev(ids), empty((N, D), "bf16"))
+    assert np.array_equal(host(outb), O.embed_fwd(Eb, ids))
+    dout = rnd((N, D))
+    dE = B.embed_bwd(dev(ids), dev(dout), empty((V, D)))
+    ref = O.embed_bwd(ids, dout, V)
+    check(host(dE), ref, TOL_SUM, O.embed_bwd(ids, np.abs(dout), V), "dE")
+    untouched = np.setdiff1d(np.arange(V), ids)
+    assert np.all(host(dE)[untouched] == 0)
+    dE2 = B.embed_bwd(dev(ids), dev(dout), empty((V, D)))
+    assert torch.equal(dE, dE2)                                              # bit-reproducible
+    acc = dev(E)
+    B.embed_bwd(dev(ids), dev(dout), acc, accumulate=True)
+    check(host(acc), O.embed_bwd(ids, dout, V, E), TOL_SUM, O.embed_bwd(ids, np.abs(dout), V, np.abs(E)), "accumulate")
+    di = RNG.integers(-3, 4, size=(N, D)).astype(np.float32)                 # integers: exact in any order
+    assert np.array_equal(host(B.embed_bwd(dev(ids), dev(di), empty((V, D)))), O.embed_bwd(ids, di, V))
