@@ -57,7 +57,7 @@ def test_gemm_layouts(dt, layout, shape):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-@pytest.mark.parametrize("shape", [(2100, 2060, 200), (1050, 1100, 136), (300, 200, 4100)])
+@pytest.mark.parametrize("shape", [(3700, 3590, 130), (1500, 1400, 136), (300, 200, 4100)])
 def test_gemm_big_tiles_exact_integers(dt, layout, shape):
     # sizes that select the 256x256 and 128x128 macro tiles, with ragged edges in every dimension
     M, N, K = shape
