@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the training-step hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A "step" is one forward + backward + SGD pass of the wide MLP workload (4096-4096-4096-4096-1000,
+GELU, batch 8192, bf16 storage with fp32 accumulation and fp32 master weights) issued call by call
+through the C ABI; the printed JSON line reports train steps/s for it, the roofline figure of the
+kernel that dominates it (the bf16 MFMA GEMM), the CPU oracle timed on a bounded sample of the same
+workload, and -- under "workloads" -- the other benchmark configurations: the array microbenchmark
+(element-wise / reduction GB/s against the HBM peak), the fp32/bf16 MLP and the LSTM language-model
+step.  All inputs are seeded synthetic tensors already resident in HBM when timing starts.
+One GPU only: this build has no multi-GPU path, and --gpus N > 1 exits with a message.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Timer:
+    """HIP-event stopwatch on the stream the kernels are launched on (torch's current stream)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def time(self, fn, iters, warmup):
+        t = self.torch
+        for _ in range(warmup):
+            fn()
+        t.cuda.synchronize()
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        t.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / iters       # seconds per call
+
+
+def bench_array(torch, B, W, timer, quick):
+    """Workload 2: y = relu(a*b + c) with a row-broadcast c, sums over both axes, transposed views."""
+    n = 8192
+    out = {}
+    w = W.config2(n)
+    for name, tdt, isz in (("f32", torch.float32, 4), ("bf16", torch.bfloat16, 2)):
+        sets = 2 if name == "f32" else 4            # rotate buffers: defeat the 256 MB Infinity Cache
+        a = [torch.from_numpy(w.a).cuda().to(tdt) for _ in range(sets)]
+        b = [torch.from_numpy(w.b).cuda().to(tdt) for _ in range(sets)]
+        c = torch.from_numpy(w.c).cuda().to(tdt)
+        y = [torch.empty(n, n, dtype=tdt, device="cuda") for _ in range(4)]
+        o = torch.empty(n, dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(256, B.reduce_axis_workspace_bytes(y[0], 0)), dtype=torch.uint8, device="cuda")
+        k = [0]
+
+        def rot(fn):
+            def g():
+                k[0] += 1
+                fn(k[0])
+            return g
+        iters = 8 if quick else 40
+        cases = {
+            "mad_relu": (rot(lambda i: B.elementwise_broadcast("mad_relu", [a[i % sets], b[i % sets], c], y[i % 4])), 3 * n * n * isz + n * isz),
+            "mad_relu_transposed_a": (rot(lambda i: B.elementwise_broadcast("mad_relu", [a[i % sets].t(), b[i % sets], c], y[i % 4])), 3 * n * n * isz + n * isz),
+            "sum_axis0": (rot(lambda i: B.reduce_axis("sum", y[i % 4], 0, o, ws=ws)), n * n * isz + n * 4),
+            "sum_axis1": (rot(lambda i: B.reduce_axis("sum", y[i % 4], 1, o, ws=ws)), n * n * isz + n * 4),
+            "sum_axis0_transposed": (rot(lambda i: B.reduce_axis("sum", y[i % 4].t(), 0, o, ws=ws)), n * n * isz + n * 4),
+            "sum_axis1_transposed": (rot(lambda i: B.reduce_axis("sum", y[i % 4].t(), 1, o, ws=ws)), n * n * isz + n * 4),
+        }
+        for cname, (fn, nbytes) in cases.items():
+            s = timer.time(fn, iters, 4)
+            gbs = nbytes / s / 1e9
+            out["%s_%s" % (cname, name)] = {"us": round(s * 1e6, 2), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                                            "algorithmic_bytes": nbytes}
+            log("  cfg2 %-28s %-5s %9.1f us  %8.1f GB/s  %.1f%% of HBM peak" % (cname, name, s * 1e6, gbs, 100 * gbs / HBM_PEAK_GBS))
+        del a, b, y
+        torch.cuda.empty_cache()
+    return out
+
+
+class GemmProbe:
+    """Brackets every GEMM launch of a recorded step with HIP events (same stream) so that the
+    per-kernel time inside the timed region can be read back afterwards."""
+
+    def __init__(self, torch, B, prog):
+        self.torch = torch
+        self.fn = B.lib().chn_gemm
+        self.prog = prog
+        self.idx = [i for i, (fn, _) in enumerate(prog.calls) if fn is self.fn]
+        self.events = []
+
+    def run(self):
+        t = self.torch
+        import ctypes as C
+        s = C.c_void_p(t.cuda.current_stream().cuda_stream)
+        ev = []
+        for fn, args in self.prog.calls:
+            if fn is self.fn:
+                e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+                e0.record()
+                st = fn(*args, s)
+                e1.record()
+                ev.append((e0, e1))
+            else:
+                st = fn(*args, s)
+            if st != 0:
+                raise RuntimeError("chn call failed with status %d" % st)
+        self.events.append(ev)
+
+    def per_call_seconds(self):
+        n = len(self.idx)
+        tot = [0.0] * n
+        for ev in self.events:
+            for i, (e0, e1) in enumerate(ev):
+                tot[i] += e0.elapsed_time(e1) * 1e-3
+        return [x / max(1, len(self.events)) for x in tot]
+
+
+def gemm_shapes_mlp(sizes, batch):
+    """(label, M, N, K) of every GEMM of one MLP step in issue order (see steps.MLPTrainer)."""
+    n = len(sizes) - 1
+    out = [("fwd%d" % l, batch, sizes[l + 1], sizes[l]) for l in range(n)]
+    for l in range(n - 1, -1, -1):
+        out.append(("dW%d" % l, sizes[l + 1], sizes[l], batch))
+        if l > 0:
+            out.append(("dx%d" % l, batch, sizes[l], sizes[l + 1]))
+    return out
+
+
+def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False):
+    tr = steps_mod.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp)
+    xs = [torch.from_numpy(x).cuda() for x in w.xs]
+    if lowp:
+        xs = [x.to(torch.bfloat16) for x in xs]
+    ts = [torch.from_numpy(t).cuda() for t in w.ts]
+    nb = len(xs)
+    for i in range(nb):
+        tr.step(xs[i], ts[i])                                   # builds the call lists
+    res = {}
+    if probe:
+        probes = [GemmProbe(torch, B, tr._progs[(xs[i].data_ptr(), ts[i].data_ptr())]) for i in range(nb)]
+        k = [0]
+
+        def fn():
+            probes[k[0] % nb].run()
+            k[0] += 1
+        for _ in range(warmup):
+            tr.step(xs[0], ts[0])
+        s = timer.time(fn, steps, 0)
+        per = [0.0] * len(probes[0].idx)
+        used = [p for p in probes if p.events]
+        for p in used:
+            for i, v in enumerate(p.per_call_seconds()):
+                per[i] += v / len(used)
+        res["gemm_calls"] = [{"call": lab, "M": M, "N": N, "K": K, "us": round(t_ * 1e6, 1),
+                              "TFLOP/s": round(2.0 * M * N * K / t_ / 1e12, 1)}
+                             for (lab, M, N, K), t_ in zip(gemm_shapes_mlp(w.sizes, w.batch), per)]
+        res["gemm_seconds_per_step"] = sum(per)
+        res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch))
+    else:
+        k = [0]
+
+        def fn():
+            tr.step(xs[k[0] % nb], ts[k[0] % nb])
+            k[0] += 1
+        s = timer.time(fn, steps, warmup)
+    res.update({"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(tr.loss.cpu()),
+                "TFLOP/s": w.flops_per_step() / s / 1e12, "launch_calls_per_step": tr.n_launch_calls(xs[0], ts[0])})
+    return res
+
+
+def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup):
+    tr = steps_mod.LSTMTrainer(w.params, w.bptt, w.batch, w.lr)
+    ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
+    s = timer.time(lambda: tr.step(ids, tg), steps, warmup)
+    return {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s, "loss": float(tr.loss.cpu()),
+            "TFLOP/s": w.flops_per_step() / s / 1e12, "frac_mfma_peak_f32": w.flops_per_step() / s / 1e12 / MFMA_PEAK_TFLOPS["f32"],
+            "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
+
+
+def cpu_baseline(W, rows=16):
+    """The CPU oracle, as it stands, on a bounded sample of the headline workload: `rows` of the 8192
+    batch rows through the full-width network (forward + backward + SGD), scaled to steps/s."""
+    from oracle import oracle as O
+    from oracle import steps as OS
+    w = W.config5(n_batches=1)
+    x = W.bf16_exact(w.xs[0][:rows])
+    t0 = time.perf_counter()
+    OS.mlp_step(w.params, x, w.ts[0][:rows], np.float32(w.lr), w.act, lowp=True)
+    dt = time.perf_counter() - t0
+    scale = w.batch / rows
+    return {"value": 1.0 / (dt * scale), "unit": "steps/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": "%d of %d batch rows through the full 4096-4096-4096-4096-1000 network (one forward+backward+SGD "
+                      "step, fp64 with bf16 storage rounding) took %.1f s; scaled by %d" % (rows, w.batch, dt, scale)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1908_00213_amd import binding as B, steps as steps_mod, workloads as W
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()
+    torch.cuda.set_device(0)
+    timer = Timer(torch)
+    extra = {}
+
+    # ---- headline: workload 5, wide MLP, bf16 storage / fp32 accumulate
+    log("workload 5: wide MLP 4096-4096-4096-4096-1000, GELU, batch 8192, bf16/fp32-accumulate")
+    w5 = W.config5(n_batches=4)
+    torch.cuda.synchronize()
+    r5 = bench_mlp(torch, B, steps_mod, w5, True, timer, args.steps, args.warmup, probe=True)
+    torch.cuda.synchronize()
+    log("  %.3f ms/step  %.1f steps/s  %.1f TFLOP/s whole step; GEMMs %.3f ms/step = %.1f TFLOP/s" % (
+        r5["ms_per_step"], r5["steps_per_s"], r5["TFLOP/s"], r5["gemm_seconds_per_step"] * 1e3,
+        r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12))
+    # dominant kernel: the 256x256-tile bf16 GEMM, forward layout (both operands unit-stride along K)
+    dom = [c for c in r5["gemm_calls"] if c["call"] in ("fwd0", "fwd1", "fwd2")]
+    dom_s = sum(c["us"] for c in dom) * 1e-6 / len(dom)
+    dom_flops = 2.0 * dom[0]["M"] * dom[0]["N"] * dom[0]["K"]
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<bf16, 256x256 tile, A and B unit-stride along K> (forward x @ W.T, M=8192 N=4096 K=4096)",
+                "achieved": dom_flops / dom_s / 1e12, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
+                "frac": dom_flops / dom_s / 1e12 / MFMA_PEAK_TFLOPS["bf16"], "traffic": None,
+                "avg_launch_us": dom_s * 1e6, "flops_per_launch": dom_flops,
+                "all_gemms_achieved": r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12}
+    extra["cfg5_wide_mlp_bf16"] = r5
+    del w5
+    torch.cuda.empty_cache()
+
+    if not args.quick:
+        log("workload 2: array primitives (8192 x 8192)")
+        extra["cfg2_array"] = bench_array(torch, B, W, timer, False)
+        log("workload 3: MLP 784-1000-1000-10, batch 1024")
+        w3 = W.config3()
+        for lowp in (False, True):
+            r = bench_mlp(torch, B, steps_mod, w3, lowp, timer, 100, 10)
+            extra["cfg3_mlp_%s" % ("bf16" if lowp else "f32")] = r
+            log("  %s: %.1f us/step  %.0f steps/s  %.2f TFLOP/s  (%d launches/step)" % (
+                "bf16" if lowp else "f32", r["ms_per_step"] * 1e3, r["steps_per_s"], r["TFLOP/s"], r["launch_calls_per_step"]))
+        log("workload 1: tiny MLP 784-100-100-10, batch 32")
+        r = bench_mlp(torch, B, steps_mod, W.config1(), False, timer, 200, 20)
+        extra["cfg1_tiny_mlp_f32"] = r
+        log("  %.1f us/step  %.0f steps/s" % (r["ms_per_step"] * 1e3, r["steps_per_s"]))
+        log("workload 4: LSTM language model step (vocab 10000, 650 hidden, batch 128, BPTT 35), fp32")
+        r = bench_lstm(torch, B, steps_mod, W.config4(), timer, 20, 3)
+        extra["cfg4_lstm_lm_f32"] = r
+        log("  %.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s (%.1f%% of fp32 MFMA peak; %d launches/step)" % (
+            r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"], 100 * r["frac_mfma_peak_f32"], r["launch_calls_per_step"]))
+
+    cpu = None
+    if not args.no_cpu:
+        log("cpu baseline: oracle on a bounded sample of workload 5")
+        cpu = cpu_baseline(W)
+        log("  %.3g steps/s on %d host threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
+
+    line = {
+        "metric": "train steps/s", "value": r5["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": r5["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg5: wide MLP 4096-4096-4096-4096-1000, GELU, softmax cross-entropy, batch 8192, "
+                               "bf16 storage / fp32 accumulate / fp32 master weights, forward+backward+SGD",
+                   "global_batch": 8192, "parallelism": "single GPU"},
+        "roofline": roofline, "cpu_baseline": cpu, "workloads": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -18,6 +18,10 @@ LIB = os.path.join(HERE, "libchn.so")
 SOURCES = ["host.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "softmax_ce.hip",
            "sgd.hip", "embed.hip"]
 
+# gemm_inst.hip is compiled once per (dtype, A layout, B layout): k = unit stride along K, m = along M/N
+GEMM_FAMILIES = [("%s_%s%s" % (tn, "k" if a else "m", "k" if b else "m"), t, a, b)
+                 for tn, t in (("f32", "float"), ("bf16", "bf16_raw")) for a in (1, 0) for b in (1, 0)]
+
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function",
@@ -31,26 +35,38 @@ def _stale(target, deps):
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def _compile(src, force, extra):
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    deps = [os.path.join(CSRC, src), os.path.join(CSRC, "common.h"),
-            os.path.join(ROOT, "include", "chn.h")]
+def _compile(job, force, extra):
+    src, objname, defs = job
+    obj = os.path.join(OBJ, objname + ".o")
+    deps = [os.path.join(CSRC, src), os.path.join(ROOT, "include", "chn.h")] + [
+        os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
+    extra = list(extra) + defs
     if force or _stale(obj, deps):
         cmd = ["hipcc"] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
-        return src, r.stderr
-    return src, ""
+        return objname, r.stderr
+    return objname, ""
+
+
+def _jobs():
+    jobs = [("gemm_inst.hip", "gemm_" + name,
+             ["-DCHN_GEMM_T=" + t, "-DCHN_GEMM_AKC=%d" % a, "-DCHN_GEMM_BKC=%d" % b,
+              "-DCHN_GEMM_NAME=launch_" + name]) for name, t, a, b in GEMM_FAMILIES]
+    jobs += [(s, os.path.splitext(s)[0], []) for s in SOURCES]
+    return jobs
 
 
 def build(force=False, verbose=False, extra=()):
     os.makedirs(OBJ, exist_ok=True)
-    with cf.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        for src, err in ex.map(lambda s: _compile(s, force, list(extra)), SOURCES):
+    jobs = _jobs()
+    with cf.ThreadPoolExecutor(max_workers=min(os.cpu_count() or 8, 16, len(jobs))) as ex:
+        for src, err in ex.map(lambda j: _compile(j, force, list(extra)), jobs):
+            err = "\n".join(l for l in err.splitlines() if "packed-fp32-ops" not in l)
             if verbose and err.strip():
                 print("[%s]\n%s" % (src, err))
-    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+    objs = [os.path.join(OBJ, j[1] + ".o") for j in jobs]
     if force or _stale(LIB, objs):
         cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
         subprocess.run(cmd, check=True)

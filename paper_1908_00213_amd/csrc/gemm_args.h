@@ -1,0 +1,27 @@
+// Kernel argument block of the GEMM kernels (shared by the host API and the kernel families).
+#pragma once
+#include <stdint.h>
+
+namespace chn {
+namespace gemm {
+
+struct GemmArgs {
+  const void *A, *B;
+  void *C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;  // elements; for a K-contiguous operand the stride between rows (m or n),
+                          // otherwise the stride between consecutive k
+  float alpha, beta;
+  int epi;
+  int c_bf16;             // C / aux / preact dtype: 0 fp32, 1 bf16
+  const float *bias;
+  const void *aux;
+  int64_t ldaux;
+  void *pre;
+  int64_t ldpre;
+  int piece;              // bytes per global load piece (16, 8 or the item size), common to A and B
+  int tiles_m, tiles_n;
+};
+
+}  // namespace gemm
+}  // namespace chn

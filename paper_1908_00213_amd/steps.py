@@ -1,0 +1,212 @@
+"""Training steps as sequences of C-ABI calls: the hand-unrolled tape of a define-by-run step.
+
+The paper's training step (Sections "On Demand Graph Construction" and "Background and Motivation")
+runs the forward computation operation by operation, then each recorded operation's backward once in
+reverse order, then the optimiser.  The classes below issue exactly that sequence for the two model
+families of the benchmark workloads.  All arithmetic happens inside libchn's kernels; Python only
+decides which call comes next.  Buffers are allocated once (PyTorch is the allocator), and the
+descriptor/argument list of every call is built once per input batch and replayed, so a step costs
+one foreign call per kernel launch and can be captured into a HIP graph.
+
+Linear layers follow the model-definition figure: W is (n_out, n_in), y = x @ W.T + b.
+Mixed precision (``lowp=True``): fp32 master weights with bf16 working copies refreshed by the SGD
+kernel; activations and activation gradients in bf16; logits, weight/bias gradients and the loss in
+fp32; every product accumulates in fp32.
+"""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _dev(a, lowp=False):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if lowp else t
+
+
+class _Program:
+    """A recorded list of foreign calls; every libchn entry point takes the stream last."""
+
+    def __init__(self):
+        self.calls = []
+        self._keep = []
+
+    def d(self, t):
+        if t is None:
+            return None
+        a = B.desc(t)
+        self._keep.append((a, t))
+        return C.byref(a)
+
+    def ptrs(self, tensors):
+        ds = [None if t is None else B.desc(t) for t in tensors]
+        arr = B._ptrs(ds)
+        self._keep.append((ds, arr, tensors))
+        return arr
+
+    def ws(self, t):
+        return (None, 0) if t is None else (C.c_void_p(t.data_ptr()), t.numel() * t.element_size())
+
+    def add(self, fn, *args):
+        self.calls.append((fn, args))
+
+    def run(self, stream=None):
+        s = C.c_void_p(torch.cuda.current_stream().cuda_stream) if stream is None else stream
+        for fn, args in self.calls:
+            st = fn(*args, s)
+            if st != 0:
+                B._check(st)
+
+
+def _gemm(p, L, A, Bm, Cm, alpha=1.0, beta=0.0, epi="none", bias=None, aux=None, pre=None):
+    p.add(L.chn_gemm, p.d(A), p.d(Bm), p.d(Cm), C.c_float(alpha), C.c_float(beta), B.EPI[epi],
+          p.d(bias), p.d(aux), p.d(pre), None, 0)
+
+
+class MLPTrainer:
+    """Forward + backward + SGD for an MLP with softmax cross-entropy (workloads 1, 3 and 5)."""
+
+    def __init__(self, params, batch, act="relu", lr=0.01, lowp=False):
+        self.L = B.lib()
+        self.act, self.lr, self.lowp, self.batch = act, float(lr), lowp, batch
+        self.W = [_dev(W) for W, _ in params]
+        self.b = [_dev(b) for _, b in params]
+        self.Wl = [w.to(torch.bfloat16) for w in self.W] if lowp else self.W
+        adt = torch.bfloat16 if lowp else torch.float32
+        n = len(params)
+        self.sizes = [params[0][0].shape[1]] + [W.shape[0] for W, _ in params]
+        mk = lambda *s, dt=torch.float32: torch.empty(*s, dtype=dt, device="cuda")
+        self.h = [None] + [mk(batch, self.sizes[l + 1], dt=adt) for l in range(n - 1)]
+        self.z = [None] + [mk(batch, self.sizes[l + 1], dt=adt) if act == "gelu" else None for l in range(n - 1)]
+        self.logits = mk(batch, self.sizes[-1])
+        self.dv = [None] + [mk(batch, self.sizes[l + 1], dt=adt) for l in range(n)]   # gradient wrt layer l's output
+        self.dW = [mk(*w.shape) for w in self.W]
+        self.db = [mk(*b.shape) for b in self.b]
+        self.loss = mk(())
+        self.lse = mk(batch)
+        self.ws_ce = torch.empty(B.softmax_ce_workspace_bytes(batch), dtype=torch.uint8, device="cuda")
+        need = max([B.reduce_axis_workspace_bytes(d, 0) for d in self.dv[1:]] + [256])
+        self.ws_red = torch.empty(need, dtype=torch.uint8, device="cuda")
+        self._progs = {}
+
+    def _build(self, x, t):
+        L, p, n = self.L, _Program(), len(self.W)
+        fwd_epi = "bias_relu" if self.act == "relu" else "bias_gelu"
+        bwd_epi = "relu_bwd" if self.act == "relu" else "gelu_bwd"
+        hs = [x] + self.h[1:]
+        # forward
+        for l in range(n):
+            last = l == n - 1
+            _gemm(p, L, hs[l], self.Wl[l].t(), self.logits if last else hs[l + 1],
+                  epi="bias" if last else fwd_epi, bias=self.b[l],
+                  pre=None if last or self.act == "relu" else self.z[l + 1])
+        wp, wn = p.ws(self.ws_ce)
+        p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
+        # backward, reverse order
+        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(t), -1, p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
+        rp, rn = p.ws(self.ws_red)
+        for l in range(n - 1, -1, -1):
+            dv = self.dv[l + 1]
+            _gemm(p, L, dv.t(), hs[l], self.dW[l])
+            p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(dv), 0, 0, p.d(self.db[l]), rp, rn)
+            if l > 0:
+                _gemm(p, L, dv, self.Wl[l], self.dv[l], epi=bwd_epi,
+                      aux=hs[l] if self.act == "relu" else self.z[l])
+        # optimiser: every parameter once
+        params = self.W + self.b
+        grads = self.dW + self.db
+        lows = (self.Wl + [None] * n) if self.lowp else None
+        p.add(L.chn_sgd_update_multi, len(params), p.ptrs(params), p.ptrs(grads), C.c_float(self.lr),
+              None if lows is None else p.ptrs(lows))
+        return p
+
+    def step(self, x, t, stream=None):
+        key = (x.data_ptr(), t.data_ptr())
+        if key not in self._progs:
+            self._progs[key] = self._build(x, t)
+        self._progs[key].run(stream)
+        return self.loss
+
+    def n_launch_calls(self, x, t):
+        self.step(x, t)
+        return len(self._progs[(x.data_ptr(), t.data_ptr())].calls)
+
+
+class LSTMTrainer:
+    """Forward + full BPTT + SGD for the single-layer LSTM language model (workload 4), fp32.
+
+    Time-major layout: row t*B + b of every (T*B, .) buffer belongs to step t, batch element b.
+    W (E,4H) and U (H,4H) give the gates as x W + h U + b; W_out (V,H) is a Linear layer.
+    """
+
+    def __init__(self, P, T, Bn, lr=0.01):
+        self.L = B.lib()
+        self.T, self.B, self.lr = T, Bn, float(lr)
+        self.P = {k: _dev(v) for k, v in P.items()}
+        V, E = P["E"].shape
+        H = P["U"].shape[0]
+        self.V, self.E, self.H = V, E, H
+        mk = lambda *s: torch.empty(*s, dtype=torch.float32, device="cuda")
+        n = T * Bn
+        self.X, self.Z, self.G = mk(n, E), mk(n, 4 * H), mk(n, 4 * H)
+        self.Hs = torch.zeros(n + Bn, H, dtype=torch.float32, device="cuda")   # block 0 = h_0 = 0
+        self.Cs = torch.zeros(n + Bn, H, dtype=torch.float32, device="cuda")   # block 0 = c_0 = 0
+        self.logits = mk(n, V)
+        self.dHs, self.dZ, self.dX = mk(n, H), mk(n, 4 * H), mk(n, E)
+        self.dc = [mk(Bn, H), mk(Bn, H)]
+        self.g = {k: mk(*v.shape) for k, v in self.P.items()}
+        self.loss, self.lse = mk(()), mk(n)
+        self.ws_ce = torch.empty(B.softmax_ce_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        need = max(B.reduce_axis_workspace_bytes(self.logits, 0), B.reduce_axis_workspace_bytes(self.dZ, 0), 256)
+        self.ws_red = torch.empty(need, dtype=torch.uint8, device="cuda")
+        self._progs = {}
+
+    def _build(self, ids, targets):
+        L, p, P, T, Bn = self.L, _Program(), self.P, self.T, self.B
+        blk = lambda buf, t: buf[t * Bn:(t + 1) * Bn]
+        ids_f, tg_f = ids.reshape(-1), targets.reshape(-1)
+        # forward
+        p.add(L.chn_embed_fwd, p.d(P["E"]), p.d(ids_f), p.d(self.X))
+        _gemm(p, L, self.X, P["W"], self.Z)                                   # x W for all steps at once
+        for t in range(T):
+            _gemm(p, L, blk(self.Hs, t), P["U"], blk(self.Z, t), beta=1.0)    # + h_{t-1} U
+            p.add(L.chn_lstm_fwd, p.d(blk(self.Z, t)), p.d(P["b"]), p.d(blk(self.Cs, t)),
+                  p.d(blk(self.Cs, t + 1)), p.d(blk(self.Hs, t + 1)), p.d(blk(self.G, t)))
+        Hall, Hprev = self.Hs[Bn:], self.Hs[:T * Bn]
+        _gemm(p, L, Hall, P["W_out"].t(), self.logits, epi="bias", bias=P["b_out"])
+        wp, wn = p.ws(self.ws_ce)
+        p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
+        # backward (dlogits overwrite the logits in place)
+        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.lse), C.c_float(1.0), p.d(self.logits), wp, wn)
+        rp, rn = p.ws(self.ws_red)
+        _gemm(p, L, self.logits.t(), Hall, self.g["W_out"])
+        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.logits), 0, 0, p.d(self.g["b_out"]), rp, rn)
+        _gemm(p, L, self.logits, P["W_out"], self.dHs)
+        for t in range(T - 1, -1, -1):
+            dc_next = None if t == T - 1 else self.dc[(t + 1) & 1]
+            p.add(L.chn_lstm_bwd, p.d(blk(self.G, t)), p.d(blk(self.Cs, t)), p.d(blk(self.Cs, t + 1)),
+                  p.d(blk(self.dHs, t)), p.d(dc_next), p.d(blk(self.dZ, t)), p.d(self.dc[t & 1]))
+            if t > 0:
+                _gemm(p, L, blk(self.dZ, t), P["U"].t(), blk(self.dHs, t - 1), beta=1.0)
+        _gemm(p, L, Hprev.t(), self.dZ, self.g["U"])
+        _gemm(p, L, self.X.t(), self.dZ, self.g["W"])
+        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.dZ), 0, 0, p.d(self.g["b"]), rp, rn)
+        _gemm(p, L, self.dZ, P["W"].t(), self.dX)
+        p.add(L.chn_embed_bwd, p.d(ids_f), p.d(self.dX), p.d(self.g["E"]), 0)
+        names = list(self.P.keys())
+        p.add(L.chn_sgd_update_multi, len(names), p.ptrs([P[k] for k in names]),
+              p.ptrs([self.g[k] for k in names]), C.c_float(self.lr), None)
+        return p
+
+    def step(self, ids, targets, stream=None):
+        key = (ids.data_ptr(), targets.data_ptr())
+        if key not in self._progs:
+            self._progs[key] = self._build(ids, targets)
+        self._progs[key].run(stream)
+        return self.loss
+
+    def n_launch_calls(self, ids, targets):
+        self.step(ids, targets)
+        return len(self._progs[(ids.data_ptr(), targets.data_ptr())].calls)

@@ -1,0 +1,116 @@
+"""GPU parity of whole training steps (forward + backward + SGD issued call by call through the C ABI)
+against the oracle's steps on the same seeded inputs: loss, every gradient and every updated
+parameter.  End-to-end errors are measured against each tensor's own scale (its largest magnitude),
+because a gradient entry is a long signed sum whose terms are of that size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from oracle import steps as OS
+from paper_1908_00213_amd import steps, workloads as W
+from tests.util import bf16r, check, host
+
+pytestmark = pytest.mark.gpu
+
+
+def cmp(got, ref, tol, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    check(host(got), ref, tol, float(np.max(np.abs(ref))) if ref.size else 0.0, what)
+
+
+def run_mlp(w, lowp, tol):
+    x, t = w.xs[0], w.ts[0]
+    if lowp:
+        x = bf16r(x)
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp)
+    xd = torch.from_numpy(x).cuda()
+    xd = xd.to(torch.bfloat16) if lowp else xd
+    td = torch.from_numpy(t).cuda()
+    loss = tr.step(xd, td)
+    r = OS.mlp_step(w.params, x, t, np.float32(w.lr), w.act, lowp)
+    assert abs(float(loss.cpu()) - r["loss"]) <= tol * max(1.0, abs(r["loss"])), (float(loss.cpu()), r["loss"])
+    cmp(tr.logits, r["logits"], tol, "logits")
+    lr = np.float32(w.lr)
+    for l, ((dW, db), (Wn, bn)) in enumerate(zip(r["grads"], r["params"])):
+        cmp(tr.dW[l], dW, tol, "dW%d" % l)
+        cmp(tr.db[l], db, tol, "db%d" % l)
+        # updated parameters: end to end they inherit lr * (gradient error); against the oracle's
+        # update of the GPU's own gradient (teacher-forced) they must agree to fp32 rounding
+        W0, b0 = w.params[l]
+        for got, old, g_gpu, new_ref, g_ref in ((tr.W[l], W0, tr.dW[l], Wn, dW), (tr.b[l], b0, tr.db[l], bn, db)):
+            check(host(got), O.sgd_update(old, host(g_gpu), lr), 1e-6, np.abs(old) + lr * np.abs(host(g_gpu)), "update %d" % l)
+            check(host(got), new_ref, 1e-6, np.abs(old) + float(lr) * tol * float(np.max(np.abs(g_ref))) / 1e-6, "param %d" % l)
+        if lowp:
+            assert np.array_equal(host(tr.Wl[l]), O.round_bf16(host(tr.W[l])))
+    return tr, xd, td
+
+
+def test_config1_tiny_mlp_step():
+    tr, xd, td = run_mlp(W.config1(), False, 1e-4)
+    # kernel launches per step: 3 forward products, loss (2), gradient (2), 3 dW + 3 db + 2 dx, 1 update
+    assert tr.n_launch_calls(xd, td) == 14
+
+
+def test_config3_mlp_step_fp32_and_bf16():
+    run_mlp(W.config3(n_batches=1), False, 1e-4)
+    run_mlp(W.config3(n_batches=1), True, 2e-2)
+
+
+def test_config5_scaled_wide_mlp_gelu_bf16_and_fp32():
+    w = W.config5(n_batches=1, scale=8)         # 512-512-512-512-1000, batch 1024
+    run_mlp(w, True, 2e-2)
+    run_mlp(w, False, 1e-4)
+
+
+def test_mlp_second_step_uses_updated_weights():
+    w = W.config1()
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, 0.5, False)
+    xd, td = torch.from_numpy(w.xs[0]).cuda(), torch.from_numpy(w.ts[0]).cuda()
+    l1 = float(tr.step(xd, td).cpu())
+    l2 = float(tr.step(xd, td).cpu())
+    r1 = OS.mlp_step(w.params, w.xs[0], w.ts[0], np.float32(0.5), w.act)
+    r2 = OS.mlp_step(r1["params"], w.xs[0], w.ts[0], np.float32(0.5), w.act)
+    assert abs(l1 - r1["loss"]) < 1e-4 and abs(l2 - r2["loss"]) < 1e-4 and l2 < l1
+
+
+def test_gradient_on_batch_is_mean_of_halves():
+    # the data-parallel identity of Section "Data and Model Parallelism", on one GPU
+    w = W.make_mlp("t", (40, 30, 7), 64, "relu", 5, 1)
+    grads = []
+    for sl in (slice(0, 64), slice(0, 32), slice(32, 64)):
+        n = sl.stop - sl.start
+        tr = steps.MLPTrainer(w.params, n, "relu", 0.0, False)
+        tr.step(torch.from_numpy(w.xs[0][sl]).cuda(), torch.from_numpy(w.ts[0][sl]).cuda())
+        grads.append([host(g) for g in tr.dW + tr.db])
+    for full, a, b in zip(*grads):
+        check(full, 0.5 * (a + b), 1e-4, float(np.max(np.abs(full))), "halves")
+
+
+@pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=72, batch=16, bptt=6),
+                                 dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])
+def test_config4_scaled_lstm_lm_step(cfg):
+    w = W.config4(**cfg)
+    w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr)
+    ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
+    loss = tr.step(ids, tg)
+    r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr))
+    assert abs(float(loss.cpu()) - r["loss"]) <= 1e-4 * abs(r["loss"])
+    lr = np.float32(w.lr)
+    for k in w.params:
+        cmp(tr.g[k], r["grads"][k], 1e-4, "d" + k)
+        check(host(tr.P[k]), O.sgd_update(w.params[k], host(tr.g[k]), lr), 1e-6,
+              np.abs(w.params[k]) + lr * np.abs(host(tr.g[k])), "update " + k)
+        check(host(tr.P[k]), r["params"][k], 1e-6,
+              np.abs(w.params[k]) + float(lr) * 1e-4 * float(np.max(np.abs(r["grads"][k]))) / 1e-6, k)
+    # rows of E that no token used keep a zero gradient and are unchanged bit for bit
+    unused = np.setdiff1d(np.arange(w.vocab), w.ids.reshape(-1))
+    assert np.all(host(tr.g["E"])[unused] == 0)
+    assert np.array_equal(host(tr.P["E"])[unused], w.params["E"][unused].astype(np.float64))
+    # a different window length (another graph topology) through the same code
+    tr2 = steps.LSTMTrainer(w.params, 2, w.batch, w.lr)
+    l2 = tr2.step(ids[:2].contiguous(), tg[:2].contiguous())
+    r2 = OS.lstm_lm_step(w.params, w.ids[:2], w.targets[:2], np.float32(w.lr))
+    assert abs(float(l2.cpu()) - r2["loss"]) <= 1e-4 * abs(r2["loss"])
+    cmp(tr2.g["U"], r2["grads"]["U"], 1e-4, "dU T=2")
