@@ -188,7 +188,7 @@ def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup):
             "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
 
 
-def cpu_baseline(W, rows=16):
+def cpu_baseline(W, rows=128):
     """The CPU oracle, as it stands, on a bounded sample of the headline workload: `rows` of the 8192
     batch rows through the full-width network (forward + backward + SGD), scaled to steps/s."""
     from oracle import oracle as O
