@@ -97,10 +97,15 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.pre = preact_out->data;
   }
   if (M == 0 || N == 0) return CHN_OK;
-  (void)csz;
   g.A = A->data; g.B = B->data; g.C = C->data;
   g.M = (int)M; g.N = (int)N; g.K = (int)K;
   g.alpha = alpha; g.beta = beta; g.epi = epilogue; g.c_bf16 = C->dtype == CHN_BF16;
+  {
+    const int vb = 4 * csz;  // bytes of a 4-element vector of C's dtype
+    auto ok = [&](const void *q, int64_t ld) { return q == nullptr || (reinterpret_cast<uintptr_t>(q) % vb == 0 && ld % 4 == 0); };
+    g.epi_vec = ok(g.C, g.ldc) && ok(g.aux, g.ldaux) && ok(g.pre, g.ldpre) &&
+                (g.bias == nullptr || reinterpret_cast<uintptr_t>(g.bias) % 16 == 0);
+  }
   const int pa = piece_bytes(A->data, g.lda, a_kc ? K : M, isz);
   const int pb = piece_bytes(B->data, g.ldb, b_kc ? K : N, isz);
   g.piece = pa < pb ? pa : pb;

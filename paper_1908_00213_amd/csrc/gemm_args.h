@@ -21,6 +21,7 @@ struct GemmArgs {
   int64_t ldpre;
   int piece;              // bytes per global load piece (16, 8 or the item size), common to A and B
   int tiles_m, tiles_n;
+  int epi_vec;            // C, aux, preact and bias allow aligned 4-element vector accesses
 };
 
 }  // namespace gemm

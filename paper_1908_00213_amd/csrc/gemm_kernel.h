@@ -8,22 +8,29 @@
 // Structure of one workgroup (256 threads = 4 waves in a 2x2 arrangement):
 //   * macro tile (64*TM) x (64*TN) of C, TM = TN in {4, 2, 1}; each wave owns TM x TN MFMA blocks
 //     of 32x32, i.e. up to 128x128 accumulators per wave held in registers;
-//   * the K loop advances 128 bytes of K per operand row per step (64 bf16 or 32 fp32).  Operand
-//     tiles live in LDS as rows of 128 bytes = 8 chunks of 16 bytes, always K-packed, with the chunk
-//     index XOR-swizzled by (row/2)%8 so that neither the 16-byte stores nor the 16-byte MFMA
-//     fragment reads collide on LDS banks, without padding;
+//   * the K loop advances one "tile step" of 128 bytes of K per operand row (64 bf16 or 32 fp32),
+//     made of four "k-steps" of two 16-byte chunks.  Operand tiles live in LDS as rows of 128 bytes
+//     = 8 chunks of 16 bytes, always K-packed, with the chunk index XOR-swizzled by (row/2)%8 so that
+//     neither the 16-byte stores nor the 16-byte MFMA fragment reads collide on LDS banks, without
+//     padding; two such stages (double buffering);
 //   * operands whose unit stride runs along K are copied chunk by chunk; operands whose unit stride
 //     runs along M/N (transposed views) are loaded in 16-byte pieces along M/N and transposed in
 //     registers (8x8 bf16 or 4x4 fp32 blocks) on their way into LDS, so the inner loop is the same
 //     for all four layout combinations and no second copy of an operand is ever made;
-//   * global loads for step t+1 are issued into registers before the MFMAs of step t and written to
-//     the other LDS buffer after them: one barrier per step;
+//   * software pipeline of one tile step (one wave per SIMD has nobody to hide its latencies, so the
+//     order is explicit): k-steps 0..2 multiply out of the current stage while the fragments of the
+//     following k-step are already being read; during k-step 2 the registers holding the next tile
+//     (loaded from HBM one whole tile step earlier) are written to the other stage and the loads of
+//     the tile after that are issued; one barrier; k-step 3 multiplies while the first fragments of
+//     the next stage are read;
 //   * since the sum over k is order-free, the 16 (8) k-values one lane feeds to an MFMA need not be
 //     the hardware's nominal ones as long as A and B agree; each lane therefore reads one whole
-//     16-byte chunk per 32 rows and step;
+//     16-byte chunk per 32 rows and k-step;
 //   * workgroups are renumbered so that the eight XCDs (which take consecutive workgroup ids
-//     round-robin) each work on a compact patch of C tiles and share operand tiles in their own L2.
-// The epilogue applies alpha/beta, bias, activation or activation-gradient in fp32 and rounds once.
+//     round-robin) each work on a compact patch of C tiles and share operand tiles in their own L2;
+//   * the epilogue stages each wave's accumulators through LDS (the operand stages are free by then)
+//     so that bias / activation / activation-gradient run on 16-byte vectors and C, aux and preact
+//     are accessed as whole 512-byte (fp32) or 256-byte (bf16) row segments; one final rounding.
 #pragma once
 #include "common.h"
 #include "gemm_args.h"
@@ -33,7 +40,9 @@ namespace gemm {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct Traits;
 template <> struct Traits<float> { static constexpr int EPC = 4; };      // elements per 16-byte chunk
@@ -45,29 +54,31 @@ __device__ __forceinline__ int lds_off(int row, int q) { return row * 128 + ((q 
 // value needs no masking (a select on loaded data would force the wave to wait for the load at once).
 __device__ const uint4 kZeroChunk = {0u, 0u, 0u, 0u};
 
-// Load one 16-byte chunk (EPC consecutive elements starting at p) in pieces of PB bytes without any
-// branch: a piece whose first element index is >= n_valid is read from the zero chunk instead.
-// Pieces never straddle the valid range because the host only picks a piece size that divides the
-// operand's extent along its unit-stride dimension.
-// Loads go through pointers that carry the global address space explicitly: a generic ("flat") load
-// would also count against the LDS counter and make every wait for an LDS read wait for HBM as well.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
+// Loads and stores go through pointers that carry the global address space explicitly: a generic
+// ("flat") access would also count against the LDS counter and make every wait for an LDS read wait
+// for HBM as well.
 template <typename V>
 __device__ __forceinline__ V global_load(uintptr_t addr) {
   return *reinterpret_cast<const __attribute__((address_space(1))) V *>(addr);
 }
+template <typename V>
+__device__ __forceinline__ void global_store(uintptr_t addr, V v) {
+  *reinterpret_cast<__attribute__((address_space(1))) V *>(addr) = v;
+}
 
+// Load one 16-byte chunk starting at address p in pieces of PB bytes without any branch: a piece
+// whose first element index is >= n_valid is read from the zero chunk instead.  Pieces never straddle
+// the valid range because the host only picks a piece size that divides the operand's extent along
+// its unit-stride dimension.
 template <typename T, int PB>
-__device__ __forceinline__ uint4 load_chunk(const T *p, int n_valid) {
+__device__ __forceinline__ uint4 load_chunk(uintptr_t p, int n_valid) {
   constexpr int PE = PB / (int)sizeof(T);   // elements per piece
   constexpr int NP = 16 / PB;               // pieces per chunk
   const uintptr_t zero = reinterpret_cast<uintptr_t>(&kZeroChunk);
   uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int j = 0; j < NP; ++j) {
-    const uintptr_t q = (j * PE < n_valid) ? reinterpret_cast<uintptr_t>(p + j * PE) : zero;
+    const uintptr_t q = (j * PE < n_valid) ? p + j * PB : zero;
     if constexpr (PB == 16) {
       const u32x4 v = global_load<u32x4>(q);
       w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
@@ -85,37 +96,58 @@ __device__ __forceinline__ uint4 load_chunk(const T *p, int n_valid) {
 }
 
 // One operand tile: ROWS rows (m or n) x 128 bytes of k, staged in registers between global memory
-// and LDS.
+// and LDS.  Everything that does not change from tile step to tile step (slot addresses, row
+// validity) is computed once in init().
 template <typename T, int ROWS, bool KC, int PB>
 struct TileLoader {
   static constexpr int EPC = Traits<T>::EPC;
   static constexpr int NS = ROWS / 32;                      // ROWS * 8 chunks / 256 threads
   static constexpr int NBLK = 8 * ROWS / EPC;               // EPC x EPC transpose blocks per tile
   static constexpr int NB = (NBLK + 255) / 256;             // ... per thread
+  static constexpr int NSLOT = KC ? NS : NB;
   uint4 reg[KC ? NS : NB * EPC];
+  uintptr_t ptr[NSLOT];   // address of the slot's first element for k0 = 0
+  int lim[NSLOT];         // KC: K - (k offset of the slot) for valid rows, else 0;  MC: rows_total - m or 0
+  int64_t kstride;        // bytes between consecutive k (MC only)
+  int K;
 
-  // rows_total: extent of the operand along m (or n); row0: first row of this tile; k0: first k.
-  __device__ __forceinline__ void load(const T *base, int64_t ld, int rows_total, int row0, int K, int k0) {
+  __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K_) {
+    K = K_;
+    kstride = ld * (int64_t)sizeof(T);
     if constexpr (KC) {
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
         const int s = threadIdx.x + i * 256;
-        const int row = row0 + (s >> 3), k = k0 + (s & 7) * EPC;
-        const int n_valid = row < rows_total ? K - k : 0;
-        reg[i] = load_chunk<T, PB>(base + (int64_t)row * ld + k, n_valid);
+        const int row = row0 + (s >> 3), kc = (s & 7) * EPC;
+        ptr[i] = reinterpret_cast<uintptr_t>(base + (int64_t)row * ld + kc);
+        lim[i] = row < rows_total ? K - kc : 0;
       }
     } else {
-      // blocks of EPC (k) x EPC (m): EPC loads of 16 bytes along m, one per k
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         const int blk = threadIdx.x + b * 256;
         const int kg = blk & 7, mc = blk >> 3;
         const int m = row0 + mc * EPC;
+        ptr[b] = reinterpret_cast<uintptr_t>(base + (int64_t)(kg * EPC) * ld + m);
+        lim[b] = blk < NBLK ? rows_total - m : 0;
+      }
+    }
+  }
+
+  // issue the global loads of the tile whose first k is k0
+  __device__ __forceinline__ void issue(int k0) {
+    if constexpr (KC) {
+#pragma unroll
+      for (int i = 0; i < NS; ++i)
+        reg[i] = load_chunk<T, PB>(ptr[i] + (int64_t)k0 * (int64_t)sizeof(T), lim[i] - k0);
+    } else {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        const int kg = (threadIdx.x + b * 256) & 7;
 #pragma unroll
         for (int j = 0; j < EPC; ++j) {
           const int k = k0 + kg * EPC + j;
-          const int n_valid = (blk < NBLK && k < K) ? rows_total - m : 0;
-          reg[b * EPC + j] = load_chunk<T, PB>(base + (int64_t)k * ld + m, n_valid);
+          reg[b * EPC + j] = load_chunk<T, PB>(ptr[b] + (int64_t)(k0 + j) * kstride, k < K ? lim[b] : 0);
         }
       }
     }
@@ -156,47 +188,146 @@ struct TileLoader {
   }
 };
 
-__device__ __forceinline__ float act_load(const void *p, int64_t idx, int is_bf16) {
-  return is_bf16 ? bf16_to_f32(static_cast<const bf16_raw *>(p)[idx]) : static_cast<const float *>(p)[idx];
-}
-
-__device__ __forceinline__ void out_store(void *p, int64_t idx, int is_bf16, float v) {
-  if (is_bf16) static_cast<bf16_raw *>(p)[idx] = f32_to_bf16(v);
-  else static_cast<float *>(p)[idx] = v;
-}
-
-// Epilogue of one 32x32 accumulator block: this lane's 16 values sit in column `col`, rows
-// row_base + 8*(v/4) + v%4.
-__device__ __forceinline__ void epilogue_block(const GemmArgs &g, const floatx16 &a, int row_base, int col) {
-  if (col >= g.N) return;
-  const float bias = (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) ? g.bias[col] : 0.0f;
+// MFMA operand fragments of one k-step: one 16-byte chunk per 32 rows of A and of B.
+template <int TM, int TN>
+struct Frags {
+  uint4 a[TM], b[TN];
+  // sa / sb: this lane's row inside the wave's A / B rows of the stage; off: swizzled chunk offset
+  __device__ __forceinline__ void read(const char *sa, const char *sb, int off) {
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int row = row_base + 8 * (v >> 2) + (v & 3);
-    if (row < g.M) {
-      const int64_t ci = (int64_t)row * g.ldc + col;
-      float x = g.alpha * a[v];
-      if (g.beta != 0.0f) x += g.beta * act_load(g.C, ci, g.c_bf16);
-      x += bias;
-      if (g.epi == CHN_EPI_BIAS_RELU) {
-        x = fmaxf(x, 0.0f);
-      } else if (g.epi == CHN_EPI_BIAS_GELU) {
-        if (g.pre) out_store(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, x);
-        x = gelu_f(x);
-      } else if (g.epi == CHN_EPI_RELU_BWD) {
-        x = act_load(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16) > 0.0f ? x : 0.0f;
-      } else if (g.epi == CHN_EPI_GELU_BWD) {
-        x *= gelu_grad_f(act_load(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16));
-      }
-      out_store(g.C, ci, g.c_bf16, x);
+    for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const uint4 *>(sa + i * (32 * 128) + off);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const uint4 *>(sb + j * (32 * 128) + off);
+  }
+};
+
+template <typename T, int TM, int TN>
+__device__ __forceinline__ void mma(floatx16 (&acc)[TM][TN], const Frags<TM, TN> &f) {
+  if constexpr (sizeof(T) == 2) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
+                                                            __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j], 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float((&f.a[i].x)[kk]),
+                                                           __uint_as_float((&f.b[j].x)[kk]), acc[i][j], 0, 0, 0);
+  }
+}
+
+// Scheduling hints (instruction-class masks of __builtin_amdgcn_sched_group_barrier).
+constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
+
+// `groups` times: `nr` LDS reads, then `nm` MFMAs.
+template <int GROUPS, int NR, int NM>
+__device__ __forceinline__ void sched_reads_mfma() {
+#pragma unroll
+  for (int g = 0; g < GROUPS; ++g) {
+    __builtin_amdgcn_sched_group_barrier(SG_DS_READ, NR, 0);
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM, 0);
+  }
+}
+
+// ---- epilogue helpers ------------------------------------------------------------------------------
+struct Vec4 { float v[4]; };
+
+__device__ __forceinline__ Vec4 load4(const void *p, int64_t idx, int is_bf16, bool vec, int n) {
+  Vec4 r;
+  if (vec) {
+    if (is_bf16) {
+      const u32x2 w = global_load<u32x2>(reinterpret_cast<uintptr_t>(static_cast<const bf16_raw *>(p) + idx));
+      r.v[0] = __uint_as_float(w[0] << 16); r.v[1] = __uint_as_float(w[0] & 0xffff0000u);
+      r.v[2] = __uint_as_float(w[1] << 16); r.v[3] = __uint_as_float(w[1] & 0xffff0000u);
+    } else {
+      const f32x4 w = global_load<f32x4>(reinterpret_cast<uintptr_t>(static_cast<const float *>(p) + idx));
+      r.v[0] = w[0]; r.v[1] = w[1]; r.v[2] = w[2]; r.v[3] = w[3];
     }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      r.v[e] = e < n ? (is_bf16 ? bf16_to_f32(static_cast<const bf16_raw *>(p)[idx + e]) : static_cast<const float *>(p)[idx + e]) : 0.0f;
+  }
+  return r;
+}
+
+__device__ __forceinline__ void store4(void *p, int64_t idx, int is_bf16, bool vec, int n, const Vec4 &x) {
+  if (vec) {
+    if (is_bf16) {
+      u32x2 w;
+      w[0] = (uint32_t)f32_to_bf16(x.v[0]) | ((uint32_t)f32_to_bf16(x.v[1]) << 16);
+      w[1] = (uint32_t)f32_to_bf16(x.v[2]) | ((uint32_t)f32_to_bf16(x.v[3]) << 16);
+      global_store<u32x2>(reinterpret_cast<uintptr_t>(static_cast<bf16_raw *>(p) + idx), w);
+    } else {
+      f32x4 w = {x.v[0], x.v[1], x.v[2], x.v[3]};
+      global_store<f32x4>(reinterpret_cast<uintptr_t>(static_cast<float *>(p) + idx), w);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (e < n) {
+        if (is_bf16) static_cast<bf16_raw *>(p)[idx + e] = f32_to_bf16(x.v[e]);
+        else static_cast<float *>(p)[idx + e] = x.v[e];
+      }
+  }
+}
+
+// Rows [row0, row0+32) x columns [col0, col0 + 32*TN) of C for one wave: `stage` holds the fp32
+// accumulators row-major with pitch PITCH floats.  Lane l handles 4 consecutive columns.
+template <int TN>
+__device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *stage, int row0, int col0, int lane) {
+  constexpr int W = 32 * TN, PITCH = W + 8, CPR = W / 4;      // 16-byte chunks per row
+  for (int c = lane; c < 32 * CPR; c += 64) {
+    const int rl = c / CPR, cl = (c % CPR) * 4;
+    const int row = row0 + rl, col = col0 + cl;
+    if (row >= g.M || col >= g.N) continue;
+    const int n = min(4, g.N - col);
+    const bool vec = g.epi_vec && n == 4;
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl);
+    Vec4 x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] = g.alpha * a[e];
+    const int64_t ci = (int64_t)row * g.ldc + col;
+    if (g.beta != 0.0f) {
+      const Vec4 c0 = load4(g.C, ci, g.c_bf16, vec, n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] += g.beta * c0.v[e];
+    }
+    if (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) {
+      const Vec4 b = load4(g.bias, col, 0, vec && (col & 3) == 0, n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] += b.v[e];
+    }
+    if (g.epi == CHN_EPI_BIAS_RELU) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] = fmaxf(x.v[e], 0.0f);
+    } else if (g.epi == CHN_EPI_BIAS_GELU) {
+      if (g.pre) store4(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, vec, n, x);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] = gelu_f(x.v[e]);
+    } else if (g.epi == CHN_EPI_RELU_BWD) {
+      const Vec4 y = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] = y.v[e] > 0.0f ? x.v[e] : 0.0f;
+    } else if (g.epi == CHN_EPI_GELU_BWD) {
+      const Vec4 z = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_f(z.v[e]);
+    }
+    store4(g.C, ci, g.c_bf16, vec, n, x);
   }
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int BK = 128 / sizeof(T);               // elements of k per step
+  constexpr int BK = 128 / sizeof(T);               // elements of k per tile step
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __align__(16) char lds[];
 
@@ -213,10 +344,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const int tn = (pid % width) / gsize;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const T *A = static_cast<const T *>(g.A);
-  const T *B = static_cast<const T *>(g.B);
   TileLoader<T, BM, A_KC, PB> la;
   TileLoader<T, BN, B_KC, PB> lb;
+  la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
+  lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -230,73 +361,92 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+  // byte offsets of this lane's fragment rows inside a stage, and of its chunk per k-step
+  const int a_row = (wm * TM * 32 + r) * 128, b_row = A_BYTES + (wn * TN * 32 + r) * 128;
+  const int sw = (r >> 1) & 7;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + h) ^ sw) << 4;
+
   const int nk = (g.K + BK - 1) / BK;
-  la.load(A, g.lda, g.M, m0, g.K, 0);
-  lb.load(B, g.ldb, g.N, n0, g.K, 0);
+  la.issue(0);
+  lb.issue(0);
   la.store(lds);
   lb.store(lds + A_BYTES);
+  la.issue(BK);
+  lb.issue(BK);
   __syncthreads();
+  Frags<TM, TN> f0, f1;
+  f0.read(lds + a_row, lds + b_row, koff[0]);
+
+  constexpr int NM = (sizeof(T) == 2 ? 1 : 4) * TM * TN;   // MFMAs per k-step
+  constexpr int NR = TM + TN;                              // fragment reads per k-step
+  constexpr bool kSched = TM == 4 && TN == 4;              // explicit interleaving for the big tile
 
   for (int kt = 0; kt < nk; ++kt) {
-    char *cur = lds + (kt & 1) * STAGE;
+    const char *cur = lds + (kt & 1) * STAGE;
     char *nxt = lds + ((kt + 1) & 1) * STAGE;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      la.load(A, g.lda, g.M, m0, g.K, (kt + 1) * BK);
-      lb.load(B, g.ldb, g.N, n0, g.K, (kt + 1) * BK);
-    }
-    const char *sa = cur + (wm * TM * 32 + r) * 128;
-    const char *sb = cur + A_BYTES + (wn * TN * 32 + r) * 128;
+    // k-step 0
+    f1.read(cur + a_row, cur + b_row, koff[1]);
+    mma<T, TM, TN>(acc, f0);
+    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
+    // k-step 1
+    f0.read(cur + a_row, cur + b_row, koff[2]);
+    mma<T, TM, TN>(acc, f1);
+    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
+    // k-step 2: also move the next tile from registers to the other stage.  The compiler must keep
+    // every LDS read ahead of every LDS write (it cannot tell the two stages apart), so the reads
+    // pair with the first half of the MFMAs and the writes with the second half.
+    f1.read(cur + a_row, cur + b_row, koff[3]);
+    la.store(nxt);
+    lb.store(nxt + A_BYTES);
+    mma<T, TM, TN>(acc, f0);
+    if constexpr (kSched) {
+      sched_reads_mfma<NR, 1, NM / NR / 2>();
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      uint4 fa[TM], fb[TN];
-      const int q = ks * 2 + h;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int row = wm * TM * 32 + i * 32 + r;
-        fa[i] = *reinterpret_cast<const uint4 *>(sa + i * 32 * 128 + ((q ^ ((row >> 1) & 7)) << 4));
+      for (int s = 0; s < NR; ++s) {
+        __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR / 2, 0);
       }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int row = wn * TN * 32 + j * 32 + r;
-        fb[j] = *reinterpret_cast<const uint4 *>(sb + j * 32 * 128 + ((q ^ ((row >> 1) & 7)) << 4));
-      }
-      if constexpr (sizeof(T) == 2) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-      } else {
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float((&fa[i].x)[kk]),
-                                                               __uint_as_float((&fb[j].x)[kk]), acc[i][j], 0, 0, 0);
-      }
-    }
-    if (more) {
-      la.store(nxt);
-      lb.store(nxt + A_BYTES);
     }
     __syncthreads();
+    // k-step 3, overlapped with the first fragment reads of the next stage and with the issue of the
+    // global loads for the tile after the next (they have until k-step 2 of the next tile step)
+    f0.read(nxt + a_row, nxt + b_row, koff[0]);
+    la.issue((kt + 2) * BK);
+    lb.issue((kt + 2) * BK);
+    mma<T, TM, TN>(acc, f1);
+    if constexpr (kSched) {
+#pragma unroll
+      for (int s = 0; s < NR; ++s) {
+        __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, 2 * (16 / PB), 0);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
+      }
+    }
   }
 
-  // ---- epilogue: lane holds, per 32x32 block, column r and rows 8*(v/4) + 4*h + v%4
+  // ---- epilogue: per wave and per 32-row block, accumulators -> LDS (row-major) -> vector epilogue.
+  // Lane holds, per 32x32 block, column r and rows 8*(v/4) + 4*h + v%4.
+  __syncthreads();   // every wave is done with the operand stages
+  constexpr int PITCH = 32 * TN + 8;
+  float *stage = reinterpret_cast<float *>(lds) + wave * (32 * PITCH);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
-      epilogue_block(g, acc[i][j], m0 + wm * TM * 32 + i * 32 + 4 * h, n0 + wn * TN * 32 + j * 32 + r);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + r] = acc[i][j][v];
+    __builtin_amdgcn_wave_barrier();
+    epilogue_rows<TN>(g, stage, m0 + (wm * TM + i) * 32, n0 + wn * TN * 32, lane);
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
 chn_status launch_piece(const GemmArgs &g, hipStream_t st) {
   constexpr int LDS = 2 * (64 * TM + 64 * TN) * 128;
+  static_assert(4 * 32 * (32 * TN + 8) * 4 <= LDS, "epilogue staging must fit in the operand stages");
   auto kern = gemm_kernel<T, TM, TN, A_KC, B_KC, PB>;
   static bool configured = false;  // per instantiation
   if (!configured) {
