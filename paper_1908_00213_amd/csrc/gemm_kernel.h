@@ -19,10 +19,9 @@
 //     for all four layout combinations and no second copy of an operand is ever made;
 //   * software pipeline of one tile step (one wave per SIMD has nobody to hide its latencies, so the
 //     order is explicit): k-steps 0..2 multiply out of the current stage while the fragments of the
-//     following k-step are already being read; during k-step 2 the registers holding the next tile
-//     (loaded from HBM one whole tile step earlier) are written to the other stage and the loads of
-//     the tile after that are issued; one barrier; k-step 3 multiplies while the first fragments of
-//     the next stage are read;
+//     following k-step are already being read; k-step 0 also issues the global loads of the next
+//     tile into registers, k-step 2 writes them to the other stage; one barrier; k-step 3 multiplies
+//     while the first fragments of the next stage are read;
 //   * since the sum over k is order-free, the 16 (8) k-values one lane feeds to an MFMA need not be
 //     the hardware's nominal ones as long as A and B agree; each lane therefore reads one whole
 //     16-byte chunk per 32 rows and k-step;
@@ -48,7 +47,19 @@ template <typename T> struct Traits;
 template <> struct Traits<float> { static constexpr int EPC = 4; };      // elements per 16-byte chunk
 template <> struct Traits<bf16_raw> { static constexpr int EPC = 8; };
 
-__device__ __forceinline__ int lds_off(int row, int q) { return row * 128 + ((q ^ ((row >> 1) & 7)) << 4); }
+// Byte offset of logical chunk q of tile row `row` inside a stage.  Two swizzles: the chunk index is
+// XORed with (row/2)%8, and rows swap places pairwise (row ^ 1) when bit log2(EPC) of the row is set.
+// The second one only matters to the transposing loader, whose 16 lanes of one LDS access write rows
+// r and r + EPC: without it both rows would sit in the same half of the banks.
+template <typename T>
+__device__ __forceinline__ int lds_row(int row) {
+  constexpr int BIT = sizeof(T) == 2 ? 3 : 2;
+  return row ^ ((row >> BIT) & 1);
+}
+template <typename T>
+__device__ __forceinline__ int lds_off(int row, int q) {
+  return lds_row<T>(row) * 128 + ((q ^ ((row >> 1) & 7)) << 4);
+}
 
 // Sixteen zero bytes in device memory: out-of-range pieces are redirected here, so that the loaded
 // value needs no masking (a select on loaded data would force the wave to wait for the load at once).
@@ -158,13 +169,15 @@ struct TileLoader {
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
         const int s = threadIdx.x + i * 256;
-        *reinterpret_cast<uint4 *>(lds + lds_off(s >> 3, s & 7)) = reg[i];
+        *reinterpret_cast<uint4 *>(lds + lds_off<T>(s >> 3, s & 7)) = reg[i];
       }
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
         const int blk = threadIdx.x + b * 256;
-        if (blk >= NBLK) continue;
+        if constexpr (NBLK % 256 != 0) {   // only small tiles have idle threads here; a branch in the
+          if (blk >= NBLK) continue;       // big tile's loop would split its scheduling region
+        }
         const int kg = blk & 7, mc = blk >> 3;
         const uint4 *r = &reg[b * EPC];
 #pragma unroll
@@ -176,12 +189,13 @@ struct TileLoader {
             uint32_t w[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
+              // one byte permute per output word: low halves (even e) or high halves (odd e) of lo, hi
               const uint32_t lo = (&r[2 * q].x)[e >> 1], hi = (&r[2 * q + 1].x)[e >> 1];
-              w[q] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+              w[q] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
             }
             o = make_uint4(w[0], w[1], w[2], w[3]);
           }
-          *reinterpret_cast<uint4 *>(lds + lds_off(mc * EPC + e, kg)) = o;
+          *reinterpret_cast<uint4 *>(lds + lds_off<T>(mc * EPC + e, kg)) = o;
         }
       }
     }
@@ -362,7 +376,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
   // byte offsets of this lane's fragment rows inside a stage, and of its chunk per k-step
-  const int a_row = (wm * TM * 32 + r) * 128, b_row = A_BYTES + (wn * TN * 32 + r) * 128;
+  const int rp = lds_row<T>(r);
+  const int a_row = (wm * TM * 32 + rp) * 128, b_row = A_BYTES + (wn * TN * 32 + rp) * 128;
   const int sw = (r >> 1) & 7;
   int koff[4];
 #pragma unroll
@@ -373,8 +388,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   lb.issue(0);
   la.store(lds);
   lb.store(lds + A_BYTES);
-  la.issue(BK);
-  lb.issue(BK);
   __syncthreads();
   Frags<TM, TN> f0, f1;
   f0.read(lds + a_row, lds + b_row, koff[0]);
@@ -386,36 +399,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   for (int kt = 0; kt < nk; ++kt) {
     const char *cur = lds + (kt & 1) * STAGE;
     char *nxt = lds + ((kt + 1) & 1) * STAGE;
-    // k-step 0
+    // k-step 0, overlapped with the issue of the global loads of the next tile (they are written to
+    // LDS in k-step 2; keeping issue and use inside one loop iteration keeps the staging registers
+    // from being carried -- and copied, which means waited for -- across the loop's back edge)
     f1.read(cur + a_row, cur + b_row, koff[1]);
+    la.issue((kt + 1) * BK);
+    lb.issue((kt + 1) * BK);
     mma<T, TM, TN>(acc, f0);
-    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
-    // k-step 1
-    f0.read(cur + a_row, cur + b_row, koff[2]);
-    mma<T, TM, TN>(acc, f1);
-    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
-    // k-step 2: also move the next tile from registers to the other stage.  The compiler must keep
-    // every LDS read ahead of every LDS write (it cannot tell the two stages apart), so the reads
-    // pair with the first half of the MFMAs and the writes with the second half.
-    f1.read(cur + a_row, cur + b_row, koff[3]);
-    la.store(nxt);
-    lb.store(nxt + A_BYTES);
-    mma<T, TM, TN>(acc, f0);
-    if constexpr (kSched) {
-      sched_reads_mfma<NR, 1, NM / NR / 2>();
-#pragma unroll
-      for (int s = 0; s < NR; ++s) {
-        __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR / 2, 0);
-      }
-    }
-    __syncthreads();
-    // k-step 3, overlapped with the first fragment reads of the next stage and with the issue of the
-    // global loads for the tile after the next (they have until k-step 2 of the next tile step)
-    f0.read(nxt + a_row, nxt + b_row, koff[0]);
-    la.issue((kt + 2) * BK);
-    lb.issue((kt + 2) * BK);
-    mma<T, TM, TN>(acc, f1);
     if constexpr (kSched) {
 #pragma unroll
       for (int s = 0; s < NR; ++s) {
@@ -424,6 +414,36 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
       }
     }
+    // k-step 1
+    f0.read(cur + a_row, cur + b_row, koff[2]);
+    mma<T, TM, TN>(acc, f1);
+    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
+    // k-step 2: also move the next tile from registers to the other stage.  The compiler must keep
+    // every LDS read ahead of every LDS write (it cannot tell the two stages apart), so the reads
+    // pair with the first half of the MFMAs and the writes with the second half.
+    f1.read(cur + a_row, cur + b_row, koff[3]);
+    if constexpr (A_KC) la.store(nxt);
+    if constexpr (B_KC) lb.store(nxt + A_BYTES);
+    mma<T, TM, TN>(acc, f0);
+    if constexpr (kSched) {
+      constexpr int NW = (A_KC ? TM * 2 : 0) + (B_KC ? TN * 2 : 0);   // 16-byte LDS writes interleaved
+      sched_reads_mfma<NR, 1, NM / NR / 2>();
+#pragma unroll
+      for (int s = 0; s < NR; ++s) {
+        __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, NW / NR, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR / 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // A transposed operand's first LDS write needs all of its loads (an 8x8 block is transposed in
+    // registers), so its wait would stall the MFMAs queued behind it: those writes go last.
+    if constexpr (!A_KC) la.store(nxt);
+    if constexpr (!B_KC) lb.store(nxt + A_BYTES);
+    __syncthreads();
+    // k-step 3, overlapped with the first fragment reads of the next stage
+    f0.read(nxt + a_row, nxt + b_row, koff[0]);
+    mma<T, TM, TN>(acc, f1);
+    if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
   }
 
   // ---- epilogue: per wave and per 32-row block, accumulators -> LDS (row-major) -> vector epilogue.
