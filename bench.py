@@ -211,6 +211,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--workloads", default="1,2,3,4", help="which of the secondary workloads to run (comma list)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -248,9 +249,11 @@ def main():
     del w5
     torch.cuda.empty_cache()
 
-    if not args.quick:
+    sel = set() if args.quick else set(x for x in args.workloads.split(",") if x)
+    if "2" in sel:
         log("workload 2: array primitives (8192 x 8192)")
         extra["cfg2_array"] = bench_array(torch, B, W, timer, False)
+    if "3" in sel:
         log("workload 3: MLP 784-1000-1000-10, batch 1024")
         w3 = W.config3()
         for lowp in (False, True):
@@ -258,10 +261,12 @@ def main():
             extra["cfg3_mlp_%s" % ("bf16" if lowp else "f32")] = r
             log("  %s: %.1f us/step  %.0f steps/s  %.2f TFLOP/s  (%d launches/step)" % (
                 "bf16" if lowp else "f32", r["ms_per_step"] * 1e3, r["steps_per_s"], r["TFLOP/s"], r["launch_calls_per_step"]))
+    if "1" in sel:
         log("workload 1: tiny MLP 784-100-100-10, batch 32")
         r = bench_mlp(torch, B, steps_mod, W.config1(), False, timer, 200, 20)
         extra["cfg1_tiny_mlp_f32"] = r
         log("  %.1f us/step  %.0f steps/s" % (r["ms_per_step"] * 1e3, r["steps_per_s"]))
+    if "4" in sel:
         log("workload 4: LSTM language model step (vocab 10000, 650 hidden, batch 128, BPTT 35), fp32")
         r = bench_lstm(torch, B, steps_mod, W.config4(), timer, 20, 3)
         extra["cfg4_lstm_lm_f32"] = r

@@ -101,13 +101,25 @@ template <> struct Elem<bf16_raw> {
   static __device__ __forceinline__ void store(bf16_raw *p, float v) { *p = f32_to_bf16(v); }
 };
 
-// 16-byte vector of T, converted to/from fp32 lanes.
+typedef float chn_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t chn_u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte vector of T, converted to/from fp32 lanes.  The *_nt forms carry the non-temporal hint:
+// streamed data that is touched once should not displace what the caches hold.
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
   static constexpr int N = 4;
   float4 raw;
   __device__ __forceinline__ void load(const float *p) { raw = *reinterpret_cast<const float4 *>(p); }
   __device__ __forceinline__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const float *p) {
+    const chn_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const chn_f32x4 *>(p));
+    raw = make_float4(v[0], v[1], v[2], v[3]);
+  }
+  __device__ __forceinline__ void store_nt(float *p) const {
+    const chn_f32x4 v = {raw.x, raw.y, raw.z, raw.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<chn_f32x4 *>(p));
+  }
   __device__ __forceinline__ float get(int i) const { return (&raw.x)[i]; }
   __device__ __forceinline__ void set(int i, float v) { (&raw.x)[i] = v; }
 };
@@ -116,6 +128,14 @@ template <> struct Vec16<bf16_raw> {
   uint4 raw;
   __device__ __forceinline__ void load(const bf16_raw *p) { raw = *reinterpret_cast<const uint4 *>(p); }
   __device__ __forceinline__ void store(bf16_raw *p) const { *reinterpret_cast<uint4 *>(p) = raw; }
+  __device__ __forceinline__ void load_nt(const bf16_raw *p) {
+    const chn_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const chn_u32x4 *>(p));
+    raw = make_uint4(v[0], v[1], v[2], v[3]);
+  }
+  __device__ __forceinline__ void store_nt(bf16_raw *p) const {
+    const chn_u32x4 v = {raw.x, raw.y, raw.z, raw.w};
+    __builtin_nontemporal_store(v, reinterpret_cast<chn_u32x4 *>(p));
+  }
   __device__ __forceinline__ float get(int i) const {
     uint32_t w = (&raw.x)[i >> 1];
     return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));

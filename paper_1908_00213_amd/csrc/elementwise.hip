@@ -13,6 +13,8 @@
 //   3  general   anything else: one thread per element, full index decomposition.
 // HBM-bound: 16-byte accesses per lane, several independent loads in flight per thread, more
 // workgroups than the 256 compute units can hold at once.
+#include <type_traits>
+
 #include "common.h"
 
 namespace chn {
@@ -72,6 +74,7 @@ struct Plan {
   int mode[3] = {0, 0, 0};               // family 0
   int64_t period[3] = {1, 1, 1};
   bool transposed[3] = {false, false, false};  // family 2
+  bool tvec = false;                           // family 2: every operand allows 16-byte accesses
 };
 
 chn_status make_plan(int op, int n_in, const chn_array *const *in, const chn_array *out, Plan *p) {
@@ -176,7 +179,19 @@ chn_status make_plan(int op, int n_in, const chn_array *const *in, const chn_arr
       if (istr[k][0] == 1) { p->transposed[k] = true; any = true; continue; }
       ok = false;
     }
-    if (ok && any) { p->family = 2; return CHN_OK; }
+    if (ok && any) {
+      p->family = 2;
+      // vector form: one dtype, extents and strides in whole 16-byte vectors, 16-byte aligned bases
+      const int e = 16 / osz;
+      bool v = n_in > 0 && in[0]->dtype == out->dtype && shape[0] % e == 0 && shape[1] % e == 0 &&
+               aligned16(out->data) && ostr[0] % e == 0;
+      for (int k = 0; k < n_in && v; ++k) {
+        if (p->transposed[k]) v = aligned16(in[k]->data) && istr[k][1] % e == 0;
+        else if (istr[k][1] == 1) v = aligned16(in[k]->data) && istr[k][0] % e == 0;
+      }
+      p->tvec = v;
+      return CHN_OK;
+    }
   }
   p->family = 3;
   return CHN_OK;
@@ -194,7 +209,7 @@ struct FlatArgs {
 };
 
 constexpr int kFlatThreads = 256;
-constexpr int kFlatUnroll = 4;
+constexpr int kFlatUnroll = 1;   // measured: one 16-byte vector per thread and a huge grid streams fastest
 
 template <typename T, int E>
 struct Pack {  // E fp32 lanes backed by 16-byte vectors of T
@@ -204,9 +219,13 @@ struct Pack {  // E fp32 lanes backed by 16-byte vectors of T
 #pragma unroll
     for (int i = 0; i < NV; ++i) v[i].load(p + i * Vec16<T>::N);
   }
-  __device__ __forceinline__ void store(T *p) const {
+  __device__ __forceinline__ void load_nt(const T *p) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) v[i].store(p + i * Vec16<T>::N);
+    for (int i = 0; i < NV; ++i) v[i].load_nt(p + i * Vec16<T>::N);
+  }
+  __device__ __forceinline__ void store_nt(T *p) const {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i].store_nt(p + i * Vec16<T>::N);
   }
   __device__ __forceinline__ float get(int i) const { return v[i / Vec16<T>::N].get(i % Vec16<T>::N); }
   __device__ __forceinline__ void set(int i, float x) { v[i / Vec16<T>::N].set(i % Vec16<T>::N, x); }
@@ -230,7 +249,7 @@ __global__ __launch_bounds__(kFlatThreads) void ew_flat_kernel(FlatArgs a) {
       for (int k = 0; k < NIN; ++k) {
         const Tin *p = static_cast<const Tin *>(a.in[k]);
         if (a.mode[k] == MODE_FULL) {
-          x[u][k].load(p + v * E);
+          x[u][k].load_nt(p + v * E);
         } else if (a.mode[k] == MODE_PERIODIC) {
           // 32-bit remainder when the index fits: 64-bit division is a long instruction sequence
           const int64_t off = a.total <= 0xffffffffll
@@ -258,7 +277,7 @@ __global__ __launch_bounds__(kFlatThreads) void ew_flat_kernel(FlatArgs a) {
         for (int k = 0; k < NIN; ++k) f[k] = a.mode[k] == MODE_SCALAR ? sc[k] : x[u][k].get(i);
         r.set(i, ew_apply<OP>(f[0], f[1], f[2], a.s0));
       }
-      r.store(static_cast<Tout *>(a.out) + v * E);
+      r.store_nt(static_cast<Tout *>(a.out) + v * E);
     }
   }
   // ragged tail (fewer than E elements), handled by the first threads of block 0
@@ -348,6 +367,7 @@ struct TransArgs {
   int64_t ostr0;
   int64_t istr0[3], istr1[3];
   int transposed[3];
+  int slot[3];   // vector form: which 16 KB LDS tile a transposed input uses
   float s0;
 };
 
@@ -391,6 +411,76 @@ __global__ __launch_bounds__(256) void ew_transpose_kernel(TransArgs a, int64_t 
   }
 }
 
+// family 2, vector form: 16-byte global accesses on every operand.  A tile is 64 columns x 16 vectors
+// of rows (64 fp32 / 128 bf16 rows).  A transposed input is read along its unit-stride (row) axis,
+// 16 bytes per lane and 256 contiguous bytes per 16 lanes, and parked in LDS as [column][row], the
+// 16-byte chunk index XORed with (column / E) so that both the 16-byte writes and the later
+// element reads along a column are free of bank conflicts.  The compute phase then walks rows:
+// each lane produces E consecutive columns of one row, gathering the transposed operands element by
+// element from LDS and everything else with 16-byte global loads, and stores 16 bytes.
+template <int OP, typename T, int NIN>
+__global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int64_t tiles_c) {
+  constexpr int E = 16 / (int)sizeof(T);
+  constexpr int TC = 64, TR = 16 * E;
+  constexpr int VPR = TC / E, RPP = 256 / VPR;
+  extern __shared__ __align__(16) char tiles[];   // one 16 KB tile per transposed input
+  const int t = threadIdx.x;
+  const int64_t r0 = ((int64_t)blockIdx.x / tiles_c) * TR;
+  const int64_t c0 = ((int64_t)blockIdx.x % tiles_c) * TC;
+  {
+    const int rchunk = t & 15, cl = t >> 4;
+    const int64_t r = r0 + rchunk * E;
+#pragma unroll
+    for (int k = 0; k < NIN; ++k) {
+      if (!a.transposed[k]) continue;
+      const T *p = static_cast<const T *>(a.in[k]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = cl + 16 * j;
+        Vec16<T> v;
+        v.raw = {};
+        if (r < a.rows && c0 + c < a.cols) v.load_nt(p + r + (c0 + c) * a.istr1[k]);
+        const int key = (c / E) & 15;
+        *reinterpret_cast<decltype(v.raw) *>(tiles + a.slot[k] * (TC * 256) + c * 256 + ((rchunk ^ key) << 4)) = v.raw;
+      }
+    }
+  }
+  __syncthreads();
+  const int cq = t % VPR, rr = t / VPR;
+  const int64_t c = c0 + cq * E;
+#pragma unroll
+  for (int pass = 0; pass < TR / RPP; ++pass) {
+    const int rl = rr + pass * RPP;
+    const int64_t r = r0 + rl;
+    if (r < a.rows && c < a.cols) {
+      float f[3][E];
+#pragma unroll
+      for (int k = 0; k < NIN; ++k) {
+        const T *p = static_cast<const T *>(a.in[k]);
+        if (a.transposed[k]) {
+          const char *base = tiles + a.slot[k] * (TC * 256) + (((rl / E) ^ (cq & 15)) << 4) + (rl % E) * (int)sizeof(T);
+#pragma unroll
+          for (int i = 0; i < E; ++i) f[k][i] = Elem<T>::load(reinterpret_cast<const T *>(base + (cq * E + i) * 256));
+        } else if (a.istr1[k] == 0) {
+          const float v = Elem<T>::load(p + r * a.istr0[k]);
+#pragma unroll
+          for (int i = 0; i < E; ++i) f[k][i] = v;
+        } else {
+          Vec16<T> v;
+          if (a.istr0[k] == 0) v.load(p + c); else v.load_nt(p + r * a.istr0[k] + c);
+#pragma unroll
+          for (int i = 0; i < E; ++i) f[k][i] = v.get(i);
+        }
+      }
+      Vec16<T> o;
+#pragma unroll
+      for (int i = 0; i < E; ++i)
+        o.set(i, ew_apply<OP>(f[0][i], NIN > 1 ? f[1][i] : 0.0f, NIN > 2 ? f[2][i] : 0.0f, a.s0));
+      o.store_nt(static_cast<T *>(a.out) + r * a.ostr0 + c);
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // dispatch
 template <int OP, typename Tin, typename Tout>
@@ -417,6 +507,17 @@ chn_status launch_fast(const Plan &p, const chn_array *const *in, const chn_arra
   int64_t tr = (a.rows + kTile - 1) / kTile, tc = (a.cols + kTile - 1) / kTile;
   if (tr * tc > 0x7fffffff) return fail(CHN_ERR_SHAPE, "elementwise: array too large");
   if constexpr (NIN > 0) {
+    if constexpr (std::is_same<Tin, Tout>::value) {
+      if (p.tvec) {
+        constexpr int TRV = 16 * (16 / (int)sizeof(Tin));
+        const int64_t trv = (a.rows + TRV - 1) / TRV;
+        if (trv * tc > 0x7fffffff) return fail(CHN_ERR_SHAPE, "elementwise: array too large");
+        int nslots = 0;
+        for (int k = 0; k < NIN; ++k) a.slot[k] = a.transposed[k] ? nslots++ : 0;
+        hipLaunchKernelGGL((ew_transpose_vec_kernel<OP, Tin, NIN>), dim3((unsigned)(trv * tc)), dim3(256), nslots * 64 * 256, st, a, tc);
+        return check_launch("elementwise transpose (vector)");
+      }
+    }
     hipLaunchKernelGGL((ew_transpose_kernel<OP, Tin, Tout, NIN>), dim3((unsigned)(tr * tc)), dim3(256), 0, st, a, tc);
   }
   return check_launch("elementwise transpose");

@@ -36,10 +36,13 @@ struct RPlan {
   int split = 1;
   int64_t rows_per_split = 0;
   bool vec = false;
+  int tx = 64;               // column groups per block
   size_t ws_bytes = 0;
 };
 
-constexpr int kColTX = 64, kColTY = 4;
+// COL kernel block shapes (column groups x row lanes = 256 threads): 16 x 16 for the large streaming
+// case (more column blocks, hence fewer row splits and a smaller second pass), 64 x 4 otherwise.
+constexpr int kColTXWide = 16, kColTXNarrow = 64;
 
 chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
   CHN_TRY(validate(in, "in", false));
@@ -79,11 +82,13 @@ chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
     p->sO = nk == 2 ? p->kstr[0] : 0;
     const int n = 16 / isz;
     p->vec = reinterpret_cast<uintptr_t>(in->data) % 16 == 0 && p->I % n == 0 && p->sR % n == 0 && p->sO % n == 0;
-    const int64_t cols_per_block = (int64_t)kColTX * (p->vec ? n : 1);
+    const int64_t groups = p->I / (p->vec ? n : 1);
+    p->tx = (p->vec && groups >= 512 && p->len >= 1024) ? kColTXWide : kColTXNarrow;
+    const int64_t cols_per_block = (int64_t)p->tx * (p->vec ? n : 1);
     const int64_t blocks_xy = ((p->I + cols_per_block - 1) / cols_per_block) * p->O;
-    int64_t s = (2048 + blocks_xy - 1) / blocks_xy;
-    int64_t max_s = p->len / 64;
-    if (s > max_s) s = max_s;
+    // Measured on 8192 x 8192: many short blocks (8 rows per thread) stream best.
+    int64_t s = p->len / (8 * (256 / p->tx));
+    if (blocks_xy * s > 16384) s = 16384 / blocks_xy;
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
     p->split = (int)s;
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(256) void reduce_row_kernel(const Tin *in, Tout *ou
       for (; v + 3 * G < nvec; v += 4 * G) {
         Vec16<Tin> x[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) x[u].load(p + (v + u * G) * N);
+        for (int u = 0; u < 4; ++u) x[u].load_nt(p + (v + u * G) * N);
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -160,10 +165,11 @@ __global__ __launch_bounds__(256) void reduce_row_kernel(const Tin *in, Tout *ou
 }
 
 // COL: out[o, i] (or partial[s, o, i]) = fold over r in this block's slice of in[o*sO + r*sR + i].
-template <int OP, typename Tin, typename Tout, bool VEC>
+template <int OP, typename Tin, typename Tout, bool VEC, int kColTX>
 __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *out, int64_t R, int64_t I, int64_t sO, int64_t sR,
                                                          int64_t rows_per_split, int64_t out_split_stride) {
   constexpr int N = VEC ? Vec16<Tin>::N : 1;
+  constexpr int kColTY = 256 / kColTX;
   const int tx = threadIdx.x % kColTX, ty = threadIdx.x / kColTX;
   const int64_t col = ((int64_t)blockIdx.x * kColTX + tx) * N;
   const int64_t o = blockIdx.z;
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *ou
       for (; r + 3 * kColTY < r_end; r += 4 * kColTY) {
         Vec16<Tin> x[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) x[u].load(p + (r + u * kColTY) * sR);
+        for (int u = 0; u < 4; ++u) x[u].load_nt(p + (r + u * kColTY) * sR);
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -238,13 +244,15 @@ __global__ __launch_bounds__(256) void reduce_gen_kernel(const Tin *in, Tout *ou
 
 template <int OP, typename Tin, typename Tout>
 chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64_t R, int64_t I, int64_t sO, int64_t sR,
-                      int split, int64_t rps, int64_t split_stride, bool vec, hipStream_t st) {
+                      int split, int64_t rps, int64_t split_stride, bool vec, int tx, hipStream_t st) {
+  if (!vec) tx = kColTXNarrow;
   const int n = vec ? 16 / (int)sizeof(Tin) : 1;
-  const int64_t cpb = (int64_t)kColTX * n;
+  const int64_t cpb = (int64_t)tx * n;
   dim3 grid((unsigned)((I + cpb - 1) / cpb), (unsigned)split, (unsigned)O);
   if (O > 65535) return fail(CHN_ERR_SHAPE, "reduce: outer extent %lld too large for the column kernel", (long long)O);
-  if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
-  else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  if (vec && tx == kColTXWide) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXWide>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   (void)p;
   return check_launch("reduce col");
 }
@@ -273,11 +281,11 @@ chn_status launch(const RPlan &p, const chn_array *in, const chn_array *out, voi
   }
   if (p.kind == KIND_COL) {
     if (p.split == 1)
-      return launch_col<OP, Tin, Tout>(src, dst, p, p.O, p.len, p.I, p.sO, p.sR, 1, p.len, 0, p.vec, st);
+      return launch_col<OP, Tin, Tout>(src, dst, p, p.O, p.len, p.I, p.sO, p.sR, 1, p.len, 0, p.vec, p.tx, st);
     float *part = static_cast<float *>(ws);
     const int64_t OI = p.O * p.I;
-    CHN_TRY((launch_col<OP, Tin, float>(src, part, p, p.O, p.len, p.I, p.sO, p.sR, p.split, p.rows_per_split, OI, p.vec, st)));
-    return launch_col<OP, float, Tout>(part, dst, p, 1, p.split, OI, 0, OI, 1, p.split, 0, OI % 4 == 0, st);
+    CHN_TRY((launch_col<OP, Tin, float>(src, part, p, p.O, p.len, p.I, p.sO, p.sR, p.split, p.rows_per_split, OI, p.vec, p.tx, st)));
+    return launch_col<OP, float, Tout>(part, dst, p, 1, p.split, OI, 0, OI, 1, p.split, 0, OI % 4 == 0, kColTXNarrow, st);
   }
   GenArgs a{};
   a.nk = p.nk; a.len = p.len; a.sR = p.sR; a.total_out = p.total_out;

@@ -102,7 +102,7 @@ def test_broadcast_patterns(dt):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(200, 330), (64, 64), (65, 63), (1000, 7)])
+@pytest.mark.parametrize("shape", [(200, 330), (64, 64), (65, 63), (1000, 7), (200, 328), (264, 136), (1032, 520), (8, 8)])
 def test_transposed_view(dt, shape):
     r, c = shape
     a_store = rnd((c, r), dt)                 # a is the transpose view of a contiguous (c, r) buffer
