@@ -156,6 +156,17 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   float phi = 0.39894228040143267794f * expf(-0.5f * x * x);
   return Phi + x * phi;
 }
+// Cheaper forms for GEMM epilogues, where the argument already carries the rounding error of a long
+// fp32 sum: erf instead of erfc (absolute instead of relative accuracy in the negative tail) and the
+// hardware exponential.
+__device__ __forceinline__ float gelu_epi_f(float x) {
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_grad_epi_f(float x) {
+  const float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
+  const float phi = 0.39894228040143267794f * __expf(-0.5f * x * x);
+  return Phi + x * phi;
+}
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
 
 // Wave-wide (64 lanes) sum / max by butterfly exchange.

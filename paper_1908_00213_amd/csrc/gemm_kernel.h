@@ -324,7 +324,7 @@ __device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *st
     } else if (g.epi == CHN_EPI_BIAS_GELU) {
       if (g.pre) store4(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, vec, n, x);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] = gelu_f(x.v[e]);
+      for (int e = 0; e < 4; ++e) x.v[e] = gelu_epi_f(x.v[e]);
     } else if (g.epi == CHN_EPI_RELU_BWD) {
       const Vec4 y = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
 #pragma unroll
@@ -332,7 +332,7 @@ __device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *st
     } else if (g.epi == CHN_EPI_GELU_BWD) {
       const Vec4 z = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_f(z.v[e]);
+      for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_epi_f(z.v[e]);
     }
     store4(g.C, ci, g.c_bf16, vec, n, x);
   }
