@@ -29,21 +29,78 @@ int piece_bytes(const void *p, int64_t ld_elems, int64_t extent_elems, int isz) 
   return isz;
 }
 
+// Operand layouts (which dimension has unit stride), leading dimensions and load piece size.
+chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a_kc, bool *b_kc) {
+  const int isz = dtype_size(A->dtype);
+  const int64_t M = A->shape[0], K = A->shape[1], N = B->shape[1];
+  auto unit = [&](const chn_array *X, int d) { return X->shape[d] <= 1 || X->strides[d] == isz; };
+  if (unit(A, 1)) { *a_kc = true; g->lda = M > 1 ? A->strides[0] / isz : K; }
+  else if (unit(A, 0)) { *a_kc = false; g->lda = K > 1 ? A->strides[1] / isz : M; }
+  else return fail(CHN_ERR_STRIDE, "gemm: A needs a unit-stride dimension");
+  if (unit(B, 0)) { *b_kc = true; g->ldb = N > 1 ? B->strides[1] / isz : K; }
+  else if (unit(B, 1)) { *b_kc = false; g->ldb = K > 1 ? B->strides[0] / isz : N; }
+  else return fail(CHN_ERR_STRIDE, "gemm: B needs a unit-stride dimension");
+  if ((*a_kc && M > 1 && g->lda < K) || (!*a_kc && K > 1 && g->lda < M) || (*b_kc && N > 1 && g->ldb < K) || (!*b_kc && K > 1 && g->ldb < N))
+    return fail(CHN_ERR_STRIDE, "gemm: overlapping (broadcast) operand rows are not supported");
+  const int pa = piece_bytes(A->data, g->lda, *a_kc ? K : M, isz);
+  const int pb = piece_bytes(B->data, g->ldb, *b_kc ? K : N, isz);
+  g->piece = pa < pb ? pa : pb;
+  if (K == 0) { *a_kc = *b_kc = true; g->piece = isz; }  // nothing to multiply: every load is redirected to zeros
+  g->M = (int)M; g->N = (int)N; g->K = (int)K;
+  return CHN_OK;
+}
+
+// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits.  A problem with too few
+// 64x64 tiles to occupy the 256 compute units but a long K is cut along K: every split writes fp32
+// partial sums to the workspace and a second kernel adds them in a fixed order and runs the epilogue.
+void plan(GemmArgs *g, int isz) {
+  auto tiles = [&](int b) { return (int64_t)((g->M + b - 1) / b) * ((g->N + b - 1) / b); };
+  const bool wide = g->piece >= 8;   // operands that need element-wise loads only get the small tile
+  g->splits = 1;
+  if (wide && tiles(256) >= 192) g->tile = 2;
+  else if (wide && tiles(128) >= 128) g->tile = 1;
+  else {
+    g->tile = 0;
+    const int64_t t = tiles(64);
+    const int nk = (g->K + 128 / isz - 1) / (128 / isz);   // tile steps along K
+    if (t < 128 && nk >= 8) {
+      int64_t s = (256 + t - 1) / t;
+      if (s > nk / 4) s = nk / 4;
+      if (s > 16) s = 16;
+      if (s >= 2) g->splits = (int)s;
+    }
+  }
+  const int b = g->tile == 2 ? 256 : g->tile == 1 ? 128 : 64;
+  g->tiles_m = (g->M + b - 1) / b;
+  g->tiles_n = (g->N + b - 1) / b;
+  g->ldp = (g->N + 3) & ~3;
+}
+
+size_t split_bytes(const GemmArgs &g) {
+  return g.splits > 1 ? (size_t)g.splits * g.M * g.ldp * sizeof(float) : 0;
+}
+
 }  // namespace
 }  // namespace chn
 
 extern "C" {
 
 size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const chn_array *C) {
-  (void)A; (void)B; (void)C;
-  return 0;
+  using namespace chn;
+  if (!A || !B || !C || A->ndim != 2 || B->ndim != 2 || !is_float(A->dtype) || A->dtype != B->dtype) return 0;
+  if (A->shape[1] != B->shape[0] || A->shape[0] <= 0 || B->shape[1] <= 0) return 0;
+  if (A->shape[0] > 0x3fffffff || A->shape[1] > 0x3fffffff || B->shape[1] > 0x3fffffff) return 0;
+  GemmArgs g{};
+  bool a_kc, b_kc;
+  if (classify(A, B, &g, &a_kc, &b_kc) != CHN_OK) return 0;
+  plan(&g, dtype_size(A->dtype));
+  return split_bytes(g);
 }
 
 chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, float alpha, float beta,
                     int epilogue, const chn_array *bias, const chn_array *aux, const chn_array *preact_out,
                     void *ws, size_t ws_bytes, chn_stream stream) {
   using namespace chn;
-  (void)ws; (void)ws_bytes;
   CHN_TRY(validate(A, "A", false));
   CHN_TRY(validate(B, "B", false));
   CHN_TRY(validate(C, "C", true));
@@ -60,17 +117,8 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
   GemmArgs g{};
   int64_t cr, cc;
   CHN_TRY(row_major_2d(C, "C", &cr, &cc, &g.ldc));
-  // operand layouts: which dimension has unit stride
-  auto unit = [&](const chn_array *X, int d) { return X->shape[d] <= 1 || X->strides[d] == isz; };
   bool a_kc, b_kc;
-  if (unit(A, 1)) { a_kc = true; g.lda = M > 1 ? A->strides[0] / isz : K; }
-  else if (unit(A, 0)) { a_kc = false; g.lda = K > 1 ? A->strides[1] / isz : M; }
-  else return fail(CHN_ERR_STRIDE, "gemm: A needs a unit-stride dimension");
-  if (unit(B, 0)) { b_kc = true; g.ldb = N > 1 ? B->strides[1] / isz : K; }
-  else if (unit(B, 1)) { b_kc = false; g.ldb = K > 1 ? B->strides[0] / isz : N; }
-  else return fail(CHN_ERR_STRIDE, "gemm: B needs a unit-stride dimension");
-  if ((a_kc && M > 1 && g.lda < K) || (!a_kc && K > 1 && g.lda < M) || (b_kc && N > 1 && g.ldb < K) || (!b_kc && K > 1 && g.ldb < N))
-    return fail(CHN_ERR_STRIDE, "gemm: overlapping (broadcast) operand rows are not supported");
+  CHN_TRY(classify(A, B, &g, &a_kc, &b_kc));
   const bool needs_bias = epilogue >= CHN_EPI_BIAS && epilogue <= CHN_EPI_BIAS_GELU;
   const bool needs_aux = epilogue == CHN_EPI_RELU_BWD || epilogue == CHN_EPI_GELU_BWD;
   if (needs_bias) {
@@ -98,7 +146,6 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
   }
   if (M == 0 || N == 0) return CHN_OK;
   g.A = A->data; g.B = B->data; g.C = C->data;
-  g.M = (int)M; g.N = (int)N; g.K = (int)K;
   g.alpha = alpha; g.beta = beta; g.epi = epilogue; g.c_bf16 = C->dtype == CHN_BF16;
   {
     const int vb = 4 * csz;  // bytes of a 4-element vector of C's dtype
@@ -106,10 +153,12 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.epi_vec = ok(g.C, g.ldc) && ok(g.aux, g.ldaux) && ok(g.pre, g.ldpre) &&
                 (g.bias == nullptr || reinterpret_cast<uintptr_t>(g.bias) % 16 == 0);
   }
-  const int pa = piece_bytes(A->data, g.lda, a_kc ? K : M, isz);
-  const int pb = piece_bytes(B->data, g.ldb, b_kc ? K : N, isz);
-  g.piece = pa < pb ? pa : pb;
-  if (K == 0) { a_kc = b_kc = true; g.piece = isz; }  // nothing to multiply: every load is redirected to zeros
+  plan(&g, isz);
+  if (g.splits > 1) {
+    // split-K is an optimisation: without (enough, aligned) workspace the product runs unsplit
+    if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);
+    else g.splits = 1;
+  }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {
     if (a_kc) return b_kc ? gemm::launch_f32_kk(g, st) : gemm::launch_f32_km(g, st);

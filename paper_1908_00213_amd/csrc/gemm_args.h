@@ -21,6 +21,10 @@ struct GemmArgs {
   int64_t ldpre;
   int piece;              // bytes per global load piece (16, 8 or the item size), common to A and B
   int tiles_m, tiles_n;
+  int tile;               // macro tile: 2 = 256x256, 1 = 128x128, 0 = 64x64
+  int splits;             // number of K splits (1 = none)
+  float *partial;         // split-K: [splits][M][ldp] fp32 partial sums in the caller's workspace
+  int64_t ldp;
   int epi_vec;            // C, aux, preact and bias allow aligned 4-element vector accesses
 };
 

@@ -292,50 +292,72 @@ __device__ __forceinline__ void store4(void *p, int64_t idx, int is_bf16, bool v
   }
 }
 
+// alpha/beta, bias, activation or activation gradient and the single final rounding for the four
+// consecutive columns col.. of row `row`, whose fp32 sums are in `a`.
+__device__ __forceinline__ void finish4(const GemmArgs &g, int row, int col, const f32x4 a) {
+  const int n = min(4, g.N - col);
+  const bool vec = g.epi_vec && n == 4;
+  Vec4 x;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) x.v[e] = g.alpha * a[e];
+  const int64_t ci = (int64_t)row * g.ldc + col;
+  if (g.beta != 0.0f) {
+    const Vec4 c0 = load4(g.C, ci, g.c_bf16, vec, n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] += g.beta * c0.v[e];
+  }
+  if (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) {
+    const Vec4 b = load4(g.bias, col, 0, vec, n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] += b.v[e];
+  }
+  if (g.epi == CHN_EPI_BIAS_RELU) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] = fmaxf(x.v[e], 0.0f);
+  } else if (g.epi == CHN_EPI_BIAS_GELU) {
+    if (g.pre) store4(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, vec, n, x);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] = gelu_epi_f(x.v[e]);
+  } else if (g.epi == CHN_EPI_RELU_BWD) {
+    const Vec4 y = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] = y.v[e] > 0.0f ? x.v[e] : 0.0f;
+  } else if (g.epi == CHN_EPI_GELU_BWD) {
+    const Vec4 z = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_epi_f(z.v[e]);
+  }
+  store4(g.C, ci, g.c_bf16, vec, n, x);
+}
+
 // Rows [row0, row0+32) x columns [col0, col0 + 32*TN) of C for one wave: `stage` holds the fp32
-// accumulators row-major with pitch PITCH floats.  Lane l handles 4 consecutive columns.
+// accumulators row-major with pitch PITCH floats.  Lane l handles 4 consecutive columns.  With K
+// splits the raw sums go to this split's slab of the workspace instead.
 template <int TN>
-__device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *stage, int row0, int col0, int lane) {
+__device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab) {
   constexpr int W = 32 * TN, PITCH = W + 8, CPR = W / 4;      // 16-byte chunks per row
   for (int c = lane; c < 32 * CPR; c += 64) {
     const int rl = c / CPR, cl = (c % CPR) * 4;
     const int row = row0 + rl, col = col0 + cl;
     if (row >= g.M || col >= g.N) continue;
-    const int n = min(4, g.N - col);
-    const bool vec = g.epi_vec && n == 4;
     const f32x4 a = *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl);
-    Vec4 x;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] = g.alpha * a[e];
-    const int64_t ci = (int64_t)row * g.ldc + col;
-    if (g.beta != 0.0f) {
-      const Vec4 c0 = load4(g.C, ci, g.c_bf16, vec, n);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] += g.beta * c0.v[e];
-    }
-    if (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) {
-      const Vec4 b = load4(g.bias, col, 0, vec && (col & 3) == 0, n);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] += b.v[e];
-    }
-    if (g.epi == CHN_EPI_BIAS_RELU) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] = fmaxf(x.v[e], 0.0f);
-    } else if (g.epi == CHN_EPI_BIAS_GELU) {
-      if (g.pre) store4(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, vec, n, x);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] = gelu_epi_f(x.v[e]);
-    } else if (g.epi == CHN_EPI_RELU_BWD) {
-      const Vec4 y = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] = y.v[e] > 0.0f ? x.v[e] : 0.0f;
-    } else if (g.epi == CHN_EPI_GELU_BWD) {
-      const Vec4 z = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_epi_f(z.v[e]);
-    }
-    store4(g.C, ci, g.c_bf16, vec, n, x);
+    if (slab) global_store<f32x4>(reinterpret_cast<uintptr_t>(slab + (int64_t)row * g.ldp + col), a);
+    else finish4(g, row, col, a);
   }
+}
+
+// Second kernel of a split product: adds the slabs in split order and runs the epilogue.
+static __global__ __launch_bounds__(256) void gemm_splitk_finish_kernel(GemmArgs g) {
+  const int groups = (int)(g.ldp / 4);
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (int64_t)g.M * groups) return;
+  const int row = (int)(e / groups), col = (int)(e % groups) * 4;
+  if (col >= g.N) return;
+  const int64_t slab = (int64_t)g.M * g.ldp;
+  const float *p = g.partial + (int64_t)row * g.ldp + col;
+  f32x4 a = global_load<f32x4>(reinterpret_cast<uintptr_t>(p));
+  for (int s = 1; s < g.splits; ++s) a += global_load<f32x4>(reinterpret_cast<uintptr_t>(p + s * slab));
+  finish4(g, row, col, a);
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
@@ -347,7 +369,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 
   // ---- which C tile: XCD-aware renumbering, then grouped (8 tile rows at a time) ordering
   const int nb = g.tiles_m * g.tiles_n;
-  int pid = blockIdx.x;
+  int pid = blockIdx.x % nb;
+  const int split = blockIdx.x / nb;
   const int nb8 = nb & ~7;
   if (pid < nb8) pid = (pid & 7) * (nb8 >> 3) + (pid >> 3);
   constexpr int GROUP = 8;
@@ -383,9 +406,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + h) ^ sw) << 4;
 
-  const int nk = (g.K + BK - 1) / BK;
-  la.issue(0);
-  lb.issue(0);
+  // this block's range of tile steps along K (all of them unless the product is split)
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int per_split = (nk_all + g.splits - 1) / g.splits;
+  const int kt0 = split * per_split;
+  const int nk = min(nk_all, kt0 + per_split);
+  la.issue(kt0 * BK);
+  lb.issue(kt0 * BK);
   la.store(lds);
   lb.store(lds + A_BYTES);
   __syncthreads();
@@ -396,9 +423,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int NR = TM + TN;                              // fragment reads per k-step
   constexpr bool kSched = TM == 4 && TN == 4;              // explicit interleaving for the big tile
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const char *cur = lds + (kt & 1) * STAGE;
-    char *nxt = lds + ((kt + 1) & 1) * STAGE;
+  for (int kt = kt0; kt < nk; ++kt) {
+    const char *cur = lds + ((kt - kt0) & 1) * STAGE;
+    char *nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
     // k-step 0, overlapped with the issue of the global loads of the next tile (they are written to
     // LDS in k-step 2; keeping issue and use inside one loop iteration keeps the staging registers
     // from being carried -- and copied, which means waited for -- across the loop's back edge)
@@ -451,6 +478,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   __syncthreads();   // every wave is done with the operand stages
   constexpr int PITCH = 32 * TN + 8;
   float *stage = reinterpret_cast<float *>(lds) + wave * (32 * PITCH);
+  float *slab = g.splits > 1 ? g.partial + (int64_t)split * g.M * g.ldp : nullptr;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -458,7 +486,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + r] = acc[i][j][v];
     __builtin_amdgcn_wave_barrier();
-    epilogue_rows<TN>(g, stage, m0 + (wm * TM + i) * 32, n0 + wn * TN * 32, lane);
+    epilogue_rows<TN>(g, stage, m0 + (wm * TM + i) * 32, n0 + wn * TN * 32, lane, slab);
     __builtin_amdgcn_wave_barrier();
   }
 }
@@ -476,8 +504,14 @@ chn_status launch_piece(const GemmArgs &g, hipStream_t st) {
     }
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n)), dim3(256), LDS, st, g);
-  return check_launch("gemm");
+  hipLaunchKernelGGL(kern, dim3((unsigned)(g.tiles_m * g.tiles_n * g.splits)), dim3(256), LDS, st, g);
+  CHN_TRY(check_launch("gemm"));
+  if (g.splits > 1) {
+    const int64_t n = (int64_t)g.M * (g.ldp / 4);
+    hipLaunchKernelGGL(gemm_splitk_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, g);
+    return check_launch("gemm split-K finish");
+  }
+  return CHN_OK;
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC>
@@ -490,19 +524,9 @@ chn_status launch_tile(const GemmArgs &g, hipStream_t st) {
 
 template <typename T, bool A_KC, bool B_KC>
 chn_status launch_layout(GemmArgs &g, hipStream_t st) {
-  auto tiles = [&](int b) { return (int64_t)((g.M + b - 1) / b) * ((g.N + b - 1) / b); };
-  int64_t t;
-  const bool wide = g.piece >= 8;   // operands that need element-wise loads only get the small tile
-  if (wide && (t = tiles(256)) >= 192) {
-    if (t > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
-    g.tiles_m = (g.M + 255) / 256; g.tiles_n = (g.N + 255) / 256;
-    return launch_tile<T, 4, 4, A_KC, B_KC>(g, st);
-  }
-  if (wide && (t = tiles(128)) >= 128) {
-    g.tiles_m = (g.M + 127) / 128; g.tiles_n = (g.N + 127) / 128;
-    return launch_tile<T, 2, 2, A_KC, B_KC>(g, st);
-  }
-  g.tiles_m = (g.M + 63) / 64; g.tiles_n = (g.N + 63) / 64;
+  if ((int64_t)g.tiles_m * g.tiles_n * g.splits > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
+  if (g.tile == 2) return launch_tile<T, 4, 4, A_KC, B_KC>(g, st);
+  if (g.tile == 1) return launch_tile<T, 2, 2, A_KC, B_KC>(g, st);
   return launch_tile<T, 1, 1, A_KC, B_KC>(g, st);
 }
 

@@ -32,6 +32,19 @@ class _Program:
     def __init__(self):
         self.calls = []
         self._keep = []
+        # one workspace shared by all GEMMs of the program (they run in stream order); sized when
+        # the program is complete, which is why the calls hold mutable ctypes objects
+        self.gemm_ws = C.c_void_p(0)
+        self.gemm_ws_bytes = C.c_size_t(0)
+        self._gemm_need = 0
+
+    def finish(self):
+        if self._gemm_need:
+            t = torch.empty(self._gemm_need, dtype=torch.uint8, device="cuda")
+            self._keep.append(t)
+            self.gemm_ws.value = t.data_ptr()
+            self.gemm_ws_bytes.value = self._gemm_need
+        return self
 
     def d(self, t):
         if t is None:
@@ -61,8 +74,10 @@ class _Program:
 
 
 def _gemm(p, L, A, Bm, Cm, alpha=1.0, beta=0.0, epi="none", bias=None, aux=None, pre=None):
-    p.add(L.chn_gemm, p.d(A), p.d(Bm), p.d(Cm), C.c_float(alpha), C.c_float(beta), B.EPI[epi],
-          p.d(bias), p.d(aux), p.d(pre), None, 0)
+    a, b, c = p.d(A), p.d(Bm), p.d(Cm)
+    p._gemm_need = max(p._gemm_need, L.chn_gemm_workspace_bytes(a, b, c))
+    p.add(L.chn_gemm, a, b, c, C.c_float(alpha), C.c_float(beta), B.EPI[epi],
+          p.d(bias), p.d(aux), p.d(pre), p.gemm_ws, p.gemm_ws_bytes)
 
 
 class MLPTrainer:
@@ -120,7 +135,7 @@ class MLPTrainer:
         lows = (self.Wl + [None] * n) if self.lowp else None
         p.add(L.chn_sgd_update_multi, len(params), p.ptrs(params), p.ptrs(grads), C.c_float(self.lr),
               None if lows is None else p.ptrs(lows))
-        return p
+        return p.finish()
 
     def step(self, x, t, stream=None):
         key = (x.data_ptr(), t.data_ptr())
@@ -198,7 +213,7 @@ class LSTMTrainer:
         names = list(self.P.keys())
         p.add(L.chn_sgd_update_multi, len(names), p.ptrs([P[k] for k in names]),
               p.ptrs([self.g[k] for k in names]), C.c_float(self.lr), None)
-        return p
+        return p.finish()
 
     def step(self, ids, targets, stream=None):
         key = (ids.data_ptr(), targets.data_ptr())

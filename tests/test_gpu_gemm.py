@@ -131,3 +131,30 @@ def test_gemm_misaligned_leading_dimensions():
     B.gemm(empty((0, 5)), empty((5, 7)), empty((0, 7)))
     z = B.gemm(empty((4, 0)), empty((0, 7)), dev(rnd((4, 7))))
     assert np.all(host(z) == 0)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("layout,shape", [("nt", (128, 650, 2600)), ("nn", (128, 2600, 650)), ("tn", (100, 70, 4099)), ("nt", (33, 10, 3000))])
+def test_gemm_split_k(dt, layout, shape):
+    # few output tiles and a long K: the product is cut along K when the caller provides the workspace
+    M, N, K = shape
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
+    need = B.gemm_workspace_bytes(Ad, Bd, empty((M, N)))
+    assert need > 0
+    w = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ref, S = O.gemm(A, Bm), O.gemm(np.abs(A), np.abs(Bm))
+    out = B.gemm(Ad, Bd, empty((M, N)), ws=w)
+    check(host(out), ref, TOL_SUM, S, "split-K")
+    out2 = B.gemm(Ad, Bd, empty((M, N)), ws=w)
+    assert torch.equal(out, out2)                                   # fixed order: bit-reproducible
+    unsplit = B.gemm(Ad, Bd, empty((M, N)))                         # no workspace: same product, unsplit
+    check(host(unsplit), ref, TOL_SUM, S, "unsplit")
+    # epilogue and beta run in the finishing kernel
+    bias, C0 = rnd((N,)), rnd((M, N))
+    Cd = dev(C0)
+    B.gemm(Ad, Bd, Cd, alpha=0.5, beta=1.0, epilogue="bias_relu", bias=dev(bias), ws=w)
+    want = O.elementwise("relu", [O.elementwise("add", [O.gemm(A, Bm, C0, 0.5, 1.0), bias])])
+    check(host(Cd), want, TOL_SUM, 0.5 * S + np.abs(C0) + np.abs(bias), "split-K epilogue")
+    gi = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gi)
+    assert np.array_equal(host(B.gemm(Ad, Bd, empty((M, N)), ws=w)), A.astype(np.float64) @ Bm.astype(np.float64))
