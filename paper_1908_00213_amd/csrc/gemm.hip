@@ -50,27 +50,34 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
   return CHN_OK;
 }
 
-// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits.  A problem with too few
-// 64x64 tiles to occupy the 256 compute units but a long K is cut along K: every split writes fp32
-// partial sums to the workspace and a second kernel adds them in a fixed order and runs the epilogue.
-void plan(GemmArgs *g, int isz) {
-  auto tiles = [&](int b) { return (int64_t)((g->M + b - 1) / b) * ((g->N + b - 1) / b); };
+// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model.
+// Every compute unit is taken to work through its share of the blocks one after another at a
+// measured fraction of its MFMA peak that depends on the tile (large tiles re-use LDS fragments
+// more); a problem with too few tiles to occupy 256 compute units but a long K is cut along K: every
+// split writes fp32 partial sums to the workspace and a second kernel adds them in a fixed order and
+// runs the epilogue (its traffic and launch are charged to the split candidates).
+void plan(GemmArgs *g, int isz, bool allow_split) {
+  static const double eff_f32[3] = {0.45, 0.78, 0.88}, eff_bf16[3] = {0.07, 0.25, 0.40};
+  const double cu_peak = (isz == 2 ? 2500e12 : 157.3e12) / 256.0;
+  const double *eff = isz == 2 ? eff_bf16 : eff_f32;
   const bool wide = g->piece >= 8;   // operands that need element-wise loads only get the small tile
-  g->splits = 1;
-  if (wide && tiles(256) >= 192) g->tile = 2;
-  else if (wide && tiles(128) >= 128) g->tile = 1;
-  else {
-    g->tile = 0;
-    const int64_t t = tiles(64);
-    const int nk = (g->K + 128 / isz - 1) / (128 / isz);   // tile steps along K
-    if (t < 128 && nk >= 8) {
-      int64_t s = (256 + t - 1) / t;
-      if (s > nk / 4) s = nk / 4;
-      if (s > 16) s = 16;
-      if (s >= 2) g->splits = (int)s;
+  const int nk = (g->K + 128 / isz - 1) / (128 / isz);   // tile steps along K
+  static const int split_choices[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
+  double best = 1e300;
+  g->tile = 0; g->splits = 1;
+  for (int tile = wide ? 2 : 0; tile >= 0; --tile) {
+    const int b = 64 << tile;
+    const int64_t tiles = (int64_t)((g->M + b - 1) / b) * ((g->N + b - 1) / b);
+    for (int s : split_choices) {
+      if (s > 1 && (!allow_split || s > nk / 4)) break;
+      const int64_t blocks = tiles * s;
+      const double per_block = 2.0 * b * b * ((double)g->K / s + 128 / isz) / (eff[tile] * cu_peak);
+      double t = (double)((blocks + 255) / 256) * per_block;
+      if (s > 1) t += 6e-6 + (double)(s + 1) * g->M * g->N * 4.0 / 4e12;
+      if (t < best * 0.97) { best = t; g->tile = tile; g->splits = s; }   // prefer larger tiles / fewer splits on near-ties
     }
   }
-  const int b = g->tile == 2 ? 256 : g->tile == 1 ? 128 : 64;
+  const int b = 64 << g->tile;
   g->tiles_m = (g->M + b - 1) / b;
   g->tiles_n = (g->N + b - 1) / b;
   g->ldp = (g->N + 3) & ~3;
@@ -93,7 +100,7 @@ size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const ch
   GemmArgs g{};
   bool a_kc, b_kc;
   if (classify(A, B, &g, &a_kc, &b_kc) != CHN_OK) return 0;
-  plan(&g, dtype_size(A->dtype));
+  plan(&g, dtype_size(A->dtype), true);
   return split_bytes(g);
 }
 
@@ -153,11 +160,11 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.epi_vec = ok(g.C, g.ldc) && ok(g.aux, g.ldaux) && ok(g.pre, g.ldpre) &&
                 (g.bias == nullptr || reinterpret_cast<uintptr_t>(g.bias) % 16 == 0);
   }
-  plan(&g, isz);
+  plan(&g, isz, true);
   if (g.splits > 1) {
-    // split-K is an optimisation: without (enough, aligned) workspace the product runs unsplit
+    // split-K is an optimisation: without (enough, aligned) workspace the product is planned unsplit
     if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);
-    else g.splits = 1;
+    else plan(&g, isz, false);
   }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {
