@@ -156,16 +156,24 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   float phi = 0.39894228040143267794f * expf(-0.5f * x * x);
   return Phi + x * phi;
 }
-// Cheaper forms for GEMM epilogues, where the argument already carries the rounding error of a long
-// fp32 sum: erf instead of erfc (absolute instead of relative accuracy in the negative tail) and the
-// hardware exponential.
-__device__ __forceinline__ float gelu_epi_f(float x) {
-  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+// Compact forms for GEMM epilogues, where the argument already carries the rounding error of a long
+// fp32 sum and the code is replicated for every accumulator a lane holds.  Phi(x) comes from the
+// classical five-term rational approximation of erf (Abramowitz & Stegun 7.1.26, absolute error
+// below 1.5e-7), whose exp(-x^2/2) factor is shared with the density phi(x); for x < 0 the form
+// 0.5 * poly * exp(-x^2/2) involves no cancellation.  One hardware exp and one hardware reciprocal.
+struct PhiParts { float Phi, e; };   // e = exp(-x^2 / 2)
+__device__ __forceinline__ PhiParts phi_parts(float x) {
+  const float y = fabsf(x) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.0f));
+  const float e = __expf(-y * y);
+  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f), 0.254829592f);
+  const float tail = 0.5f * poly * e;             // = Phi(-|x|)
+  return PhiParts{x < 0.0f ? tail : 1.0f - tail, e};
 }
+__device__ __forceinline__ float gelu_epi_f(float x) { return x * phi_parts(x).Phi; }
 __device__ __forceinline__ float gelu_grad_epi_f(float x) {
-  const float Phi = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
-  const float phi = 0.39894228040143267794f * __expf(-0.5f * x * x);
-  return Phi + x * phi;
+  const PhiParts p = phi_parts(x);
+  return fmaf(x * 0.39894228040143267794f, p.e, p.Phi);
 }
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
 

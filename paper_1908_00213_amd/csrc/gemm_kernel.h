@@ -31,6 +31,8 @@
 //     so that bias / activation / activation-gradient run on 16-byte vectors and C, aux and preact
 //     are accessed as whole 512-byte (fp32) or 256-byte (bf16) row segments; one final rounding.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_args.h"
 
@@ -250,99 +252,134 @@ __device__ __forceinline__ void sched_reads_mfma() {
 }
 
 // ---- epilogue helpers ------------------------------------------------------------------------------
+// Two paths.  The fast one handles whole 4-column groups with aligned vector accesses only (the host
+// sets epi_vec when every pointer and leading dimension allows it) and keeps its code small because
+// it is replicated for every row segment a lane owns; everything else (ragged right edge, unaligned
+// views) goes through a rolled element-by-element loop.
 struct Vec4 { float v[4]; };
 
-__device__ __forceinline__ Vec4 load4(const void *p, int64_t idx, int is_bf16, bool vec, int n) {
+__device__ __forceinline__ Vec4 load4v(const void *p, int64_t idx, int is_bf16) {
   Vec4 r;
-  if (vec) {
-    if (is_bf16) {
-      const u32x2 w = global_load<u32x2>(reinterpret_cast<uintptr_t>(static_cast<const bf16_raw *>(p) + idx));
-      r.v[0] = __uint_as_float(w[0] << 16); r.v[1] = __uint_as_float(w[0] & 0xffff0000u);
-      r.v[2] = __uint_as_float(w[1] << 16); r.v[3] = __uint_as_float(w[1] & 0xffff0000u);
-    } else {
-      const f32x4 w = global_load<f32x4>(reinterpret_cast<uintptr_t>(static_cast<const float *>(p) + idx));
-      r.v[0] = w[0]; r.v[1] = w[1]; r.v[2] = w[2]; r.v[3] = w[3];
-    }
+  if (is_bf16) {
+    const u32x2 w = global_load<u32x2>(reinterpret_cast<uintptr_t>(static_cast<const bf16_raw *>(p) + idx));
+    r.v[0] = __uint_as_float(w[0] << 16); r.v[1] = __uint_as_float(w[0] & 0xffff0000u);
+    r.v[2] = __uint_as_float(w[1] << 16); r.v[3] = __uint_as_float(w[1] & 0xffff0000u);
   } else {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      r.v[e] = e < n ? (is_bf16 ? bf16_to_f32(static_cast<const bf16_raw *>(p)[idx + e]) : static_cast<const float *>(p)[idx + e]) : 0.0f;
+    const f32x4 w = global_load<f32x4>(reinterpret_cast<uintptr_t>(static_cast<const float *>(p) + idx));
+    r.v[0] = w[0]; r.v[1] = w[1]; r.v[2] = w[2]; r.v[3] = w[3];
   }
   return r;
 }
 
-__device__ __forceinline__ void store4(void *p, int64_t idx, int is_bf16, bool vec, int n, const Vec4 &x) {
-  if (vec) {
-    if (is_bf16) {
-      u32x2 w;
-      w[0] = (uint32_t)f32_to_bf16(x.v[0]) | ((uint32_t)f32_to_bf16(x.v[1]) << 16);
-      w[1] = (uint32_t)f32_to_bf16(x.v[2]) | ((uint32_t)f32_to_bf16(x.v[3]) << 16);
-      global_store<u32x2>(reinterpret_cast<uintptr_t>(static_cast<bf16_raw *>(p) + idx), w);
-    } else {
-      f32x4 w = {x.v[0], x.v[1], x.v[2], x.v[3]};
-      global_store<f32x4>(reinterpret_cast<uintptr_t>(static_cast<float *>(p) + idx), w);
-    }
+__device__ __forceinline__ void store4v(void *p, int64_t idx, int is_bf16, const Vec4 &x) {
+  if (is_bf16) {
+    u32x2 w;
+    w[0] = (uint32_t)f32_to_bf16(x.v[0]) | ((uint32_t)f32_to_bf16(x.v[1]) << 16);
+    w[1] = (uint32_t)f32_to_bf16(x.v[2]) | ((uint32_t)f32_to_bf16(x.v[3]) << 16);
+    global_store<u32x2>(reinterpret_cast<uintptr_t>(static_cast<bf16_raw *>(p) + idx), w);
   } else {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (e < n) {
-        if (is_bf16) static_cast<bf16_raw *>(p)[idx + e] = f32_to_bf16(x.v[e]);
-        else static_cast<float *>(p)[idx + e] = x.v[e];
-      }
+    f32x4 w = {x.v[0], x.v[1], x.v[2], x.v[3]};
+    global_store<f32x4>(reinterpret_cast<uintptr_t>(static_cast<float *>(p) + idx), w);
   }
 }
 
-// alpha/beta, bias, activation or activation gradient and the single final rounding for the four
-// consecutive columns col.. of row `row`, whose fp32 sums are in `a`.
-__device__ __forceinline__ void finish4(const GemmArgs &g, int row, int col, const f32x4 a) {
-  const int n = min(4, g.N - col);
-  const bool vec = g.epi_vec && n == 4;
-  Vec4 x;
+__device__ __forceinline__ float load1(const void *p, int64_t idx, int is_bf16) {
+  return is_bf16 ? bf16_to_f32(static_cast<const bf16_raw *>(p)[idx]) : static_cast<const float *>(p)[idx];
+}
+__device__ __forceinline__ void store1(void *p, int64_t idx, int is_bf16, float v) {
+  if (is_bf16) static_cast<bf16_raw *>(p)[idx] = f32_to_bf16(v);
+  else static_cast<float *>(p)[idx] = v;
+}
+
+// alpha/beta, bias, activation or activation gradient for one value; c0 = old C, aux = retained
+// activation (both only read when the epilogue uses them).  Returns the pre-activation through *pre.
+__device__ __forceinline__ float epi_math(const GemmArgs &g, float acc, float c0, float bias, float aux, float *pre) {
+  float x = g.alpha * acc;
+  if (g.beta != 0.0f) x += g.beta * c0;
+  x += bias;
+  *pre = x;
+  if (g.epi == CHN_EPI_BIAS_RELU) x = fmaxf(x, 0.0f);
+  else if (g.epi == CHN_EPI_BIAS_GELU) x = gelu_epi_f(x);
+  else if (g.epi == CHN_EPI_RELU_BWD) x = aux > 0.0f ? x : 0.0f;
+  else if (g.epi == CHN_EPI_GELU_BWD) x *= gelu_grad_epi_f(aux);
+  return x;
+}
+
+// The fast path's dependent global reads (C when beta != 0, aux for the activation gradients) for
+// the four columns col.. of row `row`.  They are issued for several row segments at once before any
+// of them is used: a wave that is alone on its SIMD would otherwise sit out one memory latency per
+// segment.
+struct EpiIn { Vec4 c0, aux; };
+
+__device__ __forceinline__ EpiIn epi_fetch(const GemmArgs &g, int row, int col) {
+  EpiIn in;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) x.v[e] = g.alpha * a[e];
+  for (int e = 0; e < 4; ++e) in.c0.v[e] = in.aux.v[e] = 0.0f;
+  if (g.beta != 0.0f) in.c0 = load4v(g.C, (int64_t)row * g.ldc + col, g.c_bf16);
+  if (g.epi == CHN_EPI_RELU_BWD || g.epi == CHN_EPI_GELU_BWD) in.aux = load4v(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16);
+  return in;
+}
+
+__device__ __forceinline__ void finish4(const GemmArgs &g, int row, int col, const f32x4 a, const EpiIn &in) {
+  Vec4 b, x, pre;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) b.v[e] = 0.0f;
+  if (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) b = load4v(g.bias, col, 0);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) x.v[e] = epi_math(g, a[e], in.c0.v[e], b.v[e], in.aux.v[e], &pre.v[e]);
+  if (g.epi == CHN_EPI_BIAS_GELU && g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+  store4v(g.C, (int64_t)row * g.ldc + col, g.c_bf16, x);
+}
+
+// One element, any alignment (slow path).
+__device__ __forceinline__ void finish1(const GemmArgs &g, int row, int col, float acc) {
   const int64_t ci = (int64_t)row * g.ldc + col;
-  if (g.beta != 0.0f) {
-    const Vec4 c0 = load4(g.C, ci, g.c_bf16, vec, n);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] += g.beta * c0.v[e];
-  }
-  if (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) {
-    const Vec4 b = load4(g.bias, col, 0, vec, n);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] += b.v[e];
-  }
-  if (g.epi == CHN_EPI_BIAS_RELU) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] = fmaxf(x.v[e], 0.0f);
-  } else if (g.epi == CHN_EPI_BIAS_GELU) {
-    if (g.pre) store4(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, vec, n, x);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] = gelu_epi_f(x.v[e]);
-  } else if (g.epi == CHN_EPI_RELU_BWD) {
-    const Vec4 y = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] = y.v[e] > 0.0f ? x.v[e] : 0.0f;
-  } else if (g.epi == CHN_EPI_GELU_BWD) {
-    const Vec4 z = load4(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16, vec, n);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) x.v[e] *= gelu_grad_epi_f(z.v[e]);
-  }
-  store4(g.C, ci, g.c_bf16, vec, n, x);
+  const float c0 = g.beta != 0.0f ? load1(g.C, ci, g.c_bf16) : 0.0f;
+  const float bias = (g.epi >= CHN_EPI_BIAS && g.epi <= CHN_EPI_BIAS_GELU) ? g.bias[col] : 0.0f;
+  const float aux = (g.epi == CHN_EPI_RELU_BWD || g.epi == CHN_EPI_GELU_BWD) ? load1(g.aux, (int64_t)row * g.ldaux + col, g.c_bf16) : 0.0f;
+  float pre;
+  const float x = epi_math(g, acc, c0, bias, aux, &pre);
+  if (g.epi == CHN_EPI_BIAS_GELU && g.pre) store1(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+  store1(g.C, ci, g.c_bf16, x);
 }
 
 // Rows [row0, row0+32) x columns [col0, col0 + 32*TN) of C for one wave: `stage` holds the fp32
-// accumulators row-major with pitch PITCH floats.  Lane l handles 4 consecutive columns.  With K
-// splits the raw sums go to this split's slab of the workspace instead.
+// accumulators row-major with pitch PITCH floats.  With K splits the raw sums go to this split's
+// slab of the workspace instead.
 template <int TN>
 __device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab) {
   constexpr int W = 32 * TN, PITCH = W + 8, CPR = W / 4;      // 16-byte chunks per row
-  for (int c = lane; c < 32 * CPR; c += 64) {
-    const int rl = c / CPR, cl = (c % CPR) * 4;
-    const int row = row0 + rl, col = col0 + cl;
-    if (row >= g.M || col >= g.N) continue;
-    const f32x4 a = *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl);
-    if (slab) global_store<f32x4>(reinterpret_cast<uintptr_t>(slab + (int64_t)row * g.ldp + col), a);
-    else finish4(g, row, col, a);
+  constexpr int NIT = 32 * CPR / 64;                          // row segments per lane
+  constexpr int U = NIT < 4 ? NIT : 4;                        // segments whose reads are in flight together
+  if (slab) {                                                 // split-K: raw sums, always aligned (ldp % 4 == 0)
+    for (int c = lane; c < 32 * CPR; c += 64) {
+      const int rl = c / CPR, cl = (c % CPR) * 4;
+      if (row0 + rl < g.M && col0 + cl < g.N)
+        global_store<f32x4>(reinterpret_cast<uintptr_t>(slab + (int64_t)(row0 + rl) * g.ldp + col0 + cl),
+                            *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl));
+    }
+  } else if (g.epi_vec && col0 + W <= g.N) {                  // fast path: lane l handles 4 consecutive columns
+#pragma unroll 1
+    for (int base = 0; base < NIT; base += U) {
+      EpiIn in[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = lane + (base + u) * 64;
+        if (row0 + c / CPR < g.M) in[u] = epi_fetch(g, row0 + c / CPR, col0 + (c % CPR) * 4);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = lane + (base + u) * 64;
+        const int rl = c / CPR, cl = (c % CPR) * 4;
+        if (row0 + rl < g.M) finish4(g, row0 + rl, col0 + cl, *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl), in[u]);
+      }
+    }
+  } else {                                                    // slow path: one element at a time
+#pragma unroll 1
+    for (int c = lane; c < 32 * W; c += 64) {
+      const int rl = c / W, cl = c % W;
+      if (row0 + rl < g.M && col0 + cl < g.N) finish1(g, row0 + rl, col0 + cl, stage[rl * PITCH + cl]);
+    }
   }
 }
 
@@ -357,7 +394,11 @@ static __global__ __launch_bounds__(256) void gemm_splitk_finish_kernel(GemmArgs
   const float *p = g.partial + (int64_t)row * g.ldp + col;
   f32x4 a = global_load<f32x4>(reinterpret_cast<uintptr_t>(p));
   for (int s = 1; s < g.splits; ++s) a += global_load<f32x4>(reinterpret_cast<uintptr_t>(p + s * slab));
-  finish4(g, row, col, a);
+  if (g.epi_vec && col + 4 <= g.N) {
+    finish4(g, row, col, a, epi_fetch(g, row, col));
+  } else {
+    for (int e = 0; e < 4 && col + e < g.N; ++e) finish1(g, row, col + e, a[e]);
+  }
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
@@ -479,8 +520,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int PITCH = 32 * TN + 8;
   float *stage = reinterpret_cast<float *>(lds) + wave * (32 * PITCH);
   float *slab = g.splits > 1 ? g.partial + (int64_t)split * g.M * g.ldp : nullptr;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
+  // (written out per 32-row block: the compiler refuses to unroll a loop this large, and a rolled
+  // loop would index the accumulator registers dynamically, i.e. move them to scratch memory)
+  auto block = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -488,6 +531,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     __builtin_amdgcn_wave_barrier();
     epilogue_rows<TN>(g, stage, m0 + (wm * TM + i) * 32, n0 + wn * TN * 32, lane, slab);
     __builtin_amdgcn_wave_barrier();
+  };
+  block(std::integral_constant<int, 0>{});
+  if constexpr (TM > 1) block(std::integral_constant<int, 1>{});
+  if constexpr (TM > 2) {
+    block(std::integral_constant<int, 2>{});
+    block(std::integral_constant<int, 3>{});
   }
 }
 
