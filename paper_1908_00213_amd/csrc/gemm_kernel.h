@@ -123,10 +123,22 @@ struct TileLoader {
   int lim[NSLOT];         // KC: K - (k offset of the slot) for valid rows, else 0;  MC: rows_total - m or 0
   int64_t kstride;        // bytes between consecutive k (MC only)
   int K;
+  uintptr_t pf_ptr;       // cache-line prefetch: this thread's line of the tile at k0 = 0
+  int pf_lim;             // KC: K if the thread's row exists, else 0;  MC: K - (its k row) or 0
 
   __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K_) {
     K = K_;
     kstride = ld * (int64_t)sizeof(T);
+    if constexpr (KC) {   // one 128-byte line per tile row: thread t takes row t
+      const int row = row0 + (int)threadIdx.x;
+      pf_ptr = reinterpret_cast<uintptr_t>(base + (int64_t)row * ld);
+      pf_lim = (threadIdx.x < ROWS && row < rows_total) ? K_ : 0;
+    } else {              // ROWS * sizeof(T) / 128 lines per k row
+      constexpr int LPR = ROWS * (int)sizeof(T) / 128, EPL = 128 / (int)sizeof(T);
+      const int kr = threadIdx.x / LPR, m = row0 + (threadIdx.x % LPR) * EPL;
+      pf_ptr = reinterpret_cast<uintptr_t>(base + (int64_t)kr * ld + m);
+      pf_lim = (kr < 128 / (int)sizeof(T) && m < rows_total) ? K_ - kr : 0;
+    }
     if constexpr (KC) {
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
@@ -164,6 +176,14 @@ struct TileLoader {
         }
       }
     }
+  }
+
+  // Touch this thread's cache line of the tile whose first k is k0, so that the line is on its way
+  // into L2 long before the tile's real loads are issued.  The value is meaningless.
+  __device__ __forceinline__ uint32_t prefetch(int k0) const {
+    const uintptr_t zero = reinterpret_cast<uintptr_t>(&kZeroChunk);
+    const uintptr_t a = KC ? pf_ptr + (int64_t)k0 * (int64_t)sizeof(T) : pf_ptr + (int64_t)k0 * kstride;
+    return global_load<uint32_t>(k0 < pf_lim ? a : zero);
   }
 
   __device__ __forceinline__ void store(char *lds) const {
@@ -460,6 +480,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   Frags<TM, TN> f0, f1;
   f0.read(lds + a_row, lds + b_row, koff[0]);
 
+  uint32_t pf_a = 0, pf_b = 0;
+  constexpr int kPrefetchAhead = 3;
   constexpr int NM = (sizeof(T) == 2 ? 1 : 4) * TM * TN;   // MFMAs per k-step
   constexpr int NR = TM + TN;                              // fragment reads per k-step
   constexpr bool kSched = TM == 4 && TN == 4;              // explicit interleaving for the big tile
@@ -482,8 +504,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
       }
     }
-    // k-step 1
+    // k-step 1 (the big tile also touches the cache lines of the tile three steps ahead: with one wave
+    // per SIMD the two k-steps between issue and use of a tile's loads cover an L2 hit, not HBM)
     f0.read(cur + a_row, cur + b_row, koff[2]);
+    if constexpr (kSched) {
+      asm volatile("" ::"v"(pf_a), "v"(pf_b));   // the previous touches must not be optimised away
+      pf_a = la.prefetch((kt + kPrefetchAhead) * BK);
+      pf_b = lb.prefetch((kt + kPrefetchAhead) * BK);
+    }
     mma<T, TM, TN>(acc, f1);
     if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
     // k-step 2: also move the next tile from registers to the other stage.  The compiler must keep
