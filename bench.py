@@ -137,7 +137,7 @@ def gemm_shapes_mlp(sizes, batch):
     return out
 
 
-def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False):
+def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, graph=False):
     tr = steps_mod.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp)
     xs = [torch.from_numpy(x).cuda() for x in w.xs]
     if lowp:
@@ -171,7 +171,7 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False):
         k = [0]
 
         def fn():
-            tr.step(xs[k[0] % nb], ts[k[0] % nb])
+            tr.step(xs[k[0] % nb], ts[k[0] % nb], graph=graph)
             k[0] += 1
         s = timer.time(fn, steps, warmup)
     res.update({"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(tr.loss.cpu()),
@@ -179,10 +179,10 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False):
     return res
 
 
-def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup):
+def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False):
     tr = steps_mod.LSTMTrainer(w.params, w.bptt, w.batch, w.lr)
     ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
-    s = timer.time(lambda: tr.step(ids, tg), steps, warmup)
+    s = timer.time(lambda: tr.step(ids, tg, graph=graph), steps, warmup)
     return {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s, "loss": float(tr.loss.cpu()),
             "TFLOP/s": w.flops_per_step() / s / 1e12, "frac_mfma_peak_f32": w.flops_per_step() / s / 1e12 / MFMA_PEAK_TFLOPS["f32"],
             "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
@@ -257,21 +257,27 @@ def main():
         log("workload 3: MLP 784-1000-1000-10, batch 1024")
         w3 = W.config3()
         for lowp in (False, True):
-            r = bench_mlp(torch, B, steps_mod, w3, lowp, timer, 100, 10)
-            extra["cfg3_mlp_%s" % ("bf16" if lowp else "f32")] = r
-            log("  %s: %.1f us/step  %.0f steps/s  %.2f TFLOP/s  (%d launches/step)" % (
-                "bf16" if lowp else "f32", r["ms_per_step"] * 1e3, r["steps_per_s"], r["TFLOP/s"], r["launch_calls_per_step"]))
+            for graph in (False, True):
+                r = bench_mlp(torch, B, steps_mod, w3, lowp, timer, 100, 10, graph=graph)
+                tag = ("bf16" if lowp else "f32") + ("_hipgraph" if graph else "")
+                extra["cfg3_mlp_%s" % tag] = r
+                log("  %s: %.1f us/step  %.0f steps/s  %.2f TFLOP/s  (%d launches/step)" % (
+                    tag, r["ms_per_step"] * 1e3, r["steps_per_s"], r["TFLOP/s"], r["launch_calls_per_step"]))
     if "1" in sel:
         log("workload 1: tiny MLP 784-100-100-10, batch 32")
-        r = bench_mlp(torch, B, steps_mod, W.config1(), False, timer, 200, 20)
-        extra["cfg1_tiny_mlp_f32"] = r
-        log("  %.1f us/step  %.0f steps/s" % (r["ms_per_step"] * 1e3, r["steps_per_s"]))
+        for graph in (False, True):
+            r = bench_mlp(torch, B, steps_mod, W.config1(), False, timer, 200, 20, graph=graph)
+            extra["cfg1_tiny_mlp_f32" + ("_hipgraph" if graph else "")] = r
+            log("  %s%.1f us/step  %.0f steps/s" % ("HIP graph: " if graph else "", r["ms_per_step"] * 1e3, r["steps_per_s"]))
     if "4" in sel:
         log("workload 4: LSTM language model step (vocab 10000, 650 hidden, batch 128, BPTT 35), fp32")
-        r = bench_lstm(torch, B, steps_mod, W.config4(), timer, 20, 3)
-        extra["cfg4_lstm_lm_f32"] = r
-        log("  %.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s (%.1f%% of fp32 MFMA peak; %d launches/step)" % (
-            r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"], 100 * r["frac_mfma_peak_f32"], r["launch_calls_per_step"]))
+        w4 = W.config4()
+        for graph in (False, True):
+            r = bench_lstm(torch, B, steps_mod, w4, timer, 20, 3, graph=graph)
+            extra["cfg4_lstm_lm_f32" + ("_hipgraph" if graph else "")] = r
+            log("  %s%.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s (%.1f%% of fp32 MFMA peak; %d launches/step)" % (
+                "HIP graph: " if graph else "", r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"],
+                100 * r["frac_mfma_peak_f32"], r["launch_calls_per_step"]))
 
     cpu = None
     if not args.no_cpu:

@@ -72,6 +72,19 @@ class _Program:
             if st != 0:
                 B._check(st)
 
+    def replay(self):
+        """Run the program as one HIP graph launch (captured on first use, after an eager run has
+        configured every kernel).  The library enqueues kernels only -- no memsets, no allocations --
+        so the captured graph is exactly the eager launch sequence."""
+        if getattr(self, "_graph", None) is None:
+            self.run()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.run()
+            self._graph = g
+        self._graph.replay()
+
 
 def _gemm(p, L, A, Bm, Cm, alpha=1.0, beta=0.0, epi="none", bias=None, aux=None, pre=None):
     a, b, c = p.d(A), p.d(Bm), p.d(Cm)
@@ -137,11 +150,14 @@ class MLPTrainer:
               None if lows is None else p.ptrs(lows))
         return p.finish()
 
-    def step(self, x, t, stream=None):
+    def step(self, x, t, stream=None, graph=False):
         key = (x.data_ptr(), t.data_ptr())
         if key not in self._progs:
             self._progs[key] = self._build(x, t)
-        self._progs[key].run(stream)
+        if graph:
+            self._progs[key].replay()
+        else:
+            self._progs[key].run(stream)
         return self.loss
 
     def n_launch_calls(self, x, t):
@@ -215,11 +231,14 @@ class LSTMTrainer:
               p.ptrs([self.g[k] for k in names]), C.c_float(self.lr), None)
         return p.finish()
 
-    def step(self, ids, targets, stream=None):
+    def step(self, ids, targets, stream=None, graph=False):
         key = (ids.data_ptr(), targets.data_ptr())
         if key not in self._progs:
             self._progs[key] = self._build(ids, targets)
-        self._progs[key].run(stream)
+        if graph:
+            self._progs[key].replay()
+        else:
+            self._progs[key].run(stream)
         return self.loss
 
     def n_launch_calls(self, ids, targets):

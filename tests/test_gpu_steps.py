@@ -114,3 +114,36 @@ def test_config4_scaled_lstm_lm_step(cfg):
     r2 = OS.lstm_lm_step(w.params, w.ids[:2], w.targets[:2], np.float32(w.lr))
     assert abs(float(l2.cpu()) - r2["loss"]) <= 1e-4 * abs(r2["loss"])
     cmp(tr2.g["U"], r2["grads"]["U"], 1e-4, "dU T=2")
+
+
+def test_graph_replay_equals_eager():
+    # a captured step must reproduce the eager step bit for bit, on every replay, with eager work and
+    # synchronisations in between
+    w = W.config1()
+    xd, td = torch.from_numpy(w.xs[0]).cuda(), torch.from_numpy(w.ts[0]).cuda()
+    a = steps.MLPTrainer(w.params, w.batch, w.act, 0.1, False)
+    b = steps.MLPTrainer(w.params, w.batch, w.act, 0.1, False)
+    # the first graph step executes the program twice (eager warm-up, then the replay; the capture
+    # pass itself executes nothing); mirror that on the eager side
+    b.step(xd, td, graph=True)
+    for _ in range(2):
+        a.step(xd, td)
+    for k in range(4):
+        la = float(a.step(xd, td).cpu())
+        lb = float(b.step(xd, td, graph=True).cpu())
+        torch.cuda.synchronize()
+        assert la == lb, (k, la, lb)
+        for p, q in zip(a.W + a.b + a.dW + a.db, b.W + b.b + b.dW + b.db):
+            assert torch.equal(p, q)
+    wl = W.config4(vocab=200, embed=40, hidden=40, batch=8, bptt=3)
+    ids, tg = torch.from_numpy(wl.ids).cuda(), torch.from_numpy(wl.targets).cuda()
+    a = steps.LSTMTrainer(wl.params, wl.bptt, wl.batch, 0.1)
+    b = steps.LSTMTrainer(wl.params, wl.bptt, wl.batch, 0.1)
+    b.step(ids, tg, graph=True)
+    for _ in range(2):
+        a.step(ids, tg)
+    for k in range(3):
+        la, lb = float(a.step(ids, tg).cpu()), float(b.step(ids, tg, graph=True).cpu())
+        assert la == lb, (k, la, lb)
+        for name in a.P:
+            assert torch.equal(a.P[name], b.P[name]) and torch.equal(a.g[name], b.g[name])
