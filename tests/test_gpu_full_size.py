@@ -1,0 +1,185 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot afford whole products at these sizes, so each call is checked teacher-forced (the
+oracle gets the GPU call's own inputs) on outputs it can compute one by one: sampled GEMM entries as
+fp64 dot products, sampled rows / columns of the array primitives, and full tensors for the cheap
+calls (softmax cross-entropy, bias gradients, LSTM cell, embedding, SGD)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_1908_00213_amd import binding as B, steps, workloads as W
+from tests.util import TOL_BF16, TOL_EW, TOL_SUM, check, host
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(8192)
+
+
+def sample_gemm(A, Bm, n=256):
+    """fp64 reference and term-magnitude sum for n random entries of A @ B (NumPy views)."""
+    ms, ns = RNG.integers(0, A.shape[0], n), RNG.integers(0, Bm.shape[1], n)
+    return ms, ns, O.gemm_entries(A, Bm, ms, ns), O.gemm_entries(np.abs(A), np.abs(Bm), ms, ns)
+
+
+def h32(t):
+    return host(t).astype(np.float32) if t.dtype != torch.float32 else t.cpu().numpy()
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_config2_full_size_array_primitives(dt):
+    n = 8192
+    w = W.config2(n)
+    tdt = torch.float32 if dt == "f32" else torch.bfloat16
+    a, b, c = (torch.from_numpy(x).cuda().to(tdt) for x in (w.a, w.b, w.c))
+    ah, bh, ch = h32(a), h32(b), h32(c)                       # the values the kernels actually read
+    tol = TOL_EW if dt == "f32" else TOL_BF16
+    rows = np.sort(RNG.choice(n, 48, replace=False))
+    y = B.elementwise_broadcast("mad_relu", [a, b, c], torch.empty(n, n, dtype=tdt, device="cuda"))
+    yh = h32(y)
+    ref = O.elementwise("mad_relu", [ah[rows], bh[rows], ch])
+    check(yh[rows].astype(np.float64), ref, tol, O.elementwise("mad", [np.abs(ah[rows]), np.abs(bh[rows]), np.abs(ch)]), "mad_relu rows")
+    at = a.t().contiguous().t()                                # same values, transposed storage
+    assert at.stride() == (1, n)
+    yt = B.elementwise_broadcast("mad_relu", [at, b, c], torch.empty(n, n, dtype=tdt, device="cuda"))
+    assert torch.equal(y.view(torch.int16 if dt == "bf16" else torch.int32), yt.view(torch.int16 if dt == "bf16" else torch.int32))
+    ws = torch.empty(B.reduce_axis_workspace_bytes(y, 0), dtype=torch.uint8, device="cuda")
+    s0 = host(B.reduce_axis("sum", y, 0, torch.empty(n, device="cuda"), ws=ws))
+    s1 = host(B.reduce_axis("sum", y, 1, torch.empty(n, device="cuda")))
+    cols = np.sort(RNG.choice(n, 48, replace=False))
+    tol_s = TOL_SUM if dt == "f32" else TOL_BF16
+    check(s0[cols], O.reduce_axis("sum", yh[:, cols], 0), tol_s, O.reduce_axis("sum", np.abs(yh[:, cols]), 0), "sum axis 0")
+    check(s1[rows], O.reduce_axis("sum", yh[rows], 1), tol_s, O.reduce_axis("sum", np.abs(yh[rows]), 1), "sum axis 1")
+    # transposed views: the two kernels swap roles, the sums are the same sums
+    ytv = y.t()
+    wt = torch.empty(max(256, B.reduce_axis_workspace_bytes(ytv, 1)), dtype=torch.uint8, device="cuda")
+    t0 = host(B.reduce_axis("sum", ytv, 0, torch.empty(n, device="cuda"), ws=wt))
+    t1 = host(B.reduce_axis("sum", ytv, 1, torch.empty(n, device="cuda"), ws=wt))
+    check(t0[rows], O.reduce_axis("sum", yh[rows], 1), tol_s, O.reduce_axis("sum", np.abs(yh[rows]), 1), "sum T axis 0")
+    check(t1[cols], O.reduce_axis("sum", yh[:, cols], 0), tol_s, O.reduce_axis("sum", np.abs(yh[:, cols]), 0), "sum T axis 1")
+    assert abs(s0.sum() - s1.sum()) <= 1e-5 * np.abs(yh).sum(dtype=np.float64)
+
+
+def test_config5_full_size_step_sampled():
+    w = W.config5(n_batches=1)
+    x = W.bf16_exact(w.xs[0])
+    t = w.ts[0]
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp=True)
+    W0 = [h32(m) for m in tr.W]                               # masters before the step
+    Wl0 = [h32(m) for m in tr.Wl]                             # bf16 working copies the GEMMs read
+    xd, td = torch.from_numpy(x).cuda().to(torch.bfloat16), torch.from_numpy(t).cuda()
+    loss = float(tr.step(xd, td).cpu())
+    torch.cuda.synchronize()
+    n = len(tr.W)
+    hs = [x] + [h32(hh) for hh in tr.h[1:]]
+    zs = [None] + [h32(z) for z in tr.z[1:]]
+    dvs = [None] + [h32(d) for d in tr.dv[1:]]
+    bias = [b.cpu().numpy() for b in tr.b]                    # biases after the update; recover the old ones
+    db = [d.cpu().numpy() for d in tr.db]
+    b_old = [p[1] for p in w.params]
+    # forward layers
+    for l in range(n):
+        ms, ns, ref, S = sample_gemm(hs[l], Wl0[l].T)
+        v = ref + b_old[l][ns]
+        if l < n - 1:
+            check(zs[l + 1][ms, ns].astype(np.float64), v, TOL_BF16, S, "z%d" % l)
+            check(hs[l + 1][ms, ns].astype(np.float64), O.elementwise("gelu", [v]), TOL_BF16, S, "h%d" % l)
+        else:
+            logits = tr.logits.cpu().numpy()
+            check(logits[ms, ns].astype(np.float64), v, TOL_SUM, S, "logits")      # fp32 out of exact bf16 inputs
+    rl, _, _, nv = O.softmax_ce_fwd(logits, t)
+    assert abs(loss - rl) <= TOL_SUM * abs(rl) and nv == w.batch
+    check(dvs[n].astype(np.float64), O.softmax_ce_bwd(logits, t), TOL_BF16, 1.0 / w.batch, "dlogits")
+    # backward layers, teacher-forced on the GPU's own bf16 gradients
+    for l in range(n - 1, -1, -1):
+        dv = dvs[l + 1]
+        ms, ns, ref, S = sample_gemm(dv.T, hs[l])
+        check(tr.dW[l].cpu().numpy()[ms, ns].astype(np.float64), ref, TOL_SUM, S, "dW%d" % l)
+        check(db[l].astype(np.float64), O.reduce_axis("sum", dv, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dv), 0), "db%d" % l)
+        if l > 0:
+            ms, ns, ref, S = sample_gemm(dv, Wl0[l])
+            g = O.elementwise("gelu_bwd", [ref, zs[l][ms, ns]])
+            check(dvs[l][ms, ns].astype(np.float64), g, TOL_BF16, S * 1.2, "dx%d" % l)
+    # optimiser: new master = old - lr * (the GPU's gradient), working copy = RNE of the new master
+    lr = np.float32(w.lr)
+    for l in (0, n - 1):
+        gW = tr.dW[l].cpu().numpy()
+        newW = tr.W[l].cpu().numpy()
+        check(newW.astype(np.float64), O.sgd_update(W0[l], gW, lr), 1e-6, np.abs(W0[l]) + lr * np.abs(gW), "W%d" % l)
+        assert np.array_equal(h32(tr.Wl[l]).astype(np.float64), O.round_bf16(newW))
+        check(bias[l].astype(np.float64), O.sgd_update(b_old[l], db[l], lr), 1e-6, np.abs(b_old[l]) + lr * np.abs(db[l]), "b%d" % l)
+
+
+def test_config4_full_size_step_sampled():
+    w = W.config4()
+    T, Bn, H, V = w.bptt, w.batch, w.hidden, w.vocab
+    tr = steps.LSTMTrainer(w.params, T, Bn, w.lr)
+    ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
+    prog = tr._build(ids, tg)
+    L = B.lib()
+    P0 = {k: v.copy() for k, v in w.params.items()}
+    # run the recorded calls one by one; keep the logits before the gradient overwrites them in place
+    logits = None
+    for fn, args in prog.calls:
+        if fn is L.chn_softmax_ce_bwd and logits is None:
+            logits = tr.logits.cpu().numpy()
+        B._check(fn(*args, None))
+    torch.cuda.synchronize()
+    idf, tgf = w.ids.reshape(-1), w.targets.reshape(-1)
+    X = tr.X.cpu().numpy()
+    assert np.array_equal(X, P0["E"][idf])                                           # gather is a bit copy
+    Hs, Cs, Z, G = (m.cpu().numpy() for m in (tr.Hs, tr.Cs, tr.Z, tr.G))
+    Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
+    # gate pre-activations x W + h U, sampled
+    ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
+    ref = O.gemm_entries(X, P0["W"], ms, ns) + O.gemm_entries(Hprev, P0["U"], ms, ns)
+    S = O.gemm_entries(np.abs(X), np.abs(P0["W"]), ms, ns) + O.gemm_entries(np.abs(Hprev), np.abs(P0["U"]), ms, ns)
+    check(Z[ms, ns].astype(np.float64), ref, TOL_SUM, S, "gates pre-activation")
+    # cell, every step, from the GPU's own pre-activations
+    for t in (0, 1, T // 2, T - 1):
+        sl = slice(t * Bn, (t + 1) * Bn)
+        c, h, g = O.lstm_fwd(Z[sl], P0["b"], Cs[sl])
+        check(G[sl].astype(np.float64), g, TOL_EW, None, "gates %d" % t)
+        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H])
+        check(Cs[t * Bn + Bn:(t + 2) * Bn].astype(np.float64), c, TOL_EW, Sc, "c %d" % t)
+        check(Hall[sl].astype(np.float64), h, TOL_EW, Sc, "h %d" % t)
+    ms, ns, ref, S = sample_gemm(Hall, P0["W_out"].T)
+    check(logits[ms, ns].astype(np.float64), ref + P0["b_out"][ns], TOL_SUM, S, "logits")
+    rl, _, _, nv = O.softmax_ce_fwd(logits, tgf)
+    assert abs(float(tr.loss.cpu()) - rl) <= TOL_SUM * rl and nv == T * Bn
+    dlog = tr.logits.cpu().numpy()
+    check(dlog.astype(np.float64), O.softmax_ce_bwd(logits, tgf), TOL_EW * 10, 1.0 / nv, "dlogits")
+    g = {k: v.cpu().numpy() for k, v in tr.g.items()}
+    ms, ns, ref, S = sample_gemm(dlog.T, Hall)
+    check(g["W_out"][ms, ns].astype(np.float64), ref, TOL_SUM, S, "dW_out")
+    check(g["b_out"].astype(np.float64), O.reduce_axis("sum", dlog, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dlog), 0), "db_out")
+    # dHs holds the total dh_t (output layer + recurrence); the chain is replayed teacher-forced
+    dHs, dZ = tr.dHs.cpu().numpy(), tr.dZ.cpu().numpy()
+    t = T - 1
+    ms, ns, ref, S = sample_gemm(dlog[t * Bn:], P0["W_out"])
+    check(dHs[t * Bn:][ms % Bn, ns].astype(np.float64), O.gemm_entries(dlog[t * Bn:], P0["W_out"], ms % Bn, ns), TOL_SUM,
+          O.gemm_entries(np.abs(dlog[t * Bn:]), np.abs(P0["W_out"]), ms % Bn, ns), "dh last step")
+    dc = None
+    for t in range(T - 1, -1, -1):
+        sl = slice(t * Bn, (t + 1) * Bn)
+        dz, dc = O.lstm_bwd(G[sl], Cs[sl], Cs[t * Bn + Bn:(t + 2) * Bn], dHs[sl], dc)
+        if t in (T - 1, T - 2, 0):
+            Sdc = np.abs(dc) + np.abs(dHs[sl])
+            check(dZ[sl].astype(np.float64), dz, TOL_EW * 10, np.concatenate([Sdc, Sdc * np.abs(Cs[sl]) + Sdc, Sdc, np.abs(dHs[sl])], axis=1), "dz %d" % t)
+        if t > 0:      # dh_{t-1} = (output-layer part) + dz_t U^T: check the recurrent part on samples
+            ms, ns = RNG.integers(0, Bn, 16), RNG.integers(0, H, 16)
+            rec = O.gemm_entries(dZ[sl], P0["U"].T, ms, ns)
+            out = O.gemm_entries(dlog[(t - 1) * Bn:t * Bn], P0["W_out"], ms, ns)
+            S = O.gemm_entries(np.abs(dZ[sl]), np.abs(P0["U"].T), ms, ns) + O.gemm_entries(np.abs(dlog[(t - 1) * Bn:t * Bn]), np.abs(P0["W_out"]), ms, ns)
+            check(dHs[(t - 1) * Bn:t * Bn][ms, ns].astype(np.float64), rec + out, TOL_SUM, S, "dh %d" % (t - 1))
+    for name, A, Bm in (("U", Hprev.T, dZ), ("W", X.T, dZ)):
+        ms, ns, ref, S = sample_gemm(A, Bm)
+        check(g[name][ms, ns].astype(np.float64), ref, TOL_SUM, S, "d" + name)
+    check(g["b"].astype(np.float64), O.reduce_axis("sum", dZ, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dZ), 0), "db")
+    dX = tr.dX.cpu().numpy()
+    ms, ns, ref, S = sample_gemm(dZ, P0["W"].T)
+    check(dX[ms, ns].astype(np.float64), ref, TOL_SUM, S, "dX")
+    check(g["E"].astype(np.float64), O.embed_bwd(idf, dX, V), TOL_SUM, O.embed_bwd(idf, np.abs(dX), V), "dE")
+    lr = np.float32(w.lr)
+    for k in P0:
+        check(tr.P[k].cpu().numpy().astype(np.float64), O.sgd_update(P0[k], g[k], lr), 1e-6, np.abs(P0[k]) + lr * np.abs(g[k]), "update " + k)
