@@ -425,8 +425,13 @@ __global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int6
   constexpr int VPR = TC / E, RPP = 256 / VPR;
   extern __shared__ __align__(16) char tiles[];   // one 16 KB tile per transposed input
   const int t = threadIdx.x;
-  const int64_t r0 = ((int64_t)blockIdx.x / tiles_c) * TR;
-  const int64_t c0 = ((int64_t)blockIdx.x % tiles_c) * TC;
+  // Diagonal tile order: blocks that run at the same time differ in their row tile AND their column
+  // tile.  With a power-of-two leading dimension, neighbours that differed in one of them only would
+  // send all their strided 256-byte reads of one operand to the same few memory channels.
+  const int64_t tiles_r = (a.rows + TR - 1) / TR;
+  const int64_t ct = (int64_t)blockIdx.x % tiles_c;
+  const int64_t rt = ((int64_t)blockIdx.x / tiles_c + ct) % tiles_r;
+  const int64_t r0 = rt * TR, c0 = ct * TC;
   {
     const int rchunk = t & 15, cl = t >> 4;
     const int64_t r = r0 + rchunk * E;
@@ -445,31 +450,46 @@ __global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int6
       }
     }
   }
-  __syncthreads();
+  // The other operands' loads for all passes are issued now, next to the tile loads, so that every
+  // global read of the block is in flight at once and only one memory latency is exposed.
+  constexpr int NP = TR / RPP;
   const int cq = t % VPR, rr = t / VPR;
   const int64_t c = c0 + cq * E;
+  Vec16<T> d[NIN][NP];
 #pragma unroll
-  for (int pass = 0; pass < TR / RPP; ++pass) {
+  for (int k = 0; k < NIN; ++k) {
+    if (a.transposed[k]) continue;
+    const T *p = static_cast<const T *>(a.in[k]);
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass) {
+      const int64_t r = r0 + rr + pass * RPP;
+      d[k][pass].raw = {};
+      if (r < a.rows && c < a.cols) {
+        if (a.istr1[k] == 0) {
+          const float v = Elem<T>::load(p + r * a.istr0[k]);
+#pragma unroll
+          for (int i = 0; i < E; ++i) d[k][pass].set(i, v);
+        } else if (a.istr0[k] == 0) d[k][pass].load(p + c);
+        else d[k][pass].load_nt(p + r * a.istr0[k] + c);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < NP; ++pass) {
     const int rl = rr + pass * RPP;
     const int64_t r = r0 + rl;
     if (r < a.rows && c < a.cols) {
       float f[3][E];
 #pragma unroll
       for (int k = 0; k < NIN; ++k) {
-        const T *p = static_cast<const T *>(a.in[k]);
         if (a.transposed[k]) {
           const char *base = tiles + a.slot[k] * (TC * 256) + (((rl / E) ^ (cq & 15)) << 4) + (rl % E) * (int)sizeof(T);
 #pragma unroll
           for (int i = 0; i < E; ++i) f[k][i] = Elem<T>::load(reinterpret_cast<const T *>(base + (cq * E + i) * 256));
-        } else if (a.istr1[k] == 0) {
-          const float v = Elem<T>::load(p + r * a.istr0[k]);
-#pragma unroll
-          for (int i = 0; i < E; ++i) f[k][i] = v;
         } else {
-          Vec16<T> v;
-          if (a.istr0[k] == 0) v.load(p + c); else v.load_nt(p + r * a.istr0[k] + c);
 #pragma unroll
-          for (int i = 0; i < E; ++i) f[k][i] = v.get(i);
+          for (int i = 0; i < E; ++i) f[k][i] = d[k][pass].get(i);
         }
       }
       Vec16<T> o;
