@@ -285,7 +285,10 @@ chn_status launch(const RPlan &p, const chn_array *in, const chn_array *out, voi
     float *part = static_cast<float *>(ws);
     const int64_t OI = p.O * p.I;
     CHN_TRY((launch_col<OP, Tin, float>(src, part, p, p.O, p.len, p.I, p.sO, p.sR, p.split, p.rows_per_split, OI, p.vec, p.tx, st)));
-    return launch_col<OP, float, Tout>(part, dst, p, 1, p.split, OI, 0, OI, 1, p.split, 0, OI % 4 == 0, kColTXNarrow, st);
+    // Second pass over the [split, O * I] partials: a small array, so the time is one chain of
+    // dependent load batches per lane; the narrow-in-columns block shape keeps that chain short.
+    const bool wide2 = OI % 4 == 0 && OI / 4 >= 512 && p.split >= 16;
+    return launch_col<OP, float, Tout>(part, dst, p, 1, p.split, OI, 0, OI, 1, p.split, 0, OI % 4 == 0, wide2 ? kColTXWide : kColTXNarrow, st);
   }
   GenArgs a{};
   a.nk = p.nk; a.len = p.len; a.sR = p.sR; a.total_out = p.total_out;
