@@ -1,5 +1,7 @@
 // chn_gemm: host side of the dense product -- validation, layout classification and dispatch to the
 // kernel families in gemm_kernel.h (one object file per dtype and operand layout).
+#include <cstdlib>
+
 #include "common.h"
 #include "gemm_args.h"
 
@@ -165,6 +167,15 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     // split-K is an optimisation: without (enough, aligned) workspace the product is planned unsplit
     if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);
     else plan(&g, isz, false);
+  }
+  {
+    static const int dma_mask = [] { const char *e = getenv("CHN_GEMM_DMA"); return e ? atoi(e) : 15; }();
+    // bit 0: kk, bit 1: km, bit 2: mk  (+8: also fp32)
+    const int layout_bit = a_kc ? (b_kc ? 1 : 2) : (b_kc ? 4 : 0);
+    const int bk = 128 / isz;   // the direct-copy kernel handles whole tile steps of K and 32-bit row offsets
+    const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
+    g.dma = (dma_mask & layout_bit) != 0 && (A->dtype == CHN_BF16 || (dma_mask & 8)) && K > 0 && K % bk == 0 &&
+            (!a_kc || g.lda < max_ld) && (!b_kc || g.ldb < max_ld);
   }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {

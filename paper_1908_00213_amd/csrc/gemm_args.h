@@ -26,6 +26,7 @@ struct GemmArgs {
   float *partial;         // split-K: [splits][M][ldp] fp32 partial sums in the caller's workspace
   int64_t ldp;
   int epi_vec;            // C, aux, preact and bias allow aligned 4-element vector accesses
+  int dma;                // big tile: K-contiguous operands go to LDS by direct global-to-LDS loads
 };
 
 }  // namespace gemm

@@ -39,6 +39,12 @@
 namespace chn {
 namespace gemm {
 
+#ifndef CHN_EPI_U
+#define CHN_EPI_U 4
+#endif
+#ifndef CHN_TOUCH
+#define CHN_TOUCH 1
+#endif
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -259,7 +265,10 @@ __device__ __forceinline__ void mma(floatx16 (&acc)[TM][TN], const Frags<TM, TN>
 }
 
 // Scheduling hints (instruction-class masks of __builtin_amdgcn_sched_group_barrier).
-constexpr int SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
+constexpr int SG_MFMA = 0x008, SG_VMEM = 0x010, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200;
+// s_waitcnt immediate (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) that waits
+// for the vector-memory counter only.
+constexpr int kWaitVmcnt0 = 0x0F70;
 
 // `groups` times: `nr` LDS reads, then `nm` MFMAs.
 template <int GROUPS, int NR, int NM>
@@ -363,42 +372,106 @@ __device__ __forceinline__ void finish1(const GemmArgs &g, int row, int col, flo
   store1(g.C, ci, g.c_bf16, x);
 }
 
-// Rows [row0, row0+32) x columns [col0, col0 + 32*TN) of C for one wave: `stage` holds the fp32
-// accumulators row-major with pitch PITCH floats.  With K splits the raw sums go to this split's
-// slab of the workspace instead.
+// Same as finish4 with the epilogue kind fixed at compile time (the tile kernels pick the kind once
+// per pass, outside their loops).
+template <int EPI>
+__device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, const f32x4 a, const EpiIn &in) {
+  Vec4 b, x, pre;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) b.v[e] = 0.0f;
+  if constexpr (EPI >= CHN_EPI_BIAS && EPI <= CHN_EPI_BIAS_GELU) b = load4v(g.bias, col, 0);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float t = g.alpha * a[e];
+    if (g.beta != 0.0f) t += g.beta * in.c0.v[e];
+    t += b.v[e];
+    pre.v[e] = t;
+    if constexpr (EPI == CHN_EPI_BIAS_RELU) t = fmaxf(t, 0.0f);
+    else if constexpr (EPI == CHN_EPI_BIAS_GELU) t = gelu_epi_f(t);
+    else if constexpr (EPI == CHN_EPI_RELU_BWD) t = in.aux.v[e] > 0.0f ? t : 0.0f;
+    else if constexpr (EPI == CHN_EPI_GELU_BWD) t *= gelu_grad_epi_f(in.aux.v[e]);
+    x.v[e] = t;
+  }
+  if constexpr (EPI == CHN_EPI_BIAS_GELU) {
+    if (g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+  }
+  store4v(g.C, (int64_t)row * g.ldc + col, g.c_bf16, x);
+}
+
+// Where the accumulators of one wave wait in LDS between the MFMA register layout and the row-major
+// epilogue: RP rows of W = 32*TN floats.  A lane writes column r of rows .. + 4h, so rows four apart
+// must not share banks: for W >= 64 the columns of every other group of four rows are XORed with 32
+// (a row is a multiple of the 64 banks wide), the narrow W = 32 layout pads its rows instead.
 template <int TN>
-__device__ __forceinline__ void epilogue_rows(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab) {
-  constexpr int W = 32 * TN, PITCH = W + 8, CPR = W / 4;      // 16-byte chunks per row
-  constexpr int NIT = 32 * CPR / 64;                          // row segments per lane
-  constexpr int U = NIT < 4 ? NIT : 4;                        // segments whose reads are in flight together
+struct StageLayout {
+  static constexpr int W = 32 * TN;
+  static constexpr int PITCH = TN == 1 ? W + 8 : W;
+  static __device__ __forceinline__ int at(int row, int col) {
+    if constexpr (TN == 1) return row * PITCH + col;
+    else return row * W + (col ^ (((row >> 2) & 1) << 5));
+  }
+};
+
+// Vector path of one pass: RP rows x W columns starting at (row0, col0), every row and column in
+// range and all accesses aligned, so that the loop is free of per-lane conditions.  Lane l handles
+// four consecutive columns; the LDS reads and the dependent global reads (old C, aux) of U row
+// segments are in flight together.
+template <int EPI, int TN, int RP>
+__device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float *stage, int row0, int col0, int lane) {
+  using L = StageLayout<TN>;
+  constexpr int CPR = L::W / 4, NIT = RP * CPR / 64, U = CHN_EPI_U;
+  static_assert(NIT % U == 0, "row segments per lane must come in whole batches");
+  constexpr bool kAux = EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD;
+#pragma unroll 1
+  for (int base = 0; base < NIT; base += U) {
+    EpiIn in[U];
+    f32x4 a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int c = lane + (base + u) * 64;
+      const int rl = c / CPR, cl = (c % CPR) * 4;
+      a[u] = *reinterpret_cast<const f32x4 *>(stage + L::at(rl, cl));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) in[u].c0.v[e] = in[u].aux.v[e] = 0.0f;
+      if (g.beta != 0.0f) in[u].c0 = load4v(g.C, (int64_t)(row0 + rl) * g.ldc + col0 + cl, g.c_bf16);
+      if constexpr (kAux) in[u].aux = load4v(g.aux, (int64_t)(row0 + rl) * g.ldaux + col0 + cl, g.c_bf16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int c = lane + (base + u) * 64;
+      finish4_t<EPI>(g, row0 + c / CPR, col0 + (c % CPR) * 4, a[u], in[u]);
+    }
+  }
+}
+
+// One pass of a wave's epilogue: RP rows x W columns of staged accumulators.  With K splits the raw
+// sums go to this split's slab of the workspace instead.
+template <int TN, int RP>
+__device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab) {
+  using L = StageLayout<TN>;
+  constexpr int W = L::W, CPR = W / 4;
   if (slab) {                                                 // split-K: raw sums, always aligned (ldp % 4 == 0)
-    for (int c = lane; c < 32 * CPR; c += 64) {
+#pragma unroll 1
+    for (int c = lane; c < RP * CPR; c += 64) {
       const int rl = c / CPR, cl = (c % CPR) * 4;
       if (row0 + rl < g.M && col0 + cl < g.N)
         global_store<f32x4>(reinterpret_cast<uintptr_t>(slab + (int64_t)(row0 + rl) * g.ldp + col0 + cl),
-                            *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl));
+                            *reinterpret_cast<const f32x4 *>(stage + L::at(rl, cl)));
     }
-  } else if (g.epi_vec && col0 + W <= g.N) {                  // fast path: lane l handles 4 consecutive columns
-#pragma unroll 1
-    for (int base = 0; base < NIT; base += U) {
-      EpiIn in[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int c = lane + (base + u) * 64;
-        if (row0 + c / CPR < g.M) in[u] = epi_fetch(g, row0 + c / CPR, col0 + (c % CPR) * 4);
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int c = lane + (base + u) * 64;
-        const int rl = c / CPR, cl = (c % CPR) * 4;
-        if (row0 + rl < g.M) finish4(g, row0 + rl, col0 + cl, *reinterpret_cast<const f32x4 *>(stage + rl * PITCH + cl), in[u]);
-      }
+  } else if (g.epi_vec && col0 + W <= g.N && row0 + RP <= g.M) {
+    switch (g.epi) {
+      case CHN_EPI_NONE: epilogue_pass_vec<CHN_EPI_NONE, TN, RP>(g, stage, row0, col0, lane); break;
+      case CHN_EPI_BIAS: epilogue_pass_vec<CHN_EPI_BIAS, TN, RP>(g, stage, row0, col0, lane); break;
+      case CHN_EPI_BIAS_RELU: epilogue_pass_vec<CHN_EPI_BIAS_RELU, TN, RP>(g, stage, row0, col0, lane); break;
+      case CHN_EPI_BIAS_GELU: epilogue_pass_vec<CHN_EPI_BIAS_GELU, TN, RP>(g, stage, row0, col0, lane); break;
+      case CHN_EPI_RELU_BWD: epilogue_pass_vec<CHN_EPI_RELU_BWD, TN, RP>(g, stage, row0, col0, lane); break;
+      default: epilogue_pass_vec<CHN_EPI_GELU_BWD, TN, RP>(g, stage, row0, col0, lane); break;
     }
-  } else {                                                    // slow path: one element at a time
+  } else {                                                    // ragged right edge or unaligned views: one element at a time
 #pragma unroll 1
-    for (int c = lane; c < 32 * W; c += 64) {
+    for (int c = lane; c < RP * W; c += 64) {
       const int rl = c / W, cl = c % W;
-      if (row0 + rl < g.M && col0 + cl < g.N) finish1(g, row0 + rl, col0 + cl, stage[rl * PITCH + cl]);
+      if (row0 + rl < g.M && col0 + cl < g.N) finish1(g, row0 + rl, col0 + cl, stage[L::at(rl, cl)]);
     }
   }
 }
@@ -421,14 +494,10 @@ static __global__ __launch_bounds__(256) void gemm_splitk_finish_kernel(GemmArgs
   }
 }
 
-template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int BK = 128 / sizeof(T);               // elements of k per tile step
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  extern __shared__ __align__(16) char lds[];
-
-  // ---- which C tile: XCD-aware renumbering, then grouped (8 tile rows at a time) ordering
+// Which C tile (and which K split) a workgroup owns: XCD-aware renumbering, then grouped (8 tile rows
+// at a time) ordering.
+struct TilePos { int tm, tn, split; };
+__device__ __forceinline__ TilePos tile_pos(const GemmArgs &g) {
   const int nb = g.tiles_m * g.tiles_n;
   int pid = blockIdx.x % nb;
   const int split = blockIdx.x / nb;
@@ -438,9 +507,61 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const int width = GROUP * g.tiles_n;
   const int first_m = (pid / width) * GROUP;
   const int gsize = min(g.tiles_m - first_m, GROUP);
-  const int tm = first_m + (pid % width) % gsize;
-  const int tn = (pid % width) / gsize;
-  const int m0 = tm * BM, n0 = tn * BN;
+  return TilePos{first_m + (pid % width) % gsize, (pid % width) / gsize, split};
+}
+
+// Epilogue of one workgroup.  Each wave moves its accumulators through its own LDS area `stage`
+// (kEpiStageBytes<TM, TN> bytes; the caller has made sure that nobody uses that memory for anything
+// else any more) in passes of up to 64 rows: MFMA layout in, row-major out, so that bias / activation
+// / activation-gradient run on 16-byte vectors and C, aux and preact are touched as whole row
+// segments.  A lane holds, per 32x32 block, column r and rows 8*(v/4) + 4*h + v%4.  Only the
+// register-to-LDS part exists once per pass (accumulator registers cannot be indexed at run time);
+// everything after it is one loop, so the code a wave runs through stays small.
+template <int TM, int TN>
+constexpr int kEpiRows = TM == 1 ? 32 : 64;
+template <int TM, int TN>
+constexpr int kEpiStageBytes = kEpiRows<TM, TN> * StageLayout<TN>::PITCH * 4;
+
+template <int TM, int TN>
+__device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM][TN], char *stage_bytes, int m0, int n0, int split) {
+  using L = StageLayout<TN>;
+  constexpr int RP = kEpiRows<TM, TN>, IPP = RP / 32, NPASS = TM / IPP;   // 32-row blocks per pass, passes
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r = lane & 31, h = lane >> 5;
+  float *stage = reinterpret_cast<float *>(stage_bytes);
+  float *slab = g.splits > 1 ? g.partial + (int64_t)split * g.M * g.ldp : nullptr;
+  auto put = [&](auto pc) {
+    constexpr int P = decltype(pc)::value;
+#pragma unroll
+    for (int ii = 0; ii < IPP; ++ii)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          stage[L::at(ii * 32 + 8 * (v >> 2) + 4 * h + (v & 3), j * 32 + r)] = acc[P * IPP + ii][j][v];
+        __builtin_amdgcn_sched_barrier(0);   // one block's 16 values in flight at a time, not the whole pass
+      }
+  };
+#pragma unroll 1
+  for (int p = 0; p < NPASS; ++p) {
+    if (p == 0) put(std::integral_constant<int, 0>{});
+    else put(std::integral_constant<int, NPASS - 1>{});
+    __builtin_amdgcn_wave_barrier();
+    epilogue_pass<TN, RP>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab);
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int BK = 128 / sizeof(T);               // elements of k per tile step
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  extern __shared__ __align__(16) char lds[];
+
+  const TilePos tp = tile_pos(g);
+  const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
 
   TileLoader<T, BM, A_KC, PB> la;
   TileLoader<T, BN, B_KC, PB> lb;
@@ -542,36 +663,244 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     if constexpr (kSched) sched_reads_mfma<NR, 1, NM / NR>();
   }
 
-  // ---- epilogue: per wave and per 32-row block, accumulators -> LDS (row-major) -> vector epilogue.
-  // Lane holds, per 32x32 block, column r and rows 8*(v/4) + 4*h + v%4.
   __syncthreads();   // every wave is done with the operand stages
-  constexpr int PITCH = 32 * TN + 8;
-  float *stage = reinterpret_cast<float *>(lds) + wave * (32 * PITCH);
-  float *slab = g.splits > 1 ? g.partial + (int64_t)split * g.M * g.ldp : nullptr;
-  // (written out per 32-row block: the compiler refuses to unroll a loop this large, and a rolled
-  // loop would index the accumulator registers dynamically, i.e. move them to scratch memory)
-  auto block = [&](auto ic) {
-    constexpr int i = decltype(ic)::value;
+  write_out<TM, TN>(g, acc, lds + (threadIdx.x >> 6) * kEpiStageBytes<TM, TN>, m0, n0, split);
+}
+
+// ---- big tile, K-contiguous operands copied by the memory pipeline itself ---------------------------
+// A K-contiguous operand tile needs no arithmetic on its way into LDS, so gfx950's 16-byte
+// global-load-to-LDS instruction can move it: no staging registers, no LDS store instructions, and
+// the copy may be in flight for a whole tile step.  One such instruction writes the 64 lanes' chunks
+// to 1024 consecutive LDS bytes (8 tile rows), so the swizzle is applied on the global side: the
+// lane that fills physical slot (row p, chunk c) fetches the logical chunk that lives there.
+template <typename T, int ROWS>
+struct DmaLoader {
+  static constexpr int EPC = Traits<T>::EPC;
+  static constexpr int BK = 128 / (int)sizeof(T);
+  static constexpr int NS = ROWS / 32;     // instructions per wave and tile
+  const char *tile;                        // wave-uniform: first row of the tile, k = 0
+  uint32_t off[NS];                        // byte offset of the slot's chunk from `tile`
+  int wave, k_last;                        // wave-uniform
+
+  // K is a positive multiple of BK (the host only picks this kernel then), so a chunk is never
+  // partly valid along k.  Rows past the operand's end are read from its last row instead: they only
+  // feed rows or columns of C that are never written.
+  __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K) {
+    wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    k_last = K - BK;
+    tile = reinterpret_cast<const char *>(base + (int64_t)row0 * ld);
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const int slot = (i * 4 + wave) * 64 + lane;
+      const int prow = slot >> 3, pchunk = slot & 7;
+      const int row = lds_row<T>(prow);                 // the row swap is its own inverse
+      const int kc = (pchunk ^ ((row >> 1) & 7)) * EPC;
+      const int rowc = min(row, rows_total - 1 - row0);
+      off[i] = (uint32_t)(((int64_t)rowc * ld + kc) * (int64_t)sizeof(T));
+    }
+  }
+
+  // Start the copy of the tile whose first k is k0 into the operand's part of a stage.  Tiles past
+  // the end of K (requested by the last steps, never used) re-read the last tile.
+  __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
+    const char *p = tile + (int64_t)min(k0, k_last) * (int64_t)sizeof(T);
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + off[i]),
+                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
+                                       16, 0, 0);
+  }
+};
+
+// Pull the cache lines of a BM x BN tile of a row-major array (C or aux, `esz` bytes per element)
+// towards L2 without spending registers or branches: four bytes of every line are copied to a scrap
+// area in LDS.  `scrap` needs 1024 bytes; nothing ever reads it.
+template <int BM, int BN>
+__device__ __forceinline__ void touch_tile(const void *p, int64_t ld, int esz, int M, int N, int m0, int n0, char *scrap) {
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  constexpr int SEG = 8, NT = BM * SEG / 256;     // eight touches per row: every 128 (fp32) or 64 (bf16) bytes
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int i = threadIdx.x + t * 256;
+    const int row = min(m0 + i / SEG, M - 1);
+    const int col = min(n0 + (i % SEG) * (BN / SEG), N - 1) & ~1;
+    const char *a = static_cast<const char *>(p) + ((int64_t)row * ld + col) * esz;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
+                                     (__attribute__((address_space(3))) void *)(scrap + wave * 256), 4, 0, 0);
+  }
+}
+
+// 256 x 256 tile with at least one K-contiguous operand whose rows allow 16-byte pieces.  The two
+// stages are two separate LDS arrays and the K loop is written out for both roles of them: only
+// then can the compiler tell that a copy in flight into one stage does not concern the fragment
+// reads of the other, and leave the wait for the copy to the barrier.
+// One tile step: k-steps 0..2 out of `cur` while the copy of the next tile (started one step ago)
+// lands in `nxt`; barrier (copy complete, nobody reads `cur` any more); start the copy of the tile
+// after the next into `cur`; k-step 3 while the first fragments of `nxt` are read.
+#ifdef CHN_GEMM_TS
+__device__ uint64_t g_ts[16];
+#define CHN_TS(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_ts[i] = wall_clock64(); } while (0)
+#else
+#define CHN_TS(i) do {} while (0)
+#endif
+template <typename T, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
+  CHN_TS(0);
+  static_assert(A_KC || B_KC, "at least one operand must be copied directly");
+  constexpr int TM = 4, TN = 4, BM = 256, BN = 256;
+  constexpr int BK = 128 / sizeof(T);
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  // (each stage is followed by 1 KB of scrap for touch_tile: as part of the same array it falls into
+  // the same class as the stage's real copies when the compiler decides which LDS reads must wait)
+  __shared__ __align__(1024) char stage0[STAGE + 1024];
+  __shared__ __align__(1024) char stage1[STAGE + 1024];
+
+  const TilePos tp = tile_pos(g);
+  const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
+
+  std::conditional_t<A_KC, DmaLoader<T, BM>, TileLoader<T, BM, false, 16>> la;
+  std::conditional_t<B_KC, DmaLoader<T, BN>, TileLoader<T, BN, false, 16>> lb;
+  la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
+  lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r = lane & 31, h = lane >> 5;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + r] = acc[i][j][v];
-    __builtin_amdgcn_wave_barrier();
-    epilogue_rows<TN>(g, stage, m0 + (wm * TM + i) * 32, n0 + wn * TN * 32, lane, slab);
-    __builtin_amdgcn_wave_barrier();
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int rp = lds_row<T>(r);
+  const int a_row = (wm * TM * 32 + rp) * 128, b_row = A_BYTES + (wn * TN * 32 + rp) * 128;
+  const int sw = (r >> 1) & 7;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + h) ^ sw) << 4;
+
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int per_split = (nk_all + g.splits - 1) / g.splits;
+  const int kt0 = split * per_split;
+  const int nk = min(nk_all, kt0 + per_split);
+
+  auto k_of = [&](int kt) { return kt * BK; };   // first k of tile step kt
+
+  // prologue: first tile into stage 0, second tile on its way into stage 1
+  if constexpr (A_KC) { la.issue(k_of(kt0), stage0); la.issue(k_of(kt0 + 1), stage1); }
+  else { la.issue(k_of(kt0)); la.store(stage0); }
+  if constexpr (B_KC) { lb.issue(k_of(kt0), stage0 + A_BYTES); lb.issue(k_of(kt0 + 1), stage1 + A_BYTES); }
+  else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
+  CHN_TS(1);
+  __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+  __syncthreads();
+  CHN_TS(2);
+  Frags<TM, TN> f0, f1;
+  f0.read(stage0 + a_row, stage0 + b_row, koff[0]);
+
+  constexpr int NM = (sizeof(T) == 2 ? 1 : 4) * TM * TN;   // MFMAs per k-step
+  constexpr int NR = TM + TN;                              // fragment reads per k-step
+  constexpr int NMC = (A_KC ? 0 : 8) + (B_KC ? 0 : 8);     // 16-byte register loads per step (transposed operand)
+  constexpr int NDMA = (A_KC ? 8 : 0) + (B_KC ? 8 : 0);    // direct copies per wave and step
+
+  auto step = [&](char *cur, char *nxt, int kt) __attribute__((always_inline)) {
+    // k-step 0 (a transposed operand's loads of the next tile are issued here and written in k-step 2)
+    f1.read(cur + a_row, cur + b_row, koff[1]);
+    if constexpr (!A_KC) la.issue(k_of(kt + 1));
+    if constexpr (!B_KC) lb.issue(k_of(kt + 1));
+    mma<T, TM, TN>(acc, f0);
+#pragma unroll
+    for (int s = 0; s < NR; ++s) {
+      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+      if constexpr (NMC > 0) __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, NMC / NR, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
+    }
+    // k-step 1
+    f0.read(cur + a_row, cur + b_row, koff[2]);
+    mma<T, TM, TN>(acc, f1);
+    sched_reads_mfma<NR, 1, NM / NR>();
+    // k-step 2
+    f1.read(cur + a_row, cur + b_row, koff[3]);
+    mma<T, TM, TN>(acc, f0);
+    sched_reads_mfma<NR, 1, NM / NR>();
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (!A_KC) la.store(nxt);
+    if constexpr (!B_KC) lb.store(nxt + A_BYTES);
+    // A wave's own copies must have landed before it tells the others so: the counter of the vector
+    // memory pipeline (which also tracks copies to LDS) has to be zero ahead of the barrier.
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 3, overlapped with the first fragment reads of the next stage and with the issue of the
+    // copies of the tile after the next (their target, `cur`, is free from here on)
+    if constexpr (A_KC) la.issue(k_of(kt + 2), cur);
+    if constexpr (B_KC) lb.issue(k_of(kt + 2), cur + A_BYTES);
+    f0.read(nxt + a_row, nxt + b_row, koff[0]);
+    mma<T, TM, TN>(acc, f1);
+#pragma unroll
+    for (int s = 0; s < NR; ++s) {
+      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_VMEM, NDMA / NR, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   };
-  block(std::integral_constant<int, 0>{});
-  if constexpr (TM > 1) block(std::integral_constant<int, 1>{});
-  if constexpr (TM > 2) {
-    block(std::integral_constant<int, 2>{});
-    block(std::integral_constant<int, 3>{});
+
+  int kt = kt0;
+  for (; kt + 3 < nk; kt += 2) {
+    step(stage0, stage1, kt);
+    step(stage1, stage0, kt + 1);
+  }
+  // Two or three steps to go.  The epilogue's own reads (old C, retained activation) would each cost
+  // a trip to HBM with nobody to hide it, so their lines are requested now and wait in L2.  (Outside
+  // the main loop on purpose: with these extra copies around, the compiler makes the fragment reads
+  // of the following step wait for all copies in flight.  They go to the scrap of stage 1, the stage
+  // the next step does not read before its barrier.)
+  if (CHN_TOUCH && g.splits == 1) {
+    const int esz = g.c_bf16 ? 2 : 4;
+    if (g.beta != 0.0f) touch_tile<BM, BN>(g.C, g.ldc, esz, g.M, g.N, m0, n0, stage1 + STAGE);
+    if (g.epi == CHN_EPI_RELU_BWD || g.epi == CHN_EPI_GELU_BWD) touch_tile<BM, BN>(g.aux, g.ldaux, esz, g.M, g.N, m0, n0, stage1 + STAGE);
+  }
+  for (; kt + 1 < nk; kt += 2) {
+    step(stage0, stage1, kt);
+    step(stage1, stage0, kt + 1);
+  }
+  if (kt < nk) step(stage0, stage1, kt);
+
+  // The (unused) copies that the last steps started must be over: the epilogue reuses stage 0.
+  CHN_TS(3);
+  __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+  __syncthreads();
+  CHN_TS(4);
+  static_assert(2 * kEpiStageBytes<TM, TN> <= STAGE, "two waves stage their accumulators in each operand stage");
+  write_out<TM, TN>(g, acc, (wave < 2 ? stage0 : stage1) + (wave & 1) * kEpiStageBytes<TM, TN>, m0, n0, split);
+  CHN_TS(5);
+}
+
+template <typename T, bool A_KC, bool B_KC>
+chn_status launch_dma(const GemmArgs &g, hipStream_t st) {
+  if constexpr (A_KC || B_KC) {
+    hipLaunchKernelGGL((gemm_kernel_dma<T, A_KC, B_KC>), dim3((unsigned)(g.tiles_m * g.tiles_n * g.splits)), dim3(256), 0, st, g);
+    CHN_TRY(check_launch("gemm (direct-to-LDS)"));
+    if (g.splits > 1) {
+      const int64_t n = (int64_t)g.M * (g.ldp / 4);
+      hipLaunchKernelGGL(gemm_splitk_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, g);
+      return check_launch("gemm split-K finish");
+    }
+    return CHN_OK;
+  } else {
+    return fail(CHN_ERR_LAUNCH, "gemm: internal: no direct-to-LDS kernel for this layout");
   }
 }
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
 chn_status launch_piece(const GemmArgs &g, hipStream_t st) {
   constexpr int LDS = 2 * (64 * TM + 64 * TN) * 128;
-  static_assert(4 * 32 * (32 * TN + 8) * 4 <= LDS, "epilogue staging must fit in the operand stages");
+  static_assert(4 * kEpiStageBytes<TM, TN> <= LDS, "epilogue staging must fit in the operand stages");
   auto kern = gemm_kernel<T, TM, TN, A_KC, B_KC, PB>;
   static bool configured = false;  // per instantiation
   if (!configured) {
@@ -602,6 +931,9 @@ chn_status launch_tile(const GemmArgs &g, hipStream_t st) {
 template <typename T, bool A_KC, bool B_KC>
 chn_status launch_layout(GemmArgs &g, hipStream_t st) {
   if ((int64_t)g.tiles_m * g.tiles_n * g.splits > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
+  if constexpr (A_KC || B_KC) {
+    if (g.tile == 2 && g.piece == 16 && g.dma) return launch_dma<T, A_KC, B_KC>(g, st);
+  }
   if (g.tile == 2) return launch_tile<T, 4, 4, A_KC, B_KC>(g, st);
   if (g.tile == 1) return launch_tile<T, 2, 2, A_KC, B_KC>(g, st);
   return launch_tile<T, 1, 1, A_KC, B_KC>(g, st);

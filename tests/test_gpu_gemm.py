@@ -70,6 +70,23 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
     assert np.array_equal(out, ref)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("shape", [(3704, 3592, 192), (2008, 2104, 64), (520, 4104, 448)])
+def test_gemm_big_tiles_whole_k_steps(dt, layout, shape):
+    # K a multiple of the tile step and every unit-stride extent a multiple of 16 bytes: the 256x256
+    # kernel that copies its K-contiguous operands straight into LDS; an odd and an even number of
+    # tile steps, a single one, ragged last tiles in M and N
+    M, N, K = shape
+    gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gen)
+    out = host(B.gemm(Ad, Bd, empty((M, N))))
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    rows = RNG.integers(0, M, 24)
+    assert np.array_equal(O.gemm(A[rows], Bm), ref[rows])
+    assert np.array_equal(out, ref)
+
+
 def test_gemm_identity_and_ones():
     x = rnd((200, 96))
     assert np.array_equal(host(B.gemm(dev(x), dev(np.eye(96, dtype=np.float32)), empty((200, 96)))), x)
