@@ -169,13 +169,13 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     else plan(&g, isz, false);
   }
   {
-    static const int dma_mask = [] { const char *e = getenv("CHN_GEMM_DMA"); return e ? atoi(e) : 15; }();
-    // bit 0: kk, bit 1: km, bit 2: mk  (+8: also fp32)
-    const int layout_bit = a_kc ? (b_kc ? 1 : 2) : (b_kc ? 4 : 0);
-    const int bk = 128 / isz;   // the direct-copy kernel handles whole tile steps of K and 32-bit row offsets
+    // The direct-copy 256x256 kernel handles whole tile steps of K, 16-byte pieces and 32-bit offsets
+    // inside a tile; fp32 needs at least one K-contiguous operand for it.  (CHN_GEMM_DMA=0 switches
+    // it off: a tuning aid.)
+    static const bool dma_on = [] { const char *e = getenv("CHN_GEMM_DMA"); return !e || atoi(e) != 0; }();
+    const int bk = 128 / isz;
     const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
-    g.dma = (dma_mask & layout_bit) != 0 && (A->dtype == CHN_BF16 || (dma_mask & 8)) && K > 0 && K % bk == 0 &&
-            (!a_kc || g.lda < max_ld) && (!b_kc || g.ldb < max_ld);
+    g.dma = dma_on && K > 0 && K % bk == 0 && g.lda < max_ld && g.ldb < max_ld && (A->dtype == CHN_BF16 || a_kc || b_kc);
   }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {

@@ -526,7 +526,10 @@ template <int TM, int TN>
 __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM][TN], char *stage_bytes, int m0, int n0, int split) {
   using L = StageLayout<TN>;
   constexpr int RP = kEpiRows<TM, TN>, IPP = RP / 32, NPASS = TM / IPP;   // 32-row blocks per pass, passes
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // (the lane id is taken from the hardware rather than from threadIdx.x: otherwise the compiler keeps
+  // the value computed before the K loop alive across it, in a kernel that has no register to spare)
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
   const int wm = wave >> 1, wn = wave & 1;
   const int r = lane & 31, h = lane >> 5;
   float *stage = reinterpret_cast<float *>(stage_bytes);
@@ -713,6 +716,92 @@ struct DmaLoader {
   }
 };
 
+// The same for a bf16 operand whose unit stride runs along M/N: the tile goes to LDS as it lies in
+// memory, BK rows of k, each ROWS elements (512 bytes) of m, and is transposed on the way out of LDS
+// by the 16-bit transposing read (see TrReader).  The eight 64-byte blocks of a k-row are XORed with
+// k % 8, so that the four k-rows one group of lanes reads together sit in different banks.
+template <int ROWS>
+struct DmaLoaderMC {
+  static_assert(ROWS == 256, "one k-row must be 512 bytes");
+  static constexpr int BK = 64, NS = BK * 512 / 1024 / 4;   // instructions per wave and tile
+  const char *tile;                        // wave-uniform: element (k = 0, m = row0)
+  uint32_t off[NS];
+  int wave, k_last;
+  int64_t kbytes;                          // bytes between consecutive k
+
+  // rows_total is a multiple of 8 (16-byte pieces); chunks past it re-read the operand's last chunk
+  // and only feed rows or columns of C that are never written.
+  __device__ __forceinline__ void init(const bf16_raw *base, int64_t ld, int rows_total, int row0, int K) {
+    wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    k_last = K - BK;
+    kbytes = ld * 2;
+    tile = reinterpret_cast<const char *>(base + row0);
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const int slot = (i * 4 + wave) * 64 + lane;
+      const int k = slot >> 5, p = slot & 31;                  // k-row, 16-byte slot inside it
+      const int m = (((p >> 2) ^ (k & 7)) * 32) + (p & 3) * 8; // the 8 elements that live in that slot
+      const int mc = min(m, rows_total - 8 - row0);
+      off[i] = (uint32_t)(((int64_t)k * ld + mc) * 2);
+    }
+  }
+
+  __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
+    const char *p = tile + (int64_t)min(k0, k_last) * kbytes;
+#pragma unroll
+    for (int i = 0; i < NS; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + off[i]),
+                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
+                                       16, 0, 0);
+  }
+};
+
+// Fragment readers of the direct-copy kernel: read(stage, k-step, 32-row block)
+// returns the lane's 16 bytes (8 bf16 or 4 fp32 along k) for an MFMA.
+// K-packed tile (lds_off layout): one 16-byte read.
+template <typename T>
+struct KcReader {
+  int row, koff[4];
+  // first_block: the wave's first 32-row block; region: byte offset of the operand's part of a stage
+  __device__ __forceinline__ void init(int first_block, int lane, int region) {
+    const int r = lane & 31, h = lane >> 5;
+    row = region + (first_block * 32 + lds_row<T>(r)) * 128;
+    const int sw = (r >> 1) & 7;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + h) ^ sw) << 4;
+  }
+  __device__ __forceinline__ uint4 read(const char *stage, int ks, int i) const {
+    return *reinterpret_cast<const uint4 *>(stage + row + i * (32 * 128) + koff[ks]);
+  }
+};
+// bf16 tile stored [k][m] (DmaLoaderMC): two transposing 8-byte reads.  Within a group of 16 lanes the
+// instruction hands lane i element (i % 4) of the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and
+// 12 + i/4; so lane 4e + q of a group points at (k = .. + e, m = .. + 4q), and every lane ends up with
+// four consecutive k of its own m.  Lanes 0-31 / 32-63 take k 0-7 / 8-15 of the k-step like the K-packed
+// reader, first read k .. + 0-3, second read k .. + 4-7.
+typedef short short4v __attribute__((ext_vector_type(4)));
+struct TrReader {
+  int base[4][2];   // per 32-row block and half: byte offset inside a stage, k-step 0
+  __device__ __forceinline__ void init(int first_block, int lane, int region) {
+    const int G = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3, h = G >> 1, g1 = G & 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int k = 8 * h + 4 * t + e;
+        base[i][t] = region + k * 512 + (((first_block + i) ^ (k & 7)) * 64) + (16 * g1 + 4 * q) * 2;
+      }
+  }
+  __device__ __forceinline__ uint4 read(const char *stage, int ks, int i) const {
+    typedef __attribute__((address_space(3))) short4v *lds_ptr;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stage + base[i][0] + ks * (16 * 512)));
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(stage + base[i][1] + ks * (16 * 512)));
+    const uint2 l = __builtin_bit_cast(uint2, lo), u = __builtin_bit_cast(uint2, hi);
+    return make_uint4(l.x, l.y, u.x, u.y);
+  }
+};
+
 // Pull the cache lines of a BM x BN tile of a row-major array (C or aux, `esz` bytes per element)
 // towards L2 without spending registers or branches: four bytes of every line are copied to a scrap
 // area in LDS.  `scrap` needs 1024 bytes; nothing ever reads it.
@@ -747,7 +836,11 @@ __device__ uint64_t g_ts[16];
 template <typename T, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   CHN_TS(0);
-  static_assert(A_KC || B_KC, "at least one operand must be copied directly");
+  // How each operand reaches LDS: K-contiguous -> direct copy, K-packed; bf16 M/N-contiguous -> direct
+  // copy as it lies, transposing reads; fp32 M/N-contiguous -> through registers (TileLoader).
+  constexpr bool kBf16 = sizeof(T) == 2;
+  constexpr bool A_DMA = A_KC || kBf16, B_DMA = B_KC || kBf16;
+  static_assert(A_DMA || B_DMA, "at least one operand must be copied directly");
   constexpr int TM = 4, TN = 4, BM = 256, BN = 256;
   constexpr int BK = 128 / sizeof(T);
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
@@ -759,8 +852,8 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   const TilePos tp = tile_pos(g);
   const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
 
-  std::conditional_t<A_KC, DmaLoader<T, BM>, TileLoader<T, BM, false, 16>> la;
-  std::conditional_t<B_KC, DmaLoader<T, BN>, TileLoader<T, BN, false, 16>> lb;
+  std::conditional_t<A_KC, DmaLoader<T, BM>, std::conditional_t<kBf16, DmaLoaderMC<BM>, TileLoader<T, BM, false, 16>>> la;
+  std::conditional_t<B_KC, DmaLoader<T, BN>, std::conditional_t<kBf16, DmaLoaderMC<BN>, TileLoader<T, BN, false, 16>>> lb;
   la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
   lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
 
@@ -776,12 +869,16 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int rp = lds_row<T>(r);
-  const int a_row = (wm * TM * 32 + rp) * 128, b_row = A_BYTES + (wn * TN * 32 + rp) * 128;
-  const int sw = (r >> 1) & 7;
-  int koff[4];
+  std::conditional_t<A_KC || !kBf16, KcReader<T>, TrReader> ra;
+  std::conditional_t<B_KC || !kBf16, KcReader<T>, TrReader> rb;
+  ra.init(wm * TM, lane, 0);
+  rb.init(wn * TN, lane, A_BYTES);
+  auto read_frags = [&](Frags<TM, TN> &f, const char *stage, int ks) __attribute__((always_inline)) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + h) ^ sw) << 4;
+    for (int i = 0; i < TM; ++i) f.a[i] = ra.read(stage, ks, i);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = rb.read(stage, ks, j);
+  };
 
   const int nk_all = (g.K + BK - 1) / BK;
   const int per_split = (nk_all + g.splits - 1) / g.splits;
@@ -791,45 +888,59 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   auto k_of = [&](int kt) { return kt * BK; };   // first k of tile step kt
 
   // prologue: first tile into stage 0, second tile on its way into stage 1
-  if constexpr (A_KC) { la.issue(k_of(kt0), stage0); la.issue(k_of(kt0 + 1), stage1); }
+  if constexpr (A_DMA) { la.issue(k_of(kt0), stage0); la.issue(k_of(kt0 + 1), stage1); }
   else { la.issue(k_of(kt0)); la.store(stage0); }
-  if constexpr (B_KC) { lb.issue(k_of(kt0), stage0 + A_BYTES); lb.issue(k_of(kt0 + 1), stage1 + A_BYTES); }
+  if constexpr (B_DMA) { lb.issue(k_of(kt0), stage0 + A_BYTES); lb.issue(k_of(kt0 + 1), stage1 + A_BYTES); }
   else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
   CHN_TS(1);
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
   CHN_TS(2);
   Frags<TM, TN> f0, f1;
-  f0.read(stage0 + a_row, stage0 + b_row, koff[0]);
+  read_frags(f0, stage0, 0);
 
   constexpr int NM = (sizeof(T) == 2 ? 1 : 4) * TM * TN;   // MFMAs per k-step
-  constexpr int NR = TM + TN;                              // fragment reads per k-step
-  constexpr int NMC = (A_KC ? 0 : 8) + (B_KC ? 0 : 8);     // 16-byte register loads per step (transposed operand)
-  constexpr int NDMA = (A_KC ? 8 : 0) + (B_KC ? 8 : 0);    // direct copies per wave and step
+  constexpr int NG = TM + TN;                              // fragments (scheduling groups) per k-step
+  constexpr int RPG_A = (A_KC || !kBf16) ? 1 : 2, RPG_B = (B_KC || !kBf16) ? 1 : 2;   // LDS reads per fragment
+  constexpr int NMC = (A_DMA ? 0 : 8) + (B_DMA ? 0 : 8);   // 16-byte register loads per step (fp32 transposed operand)
+  constexpr int NDMA = (A_DMA ? 8 : 0) + (B_DMA ? 8 : 0);  // direct copies per wave and step
+  // interleaving hint for one k-step: per fragment its LDS reads, then `vm` memory instructions of
+  // class `vmask`, then its share of the MFMAs
+  auto sched_kstep = [&](auto vmask_c, auto vm_c) __attribute__((always_inline)) {
+    constexpr int vmask = decltype(vmask_c)::value, vm = decltype(vm_c)::value;
+#pragma unroll
+    for (int s = 0; s < TM; ++s) {
+      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, RPG_A, 0);
+      if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(vmask, vm, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NG, 0);
+    }
+#pragma unroll
+    for (int s = 0; s < TN; ++s) {
+      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, RPG_B, 0);
+      if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(vmask, vm, 0);
+      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NG, 0);
+    }
+  };
+  using IC0 = std::integral_constant<int, 0>;
 
   auto step = [&](char *cur, char *nxt, int kt) __attribute__((always_inline)) {
-    // k-step 0 (a transposed operand's loads of the next tile are issued here and written in k-step 2)
-    f1.read(cur + a_row, cur + b_row, koff[1]);
-    if constexpr (!A_KC) la.issue(k_of(kt + 1));
-    if constexpr (!B_KC) lb.issue(k_of(kt + 1));
+    // k-step 0 (an fp32 transposed operand's loads of the next tile are issued here and written in k-step 2)
+    read_frags(f1, cur, 1);
+    if constexpr (!A_DMA) la.issue(k_of(kt + 1));
+    if constexpr (!B_DMA) lb.issue(k_of(kt + 1));
     mma<T, TM, TN>(acc, f0);
-#pragma unroll
-    for (int s = 0; s < NR; ++s) {
-      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-      if constexpr (NMC > 0) __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, NMC / NR, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
-    }
+    sched_kstep(std::integral_constant<int, SG_VMEM_READ>{}, std::integral_constant<int, NMC / NG>{});
     // k-step 1
-    f0.read(cur + a_row, cur + b_row, koff[2]);
+    read_frags(f0, cur, 2);
     mma<T, TM, TN>(acc, f1);
-    sched_reads_mfma<NR, 1, NM / NR>();
+    sched_kstep(IC0{}, IC0{});
     // k-step 2
-    f1.read(cur + a_row, cur + b_row, koff[3]);
+    read_frags(f1, cur, 3);
     mma<T, TM, TN>(acc, f0);
-    sched_reads_mfma<NR, 1, NM / NR>();
+    sched_kstep(IC0{}, IC0{});
     __builtin_amdgcn_sched_barrier(0);
-    if constexpr (!A_KC) la.store(nxt);
-    if constexpr (!B_KC) lb.store(nxt + A_BYTES);
+    if constexpr (!A_DMA) la.store(nxt);
+    if constexpr (!B_DMA) lb.store(nxt + A_BYTES);
     // A wave's own copies must have landed before it tells the others so: the counter of the vector
     // memory pipeline (which also tracks copies to LDS) has to be zero ahead of the barrier.
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
@@ -837,16 +948,11 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
     __builtin_amdgcn_sched_barrier(0);
     // k-step 3, overlapped with the first fragment reads of the next stage and with the issue of the
     // copies of the tile after the next (their target, `cur`, is free from here on)
-    if constexpr (A_KC) la.issue(k_of(kt + 2), cur);
-    if constexpr (B_KC) lb.issue(k_of(kt + 2), cur + A_BYTES);
-    f0.read(nxt + a_row, nxt + b_row, koff[0]);
+    if constexpr (A_DMA) la.issue(k_of(kt + 2), cur);
+    if constexpr (B_DMA) lb.issue(k_of(kt + 2), cur + A_BYTES);
+    read_frags(f0, nxt, 0);
     mma<T, TM, TN>(acc, f1);
-#pragma unroll
-    for (int s = 0; s < NR; ++s) {
-      __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_VMEM, NDMA / NR, 0);
-      __builtin_amdgcn_sched_group_barrier(SG_MFMA, NM / NR, 0);
-    }
+    sched_kstep(std::integral_constant<int, SG_VMEM>{}, std::integral_constant<int, NDMA / NG>{});
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -882,8 +988,11 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
 }
 
 template <typename T, bool A_KC, bool B_KC>
+constexpr bool kHasDmaKernel = A_KC || B_KC || sizeof(T) == 2;
+
+template <typename T, bool A_KC, bool B_KC>
 chn_status launch_dma(const GemmArgs &g, hipStream_t st) {
-  if constexpr (A_KC || B_KC) {
+  if constexpr (kHasDmaKernel<T, A_KC, B_KC>) {
     hipLaunchKernelGGL((gemm_kernel_dma<T, A_KC, B_KC>), dim3((unsigned)(g.tiles_m * g.tiles_n * g.splits)), dim3(256), 0, st, g);
     CHN_TRY(check_launch("gemm (direct-to-LDS)"));
     if (g.splits > 1) {
@@ -931,7 +1040,7 @@ chn_status launch_tile(const GemmArgs &g, hipStream_t st) {
 template <typename T, bool A_KC, bool B_KC>
 chn_status launch_layout(GemmArgs &g, hipStream_t st) {
   if ((int64_t)g.tiles_m * g.tiles_n * g.splits > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
-  if constexpr (A_KC || B_KC) {
+  if constexpr (kHasDmaKernel<T, A_KC, B_KC>) {
     if (g.tile == 2 && g.piece == 16 && g.dma) return launch_dma<T, A_KC, B_KC>(g, st);
   }
   if (g.tile == 2) return launch_tile<T, 4, 4, A_KC, B_KC>(g, st);
