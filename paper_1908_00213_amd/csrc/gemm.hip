@@ -169,13 +169,12 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     else plan(&g, isz, false);
   }
   {
-    // The direct-copy 256x256 kernel handles whole tile steps of K, 16-byte pieces and 32-bit offsets
-    // inside a tile; fp32 needs at least one K-contiguous operand for it.  (CHN_GEMM_DMA=0 switches
-    // it off: a tuning aid.)
+    // The direct-copy 256x256 kernel needs 16-byte pieces (so K is a multiple of the chunk length for
+    // K-contiguous operands) and 32-bit offsets inside a tile; fp32 needs at least one K-contiguous
+    // operand for it.  (CHN_GEMM_DMA=0 switches it off: a tuning aid.)
     static const bool dma_on = [] { const char *e = getenv("CHN_GEMM_DMA"); return !e || atoi(e) != 0; }();
-    const int bk = 128 / isz;
     const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
-    g.dma = dma_on && K > 0 && K % bk == 0 && g.lda < max_ld && g.ldb < max_ld && (A->dtype == CHN_BF16 || a_kc || b_kc);
+    g.dma = dma_on && K > 0 && g.lda < max_ld && g.ldb < max_ld && (A->dtype == CHN_BF16 || a_kc || b_kc);
   }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {

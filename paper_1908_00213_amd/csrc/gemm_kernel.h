@@ -39,9 +39,6 @@
 namespace chn {
 namespace gemm {
 
-#ifndef CHN_EPI_U
-#define CHN_EPI_U 4
-#endif
 #ifndef CHN_TOUCH
 #define CHN_TOUCH 1
 #endif
@@ -372,18 +369,41 @@ __device__ __forceinline__ void finish1(const GemmArgs &g, int row, int col, flo
   store1(g.C, ci, g.c_bf16, x);
 }
 
-// Same as finish4 with the epilogue kind fixed at compile time (the tile kernels pick the kind once
-// per pass, outside their loops).
-template <int EPI>
-__device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, const f32x4 a, const EpiIn &in) {
-  Vec4 b, x, pre;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) b.v[e] = 0.0f;
-  if constexpr (EPI >= CHN_EPI_BIAS && EPI <= CHN_EPI_BIAS_GELU) b = load4v(g.bias, col, 0);
+// Four elements of C's dtype as they come from memory; converted only where they are used, so that
+// issuing the load does not tie the wave to its arrival.
+template <bool CB> struct Raw4 { typedef f32x4 type; };
+template <> struct Raw4<true> { typedef u32x2 type; };
+template <bool CB>
+__device__ __forceinline__ typename Raw4<CB>::type load4raw(const void *p, int64_t idx) {
+  if constexpr (CB) return global_load<u32x2>(reinterpret_cast<uintptr_t>(static_cast<const bf16_raw *>(p) + idx));
+  else return global_load<f32x4>(reinterpret_cast<uintptr_t>(static_cast<const float *>(p) + idx));
+}
+__device__ __forceinline__ Vec4 cvt4(const u32x2 w) {
+  Vec4 r;
+  r.v[0] = __uint_as_float(w[0] << 16); r.v[1] = __uint_as_float(w[0] & 0xffff0000u);
+  r.v[2] = __uint_as_float(w[1] << 16); r.v[3] = __uint_as_float(w[1] & 0xffff0000u);
+  return r;
+}
+__device__ __forceinline__ Vec4 cvt4(const f32x4 w) {
+  Vec4 r;
+  r.v[0] = w[0]; r.v[1] = w[1]; r.v[2] = w[2]; r.v[3] = w[3];
+  return r;
+}
+template <bool CB> struct EpiRaw { typename Raw4<CB>::type c0, aux; };
+
+// Same as finish4 with the epilogue kind, C's dtype (CB: bf16) and whether old C is added (BETA) fixed
+// at compile time (the tile kernels pick them once per pass, outside their loops, which are then free
+// of branches).
+template <int EPI, bool CB, bool BETA>
+__device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, const f32x4 a, const EpiRaw<CB> &raw, const Vec4 &b) {
+  Vec4 x, pre;
+  EpiIn in;
+  if constexpr (BETA) in.c0 = cvt4(raw.c0);
+  if constexpr (EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD) in.aux = cvt4(raw.aux);
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     float t = g.alpha * a[e];
-    if (g.beta != 0.0f) t += g.beta * in.c0.v[e];
+    if constexpr (BETA) t += g.beta * in.c0.v[e];
     t += b.v[e];
     pre.v[e] = t;
     if constexpr (EPI == CHN_EPI_BIAS_RELU) t = fmaxf(t, 0.0f);
@@ -393,9 +413,9 @@ __device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, c
     x.v[e] = t;
   }
   if constexpr (EPI == CHN_EPI_BIAS_GELU) {
-    if (g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+    if (g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, CB, pre);
   }
-  store4v(g.C, (int64_t)row * g.ldc + col, g.c_bf16, x);
+  store4v(g.C, (int64_t)row * g.ldc + col, CB, x);
 }
 
 // Where the accumulators of one wave wait in LDS between the MFMA register layout and the row-major
@@ -416,31 +436,51 @@ struct StageLayout {
 // range and all accesses aligned, so that the loop is free of per-lane conditions.  Lane l handles
 // four consecutive columns; the LDS reads and the dependent global reads (old C, aux) of U row
 // segments are in flight together.
-template <int EPI, int TN, int RP>
+template <int EPI, bool CB, bool BETA, int TN, int RP>
 __device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float *stage, int row0, int col0, int lane) {
   using L = StageLayout<TN>;
-  constexpr int CPR = L::W / 4, NIT = RP * CPR / 64, U = CHN_EPI_U;
-  static_assert(NIT % U == 0, "row segments per lane must come in whole batches");
+  constexpr int CPR = L::W / 4, RPI = 64 / CPR;            // 16-byte chunks per row, rows per wave-wide access
+  constexpr int NIT = RP / RPI, U = NIT >= 8 ? 4 : NIT / 2;
   constexpr bool kAux = EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD;
-#pragma unroll 1
-  for (int base = 0; base < NIT; base += U) {
-    EpiIn in[U];
+  // a lane keeps its four columns for the whole pass and walks down the rows
+  const int cl = (lane % CPR) * 4, col = col0 + cl, rl0 = lane / CPR;
+  Vec4 bias;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) bias.v[e] = 0.0f;
+  if constexpr (EPI >= CHN_EPI_BIAS && EPI <= CHN_EPI_BIAS_GELU) bias = load4v(g.bias, col, 0);
+  // The global reads of the next batch are issued before the current one is worked on, so that only
+  // the first batch's memory latency is exposed (a wave has its SIMD to itself here: nobody else would
+  // hide it).
+  auto fetch = [&](EpiRaw<CB> (&in)[U], int base) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = row0 + rl0 + (base + u) * RPI;
+      if constexpr (BETA) in[u].c0 = load4raw<CB>(g.C, (int64_t)row * g.ldc + col);
+      if constexpr (kAux) in[u].aux = load4raw<CB>(g.aux, (int64_t)row * g.ldaux + col);
+    }
+  };
+  auto compute = [&](const EpiRaw<CB> (&in)[U], int base) __attribute__((always_inline)) {
     f32x4 a[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int c = lane + (base + u) * 64;
-      const int rl = c / CPR, cl = (c % CPR) * 4;
-      a[u] = *reinterpret_cast<const f32x4 *>(stage + L::at(rl, cl));
+    for (int u = 0; u < U; ++u) a[u] = *reinterpret_cast<const f32x4 *>(stage + L::at(rl0 + (base + u) * RPI, cl));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) in[u].c0.v[e] = in[u].aux.v[e] = 0.0f;
-      if (g.beta != 0.0f) in[u].c0 = load4v(g.C, (int64_t)(row0 + rl) * g.ldc + col0 + cl, g.c_bf16);
-      if constexpr (kAux) in[u].aux = load4v(g.aux, (int64_t)(row0 + rl) * g.ldaux + col0 + cl, g.c_bf16);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int c = lane + (base + u) * 64;
-      finish4_t<EPI>(g, row0 + c / CPR, col0 + (c % CPR) * 4, a[u], in[u]);
-    }
+    for (int u = 0; u < U; ++u) finish4_t<EPI, CB, BETA>(g, row0 + rl0 + (base + u) * RPI, col, a[u], in[u], bias);
+  };
+  // Two register sets take turns (the last iteration fetches its own batch once more rather than
+  // branch); the scheduling fences keep the compiler from moving the reads back next to their use.
+  static_assert(NIT % (2 * U) == 0, "batches come in pairs");
+  EpiRaw<CB> ea[U], eb[U];
+  fetch(ea, 0);
+#pragma unroll 1
+  for (int base = 0; base < NIT; base += 2 * U) {
+    fetch(eb, base + U);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(ea, base);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(ea, min(base + 2 * U, NIT - U));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(eb, base + U);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -459,13 +499,23 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
                             *reinterpret_cast<const f32x4 *>(stage + L::at(rl, cl)));
     }
   } else if (g.epi_vec && col0 + W <= g.N && row0 + RP <= g.M) {
+    auto run = [&](auto epi_c) __attribute__((always_inline)) {
+      constexpr int EPI = decltype(epi_c)::value;
+      if (g.beta != 0.0f) {
+        if (g.c_bf16) epilogue_pass_vec<EPI, true, true, TN, RP>(g, stage, row0, col0, lane);
+        else epilogue_pass_vec<EPI, false, true, TN, RP>(g, stage, row0, col0, lane);
+      } else {
+        if (g.c_bf16) epilogue_pass_vec<EPI, true, false, TN, RP>(g, stage, row0, col0, lane);
+        else epilogue_pass_vec<EPI, false, false, TN, RP>(g, stage, row0, col0, lane);
+      }
+    };
     switch (g.epi) {
-      case CHN_EPI_NONE: epilogue_pass_vec<CHN_EPI_NONE, TN, RP>(g, stage, row0, col0, lane); break;
-      case CHN_EPI_BIAS: epilogue_pass_vec<CHN_EPI_BIAS, TN, RP>(g, stage, row0, col0, lane); break;
-      case CHN_EPI_BIAS_RELU: epilogue_pass_vec<CHN_EPI_BIAS_RELU, TN, RP>(g, stage, row0, col0, lane); break;
-      case CHN_EPI_BIAS_GELU: epilogue_pass_vec<CHN_EPI_BIAS_GELU, TN, RP>(g, stage, row0, col0, lane); break;
-      case CHN_EPI_RELU_BWD: epilogue_pass_vec<CHN_EPI_RELU_BWD, TN, RP>(g, stage, row0, col0, lane); break;
-      default: epilogue_pass_vec<CHN_EPI_GELU_BWD, TN, RP>(g, stage, row0, col0, lane); break;
+      case CHN_EPI_NONE: run(std::integral_constant<int, CHN_EPI_NONE>{}); break;
+      case CHN_EPI_BIAS: run(std::integral_constant<int, CHN_EPI_BIAS>{}); break;
+      case CHN_EPI_BIAS_RELU: run(std::integral_constant<int, CHN_EPI_BIAS_RELU>{}); break;
+      case CHN_EPI_BIAS_GELU: run(std::integral_constant<int, CHN_EPI_BIAS_GELU>{}); break;
+      case CHN_EPI_RELU_BWD: run(std::integral_constant<int, CHN_EPI_RELU_BWD>{}); break;
+      default: run(std::integral_constant<int, CHN_EPI_GELU_BWD>{}); break;
     }
   } else {                                                    // ragged right edge or unaligned views: one element at a time
 #pragma unroll 1
@@ -676,18 +726,20 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 // the copy may be in flight for a whole tile step.  One such instruction writes the 64 lanes' chunks
 // to 1024 consecutive LDS bytes (8 tile rows), so the swizzle is applied on the global side: the
 // lane that fills physical slot (row p, chunk c) fetches the logical chunk that lives there.
-template <typename T, int ROWS>
+template <typename T, int ROWS, bool RAGGED>
 struct DmaLoader {
   static constexpr int EPC = Traits<T>::EPC;
   static constexpr int BK = 128 / (int)sizeof(T);
   static constexpr int NS = ROWS / 32;     // instructions per wave and tile
   const char *tile;                        // wave-uniform: first row of the tile, k = 0
   uint32_t off[NS];                        // byte offset of the slot's chunk from `tile`
+  int lim[RAGGED ? NS : 1];                // RAGGED: K - (k offset of the slot's chunk)
   int wave, k_last;                        // wave-uniform
 
-  // K is a positive multiple of BK (the host only picks this kernel then), so a chunk is never
-  // partly valid along k.  Rows past the operand's end are read from its last row instead: they only
-  // feed rows or columns of C that are never written.
+  // K is a multiple of the chunk length (16-byte pieces), so a chunk is never partly valid along k.
+  // Without RAGGED, K is also a multiple of BK and every chunk of every tile exists; with it, chunks at
+  // or past K are fetched from the zero chunk.  Rows past the operand's end are read from its last row
+  // instead: they only feed rows or columns of C that are never written.
   __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K) {
     wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     k_last = K - BK;
@@ -701,18 +753,23 @@ struct DmaLoader {
       const int kc = (pchunk ^ ((row >> 1) & 7)) * EPC;
       const int rowc = min(row, rows_total - 1 - row0);
       off[i] = (uint32_t)(((int64_t)rowc * ld + kc) * (int64_t)sizeof(T));
+      if constexpr (RAGGED) lim[i] = K - kc;
     }
   }
 
   // Start the copy of the tile whose first k is k0 into the operand's part of a stage.  Tiles past
-  // the end of K (requested by the last steps, never used) re-read the last tile.
+  // the end of K (requested by the last steps, never used) re-read the last tile or read zeros.
   __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
-    const char *p = tile + (int64_t)min(k0, k_last) * (int64_t)sizeof(T);
+    const char *p = tile + (int64_t)(RAGGED ? k0 : min(k0, k_last)) * (int64_t)sizeof(T);
+    const char *zero = reinterpret_cast<const char *>(&kZeroChunk);
 #pragma unroll
-    for (int i = 0; i < NS; ++i)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + off[i]),
+    for (int i = 0; i < NS; ++i) {
+      const char *a = p + off[i];
+      if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
                                        (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
                                        16, 0, 0);
+    }
   }
 };
 
@@ -720,12 +777,13 @@ struct DmaLoader {
 // memory, BK rows of k, each ROWS elements (512 bytes) of m, and is transposed on the way out of LDS
 // by the 16-bit transposing read (see TrReader).  The eight 64-byte blocks of a k-row are XORed with
 // k % 8, so that the four k-rows one group of lanes reads together sit in different banks.
-template <int ROWS>
+template <int ROWS, bool RAGGED>
 struct DmaLoaderMC {
   static_assert(ROWS == 256, "one k-row must be 512 bytes");
   static constexpr int BK = 64, NS = BK * 512 / 1024 / 4;   // instructions per wave and tile
   const char *tile;                        // wave-uniform: element (k = 0, m = row0)
   uint32_t off[NS];
+  int lim[RAGGED ? NS : 1];                // RAGGED: K - (k-row of the slot)
   int wave, k_last;
   int64_t kbytes;                          // bytes between consecutive k
 
@@ -744,16 +802,21 @@ struct DmaLoaderMC {
       const int m = (((p >> 2) ^ (k & 7)) * 32) + (p & 3) * 8; // the 8 elements that live in that slot
       const int mc = min(m, rows_total - 8 - row0);
       off[i] = (uint32_t)(((int64_t)k * ld + mc) * 2);
+      if constexpr (RAGGED) lim[i] = K - k;
     }
   }
 
   __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
-    const char *p = tile + (int64_t)min(k0, k_last) * kbytes;
+    const char *p = tile + (int64_t)(RAGGED ? k0 : min(k0, k_last)) * kbytes;
+    const char *zero = reinterpret_cast<const char *>(&kZeroChunk);
 #pragma unroll
-    for (int i = 0; i < NS; ++i)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + off[i]),
+    for (int i = 0; i < NS; ++i) {
+      const char *a = p + off[i];
+      if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;   // k-rows at or past K read as zeros
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
                                        (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
                                        16, 0, 0);
+    }
   }
 };
 
@@ -833,7 +896,7 @@ __device__ uint64_t g_ts[16];
 #else
 #define CHN_TS(i) do {} while (0)
 #endif
-template <typename T, bool A_KC, bool B_KC>
+template <typename T, bool A_KC, bool B_KC, bool RAGGED>
 __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   CHN_TS(0);
   // How each operand reaches LDS: K-contiguous -> direct copy, K-packed; bf16 M/N-contiguous -> direct
@@ -852,8 +915,8 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   const TilePos tp = tile_pos(g);
   const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
 
-  std::conditional_t<A_KC, DmaLoader<T, BM>, std::conditional_t<kBf16, DmaLoaderMC<BM>, TileLoader<T, BM, false, 16>>> la;
-  std::conditional_t<B_KC, DmaLoader<T, BN>, std::conditional_t<kBf16, DmaLoaderMC<BN>, TileLoader<T, BN, false, 16>>> lb;
+  std::conditional_t<A_KC, DmaLoader<T, BM, RAGGED>, std::conditional_t<kBf16, DmaLoaderMC<BM, RAGGED>, TileLoader<T, BM, false, 16>>> la;
+  std::conditional_t<B_KC, DmaLoader<T, BN, RAGGED>, std::conditional_t<kBf16, DmaLoaderMC<BN, RAGGED>, TileLoader<T, BN, false, 16>>> lb;
   la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
   lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
 
@@ -993,7 +1056,9 @@ constexpr bool kHasDmaKernel = A_KC || B_KC || sizeof(T) == 2;
 template <typename T, bool A_KC, bool B_KC>
 chn_status launch_dma(const GemmArgs &g, hipStream_t st) {
   if constexpr (kHasDmaKernel<T, A_KC, B_KC>) {
-    hipLaunchKernelGGL((gemm_kernel_dma<T, A_KC, B_KC>), dim3((unsigned)(g.tiles_m * g.tiles_n * g.splits)), dim3(256), 0, st, g);
+    const dim3 grid((unsigned)(g.tiles_m * g.tiles_n * g.splits));
+    if (g.K % (128 / (int)sizeof(T)) == 0) hipLaunchKernelGGL((gemm_kernel_dma<T, A_KC, B_KC, false>), grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((gemm_kernel_dma<T, A_KC, B_KC, true>), grid, dim3(256), 0, st, g);
     CHN_TRY(check_launch("gemm (direct-to-LDS)"));
     if (g.splits > 1) {
       const int64_t n = (int64_t)g.M * (g.ldp / 4);

@@ -72,11 +72,11 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-@pytest.mark.parametrize("shape", [(3704, 3592, 192), (2008, 2104, 64), (520, 4104, 448)])
-def test_gemm_big_tiles_whole_k_steps(dt, layout, shape):
-    # K a multiple of the tile step and every unit-stride extent a multiple of 16 bytes: the 256x256
-    # kernel that copies its K-contiguous operands straight into LDS; an odd and an even number of
-    # tile steps, a single one, ragged last tiles in M and N
+@pytest.mark.parametrize("shape", [(3704, 3592, 192), (2008, 2104, 64), (520, 4104, 448), (3704, 3592, 200), (1032, 4104, 1000)])
+def test_gemm_big_tiles_direct_copy(dt, layout, shape):
+    # every unit-stride extent a multiple of 16 bytes: the 256x256 kernel that copies its operands
+    # straight into LDS; an odd and an even number of tile steps, a single one, K with and without a
+    # ragged last step, ragged last tiles in M and N
     M, N, K = shape
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gen)
@@ -85,6 +85,15 @@ def test_gemm_big_tiles_whole_k_steps(dt, layout, shape):
     rows = RNG.integers(0, M, 24)
     assert np.array_equal(O.gemm(A[rows], Bm), ref[rows])
     assert np.array_equal(out, ref)
+
+
+def test_gemm_direct_copy_odd_k_both_transposed():
+    # with both operands stored along M / N, K itself needs no alignment for the direct-copy kernel
+    M, N, K = 2056, 2312, 203
+    gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, "tn", "bf16", gen)
+    out = host(B.gemm(Ad, Bd, empty((M, N))))
+    assert np.array_equal(out, A.astype(np.float64) @ Bm.astype(np.float64))
 
 
 def test_gemm_identity_and_ones():
