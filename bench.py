@@ -22,6 +22,10 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# HBM-side bytes per launch of the dominant kernel (L2 misses fetched + bytes written), from the two
+# counter runs recorded in profiles/gemm_bf16_forward_8192x4096x4096_hbm_traffic.txt (made with
+# `bench.py --traffic-driver` under rocprofv3 --pmc); 403.2 MB fetched + 134.2 MB written.
+DOMINANT_KERNEL_TRAFFIC_BYTES = 537.4e6
 
 
 def log(*a):
@@ -188,6 +192,31 @@ def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False):
             "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
 
 
+def traffic_driver(torch, B, W):
+    """What `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` are pointed at: three rounds of a 256 MiB
+    fp32 copy through chn_elementwise_broadcast (the calibration launch: reads and writes exactly
+    268435456 bytes), a 256 MiB scratch add that flushes the caches, and the dominant launch of the
+    headline workload: one hidden layer's forward product x @ W.T + b with the GELU epilogue that also
+    writes the pre-activation (M=8192, N=4096, K=4096, bf16 in / bf16 out)."""
+    w = W.config5(n_batches=1)
+    bf = torch.bfloat16
+    x = torch.from_numpy(W.bf16_exact(w.xs[0])).cuda().to(bf)
+    Wm = torch.from_numpy(W.bf16_exact(w.params[0][0])).cuda().to(bf)
+    bias = torch.from_numpy(w.params[0][1]).cuda()
+    out = torch.empty((w.batch, Wm.shape[0]), device="cuda", dtype=bf)
+    pre = torch.empty_like(out)
+    src = torch.zeros(64 * 1024 * 1024, device="cuda", dtype=torch.float32)
+    dst = torch.empty_like(src)
+    scratch = torch.zeros(64 * 1024 * 1024, device="cuda", dtype=torch.float32)
+    for _ in range(3):
+        B.elementwise_broadcast("copy", [src], dst)
+        scratch.add_(1.0)
+        B.gemm(x, Wm.t(), out, epilogue="bias_gelu", bias=bias, preact_out=pre)
+        scratch.add_(1.0)
+    torch.cuda.synchronize()
+    log("traffic driver: 3 x (copy 256 MiB, flush, forward GEMM 8192x4096x4096 with bias+GELU epilogue, flush) done")
+
+
 def cpu_baseline(W, rows=128):
     """The CPU oracle, as it stands, on a bounded sample of the headline workload: `rows` of the 8192
     batch rows through the full-width network (forward + backward + SGD), scaled to steps/s."""
@@ -212,6 +241,8 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--workloads", default="1,2,3,4", help="which of the secondary workloads to run (comma list)")
+    ap.add_argument("--traffic-driver", action="store_true",
+                    help="run only the calibration copy + dominant GEMM launches (for rocprofv3 --pmc) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -226,6 +257,9 @@ def main():
     torch.cuda.set_device(0)
     timer = Timer(torch)
     extra = {}
+    if args.traffic_driver:
+        traffic_driver(torch, B, W)
+        return
 
     # ---- headline: workload 5, wide MLP, bf16 storage / fp32 accumulate
     log("workload 5: wide MLP 4096-4096-4096-4096-1000, GELU, batch 8192, bf16/fp32-accumulate")
@@ -240,9 +274,10 @@ def main():
     dom = [c for c in r5["gemm_calls"] if c["call"] in ("fwd0", "fwd1", "fwd2")]
     dom_s = sum(c["us"] for c in dom) * 1e-6 / len(dom)
     dom_flops = 2.0 * dom[0]["M"] * dom[0]["N"] * dom[0]["K"]
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel<bf16, 256x256 tile, A and B unit-stride along K> (forward x @ W.T, M=8192 N=4096 K=4096)",
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel_dma<bf16, A and B unit-stride along K> (256x256 tile, direct global-to-LDS copies; "
+                                           "hidden-layer forward x @ W.T + b with GELU, M=8192 N=4096 K=4096)",
                 "achieved": dom_flops / dom_s / 1e12, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
-                "frac": dom_flops / dom_s / 1e12 / MFMA_PEAK_TFLOPS["bf16"], "traffic": None,
+                "frac": dom_flops / dom_s / 1e12 / MFMA_PEAK_TFLOPS["bf16"], "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES,
                 "avg_launch_us": dom_s * 1e6, "flops_per_launch": dom_flops,
                 "all_gemms_achieved": r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12}
     extra["cfg5_wide_mlp_bf16"] = r5
