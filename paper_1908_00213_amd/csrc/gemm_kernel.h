@@ -759,11 +759,12 @@ struct DmaLoader {
 
   // Start the copy of the tile whose first k is k0 into the operand's part of a stage.  Tiles past
   // the end of K (requested by the last steps, never used) re-read the last tile or read zeros.
+  template <int FIRST = 0, int COUNT = NS>
   __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
     const char *p = tile + (int64_t)(RAGGED ? k0 : min(k0, k_last)) * (int64_t)sizeof(T);
     const char *zero = reinterpret_cast<const char *>(&kZeroChunk);
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
+    for (int i = FIRST; i < FIRST + COUNT; ++i) {
       const char *a = p + off[i];
       if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
@@ -806,11 +807,12 @@ struct DmaLoaderMC {
     }
   }
 
+  template <int FIRST = 0, int COUNT = NS>
   __device__ __forceinline__ void issue(int k0, char *lds_operand) const {
     const char *p = tile + (int64_t)(RAGGED ? k0 : min(k0, k_last)) * kbytes;
     const char *zero = reinterpret_cast<const char *>(&kZeroChunk);
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
+    for (int i = FIRST; i < FIRST + COUNT; ++i) {
       const char *a = p + off[i];
       if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;   // k-rows at or past K read as zeros
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
@@ -953,8 +955,10 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   // prologue: first tile into stage 0, second tile on its way into stage 1
   if constexpr (A_DMA) { la.issue(k_of(kt0), stage0); la.issue(k_of(kt0 + 1), stage1); }
   else { la.issue(k_of(kt0)); la.store(stage0); }
-  if constexpr (B_DMA) { lb.issue(k_of(kt0), stage0 + A_BYTES); lb.issue(k_of(kt0 + 1), stage1 + A_BYTES); }
-  else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
+  if constexpr (B_DMA) {
+    lb.issue(k_of(kt0), stage0 + A_BYTES);
+    if constexpr (!(A_DMA && B_DMA)) lb.issue(k_of(kt0 + 1), stage1 + A_BYTES);   // (else: in the first step's k-step 0)
+  } else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
   CHN_TS(1);
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
@@ -986,13 +990,20 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   };
   using IC0 = std::integral_constant<int, 0>;
 
+  // B's copy runs half a step behind A's when both are direct (SPLIT): the copy instructions of a tile
+  // are then spread over two k-steps instead of crowding the MFMAs of one.
+  constexpr bool SPLIT = A_DMA && B_DMA;
   auto step = [&](char *cur, char *nxt, int kt) __attribute__((always_inline)) {
-    // k-step 0 (an fp32 transposed operand's loads of the next tile are issued here and written in k-step 2)
+    // k-step 0 (an fp32 transposed operand's loads of the next tile are issued here and written in
+    // k-step 2; with SPLIT, B's copy of the next tile starts here: `nxt` has been free since the
+    // previous step's barrier)
     read_frags(f1, cur, 1);
     if constexpr (!A_DMA) la.issue(k_of(kt + 1));
     if constexpr (!B_DMA) lb.issue(k_of(kt + 1));
+    if constexpr (SPLIT) lb.issue(k_of(kt + 1), nxt + A_BYTES);
     mma<T, TM, TN>(acc, f0);
-    sched_kstep(std::integral_constant<int, SG_VMEM_READ>{}, std::integral_constant<int, NMC / NG>{});
+    if constexpr (SPLIT) sched_kstep(std::integral_constant<int, SG_VMEM>{}, std::integral_constant<int, 8 / NG>{});
+    else sched_kstep(std::integral_constant<int, SG_VMEM_READ>{}, std::integral_constant<int, NMC / NG>{});
     // k-step 1
     read_frags(f0, cur, 2);
     mma<T, TM, TN>(acc, f1);
@@ -1012,10 +1023,10 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
     // k-step 3, overlapped with the first fragment reads of the next stage and with the issue of the
     // copies of the tile after the next (their target, `cur`, is free from here on)
     if constexpr (A_DMA) la.issue(k_of(kt + 2), cur);
-    if constexpr (B_DMA) lb.issue(k_of(kt + 2), cur + A_BYTES);
+    if constexpr (B_DMA && !SPLIT) lb.issue(k_of(kt + 2), cur + A_BYTES);
     read_frags(f0, nxt, 0);
     mma<T, TM, TN>(acc, f1);
-    sched_kstep(std::integral_constant<int, SG_VMEM>{}, std::integral_constant<int, NDMA / NG>{});
+    sched_kstep(std::integral_constant<int, SG_VMEM>{}, std::integral_constant<int, (SPLIT ? 8 : NDMA) / NG>{});
     __builtin_amdgcn_sched_barrier(0);
   };
 
