@@ -14,6 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchn.so")
+TOOL = os.path.join(HERE, "mfma_ceiling")
 
 SOURCES = ["host.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "softmax_ce.hip",
            "sgd.hip", "embed.hip"]
@@ -79,6 +80,11 @@ def build(force=False, verbose=False, extra=()):
     if force or _stale(LIB, objs):
         cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
         subprocess.run(cmd, check=True)
+    # measurement aid: what the matrix cores sustain (a stand-alone program, see its header)
+    tool_src = os.path.join(CSRC, "mfma_ceiling.hip")
+    if force or _stale(TOOL, [tool_src]):
+        subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-Wno-unused-command-line-argument", tool_src, "-o", TOOL],
+                       check=True, capture_output=not verbose)
     return LIB
 
 
