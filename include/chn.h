@@ -217,6 +217,10 @@ int chn_version(void);
  * Returns a small integer code (>= 0) or a negative chn_status.  Element-wise families:
  * 0 flat contiguous/row-broadcast, 1 pitched rows, 2 tile-transposed, 3 general strided. */
 int chn_elementwise_plan(int op, int n_in, const chn_array *const *in, const chn_array *out);
+/* The same for chn_gemm: bits 0-1 macro tile (0: 64x64, 1: 128x128, 2: 256x256), bit 2 set when the
+ * 256x256 kernel that copies operand tiles straight from global memory into LDS is taken, bits 4 and
+ * up the number of K splits (1 = none; have_workspace = 0 plans as chn_gemm does without workspace). */
+int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace);
 
 #ifdef __cplusplus
 }

@@ -29,7 +29,7 @@ EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_embed_fwd", "chn_embed_bwd",
-           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan"]
+           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan"]
 
 
 class ChnArray(C.Structure):
@@ -65,6 +65,7 @@ def lib():
     L.chn_reduce_axis.argtypes = [C.c_int, AP, C.c_int, C.c_int, AP, vp, C.c_size_t, st]
     L.chn_gemm_workspace_bytes.argtypes = [AP, AP, AP]
     L.chn_gemm_workspace_bytes.restype = C.c_size_t
+    L.chn_gemm_plan.argtypes = [AP, AP, AP, C.c_int]
     L.chn_gemm.argtypes = [AP, AP, AP, C.c_float, C.c_float, C.c_int, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_lstm_fwd.argtypes = [AP, AP, AP, AP, AP, AP, st]
     L.chn_lstm_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, st]
@@ -83,7 +84,7 @@ def lib():
     L.chn_version.argtypes = []
     for name in EXPORTS:
         fn = getattr(L, name)
-        if fn.restype is C.c_int and name not in ("chn_version", "chn_elementwise_plan"):
+        if fn.restype is C.c_int and name not in ("chn_version", "chn_elementwise_plan", "chn_gemm_plan"):
             fn.restype = C.c_int32
     _lib = L
     return L
@@ -179,6 +180,14 @@ def reduce_axis(op, x, axis, out, keepdims=False, ws=None, stream=None):
 
 def gemm_workspace_bytes(A, B, Cm):
     return lib().chn_gemm_workspace_bytes(_ref(desc(A)), _ref(desc(B)), _ref(desc(Cm)))
+
+
+def gemm_plan(A, B, Cm, have_workspace=False):
+    """(tile, direct_copy, splits) chn_gemm would use: tile 0/1/2 = 64/128/256 square."""
+    code = lib().chn_gemm_plan(_ref(desc(A)), _ref(desc(B)), _ref(desc(Cm)), 1 if have_workspace else 0)
+    if code < 0:
+        _check(code)
+    return code & 3, bool(code & 4), code >> 4
 
 
 def gemm(A, B, Cm, alpha=1.0, beta=0.0, epilogue="none", bias=None, aux=None, preact_out=None,

@@ -52,17 +52,34 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
   return CHN_OK;
 }
 
-// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model.
-// Every compute unit is taken to work through its share of the blocks one after another at a
-// measured fraction of its MFMA peak that depends on the tile (large tiles re-use LDS fragments
-// more); a problem with too few tiles to occupy 256 compute units but a long K is cut along K: every
-// split writes fp32 partial sums to the workspace and a second kernel adds them in a fixed order and
-// runs the epilogue (its traffic and launch are charged to the split candidates).
-void plan(GemmArgs *g, int isz, bool allow_split) {
-  static const double eff_f32[3] = {0.45, 0.78, 0.88}, eff_bf16[3] = {0.07, 0.25, 0.40};
-  const double cu_peak = (isz == 2 ? 2500e12 : 157.3e12) / 256.0;
-  const double *eff = isz == 2 ? eff_bf16 : eff_f32;
+// Whether the direct-copy 256x256 kernel can take the product: it needs 16-byte pieces (so K is a
+// multiple of the chunk length for K-contiguous operands) and 32-bit offsets inside a tile; fp32 needs
+// at least one K-contiguous operand for it.  (CHN_GEMM_DMA=0 in the environment switches it off: a
+// tuning aid.)
+bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
+  static const bool dma_on = [] { const char *e = getenv("CHN_GEMM_DMA"); return !e || atoi(e) != 0; }();
+  const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
+  return dma_on && g.piece == 16 && g.K > 0 && g.lda < max_ld && g.ldb < max_ld && (isz == 2 || a_kc || b_kc);
+}
+
+// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model
+// from measured figures: every compute unit works through its share of the blocks one after another,
+// a block costing a fixed part (launch, prologue, epilogue) plus its tile steps times the time one
+// compute unit needs per tile step of that tile and kernel (for the smaller tiles, of which several
+// run on a compute unit at once, the amortised figure).  A problem with too few tiles to occupy 256
+// compute units but a long K is cut along K: every split writes fp32 partial sums to the workspace and
+// a second kernel adds them in a fixed order and runs the epilogue (its traffic and launch are charged
+// to the split candidates).
+void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split) {
+  // microseconds per tile step [tile][0: both operands K-contiguous, 1: one, 2: none] and per block
+  static const double step_bf16[3][3] = {{0.27, 0.50, 0.56}, {0.83, 1.08, 1.00}, {1.90, 2.25, 2.70}};
+  static const double step_f32[3][3] = {{0.52, 0.62, 0.65}, {1.95, 2.40, 2.10}, {6.90, 7.50, 7.90}};
+  static const double fixed_bf16[3] = {1.0, 3.0, 12.0}, fixed_f32[3] = {1.5, 4.0, 18.0};
+  const double step_direct = 1.48;                        // bf16 direct-copy kernel, any layout
+  const int lay = (a_kc ? 0 : 1) + (b_kc ? 0 : 1);
+  const bool direct = direct_copy_fits(*g, isz, a_kc, b_kc);
   const bool wide = g->piece >= 8;   // operands that need element-wise loads only get the small tile
+  const double narrow = g->piece >= 16 ? 1.0 : g->piece >= 8 ? 1.15 : 2.0;   // more, smaller loads per step
   const int nk = (g->K + 128 / isz - 1) / (128 / isz);   // tile steps along K
   static const int split_choices[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, 16};
   double best = 1e300;
@@ -70,19 +87,41 @@ void plan(GemmArgs *g, int isz, bool allow_split) {
   for (int tile = wide ? 2 : 0; tile >= 0; --tile) {
     const int b = 64 << tile;
     const int64_t tiles = (int64_t)((g->M + b - 1) / b) * ((g->N + b - 1) / b);
+    double per_step = (isz == 2 ? step_bf16 : step_f32)[tile][lay] * narrow;
+    if (tile == 2 && direct && isz == 2) per_step = step_direct;
+    const double fixed = (isz == 2 ? fixed_bf16 : fixed_f32)[tile];
     for (int s : split_choices) {
       if (s > 1 && (!allow_split || s > nk / 4)) break;
       const int64_t blocks = tiles * s;
-      const double per_block = 2.0 * b * b * ((double)g->K / s + 128 / isz) / (eff[tile] * cu_peak);
-      double t = (double)((blocks + 255) / 256) * per_block;
-      if (s > 1) t += 6e-6 + (double)(s + 1) * g->M * g->N * 4.0 / 4e12;
+      const int steps = (nk + s - 1) / s;
+      // Up to `conc` blocks of this tile run on a compute unit at once, each then `conc` times slower
+      // per step than the amortised figure; a lone block only `slow` times (it is not that much faster
+      // alone), in between linearly.  Full rounds of 256 * conc blocks, then the remainder.
+      const int conc = tile == 2 ? 1 : tile == 1 ? 2 : 4;
+      const double slow = tile == 2 ? 1.0 : tile == 1 ? 1.5 : 2.0;
+      const int64_t full = blocks / (256 * conc), rem = blocks % (256 * conc);
+      double t = (double)full * (fixed + steps * per_step * conc);
+      if (rem > 0) {
+        const int per_cu = (int)((rem + 255) / 256);
+        const double f = conc == 1 ? 1.0 : slow + (conc - slow) * (per_cu - 1) / (conc - 1);
+        t += fixed + steps * per_step * f;
+      }
+      t *= 1e-6;
+      if (s > 1) t += 10e-6 + (double)(s + 1) * g->M * g->N * 4.0 / 4e12;
       if (t < best * 0.97) { best = t; g->tile = tile; g->splits = s; }   // prefer larger tiles / fewer splits on near-ties
     }
+  }
+  {   // tuning aids: force the tile / the number of splits from the environment
+    static const int force_tile = [] { const char *e = getenv("CHN_GEMM_TILE"); return e ? atoi(e) : -1; }();
+    static const int force_splits = [] { const char *e = getenv("CHN_GEMM_SPLITS"); return e ? atoi(e) : 0; }();
+    if (force_tile >= 0 && force_tile <= (wide ? 2 : 0)) g->tile = force_tile;
+    if (force_splits >= 1 && allow_split && force_splits <= nk) g->splits = force_splits;
   }
   const int b = 64 << g->tile;
   g->tiles_m = (g->M + b - 1) / b;
   g->tiles_n = (g->N + b - 1) / b;
   g->ldp = (g->N + 3) & ~3;
+  g->dma = g->tile == 2 && direct;
 }
 
 size_t split_bytes(const GemmArgs &g) {
@@ -102,8 +141,25 @@ size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const ch
   GemmArgs g{};
   bool a_kc, b_kc;
   if (classify(A, B, &g, &a_kc, &b_kc) != CHN_OK) return 0;
-  plan(&g, dtype_size(A->dtype), true);
+  plan(&g, dtype_size(A->dtype), a_kc, b_kc, true);
   return split_bytes(g);
+}
+
+int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace) {
+  using namespace chn;
+  CHN_TRY(validate(A, "A", false));
+  CHN_TRY(validate(B, "B", false));
+  CHN_TRY(validate(C, "C", true));
+  if (A->ndim != 2 || B->ndim != 2 || C->ndim != 2) return fail(CHN_ERR_NDIM, "gemm: A, B and C must be 2-d");
+  if (!is_float(A->dtype) || A->dtype != B->dtype) return fail(CHN_ERR_DTYPE, "gemm: A and B must share F32 or BF16");
+  if (A->shape[1] != B->shape[0] || C->shape[0] != A->shape[0] || C->shape[1] != B->shape[1]) return fail(CHN_ERR_SHAPE, "gemm: shapes do not match");
+  if (A->shape[0] > 0x3fffffff || A->shape[1] > 0x3fffffff || B->shape[1] > 0x3fffffff) return fail(CHN_ERR_SHAPE, "gemm: dimension too large");
+  GemmArgs g{};
+  bool a_kc, b_kc;
+  CHN_TRY(classify(A, B, &g, &a_kc, &b_kc));
+  const int isz = dtype_size(A->dtype);
+  plan(&g, isz, a_kc, b_kc, have_workspace != 0);
+  return g.tile | (g.dma ? 4 : 0) | (g.splits << 4);
 }
 
 chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, float alpha, float beta,
@@ -162,19 +218,11 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.epi_vec = ok(g.C, g.ldc) && ok(g.aux, g.ldaux) && ok(g.pre, g.ldpre) &&
                 (g.bias == nullptr || reinterpret_cast<uintptr_t>(g.bias) % 16 == 0);
   }
-  plan(&g, isz, true);
+  plan(&g, isz, a_kc, b_kc, true);
   if (g.splits > 1) {
     // split-K is an optimisation: without (enough, aligned) workspace the product is planned unsplit
     if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);
-    else plan(&g, isz, false);
-  }
-  {
-    // The direct-copy 256x256 kernel needs 16-byte pieces (so K is a multiple of the chunk length for
-    // K-contiguous operands) and 32-bit offsets inside a tile; fp32 needs at least one K-contiguous
-    // operand for it.  (CHN_GEMM_DMA=0 switches it off: a tuning aid.)
-    static const bool dma_on = [] { const char *e = getenv("CHN_GEMM_DMA"); return !e || atoi(e) != 0; }();
-    const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
-    g.dma = dma_on && K > 0 && g.lda < max_ld && g.ldb < max_ld && (A->dtype == CHN_BF16 || a_kc || b_kc);
+    else plan(&g, isz, a_kc, b_kc, false);
   }
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {

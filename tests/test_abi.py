@@ -117,3 +117,28 @@ def test_reduce_gemm_and_layer_validation():
     assert L.chn_sgd_update(C.byref(c), C.byref(c), 0.1, C.byref(c), None) == -3
     assert L.chn_embed_fwd(C.byref(c), C.byref(f((3,), (4,), B.F32)), C.byref(f((3, 8), (32, 4))), None) == -3
     assert L.chn_embed_fwd(C.byref(c), C.byref(f((3,), (4,), B.I32)), C.byref(f((3, 7), (28, 4))), None) == -4
+
+
+def test_gemm_plan_picks_the_direct_copy_kernel_only_where_it_applies():
+    L = B.lib()
+    d = lambda shape, strides, dt: B.raw_desc(P, shape, strides, dt)
+    def plan(M, N, K, dt, a_t=False, b_t=True, ws=0, pad_k=0):
+        isz = 2 if dt == B.BF16 else 4
+        A = d((M, K), (isz, isz * M) if a_t else (isz * (K + pad_k), isz), dt)
+        Bm = d((K, N), (isz, isz * (K + pad_k)) if b_t else (isz * N, isz), dt)
+        Cm = d((M, N), (4 * N, 4), B.F32)
+        code = L.chn_gemm_plan(C.byref(A), C.byref(Bm), C.byref(Cm), ws)
+        assert code >= 0, B.lib().chn_last_error()
+        return code & 3, bool(code & 4), code >> 4
+    assert plan(8192, 4096, 4096, B.BF16) == (2, True, 1)                 # x @ W.T
+    assert plan(8192, 4096, 4096, B.BF16, b_t=False) == (2, True, 1)      # dY @ W
+    assert plan(4096, 4096, 8192, B.BF16, a_t=True, b_t=False) == (2, True, 1)   # dY.T @ X
+    assert plan(8192, 4096, 1000, B.BF16, b_t=False) == (2, True, 1)      # ragged last K step
+    assert plan(8192, 4096, 4096, B.F32) == (2, True, 1)
+    assert plan(4096, 4096, 8192, B.F32, a_t=True, b_t=False)[:2] == (2, False)  # fp32, no K-contiguous operand
+    assert plan(4480, 10000, 650, B.F32)[:2] == (2, False)                # rows of 2600 bytes: 8-byte pieces only
+    assert plan(8192, 4096, 4098, B.BF16)[1] is False                     # K not a multiple of 8 elements
+    assert plan(64, 64, 64, B.BF16) == (0, False, 1)
+    tile, dc, splits = plan(1000, 4096, 8192, B.BF16, a_t=True, b_t=False, ws=1)
+    assert (tile, dc) == (2, True) and splits > 1                         # few tiles, long K: split
+    assert plan(1000, 4096, 8192, B.BF16, a_t=True, b_t=False, ws=0)[2] == 1

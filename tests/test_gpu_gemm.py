@@ -8,7 +8,7 @@ import torch
 
 from oracle import oracle as O
 from paper_1908_00213_amd import binding as B
-from tests.util import TOL_BF16, TOL_SUM, bf16r, check, dev, empty, host
+from tests.util import TOL_BF16, TOL_SUM, bf16r, check, dev, empty, host, ws
 
 pytestmark = pytest.mark.gpu
 RNG = np.random.default_rng(213_1908)
@@ -72,7 +72,7 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-@pytest.mark.parametrize("shape", [(3704, 3592, 192), (2008, 2104, 64), (520, 4104, 448), (3704, 3592, 200), (1032, 4104, 1000)])
+@pytest.mark.parametrize("shape", [(3704, 3592, 192), (3704, 3592, 64), (3720, 3592, 448), (3704, 3592, 200), (3720, 3592, 1000)])
 def test_gemm_big_tiles_direct_copy(dt, layout, shape):
     # every unit-stride extent a multiple of 16 bytes: the 256x256 kernel that copies its operands
     # straight into LDS; an odd and an even number of tile steps, a single one, K with and without a
@@ -80,6 +80,8 @@ def test_gemm_big_tiles_direct_copy(dt, layout, shape):
     M, N, K = shape
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gen)
+    direct = not (dt == "f32" and layout == "tn")     # fp32 with both operands stored along M/N: register-staged
+    assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, direct)
     out = host(B.gemm(Ad, Bd, empty((M, N))))
     ref = A.astype(np.float64) @ Bm.astype(np.float64)
     rows = RNG.integers(0, M, 24)
@@ -89,9 +91,10 @@ def test_gemm_big_tiles_direct_copy(dt, layout, shape):
 
 def test_gemm_direct_copy_odd_k_both_transposed():
     # with both operands stored along M / N, K itself needs no alignment for the direct-copy kernel
-    M, N, K = 2056, 2312, 203
+    M, N, K = 3720, 3592, 203
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, "tn", "bf16", gen)
+    assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, True)
     out = host(B.gemm(Ad, Bd, empty((M, N))))
     assert np.array_equal(out, A.astype(np.float64) @ Bm.astype(np.float64))
 
@@ -184,3 +187,63 @@ def test_gemm_split_k(dt, layout, shape):
     gi = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gi)
     assert np.array_equal(host(B.gemm(Ad, Bd, empty((M, N)), ws=w)), A.astype(np.float64) @ Bm.astype(np.float64))
+
+
+@pytest.mark.parametrize("dt,cdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
+def test_gemm_direct_copy_epilogues(dt, cdt, layout):
+    # every epilogue, beta and both C dtypes on the 256x256 direct-copy kernel: an interior of full tiles
+    # (vector path), a ragged last tile in M (rows past the end) and in N (element-wise path)
+    if dt == "f32" and layout == "tn":
+        pytest.skip("fp32 with both operands stored along M/N takes the register-staged kernel")
+    M, N, K = 3720, 3592, 192
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
+    assert B.gemm_plan(Ad, Bd, empty((M, N), cdt))[:2] == (2, True)
+    tol = TOL_BF16 if cdt == "bf16" else TOL_SUM
+    rd = (lambda a: bf16r(a)) if cdt == "bf16" else (lambda a: a)
+    bias = rnd((N,))
+    aux = rd(rnd((M, N)))
+    c0 = rd(rnd((M, N)))
+    # the linear part in fp64 by a library product, tied to the oracle on sampled rows
+    lin = A.astype(np.float64) @ Bm.astype(np.float64)
+    S = np.abs(A).astype(np.float64) @ np.abs(Bm).astype(np.float64)
+    rows = RNG.integers(0, M, 16)
+    assert np.allclose(O.gemm(A[rows], Bm), lin[rows], rtol=1e-12, atol=1e-12)
+    # alpha / beta
+    out = B.gemm(Ad, Bd, dev(c0, cdt), alpha=0.5, beta=-1.25)
+    check(host(out), 0.5 * lin - 1.25 * c0.astype(np.float64), tol, 0.5 * S + 1.25 * np.abs(c0), "alpha/beta")
+    # bias, bias+relu, bias+gelu (+ pre-activation)
+    z = lin + bias
+    Sz = S + np.abs(bias)
+    check(host(B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias", bias=dev(bias))), z, tol, Sz, "bias")
+    check(host(B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_relu", bias=dev(bias))), np.maximum(z, 0), tol, Sz, "bias_relu")
+    pre = empty((M, N), cdt)
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_gelu", bias=dev(bias), preact_out=pre)
+    check(host(pre), z, tol, Sz, "preact")
+    check(host(out), O.elementwise("gelu", [z]), tol, Sz, "bias_gelu")
+    # activation gradients against the retained activation / pre-activation
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="relu_bwd", aux=dev(aux, cdt))
+    check(host(out), np.where(aux > 0, lin, 0.0), tol, S, "relu_bwd")
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="gelu_bwd", aux=dev(aux, cdt))
+    gp = O.elementwise("gelu_bwd", [np.ones_like(aux, dtype=np.float64), aux.astype(np.float64)])
+    # (the epilogue's gelu' has an absolute error of up to 3e-7 -- a 1.5e-7 rational erf plus fp32
+    # rounding -- which the product magnifies by |lin| <= S: 3e-7 S = tol * 3e-3 S at the fp32 bar)
+    check(host(out), lin * gp, tol, S * np.abs(gp) + 3e-3 * S, "gelu_bwd")
+    # gelu_bwd with beta: accumulate into old C
+    out = B.gemm(Ad, Bd, dev(c0, cdt), beta=1.0, epilogue="gelu_bwd", aux=dev(aux, cdt))
+    check(host(out), (lin + c0) * gp, tol, (S + np.abs(c0)) * (np.abs(gp) + 3e-3), "gelu_bwd beta")
+
+
+@pytest.mark.parametrize("layout", ["nt", "tn"])
+def test_gemm_direct_copy_split_k(layout):
+    # few tiles and a long K: the direct-copy kernel writes fp32 slabs, the finishing kernel adds them
+    M, N, K = 1000, 4096, 8192
+    gen = lambda s, d: RNG.integers(-2, 3, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, layout, "bf16", gen)
+    out = empty((M, N))
+    tile, dc, splits = B.gemm_plan(Ad, Bd, out, have_workspace=True)
+    assert (tile, dc) == (2, True) and splits > 1
+    need = B.gemm_workspace_bytes(Ad, Bd, out)
+    assert need > 0
+    B.gemm(Ad, Bd, out, ws=ws(need))
+    assert np.array_equal(host(out), A.astype(np.float64) @ Bm.astype(np.float64))
