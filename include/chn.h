@@ -124,7 +124,18 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
  *              shape as C) for the backward pass
  *   RELU_BWD   v * [aux > 0]                       aux (M,N): the retained forward output
  *   GELU_BWD   v * gelu'(aux)                      aux (M,N): the retained pre-activation
- * Unused optional arguments are NULL.  beta != 0 reads C before writing it. */
+ * Unused optional arguments are NULL.  beta != 0 reads C before writing it.
+ * gelu / gelu' in the epilogue use a five-term rational erf (absolute error below 1.5e-7 in Phi).
+ * Workspace: optional.  chn_gemm_workspace_bytes returns what a product with few output tiles and a
+ * long K would use to be cut along K (fp32 partial sums per cut, added in a fixed order by a second
+ * kernel: bit-reproducible); `ws` is device memory, 256-byte aligned, owned by the caller and free
+ * again when the call's work on `stream` is done.  With ws == NULL, too small or misaligned the
+ * product runs uncut -- same result up to summation order, possibly slower.
+ * Errors (nothing is launched): CHN_ERR_NULL / NDIM / DTYPE / SHAPE / STRIDE for malformed or
+ * mismatched views (a bias or aux that the epilogue needs and that is NULL: CHN_ERR_NULL), CHN_ERR_OP
+ * for an unknown epilogue or a preact_out given to an epilogue other than BIAS_GELU, CHN_ERR_LAUNCH
+ * if the launch itself is refused.  M == 0 or N == 0 is a no-op; K == 0 applies the
+ * epilogue to beta * C. */
 typedef enum {
   CHN_EPI_NONE = 0,
   CHN_EPI_BIAS,
