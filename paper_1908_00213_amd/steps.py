@@ -165,70 +165,125 @@ class MLPTrainer:
         return len(self._progs[(x.data_ptr(), t.data_ptr())].calls)
 
 
+def _ceil32(n):
+    return (n + 31) // 32 * 32
+
+
 class LSTMTrainer:
     """Forward + full BPTT + SGD for the single-layer LSTM language model (workload 4), fp32.
 
     Time-major layout: row t*B + b of every (T*B, .) buffer belongs to step t, batch element b.
     W (E,4H) and U (H,4H) give the gates as x W + h U + b; W_out (V,H) is a Linear layer.
+
+    Layout in HBM: the embedding width E and the hidden width H are rounded up to multiples of 32 and
+    every parameter is embedded in a zero-padded array of the rounded shape (gate blocks of W, U and b
+    stay gate blocks, now of the rounded width).  The added embedding columns and hidden units are
+    inert: their weights, biases, activations, cell states and every gradient that touches them are
+    exactly zero from the first step on and stay zero under SGD, so the real entries take the values
+    they would take unpadded, bit for bit (the padding only adds exact zeros to sums) -- but every row of
+    every operand now starts on a 16-byte boundary and every contraction length is a whole number of
+    tile steps, which is what the fast GEMM paths need (650 floats per row would allow 8-byte pieces
+    only).  `P`, `g` and the activation buffers are exposed without the padding.
     """
 
     def __init__(self, P, T, Bn, lr=0.01):
         self.L = B.lib()
         self.T, self.B, self.lr = T, Bn, float(lr)
-        self.P = {k: _dev(v) for k, v in P.items()}
         V, E = P["E"].shape
         H = P["U"].shape[0]
         self.V, self.E, self.H = V, E, H
-        mk = lambda *s: torch.empty(*s, dtype=torch.float32, device="cuda")
+        Ep, Hp = _ceil32(E), _ceil32(H)
+        self.Ep, self.Hp = Ep, Hp
+        z = lambda *s: torch.zeros(*s, dtype=torch.float32, device="cuda")
+        self._P = {"E": z(V, Ep), "W": z(Ep, 4 * Hp), "U": z(Hp, 4 * Hp), "b": z(4 * Hp), "W_out": z(V, Hp), "b_out": z(V)}
+        for k in self._P:
+            dst = self._real(self._P, k)
+            dst.copy_(_dev(P[k]).reshape(dst.shape))
         n = T * Bn
-        self.X, self.Z, self.G = mk(n, E), mk(n, 4 * H), mk(n, 4 * H)
-        self.Hs = torch.zeros(n + Bn, H, dtype=torch.float32, device="cuda")   # block 0 = h_0 = 0
-        self.Cs = torch.zeros(n + Bn, H, dtype=torch.float32, device="cuda")   # block 0 = c_0 = 0
-        self.logits = mk(n, V)
-        self.dHs, self.dZ, self.dX = mk(n, H), mk(n, 4 * H), mk(n, E)
-        self.dc = [mk(Bn, H), mk(Bn, H)]
-        self.g = {k: mk(*v.shape) for k, v in self.P.items()}
-        self.loss, self.lse = mk(()), mk(n)
+        # zero-initialised: the inert columns must hold zeros before the first step
+        self._X, self._Z, self._G = z(n, Ep), z(n, 4 * Hp), z(n, 4 * Hp)
+        self._Hs = z(n + Bn, Hp)   # block 0 = h_0 = 0
+        self._Cs = z(n + Bn, Hp)   # block 0 = c_0 = 0
+        self.logits = z(n, V)
+        self._dHs, self._dZ, self._dX = z(n, Hp), z(n, 4 * Hp), z(n, Ep)
+        self._dc = [z(Bn, Hp), z(Bn, Hp)]
+        self._g = {k: z(*v.shape) for k, v in self._P.items()}
+        self.loss, self.lse = z(()), z(n)
         self.ws_ce = torch.empty(B.softmax_ce_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-        need = max(B.reduce_axis_workspace_bytes(self.logits, 0), B.reduce_axis_workspace_bytes(self.dZ, 0), 256)
+        need = max(B.reduce_axis_workspace_bytes(self.logits, 0), B.reduce_axis_workspace_bytes(self._dZ, 0), 256)
         self.ws_red = torch.empty(need, dtype=torch.uint8, device="cuda")
         self._progs = {}
 
+    # ---- views without the padding (for callers and tests; the step itself never uses them) ----------
+    def _real(self, d, k):
+        E, H, Hp = self.E, self.H, self.Hp
+        t = d[k]
+        if k == "E":
+            return t[:, :E]
+        if k == "W":
+            return t.view(self.Ep, 4, Hp)[:E, :, :H]
+        if k == "U":
+            return t.view(Hp, 4, Hp)[:H, :, :H]
+        if k == "b":
+            return t.view(4, Hp)[:, :H]
+        if k == "W_out":
+            return t[:, :H]
+        return t
+
+    def _unpadded(self, d):
+        shapes = {"W": (self.E, 4 * self.H), "U": (self.H, 4 * self.H), "b": (4 * self.H,)}
+        return {k: self._real(d, k).reshape(shapes[k]) if k in shapes else self._real(d, k) for k in d}
+
+    def _gates(self, t):
+        return t.view(t.shape[0], 4, self.Hp)[:, :, :self.H].reshape(t.shape[0], 4 * self.H)
+
+    P = property(lambda self: self._unpadded(self._P))
+    g = property(lambda self: self._unpadded(self._g))
+    X = property(lambda self: self._X[:, :self.E])
+    dX = property(lambda self: self._dX[:, :self.E])
+    Hs = property(lambda self: self._Hs[:, :self.H])
+    Cs = property(lambda self: self._Cs[:, :self.H])
+    dHs = property(lambda self: self._dHs[:, :self.H])
+    dc = property(lambda self: [t[:, :self.H] for t in self._dc])
+    Z = property(lambda self: self._gates(self._Z))
+    G = property(lambda self: self._gates(self._G))
+    dZ = property(lambda self: self._gates(self._dZ))
+
     def _build(self, ids, targets):
-        L, p, P, T, Bn = self.L, _Program(), self.P, self.T, self.B
+        L, p, P, T, Bn = self.L, _Program(), self._P, self.T, self.B
         blk = lambda buf, t: buf[t * Bn:(t + 1) * Bn]
         ids_f, tg_f = ids.reshape(-1), targets.reshape(-1)
         # forward
-        p.add(L.chn_embed_fwd, p.d(P["E"]), p.d(ids_f), p.d(self.X))
-        _gemm(p, L, self.X, P["W"], self.Z)                                   # x W for all steps at once
+        p.add(L.chn_embed_fwd, p.d(P["E"]), p.d(ids_f), p.d(self._X))
+        _gemm(p, L, self._X, P["W"], self._Z)                                   # x W for all steps at once
         for t in range(T):
-            _gemm(p, L, blk(self.Hs, t), P["U"], blk(self.Z, t), beta=1.0)    # + h_{t-1} U
-            p.add(L.chn_lstm_fwd, p.d(blk(self.Z, t)), p.d(P["b"]), p.d(blk(self.Cs, t)),
-                  p.d(blk(self.Cs, t + 1)), p.d(blk(self.Hs, t + 1)), p.d(blk(self.G, t)))
-        Hall, Hprev = self.Hs[Bn:], self.Hs[:T * Bn]
+            _gemm(p, L, blk(self._Hs, t), P["U"], blk(self._Z, t), beta=1.0)    # + h_{t-1} U
+            p.add(L.chn_lstm_fwd, p.d(blk(self._Z, t)), p.d(P["b"]), p.d(blk(self._Cs, t)),
+                  p.d(blk(self._Cs, t + 1)), p.d(blk(self._Hs, t + 1)), p.d(blk(self._G, t)))
+        Hall, Hprev = self._Hs[Bn:], self._Hs[:T * Bn]
         _gemm(p, L, Hall, P["W_out"].t(), self.logits, epi="bias", bias=P["b_out"])
         wp, wn = p.ws(self.ws_ce)
         p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
         # backward (dlogits overwrite the logits in place)
         p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.lse), C.c_float(1.0), p.d(self.logits), wp, wn)
         rp, rn = p.ws(self.ws_red)
-        _gemm(p, L, self.logits.t(), Hall, self.g["W_out"])
-        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.logits), 0, 0, p.d(self.g["b_out"]), rp, rn)
-        _gemm(p, L, self.logits, P["W_out"], self.dHs)
+        _gemm(p, L, self.logits.t(), Hall, self._g["W_out"])
+        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.logits), 0, 0, p.d(self._g["b_out"]), rp, rn)
+        _gemm(p, L, self.logits, P["W_out"], self._dHs)
         for t in range(T - 1, -1, -1):
-            dc_next = None if t == T - 1 else self.dc[(t + 1) & 1]
-            p.add(L.chn_lstm_bwd, p.d(blk(self.G, t)), p.d(blk(self.Cs, t)), p.d(blk(self.Cs, t + 1)),
-                  p.d(blk(self.dHs, t)), p.d(dc_next), p.d(blk(self.dZ, t)), p.d(self.dc[t & 1]))
+            dc_next = None if t == T - 1 else self._dc[(t + 1) & 1]
+            p.add(L.chn_lstm_bwd, p.d(blk(self._G, t)), p.d(blk(self._Cs, t)), p.d(blk(self._Cs, t + 1)),
+                  p.d(blk(self._dHs, t)), p.d(dc_next), p.d(blk(self._dZ, t)), p.d(self._dc[t & 1]))
             if t > 0:
-                _gemm(p, L, blk(self.dZ, t), P["U"].t(), blk(self.dHs, t - 1), beta=1.0)
-        _gemm(p, L, Hprev.t(), self.dZ, self.g["U"])
-        _gemm(p, L, self.X.t(), self.dZ, self.g["W"])
-        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.dZ), 0, 0, p.d(self.g["b"]), rp, rn)
-        _gemm(p, L, self.dZ, P["W"].t(), self.dX)
-        p.add(L.chn_embed_bwd, p.d(ids_f), p.d(self.dX), p.d(self.g["E"]), 0)
-        names = list(self.P.keys())
+                _gemm(p, L, blk(self._dZ, t), P["U"].t(), blk(self._dHs, t - 1), beta=1.0)
+        _gemm(p, L, Hprev.t(), self._dZ, self._g["U"])
+        _gemm(p, L, self._X.t(), self._dZ, self._g["W"])
+        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self._dZ), 0, 0, p.d(self._g["b"]), rp, rn)
+        _gemm(p, L, self._dZ, P["W"].t(), self._dX)
+        p.add(L.chn_embed_bwd, p.d(ids_f), p.d(self._dX), p.d(self._g["E"]), 0)
+        names = list(P.keys())
         p.add(L.chn_sgd_update_multi, len(names), p.ptrs([P[k] for k in names]),
-              p.ptrs([self.g[k] for k in names]), C.c_float(self.lr), None)
+              p.ptrs([self._g[k] for k in names]), C.c_float(self.lr), None)
         return p.finish()
 
     def step(self, ids, targets, stream=None, graph=False):
