@@ -42,7 +42,7 @@ struct RPlan {
 
 // COL kernel block shapes (column groups x row lanes = 256 threads): 16 x 16 for the large streaming
 // case (more column blocks, hence fewer row splits and a smaller second pass), 64 x 4 otherwise.
-constexpr int kColTXWide = 16, kColTXNarrow = 64;
+constexpr int kColTXWide = 16, kColTXMid = 32, kColTXNarrow = 64;
 
 chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
   CHN_TRY(validate(in, "in", false));
@@ -83,7 +83,7 @@ chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
     const int n = 16 / isz;
     p->vec = reinterpret_cast<uintptr_t>(in->data) % 16 == 0 && p->I % n == 0 && p->sR % n == 0 && p->sO % n == 0;
     const int64_t groups = p->I / (p->vec ? n : 1);
-    p->tx = (p->vec && groups >= 512 && p->len >= 1024) ? kColTXWide : kColTXNarrow;
+    p->tx = (p->vec && groups >= 512 && p->len >= 1024) ? (isz == 2 && groups >= 1024 ? kColTXMid : kColTXWide) : kColTXNarrow;
     const int64_t cols_per_block = (int64_t)p->tx * (p->vec ? n : 1);
     const int64_t blocks_xy = ((p->I + cols_per_block - 1) / cols_per_block) * p->O;
     // Measured on 8192 x 8192: many short blocks (8 rows per thread) stream best.
@@ -251,6 +251,7 @@ chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64
   dim3 grid((unsigned)((I + cpb - 1) / cpb), (unsigned)split, (unsigned)O);
   if (O > 65535) return fail(CHN_ERR_SHAPE, "reduce: outer extent %lld too large for the column kernel", (long long)O);
   if (vec && tx == kColTXWide) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXWide>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else if (vec && tx == kColTXMid) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXMid>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   (void)p;
