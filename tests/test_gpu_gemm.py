@@ -247,3 +247,23 @@ def test_gemm_direct_copy_split_k(layout):
     assert need > 0
     B.gemm(Ad, Bd, out, ws=ws(need))
     assert np.array_equal(host(out), A.astype(np.float64) @ Bm.astype(np.float64))
+
+
+def test_gemm_degenerate_sizes():
+    # K == 0: nothing to multiply, the epilogue still runs on beta * C;  M == 0 or N == 0: nothing to do
+    c0 = rnd((70, 90))
+    bias = rnd((90,))
+    a = torch.empty((70, 0), device="cuda")
+    b = torch.empty((0, 90), device="cuda")
+    out = B.gemm(a, b, dev(c0), alpha=3.0, beta=2.0, epilogue="bias", bias=dev(bias))
+    check(host(out), 2.0 * c0.astype(np.float64) + bias, 1e-6, np.abs(bias), "K = 0")
+    out = B.gemm(a, b, dev(c0))                      # beta = 0: C must not be read (it may hold NaNs)
+    assert np.all(host(out) == 0.0)
+    nan = dev(np.full((70, 90), np.nan, np.float32))
+    assert np.all(host(B.gemm(a, b, nan)) == 0.0)
+    x = dev(rnd((0, 33)))
+    B.gemm(x, dev(rnd((33, 20))), torch.empty((0, 20), device="cuda"))
+    B.gemm(dev(rnd((20, 33))), torch.empty((33, 0), device="cuda"), torch.empty((20, 0), device="cuda"))
+    # beta = 0 never reads C either when there is something to multiply
+    A, Bm, Ad, Bd = operands(64, 48, 40, "nt", "f32")
+    check(host(B.gemm(Ad, Bd, dev(np.full((64, 48), np.nan, np.float32)))), O.gemm(A, Bm), TOL_SUM, O.gemm(np.abs(A), np.abs(Bm)), "NaN in C, beta 0")
