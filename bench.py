@@ -130,19 +130,22 @@ class GemmProbe:
         return [x / max(1, len(self.events)) for x in tot]
 
 
-def gemm_shapes_mlp(sizes, batch):
+def gemm_shapes_mlp(sizes, batch, fused_update):
     """(label, M, N, K) of every GEMM of one MLP step in issue order (see steps.MLPTrainer)."""
     n = len(sizes) - 1
     out = [("fwd%d" % l, batch, sizes[l + 1], sizes[l]) for l in range(n)]
     for l in range(n - 1, -1, -1):
-        out.append(("dW%d" % l, sizes[l + 1], sizes[l], batch))
-        if l > 0:
-            out.append(("dx%d" % l, batch, sizes[l], sizes[l + 1]))
+        dW = ("dW%d%s" % (l, "+sgd" if fused_update else ""), sizes[l + 1], sizes[l], batch)
+        dx = [("dx%d" % l, batch, sizes[l], sizes[l + 1])] if l > 0 else []
+        out += dx + [dW] if fused_update else [dW] + dx
     return out
 
 
-def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, graph=False):
-    tr = steps_mod.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp)
+def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, graph=False, fused_update=False):
+    """fused_update: the SGD update of the weights runs in the epilogue of the weight-gradient products
+    (same arithmetic, the gradients do not travel through memory); still one full
+    forward + backward + update step."""
+    tr = steps_mod.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp, fused_update=fused_update)
     xs = [torch.from_numpy(x).cuda() for x in w.xs]
     if lowp:
         xs = [x.to(torch.bfloat16) for x in xs]
@@ -168,9 +171,9 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, g
                 per[i] += v / len(used)
         res["gemm_calls"] = [{"call": lab, "M": M, "N": N, "K": K, "us": round(t_ * 1e6, 1),
                               "TFLOP/s": round(2.0 * M * N * K / t_ / 1e12, 1)}
-                             for (lab, M, N, K), t_ in zip(gemm_shapes_mlp(w.sizes, w.batch), per)]
+                             for (lab, M, N, K), t_ in zip(gemm_shapes_mlp(w.sizes, w.batch, fused_update), per)]
         res["gemm_seconds_per_step"] = sum(per)
-        res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch))
+        res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch, fused_update))
     else:
         k = [0]
 
@@ -241,6 +244,9 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--workloads", default="1,2,3,4", help="which of the secondary workloads to run (comma list)")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="headline workload: write the weight gradients and update in a separate SGD launch "
+                         "instead of updating in the epilogue of the weight-gradient products (about 1 %% slower)")
     ap.add_argument("--traffic-driver", action="store_true",
                     help="run only the calibration copy + dominant GEMM launches (for rocprofv3 --pmc) and exit")
     args = ap.parse_args()
@@ -265,7 +271,8 @@ def main():
     log("workload 5: wide MLP 4096-4096-4096-4096-1000, GELU, batch 8192, bf16/fp32-accumulate")
     w5 = W.config5(n_batches=4)
     torch.cuda.synchronize()
-    r5 = bench_mlp(torch, B, steps_mod, w5, True, timer, args.steps, args.warmup, probe=True)
+    r5 = bench_mlp(torch, B, steps_mod, w5, True, timer, args.steps, args.warmup, probe=True,
+                   fused_update=not args.separate_update)
     torch.cuda.synchronize()
     log("  %.3f ms/step  %.1f steps/s  %.1f TFLOP/s whole step; GEMMs %.3f ms/step = %.1f TFLOP/s" % (
         r5["ms_per_step"], r5["steps_per_s"], r5["TFLOP/s"], r5["gemm_seconds_per_step"] * 1e3,
@@ -326,7 +333,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "cfg5: wide MLP 4096-4096-4096-4096-1000, GELU, softmax cross-entropy, batch 8192, "
-                               "bf16 storage / fp32 accumulate / fp32 master weights, forward+backward+SGD",
+                               "bf16 storage / fp32 accumulate / fp32 master weights, forward+backward+SGD "
+                               "(weight update applied in the epilogue of the weight-gradient products)",
                    "global_batch": 8192, "parallelism": "single GPU"},
         "roofline": roofline, "cpu_baseline": cpu, "workloads": extra,
     }

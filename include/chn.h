@@ -124,6 +124,11 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
  *              shape as C) for the backward pass
  *   RELU_BWD   v * [aux > 0]                       aux (M,N): the retained forward output
  *   GELU_BWD   v * gelu'(aux)                      aux (M,N): the retained pre-activation
+ *   BF16_COPY  v, and preact_out (M,N) BF16 receives v rounded to bfloat16 as well (C must be F32):
+ *              with alpha = -lr, beta = 1 and C the fp32 master weights, the weight-gradient product
+ *              of a layer becomes the SGD update W <- W - lr * dW of Section "Background and
+ *              Motivation"'s training loop together with the refresh of the bf16 working copy, and
+ *              the gradient never travels through memory
  * Unused optional arguments are NULL.  beta != 0 reads C before writing it.
  * gelu / gelu' in the epilogue use a five-term rational erf (absolute error below 1.5e-7 in Phi).
  * Workspace: optional.  chn_gemm_workspace_bytes returns what a product with few output tiles and a
@@ -133,7 +138,8 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
  * product runs uncut -- same result up to summation order, possibly slower.
  * Errors (nothing is launched): CHN_ERR_NULL / NDIM / DTYPE / SHAPE / STRIDE for malformed or
  * mismatched views (a bias or aux that the epilogue needs and that is NULL: CHN_ERR_NULL), CHN_ERR_OP
- * for an unknown epilogue or a preact_out given to an epilogue other than BIAS_GELU, CHN_ERR_LAUNCH
+ * for an unknown epilogue or a preact_out given to an epilogue other than BIAS_GELU / BF16_COPY
+ * (BF16_COPY requires it), CHN_ERR_LAUNCH
  * if the launch itself is refused.  M == 0 or N == 0 is a no-op; K == 0 applies the
  * epilogue to beta * C. */
 typedef enum {
@@ -143,6 +149,7 @@ typedef enum {
   CHN_EPI_BIAS_GELU,
   CHN_EPI_RELU_BWD,
   CHN_EPI_GELU_BWD,
+  CHN_EPI_BF16_COPY,
   CHN_EPI_COUNT_
 } chn_epilogue;
 

@@ -22,7 +22,7 @@ OPS = ["copy", "add", "sub", "mul", "mad", "mad_relu", "relu", "relu_bwd", "gelu
        "scale", "axpy", "add_relu", "add_gelu", "fill", "sigmoid", "tanh", "sqrt"]
 OP = {n: i for i, n in enumerate(OPS)}
 REDUCE = {"sum": 0, "max": 1}
-EPILOGUES = ["none", "bias", "bias_relu", "bias_gelu", "relu_bwd", "gelu_bwd"]
+EPILOGUES = ["none", "bias", "bias_relu", "bias_gelu", "relu_bwd", "gelu_bwd", "bf16_copy"]
 EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis",

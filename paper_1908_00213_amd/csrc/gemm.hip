@@ -200,10 +200,16 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     if (ar != M || ac != N) return fail(CHN_ERR_SHAPE, "gemm: aux must have C's shape");
     g.aux = aux->data;
   }
+  if (epilogue == CHN_EPI_BF16_COPY && !preact_out) return fail(CHN_ERR_NULL, "gemm: the BF16_COPY epilogue needs preact_out");
   if (preact_out) {
-    if (epilogue != CHN_EPI_BIAS_GELU) return fail(CHN_ERR_OP, "gemm: preact_out is only produced by the BIAS_GELU epilogue");
+    if (epilogue != CHN_EPI_BIAS_GELU && epilogue != CHN_EPI_BF16_COPY)
+      return fail(CHN_ERR_OP, "gemm: preact_out is only produced by the BIAS_GELU and BF16_COPY epilogues");
     CHN_TRY(validate(preact_out, "preact_out", true));
-    if (preact_out->dtype != C->dtype) return fail(CHN_ERR_DTYPE, "gemm: preact_out must have C's dtype");
+    if (epilogue == CHN_EPI_BF16_COPY) {
+      if (C->dtype != CHN_F32 || preact_out->dtype != CHN_BF16) return fail(CHN_ERR_DTYPE, "gemm: BF16_COPY needs an F32 C and a BF16 preact_out");
+    } else if (preact_out->dtype != C->dtype) {
+      return fail(CHN_ERR_DTYPE, "gemm: preact_out must have C's dtype");
+    }
     int64_t pr, pc;
     CHN_TRY(row_major_2d(preact_out, "preact_out", &pr, &pc, &g.ldpre));
     if (pr != M || pc != N) return fail(CHN_ERR_SHAPE, "gemm: preact_out must have C's shape");

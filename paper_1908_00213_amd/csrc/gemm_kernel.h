@@ -354,6 +354,7 @@ __device__ __forceinline__ void finish4(const GemmArgs &g, int row, int col, con
 #pragma unroll
   for (int e = 0; e < 4; ++e) x.v[e] = epi_math(g, a[e], in.c0.v[e], b.v[e], in.aux.v[e], &pre.v[e]);
   if (g.epi == CHN_EPI_BIAS_GELU && g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+  if (g.epi == CHN_EPI_BF16_COPY) store4v(g.pre, (int64_t)row * g.ldpre + col, 1, x);
   store4v(g.C, (int64_t)row * g.ldc + col, g.c_bf16, x);
 }
 
@@ -366,6 +367,7 @@ __device__ __forceinline__ void finish1(const GemmArgs &g, int row, int col, flo
   float pre;
   const float x = epi_math(g, acc, c0, bias, aux, &pre);
   if (g.epi == CHN_EPI_BIAS_GELU && g.pre) store1(g.pre, (int64_t)row * g.ldpre + col, g.c_bf16, pre);
+  if (g.epi == CHN_EPI_BF16_COPY) store1(g.pre, (int64_t)row * g.ldpre + col, 1, x);
   store1(g.C, ci, g.c_bf16, x);
 }
 
@@ -415,6 +417,7 @@ __device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, c
   if constexpr (EPI == CHN_EPI_BIAS_GELU) {
     if (g.pre) store4v(g.pre, (int64_t)row * g.ldpre + col, CB, pre);
   }
+  if constexpr (EPI == CHN_EPI_BF16_COPY) store4v(g.pre, (int64_t)row * g.ldpre + col, true, x);
   store4v(g.C, (int64_t)row * g.ldc + col, CB, x);
 }
 
@@ -501,11 +504,12 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
   } else if (g.epi_vec && col0 + W <= g.N && row0 + RP <= g.M) {
     auto run = [&](auto epi_c) __attribute__((always_inline)) {
       constexpr int EPI = decltype(epi_c)::value;
+      constexpr bool kF32Only = EPI == CHN_EPI_BF16_COPY;   // (the host refuses a bf16 C for it)
       if (g.beta != 0.0f) {
-        if (g.c_bf16) epilogue_pass_vec<EPI, true, true, TN, RP>(g, stage, row0, col0, lane);
+        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, true, TN, RP>(g, stage, row0, col0, lane);
         else epilogue_pass_vec<EPI, false, true, TN, RP>(g, stage, row0, col0, lane);
       } else {
-        if (g.c_bf16) epilogue_pass_vec<EPI, true, false, TN, RP>(g, stage, row0, col0, lane);
+        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, false, TN, RP>(g, stage, row0, col0, lane);
         else epilogue_pass_vec<EPI, false, false, TN, RP>(g, stage, row0, col0, lane);
       }
     };
@@ -515,7 +519,8 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
       case CHN_EPI_BIAS_RELU: run(std::integral_constant<int, CHN_EPI_BIAS_RELU>{}); break;
       case CHN_EPI_BIAS_GELU: run(std::integral_constant<int, CHN_EPI_BIAS_GELU>{}); break;
       case CHN_EPI_RELU_BWD: run(std::integral_constant<int, CHN_EPI_RELU_BWD>{}); break;
-      default: run(std::integral_constant<int, CHN_EPI_GELU_BWD>{}); break;
+      case CHN_EPI_GELU_BWD: run(std::integral_constant<int, CHN_EPI_GELU_BWD>{}); break;
+      default: run(std::integral_constant<int, CHN_EPI_BF16_COPY>{}); break;
     }
   } else {                                                    // ragged right edge or unaligned views: one element at a time
 #pragma unroll 1

@@ -96,9 +96,14 @@ def _gemm(p, L, A, Bm, Cm, alpha=1.0, beta=0.0, epi="none", bias=None, aux=None,
 class MLPTrainer:
     """Forward + backward + SGD for an MLP with softmax cross-entropy (workloads 1, 3 and 5)."""
 
-    def __init__(self, params, batch, act="relu", lr=0.01, lowp=False):
+    def __init__(self, params, batch, act="relu", lr=0.01, lowp=False, fused_update=False):
+        """fused_update: the weight-gradient product of every layer applies the SGD update in its
+        epilogue (alpha = -lr, beta = 1 on the fp32 weights, bf16 working copy refreshed in the same
+        pass), so weight gradients never travel through memory and `dW` stays unwritten; the input
+        gradient of a layer, which needs the weights of the forward pass, is then computed first."""
         self.L = B.lib()
         self.act, self.lr, self.lowp, self.batch = act, float(lr), lowp, batch
+        self.fused_update = fused_update
         self.W = [_dev(W) for W, _ in params]
         self.b = [_dev(b) for _, b in params]
         self.Wl = [w.to(torch.bfloat16) for w in self.W] if lowp else self.W
@@ -137,15 +142,22 @@ class MLPTrainer:
         rp, rn = p.ws(self.ws_red)
         for l in range(n - 1, -1, -1):
             dv = self.dv[l + 1]
-            _gemm(p, L, dv.t(), hs[l], self.dW[l])
+            if not self.fused_update:
+                _gemm(p, L, dv.t(), hs[l], self.dW[l])
             p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(dv), 0, 0, p.d(self.db[l]), rp, rn)
             if l > 0:
                 _gemm(p, L, dv, self.Wl[l], self.dv[l], epi=bwd_epi,
                       aux=hs[l] if self.act == "relu" else self.z[l])
-        # optimiser: every parameter once
-        params = self.W + self.b
-        grads = self.dW + self.db
-        lows = (self.Wl + [None] * n) if self.lowp else None
+            if self.fused_update:     # after dx: that product still reads this layer's old weights
+                _gemm(p, L, dv.t(), hs[l], self.W[l], alpha=-self.lr, beta=1.0,
+                      epi="bf16_copy" if self.lowp else "none", pre=self.Wl[l] if self.lowp else None)
+        # optimiser: every parameter once (with fused_update only the biases are left)
+        if self.fused_update:
+            params, grads, lows = self.b, self.db, None
+        else:
+            params = self.W + self.b
+            grads = self.dW + self.db
+            lows = (self.Wl + [None] * n) if self.lowp else None
         p.add(L.chn_sgd_update_multi, len(params), p.ptrs(params), p.ptrs(grads), C.c_float(self.lr),
               None if lows is None else p.ptrs(lows))
         return p.finish()

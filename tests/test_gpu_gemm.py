@@ -267,3 +267,25 @@ def test_gemm_degenerate_sizes():
     # beta = 0 never reads C either when there is something to multiply
     A, Bm, Ad, Bd = operands(64, 48, 40, "nt", "f32")
     check(host(B.gemm(Ad, Bd, dev(np.full((64, 48), np.nan, np.float32)))), O.gemm(A, Bm), TOL_SUM, O.gemm(np.abs(A), np.abs(Bm)), "NaN in C, beta 0")
+
+
+@pytest.mark.parametrize("shape,layout", [((150, 200, 90), "tn"), ((3720, 3592, 192), "tn"), ((1000, 4096, 8192), "tn"), ((257, 130, 100), "nt")])
+def test_gemm_bf16_copy_epilogue_is_an_sgd_update(shape, layout):
+    # C (fp32 master weights) <- C - lr * A B, preact_out <- bf16(C): small tile, direct-copy kernel,
+    # split-K finishing kernel, element-wise path (N not a multiple of 4)
+    M, N, K = shape
+    lr = 0.05
+    A, Bm, Ad, Bd = operands(M, N, K, layout, "bf16")
+    W0 = rnd((M, N))
+    Wd = dev(W0)
+    low = empty((M, N), "bf16")
+    need = B.gemm_workspace_bytes(Ad, Bd, Wd)
+    B.gemm(Ad, Bd, Wd, alpha=-lr, beta=1.0, epilogue="bf16_copy", preact_out=low, ws=ws(need) if need else None)
+    g = A.astype(np.float64) @ Bm.astype(np.float64)
+    S = np.abs(A).astype(np.float64) @ np.abs(Bm).astype(np.float64)
+    check(host(Wd), W0 - lr * g, TOL_SUM, np.abs(W0) + lr * S, "update")
+    assert np.array_equal(host(low), O.round_bf16(host(Wd)))
+    with pytest.raises(B.ChnError):
+        B.gemm(Ad, Bd, Wd, epilogue="bf16_copy")                                   # needs preact_out
+    with pytest.raises(B.ChnError):
+        B.gemm(Ad, Bd, empty((M, N), "bf16"), epilogue="bf16_copy", preact_out=low)  # C must be fp32

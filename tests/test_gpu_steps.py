@@ -147,3 +147,37 @@ def test_graph_replay_equals_eager():
         assert la == lb, (k, la, lb)
         for name in a.P:
             assert torch.equal(a.P[name], b.P[name]) and torch.equal(a.g[name], b.g[name])
+
+
+@pytest.mark.parametrize("lowp", [False, True])
+def test_mlp_step_with_update_fused_into_the_weight_gradient_products(lowp):
+    # the same step with W <- W - lr * dW applied in the epilogue of each dW product (and the bf16
+    # working copies refreshed there): parameters, loss and logits must match the oracle's step, and
+    # the unfused trainer's parameters to fp32 rounding of the update
+    w = W.config5(n_batches=1, scale=8)
+    tol = 2e-2 if lowp else 1e-4
+    x, t = w.xs[0], w.ts[0]
+    if lowp:
+        x = bf16r(x)
+    xd = torch.from_numpy(x).cuda()
+    xd = xd.to(torch.bfloat16) if lowp else xd
+    td = torch.from_numpy(t).cuda()
+    fused = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp, fused_update=True)
+    plain = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp)
+    lf, lp = float(fused.step(xd, td).cpu()), float(plain.step(xd, td).cpu())
+    assert lf == lp                                    # the forward passes are the same calls
+    r = OS.mlp_step(w.params, x, t, np.float32(w.lr), w.act, lowp)
+    lr = np.float32(w.lr)
+    for l, ((dW, db), (Wn, bn)) in enumerate(zip(r["grads"], r["params"])):
+        W0 = w.params[l][0]
+        g = host(plain.dW[l])
+        bound = np.abs(W0) + lr * np.abs(g)
+        check(host(fused.W[l]), host(plain.W[l]), 1e-6, bound, "fused vs separate update, layer %d" % l)
+        check(host(fused.W[l]), Wn, 1e-6, np.abs(W0) + float(lr) * tol * float(np.max(np.abs(dW))) / 1e-6, "param %d" % l)
+        assert torch.equal(fused.b[l], plain.b[l])
+        if lowp:
+            assert np.array_equal(host(fused.Wl[l]), O.round_bf16(host(fused.W[l])))
+    # and the second step starts from the updated weights in both
+    l2f, l2p = float(fused.step(xd, td).cpu()), float(plain.step(xd, td).cpu())
+    assert abs(l2f - l2p) <= 1e-5 * max(1.0, abs(l2p)) and l2f < lf
+    assert fused.n_launch_calls(xd, td) == plain.n_launch_calls(xd, td)
