@@ -39,9 +39,6 @@
 namespace chn {
 namespace gemm {
 
-#ifndef CHN_TOUCH
-#define CHN_TOUCH 1
-#endif
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -897,15 +894,8 @@ __device__ __forceinline__ void touch_tile(const void *p, int64_t ld, int esz, i
 // One tile step: k-steps 0..2 out of `cur` while the copy of the next tile (started one step ago)
 // lands in `nxt`; barrier (copy complete, nobody reads `cur` any more); start the copy of the tile
 // after the next into `cur`; k-step 3 while the first fragments of `nxt` are read.
-#ifdef CHN_GEMM_TS
-__device__ uint64_t g_ts[16];
-#define CHN_TS(i) do { if (blockIdx.x == 0 && threadIdx.x == 0) g_ts[i] = wall_clock64(); } while (0)
-#else
-#define CHN_TS(i) do {} while (0)
-#endif
 template <typename T, bool A_KC, bool B_KC, bool RAGGED>
 __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
-  CHN_TS(0);
   // How each operand reaches LDS: K-contiguous -> direct copy, K-packed; bf16 M/N-contiguous -> direct
   // copy as it lies, transposing reads; fp32 M/N-contiguous -> through registers (TileLoader).
   constexpr bool kBf16 = sizeof(T) == 2;
@@ -964,10 +954,8 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
     lb.issue(k_of(kt0), stage0 + A_BYTES);
     if constexpr (!(A_DMA && B_DMA)) lb.issue(k_of(kt0 + 1), stage1 + A_BYTES);   // (else: in the first step's k-step 0)
   } else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
-  CHN_TS(1);
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
-  CHN_TS(2);
   Frags<TM, TN> f0, f1;
   read_frags(f0, stage0, 0);
 
@@ -1045,7 +1033,7 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   // the main loop on purpose: with these extra copies around, the compiler makes the fragment reads
   // of the following step wait for all copies in flight.  They go to the scrap of stage 1, the stage
   // the next step does not read before its barrier.)
-  if (CHN_TOUCH && g.splits == 1) {
+  if (g.splits == 1) {
     const int esz = g.c_bf16 ? 2 : 4;
     if (g.beta != 0.0f) touch_tile<BM, BN>(g.C, g.ldc, esz, g.M, g.N, m0, n0, stage1 + STAGE);
     if (g.epi == CHN_EPI_RELU_BWD || g.epi == CHN_EPI_GELU_BWD) touch_tile<BM, BN>(g.aux, g.ldaux, esz, g.M, g.N, m0, n0, stage1 + STAGE);
@@ -1057,13 +1045,10 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   if (kt < nk) step(stage0, stage1, kt);
 
   // The (unused) copies that the last steps started must be over: the epilogue reuses stage 0.
-  CHN_TS(3);
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
-  CHN_TS(4);
   static_assert(2 * kEpiStageBytes<TM, TN> <= STAGE, "two waves stage their accumulators in each operand stage");
   write_out<TM, TN>(g, acc, (wave < 2 ? stage0 : stage1) + (wave & 1) * kEpiStageBytes<TM, TN>, m0, n0, split);
-  CHN_TS(5);
 }
 
 template <typename T, bool A_KC, bool B_KC>
