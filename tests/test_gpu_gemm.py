@@ -70,28 +70,57 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
     assert np.array_equal(out, ref)
 
 
-@pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-@pytest.mark.parametrize("shape", [(3704, 3592, 192), (3704, 3592, 64), (3720, 3592, 448), (3704, 3592, 200), (3720, 3592, 1000)])
-def test_gemm_big_tiles_direct_copy(dt, layout, shape):
+# The planner takes the 256x256 tile only when K is long enough to pay for its fixed cost; the short-K
+# cases (one, two, three tile steps: where a pipeline's prologue and tail go wrong) run in a child
+# process that forces the tile through the library's tuning variable CHN_GEMM_TILE.
+DIRECT_COPY_CASES = [("bf16", s) for s in [(3704, 3592, 1024), (3720, 3592, 1000), (3704, 3592, 1088)]] + \
+                    [("f32", s) for s in [(3704, 3592, 1000), (3720, 3592, 1024), (3704, 3592, 1056)]]
+DIRECT_COPY_SHORT_K = [("bf16", s) for s in [(3704, 3592, 192), (3704, 3592, 64), (3720, 3592, 128), (3704, 3592, 200), (520, 264, 448)]] + \
+                      [("f32", s) for s in [(3704, 3592, 32), (3720, 3592, 64), (1032, 520, 100)]]
+
+
+def direct_copy_case(dt, layout, shape):
     # every unit-stride extent a multiple of 16 bytes: the 256x256 kernel that copies its operands
-    # straight into LDS; an odd and an even number of tile steps, a single one, K with and without a
-    # ragged last step, ragged last tiles in M and N
+    # straight into LDS; odd and even numbers of tile steps, K with and without a ragged last step,
+    # ragged last tiles in M and N; exact small integers, bit for bit
     M, N, K = shape
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt, gen)
     direct = not (dt == "f32" and layout == "tn")     # fp32 with both operands stored along M/N: register-staged
-    assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, direct)
+    assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, direct), (dt, layout, shape)
     out = host(B.gemm(Ad, Bd, empty((M, N))))
     ref = A.astype(np.float64) @ Bm.astype(np.float64)
     rows = RNG.integers(0, M, 24)
     assert np.array_equal(O.gemm(A[rows], Bm), ref[rows])
-    assert np.array_equal(out, ref)
+    assert np.array_equal(out, ref), (dt, layout, shape)
+
+
+@pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("dt,shape", DIRECT_COPY_CASES)
+def test_gemm_big_tiles_direct_copy(dt, layout, shape):
+    direct_copy_case(dt, layout, shape)
+
+
+def test_gemm_big_tiles_direct_copy_short_k_forced_tile():
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, CHN_GEMM_TILE="2", PYTHONPATH=root)
+    code = ("import tests.test_gpu_gemm as t\n"
+            "n = 0\n"
+            "for dt, shape in t.DIRECT_COPY_SHORT_K:\n"
+            "    for layout in ('nt', 'nn', 'tn'):\n"
+            "        print(dt, layout, shape, flush=True)\n"
+            "        t.direct_copy_case(dt, layout, shape)\n"
+            "        n += 1\n"
+            "print('cases passed:', n)\n")
+    r = subprocess.run([sys.executable, "-u", "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
+    assert "cases passed: %d" % (3 * len(DIRECT_COPY_SHORT_K)) in r.stdout
 
 
 def test_gemm_direct_copy_odd_k_both_transposed():
     # with both operands stored along M / N, K itself needs no alignment for the direct-copy kernel
-    M, N, K = 3720, 3592, 203
+    M, N, K = 3720, 3592, 1003
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
     A, Bm, Ad, Bd = operands(M, N, K, "tn", "bf16", gen)
     assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, True)
@@ -196,7 +225,7 @@ def test_gemm_direct_copy_epilogues(dt, cdt, layout):
     # (vector path), a ragged last tile in M (rows past the end) and in N (element-wise path)
     if dt == "f32" and layout == "tn":
         pytest.skip("fp32 with both operands stored along M/N takes the register-staged kernel")
-    M, N, K = 3720, 3592, 192
+    M, N, K = 3720, 3592, 1000      # (long enough for the planner to take the 256x256 tile)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
     assert B.gemm_plan(Ad, Bd, empty((M, N), cdt))[:2] == (2, True)
     tol = TOL_BF16 if cdt == "bf16" else TOL_SUM
