@@ -921,14 +921,6 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
   const int r = lane & 31, h = lane >> 5;
 
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
   std::conditional_t<A_KC || !kBf16, KcReader<T>, TrReader> ra;
   std::conditional_t<B_KC || !kBf16, KcReader<T>, TrReader> rb;
   ra.init(wm * TM, lane, 0);
@@ -954,6 +946,15 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
     lb.issue(k_of(kt0), stage0 + A_BYTES);
     if constexpr (!(A_DMA && B_DMA)) lb.issue(k_of(kt0 + 1), stage1 + A_BYTES);   // (else: in the first step's k-step 0)
   } else { lb.issue(k_of(kt0)); lb.store(stage0 + A_BYTES); }
+  // (the accumulators are cleared while the first copies are in flight)
+  __builtin_amdgcn_sched_barrier(0);
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
   Frags<TM, TN> f0, f1;
