@@ -318,3 +318,50 @@ def test_gemm_bf16_copy_epilogue_is_an_sgd_update(shape, layout):
         B.gemm(Ad, Bd, Wd, epilogue="bf16_copy")                                   # needs preact_out
     with pytest.raises(B.ChnError):
         B.gemm(Ad, Bd, empty((M, N), "bf16"), epilogue="bf16_copy", preact_out=low)  # C must be fp32
+
+
+def test_gemm_random_shapes_exact_integers():
+    # a seeded sweep over dtypes, layouts, ragged and aligned sizes, epilogues, beta and C dtypes with
+    # small-integer operands: every sum is exact in fp32, so whatever kernel, tile and K split the
+    # planner picks the result must equal the fp64 product bit for bit (after C's own rounding)
+    rng = np.random.default_rng(1908_00213)
+    for it in range(120):
+        dt = rng.choice(["bf16", "f32"])
+        lay = rng.choice(["nt", "nn", "tn", "tt"])
+        m8 = 8 if dt == "bf16" else 4
+        M, N, K = (int(rng.integers(1, 160)) * m8 for _ in range(3))
+        if rng.random() < 0.3:
+            K = int(rng.integers(1, 2000))
+        if rng.random() < 0.2:
+            M = int(rng.integers(1, 1200))
+        if rng.random() < 0.2:
+            N = int(rng.integers(1, 1200))
+        cdt = "f32" if dt == "f32" else rng.choice(["bf16", "f32"])
+        gen = lambda s: rng.integers(-3, 4, size=s).astype(np.float32)
+        a = gen((M, K)) if lay[0] == "n" else gen((K, M))
+        b = gen((K, N)) if lay[1] == "n" else gen((N, K))
+        A, Bm = (a if lay[0] == "n" else a.T), (b if lay[1] == "n" else b.T)
+        Ad = dev(a, dt) if lay[0] == "n" else dev(a, dt).t()
+        Bd = dev(b, dt) if lay[1] == "n" else dev(b, dt).t()
+        ref = A.astype(np.float64) @ Bm.astype(np.float64)
+        c0 = gen((M, N))
+        Cd = dev(c0, cdt)
+        epi = rng.choice(["none", "bias", "bias_relu", "relu_bwd", "beta"])
+        kw = {}
+        if epi in ("bias", "bias_relu"):
+            bias = gen((N,))
+            kw = dict(epilogue=epi, bias=dev(bias))
+            ref = ref + bias
+            if epi == "bias_relu":
+                ref = np.maximum(ref, 0)
+        elif epi == "relu_bwd":
+            aux = gen((M, N))
+            kw = dict(epilogue=epi, aux=dev(aux, cdt))
+            ref = np.where(aux > 0, ref, 0.0)
+        elif epi == "beta":
+            kw = dict(alpha=2.0, beta=-1.0)
+            ref = 2.0 * ref - c0
+        need = B.gemm_workspace_bytes(Ad, Bd, Cd)
+        out = host(B.gemm(Ad, Bd, Cd, ws=ws(need) if need else None, **kw))
+        want = bf16r(ref.astype(np.float32)).astype(np.float64) if cdt == "bf16" else ref
+        assert np.array_equal(out, want), (it, dt, cdt, lay, (M, N, K), epi, B.gemm_plan(Ad, Bd, Cd, need > 0))
