@@ -537,8 +537,17 @@ static __global__ __launch_bounds__(256) void gemm_splitk_finish_kernel(GemmArgs
   if (col >= g.N) return;
   const int64_t slab = (int64_t)g.M * g.ldp;
   const float *p = g.partial + (int64_t)row * g.ldp + col;
+  // slabs are read eight at a time (all loads of a batch in flight together; slabs past the last one
+  // read zeros) and added in split order, so the sum does not depend on the batching
+  const uintptr_t zero = reinterpret_cast<uintptr_t>(&kZeroChunk);
   f32x4 a = global_load<f32x4>(reinterpret_cast<uintptr_t>(p));
-  for (int s = 1; s < g.splits; ++s) a += global_load<f32x4>(reinterpret_cast<uintptr_t>(p + s * slab));
+  for (int s0 = 1; s0 < g.splits; s0 += 8) {
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = global_load<f32x4>(s0 + u < g.splits ? reinterpret_cast<uintptr_t>(p + (s0 + u) * slab) : zero);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a += v[u];
+  }
   if (g.epi_vec && col + 4 <= g.N) {
     finish4(g, row, col, a, epi_fetch(g, row, col));
   } else {
