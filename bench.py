@@ -195,6 +195,56 @@ def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False):
             "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
 
 
+def bench_tape(torch, W, timer, quick):
+    """The same training steps issued by the define-by-run tape instead of a recorded call list:
+    graph recorded during the forward code, walked back, released, optimiser -- every iteration."""
+    from paper_1908_00213_amd import tape as T
+    F = T.backend()
+    res = {}
+
+    def mlp(w, lowp, steps, warmup):
+        model = T.MLP([(F.from_numpy(Wm), F.from_numpy(b)) for Wm, b in w.params], w.act, lowp)
+        opt = T.SGD(model.params(), w.lr)
+        xs = [F.from_numpy(x, "bf16" if lowp else None) for x in w.xs]
+        ts = [F.from_numpy(t) for t in w.ts]
+        k, last = [0], [None]
+
+        def fn():
+            opt.cleargrads()
+            loss = model.loss(xs[k[0] % len(xs)], ts[k[0] % len(xs)])
+            loss.backward()
+            opt.update()
+            last[0] = loss.array
+            k[0] += 1
+        s = timer.time(fn, steps, warmup)
+        return {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(last[0].cpu()),
+                "TFLOP/s": w.flops_per_step() / s / 1e12}
+
+    res["cfg5_wide_mlp_bf16"] = mlp(W.config5(n_batches=4), True, 20, 3)
+    torch.cuda.empty_cache()
+    if quick:
+        return res
+    res["cfg3_mlp_f32"] = mlp(W.config3(), False, 100, 10)
+    res["cfg3_mlp_bf16"] = mlp(W.config3(), True, 100, 10)
+    res["cfg1_tiny_mlp_f32"] = mlp(W.config1(), False, 200, 20)
+    w = W.config4()
+    model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()})
+    opt = T.SGD(model.params(), w.lr)
+    ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
+    last = [None]
+
+    def fn():
+        opt.cleargrads()
+        loss, _ = model.loss(ids, tg, w.bptt)
+        loss.backward()
+        opt.update()
+        last[0] = loss.array
+    s = timer.time(fn, 10, 2)
+    res["cfg4_lstm_lm_f32"] = {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s,
+                               "loss": float(last[0].cpu())}
+    return res
+
+
 def traffic_driver(torch, B, W):
     """What `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` are pointed at: three rounds of a 256 MiB
     fp32 copy through chn_elementwise_broadcast (the calibration launch: reads and writes exactly
@@ -243,7 +293,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--workloads", default="1,2,3,4", help="which of the secondary workloads to run (comma list)")
+    ap.add_argument("--workloads", default="1,2,3,4,tape",
+                    help="which of the secondary workloads to run (comma list; `tape` = the steps driven by the define-by-run tape)")
     ap.add_argument("--separate-update", action="store_true",
                     help="headline workload: write the weight gradients and update in a separate SGD launch "
                          "instead of updating in the epilogue of the weight-gradient products (about 1 %% slower)")
@@ -320,6 +371,12 @@ def main():
             log("  %s%.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s (%.1f%% of fp32 MFMA peak; %d launches/step)" % (
                 "HIP graph: " if graph else "", r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"],
                 100 * r["frac_mfma_peak_f32"], r["launch_calls_per_step"]))
+
+    if "tape" in sel:
+        log("define-by-run tape driving the same steps")
+        extra["tape"] = bench_tape(torch, W, timer, False)
+        for k, r in extra["tape"].items():
+            log("  %s: %.3f ms/step  %.1f steps/s" % (k, r["ms_per_step"], r["steps_per_s"]))
 
     cpu = None
     if not args.no_cpu:

@@ -97,12 +97,12 @@ def desc(t):
     if isinstance(t, ChnArray):
         return t
     a = ChnArray()
-    a.data = t.data_ptr()
-    a.ndim = t.dim()
+    n = t.dim()
     isz = t.element_size()
-    for d in range(t.dim()):
-        a.shape[d] = t.shape[d]
-        a.strides[d] = t.stride(d) * isz
+    a.data = t.data_ptr()
+    a.ndim = n
+    a.shape[:n] = t.shape
+    a.strides[:n] = [s * isz for s in t.stride()]
     a.dtype = _DTYPES[t.dtype]
     return a
 

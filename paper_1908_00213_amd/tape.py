@@ -1,0 +1,875 @@
+"""Define-by-run tape: the backtracking graph is recorded while the forward code runs.
+
+Section "On Demand Graph Construction": every differentiable operation applied to variables records
+a *function node* that references the *variable nodes* of its inputs; each output's variable node
+references the function node that made it.  The graph says nothing about the forward computation
+(plain Python does that, so control flow may change from one iteration to the next); it only tells
+``backward`` how to walk back: function nodes are visited once each in reverse topological order.
+
+Memory (Sections "Global Memory Usage Reduction" and "Function-wise Local Memory Usage Reduction"):
+
+* the user-facing :class:`Variable` owns its array; the :class:`VariableNode` in the graph refers to
+  the array only while some function has declared that its backward needs it (``retain_inputs`` /
+  ``retain_outputs``).  A function that can differentiate from its outputs (ReLU, the LSTM cell)
+  retains those and lets its inputs go; one that needs nothing (addition) retains nothing;
+* ``backward`` cuts every function node out of the graph right after calling its backward, so plain
+  reference counting returns the buffers of everything behind it at once -- no collector pass;
+* gradients of intermediate variables are dropped as soon as they have been consumed.
+
+All arithmetic happens in the library behind the C ABI: each function's forward and backward is a
+handful of calls on a *backend* object whose methods carry the names of the entry points
+(``gemm``, ``elementwise_broadcast``, ``reduce_axis``, ``lstm_fwd`` ...).  :class:`GpuBackend` routes
+them to the binding (PyTorch is the allocator, nothing more) and refuses to work without the built
+library.  Host-logic tests drive the same tape with a backend of their own.
+"""
+import heapq
+import itertools
+import weakref
+
+__all__ = ["Variable", "Parameter", "VariableNode", "FunctionNode", "GpuBackend", "using_backend",
+           "no_backprop_mode", "linear", "matmul", "relu", "gelu", "add", "softmax_cross_entropy",
+           "embed_id", "lstm", "split_rows", "concat_rows", "Linear", "SGD", "live_function_nodes",
+           "MLP", "LSTMLanguageModel"]
+
+
+# ---- backend ----------------------------------------------------------------------------------------
+class GpuBackend:
+    """Routes the tape's kernel calls to libchn through the binding; arrays are CUDA tensors."""
+
+    def __init__(self):
+        import torch
+        from . import binding
+        binding.lib()                       # fails loudly when the library has not been built
+        self.torch, self.B = torch, binding
+        self._dt = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
+        self._name = {v: k for k, v in self._dt.items()}
+        self._gemm_ws = None
+
+    # allocation (PyTorch's caching allocator; freed by reference count, reused in stream order)
+    def empty(self, shape, dtype="f32"):
+        return self.torch.empty(tuple(shape), dtype=self._dt[dtype], device="cuda")
+
+    def dtype(self, a):
+        return self._name[a.dtype]
+
+    def from_numpy(self, a, dtype=None):
+        import numpy as np
+        t = self.torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        return t if dtype is None else t.to(self._dt[dtype])
+
+    def to_numpy(self, a):
+        return a.detach().to(self.torch.float64 if a.is_floating_point() else a.dtype).cpu().numpy()
+
+    def _bytes(self, n):
+        return None if n == 0 else self.torch.empty(n, dtype=self.torch.uint8, device="cuda")
+
+    # kernels: same names and argument order as the binding
+    def gemm(self, A, Bm, Cm, alpha=1.0, beta=0.0, epilogue="none", bias=None, aux=None, preact_out=None):
+        A, Bm, Cm = self.B.desc(A), self.B.desc(Bm), self.B.desc(Cm)     # marshalled once for both calls
+        need = self.B.gemm_workspace_bytes(A, Bm, Cm)
+        if need and (self._gemm_ws is None or self._gemm_ws.numel() < need):
+            self._gemm_ws = self._bytes(need)   # the old one stays valid for launches already queued
+        return self.B.gemm(A, Bm, Cm, alpha, beta, epilogue, bias, aux, preact_out,
+                           ws=self._gemm_ws if need else None)
+
+    def elementwise_broadcast(self, op, inputs, out, scalars=()):
+        return self.B.elementwise_broadcast(op, inputs, out, scalars)
+
+    def reduce_axis(self, op, x, axis, out):
+        return self.B.reduce_axis(op, x, axis, out, ws=self._bytes(self.B.reduce_axis_workspace_bytes(x, axis)))
+
+    def lstm_fwd(self, z, bias, c_prev, c, h, gates):
+        self.B.lstm_fwd(z, bias, c_prev, c, h, gates)
+
+    def lstm_bwd(self, gates, c_prev, c, dh, dc_next, dz, dc_prev):
+        self.B.lstm_bwd(gates, c_prev, c, dh, dc_next, dz, dc_prev)
+
+    def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
+        ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
+        self.B.softmax_ce_fwd(logits, labels, loss_mean, None, lse, ignore_label, ws)
+
+    def softmax_ce_bwd(self, logits, labels, dlogits, lse, upstream, ignore_label):
+        ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
+        self.B.softmax_ce_bwd(logits, labels, dlogits, lse, upstream, ignore_label, ws)
+
+    def embed_fwd(self, table, ids, out):
+        self.B.embed_fwd(table, ids, out)
+
+    def embed_bwd(self, ids, dout, dtable, accumulate):
+        self.B.embed_bwd(ids, dout, dtable, accumulate)
+
+    def sgd_update_multi(self, params, grads, lr, lowp_copies):
+        self.B.sgd_update_multi(params, grads, lr, lowp_copies)
+
+
+_backend = None
+
+
+def backend():
+    global _backend
+    if _backend is None:
+        _backend = GpuBackend()
+    return _backend
+
+
+class using_backend:
+    """``with using_backend(b):`` -- run the tape on another backend (tests of the host logic)."""
+
+    def __init__(self, b):
+        self.b = b
+
+    def __enter__(self):
+        global _backend
+        self.prev, _backend = _backend, self.b
+        return self.b
+
+    def __exit__(self, *exc):
+        global _backend
+        _backend = self.prev
+
+
+_record = True
+
+
+class no_backprop_mode:
+    """Inside the block no function node is recorded (pure forward evaluation)."""
+
+    def __enter__(self):
+        global _record
+        self.prev, _record = _record, False
+
+    def __exit__(self, *exc):
+        global _record
+        _record = self.prev
+
+
+# ---- graph objects ----------------------------------------------------------------------------------
+class VariableNode:
+    """A variable's place in the backtracking graph.
+
+    Holds the creator function node, the topological rank, and -- only while a function has asked
+    for it -- the array (Section "Function-wise Local Memory Usage Reduction").  The gradient that
+    back-propagation delivers lives here too, so the user handle can be dropped at any time.
+    """
+    __slots__ = ("creator", "rank", "requires_grad", "data", "grad", "_grad_owned", "_retainers", "name",
+                 "__weakref__")
+
+    def __init__(self, requires_grad, name=None):
+        self.creator = None
+        self.rank = 0
+        self.requires_grad = requires_grad
+        self.data = None
+        self.grad = None
+        self._grad_owned = False
+        self._retainers = 0
+        self.name = name
+
+    def _retain(self, array):
+        self.data = array
+        self._retainers += 1
+
+    def _release(self):
+        self._retainers -= 1
+        if self._retainers <= 0:
+            self._retainers = 0
+            self.data = None
+
+
+class Variable:
+    """User handle: owns the array, points at its node (Section "Global Memory Usage Reduction":
+    the array of an intermediate result is returned as soon as the handle is dropped unless a
+    function retained it)."""
+
+    def __init__(self, array, requires_grad=True, name=None):
+        self.array = array
+        self.node = VariableNode(requires_grad, name)
+
+    shape = property(lambda self: self.array.shape)
+    creator = property(lambda self: self.node.creator)
+    requires_grad = property(lambda self: self.node.requires_grad)
+
+    @property
+    def grad(self):
+        return self.node.grad
+
+    @grad.setter
+    def grad(self, g):
+        self.node.grad = g
+        self.node._grad_owned = False
+
+    def cleargrad(self):
+        self.grad = None
+
+    def unchain(self):
+        """Forget how this variable was computed (truncates back-propagation here)."""
+        self.node.creator = None
+        self.node.rank = 0
+
+    def backward(self, retain_grad=False):
+        _backward(self, retain_grad)
+
+
+class Parameter(Variable):
+    """A leaf variable that persists across iterations: fp32 master array, optionally a bf16
+    working copy (``lowp``) that the optimiser refreshes and that products read instead."""
+
+    def __init__(self, array, lowp=None, name=None):
+        super().__init__(array, True, name)
+        self.lowp = lowp
+
+    @property
+    def compute_array(self):
+        return self.array if self.lowp is None else self.lowp
+
+
+_live = weakref.WeakSet()
+
+
+def live_function_nodes():
+    """Number of function nodes still chained into some graph (0 after a full backward)."""
+    return sum(1 for f in _live if f.inputs is not None)
+
+
+class FunctionNode:
+    """One applied operation.  Subclasses give ``forward(xs) -> tuple of arrays`` and
+    ``backward(indexes, gys) -> tuple of arrays or None, one per index``; inside ``forward`` they
+    declare what backward will need with ``retain_inputs`` / ``retain_outputs`` -- everything else
+    is let go when the forward returns.
+
+    ``fresh``: positions of inputs whose gradient, as returned by ``backward``, is always a newly
+    allocated array nobody else refers to (the tape may then accumulate into it in place).
+    """
+    fresh = ()
+
+    def __init__(self):
+        self.inputs = None            # tuple of VariableNode (strong references)
+        self.outputs = None           # tuple of weak references to VariableNode
+        self.rank = 0
+        self._retain_in = ()
+        self._retain_out = ()
+        self._out_data = None
+
+    # -- declarations made inside forward
+    def retain_inputs(self, indexes):
+        self._retain_in = tuple(indexes)
+
+    def retain_outputs(self, indexes):
+        self._retain_out = tuple(indexes)
+
+    # -- what backward may look at
+    def get_retained_inputs(self):
+        return tuple(self.inputs[i].data for i in self._retain_in)
+
+    def get_retained_outputs(self):
+        return self._out_data
+
+    def apply(self, inputs):
+        """Run forward on the inputs' arrays, wrap the results, and record this node if any
+        input takes part in back-propagation."""
+        inputs = tuple(x if isinstance(x, Variable) else Variable(x, requires_grad=False) for x in inputs)
+        self.in_vars = inputs                # compute_array lookups inside forward; dropped below
+        outs = self.forward(tuple(x.array for x in inputs))
+        self.in_vars = None
+        record = _record and any(x.node.requires_grad for x in inputs)
+        ys = tuple(Variable(a, requires_grad=record) for a in outs)
+        if record:
+            self.inputs = tuple(x.node for x in inputs)
+            self.rank = max(n.rank for n in self.inputs)
+            for y in ys:
+                y.node.creator = self
+                y.node.rank = self.rank + 1
+            self.outputs = tuple(weakref.ref(y.node) for y in ys)
+            for i in self._retain_in:
+                inputs[i].node._retain(self._input_array(inputs[i]))
+            self._out_data = tuple(outs[i] for i in self._retain_out)
+            _live.add(self)
+        else:
+            self._retain_in, self._retain_out = (), ()
+            self.release_locals()
+        return ys
+
+    def _input_array(self, var):
+        return var.array
+
+    def release_locals(self):
+        """Drop arrays the subclass stashed for its backward (called when the node is cut out)."""
+
+    def unchain(self):
+        """Cut this node out of the graph: outputs forget their creator, inputs lose the reference
+        that kept them alive, retained arrays are let go."""
+        if self.inputs is None:
+            return
+        for ref in self.outputs:
+            n = ref()
+            if n is not None and n.creator is self:
+                n.creator = None
+        for i in self._retain_in:
+            self.inputs[i]._release()
+        self.inputs = None
+        self.outputs = None
+        self._out_data = None
+        self.release_locals()
+
+    def forward(self, xs):
+        raise NotImplementedError
+
+    def backward(self, indexes, gys):
+        raise NotImplementedError
+
+
+def _accumulate(node, g, fresh):
+    """node.grad += g; in place only into an array the tape itself owns."""
+    if node.grad is None:
+        node.grad, node._grad_owned = g, fresh
+        return
+    F = backend()
+    if node._grad_owned:
+        F.elementwise_broadcast("add", [node.grad, g], node.grad)
+    elif fresh:
+        F.elementwise_broadcast("add", [g, node.grad], g)
+        node.grad, node._grad_owned = g, True
+    else:
+        out = F.empty(g.shape, F.dtype(g))
+        F.elementwise_broadcast("add", [node.grad, g], out)
+        node.grad, node._grad_owned = out, True
+
+
+def _backward(root, retain_grad):
+    """Backtrack from `root` (Section "On Demand Graph Construction"): function nodes in order of
+    decreasing rank, each exactly once; each is cut out of the graph as soon as it has run
+    (Section "Global Memory Usage Reduction"), and gradients of intermediate variables are dropped
+    once consumed unless `retain_grad`."""
+    F = backend()
+    rn = root.node
+    if rn.grad is None:
+        n = 1
+        for s in root.shape:
+            n *= s
+        if n != 1:
+            raise ValueError("backward() from a non-scalar needs its .grad set first")
+        one = F.empty(root.shape, F.dtype(root.array))
+        F.elementwise_broadcast("fill", [], one, (1.0,))
+        rn.grad, rn._grad_owned = one, True
+        rn_unit = True
+    else:
+        rn_unit = False
+    if rn.creator is None:
+        return
+    tie = itertools.count()
+    heap, waiting = [], {}
+
+    def push(node):
+        # the entry holds the node: once its consumers are cut out nothing else would keep an
+        # intermediate result's node -- and the gradient stored on it -- alive
+        f = node.creator
+        held = waiting.get(id(f))
+        if held is None:
+            waiting[id(f)] = [node]
+            heapq.heappush(heap, (-f.rank, next(tie), f))
+        else:
+            held.append(node)
+
+    push(rn)
+    while heap:
+        _, _, f = heapq.heappop(heap)
+        held = waiting[id(f)]            # stays registered while f runs: f is visited once
+        outs = [ref() for ref in f.outputs]
+        gys = tuple(None if o is None else o.grad for o in outs)
+        f.unit_seed = rn_unit and len(outs) == 1 and outs[0] is rn
+        if not retain_grad:
+            for o in outs:
+                if o is not None and o is not rn:
+                    o.grad, o._grad_owned = None, False
+        indexes = tuple(i for i, n in enumerate(f.inputs) if n.requires_grad)
+        # slots a function may accumulate into directly (a product can add into its output)
+        slots = f.grad_slots = tuple(f.inputs[i].grad if f.inputs[i]._grad_owned else None for i in indexes)
+        gxs = f.backward(indexes, gys)
+        f.grad_slots = None
+        if len(gxs) != len(indexes):
+            raise RuntimeError("%s.backward returned %d gradients for %d inputs"
+                               % (type(f).__name__, len(gxs), len(indexes)))
+        for i, gx, slot in zip(indexes, gxs, slots):
+            if gx is None:
+                continue
+            n = f.inputs[i]
+            if slot is None or gx is not slot:      # else: the function added into the slot itself
+                _accumulate(n, gx, i in f.fresh)
+            if n.creator is not None:
+                push(n)
+        del gys, gxs, outs, held
+        waiting[id(f)] = None
+        f.unchain()
+
+
+# ---- functions ----------------------------------------------------------------------------------------
+def _t(a):
+    return a.T
+
+
+class LinearFunction(FunctionNode):
+    """y = act(x @ W.T + b), W of shape (n_out, n_in) as in the model-definition figure (Section
+    "API Design"); bias and activation run in the product's epilogue.  Retains x and W; ReLU is
+    differentiated from the retained *output*, GELU from the pre-activation the epilogue stores."""
+    fresh = (0, 1, 2)
+
+    def __init__(self, act=None, out_dtype=None):
+        super().__init__()
+        self.act, self.out_dtype, self.z = act, out_dtype, None
+
+    def _input_array(self, var):
+        return var.compute_array if isinstance(var, Parameter) else var.array
+
+    def forward(self, xs):
+        F = backend()
+        x, _, b = xs
+        W = self._input_array(self.in_vars[1])
+        dt = self.out_dtype or F.dtype(x)
+        y = F.empty((x.shape[0], W.shape[0]), dt)
+        if self.act == "gelu":
+            self.z = F.empty(y.shape, dt)
+        epi = {None: "bias", "relu": "bias_relu", "gelu": "bias_gelu"}[self.act]
+        F.gemm(x, _t(W), y, epilogue=epi, bias=b, preact_out=self.z)
+        self.retain_inputs((0, 1))
+        if self.act == "relu":
+            self.retain_outputs((0,))
+        return (y,)
+
+    def release_locals(self):
+        self.z = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        x, W = self.get_retained_inputs()
+        gy, = gys
+        if self.act is not None:
+            ref = self.get_retained_outputs()[0] if self.act == "relu" else self.z
+            gz = F.empty(gy.shape, F.dtype(gy))
+            F.elementwise_broadcast(self.act + "_bwd", [gy, ref], gz)
+            gy = gz
+        out = []
+        for k, i in enumerate(indexes):
+            if i == 0:
+                gx = F.empty(x.shape, F.dtype(x))
+                F.gemm(gy, W, gx)
+            elif i == 1:
+                gx = self.grad_slots[k]
+                if gx is None:
+                    gx = F.empty(W.shape, "f32")
+                    F.gemm(_t(gy), x, gx)
+                else:
+                    F.gemm(_t(gy), x, gx, beta=1.0)
+            else:
+                gx = F.empty((gy.shape[1],), "f32")
+                F.reduce_axis("sum", gy, 0, gx)
+            out.append(gx)
+        return tuple(out)
+
+
+class MatMul(FunctionNode):
+    """y = x @ W (both 2-d); retains both inputs."""
+    fresh = (0, 1)
+
+    def _input_array(self, var):
+        return var.compute_array if isinstance(var, Parameter) else var.array
+
+    def forward(self, xs):
+        F = backend()
+        x = xs[0]
+        W = self._input_array(self.in_vars[1])
+        y = F.empty((x.shape[0], W.shape[1]), F.dtype(x))
+        F.gemm(x, W, y)
+        self.retain_inputs((0, 1))
+        return (y,)
+
+    def backward(self, indexes, gys):
+        F = backend()
+        x, W = self.get_retained_inputs()
+        gy, = gys
+        out = []
+        for k, i in enumerate(indexes):
+            if i == 0:
+                gx = F.empty(x.shape, F.dtype(x))
+                F.gemm(gy, _t(W), gx)
+            else:
+                gx = self.grad_slots[k]
+                if gx is None:
+                    gx = F.empty(W.shape, "f32")
+                    F.gemm(_t(x), gy, gx)
+                else:
+                    F.gemm(_t(x), gy, gx, beta=1.0)
+            out.append(gx)
+        return tuple(out)
+
+
+class _Activation(FunctionNode):
+    fresh = (0,)
+    op = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        ref = self.saved()
+        gx = F.empty(ref.shape, F.dtype(gys[0]))
+        F.elementwise_broadcast(self.op + "_bwd", [gys[0], ref], gx)
+        return (gx,)
+
+
+class ReLU(_Activation):
+    """Differentiated from its output: the input is not retained (Section "Function-wise Local
+    Memory Usage Reduction")."""
+    op = "relu"
+
+    def forward(self, xs):
+        F = backend()
+        y = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("relu", [xs[0]], y)
+        self.retain_outputs((0,))
+        return (y,)
+
+    def saved(self):
+        return self.get_retained_outputs()[0]
+
+
+class GELU(_Activation):
+    """x * Phi(x); its derivative needs the input, so that is what it retains."""
+    op = "gelu"
+
+    def forward(self, xs):
+        F = backend()
+        y = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("gelu", [xs[0]], y)
+        self.retain_inputs((0,))
+        return (y,)
+
+    def saved(self):
+        return self.get_retained_inputs()[0]
+
+
+class Add(FunctionNode):
+    """x + y with NumPy broadcasting of y's leading axes (a bias); retains nothing."""
+
+    def forward(self, xs):
+        F = backend()
+        x, y = xs
+        self.bias_like = tuple(y.shape) != tuple(x.shape)
+        if self.bias_like and (len(y.shape) != 1 or y.shape[0] != x.shape[-1] or len(x.shape) != 2):
+            raise ValueError("add: second operand must match the first or be its row-shaped bias")
+        out = F.empty(x.shape, F.dtype(x))
+        F.elementwise_broadcast("add", [x, y], out)
+        return (out,)
+
+    def backward(self, indexes, gys):
+        F = backend()
+        out = []
+        for i in indexes:
+            if i == 1 and self.bias_like:
+                g = F.empty((gys[0].shape[1],), "f32")
+                F.reduce_axis("sum", gys[0], 0, g)
+                out.append(g)
+            else:
+                out.append(gys[0])
+        return tuple(out)
+
+
+class SoftmaxCrossEntropy(FunctionNode):
+    """Mean softmax cross-entropy of (N,C) logits against integer labels.  Retains the logits and
+    keeps the per-row log-sum-exp the forward kernel produced, so the backward is one pass."""
+    fresh = (0,)
+
+    def __init__(self, ignore_label=-1, grad_dtype=None):
+        super().__init__()
+        self.ignore_label, self.grad_dtype, self.lse, self.labels = ignore_label, grad_dtype, None, None
+
+    def forward(self, xs):
+        F = backend()
+        logits, labels = xs
+        loss = F.empty((), "f32")
+        self.lse = F.empty((logits.shape[0],), "f32")
+        self.labels = labels
+        F.softmax_ce_fwd(logits, labels, loss, self.lse, self.ignore_label)
+        self.retain_inputs((0,))
+        return (loss,)
+
+    def release_locals(self):
+        self.lse = self.labels = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        logits, = self.get_retained_inputs()
+        g = F.empty(logits.shape, self.grad_dtype or F.dtype(logits))
+        F.softmax_ce_bwd(logits, self.labels, g, self.lse, 1.0, self.ignore_label)
+        if not self.unit_seed:                 # an upstream factor other than the implicit 1
+            F.elementwise_broadcast("mul", [g, gys[0]], g)
+        return tuple(g if i == 0 else None for i in indexes)
+
+
+class EmbedID(FunctionNode):
+    """out[n] = table[ids[n]]; the backward scatters rows back (a dense gradient of the table,
+    summed in a fixed order).  Retains nothing but the ids."""
+    fresh = (1,)
+
+    def forward(self, xs):
+        F = backend()
+        ids, table = xs
+        self.ids, self.table_shape = ids, tuple(table.shape)
+        out = F.empty((ids.shape[0], table.shape[1]), F.dtype(table))
+        F.embed_fwd(table, ids, out)
+        return (out,)
+
+    def release_locals(self):
+        self.ids = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        out = []
+        for k, i in enumerate(indexes):
+            if i != 1:
+                out.append(None)
+                continue
+            g = self.grad_slots[k]
+            if g is None:
+                g = F.empty(self.table_shape, "f32")
+                F.embed_bwd(self.ids, gys[0], g, False)
+            else:
+                F.embed_bwd(self.ids, gys[0], g, True)
+            out.append(g)
+        return tuple(out)
+
+
+class LSTM(FunctionNode):
+    """(c_prev, z[, bias]) -> (c, h): the cell of the recurrent language model; z holds the four
+    gate pre-activations.  Backward works from retained outputs: the activated gates the forward
+    kernel stored, c_prev and c."""
+    fresh = (0, 1, 2)
+
+    def forward(self, xs):
+        F = backend()
+        c_prev, z = xs[0], xs[1]
+        bias = xs[2] if len(xs) > 2 else None
+        c = F.empty(c_prev.shape, "f32")
+        h = F.empty(c_prev.shape, "f32")
+        self.gates = F.empty(z.shape, "f32")
+        F.lstm_fwd(z, bias, c_prev, c, h, self.gates)
+        self.retain_inputs((0,))
+        self.retain_outputs((0,))
+        return (c, h)
+
+    def release_locals(self):
+        self.gates = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        c_prev, = self.get_retained_inputs()
+        c, = self.get_retained_outputs()
+        gc, gh = gys
+        if gh is None:
+            gh = F.empty(c.shape, "f32")
+            F.elementwise_broadcast("fill", [], gh, (0.0,))
+        dz = F.empty(self.gates.shape, "f32")
+        dc_prev = F.empty(c.shape, "f32")
+        F.lstm_bwd(self.gates, c_prev, c, gh, gc, dz, dc_prev)
+        out = []
+        for i in indexes:
+            if i == 0:
+                out.append(dc_prev)
+            elif i == 1:
+                out.append(dz)
+            else:
+                gb = F.empty((dz.shape[1],), "f32")
+                F.reduce_axis("sum", dz, 0, gb)
+                out.append(gb)
+        return tuple(out)
+
+
+class SplitRows(FunctionNode):
+    """Cut a (n*r, d) array into n views of r rows (no copy; the views keep the buffer alive).
+    The backward gathers the pieces' gradients into one array, zero where a piece was unused."""
+    fresh = (0,)
+
+    def __init__(self, n):
+        super().__init__()
+        self.n = n
+
+    def forward(self, xs):
+        x, = xs
+        if x.shape[0] % self.n:
+            raise ValueError("split_rows: %d rows do not divide into %d pieces" % (x.shape[0], self.n))
+        r = x.shape[0] // self.n
+        self.shape, self.dt = tuple(x.shape), backend().dtype(x)
+        return tuple(x[k * r:(k + 1) * r] for k in range(self.n))
+
+    def backward(self, indexes, gys):
+        F = backend()
+        g = F.empty(self.shape, self.dt)
+        r = self.shape[0] // self.n
+        for k, gy in enumerate(gys):
+            blk = g[k * r:(k + 1) * r]
+            if gy is None:
+                F.elementwise_broadcast("fill", [], blk, (0.0,))
+            else:
+                F.elementwise_broadcast("copy", [gy], blk)
+        return (g,)
+
+
+class ConcatRows(FunctionNode):
+    """Stack equally shaped (r, d) arrays along the rows; the backward hands out views."""
+
+    def forward(self, xs):
+        F = backend()
+        r = xs[0].shape[0]
+        out = F.empty((r * len(xs),) + tuple(xs[0].shape[1:]), F.dtype(xs[0]))
+        for k, x in enumerate(xs):
+            if tuple(x.shape) != tuple(xs[0].shape):
+                raise ValueError("concat_rows: pieces differ in shape")
+            F.elementwise_broadcast("copy", [x], out[k * r:(k + 1) * r])
+        self.r = r
+        return (out,)
+
+    def backward(self, indexes, gys):
+        return tuple(gys[0][i * self.r:(i + 1) * self.r] for i in indexes)
+
+
+def linear(x, W, b, act=None, out_dtype=None):
+    return LinearFunction(act, out_dtype).apply((x, W, b))[0]
+
+
+def matmul(x, W):
+    return MatMul().apply((x, W))[0]
+
+
+def relu(x):
+    return ReLU().apply((x,))[0]
+
+
+def gelu(x):
+    return GELU().apply((x,))[0]
+
+
+def add(x, y):
+    return Add().apply((x, y))[0]
+
+
+def softmax_cross_entropy(logits, labels, ignore_label=-1, grad_dtype=None):
+    return SoftmaxCrossEntropy(ignore_label, grad_dtype).apply((logits, labels))[0]
+
+
+def embed_id(ids, table):
+    return EmbedID().apply((ids, table))[0]
+
+
+def lstm(c_prev, z, bias=None):
+    """Returns (c, h)."""
+    return LSTM().apply((c_prev, z) if bias is None else (c_prev, z, bias))
+
+
+def split_rows(x, n):
+    return SplitRows(n).apply((x,))
+
+
+def concat_rows(xs):
+    return ConcatRows().apply(tuple(xs))[0]
+
+
+# ---- links and optimiser -------------------------------------------------------------------------------
+class Linear:
+    """The Linear link of the model-definition figure: parameters W (n_out, n_in) and b (n_out,)
+    bound to the forward code ``y = x W^T + b``."""
+
+    def __init__(self, W, b, lowp=None):
+        self.W = Parameter(W, lowp, "W")
+        self.b = Parameter(b, None, "b")
+
+    def params(self):
+        return [self.W, self.b]
+
+    def __call__(self, x, act=None, out_dtype=None):
+        return linear(x, self.W, self.b, act, out_dtype)
+
+
+class SGD:
+    """param <- param - lr * grad for every parameter that received a gradient, in one call for the
+    whole set (Section "Background and Motivation": the update ends each iteration)."""
+
+    def __init__(self, params, lr):
+        self.params, self.lr = list(params), float(lr)
+
+    def cleargrads(self):
+        for p in self.params:
+            p.cleargrad()
+
+    def update(self):
+        ps = [p for p in self.params if p.grad is not None]
+        if not ps:
+            return
+        lows = [p.lowp for p in ps]
+        backend().sgd_update_multi([p.array for p in ps], [p.grad for p in ps], self.lr,
+                                   lows if any(l is not None for l in lows) else None)
+
+
+# ---- the two model families of the benchmark workloads, written as define-by-run forward code ---------
+class MLP:
+    """``l_n(act(... act(l_1(x))))`` with softmax cross-entropy on top (the model-definition figure
+    of Section "API Design", any depth).  ``params``: list of (W, b) backend arrays.
+
+    ``lowp``: bf16 working copies of the weights, bf16 activations and activation gradients; fp32
+    logits, loss, weight/bias gradients and master weights.  ``fused_activation=False`` applies the
+    activation as a function node of its own instead of in the product's epilogue.
+    """
+
+    def __init__(self, params, act="relu", lowp=False, fused_activation=True):
+        F = backend()
+        self.act, self.lowp, self.fused = act, lowp, fused_activation
+        self.layers = []
+        for W, b in params:
+            low = None
+            if lowp:
+                low = F.empty(W.shape, "bf16")
+                F.elementwise_broadcast("copy", [W], low)
+            self.layers.append(Linear(W, b, low))
+
+    def params(self):
+        return [p for l in self.layers for p in l.params()]
+
+    def __call__(self, x):
+        h = x
+        for l in self.layers[:-1]:
+            if self.fused:
+                h = l(h, act=self.act)
+            else:
+                h = (relu if self.act == "relu" else gelu)(l(h))
+        return self.layers[-1](h, out_dtype="f32")
+
+    def loss(self, x, t):
+        return softmax_cross_entropy(self(x), t, grad_dtype="bf16" if self.lowp else None)
+
+
+class LSTMLanguageModel:
+    """Embedding, one LSTM layer, output Linear layer, softmax cross-entropy over every (time,
+    batch) token; time-major rows (row t*B + b).  ``P``: dict of backend arrays E (V,E), W (E,4H),
+    U (H,4H), b (4H,), W_out (V,H), b_out (V,).  The forward code is ordinary Python: the number of
+    time steps is whatever the batch at hand has."""
+
+    def __init__(self, P):
+        self.P = {k: Parameter(v, None, k) for k, v in P.items()}
+
+    def params(self):
+        return list(self.P.values())
+
+    def loss(self, ids, targets, n_steps, state=None):
+        """ids, targets: flat (T*B,) integer arrays.  Returns (loss, (c, h)) so that a caller may
+        carry the state into the next window (after ``unchain`` for truncated back-propagation)."""
+        P, F = self.P, backend()
+        X = embed_id(ids, P["E"])
+        zs = split_rows(matmul(X, P["W"]), n_steps)
+        if state is None:
+            Bn, H = ids.shape[0] // n_steps, P["U"].shape[0]
+            z0 = F.empty((Bn, H), "f32")
+            F.elementwise_broadcast("fill", [], z0, (0.0,))
+            c = h = Variable(z0, requires_grad=False)
+        else:
+            c, h = state
+        hs = []
+        for t in range(n_steps):
+            c, h = lstm(c, add(zs[t], matmul(h, P["U"])), P["b"])
+            hs.append(h)
+        logits = linear(concat_rows(hs), P["W_out"], P["b_out"])
+        return softmax_cross_entropy(logits, targets), (c, h)

@@ -1,0 +1,87 @@
+"""A tape backend whose kernels are the CPU oracle's functions (float64 NumPy arrays).
+
+It lets the host logic of the define-by-run tape -- recording, ordering, accumulation, release --
+be tested where no GPU exists, and compared with the hand-written oracle steps.  Fresh arrays are
+filled with NaN so that a function reading a buffer nobody wrote shows up in the result.
+"""
+import numpy as np
+
+from oracle import oracle as O
+
+
+class OracleBackend:
+    def __init__(self):
+        self.calls = []                       # (name, detail) per kernel call, in issue order
+        self.live_bytes = 0
+
+    def empty(self, shape, dtype="f32"):
+        if dtype in ("i64", "i32"):
+            return np.zeros(tuple(shape), dtype=np.int64)
+        return np.full(tuple(shape), np.nan, dtype=np.float64)
+
+    def dtype(self, a):
+        return "i64" if np.issubdtype(a.dtype, np.integer) else "f32"
+
+    def from_numpy(self, a, dtype=None):
+        a = np.asarray(a)
+        return a.astype(np.int64) if np.issubdtype(a.dtype, np.integer) else a.astype(np.float64)
+
+    def to_numpy(self, a):
+        return np.asarray(a)
+
+    def gemm(self, A, Bm, Cm, alpha=1.0, beta=0.0, epilogue="none", bias=None, aux=None, preact_out=None):
+        self.calls.append(("gemm", epilogue))
+        v = O.gemm(A, Bm, Cm if beta != 0.0 else None, alpha, beta)
+        if epilogue in ("bias", "bias_relu", "bias_gelu"):
+            v = O.elementwise("add", [v, bias])
+            if preact_out is not None:
+                preact_out[...] = v
+            if epilogue != "bias":
+                v = O.elementwise(epilogue[5:], [v])
+        elif epilogue in ("relu_bwd", "gelu_bwd"):
+            v = O.elementwise(epilogue, [v, aux])
+        elif epilogue != "none":
+            raise ValueError(epilogue)
+        Cm[...] = v
+        return Cm
+
+    def elementwise_broadcast(self, op, inputs, out, scalars=()):
+        self.calls.append(("elementwise", op))
+        out[...] = O.elementwise(op, list(inputs), out.shape, scalars)
+        return out
+
+    def reduce_axis(self, op, x, axis, out):
+        self.calls.append(("reduce", op))
+        out[...] = O.reduce_axis(op, x, axis)
+        return out
+
+    def lstm_fwd(self, z, bias, c_prev, c, h, gates):
+        self.calls.append(("lstm_fwd", None))
+        c[...], h[...], gates[...] = O.lstm_fwd(z, bias, c_prev)
+
+    def lstm_bwd(self, gates, c_prev, c, dh, dc_next, dz, dc_prev):
+        self.calls.append(("lstm_bwd", None))
+        dz[...], dc_prev[...] = O.lstm_bwd(gates, c_prev, c, dh, dc_next)
+
+    def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
+        self.calls.append(("softmax_ce_fwd", None))
+        loss, _, l, _ = O.softmax_ce_fwd(logits, labels, ignore_label)
+        loss_mean[...] = loss
+        lse[...] = l
+
+    def softmax_ce_bwd(self, logits, labels, dlogits, lse, upstream, ignore_label):
+        self.calls.append(("softmax_ce_bwd", None))
+        dlogits[...] = O.softmax_ce_bwd(logits, labels, ignore_label, upstream)
+
+    def embed_fwd(self, table, ids, out):
+        self.calls.append(("embed_fwd", None))
+        out[...] = O.embed_fwd(table, ids)
+
+    def embed_bwd(self, ids, dout, dtable, accumulate):
+        self.calls.append(("embed_bwd", accumulate))
+        dtable[...] = O.embed_bwd(ids, dout, dtable.shape[0], dtable if accumulate else None)
+
+    def sgd_update_multi(self, params, grads, lr, lowp_copies):
+        self.calls.append(("sgd", len(params)))
+        for p, g in zip(params, grads):
+            p[...] = O.sgd_update(p, g, lr)

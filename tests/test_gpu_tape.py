@@ -1,0 +1,221 @@
+"""GPU parity of training steps driven by the define-by-run tape (every kernel through the C ABI)
+against the oracle's hand-ordered steps, and against the same tape run on the CPU with the oracle's
+functions as kernels where the oracle has no ready-made step (carried state, changing topology).
+Errors are measured against each tensor's own scale, as for the recorded step drivers."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from oracle import steps as OS
+from paper_1908_00213_amd import steps, tape as T, workloads as W
+from tests.oracle_backend import OracleBackend
+from tests.util import bf16r, check, host
+
+pytestmark = pytest.mark.gpu
+
+
+def cmp(got, ref, tol, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    check(host(got), ref, tol, float(np.max(np.abs(ref))) if ref.size else 0.0, what)
+
+
+def run_mlp(w, lowp, tol, fused=True):
+    F = T.backend()
+    x, t = w.xs[0], w.ts[0]
+    if lowp:
+        x = bf16r(x)
+    model = T.MLP([(F.from_numpy(Wm), F.from_numpy(b)) for Wm, b in w.params], w.act, lowp, fused)
+    opt = T.SGD(model.params(), w.lr)
+    xd = F.from_numpy(x, "bf16" if lowp else None)
+    td = F.from_numpy(t)
+    loss = model.loss(xd, td)
+    loss.backward()
+    r = OS.mlp_step(w.params, x, t, np.float32(w.lr), w.act, lowp)
+    assert abs(float(loss.array.cpu()) - r["loss"]) <= tol * max(1.0, abs(r["loss"]))
+    grads = [(host(l.W.grad), host(l.b.grad)) for l in model.layers]
+    for l, (dW, db) in enumerate(r["grads"]):
+        cmp(model.layers[l].W.grad, dW, tol, "dW%d" % l)
+        cmp(model.layers[l].b.grad, db, tol, "db%d" % l)
+        assert model.layers[l].W.grad.dtype == torch.float32
+    opt.update()
+    lr = np.float32(w.lr)
+    for l, layer in enumerate(model.layers):
+        for p, old, g in ((layer.W, w.params[l][0], grads[l][0]), (layer.b, w.params[l][1], grads[l][1])):
+            check(host(p.array), O.sgd_update(old, g, lr), 1e-6, np.abs(old) + lr * np.abs(g), "update %d" % l)
+        if lowp:
+            assert np.array_equal(host(layer.W.lowp), O.round_bf16(host(layer.W.array)))
+    assert T.live_function_nodes() == 0
+    return model, opt, xd, td
+
+
+def test_tape_mlp_steps_match_the_oracle():
+    run_mlp(W.config1(), False, 1e-4)
+    run_mlp(W.config1(), False, 1e-4, fused=False)
+    run_mlp(W.config3(n_batches=1), False, 1e-4)
+    run_mlp(W.config3(n_batches=1), True, 2e-2)
+    w = W.config5(n_batches=1, scale=8)
+    run_mlp(w, True, 2e-2)
+    run_mlp(w, False, 1e-4)
+    run_mlp(w, True, 2e-2, fused=False)
+
+
+def test_tape_mlp_equals_the_recorded_step_bit_for_bit_in_fp32():
+    # same kernels on the same operands; only who decides the order of the calls differs
+    w = W.config3(n_batches=1)
+    model, opt, xd, td = run_mlp(w, False, 1e-4)
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, False)
+    tr.step(xd, td)
+    for l, layer in enumerate(model.layers):
+        assert torch.equal(layer.W.grad, tr.dW[l]) and torch.equal(layer.b.grad, tr.db[l])
+        assert torch.equal(layer.W.array, tr.W[l]) and torch.equal(layer.b.array, tr.b[l])
+
+
+def test_tape_second_iteration_uses_updated_weights_and_cleared_gradients():
+    w = W.config1()
+    model, opt, xd, td = run_mlp(w, False, 1e-4)          # one step taken
+    r1 = OS.mlp_step(w.params, w.xs[0], w.ts[0], np.float32(w.lr), w.act)
+    opt.cleargrads()
+    loss = model.loss(xd, td)
+    loss.backward()
+    r2 = OS.mlp_step(r1["params"], w.xs[0], w.ts[0], np.float32(w.lr), w.act)
+    assert abs(float(loss.array.cpu()) - r2["loss"]) < 1e-4
+    cmp(model.layers[0].W.grad, r2["grads"][0][0], 1e-4, "dW0 second step")
+
+
+@pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=72, batch=16, bptt=6),
+                                 dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])
+def test_tape_lstm_language_model_step_matches_the_oracle(cfg):
+    F = T.backend()
+    w = W.config4(**cfg)
+    w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()})
+    ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
+    loss, _ = model.loss(ids, tg, w.bptt)
+    loss.backward()
+    r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr))
+    assert abs(float(loss.array.cpu()) - r["loss"]) <= 1e-4 * abs(r["loss"])
+    for k in w.params:
+        cmp(model.P[k].grad, r["grads"][k], 1e-4, "d" + k)
+    unused = np.setdiff1d(np.arange(w.vocab), w.ids.reshape(-1))
+    assert np.all(host(model.P["E"].grad)[unused] == 0)
+    g = {k: host(p.grad) for k, p in model.P.items()}
+    T.SGD(model.params(), w.lr).update()
+    lr = np.float32(w.lr)
+    for k in w.params:
+        check(host(model.P[k].array), O.sgd_update(w.params[k], g[k], lr), 1e-6,
+              np.abs(w.params[k]) + lr * np.abs(g[k]), "update " + k)
+    assert T.live_function_nodes() == 0
+
+
+def test_tape_window_length_changes_and_state_is_carried_across_windows():
+    # truncated back-propagation over two windows of different length: the second starts from the
+    # first one's final state, cut from its history.  Reference: the same tape on the CPU with the
+    # oracle's functions as kernels.
+    w = W.config4(vocab=120, embed=40, hidden=48, batch=8, bptt=7)
+    w.params["b"] = (np.random.default_rng(4).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    ids, tg = w.ids.reshape(-1).astype(np.int64), w.targets.reshape(-1).astype(np.int64)
+    Bn = w.batch
+
+    def two_windows(F):
+        model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()})
+        out, state = [], None
+        for lo, hi in ((0, 3), (3, 7)):
+            for p in model.params():
+                p.cleargrad()
+            sl = slice(lo * Bn, hi * Bn)
+            loss, state = model.loss(F.from_numpy(ids[sl]), F.from_numpy(tg[sl]), hi - lo, state)
+            loss.backward()
+            for v in state:
+                v.unchain()
+            out.append((float(F.to_numpy(loss.array)), {k: F.to_numpy(p.grad) for k, p in model.P.items()}))
+        return out
+
+    got = two_windows(T.backend())
+    with T.using_backend(OracleBackend()) as Fo:
+        ref = two_windows(Fo)
+    for (lg, gg), (lr_, gr) in zip(got, ref):
+        assert abs(lg - lr_) <= 1e-4 * abs(lr_)
+        for k in gr:
+            check(gg[k], gr[k], 1e-4, float(np.max(np.abs(gr[k]))), "d" + k)
+
+
+def test_tape_depth_chosen_per_iteration():
+    rng = np.random.default_rng(12)
+    Wm = (rng.standard_normal((64, 64)) * 0.2).astype(np.float32)
+    b = (rng.standard_normal(64) * 0.1).astype(np.float32)
+    x = rng.standard_normal((48, 64)).astype(np.float32)
+    t = rng.integers(0, 64, 48)
+
+    def run(F, depth):
+        layer = T.Linear(F.from_numpy(Wm), F.from_numpy(b))
+        h = F.from_numpy(x)
+        for _ in range(depth):
+            h = layer(h, act="gelu")
+        loss = T.softmax_cross_entropy(h, F.from_numpy(t))
+        loss.backward()
+        return float(F.to_numpy(loss.array)), F.to_numpy(layer.W.grad), F.to_numpy(layer.b.grad)
+
+    for depth in (3, 1, 4):
+        got = run(T.backend(), depth)
+        with T.using_backend(OracleBackend()) as Fo:
+            ref = run(Fo, depth)
+        assert abs(got[0] - ref[0]) <= 1e-5 * abs(ref[0])
+        check(got[1], ref[1], 1e-4, float(np.max(np.abs(ref[1]))), "dW depth %d" % depth)
+        check(got[2], ref[2], 1e-4, float(np.max(np.abs(ref[2]))), "db depth %d" % depth)
+
+
+def test_tape_returns_device_memory_while_walking_back():
+    F = T.backend()
+    n, width, depth = 2048, 1024, 8
+    rng = np.random.default_rng(1)
+    layers = [T.Linear(F.from_numpy((rng.standard_normal((width, width)) * 0.03).astype(np.float32)),
+                       F.from_numpy(np.zeros(width, dtype=np.float32))) for _ in range(depth)]
+    x = F.from_numpy(rng.standard_normal((n, width)).astype(np.float32))
+    t = F.from_numpy(rng.integers(0, width, n))
+    act_bytes = n * width * 4
+
+    def forward():
+        h = x
+        for l in layers:
+            h = l(h, act="relu")
+        return T.softmax_cross_entropy(h, t)
+
+    gc.collect()
+    torch.cuda.synchronize()
+    base = torch.cuda.memory_allocated()
+    loss = forward()
+    held = torch.cuda.memory_allocated() - base
+    assert held >= depth * act_bytes                       # every layer's output is retained
+    seen = []
+    orig = F.gemm
+
+    def spy(*a, **k):
+        seen.append(torch.cuda.memory_allocated() - base)
+        return orig(*a, **k)
+
+    F.gemm = spy
+    gc.disable()
+    try:
+        loss.backward()
+    finally:
+        gc.enable()
+        del F.gemm
+    grads = depth * (width * width + width) * 4
+    # activations are given back layer by layer: when the walk reaches the first layer, what is
+    # allocated beyond the parameters' gradients is that layer's own working set (its retained
+    # output, the gradient that arrived, the masked gradient), not the eight retained outputs that
+    # were there when the walk began
+    assert seen[-1] - grads <= seen[0] - 4 * act_bytes
+    del loss
+    torch.cuda.synchronize()
+    after = torch.cuda.memory_allocated() - base
+    assert after <= grads + 4 * act_bytes                  # parameters' gradients and little else
+    assert T.live_function_nodes() == 0
+    # no_backprop_mode: nothing is retained at all
+    with T.no_backprop_mode():
+        l2 = forward()
+    assert torch.cuda.memory_allocated() - base - after <= 2 * act_bytes
+    assert abs(float(l2.array.cpu()) - np.log(width)) < 2.0

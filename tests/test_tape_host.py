@@ -1,0 +1,324 @@
+"""Host logic of the define-by-run tape, run on the CPU with the oracle's functions as kernels.
+
+What is pinned here, against things other than the tape itself:
+* gradients against central finite differences of the forward value (every function, graphs with a
+  variable used twice, a diamond, shared weights over time);
+* whole steps against the hand-ordered oracle steps (same kernels, so equality up to the order of
+  gradient accumulation);
+* the memory rules of Sections "Global Memory Usage Reduction" and "Function-wise Local Memory
+  Usage Reduction": what each function retains, that every function node is cut out by backward,
+  that arrays die as soon as nothing needs them;
+* the traversal order of Section "On Demand Graph Construction": each function node's backward
+  runs once, after those of all its consumers.
+"""
+import gc
+import weakref
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from oracle import steps as OS
+from paper_1908_00213_amd import tape as T
+from paper_1908_00213_amd import workloads as W
+from tests.oracle_backend import OracleBackend
+
+
+@pytest.fixture
+def F():
+    with T.using_backend(OracleBackend()) as b:
+        yield b
+
+
+def fd_grad(f, arrays, eps=1e-6):
+    """Central differences of the scalar f() with respect to every entry of every array (in place)."""
+    out = []
+    for a in arrays:
+        g = np.zeros_like(a)
+        it = np.nditer(a, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = a[i]
+            a[i] = old + eps
+            hi = f()
+            a[i] = old - eps
+            lo = f()
+            a[i] = old
+            g[i] = (hi - lo) / (2 * eps)
+        out.append(g)
+    return out
+
+
+def rnd(rng, *shape):
+    return rng.standard_normal(shape)
+
+
+# ---- gradients against finite differences -----------------------------------------------------------
+@pytest.mark.parametrize("act", [None, "relu", "gelu"])
+def test_linear_with_fused_activation_matches_finite_differences(F, act):
+    rng = np.random.default_rng(1)
+    x, Wm, b, t = rnd(rng, 5, 4), rnd(rng, 3, 4), rnd(rng, 3), np.array([0, 2, 1, 1, 0])
+
+    def loss(record=False):
+        xs = [T.Variable(x), T.Parameter(Wm), T.Parameter(b)]
+        l = T.softmax_cross_entropy(T.linear(*xs, act=act), t)
+        return (l, xs) if record else float(l.array)
+
+    l, xs = loss(True)
+    l.backward()
+    for v, g in zip(xs, fd_grad(loss, [x, Wm, b])):
+        np.testing.assert_allclose(v.grad, g, rtol=1e-6, atol=1e-8)
+
+
+def test_variable_used_twice_and_diamond_accumulate(F):
+    rng = np.random.default_rng(2)
+    x, Wa, Wb, t = rnd(rng, 4, 3), rnd(rng, 3, 3), rnd(rng, 3, 3), np.array([2, 0, 1, 1])
+
+    def loss(record=False):
+        xv, A, Bv = T.Variable(x), T.Parameter(Wa), T.Parameter(Wb)
+        h = T.gelu(T.matmul(xv, A))                    # h feeds three consumers
+        y = T.add(T.add(T.matmul(h, Bv), T.relu(h)), T.matmul(h, A))   # A used twice
+        l = T.softmax_cross_entropy(y, t)
+        return (l, [xv, A, Bv]) if record else float(l.array)
+
+    l, vs = loss(True)
+    l.backward()
+    for v, g in zip(vs, fd_grad(loss, [x, Wa, Wb])):
+        np.testing.assert_allclose(v.grad, g, rtol=1e-6, atol=1e-8)
+
+
+def test_lstm_language_model_matches_finite_differences_and_oracle_step(F):
+    w = W.config4(seed=5, vocab=11, embed=3, hidden=4, batch=2, bptt=3)
+    P = {k: v.astype(np.float64) for k, v in w.params.items()}
+    P["b"] = np.random.default_rng(3).standard_normal(P["b"].shape) * 0.1
+    ids, tg = w.ids.reshape(-1).astype(np.int64), w.targets.reshape(-1).astype(np.int64)
+
+    model = T.LSTMLanguageModel(P)
+    loss, _ = model.loss(ids, tg, w.bptt)
+    loss.backward()
+    ref = OS.lstm_lm_step(P, w.ids, w.targets, 0.1)
+    assert float(loss.array) == pytest.approx(ref["loss"], rel=1e-13)
+    for k, p in model.P.items():
+        np.testing.assert_allclose(p.grad, ref["grads"][k], rtol=1e-10, atol=1e-13, err_msg=k)
+
+    def f():
+        with T.no_backprop_mode():
+            return float(T.LSTMLanguageModel(P).loss(ids, tg, w.bptt)[0].array)
+
+    for k in ("U", "b", "W"):
+        g, = fd_grad(f, [P[k]])
+        np.testing.assert_allclose(model.P[k].grad, g, rtol=2e-5, atol=1e-8, err_msg=k)
+    # the optimiser applies the oracle's update to every parameter once
+    T.SGD(model.params(), 0.1).update()
+    for k in P:
+        np.testing.assert_allclose(P[k], ref["params"][k], rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("act,fused", [("relu", True), ("relu", False), ("gelu", True), ("gelu", False)])
+def test_mlp_step_equals_the_hand_ordered_oracle_step(F, act, fused):
+    w = W.make_mlp("t", (7, 6, 5, 4), 9, act, seed=11)
+    params = [(Wm.astype(np.float64), np.random.default_rng(l).standard_normal(b.shape))
+              for l, (Wm, b) in enumerate(w.params)]
+    ref = OS.mlp_step(params, w.xs[0], w.ts[0], 0.05, act)
+    model = T.MLP([(a.copy(), b.copy()) for a, b in params], act, fused_activation=fused)
+    opt = T.SGD(model.params(), 0.05)
+    loss = model.loss(w.xs[0].astype(np.float64), w.ts[0].astype(np.int64))
+    loss.backward()
+    assert float(loss.array) == pytest.approx(ref["loss"], rel=1e-14)
+    for l, layer in enumerate(model.layers):
+        np.testing.assert_allclose(layer.W.grad, ref["grads"][l][0], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(layer.b.grad, ref["grads"][l][1], rtol=1e-12, atol=1e-15)
+    opt.update()
+    for l, layer in enumerate(model.layers):
+        np.testing.assert_allclose(layer.W.array, ref["params"][l][0], rtol=1e-13)
+        np.testing.assert_allclose(layer.b.array, ref["params"][l][1], rtol=1e-13, atol=1e-16)
+    # the first layer's input is data: no product is spent on its gradient
+    n_gemm = sum(1 for c in F.calls if c[0] == "gemm")
+    assert n_gemm == 3 + 3 + 2
+
+
+# ---- topology is whatever the forward code did -------------------------------------------------------
+def test_graph_may_change_from_one_iteration_to_the_next(F):
+    rng = np.random.default_rng(4)
+    Wm, b = rnd(rng, 4, 4) * 0.5, rnd(rng, 4) * 0.1
+    x, t = rnd(rng, 3, 4), np.array([1, 3, 0])
+    layer = T.Linear(Wm, b)
+
+    def forward(depth):
+        h = T.Variable(x, requires_grad=False)
+        for _ in range(depth):                        # the same link applied `depth` times
+            h = layer(h, act="relu")
+        return T.softmax_cross_entropy(h, t)
+
+    for depth in (1, 3, 2):
+        for p in layer.params():
+            p.cleargrad()
+        l = forward(depth)
+        l.backward()
+
+        def f():
+            with T.no_backprop_mode():
+                return float(forward(depth).array)
+
+        gW, gb = fd_grad(f, [Wm, b])
+        np.testing.assert_allclose(layer.W.grad, gW, rtol=1e-6, atol=1e-8)
+        np.testing.assert_allclose(layer.b.grad, gb, rtol=1e-6, atol=1e-8)
+        assert T.live_function_nodes() == 0
+
+
+def test_gradients_accumulate_until_cleared_and_unchain_truncates(F):
+    rng = np.random.default_rng(6)
+    Wm, x, t = rnd(rng, 3, 3), rnd(rng, 2, 3), np.array([0, 2])
+    p = T.Parameter(Wm)
+    T.softmax_cross_entropy(T.matmul(T.Variable(x, False), p), t).backward()
+    g1 = p.grad.copy()
+    T.softmax_cross_entropy(T.matmul(T.Variable(x, False), p), t).backward()
+    np.testing.assert_allclose(p.grad, 2 * g1, rtol=1e-14)
+    p.cleargrad()
+    assert p.grad is None
+    # truncation: a variable cut from its history is a leaf; nothing behind it receives a gradient
+    h = T.matmul(T.Variable(x, False), p)
+    h.unchain()
+    q = T.Parameter(rnd(rng, 3, 3))
+    T.softmax_cross_entropy(T.matmul(h, q), t).backward()
+    assert p.grad is None and q.grad is not None and h.grad is not None
+
+
+def test_non_unit_seed_scales_every_gradient(F):
+    rng = np.random.default_rng(7)
+    Wm, x, t = rnd(rng, 3, 3), rnd(rng, 2, 3), np.array([1, 2])
+    p = T.Parameter(Wm)
+    T.softmax_cross_entropy(T.matmul(T.Variable(x, False), p), t).backward()
+    g = p.grad.copy()
+    p.cleargrad()
+    l = T.softmax_cross_entropy(T.matmul(T.Variable(x, False), p), t)
+    l.grad = np.full((), 2.5)
+    l.backward()
+    np.testing.assert_allclose(p.grad, 2.5 * g, rtol=1e-14)
+    with pytest.raises(ValueError):
+        T.matmul(T.Variable(x, False), p).backward()       # not a scalar and no gradient given
+
+
+# ---- traversal order ------------------------------------------------------------------------------------
+def test_each_backward_runs_once_after_all_its_consumers(F):
+    order = []
+
+    class Probe(T.FunctionNode):
+        def __init__(self, tag):
+            super().__init__()
+            self.tag = tag
+
+        def forward(self, xs):
+            return (sum(xs) * 1.0,)
+
+        def backward(self, indexes, gys):
+            order.append(self.tag)
+            return tuple(gys[0] for _ in indexes)
+
+    a = T.Variable(np.ones(()))
+    b = Probe("b").apply((a,))[0]
+    c = Probe("c").apply((b,))[0]
+    d = Probe("d").apply((b, c))[0]          # b reaches the root along two paths of unequal length
+    e = Probe("e").apply((d, a, c))[0]
+    e.backward()
+    assert sorted(order) == ["b", "c", "d", "e"]
+    assert order.index("e") < order.index("d") < order.index("c") < order.index("b")
+    # paths from e to a: direct; d-b; d-c-b; c-b  => de/da = 4
+    assert float(a.grad) == 4.0
+
+
+# ---- what is retained, and when it is let go ---------------------------------------------------------
+def test_functions_retain_only_what_their_backward_needs(F):
+    rng = np.random.default_rng(8)
+    x = T.Variable(rnd(rng, 2, 3))
+    y = T.relu(x)
+    assert x.node.data is None and y.creator.get_retained_outputs()[0] is y.array    # from the output
+    z = T.gelu(x)
+    assert x.node.data is x.array and z.creator.get_retained_outputs() == ()          # from the input
+    s = T.add(y, z)
+    assert y.node.data is None and z.node.data is None and s.creator.get_retained_inputs() == ()
+    c0 = T.Variable(rnd(rng, 2, 3))
+    pre = T.Variable(rnd(rng, 2, 12))
+    c1, h1 = T.lstm(c0, pre)
+    f = c1.creator
+    assert pre.node.data is None and c0.node.data is c0.array and f.get_retained_outputs()[0] is c1.array
+    # releasing the function releases the claim on its inputs
+    f.unchain()
+    assert c0.node.data is None and c1.creator is None and h1.creator is None
+
+
+def test_intermediate_arrays_die_as_backward_passes_them(F):
+    rng = np.random.default_rng(9)
+    Wm, t = rnd(rng, 4, 4), np.array([0, 1, 2])
+    p = T.Parameter(Wm)
+    h = T.Variable(rnd(rng, 3, 4), requires_grad=False)
+    refs = []
+    for _ in range(4):
+        h = T.matmul(h, p)
+        h = T.relu(h)
+        refs.append(weakref.ref(h.array))
+    loss = T.softmax_cross_entropy(h, t)
+    del h
+    gc.disable()                      # reference counting alone must do it
+    try:
+        assert all(r() is not None for r in refs)       # retained by the graph, not by the user
+        alive_during = []
+
+        class Spy(OracleBackend):
+            def gemm(self, *a, **k):
+                alive_during.append(sum(r() is not None for r in refs))
+                return super().gemm(*a, **k)
+
+        with T.using_backend(Spy()):
+            loss.backward()
+        assert all(r() is None for r in refs)
+        assert T.live_function_nodes() == 0
+        # while walking back, every function node already passed has given its arrays back
+        assert alive_during == sorted(alive_during, reverse=True) and alive_during[-1] <= 1
+    finally:
+        gc.enable()
+
+
+def test_dropping_the_user_handle_frees_an_unretained_result(F):
+    x = T.Variable(np.ones((2, 2)))
+    y = T.add(x, x)                   # addition retains nothing
+    z = T.add(y, y)
+    r = weakref.ref(y.array)
+    gc.disable()
+    try:
+        del y
+        assert r() is None            # the node is still in the graph, the array is gone
+        z.grad = np.ones((2, 2))
+        z.backward()
+        np.testing.assert_array_equal(x.grad, 4 * np.ones((2, 2)))
+    finally:
+        gc.enable()
+
+
+def test_retain_grad_keeps_intermediate_gradients(F):
+    x = T.Variable(np.ones((2, 2)))
+    y = T.relu(x)
+    z = T.add(y, y)
+    z.grad = np.ones((2, 2))
+    z.backward(retain_grad=True)
+    np.testing.assert_array_equal(y.grad, 2 * np.ones((2, 2)))
+    y2 = T.relu(x)
+    z2 = T.add(y2, y2)
+    z2.grad = np.ones((2, 2))
+    z2.backward()
+    assert y2.grad is None
+
+
+def test_no_backprop_mode_records_nothing(F):
+    p = T.Parameter(np.ones((2, 2)))
+    with T.no_backprop_mode():
+        y = T.matmul(T.Variable(np.ones((2, 2))), p)
+    assert y.creator is None and p.node.data is None and T.live_function_nodes() == 0
+
+
+def test_gpu_backend_refuses_to_exist_without_the_library(monkeypatch):
+    from paper_1908_00213_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libchn.so")
+    with pytest.raises(Exception):
+        T.GpuBackend()
