@@ -60,7 +60,8 @@ enum {
   CHN_ERR_OP = -6,        /* unknown operation / epilogue code or wrong operand count    */
   CHN_ERR_AXIS = -7,      /* axis out of range                                           */
   CHN_ERR_WORKSPACE = -8, /* workspace missing, misaligned or too small                  */
-  CHN_ERR_LAUNCH = -9     /* the HIP runtime refused a launch                            */
+  CHN_ERR_LAUNCH = -9,    /* the HIP runtime refused a launch                            */
+  CHN_ERR_COMPILE = -10   /* a user-defined kernel's snippet does not compile            */
 };
 
 typedef void *chn_stream; /* hipStream_t */
@@ -225,6 +226,92 @@ chn_status chn_embed_fwd(const chn_array *table, const chn_array *ids, const chn
                          chn_stream stream);
 chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_array *dtable,
                          int accumulate, chn_stream stream);
+
+/* ---- user-defined kernels ----------------------------------------------------------------------------
+ * Section "Custom CUDA Kernels" and the figure "Example of a user-defined kernel": a kernel is
+ * declared by a list of input parameters, a list of output parameters ("<type> <name>", comma
+ * separated), C++ snippets over those names and a kernel name; the library wraps the snippets into
+ * a complete kernel, compiles it at run time (hipRTC, for the architecture of the current device),
+ * and caches the code object in memory and on disk so that later runs do not compile again.
+ * Types: float32, bfloat16, int32, int64, or any other identifier, which is a TYPE PARAMETER (the
+ * paper's generic types): it is bound by the dtype of the arrays passed for it, all parameters that
+ * share it must receive one dtype, and one kernel object serves every binding.  Inside a snippet a
+ * parameter has its COMPUTE type -- float for float32 and bfloat16 arrays (a bfloat16 store rounds
+ * to nearest even), int, long long -- and a type parameter names that compute type.
+ *
+ * Objects: chn_*_kernel_create parses and checks the declaration (nothing is compiled yet) and
+ * returns a host object owned by the caller until chn_user_kernel_destroy.  These objects are the
+ * one place where the library allocates: host memory for the object, and device code memory when a
+ * specialisation is loaded; a launch of an already loaded specialisation allocates nothing.  A
+ * kernel object may be used from several threads (calls on one object are serialised).
+ *
+ * Arguments of a call: `in[i]` is the array for input parameter i, or NULL when that parameter is
+ * a SCALAR, whose value is then the next entry of `scalars` (host doubles, converted to the
+ * parameter's compute type; a type parameter used only by scalars is an error).  Inputs broadcast
+ * NumPy-style; any non-negative byte strides.
+ *
+ * Element-wise kernel: `operation` is a statement list that assigns every output name, e.g.
+ * "w = x * y + z"; it runs once per element of the outputs (all outputs share one shape, every
+ * input broadcasts to it).  Also visible: `i`, the C-order flat index of the element (long long).
+ *
+ * Reduction kernel: the value map_expr (over the input names) of every element is folded by
+ * reduce_expr, an expression over `a` and `b`, starting from `identity`; post_map_expr is a
+ * statement list that assigns every output from the folded value `a` (scalar parameters are
+ * visible too).  The fold runs in the compute type of the first output, over one axis (negative
+ * counts from the end) or over all of them (CHN_AXIS_ALL); outputs have the common input shape
+ * without the reduced dimensions (keepdims: with them set to 1).  reduce_expr must be associative
+ * and commutative; the order of the fold is fixed for given shapes (bit-reproducible).  An empty
+ * reduced range yields post_map(identity).  Workspace as for chn_reduce_axis.
+ *
+ * chn_*_kernel_prepare compiles (or fetches) the specialisation a call with these descriptors
+ * would use without loading or launching it -- it needs no GPU once an architecture is configured.
+ * chn_user_kernel_config: `cache_dir` (default $CHN_KERNEL_CACHE_DIR, else ~/.cache/libchn/kernels)
+ * and `arch` (default: the current device's, e.g. "gfx950"); NULL keeps a setting.  Cache files are
+ * named by a digest of the generated source, the architecture, the compiler version and the library
+ * version, and written atomically; an unwritable cache is not an error.
+ * Errors: CHN_ERR_OP (malformed declaration, wrong argument count), CHN_ERR_DTYPE (array dtype
+ * against the declaration, inconsistent binding of a type parameter), CHN_ERR_SHAPE, CHN_ERR_AXIS,
+ * CHN_ERR_WORKSPACE, CHN_ERR_COMPILE (chn_last_error holds the compiler's first error),
+ * CHN_ERR_LAUNCH.  A failing call enqueues nothing. */
+typedef struct chn_user_kernel chn_user_kernel;
+#define CHN_AXIS_ALL (-1000)
+
+chn_status chn_user_kernel_config(const char *cache_dir, const char *arch);
+/* process-wide counters: compiler runs, code objects found on disk, found in memory */
+void chn_user_kernel_stats(long long *compiles, long long *disk_hits, long long *memory_hits);
+void chn_user_kernel_destroy(chn_user_kernel *k);
+
+chn_status chn_elementwise_kernel_create(const char *in_params, const char *out_params,
+                                         const char *operation, const char *name,
+                                         const char *preamble /* or NULL: code placed before the kernel */,
+                                         chn_user_kernel **out);
+chn_status chn_elementwise_kernel_prepare(chn_user_kernel *k, int n_in, const chn_array *const *in,
+                                          int n_out, const chn_array *const *out);
+chn_status chn_elementwise_kernel_launch(chn_user_kernel *k, int n_in, const chn_array *const *in,
+                                         int n_out, const chn_array *const *out,
+                                         const double *scalars, chn_stream stream);
+
+chn_status chn_reduction_kernel_create(const char *in_params, const char *out_params,
+                                       const char *map_expr, const char *reduce_expr,
+                                       const char *post_map_expr, const char *identity,
+                                       const char *name, const char *preamble,
+                                       chn_user_kernel **out);
+size_t chn_reduction_kernel_workspace_bytes(chn_user_kernel *k, int n_in, const chn_array *const *in,
+                                            int n_out, const chn_array *const *out, int axis,
+                                            int keepdims);
+chn_status chn_reduction_kernel_prepare(chn_user_kernel *k, int n_in, const chn_array *const *in,
+                                        int n_out, const chn_array *const *out, int axis,
+                                        int keepdims);
+chn_status chn_reduction_kernel_launch(chn_user_kernel *k, int n_in, const chn_array *const *in,
+                                       int n_out, const chn_array *const *out, const double *scalars,
+                                       int axis, int keepdims, void *ws, size_t ws_bytes,
+                                       chn_stream stream);
+/* The generated source of the specialisation a call would use (axis/keepdims: reductions only).
+ * Copies at most buf_bytes - 1 characters plus a terminator; *needed (if not NULL) receives the
+ * full size including the terminator. */
+chn_status chn_user_kernel_source(chn_user_kernel *k, int n_in, const chn_array *const *in, int n_out,
+                                  const chn_array *const *out, int axis, int keepdims, char *buf,
+                                  size_t buf_bytes, size_t *needed);
 
 /* ---- diagnostics ---------------------------------------------------------------------------------------- */
 const char *chn_status_string(chn_status status);

@@ -29,7 +29,12 @@ EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_embed_fwd", "chn_embed_bwd",
-           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan"]
+           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan",
+           "chn_user_kernel_config", "chn_user_kernel_stats", "chn_user_kernel_destroy",
+           "chn_elementwise_kernel_create", "chn_elementwise_kernel_prepare", "chn_elementwise_kernel_launch",
+           "chn_reduction_kernel_create", "chn_reduction_kernel_workspace_bytes", "chn_reduction_kernel_prepare",
+           "chn_reduction_kernel_launch", "chn_user_kernel_source"]
+AXIS_ALL = -1000
 
 
 class ChnArray(C.Structure):
@@ -82,9 +87,25 @@ def lib():
     L.chn_last_error.argtypes = []
     L.chn_last_error.restype = C.c_char_p
     L.chn_version.argtypes = []
+    cs, KP, dp = C.c_char_p, C.c_void_p, C.POINTER(C.c_double)
+    L.chn_user_kernel_config.argtypes = [cs, cs]
+    L.chn_user_kernel_stats.argtypes = [C.POINTER(C.c_longlong)] * 3
+    L.chn_user_kernel_stats.restype = None
+    L.chn_user_kernel_destroy.argtypes = [KP]
+    L.chn_user_kernel_destroy.restype = None
+    L.chn_elementwise_kernel_create.argtypes = [cs, cs, cs, cs, cs, C.POINTER(KP)]
+    L.chn_elementwise_kernel_prepare.argtypes = [KP, C.c_int, APP, C.c_int, APP]
+    L.chn_elementwise_kernel_launch.argtypes = [KP, C.c_int, APP, C.c_int, APP, dp, st]
+    L.chn_reduction_kernel_create.argtypes = [cs, cs, cs, cs, cs, cs, cs, cs, C.POINTER(KP)]
+    L.chn_reduction_kernel_workspace_bytes.argtypes = [KP, C.c_int, APP, C.c_int, APP, C.c_int, C.c_int]
+    L.chn_reduction_kernel_workspace_bytes.restype = C.c_size_t
+    L.chn_reduction_kernel_prepare.argtypes = [KP, C.c_int, APP, C.c_int, APP, C.c_int, C.c_int]
+    L.chn_reduction_kernel_launch.argtypes = [KP, C.c_int, APP, C.c_int, APP, dp, C.c_int, C.c_int, vp, C.c_size_t, st]
+    L.chn_user_kernel_source.argtypes = [KP, C.c_int, APP, C.c_int, APP, C.c_int, C.c_int, C.c_char_p, C.c_size_t,
+                                         C.POINTER(C.c_size_t)]
     for name in EXPORTS:
         fn = getattr(L, name)
-        if fn.restype is C.c_int and name not in ("chn_version", "chn_elementwise_plan", "chn_gemm_plan"):
+        if fn.restype is C.c_int and name not in ("chn_version", "chn_elementwise_plan", "chn_gemm_plan"):  # i.e. not set above
             fn.restype = C.c_int32
     _lib = L
     return L
@@ -256,3 +277,151 @@ def embed_bwd(ids, dout, dtable, accumulate=False, stream=None):
     _check(lib().chn_embed_bwd(_ref(desc(ids)), _ref(desc(dout)), _ref(desc(dtable)), int(accumulate),
                                _stream() if stream is None else stream))
     return dtable
+
+
+# ---- user-defined kernels ---------------------------------------------------------------------------------
+def user_kernel_config(cache_dir=None, arch=None):
+    enc = lambda v: None if v is None else str(v).encode()
+    _check(lib().chn_user_kernel_config(enc(cache_dir), enc(arch)))
+
+
+def user_kernel_stats():
+    """(compiler runs, code objects found on disk, found in memory) since the library was loaded."""
+    v = [C.c_longlong(0) for _ in range(3)]
+    lib().chn_user_kernel_stats(*[C.byref(x) for x in v])
+    return tuple(int(x.value) for x in v)
+
+
+_TORCH_OF = {F32: torch.float32, BF16: torch.bfloat16, I32: torch.int32, I64: torch.int64}
+_CONCRETE = {"float32": F32, "bfloat16": BF16, "int32": I32, "int64": I64}
+
+
+class _UserKernel:
+    """Owner of a chn_user_kernel handle.  Arguments of a call: arrays (tensors or descriptors) and
+    Python numbers for scalar parameters, inputs first, then optionally the outputs; outputs that
+    are left out are allocated (shape from broadcasting, dtype from the declaration or from the
+    arrays that bind the output's type parameter)."""
+
+    def __init__(self, handle, in_params, out_params, name):
+        self._h = handle
+        self.name = name
+        split = lambda text: [tuple(item.split()) for item in text.split(",") if item.strip()]
+        self.in_params, self.out_params = split(in_params), split(out_params)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h is not None and _lib is not None:
+            _lib.chn_user_kernel_destroy(h)
+
+    def _split(self, args):
+        n_in, n_out = len(self.in_params), len(self.out_params)
+        if len(args) not in (n_in, n_in + n_out):
+            raise TypeError("%s takes %d inputs (and optionally %d outputs), got %d arguments"
+                            % (self.name, n_in, n_out, len(args)))
+        ins = list(args[:n_in])
+        scalars = [float(a) for a in ins if isinstance(a, (int, float))]
+        arrays = [None if isinstance(a, (int, float)) else a for a in ins]
+        return arrays, scalars, list(args[n_in:])
+
+    def _out_dtype(self, j, arrays):
+        t = self.out_params[j][0]
+        if t in _CONCRETE:
+            return _TORCH_OF[_CONCRETE[t]]
+        for (pt, _), a in zip(self.in_params, arrays):
+            if pt == t and a is not None:
+                return a.dtype
+        raise TypeError("%s: no input binds the type parameter %s of output %s" % (self.name, t, self.out_params[j][1]))
+
+    @staticmethod
+    def _marshal(arrays, scalars):
+        ds = [desc(a) for a in arrays]
+        sc = (C.c_double * max(1, len(scalars)))(*scalars)
+        return ds, sc
+
+    def source(self, *args, axis=None, keepdims=False):
+        """Generated source of the specialisation this call would use (outputs must be given)."""
+        arrays, scalars, outs = self._split(args)
+        ds, _ = self._marshal(arrays, scalars)
+        os_ = [desc(o) for o in outs]
+        need = C.c_size_t(0)
+        ax = AXIS_ALL if axis is None else int(axis)
+        _check(lib().chn_user_kernel_source(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims), None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value)
+        _check(lib().chn_user_kernel_source(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims), buf, need.value, None))
+        return buf.value.decode()
+
+
+class ElementwiseKernel(_UserKernel):
+    """``kernel = ElementwiseKernel('float32 x, float32 y, float32 z', 'float32 w', 'w = x * y + z',
+    'my_mad'); w = kernel(x, y, z)`` -- the figure "Example of a user-defined kernel"."""
+
+    def __init__(self, in_params, out_params, operation, name="kernel", preamble=""):
+        h = C.c_void_p(None)
+        _check(lib().chn_elementwise_kernel_create(in_params.encode(), out_params.encode(), operation.encode(),
+                                                   name.encode(), preamble.encode(), C.byref(h)))
+        super().__init__(h, in_params, out_params, name)
+
+    def _outputs(self, arrays, outs):
+        if outs:
+            return outs
+        shape = torch.broadcast_shapes(*[tuple(a.shape) for a in arrays if a is not None])
+        dev = next(a.device for a in arrays if a is not None)
+        return [torch.empty(shape, dtype=self._out_dtype(j, arrays), device=dev) for j in range(len(self.out_params))]
+
+    def prepare(self, *args):
+        arrays, scalars, outs = self._split(args)
+        ds, _ = self._marshal(arrays, scalars)
+        os_ = [desc(o) for o in self._outputs(arrays, outs)]
+        _check(lib().chn_elementwise_kernel_prepare(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_)))
+
+    def __call__(self, *args, stream=None):
+        arrays, scalars, outs = self._split(args)
+        outs = self._outputs(arrays, outs)
+        ds, sc = self._marshal(arrays, scalars)
+        os_ = [desc(o) for o in outs]
+        _check(lib().chn_elementwise_kernel_launch(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), sc,
+                                                   _stream() if stream is None else stream))
+        return outs[0] if len(outs) == 1 else tuple(outs)
+
+
+class ReductionKernel(_UserKernel):
+    """``ReductionKernel('T x', 'T y', 'x * x', 'a + b', 'y = sqrt(a)', '0', 'l2norm')(x, axis=1)``:
+    fold map_expr of every element by reduce_expr from `identity`, then post_map_expr."""
+
+    def __init__(self, in_params, out_params, map_expr, reduce_expr, post_map_expr, identity, name="reduce", preamble=""):
+        h = C.c_void_p(None)
+        _check(lib().chn_reduction_kernel_create(in_params.encode(), out_params.encode(), map_expr.encode(),
+                                                 reduce_expr.encode(), post_map_expr.encode(), str(identity).encode(),
+                                                 name.encode(), preamble.encode(), C.byref(h)))
+        super().__init__(h, in_params, out_params, name)
+
+    def _outputs(self, arrays, outs, axis, keepdims):
+        if outs:
+            return outs
+        shape = list(torch.broadcast_shapes(*[tuple(a.shape) for a in arrays if a is not None]))
+        axes = range(len(shape)) if axis is None else [axis % len(shape)]
+        oshape = [1 if d in axes else n for d, n in enumerate(shape)] if keepdims else [n for d, n in enumerate(shape) if d not in axes]
+        dev = next(a.device for a in arrays if a is not None)
+        return [torch.empty(oshape, dtype=self._out_dtype(j, arrays), device=dev) for j in range(len(self.out_params))]
+
+    def prepare(self, *args, axis=None, keepdims=False):
+        arrays, scalars, outs = self._split(args)
+        ds, _ = self._marshal(arrays, scalars)
+        os_ = [desc(o) for o in self._outputs(arrays, outs, axis, keepdims)]
+        _check(lib().chn_reduction_kernel_prepare(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_),
+                                                  AXIS_ALL if axis is None else int(axis), int(keepdims)))
+
+    def __call__(self, *args, axis=None, keepdims=False, ws=None, stream=None):
+        arrays, scalars, outs = self._split(args)
+        outs = self._outputs(arrays, outs, axis, keepdims)
+        ds, sc = self._marshal(arrays, scalars)
+        os_ = [desc(o) for o in outs]
+        ax = AXIS_ALL if axis is None else int(axis)
+        if ws is None:
+            need = lib().chn_reduction_kernel_workspace_bytes(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims))
+            if need:
+                ws = torch.empty(need, dtype=torch.uint8, device=outs[0].device)
+        p, n = _ws(ws)
+        _check(lib().chn_reduction_kernel_launch(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), sc, ax, int(keepdims),
+                                                 p, n, _stream() if stream is None else stream))
+        return outs[0] if len(outs) == 1 else tuple(outs)

@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchn.so")
 TOOL = os.path.join(HERE, "mfma_ceiling")
 
-SOURCES = ["host.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "softmax_ce.hip",
+SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "softmax_ce.hip",
            "sgd.hip", "embed.hip"]
 
 # gemm_inst.hip is compiled once per (dtype, A layout, B layout): k = unit stride along K, m = along M/N
@@ -78,7 +78,7 @@ def build(force=False, verbose=False, extra=()):
                 print("[%s]\n%s" % (src, err))
     objs = [os.path.join(OBJ, j[1] + ".o") for j in jobs]
     if force or _stale(LIB, objs):
-        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lhiprtc"]
         subprocess.run(cmd, check=True)
     # measurement aid: what the matrix cores sustain (a stand-alone program, see its header)
     tool_src = os.path.join(CSRC, "mfma_ceiling.hip")

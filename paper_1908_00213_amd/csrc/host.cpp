@@ -74,6 +74,7 @@ const char *chn_status_string(chn_status s) {
     case CHN_ERR_AXIS: return "axis out of range";
     case CHN_ERR_WORKSPACE: return "workspace missing or too small";
     case CHN_ERR_LAUNCH: return "kernel launch failed";
+    case CHN_ERR_COMPILE: return "user kernel does not compile";
   }
   return "unknown status";
 }
