@@ -81,6 +81,19 @@ def bench_array(torch, B, W, timer, quick):
             "sum_axis0_transposed": (rot(lambda i: B.reduce_axis("sum", y[i % 4].t(), 0, o, ws=ws)), n * n * isz + n * 4),
             "sum_axis1_transposed": (rot(lambda i: B.reduce_axis("sum", y[i % 4].t(), 1, o, ws=ws)), n * n * isz + n * 4),
         }
+        # the same work through user-defined kernels (snippets compiled at run time, generic type T)
+        uk_mad = B.ElementwiseKernel("T x, T y, T z", "T w", "w = x * y + z", "my_mad")
+        uk_mad_relu = B.ElementwiseKernel("T x, T y, T z", "T w", "w = fmaxf(x * y + z, 0.0f)", "my_mad_relu")
+        uk_sum = B.ReductionKernel("T x", "float32 y", "x", "a + b", "y = a", "0", "my_sum")
+        o0 = torch.empty((), dtype=torch.float32, device="cuda")
+        uws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+        cases.update({
+            "user_my_mad": (rot(lambda i: uk_mad(a[i % sets], b[i % sets], y[(i + 1) % 4], y[i % 4])), 4 * n * n * isz),
+            "user_mad_relu_row_c": (rot(lambda i: uk_mad_relu(a[i % sets], b[i % sets], c, y[i % 4])), 3 * n * n * isz + n * isz),
+            "user_sum_axis0": (rot(lambda i: uk_sum(y[i % 4], o, axis=0, ws=uws)), n * n * isz + n * 4),
+            "user_sum_axis1": (rot(lambda i: uk_sum(y[i % 4], o, axis=1, ws=uws)), n * n * isz + n * 4),
+            "user_sum_all": (rot(lambda i: uk_sum(y[i % 4], o0, axis=None, ws=uws)), n * n * isz + 4),
+        })
         for cname, (fn, nbytes) in cases.items():
             s = timer.time(fn, iters, 4)
             gbs = nbytes / s / 1e9

@@ -436,7 +436,7 @@ chn_status function_for(chn_user_kernel *k, const std::string &key, const std::s
   e = hipModuleGetFunction(&l.fn, l.mod, k->name.c_str());
   if (e == hipSuccess && second) e = hipModuleGetFunction(&l.fn2, l.mod, (k->name + "_finish").c_str());
   if (e != hipSuccess) {
-    hipModuleUnload(l.mod);
+    (void)hipModuleUnload(l.mod);
     return fail(CHN_ERR_LAUNCH, "%s: kernel symbol not found in the code object: %s", k->name.c_str(), hipGetErrorString(e));
   }
   k->loaded[lkey] = l;
@@ -461,9 +461,10 @@ struct EwPlan {
   Dims g;                      // operands: array inputs in order, then outputs
   std::vector<int> arr_of_in;  // input index -> operand index, -1 for scalars
   int n_arr = 0, n_sc = 0;
-  bool flat = false, idx32 = false;
+  bool flat = false, rows = false, idx32 = false;
   int E = 1;
   std::vector<bool> full;      // flat: operand is full-size (else a single repeated element)
+                               // rows: operand advances along the inner dimension (else it repeats)
   int64_t total = 0;
   std::string key, src;
   int n_slots = 0;
@@ -557,6 +558,44 @@ std::string ew_source(const chn_user_kernel &k, const EwPlan &p) {
     o << "  }\n}\n";
     return o.s;
   }
+  if (p.rows) {
+    // two dimensions, every operand with inner stride 1 or 0 and rows that start on vector
+    // boundaries: one vector of the inner dimension per thread (a bias row, a column operand and
+    // pitched views all land here)
+    const int E = p.E;
+    const char *IDX = p.idx32 ? "unsigned" : "long long";
+    o << "  const long long chn_v = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (chn_v >= chn_n / " << E << ") return;\n"
+      << "  const " << IDX << " chn_cvn = (" << IDX << ")chn_s.v[" << geo + 1 << "];\n"
+      << "  const " << IDX << " chn_row = (" << IDX << ")chn_v / chn_cvn;\n"
+      << "  const long long chn_cv = (long long)((" << IDX << ")chn_v - chn_row * chn_cvn);\n";
+    for (int a = 0; a < p.n_arr; ++a)
+      o << "  const long long chn_o" << a << " = (long long)chn_row * (long long)chn_s.v[" << geo + 2 + a << "]"
+        << (p.full[a] ? std::string(" + chn_cv * ") + std::to_string(E) : std::string("")) << ";\n";
+    for (int i = 0; i < n_in; ++i) {
+      const int a = p.arr_of_in[i];
+      if (a < 0) continue;
+      if (p.full[a])
+        o << "  chn_pack<" << storage_type(b.in_dtype[i]) << ", " << E << "> chn_k" << a << "; chn_k" << a << ".load(chn_p" << a << " + chn_o" << a << ");\n";
+      else
+        o << "  const " << compute_type(b.in_dtype[i]) << " chn_x" << i << " = chn_io<" << storage_type(b.in_dtype[i]) << ">::ld(chn_p" << a << " + chn_o" << a << ");\n";
+    }
+    for (int j = 0; j < n_out; ++j)
+      o << "  chn_pack<" << storage_type(b.out_dtype[j]) << ", " << E << "> chn_k" << first_out + j << ";\n";
+    o << "#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j) {\n";
+    for (int i = 0; i < n_in; ++i) {
+      const int a = p.arr_of_in[i];
+      if (a >= 0 && p.full[a])
+        o << "    const " << compute_type(b.in_dtype[i]) << " chn_x" << i << " = chn_io<" << storage_type(b.in_dtype[i]) << ">::up(chn_k" << a << ".e[chn_j]);\n";
+    }
+    for (int j = 0; j < n_out; ++j) o << "    " << compute_type(b.out_dtype[j]) << " chn_y" << j << " = 0;\n";
+    o << "    " << call("chn_v * " + std::to_string(E) + " + chn_j") << "\n";
+    for (int j = 0; j < n_out; ++j)
+      o << "    chn_k" << first_out + j << ".e[chn_j] = chn_io<" << storage_type(b.out_dtype[j]) << ">::pk(chn_y" << j << ");\n";
+    o << "  }\n";
+    for (int j = 0; j < n_out; ++j) o << "  chn_k" << first_out + j << ".store(chn_p" << first_out + j << " + chn_o" << first_out + j << ");\n";
+    o << "}\n";
+    return o.s;
+  }
   // general: one thread per element, full index decomposition (32-bit when the count allows)
   const int nd = p.g.nd;
   const char *IDX = p.idx32 ? "unsigned" : "long long";
@@ -636,9 +675,23 @@ chn_status ew_plan(chn_user_kernel *k, int n_in, const chn_array *const *in, int
     if (p->full[a] && reinterpret_cast<uintptr_t>(arrs[a]->data) % (p->E * dtype_size(arrs[a]->dtype))) p->flat = false;
   }
   p->idx32 = p->total < 0x7fffffffll;
+  if (!p->flat && p->g.nd == 2 && p->g.shape[1] % p->E == 0) {
+    p->rows = true;
+    for (int a = 0; a < p->n_arr && p->rows; ++a) {
+      const int64_t s0 = p->g.str[a][0], s1 = p->g.str[a][1];
+      const bool is_out = a >= p->n_arr - n_out;
+      p->full[a] = s1 == 1;
+      if (s1 != 1 && (s1 != 0 || is_out)) p->rows = false;
+      if (p->full[a] && (s0 % p->E || reinterpret_cast<uintptr_t>(arrs[a]->data) % (p->E * dtype_size(arrs[a]->dtype)))) p->rows = false;
+    }
+  }
   Src key;
   key << "ew|" << dtype_key(p->b) << "|";
-  if (p->flat) {
+  if (p->rows) {
+    key << "rows" << p->E << (p->idx32 ? "|i32|" : "|i64|");
+    for (int a = 0; a < p->n_arr; ++a) key << (p->full[a] ? "f" : "s");
+    p->n_slots = p->n_arr + p->n_sc + 2 + p->n_arr;
+  } else if (p->flat) {
     key << "flat" << p->E << "|";
     for (int a = 0; a < p->n_arr; ++a) key << (p->full[a] ? "f" : "s");
     p->n_slots = p->n_arr + p->n_sc + 1;
@@ -660,7 +713,10 @@ void ew_slots(const EwPlan &p, int n_in, const chn_array *const *in, int n_out, 
   for (int j = 0; j < n_out; ++j) s->ptr(out[j]->data);
   for (int c = 0; c < p.n_sc; ++c) s->f64(scalars[c]);
   s->i64(p.total);
-  if (!p.flat) {
+  if (p.rows) {
+    s->i64(p.g.shape[1] / p.E);
+    for (int a = 0; a < p.n_arr; ++a) s->i64(p.g.str[a][0]);
+  } else if (!p.flat) {
     for (int d = 0; d < p.g.nd; ++d) s->i64(p.g.shape[d]);
     for (int a = 0; a < p.n_arr; ++a)
       for (int d = 0; d < p.g.nd; ++d) s->i64(p.g.str[a][d]);
@@ -676,6 +732,8 @@ struct RdPlan {
   int64_t n_res = 0, R = 0;    // number of results, elements folded into each
   bool per_thread = false;     // one thread per result (the contiguous dimension is kept) vs one block per result
   bool idx32 = false;
+  int E = 1;                   // elements per vector access (1: scalar accesses)
+  bool finish_block = false;   // second pass: one block per result (few results, many slices)
   int64_t slices = 1, chunk = 0;
   std::string key, src;
   int n_slots = 0;
@@ -683,9 +741,19 @@ struct RdPlan {
 
 constexpr int kAxisAll = CHN_AXIS_ALL;
 
+// Two mappings, each in a scalar and a vector form:
+//   per block   one workgroup folds one result (or one slice of it); lanes stride along the reduced
+//               range -- taken when the reduced dimension is the contiguous one (row sums, full sums);
+//               vector form: 16 bytes per lane along that range;
+//   per thread  one thread folds one result; neighbouring threads hold neighbouring results -- taken
+//               when a kept dimension is the contiguous one (column sums); vector form: each thread
+//               holds E neighbouring results and reads them with one 16-byte access per row.
+// A long reduced range is cut into slices (grid dimension y) whose partial values a second kernel
+// folds in slice order.
 std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
   const Binding &b = p.b;
   const int n_in = (int)k.in.size(), n_out = (int)k.out.size();
+  const int E = p.E;
   const std::string RT = compute_type(b.out_dtype[0]);
   Src o;
   o << kPrelude << "struct chn_slots { unsigned long long v[" << p.n_slots << "]; };\ntypedef " << RT << " chn_R;\n" << k.preamble << "\n";
@@ -727,7 +795,7 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
       s << "  " << storage_type(b.out_dtype[j]) << " *chn_p" << p.n_arr_in + j << " = (" << storage_type(b.out_dtype[j]) << " *)chn_s.v[" << p.n_arr_in + j << "];\n";
     s << "  const long long chn_nres = (long long)chn_s.v[" << geo << "];\n  const long long chn_R_len = (long long)chn_s.v[" << geo + 1 << "];\n"
       << "  const long long chn_slices = (long long)chn_s.v[" << geo + 2 << "];\n  const long long chn_chunk = (long long)chn_s.v[" << geo + 3 << "];\n"
-      << "  chn_R *chn_part = (chn_R *)chn_s.v[" << geo + 4 << "];\n";
+      << "  chn_R *chn_part = (chn_R *)chn_s.v[" << geo + 4 << "];\n  (void)chn_R_len; (void)chn_chunk; (void)chn_slices; (void)chn_part;\n";
   };
   // offsets of result `chn_res` in every operand
   auto out_offsets = [&](Src &s, bool inputs) {
@@ -742,22 +810,26 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
     }
     s << "  }\n";
   };
-  // one mapped element at reduce index chn_r folded into chn_acc
-  auto fold_one = [&](Src &s, const char *ind) {
-    s << ind << "{\n";
+  // offsets chn_q<a> of reduce index chn_r in every array input
+  auto reduce_offsets = [&](Src &s, const std::string &ind) {
     if (ndr == 1) {
-      for (int a = 0; a < p.n_arr_in; ++a) s << ind << "  const long long chn_q" << a << " = chn_o" << a << " + chn_r * (long long)chn_s.v[" << sr + 1 + a << "];\n";
-    } else {
-      for (int a = 0; a < p.n_arr_in; ++a) s << ind << "  long long chn_q" << a << " = chn_o" << a << ";\n";
-      s << ind << "  " << IDX << " chn_rr = (" << IDX << ")chn_r;\n";
-      for (int d = ndr - 1; d >= 0; --d) {
-        s << ind << "  {\n" << ind << "    const " << IDX << " chn_sh = (" << IDX << ")chn_s.v[" << sr + d << "];\n" << ind << "    const " << IDX
-          << " chn_q = chn_rr / chn_sh;\n" << ind << "    const long long chn_i = (long long)(chn_rr - chn_q * chn_sh);\n" << ind << "    chn_rr = chn_q;\n";
-        for (int a = 0; a < p.n_arr_in; ++a)
-          s << ind << "    chn_q" << a << " += chn_i * (long long)chn_s.v[" << sr + ndr + a * ndr + d << "];\n";
-        s << ind << "  }\n";
-      }
+      for (int a = 0; a < p.n_arr_in; ++a) s << ind << "const long long chn_q" << a << " = chn_o" << a << " + chn_r * (long long)chn_s.v[" << sr + 1 + a << "];\n";
+      return;
     }
+    for (int a = 0; a < p.n_arr_in; ++a) s << ind << "long long chn_q" << a << " = chn_o" << a << ";\n";
+    s << ind << IDX << " chn_rr = (" << IDX << ")chn_r;\n";
+    for (int d = ndr - 1; d >= 0; --d) {
+      s << ind << "{\n" << ind << "  const " << IDX << " chn_sh = (" << IDX << ")chn_s.v[" << sr + d << "];\n" << ind << "  const " << IDX
+        << " chn_q = chn_rr / chn_sh;\n" << ind << "  const long long chn_i = (long long)(chn_rr - chn_q * chn_sh);\n" << ind << "  chn_rr = chn_q;\n";
+      for (int a = 0; a < p.n_arr_in; ++a)
+        s << ind << "  chn_q" << a << " += chn_i * (long long)chn_s.v[" << sr + ndr + a * ndr + d << "];\n";
+      s << ind << "}\n";
+    }
+  };
+  // one mapped element at reduce index chn_r folded into chn_acc (scalar accesses)
+  auto fold_one = [&](Src &s, const std::string &ind) {
+    s << ind << "{\n";
+    reduce_offsets(s, ind + "  ");
     for (int i = 0; i < n_in; ++i) {
       const int a = p.arr_of_in[i];
       if (a >= 0)
@@ -765,46 +837,113 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
     }
     s << ind << "  chn_acc = chn_fold(chn_acc, chn_map(" << in_args << "chn_res * chn_R_len + chn_r));\n" << ind << "}\n";
   };
-  auto finish = [&](Src &s, const char *ind) {
-    for (int j = 0; j < n_out; ++j) s << ind << compute_type(b.out_dtype[j]) << " chn_y" << j << " = 0;\n";
-    s << ind << "chn_post(chn_acc" << out_args << sc_args << ");\n";
+  // final expression and stores for the result whose folded value is `acc`, outputs at offset chn_o<a> + `shift`
+  auto finish = [&](Src &s, const std::string &ind, const std::string &acc, const std::string &shift) {
+    s << ind << "{\n";
+    for (int j = 0; j < n_out; ++j) s << ind << "  " << compute_type(b.out_dtype[j]) << " chn_y" << j << " = 0;\n";
+    s << ind << "  chn_post(" << acc << out_args << sc_args << ");\n";
     for (int j = 0; j < n_out; ++j)
-      s << ind << "chn_p" << p.n_arr_in + j << "[chn_o" << p.n_arr_in + j << "] = chn_io<" << storage_type(b.out_dtype[j]) << ">::pk(chn_y" << j << ");\n";
+      s << ind << "  chn_p" << p.n_arr_in + j << "[chn_o" << p.n_arr_in + j << shift << "] = chn_io<" << storage_type(b.out_dtype[j]) << ">::pk(chn_y" << j << ");\n";
+    s << ind << "}\n";
   };
+  const std::string tree =
+      "  chn_sm[threadIdx.x] = chn_acc;\n  __syncthreads();\n"
+      "  for (int chn_w = 128; chn_w > 0; chn_w >>= 1) {\n"
+      "    if ((int)threadIdx.x < chn_w) chn_sm[threadIdx.x] = chn_fold(chn_sm[threadIdx.x], chn_sm[threadIdx.x + chn_w]);\n"
+      "    __syncthreads();\n  }\n  if (threadIdx.x != 0) return;\n  chn_acc = chn_sm[0];\n";
+
   o << "extern \"C\" __global__ __launch_bounds__(256) void " << k.name << "(const chn_slots chn_s) {\n";
   decl(o);
   if (p.per_thread) {
-    o << "  const long long chn_res = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (chn_res >= chn_nres) return;\n";
+    o << "  const long long chn_res = ((long long)blockIdx.x * 256 + threadIdx.x) * " << E << ";\n  if (chn_res >= chn_nres) return;\n";
   } else {
     o << "  __shared__ chn_R chn_sm[256];\n  const long long chn_res = blockIdx.x;\n";
   }
   out_offsets(o, true);
   o << "  const long long chn_lo = (long long)blockIdx.y * chn_chunk;\n"
-    << "  const long long chn_hi = chn_lo + chn_chunk < chn_R_len ? chn_lo + chn_chunk : chn_R_len;\n"
-    << "  chn_R chn_acc = (chn_R)(" << k.identity << ");\n";
-  if (p.per_thread) {
-    o << "#pragma unroll 8\n  for (long long chn_r = chn_lo; chn_r < chn_hi; ++chn_r)\n";
-    fold_one(o, "  ");
+    << "  const long long chn_hi = chn_lo + chn_chunk < chn_R_len ? chn_lo + chn_chunk : chn_R_len;\n";
+  if (p.per_thread && E > 1) {
+    // E neighbouring results per thread: the last kept dimension is contiguous in every input
+    o << "  chn_R chn_acc[" << E << "];\n#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j) chn_acc[chn_j] = (chn_R)(" << k.identity << ");\n";
+    o << "#pragma unroll 4\n  for (long long chn_r = chn_lo; chn_r < chn_hi; ++chn_r) {\n";
+    reduce_offsets(o, "    ");
+    for (int i = 0; i < n_in; ++i) {
+      const int a = p.arr_of_in[i];
+      if (a >= 0) o << "    chn_pack<" << storage_type(b.in_dtype[i]) << ", " << E << "> chn_k" << a << "; chn_k" << a << ".load(chn_p" << a << " + chn_q" << a << ");\n";
+    }
+    o << "#pragma unroll\n    for (int chn_j = 0; chn_j < " << E << "; ++chn_j) {\n";
+    for (int i = 0; i < n_in; ++i) {
+      const int a = p.arr_of_in[i];
+      if (a >= 0) o << "      const " << compute_type(b.in_dtype[i]) << " chn_x" << i << " = chn_io<" << storage_type(b.in_dtype[i]) << ">::up(chn_k" << a << ".e[chn_j]);\n";
+    }
+    o << "      chn_acc[chn_j] = chn_fold(chn_acc[chn_j], chn_map(" << in_args << "(chn_res + chn_j) * chn_R_len + chn_r));\n    }\n  }\n";
+    o << "  if (chn_slices > 1) {\n#pragma unroll\n    for (int chn_j = 0; chn_j < " << E << "; ++chn_j) chn_part[(long long)blockIdx.y * chn_nres + chn_res + chn_j] = chn_acc[chn_j];\n    return;\n  }\n";
+    o << "#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j)\n";
+    // the E results differ only in the last kept dimension: their outputs are one stride apart
+    std::string body;
+    {
+      Src t;
+      t << "  {\n";
+      for (int j = 0; j < n_out; ++j) t << "    " << compute_type(b.out_dtype[j]) << " chn_y" << j << " = 0;\n";
+      t << "    chn_post(chn_acc[chn_j]" << out_args << sc_args << ");\n";
+      for (int j = 0; j < n_out; ++j)
+        t << "    chn_p" << p.n_arr_in + j << "[chn_o" << p.n_arr_in + j << " + chn_j * (long long)chn_s.v[" << so + ndo + (p.n_arr_in + j) * ndo + (ndo - 1)
+          << "]] = chn_io<" << storage_type(b.out_dtype[j]) << ">::pk(chn_y" << j << ");\n";
+      t << "  }\n";
+      body = t.s;
+    }
+    o << body << "}\n";
   } else {
-    o << "#pragma unroll 4\n  for (long long chn_r = chn_lo + threadIdx.x; chn_r < chn_hi; chn_r += 256)\n";
-    fold_one(o, "  ");
-    o << "  chn_sm[threadIdx.x] = chn_acc;\n  __syncthreads();\n"
-      << "  for (int chn_w = 128; chn_w > 0; chn_w >>= 1) {\n"
-      << "    if ((int)threadIdx.x < chn_w) chn_sm[threadIdx.x] = chn_fold(chn_sm[threadIdx.x], chn_sm[threadIdx.x + chn_w]);\n"
-      << "    __syncthreads();\n  }\n  if (threadIdx.x != 0) return;\n  chn_acc = chn_sm[0];\n";
+    o << "  chn_R chn_acc = (chn_R)(" << k.identity << ");\n";
+    if (p.per_thread) {
+      o << "#pragma unroll 8\n  for (long long chn_r = chn_lo; chn_r < chn_hi; ++chn_r)\n";
+      fold_one(o, "  ");
+    } else if (E > 1) {
+      // the reduced range is contiguous in every input: 16 bytes per lane, then a scalar tail
+      o << "  const long long chn_nv = (chn_hi - chn_lo) / " << E << ";\n#pragma unroll 4\n"
+        << "  for (long long chn_vi = threadIdx.x; chn_vi < chn_nv; chn_vi += 256) {\n    const long long chn_r0 = chn_lo + chn_vi * " << E << ";\n";
+      for (int i = 0; i < n_in; ++i) {
+        const int a = p.arr_of_in[i];
+        if (a >= 0) o << "    chn_pack<" << storage_type(b.in_dtype[i]) << ", " << E << "> chn_k" << a << "; chn_k" << a << ".load(chn_p" << a << " + chn_o" << a << " + chn_r0);\n";
+      }
+      o << "#pragma unroll\n    for (int chn_j = 0; chn_j < " << E << "; ++chn_j) {\n";
+      for (int i = 0; i < n_in; ++i) {
+        const int a = p.arr_of_in[i];
+        if (a >= 0) o << "      const " << compute_type(b.in_dtype[i]) << " chn_x" << i << " = chn_io<" << storage_type(b.in_dtype[i]) << ">::up(chn_k" << a << ".e[chn_j]);\n";
+      }
+      o << "      chn_acc = chn_fold(chn_acc, chn_map(" << in_args << "chn_res * chn_R_len + chn_r0 + chn_j));\n    }\n  }\n"
+        << "  for (long long chn_r = chn_lo + chn_nv * " << E << " + threadIdx.x; chn_r < chn_hi; chn_r += 256)\n";
+      fold_one(o, "  ");
+    } else {
+      o << "#pragma unroll 4\n  for (long long chn_r = chn_lo + threadIdx.x; chn_r < chn_hi; chn_r += 256)\n";
+      fold_one(o, "  ");
+    }
+    if (!p.per_thread) o << tree;
+    o << "  if (chn_slices > 1) {\n    chn_part[(long long)blockIdx.y * chn_nres + chn_res] = chn_acc;\n    return;\n  }\n";
+    finish(o, "  ", "chn_acc", "");
+    o << "}\n";
   }
-  o << "  if (chn_slices > 1) {\n    chn_part[(long long)blockIdx.y * chn_nres + chn_res] = chn_acc;\n    return;\n  }\n";
-  finish(o, "  ");
-  o << "}\n";
-  // second pass: fold the slices of every result in slice order, then the final expression
+  // second pass: fold the slices of every result in a fixed order, then the final expression
   o << "extern \"C\" __global__ __launch_bounds__(256) void " << k.name << "_finish(const chn_slots chn_s) {\n";
   decl(o);
-  o << "  const long long chn_res = (long long)blockIdx.x * 256 + threadIdx.x;\n  if (chn_res >= chn_nres) return;\n";
+  if (p.finish_block) {
+    o << "  __shared__ chn_R chn_sm[256];\n  const long long chn_res = blockIdx.x;\n"
+      << "  chn_R chn_acc = (chn_R)(" << k.identity << ");\n"
+      << "  for (long long chn_sl = threadIdx.x; chn_sl < chn_slices; chn_sl += 256) chn_acc = chn_fold(chn_acc, chn_part[chn_sl * chn_nres + chn_res]);\n"
+      << tree;
+  } else {
+    // 64 neighbouring results per block, four lanes of slices each, combined in a fixed order
+    o << "  __shared__ chn_R chn_sm[256];\n  const int chn_lane = threadIdx.x & 63, chn_grp = threadIdx.x >> 6;\n"
+      << "  const long long chn_res = (long long)blockIdx.x * 64 + chn_lane;\n"
+      << "  chn_R chn_acc = (chn_R)(" << k.identity << ");\n"
+      << "  if (chn_res < chn_nres) {\n#pragma unroll 8\n"
+      << "    for (long long chn_sl = chn_grp; chn_sl < chn_slices; chn_sl += 4) chn_acc = chn_fold(chn_acc, chn_part[chn_sl * chn_nres + chn_res]);\n  }\n"
+      << "  chn_sm[threadIdx.x] = chn_acc;\n  __syncthreads();\n  if (chn_grp != 0 || chn_res >= chn_nres) return;\n"
+      << "  chn_acc = chn_fold(chn_fold(chn_fold(chn_sm[chn_lane], chn_sm[64 + chn_lane]), chn_sm[128 + chn_lane]), chn_sm[192 + chn_lane]);\n";
+  }
   out_offsets(o, false);
-  o << "  chn_R chn_acc = chn_part[chn_res];\n"
-    << "  for (long long chn_sl = 1; chn_sl < chn_slices; ++chn_sl) chn_acc = chn_fold(chn_acc, chn_part[chn_sl * chn_nres + chn_res]);\n";
-  finish(o, "  ");
-  o << "  (void)chn_R_len; (void)chn_chunk;\n}\n";
+  finish(o, "  ", "chn_acc", "");
+  o << "}\n";
   return o.s;
 }
 
@@ -889,19 +1028,44 @@ chn_status rd_plan(chn_user_kernel *k, int n_in, const chn_array *const *in, int
   collapse(&p->gr);
   if (p->gr.nd == 0) { p->gr.nd = 1; p->gr.shape[0] = p->R; for (auto &s : p->gr.str) s.assign(1, 0); }
   p->idx32 = p->n_res < 0x7fffffffll && p->R < 0x7fffffffll;
+  // vector accesses: 16 bytes per lane along the contiguous dimension when every array input
+  // allows it (unit stride there, every other stride and the base address on vector boundaries)
+  {
+    int max_isz = 1;
+    std::vector<const chn_array *> ins;
+    for (int i = 0; i < n_in; ++i) if (in[i]) { ins.push_back(in[i]); max_isz = std::max(max_isz, dtype_size(in[i]->dtype)); }
+    const int E = 16 / max_isz;
+    bool ok = p->R > 0;
+    for (int a = 0; a < p->n_arr_in && ok; ++a) {
+      ok = reinterpret_cast<uintptr_t>(ins[a]->data) % (E * dtype_size(ins[a]->dtype)) == 0;
+      if (p->per_thread) {
+        const int last = p->go.nd - 1;
+        ok = ok && last >= 0 && p->go.shape[last] % E == 0 && p->go.str[a][last] == 1;
+        for (int d = 0; d < last && ok; ++d) ok = p->go.str[a][d] % E == 0;
+        for (int d = 0; d < p->gr.nd && ok; ++d) ok = p->gr.str[a][d] % E == 0;
+      } else {
+        ok = ok && p->gr.nd == 1 && p->gr.str[a][0] == 1;
+        for (int d = 0; d < p->go.nd && ok; ++d) ok = p->go.str[a][d] % E == 0;
+      }
+    }
+    p->E = ok ? E : 1;
+  }
   // slices of the reduced range so that the launch fills the chip; each slice at least 64 (per
-  // thread) or 1024 (per block) elements long
-  const int64_t blocks = p->per_thread ? (p->n_res + 255) / 256 : p->n_res;
-  const int64_t min_len = p->per_thread ? 64 : 1024;
+  // thread) or 4096 (per block) elements long and a whole number of vectors
+  const int64_t blocks = p->per_thread ? (p->n_res / p->E + 255) / 256 : p->n_res;
+  const int64_t min_len = p->per_thread ? 64 : 4096;
   int64_t s = blocks >= 2048 ? 1 : (2048 + blocks - 1) / blocks;
   s = std::min<int64_t>(s, std::max<int64_t>(1, p->R / min_len));
   s = std::min<int64_t>(s, 1024);
   p->chunk = p->R == 0 ? 1 : (p->R + s - 1) / s;
+  p->chunk = (p->chunk + p->E - 1) / p->E * p->E;
   p->slices = p->R == 0 ? 1 : (p->R + p->chunk - 1) / p->chunk;
+  p->finish_block = !p->per_thread && p->n_res <= 64;
   const int n_arr = p->n_arr_in + n_out;
   p->n_slots = n_arr + p->n_sc + 5 + p->go.nd * (1 + n_arr) + p->gr.nd * (1 + p->n_arr_in);
   Src key;
-  key << "rd|" << dtype_key(p->b) << "|" << (p->per_thread ? "t" : "b") << "|o" << p->go.nd << "r" << p->gr.nd << (p->idx32 ? "|i32" : "|i64");
+  key << "rd|" << dtype_key(p->b) << "|" << (p->per_thread ? "t" : "b") << p->E << (p->finish_block ? "B" : "T") << "|o" << p->go.nd << "r" << p->gr.nd
+      << (p->idx32 ? "|i32" : "|i64");
   p->key = key.s;
   p->src = rd_source(*k, *p);
   return CHN_OK;
@@ -996,7 +1160,7 @@ chn_status chn_reduction_kernel_create(const char *in_params, const char *out_pa
 
 void chn_user_kernel_destroy(chn_user_kernel *k) {
   if (!k) return;
-  for (auto &l : k->loaded) hipModuleUnload(l.second.mod);
+  for (auto &l : k->loaded) (void)hipModuleUnload(l.second.mod);
   delete k;
 }
 
@@ -1023,7 +1187,7 @@ chn_status chn_elementwise_kernel_launch(chn_user_kernel *k, int n_in, const chn
   CHN_TRY(function_for(k, p.key, p.src, false, &f));
   Slots s;
   ew_slots(p, n_in, in, n_out, out, scalars, &s);
-  const int64_t threads = p.flat ? std::max<int64_t>(p.total / p.E, p.E) : p.total;
+  const int64_t threads = p.rows ? p.total / p.E : p.flat ? std::max<int64_t>(p.total / p.E, p.E) : p.total;
   const int64_t blocks = (threads + 255) / 256;
   if (blocks > 0x7fffffffll) return fail(CHN_ERR_SHAPE, "%s: too many elements for one launch", k->name.c_str());
   return launch(k, f.fn, (unsigned)blocks, 1, 256, s, p.n_slots, stream);
@@ -1063,10 +1227,11 @@ chn_status chn_reduction_kernel_launch(chn_user_kernel *k, int n_in, const chn_a
   CHN_TRY(function_for(k, p.key, p.src, true, &f));
   Slots s;
   rd_slots(p, n_in, in, n_out, out, scalars, p.slices > 1 ? ws : nullptr, &s);
-  const int64_t gx = p.per_thread ? (p.n_res + 255) / 256 : p.n_res;
+  const int64_t gx = p.per_thread ? (p.n_res / p.E + 255) / 256 : p.n_res;
   if (gx > 0x7fffffffll || p.slices > 65535) return fail(CHN_ERR_SHAPE, "%s: too many results for one launch", k->name.c_str());
   CHN_TRY(launch(k, f.fn, (unsigned)gx, (unsigned)p.slices, 256, s, p.n_slots, stream));
-  if (p.slices > 1) CHN_TRY(launch(k, f.fn2, (unsigned)((p.n_res + 255) / 256), 1, 256, s, p.n_slots, stream));
+  if (p.slices > 1)
+    CHN_TRY(launch(k, f.fn2, (unsigned)(p.finish_block ? p.n_res : (p.n_res + 63) / 64), 1, 256, s, p.n_slots, stream));
   return CHN_OK;
 }
 

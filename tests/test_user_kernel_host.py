@@ -93,14 +93,19 @@ def test_generated_form_follows_layout_and_types(cache):
     assert "chn_pack<chn_bf16, 8>" in k.source(h, h, h)                       # 16 bytes per lane
     li = fake((64, 100), B.I64)
     assert "chn_pack<long long, 2>" in k.source(li, li, li) and "typedef long long T;" in k.source(li, li, li)
-    # a repeated single element is read once; a row-shaped operand needs the strided form
+    # a repeated single element is read once
     one = fake((1, 1))
     assert "chn_io<float>::ld(chn_p1);" in k.source(x, one, x)
-    row = fake((100,))
-    assert "chn_rem" in k.source(x, row, x)
-    # transposed view, pitched rows, a pointer that is not 16-byte aligned: the strided form
+    # a row operand, a column operand, rows pitched by whole vectors: one vector of the row per thread
+    for other in (fake((100,)), fake((64, 1)), fake((64, 100), strides=[512, 4])):
+        src = k.source(x, other, x)
+        assert "chn_row" in src and "chn_pack<float, 4>" in src and "chn_rem" not in src
+    assert "chn_io<float>::ld(chn_p1 + chn_o1);" in k.source(x, fake((64, 1)), x)      # the column: once per thread
+    # transposed view, rows pitched by an odd count, a row length that is no whole number of
+    # vectors, a pointer that is not 16-byte aligned: one element per thread
     assert "chn_rem" in k.source(fake((64, 100), strides=[4, 256]), x, x)
-    assert "chn_rem" in k.source(fake((64, 100), strides=[512, 4]), x, x)
+    assert "chn_rem" in k.source(fake((64, 100), strides=[404, 4]), x, x)
+    assert "chn_rem" in k.source(fake((64, 99)), fake((99,)), fake((64, 99)))
     assert "chn_rem" in k.source(fake((64, 100), ptr=0x7f0000000004), x, x)
     # more than 2^31 elements: 64-bit index arithmetic
     big = fake((1 << 16, 1 << 16), strides=[0, 0])
@@ -145,7 +150,7 @@ def test_compile_cache_memory_then_disk_then_compiler(cache):
     k2 = B.ElementwiseKernel("float32 x, float32 y, float32 z", "float32 w", "w = x * y + z", "my_mad")
     k2.prepare(x, x, x, x)                                   # a later object (or run): disk
     assert B.user_kernel_stats() == (c0 + 1, d0 + 1, m0 + 1)
-    k2.prepare(fake((32, 32), strides=[256, 4]), x, x, x)    # another form of the same kernel: compiled
+    k2.prepare(fake((32, 32), strides=[4, 128]), x, x, x)    # another form of the same kernel: compiled
     assert B.user_kernel_stats()[0] == c0 + 2 and len(os.listdir(cache)) == 2
     k3 = B.ElementwiseKernel("float32 x, float32 y, float32 z", "float32 w", "w = x * y - z", "my_mad")
     k3.prepare(x, x, x, x)                                   # another snippet: compiled
@@ -185,7 +190,12 @@ def test_reduction_declaration_shapes_and_workspace(cache):
         assert e.value.status == status
     src_row = s.source(x, fake((8192,)), axis=1)
     src_col = s.source(x, fake((4096,)), axis=0)
-    assert "__shared__" in src_row.split("_finish")[0] and "__shared__" not in src_col
+    assert "__shared__" in src_row.split("_finish")[0] and "__shared__" not in src_col.split("_finish")[0]
+    assert "chn_pack<float, 4>" in src_row and "chn_acc[4]" in src_col             # 16 bytes per lane in both
+    odd = fake((8192, 4095))
+    assert "chn_pack<float" not in s.source(odd, fake((8192,)), axis=1)              # rows off the vector grid
+    assert "chn_pack<float" not in s.source(odd, fake((4095,)), axis=0)
+    assert "chn_sl += 256" in s.source(x, fake(()), axis=None).split("_finish")[1]   # one result: a block folds the slices
 
 
 def test_new_entry_points_are_exported():
