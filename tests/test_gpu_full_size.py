@@ -60,6 +60,38 @@ def test_config2_full_size_array_primitives(dt):
     assert abs(s0.sum() - s1.sum()) <= 1e-5 * np.abs(yh).sum(dtype=np.float64)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_config2_full_size_user_defined_kernels(dt):
+    """The benchmark's user-kernel lines: the figure's multiply-add with type parameter T, its
+    ReLU variant with a row operand, and a user-written sum over either axis and over everything."""
+    from oracle import user_kernel as OU
+    n = 8192
+    w = W.config2(n)
+    tdt = torch.float32 if dt == "f32" else torch.bfloat16
+    a, b, c = (torch.from_numpy(x).cuda().to(tdt) for x in (w.a, w.b, w.c))
+    ah, bh, ch = h32(a), h32(b), h32(c)
+    tol = TOL_EW if dt == "f32" else TOL_BF16
+    tol_s = TOL_SUM if dt == "f32" else TOL_BF16
+    rows = np.sort(RNG.choice(n, 48, replace=False))
+    cols = np.sort(RNG.choice(n, 48, replace=False))
+    mad = ("T x, T y, T z", "T w", "w = x * y + z", "my_mad")
+    y = B.ElementwiseKernel(*mad)(a, b, a)
+    check(host(y)[rows], OU.ElementwiseKernel(*mad)(ah[rows], bh[rows], ah[rows]), tol,
+          np.abs(ah[rows] * bh[rows]) + np.abs(ah[rows]), "my_mad rows")
+    mr = ("T x, T y, T z", "T w", "w = fmax(x * y + z, (T)0)", "my_mad_relu")
+    y = B.ElementwiseKernel(*mr)(a, b, c)
+    yh = h32(y)
+    check(yh[rows].astype(np.float64), OU.ElementwiseKernel(*mr)(ah[rows], bh[rows], ch), tol,
+          np.abs(ah[rows] * bh[rows]) + np.abs(ch), "my_mad_relu rows")
+    sm = ("T x", "float32 y", "x", "a + b", "y = a", "0", "my_sum")
+    k, ko = B.ReductionKernel(*sm), OU.ReductionKernel(*sm)
+    s0, s1, sa = host(k(y, axis=0)), host(k(y, axis=1)), float(k(y, axis=None).cpu())
+    check(s0[cols], ko(yh[:, cols], axis=0), tol_s, np.abs(yh[:, cols]).sum(axis=0, dtype=np.float64), "user sum axis 0")
+    check(s1[rows], ko(yh[rows], axis=1), tol_s, np.abs(yh[rows]).sum(axis=1, dtype=np.float64), "user sum axis 1")
+    total = float(ko(yh, axis=None))
+    assert abs(sa - total) <= tol_s * float(np.abs(yh).sum(dtype=np.float64))
+
+
 def test_config5_full_size_step_sampled():
     w = W.config5(n_batches=1)
     x = W.bf16_exact(w.xs[0])
