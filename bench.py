@@ -199,8 +199,8 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, g
     return res
 
 
-def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False):
-    tr = steps_mod.LSTMTrainer(w.params, w.bptt, w.batch, w.lr)
+def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False, lowp=False):
+    tr = steps_mod.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, lowp=lowp)
     ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
     s = timer.time(lambda: tr.step(ids, tg, graph=graph), steps, warmup)
     return {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s, "loss": float(tr.loss.cpu()),
@@ -384,6 +384,11 @@ def main():
             log("  %s%.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s (%.1f%% of fp32 MFMA peak; %d launches/step)" % (
                 "HIP graph: " if graph else "", r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"],
                 100 * r["frac_mfma_peak_f32"], r["launch_calls_per_step"]))
+        r = bench_lstm(torch, B, steps_mod, w4, timer, 20, 3, lowp=True)
+        r.pop("frac_mfma_peak_f32")
+        extra["cfg4_lstm_lm_bf16"] = r
+        log("  mixed precision (bf16 storage, fp32 accumulate): %.3f ms/step  %.1f steps/s  %.0f tokens/s  %.1f TFLOP/s" % (
+            r["ms_per_step"], r["steps_per_s"], r["tokens_per_s"], r["TFLOP/s"]))
 
     if "tape" in sel:
         log("define-by-run tape driving the same steps")

@@ -166,7 +166,9 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
  * last axis in the order i, f, g, o; `bias` (4H,) or NULL is added to z.
  *   i,f,o = sigmoid(z_i,z_f,z_o)  g = tanh(z_g)  c = f*c_prev + i*g  h = o*tanh(c)
  * c_prev, c, h are (B,H); `gates` (B,4H) or NULL receives the activated i,f,g,o for the backward.
- * All F32, rows may be pitched (stride[0] free), unit stride along the last axis. */
+ * F32, rows may be pitched (stride[0] free), unit stride along the last axis.  Mixed precision: the
+ * arrays that feed matrix products -- h here, dh and dz in the backward -- may be BF16 (stores round to
+ * nearest even); z, gates and the cell state are always F32. */
 chn_status chn_lstm_fwd(const chn_array *z, const chn_array *bias, const chn_array *c_prev,
                         const chn_array *c, const chn_array *h, const chn_array *gates,
                         chn_stream stream);

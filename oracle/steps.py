@@ -71,56 +71,71 @@ def mlp_loss(params, x, t, act="relu"):
     return O.softmax_ce_fwd(h, t)[0]
 
 
-def lstm_lm_forward(P, ids, targets):
+def lstm_lm_forward(P, ids, targets, lowp=False):
     """Forward of the LSTM language model.  P: dict(E, W, U, b, W_out, b_out); ids, targets (T,B).
 
     W (E_dim,4H) and U (H,4H) are stored so that the gates are x W + h U + b; W_out (V,H) follows the
     Linear convention y = h @ W_out.T + b_out.
+
+    ``lowp``: the arrays that feed matrix products are stored in bfloat16 -- working copies of E, W, U
+    and W_out, and every h; gate pre-activations, activated gates, the cell state, logits and the loss
+    stay unrounded.
     """
     T, B = ids.shape
     H = P["U"].shape[0]
-    X = O.embed_fwd(P["E"], ids.reshape(-1))                  # (T*B, E_dim), time-major
-    Zx = O.gemm(X, P["W"])                                    # (T*B, 4H)
+    Pl = {k: _st(np.asarray(P[k], dtype=np.float64), lowp) if k in ("E", "W", "U", "W_out") else np.asarray(P[k], dtype=np.float64)
+          for k in P}
+    X = O.embed_fwd(Pl["E"], ids.reshape(-1))                 # (T*B, E_dim), time-major
+    Zx = O.gemm(X, Pl["W"])                                   # (T*B, 4H)
     h = np.zeros((B, H))
     c = np.zeros((B, H))
     Hs, Cs, Gs, Cprev, Hprev = [], [], [], [], []
     for t in range(T):
-        z = O.gemm(h, P["U"], Zx[t * B:(t + 1) * B], 1.0, 1.0)
+        z = O.gemm(h, Pl["U"], Zx[t * B:(t + 1) * B], 1.0, 1.0)
         Cprev.append(c)
         Hprev.append(h)
         c, h, g = O.lstm_fwd(z, P["b"], c)
+        h = _st(h, lowp)
         Hs.append(h); Cs.append(c); Gs.append(g)
     Hall = np.concatenate(Hs, axis=0)                         # (T*B, H)
-    logits = O.elementwise("add", [O.gemm(Hall, np.asarray(P["W_out"], dtype=np.float64).T),
-                                   P["b_out"]])
+    logits = O.elementwise("add", [O.gemm(Hall, Pl["W_out"].T), P["b_out"]])
     loss = O.softmax_ce_fwd(logits, targets.reshape(-1))[0]
-    return dict(loss=loss, logits=logits, X=X, Hall=Hall, Cs=Cs, Gs=Gs, Cprev=Cprev, Hprev=Hprev)
+    return dict(loss=loss, logits=logits, X=X, Hall=Hall, Cs=Cs, Gs=Gs, Cprev=Cprev, Hprev=Hprev, Pl=Pl)
 
 
-def lstm_lm_step(P, ids, targets, lr):
-    """One forward + full BPTT + SGD step.  Returns dict(loss, grads{name}, params{name})."""
+def lstm_lm_step(P, ids, targets, lr, lowp=False):
+    """One forward + full BPTT + SGD step.  Returns dict(loss, grads{name}, params{name}).
+
+    ``lowp`` additionally stores the activation gradients that feed matrix products in bfloat16:
+    the logit gradients, the gradient of every h (rounded again after the recurrent term has been
+    added into it) and the gate gradients; parameter gradients, the cell-state gradient, the
+    embedding-output gradient and the master parameters are never rounded."""
     T, B = ids.shape
     H = P["U"].shape[0]
     V = P["E"].shape[0]
-    F = lstm_lm_forward(P, ids, targets)
-    dlogits = O.softmax_ce_bwd(F["logits"], targets.reshape(-1))
+    F = lstm_lm_forward(P, ids, targets, lowp)
+    Pl = F["Pl"]
+    dlogits = _st(O.softmax_ce_bwd(F["logits"], targets.reshape(-1)), lowp)
     g = {}
     g["W_out"] = O.gemm(dlogits.T, F["Hall"])
     g["b_out"] = O.reduce_axis("sum", dlogits, 0)
-    dHall = O.gemm(dlogits, P["W_out"])                       # (T*B, H)
+    dHall = _st(O.gemm(dlogits, Pl["W_out"]), lowp)          # (T*B, H)
     dZ = np.zeros((T * B, 4 * H))
-    dh_rec = np.zeros((B, H))
+    dh_rec = None
     dc = None
     for t in range(T - 1, -1, -1):
-        dh = O.elementwise("add", [dHall[t * B:(t + 1) * B], dh_rec])
+        dh = dHall[t * B:(t + 1) * B]
+        if dh_rec is not None:
+            dh = _st(O.elementwise("add", [dh, dh_rec]), lowp)
         dz, dc = O.lstm_bwd(F["Gs"][t], F["Cprev"][t], F["Cs"][t], dh, dc)
+        dz = _st(dz, lowp)
         dZ[t * B:(t + 1) * B] = dz
-        dh_rec = O.gemm(dz, np.asarray(P["U"], dtype=np.float64).T)
+        dh_rec = O.gemm(dz, Pl["U"].T)
     Hprev_all = np.concatenate(F["Hprev"], axis=0)
     g["U"] = O.gemm(Hprev_all.T, dZ)
     g["W"] = O.gemm(F["X"].T, dZ)
     g["b"] = O.reduce_axis("sum", dZ, 0)
-    dX = O.gemm(dZ, np.asarray(P["W"], dtype=np.float64).T)
+    dX = O.gemm(dZ, Pl["W"].T)
     g["E"] = O.embed_bwd(ids.reshape(-1), dX, V)
     new = {k: O.sgd_update(P[k], g[k], lr) for k in g}
     return dict(loss=F["loss"], grads=g, params=new, logits=F["logits"])

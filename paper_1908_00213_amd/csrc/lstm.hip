@@ -5,6 +5,8 @@
 // paper's Section "Function-wise Local Memory Usage Reduction" describes for tanh-like operations.
 // A call moves a few megabytes, so it is launch-latency bound; one thread per (batch, unit) pair with
 // accesses coalesced along the hidden axis.
+// Mixed precision: the arrays that feed matrix products -- h, the incoming dh and the outgoing dz --
+// may be bfloat16 (rounded to nearest even on store); z, the gates and the cell state stay fp32.
 #include "common.h"
 
 namespace chn {
@@ -16,10 +18,11 @@ struct LstmArgs {
   const float *bias;
   const float *c_prev; int64_t cp_pitch;
   float *c; int64_t c_pitch;
-  float *h; int64_t h_pitch;
+  void *h; int64_t h_pitch;
   float *gates; int64_t g_pitch;
 };
 
+template <typename TH>
 __global__ __launch_bounds__(256) void lstm_fwd_kernel(LstmArgs a) {
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= a.B * a.H) return;
@@ -30,7 +33,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_kernel(LstmArgs a) {
   const float i = sigmoid_f(zi), f = sigmoid_f(zf), g = tanhf(zg), o = sigmoid_f(zo);
   const float cn = f * a.c_prev[b * a.cp_pitch + j] + i * g;
   a.c[b * a.c_pitch + j] = cn;
-  a.h[b * a.h_pitch + j] = o * tanhf(cn);
+  Elem<TH>::store(static_cast<TH *>(a.h) + b * a.h_pitch + j, o * tanhf(cn));
   if (a.gates) {
     float *gr = a.gates + b * a.g_pitch;
     gr[j] = i; gr[a.H + j] = f; gr[2 * a.H + j] = g; gr[3 * a.H + j] = o;
@@ -42,12 +45,13 @@ struct LstmBwdArgs {
   const float *gates; int64_t g_pitch;
   const float *c_prev; int64_t cp_pitch;
   const float *c; int64_t c_pitch;
-  const float *dh; int64_t dh_pitch;
+  const void *dh; int64_t dh_pitch;
   const float *dc_next; int64_t dcn_pitch;
-  float *dz; int64_t dz_pitch;
+  void *dz; int64_t dz_pitch;
   float *dc_prev; int64_t dcp_pitch;
 };
 
+template <typename TDH, typename TDZ>
 __global__ __launch_bounds__(256) void lstm_bwd_kernel(LstmBwdArgs a) {
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= a.B * a.H) return;
@@ -55,21 +59,22 @@ __global__ __launch_bounds__(256) void lstm_bwd_kernel(LstmBwdArgs a) {
   const float *gr = a.gates + b * a.g_pitch;
   const float i = gr[j], f = gr[a.H + j], g = gr[2 * a.H + j], o = gr[3 * a.H + j];
   const float tc = tanhf(a.c[b * a.c_pitch + j]);
-  const float dh = a.dh[b * a.dh_pitch + j];
+  const float dh = Elem<TDH>::load(static_cast<const TDH *>(a.dh) + b * a.dh_pitch + j);
   const float d_o = dh * tc;
   const float dc = (a.dc_next ? a.dc_next[b * a.dcn_pitch + j] : 0.0f) + dh * o * (1.0f - tc * tc);
   const float di = dc * g, dg = dc * i, df = dc * a.c_prev[b * a.cp_pitch + j];
   a.dc_prev[b * a.dcp_pitch + j] = dc * f;
-  float *dr = a.dz + b * a.dz_pitch;
-  dr[j] = di * i * (1.0f - i);
-  dr[a.H + j] = df * f * (1.0f - f);
-  dr[2 * a.H + j] = dg * (1.0f - g * g);
-  dr[3 * a.H + j] = d_o * o * (1.0f - o);
+  TDZ *dr = static_cast<TDZ *>(a.dz) + b * a.dz_pitch;
+  Elem<TDZ>::store(dr + j, di * i * (1.0f - i));
+  Elem<TDZ>::store(dr + a.H + j, df * f * (1.0f - f));
+  Elem<TDZ>::store(dr + 2 * a.H + j, dg * (1.0f - g * g));
+  Elem<TDZ>::store(dr + 3 * a.H + j, d_o * o * (1.0f - o));
 }
 
-chn_status mat(const chn_array *a, const char *name, bool out, int64_t B, int64_t cols, int64_t *pitch) {
+chn_status mat(const chn_array *a, const char *name, bool out, int64_t B, int64_t cols, int64_t *pitch, bool bf16_ok = false) {
   CHN_TRY(validate(a, name, out));
-  if (a->dtype != CHN_F32) return fail(CHN_ERR_DTYPE, "lstm: %s must be F32", name);
+  if (a->dtype != CHN_F32 && !(bf16_ok && a->dtype == CHN_BF16))
+    return fail(CHN_ERR_DTYPE, "lstm: %s must be F32%s", name, bf16_ok ? " or BF16" : "");
   int64_t r, c;
   CHN_TRY(row_major_2d(a, name, &r, &c, pitch));
   if (r != B || c != cols) return fail(CHN_ERR_SHAPE, "lstm: %s must have shape (%lld,%lld)", name, (long long)B, (long long)cols);
@@ -92,7 +97,7 @@ chn_status chn_lstm_fwd(const chn_array *z, const chn_array *bias, const chn_arr
   CHN_TRY(mat(c_prev, "c_prev", false, a.B, a.H, &a.cp_pitch));
   CHN_TRY(mat(z, "z", false, a.B, 4 * a.H, &a.z_pitch));
   CHN_TRY(mat(c, "c", true, a.B, a.H, &a.c_pitch));
-  CHN_TRY(mat(h, "h", true, a.B, a.H, &a.h_pitch));
+  CHN_TRY(mat(h, "h", true, a.B, a.H, &a.h_pitch, true));
   if (gates) CHN_TRY(mat(gates, "gates", true, a.B, 4 * a.H, &a.g_pitch));
   if (bias) {
     CHN_TRY(validate(bias, "bias", false));
@@ -105,11 +110,12 @@ chn_status chn_lstm_fwd(const chn_array *z, const chn_array *bias, const chn_arr
   a.bias = bias ? static_cast<const float *>(bias->data) : nullptr;
   a.c_prev = static_cast<const float *>(c_prev->data);
   a.c = static_cast<float *>(c->data);
-  a.h = static_cast<float *>(h->data);
+  a.h = h->data;
   a.gates = gates ? static_cast<float *>(gates->data) : nullptr;
   const int64_t blocks = (a.B * a.H + 255) / 256;
   if (blocks > 0x7fffffff) return fail(CHN_ERR_SHAPE, "lstm: too large");
-  hipLaunchKernelGGL(lstm_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), a);
+  if (h->dtype == CHN_BF16) hipLaunchKernelGGL(lstm_fwd_kernel<bf16_raw>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), a);
+  else hipLaunchKernelGGL(lstm_fwd_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), a);
   return check_launch("lstm_fwd");
 }
 
@@ -124,21 +130,26 @@ chn_status chn_lstm_bwd(const chn_array *gates, const chn_array *c_prev, const c
   CHN_TRY(mat(c, "c", false, a.B, a.H, &a.c_pitch));
   CHN_TRY(mat(gates, "gates", false, a.B, 4 * a.H, &a.g_pitch));
   CHN_TRY(mat(c_prev, "c_prev", false, a.B, a.H, &a.cp_pitch));
-  CHN_TRY(mat(dh, "dh", false, a.B, a.H, &a.dh_pitch));
+  CHN_TRY(mat(dh, "dh", false, a.B, a.H, &a.dh_pitch, true));
   if (dc_next) CHN_TRY(mat(dc_next, "dc_next", false, a.B, a.H, &a.dcn_pitch));
-  CHN_TRY(mat(dz, "dz", true, a.B, 4 * a.H, &a.dz_pitch));
+  CHN_TRY(mat(dz, "dz", true, a.B, 4 * a.H, &a.dz_pitch, true));
   CHN_TRY(mat(dc_prev, "dc_prev", true, a.B, a.H, &a.dcp_pitch));
   if (a.B * a.H == 0) return CHN_OK;
   a.gates = static_cast<const float *>(gates->data);
   a.c_prev = static_cast<const float *>(c_prev->data);
   a.c = static_cast<const float *>(c->data);
-  a.dh = static_cast<const float *>(dh->data);
+  a.dh = dh->data;
   a.dc_next = dc_next ? static_cast<const float *>(dc_next->data) : nullptr;
-  a.dz = static_cast<float *>(dz->data);
+  a.dz = dz->data;
   a.dc_prev = static_cast<float *>(dc_prev->data);
   const int64_t blocks = (a.B * a.H + 255) / 256;
   if (blocks > 0x7fffffff) return fail(CHN_ERR_SHAPE, "lstm: too large");
-  hipLaunchKernelGGL(lstm_bwd_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), a);
+  const dim3 grid((unsigned)blocks), block(256);
+  const bool hb = dh->dtype == CHN_BF16, zb = dz->dtype == CHN_BF16;
+  if (hb && zb) hipLaunchKernelGGL((lstm_bwd_kernel<bf16_raw, bf16_raw>), grid, block, 0, as_stream(stream), a);
+  else if (hb) hipLaunchKernelGGL((lstm_bwd_kernel<bf16_raw, float>), grid, block, 0, as_stream(stream), a);
+  else if (zb) hipLaunchKernelGGL((lstm_bwd_kernel<float, bf16_raw>), grid, block, 0, as_stream(stream), a);
+  else hipLaunchKernelGGL((lstm_bwd_kernel<float, float>), grid, block, 0, as_stream(stream), a);
   return check_launch("lstm_bwd");
 }
 

@@ -196,11 +196,17 @@ class LSTMTrainer:
     every operand now starts on a 16-byte boundary and every contraction length is a whole number of
     tile steps, which is what the fast GEMM paths need (650 floats per row would allow 8-byte pieces
     only).  `P`, `g` and the activation buffers are exposed without the padding.
+
+    Mixed precision (``lowp=True``): everything that feeds a matrix product is stored in bf16 -- working
+    copies of E, W, U and W_out (refreshed by the SGD kernel), the embeddings, every h, the logit
+    gradients, the gradients of h and of the gate pre-activations; gate pre-activations, activated
+    gates, cell state and its gradient, logits, loss, parameter gradients and master weights stay fp32;
+    every product accumulates in fp32.
     """
 
-    def __init__(self, P, T, Bn, lr=0.01):
+    def __init__(self, P, T, Bn, lr=0.01, lowp=False):
         self.L = B.lib()
-        self.T, self.B, self.lr = T, Bn, float(lr)
+        self.T, self.B, self.lr, self.lowp = T, Bn, float(lr), lowp
         V, E = P["E"].shape
         H = P["U"].shape[0]
         self.V, self.E, self.H = V, E, H
@@ -212,17 +218,22 @@ class LSTMTrainer:
             dst = self._real(self._P, k)
             dst.copy_(_dev(P[k]).reshape(dst.shape))
         n = T * Bn
+        adt = torch.bfloat16 if lowp else torch.float32
+        za = lambda *s: torch.zeros(*s, dtype=adt, device="cuda")
+        # working copies the products read: bf16 in mixed precision, else the parameters themselves
+        self._Pl = {k: (v.to(torch.bfloat16) if lowp and k in ("E", "W", "U", "W_out") else v) for k, v in self._P.items()}
         # zero-initialised: the inert columns must hold zeros before the first step
-        self._X, self._Z, self._G = z(n, Ep), z(n, 4 * Hp), z(n, 4 * Hp)
-        self._Hs = z(n + Bn, Hp)   # block 0 = h_0 = 0
+        self._X, self._Z, self._G = za(n, Ep), z(n, 4 * Hp), z(n, 4 * Hp)
+        self._Hs = za(n + Bn, Hp)  # block 0 = h_0 = 0
         self._Cs = z(n + Bn, Hp)   # block 0 = c_0 = 0
         self.logits = z(n, V)
-        self._dHs, self._dZ, self._dX = z(n, Hp), z(n, 4 * Hp), z(n, Ep)
+        self._dlogits = za(n, V) if lowp else self.logits      # fp32: the gradient overwrites the logits
+        self._dHs, self._dZ, self._dX = za(n, Hp), za(n, 4 * Hp), z(n, Ep)
         self._dc = [z(Bn, Hp), z(Bn, Hp)]
         self._g = {k: z(*v.shape) for k, v in self._P.items()}
         self.loss, self.lse = z(()), z(n)
         self.ws_ce = torch.empty(B.softmax_ce_workspace_bytes(n), dtype=torch.uint8, device="cuda")
-        need = max(B.reduce_axis_workspace_bytes(self.logits, 0), B.reduce_axis_workspace_bytes(self._dZ, 0), 256)
+        need = max(B.reduce_axis_workspace_bytes(self._dlogits, 0), B.reduce_axis_workspace_bytes(self._dZ, 0), 256)
         self.ws_red = torch.empty(need, dtype=torch.uint8, device="cuda")
         self._progs = {}
 
@@ -262,40 +273,42 @@ class LSTMTrainer:
     dZ = property(lambda self: self._gates(self._dZ))
 
     def _build(self, ids, targets):
-        L, p, P, T, Bn = self.L, _Program(), self._P, self.T, self.B
+        L, p, P, Pl, T, Bn = self.L, _Program(), self._P, self._Pl, self.T, self.B
         blk = lambda buf, t: buf[t * Bn:(t + 1) * Bn]
         ids_f, tg_f = ids.reshape(-1), targets.reshape(-1)
+        dlog = self._dlogits
         # forward
-        p.add(L.chn_embed_fwd, p.d(P["E"]), p.d(ids_f), p.d(self._X))
-        _gemm(p, L, self._X, P["W"], self._Z)                                   # x W for all steps at once
+        p.add(L.chn_embed_fwd, p.d(Pl["E"]), p.d(ids_f), p.d(self._X))
+        _gemm(p, L, self._X, Pl["W"], self._Z)                                  # x W for all steps at once
         for t in range(T):
-            _gemm(p, L, blk(self._Hs, t), P["U"], blk(self._Z, t), beta=1.0)    # + h_{t-1} U
+            _gemm(p, L, blk(self._Hs, t), Pl["U"], blk(self._Z, t), beta=1.0)   # + h_{t-1} U
             p.add(L.chn_lstm_fwd, p.d(blk(self._Z, t)), p.d(P["b"]), p.d(blk(self._Cs, t)),
                   p.d(blk(self._Cs, t + 1)), p.d(blk(self._Hs, t + 1)), p.d(blk(self._G, t)))
         Hall, Hprev = self._Hs[Bn:], self._Hs[:T * Bn]
-        _gemm(p, L, Hall, P["W_out"].t(), self.logits, epi="bias", bias=P["b_out"])
+        _gemm(p, L, Hall, Pl["W_out"].t(), self.logits, epi="bias", bias=P["b_out"])
         wp, wn = p.ws(self.ws_ce)
         p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
-        # backward (dlogits overwrite the logits in place)
-        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.lse), C.c_float(1.0), p.d(self.logits), wp, wn)
+        # backward (in fp32 the logit gradients overwrite the logits in place)
+        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.lse), C.c_float(1.0), p.d(dlog), wp, wn)
         rp, rn = p.ws(self.ws_red)
-        _gemm(p, L, self.logits.t(), Hall, self._g["W_out"])
-        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.logits), 0, 0, p.d(self._g["b_out"]), rp, rn)
-        _gemm(p, L, self.logits, P["W_out"], self._dHs)
+        _gemm(p, L, dlog.t(), Hall, self._g["W_out"])
+        p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(dlog), 0, 0, p.d(self._g["b_out"]), rp, rn)
+        _gemm(p, L, dlog, Pl["W_out"], self._dHs)
         for t in range(T - 1, -1, -1):
             dc_next = None if t == T - 1 else self._dc[(t + 1) & 1]
             p.add(L.chn_lstm_bwd, p.d(blk(self._G, t)), p.d(blk(self._Cs, t)), p.d(blk(self._Cs, t + 1)),
                   p.d(blk(self._dHs, t)), p.d(dc_next), p.d(blk(self._dZ, t)), p.d(self._dc[t & 1]))
             if t > 0:
-                _gemm(p, L, blk(self._dZ, t), P["U"].t(), blk(self._dHs, t - 1), beta=1.0)
+                _gemm(p, L, blk(self._dZ, t), Pl["U"].t(), blk(self._dHs, t - 1), beta=1.0)
         _gemm(p, L, Hprev.t(), self._dZ, self._g["U"])
         _gemm(p, L, self._X.t(), self._dZ, self._g["W"])
         p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self._dZ), 0, 0, p.d(self._g["b"]), rp, rn)
-        _gemm(p, L, self._dZ, P["W"].t(), self._dX)
+        _gemm(p, L, self._dZ, Pl["W"].t(), self._dX)
         p.add(L.chn_embed_bwd, p.d(ids_f), p.d(self._dX), p.d(self._g["E"]), 0)
         names = list(P.keys())
+        lows = p.ptrs([Pl[k] if Pl[k] is not P[k] else None for k in names]) if self.lowp else None
         p.add(L.chn_sgd_update_multi, len(names), p.ptrs([P[k] for k in names]),
-              p.ptrs([self._g[k] for k in names]), C.c_float(self.lr), None)
+              p.ptrs([self._g[k] for k in names]), C.c_float(self.lr), lows)
         return p.finish()
 
     def step(self, ids, targets, stream=None, graph=False):

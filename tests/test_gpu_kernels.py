@@ -299,6 +299,19 @@ def test_lstm_cell(Bn, H):
     c3, h3 = empty((Bn, H)), empty((Bn, H))
     B.lstm_fwd(zz, dev(bias), dev(cp), c3, h3, None)
     assert torch.equal(c3, c) and torch.equal(h3, h)
+    # mixed precision: h stored in bf16 is the fp32 h rounded to nearest even; dh read and dz stored
+    # in bf16 are the fp32 kernel on the same (bf16-exact) dh, rounded at the store
+    hb = empty((Bn, H), "bf16")
+    B.lstm_fwd(dev(z), dev(bias), dev(cp), c3, hb, None)
+    assert np.array_equal(host(hb), O.round_bf16(host(h))) and torch.equal(c3, c)
+    dhb = bf16r(dh)
+    dzb, dz32 = empty((Bn, 4 * H), "bf16"), empty((Bn, 4 * H))
+    B.lstm_bwd(g, dev(cp), c, dev(dhb, "bf16"), dev(dcn), dzb, dcp)
+    dcp_b = dcp.clone()
+    B.lstm_bwd(g, dev(cp), c, dev(dhb), dev(dcn), dz32, dcp)
+    assert np.array_equal(host(dzb), O.round_bf16(host(dz32))) and torch.equal(dcp_b, dcp)
+    rdzb, _ = O.lstm_bwd(gh, cp, ch, dhb, dcn)
+    check(host(dzb), rdzb, TOL_BF16, Sdz, "dz bf16")
 
 
 def test_lstm_zero_preactivation_closed_form():

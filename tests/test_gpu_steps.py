@@ -116,6 +116,34 @@ def test_config4_scaled_lstm_lm_step(cfg):
     cmp(tr2.g["U"], r2["grads"]["U"], 1e-4, "dU T=2")
 
 
+@pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=72, batch=16, bptt=6),
+                                 dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])
+def test_config4_scaled_lstm_lm_step_mixed_precision(cfg):
+    w = W.config4(**cfg)
+    w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, lowp=True)
+    ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
+    loss = tr.step(ids, tg)
+    r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr), lowp=True)
+    assert abs(float(loss.cpu()) - r["loss"]) <= 2e-2 * abs(r["loss"])
+    assert tr.Hs.dtype == torch.bfloat16 and tr.dZ.dtype == torch.bfloat16 and tr.Z.dtype == torch.float32
+    lr = np.float32(w.lr)
+    for k in w.params:
+        assert tr.g[k].dtype == torch.float32
+        cmp(tr.g[k], r["grads"][k], 2e-2, "d" + k)
+        # the update itself is fp32 arithmetic on the master weights
+        check(host(tr.P[k]), O.sgd_update(w.params[k], host(tr.g[k]), lr), 1e-6,
+              np.abs(w.params[k]) + lr * np.abs(host(tr.g[k])), "update " + k)
+    # the working copies follow the masters (nearest-even rounding of the updated value)
+    for k in ("E", "W", "U", "W_out"):
+        assert np.array_equal(host(tr._unpadded(tr._Pl)[k]), O.round_bf16(host(tr.P[k]))), k
+    # second step reads the refreshed copies
+    r1 = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr), lowp=True)
+    l2 = float(tr.step(ids, tg).cpu())
+    r2 = OS.lstm_lm_step(r1["params"], w.ids, w.targets, np.float32(w.lr), lowp=True)
+    assert abs(l2 - r2["loss"]) <= 2e-2 * abs(r2["loss"])
+
+
 def test_graph_replay_equals_eager():
     # a captured step must reproduce the eager step bit for bit, on every replay, with eager work and
     # synchronisations in between
