@@ -215,3 +215,66 @@ def test_config4_full_size_step_sampled():
     lr = np.float32(w.lr)
     for k in P0:
         check(tr.P[k].cpu().numpy().astype(np.float64), O.sgd_update(P0[k], g[k], lr), 1e-6, np.abs(P0[k]) + lr * np.abs(g[k]), "update " + k)
+
+
+def test_config4_full_size_mixed_precision_sampled():
+    """Workload 4 in mixed precision at full size: every product checked on sampled entries against
+    fp64 dot products of the very bf16 operands it read (so the bar is the fp32-accumulation one),
+    every bf16 store against the bf16 bar."""
+    w = W.config4()
+    T, Bn, H, V = w.bptt, w.batch, w.hidden, w.vocab
+    tr = steps.LSTMTrainer(w.params, T, Bn, w.lr, lowp=True)
+    ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
+    Pl0 = {k: host(v) for k, v in tr._unpadded(tr._Pl).items()}          # the working copies the step reads
+    P0 = {k: host(v) for k, v in tr.P.items()}
+    for k in ("E", "W", "U", "W_out"):
+        assert np.array_equal(Pl0[k], O.round_bf16(P0[k]))
+    tr.step(ids, tg)
+    torch.cuda.synchronize()
+    idf, tgf = w.ids.reshape(-1), w.targets.reshape(-1)
+    X, Hs, Cs, Z, G = (host(m) for m in (tr.X, tr.Hs, tr.Cs, tr.Z, tr.G))
+    assert np.array_equal(X, Pl0["E"][idf])
+    Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
+    ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
+    ref = O.gemm_entries(X, Pl0["W"], ms, ns) + O.gemm_entries(Hprev, Pl0["U"], ms, ns)
+    S = O.gemm_entries(np.abs(X), np.abs(Pl0["W"]), ms, ns) + O.gemm_entries(np.abs(Hprev), np.abs(Pl0["U"]), ms, ns)
+    check(Z[ms, ns], ref, TOL_SUM, S, "gates pre-activation")
+    for t in (0, T // 2, T - 1):
+        sl = slice(t * Bn, (t + 1) * Bn)
+        c, h, g = O.lstm_fwd(Z[sl], P0["b"], Cs[sl])
+        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H])
+        check(Cs[t * Bn + Bn:(t + 2) * Bn], c, TOL_EW, Sc, "c %d" % t)
+        check(Hall[sl], h, TOL_BF16, Sc, "h %d" % t)
+    logits = host(tr.logits)
+    ms, ns, ref, S = sample_gemm(Hall, Pl0["W_out"].T)
+    check(logits[ms, ns], ref + P0["b_out"][ns], TOL_SUM, S, "logits")
+    rl, _, _, nv = O.softmax_ce_fwd(logits, tgf)
+    assert abs(float(tr.loss.cpu()) - rl) <= TOL_SUM * rl
+    dlog = host(tr._dlogits)
+    rows = np.sort(RNG.choice(T * Bn, 64, replace=False))
+    check(dlog[rows], O.softmax_ce_bwd(logits, tgf)[rows], TOL_BF16, 1.0 / nv, "dlogits")
+    g = {k: host(v) for k, v in tr.g.items()}
+    ms, ns, ref, S = sample_gemm(dlog.T, Hall)
+    check(g["W_out"][ms, ns], ref, TOL_SUM, S, "dW_out")
+    check(g["b_out"], O.reduce_axis("sum", dlog, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dlog), 0), "db_out")
+    dHs, dZ, dX = host(tr.dHs), host(tr.dZ), host(tr.dX)
+    t = T - 1
+    ms, ns = RNG.integers(0, Bn, 128), RNG.integers(0, H, 128)
+    check(dHs[t * Bn:][ms, ns], O.gemm_entries(dlog[t * Bn:], Pl0["W_out"], ms, ns), TOL_BF16,
+          O.gemm_entries(np.abs(dlog[t * Bn:]), np.abs(Pl0["W_out"]), ms, ns), "dh last step")
+    dz, _ = O.lstm_bwd(G[t * Bn:(t + 1) * Bn], Cs[t * Bn:(t + 1) * Bn], Cs[(t + 1) * Bn:(t + 2) * Bn], dHs[t * Bn:], None)
+    Sd = np.abs(dHs[t * Bn:])
+    check(dZ[t * Bn:], dz, TOL_BF16, np.concatenate([Sd, Sd * (1 + np.abs(Cs[t * Bn:(t + 1) * Bn])), Sd, Sd], axis=1), "dz last step")
+    for name, A, Bm in (("U", Hprev.T, dZ), ("W", X.T, dZ)):
+        ms, ns, ref, S = sample_gemm(A, Bm)
+        check(g[name][ms, ns], ref, TOL_SUM, S, "d" + name)
+    check(g["b"], O.reduce_axis("sum", dZ, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dZ), 0), "db")
+    ms, ns, ref, S = sample_gemm(dZ, Pl0["W"].T)
+    check(dX[ms, ns], ref, TOL_SUM, S, "dX")
+    check(g["E"], O.embed_bwd(idf, dX, V), TOL_SUM, O.embed_bwd(idf, np.abs(dX), V), "dE")
+    lr = np.float32(w.lr)
+    for k in P0:
+        new = host(tr.P[k])
+        check(new, O.sgd_update(P0[k], g[k], lr), 1e-6, np.abs(P0[k]) + lr * np.abs(g[k]), "update " + k)
+        if k in ("E", "W", "U", "W_out"):
+            assert np.array_equal(host(tr._unpadded(tr._Pl)[k]), O.round_bf16(new)), k
