@@ -218,6 +218,21 @@ chn_status chn_sgd_update_multi(int n, const chn_array *const *params,
                                 const chn_array *const *grads, float lr,
                                 const chn_array *const *lowp_copies, chn_stream stream);
 
+/* Adam (the paper names it as an optimiser choice in the code figure of Section "Distributed Parallel
+ * Training"; the update is Algorithm 1 of Kingma & Ba, "Adam: A Method for Stochastic Optimization"):
+ *   m <- beta1 m + (1 - beta1) g        v <- beta2 v + (1 - beta2) g^2
+ *   param <- param - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * for `n` tensors at once.  params, grads, ms, vs: F32, contiguous, same shape per tensor; m and v
+ * are the caller's state, zero before the first call; `step` counts calls from 1.  The
+ * hyper-parameters are doubles: 1 - beta and the bias corrections are formed on the host in double
+ * precision and rounded to fp32 once.  lowp_copies as for chn_sgd_update_multi.
+ * Errors: CHN_ERR_OP for step < 1 or a beta outside [0, 1); otherwise as for chn_sgd_update_multi. */
+chn_status chn_adam_update_multi(int n, const chn_array *const *params,
+                                 const chn_array *const *grads, const chn_array *const *ms,
+                                 const chn_array *const *vs, double lr, double beta1, double beta2,
+                                 double eps, int64_t step, const chn_array *const *lowp_copies,
+                                 chn_stream stream);
+
 /* ---- embedding ----------------------------------------------------------------------------------------
  * Array indexing of the ndarray layer (Section "GPU Support by CuPy") as the language model uses it:
  * out[n,:] = table[ids[n],:] (bit copies), and its gradient
@@ -260,7 +275,8 @@ chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_
  * reduce_expr, an expression over `a` and `b`, starting from `identity`; post_map_expr is a
  * statement list that assigns every output from the folded value `a` (scalar parameters are
  * visible too).  The fold runs in the compute type of the first output, over one axis (negative
- * counts from the end) or over all of them (CHN_AXIS_ALL); outputs have the common input shape
+ * counts from the end), over several (CHN_AXES(mask), dimensions of the broadcast input shape) or
+ * over all of them (CHN_AXIS_ALL); outputs have the common input shape
  * without the reduced dimensions (keepdims: with them set to 1).  reduce_expr must be associative
  * and commutative; the order of the fold is fixed for given shapes (bit-reproducible).  An empty
  * reduced range yields post_map(identity).  Workspace as for chn_reduce_axis.
@@ -277,6 +293,7 @@ chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_
  * CHN_ERR_LAUNCH.  A failing call enqueues nothing. */
 typedef struct chn_user_kernel chn_user_kernel;
 #define CHN_AXIS_ALL (-1000)
+#define CHN_AXES(mask) (0x40000000 + (mask)) /* several axes at once: bit d set = dimension d is reduced */
 
 chn_status chn_user_kernel_config(const char *cache_dir, const char *arch);
 /* process-wide counters: compiler runs, code objects found on disk, found in memory */

@@ -222,6 +222,16 @@ def sgd_update(p, g, lr):
     return out
 
 
+def adam_update(p, g, m, v, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step (Kingma & Ba, Algorithm 1), written out: returns (p', m', v').  `step` counts from 1."""
+    p, g, m, v = (np.asarray(a, dtype=np.float64) for a in (p, g, m, v))
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    return p - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
 def embed_fwd(table, ids):
     table, ids = _c64(table), _i64(ids).reshape(-1)
     out = np.empty((ids.size, table.shape[1]))

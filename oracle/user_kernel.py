@@ -144,7 +144,7 @@ class ElementwiseKernel(_Kernel):
 class ReductionKernel(_Kernel):
     """Fold ``map_expr`` of every element by ``reduce_expr`` (over ``a`` and ``b``) from ``identity``
     in index order, then ``post_map_expr`` assigns the outputs from the folded value ``a``.  The fold
-    runs in the type of the first output; ``axis=None`` folds everything."""
+    runs in the type of the first output; ``axis`` is one axis, a tuple of axes, or None for all."""
 
     def __init__(self, in_params, out_params, map_expr, reduce_expr, post_map_expr, identity, name="reduce", preamble=""):
         super().__init__(in_params, out_params, preamble)
@@ -155,7 +155,7 @@ class ReductionKernel(_Kernel):
         arrays = [None if np.isscalar(a) else np.asarray(a) for a in args]
         shape = np.broadcast_shapes(*[a.shape for a in arrays if a is not None])
         nd = len(shape)
-        axes = tuple(range(nd)) if axis is None else (axis % nd,)
+        axes = tuple(range(nd)) if axis is None else tuple(sorted(a % nd for a in (axis if isinstance(axis, (tuple, list)) else (axis,))))
         kept = [d for d in range(nd) if d not in axes]
         n_res = int(np.prod([shape[d] for d in kept], dtype=np.int64))
         R = int(np.prod([shape[d] for d in axes], dtype=np.int64))

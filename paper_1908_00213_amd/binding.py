@@ -28,13 +28,25 @@ EPI = {n: i for i, n in enumerate(EPILOGUES)}
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd",
-           "chn_sgd_update", "chn_sgd_update_multi", "chn_embed_fwd", "chn_embed_bwd",
+           "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan",
            "chn_user_kernel_config", "chn_user_kernel_stats", "chn_user_kernel_destroy",
            "chn_elementwise_kernel_create", "chn_elementwise_kernel_prepare", "chn_elementwise_kernel_launch",
            "chn_reduction_kernel_create", "chn_reduction_kernel_workspace_bytes", "chn_reduction_kernel_prepare",
            "chn_reduction_kernel_launch", "chn_user_kernel_source"]
 AXIS_ALL = -1000
+
+
+def _axis_code(axis, ndim):
+    """The C ABI's axis argument: one axis, CHN_AXIS_ALL for None, CHN_AXES(mask) for a tuple."""
+    if axis is None:
+        return AXIS_ALL
+    if isinstance(axis, (tuple, list)):
+        mask = 0
+        for a in axis:
+            mask |= 1 << (a % ndim)
+        return 0x40000000 + mask
+    return int(axis)
 
 
 class ChnArray(C.Structure):
@@ -80,6 +92,7 @@ def lib():
     L.chn_softmax_ce_bwd.argtypes = [AP, AP, C.c_int64, AP, C.c_float, AP, vp, C.c_size_t, st]
     L.chn_sgd_update.argtypes = [AP, AP, C.c_float, AP, st]
     L.chn_sgd_update_multi.argtypes = [C.c_int, APP, APP, C.c_float, APP, st]
+    L.chn_adam_update_multi.argtypes = [C.c_int, APP, APP, APP, APP, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int64, APP, st]
     L.chn_embed_fwd.argtypes = [AP, AP, AP, st]
     L.chn_embed_bwd.argtypes = [AP, AP, AP, C.c_int, st]
     L.chn_status_string.argtypes = [C.c_int32]
@@ -267,6 +280,14 @@ def sgd_update_multi(params, grads, lr, lowp_copies=None, stream=None):
                                       _stream() if stream is None else stream))
 
 
+def adam_update_multi(params, grads, ms, vs, lr, step, beta1=0.9, beta2=0.999, eps=1e-8, lowp_copies=None, stream=None):
+    ps, gs, m_, v_ = ([desc(t) for t in ts] for ts in (params, grads, ms, vs))
+    ls = None if lowp_copies is None else [desc(l) for l in lowp_copies]
+    _check(lib().chn_adam_update_multi(len(ps), _ptrs(ps), _ptrs(gs), _ptrs(m_), _ptrs(v_), float(lr), float(beta1),
+                                       float(beta2), float(eps), int(step), None if ls is None else _ptrs(ls),
+                                       _stream() if stream is None else stream))
+
+
 def embed_fwd(table, ids, out, stream=None):
     _check(lib().chn_embed_fwd(_ref(desc(table)), _ref(desc(ids)), _ref(desc(out)),
                                _stream() if stream is None else stream))
@@ -344,7 +365,7 @@ class _UserKernel:
         ds, _ = self._marshal(arrays, scalars)
         os_ = [desc(o) for o in outs]
         need = C.c_size_t(0)
-        ax = AXIS_ALL if axis is None else int(axis)
+        ax = _axis_code(axis, max((a.ndim if isinstance(a, ChnArray) else a.dim()) for a in arrays if a is not None))
         _check(lib().chn_user_kernel_source(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims), None, 0, C.byref(need)))
         buf = C.create_string_buffer(need.value)
         _check(lib().chn_user_kernel_source(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims), buf, need.value, None))
@@ -399,24 +420,28 @@ class ReductionKernel(_UserKernel):
         if outs:
             return outs
         shape = list(torch.broadcast_shapes(*[tuple(a.shape) for a in arrays if a is not None]))
-        axes = range(len(shape)) if axis is None else [axis % len(shape)]
+        axes = range(len(shape)) if axis is None else [a % len(shape) for a in (axis if isinstance(axis, (tuple, list)) else [axis])]
         oshape = [1 if d in axes else n for d, n in enumerate(shape)] if keepdims else [n for d, n in enumerate(shape) if d not in axes]
         dev = next(a.device for a in arrays if a is not None)
         return [torch.empty(oshape, dtype=self._out_dtype(j, arrays), device=dev) for j in range(len(self.out_params))]
+
+    @staticmethod
+    def _ndim(arrays):
+        return max((a.ndim if isinstance(a, ChnArray) else a.dim()) for a in arrays if a is not None)
 
     def prepare(self, *args, axis=None, keepdims=False):
         arrays, scalars, outs = self._split(args)
         ds, _ = self._marshal(arrays, scalars)
         os_ = [desc(o) for o in self._outputs(arrays, outs, axis, keepdims)]
         _check(lib().chn_reduction_kernel_prepare(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_),
-                                                  AXIS_ALL if axis is None else int(axis), int(keepdims)))
+                                                  _axis_code(axis, self._ndim(arrays)), int(keepdims)))
 
     def __call__(self, *args, axis=None, keepdims=False, ws=None, stream=None):
         arrays, scalars, outs = self._split(args)
         outs = self._outputs(arrays, outs, axis, keepdims)
         ds, sc = self._marshal(arrays, scalars)
         os_ = [desc(o) for o in outs]
-        ax = AXIS_ALL if axis is None else int(axis)
+        ax = _axis_code(axis, self._ndim(arrays))
         if ws is None:
             need = lib().chn_reduction_kernel_workspace_bytes(self._h, len(ds), _ptrs(ds), len(os_), _ptrs(os_), ax, int(keepdims))
             if need:

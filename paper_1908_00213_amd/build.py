@@ -17,7 +17,7 @@ LIB = os.path.join(HERE, "libchn.so")
 TOOL = os.path.join(HERE, "mfma_ceiling")
 
 SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "softmax_ce.hip",
-           "sgd.hip", "embed.hip"]
+           "sgd.hip", "adam.hip", "embed.hip"]
 
 # gemm_inst.hip is compiled once per (dtype, A layout, B layout): k = unit stride along K, m = along M/N
 GEMM_FAMILIES = [("%s_%s%s" % (tn, "k" if a else "m", "k" if b else "m"), t, a, b)

@@ -970,17 +970,24 @@ chn_status rd_plan(chn_user_kernel *k, int n_in, const chn_array *const *in, int
       shape[shift + d] = len;
     }
   }
-  int ax = axis;
-  if (axis != kAxisAll) {
-    if (ax < 0) ax += nd;
+  // which dimensions are folded: one axis, all of them, or the set bits of CHN_AXES(mask)
+  bool red[CHN_MAX_NDIM] = {false};
+  if (axis == kAxisAll) {
+    for (int d = 0; d < nd; ++d) red[d] = true;
+  } else if (axis >= CHN_AXES(0)) {
+    const int mask = axis - CHN_AXES(0);
+    if (mask == 0 || (mask >> nd) != 0) return fail(CHN_ERR_AXIS, "%s: axis set 0x%x out of range for %d dimensions", kn, mask, nd);
+    for (int d = 0; d < nd; ++d) red[d] = (mask >> d) & 1;
+  } else {
+    int ax = axis < 0 ? axis + nd : axis;
     if (ax < 0 || ax >= nd) return fail(CHN_ERR_AXIS, "%s: axis %d out of range for %d dimensions", kn, axis, nd);
+    red[ax] = true;
   }
   // expected output shape
   int ond = 0;
   int64_t oshape[CHN_MAX_NDIM];
   for (int d = 0; d < nd; ++d) {
-    const bool red = axis == kAxisAll || d == ax;
-    if (!red) oshape[ond++] = shape[d];
+    if (!red[d]) oshape[ond++] = shape[d];
     else if (keepdims) oshape[ond++] = 1;
   }
   for (int j = 0; j < n_out; ++j) {
@@ -1002,11 +1009,10 @@ chn_status rd_plan(chn_user_kernel *k, int n_in, const chn_array *const *in, int
   p->gr.str.assign(p->n_arr_in, {});
   int od = 0;
   for (int d = 0; d < nd; ++d) {
-    const bool red = axis == kAxisAll || d == ax;
-    Dims &g = red ? p->gr : p->go;
+    Dims &g = red[d] ? p->gr : p->go;
     g.shape[g.nd++] = shape[d];
     for (int a = 0; a < p->n_arr_in; ++a) g.str[a].push_back(istr[a][d]);
-    if (!red) {
+    if (!red[d]) {
       for (int j = 0; j < n_out; ++j) {
         const int isz = dtype_size(out[j]->dtype);
         p->go.str[p->n_arr_in + j].push_back(out[j]->shape[od] == 1 ? 0 : out[j]->strides[od] / isz);

@@ -28,7 +28,7 @@ import weakref
 
 __all__ = ["Variable", "Parameter", "VariableNode", "FunctionNode", "GpuBackend", "using_backend",
            "no_backprop_mode", "linear", "matmul", "relu", "gelu", "add", "softmax_cross_entropy",
-           "embed_id", "lstm", "split_rows", "concat_rows", "Linear", "SGD", "live_function_nodes",
+           "embed_id", "lstm", "split_rows", "concat_rows", "Linear", "SGD", "Adam", "live_function_nodes",
            "MLP", "LSTMLanguageModel"]
 
 
@@ -100,6 +100,9 @@ class GpuBackend:
 
     def sgd_update_multi(self, params, grads, lr, lowp_copies):
         self.B.sgd_update_multi(params, grads, lr, lowp_copies)
+
+    def adam_update_multi(self, params, grads, ms, vs, lr, step, beta1, beta2, eps, lowp_copies):
+        self.B.adam_update_multi(params, grads, ms, vs, lr, step, beta1, beta2, eps, lowp_copies)
 
 
 _backend = None
@@ -803,6 +806,33 @@ class SGD:
         lows = [p.lowp for p in ps]
         backend().sgd_update_multi([p.array for p in ps], [p.grad for p in ps], self.lr,
                                    lows if any(l is not None for l in lows) else None)
+
+
+class Adam(SGD):
+    """Adam (the optimiser of the paper's distributed-training code figure): first and second moment
+    estimates per parameter, created zero on first use; one call updates the whole set."""
+
+    def __init__(self, params, lr=0.001, beta1=0.9, beta2=0.999, eps=1e-8):
+        super().__init__(params, lr)
+        self.beta1, self.beta2, self.eps, self.t = beta1, beta2, eps, 0
+        self._state = {}
+
+    def update(self):
+        ps = [p for p in self.params if p.grad is not None]
+        if not ps:
+            return
+        F = backend()
+        self.t += 1
+        for p in ps:
+            if id(p) not in self._state:
+                m, v = F.empty(p.array.shape, "f32"), F.empty(p.array.shape, "f32")
+                F.elementwise_broadcast("fill", [], m, (0.0,))
+                F.elementwise_broadcast("fill", [], v, (0.0,))
+                self._state[id(p)] = (m, v)
+        lows = [p.lowp for p in ps]
+        F.adam_update_multi([p.array for p in ps], [p.grad for p in ps], [self._state[id(p)][0] for p in ps],
+                            [self._state[id(p)][1] for p in ps], self.lr, self.t, self.beta1, self.beta2, self.eps,
+                            lows if any(l is not None for l in lows) else None)
 
 
 # ---- the two model families of the benchmark workloads, written as define-by-run forward code ---------

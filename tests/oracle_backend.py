@@ -85,3 +85,8 @@ class OracleBackend:
         self.calls.append(("sgd", len(params)))
         for p, g in zip(params, grads):
             p[...] = O.sgd_update(p, g, lr)
+
+    def adam_update_multi(self, params, grads, ms, vs, lr, step, beta1, beta2, eps, lowp_copies):
+        self.calls.append(("adam", len(params)))
+        for p, g, m, v in zip(params, grads, ms, vs):
+            p[...], m[...], v[...] = O.adam_update(p, g, m, v, lr, step, beta1, beta2, eps)

@@ -376,3 +376,33 @@ def test_embedding(V, D, N, idt):
     check(host(acc), O.embed_bwd(ids, dout, V, E), TOL_SUM, O.embed_bwd(ids, np.abs(dout), V, np.abs(E)), "accumulate")
     di = RNG.integers(-3, 4, size=(N, D)).astype(np.float32)                 # integers: exact in any order
     assert np.array_equal(host(B.embed_bwd(dev(ids), dev(di), empty((V, D)))), O.embed_bwd(ids, di, V))
+
+
+# ------------------------------------------------------------------------------------ Adam
+def test_adam_update_multi_follows_the_oracle_over_several_steps():
+    rng = np.random.default_rng(31)
+    shapes = [(1000, 37), (5,), (4096,), (3, 3, 3), (0,), (129, 64)]
+    P = [rng.standard_normal(s).astype(np.float32) for s in shapes]
+    pd = [dev(p) for p in P]
+    md, vd = [torch.zeros_like(p) for p in pd], [torch.zeros_like(p) for p in pd]
+    low = [torch.zeros(s, dtype=torch.bfloat16, device="cuda") if i % 2 == 0 else None for i, s in enumerate(shapes)]
+    ref = [(p.astype(np.float64), np.zeros(p.shape), np.zeros(p.shape)) for p in P]
+    for step in range(1, 4):
+        G = [rng.standard_normal(s).astype(np.float32) * 10.0 ** rng.integers(-3, 2) for s in shapes]
+        before = [(host(p), host(m), host(v)) for p, m, v in zip(pd, md, vd)]
+        B.adam_update_multi(pd, [dev(g) for g in G], md, vd, 0.01, step, 0.9, 0.999, 1e-8, lowp_copies=low)
+        for i, g in enumerate(G):
+            # teacher-forced on the GPU's own state: one step of fp32 arithmetic
+            rp, rm, rv = O.adam_update(before[i][0], g, before[i][1], before[i][2], 0.01, step)
+            check(host(md[i]), rm, TOL_EW, np.abs(before[i][1]) + np.abs(g), "m")
+            check(host(vd[i]), rv, TOL_EW, None, "v")
+            check(host(pd[i]), rp, TOL_EW, np.abs(before[i][0]) + 0.01 * 10, "p")
+            # and end to end against the oracle's own trajectory
+            ref[i] = O.adam_update(ref[i][0], g, ref[i][1], ref[i][2], 0.01, step)
+            check(host(pd[i]), ref[i][0], 1e-5, np.abs(ref[i][0]) + 0.01 * 10 * step, "p trajectory")
+            if low[i] is not None:
+                assert np.array_equal(host(low[i]), O.round_bf16(host(pd[i])))
+    with pytest.raises(B.ChnError):
+        B.adam_update_multi(pd[:1], [dev(G[0])], md[:1], vd[:1], 0.01, 0)           # steps count from 1
+    with pytest.raises(B.ChnError):
+        B.adam_update_multi(pd[:1], [dev(G[0])], md[:1], vd[1:2], 0.01, 1)          # state of another shape

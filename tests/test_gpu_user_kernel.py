@@ -120,6 +120,29 @@ def test_sum_l2norm_and_max_over_one_axis_or_all(shape, axis):
     assert tuple(kd.shape) == OU.ReductionKernel(*SUM)(x, axis=axis, keepdims=True).shape
 
 
+@pytest.mark.parametrize("axes", [(0, 2), (1, 3), (0, 1, 2), (1, 2), (0, 3), (2, 3), (0, 1, 2, 3)])
+def test_reductions_over_several_axes(axes):
+    rng = np.random.default_rng(sum(axes) + 40)
+    x = rng.standard_normal((4, 50, 6, 72)).astype(np.float32)
+    xd = dev(x)
+    for decl in (SUM, L2, MAX):
+        got = B.ReductionKernel(*decl)(xd, axis=axes)
+        ref = OU.ReductionKernel(*decl)(x, axis=axes)
+        assert tuple(got.shape) == ref.shape
+        if decl is MAX:
+            assert np.array_equal(host(got), ref)
+        else:
+            check(host(got), ref, TOL_SUM, np.abs(x).sum(axis=axes) if decl is SUM else ref, decl[-1])
+    kd = B.ReductionKernel(*SUM)(xd, axis=axes, keepdims=True)
+    assert tuple(kd.shape) == x.sum(axis=axes, keepdims=True).shape
+    check(host(kd), x.astype(np.float64).sum(axis=axes, keepdims=True), TOL_SUM, np.abs(x).sum(axis=axes, keepdims=True), "keepdims")
+    # a transposed view reduces to the same numbers
+    xt = xd.permute(3, 1, 2, 0)
+    at = tuple(sorted({0: 3, 1: 1, 2: 2, 3: 0}[a] for a in axes))
+    check(host(B.ReductionKernel(*SUM)(xt, axis=at)), OU.ReductionKernel(*SUM)(x.transpose(3, 1, 2, 0), axis=at), TOL_SUM,
+          np.abs(x.transpose(3, 1, 2, 0)).sum(axis=at), "permuted")
+
+
 def test_reduction_types_views_two_inputs_and_reproducibility():
     rng = np.random.default_rng(10)
     xi = rng.integers(-1000, 1000, (513, 300)).astype(np.int64)

@@ -361,3 +361,27 @@ def test_fd_lstm_lm_step_bptt():
     # topology changes with the trace: another window length still gives correct gradients
     r2 = OS.lstm_lm_step(P, ids[:2], tg[:2], 0.1)
     _close(r2["grads"]["U"], _fd(lambda v: OS.lstm_lm_forward({**P, "U": v}, ids[:2], tg[:2])["loss"], P["U"]), 5e-6)
+
+
+def test_adam_first_step_is_a_signed_step_and_constant_gradients_keep_it_so():
+    # with zero state the corrected moments after step 1 are g and g^2: the move is lr * g / (|g| + eps);
+    # a gradient that never changes keeps m_hat = g and v_hat = g^2 at every step
+    rng = np.random.default_rng(21)
+    p0, g = rng.standard_normal(50), rng.standard_normal(50)
+    p, m, v = p0, np.zeros(50), np.zeros(50)
+    for t in range(1, 6):
+        p_new, m, v = O.adam_update(p, g, m, v, 0.01, t, 0.9, 0.999, 1e-8)
+        np.testing.assert_allclose(p_new, p - 0.01 * g / (np.abs(g) + 1e-8), rtol=1e-12, atol=1e-15)
+        p = p_new
+    np.testing.assert_allclose(m, (1 - 0.9 ** 5) * g, rtol=1e-12)
+    np.testing.assert_allclose(v, (1 - 0.999 ** 5) * g * g, rtol=1e-12)
+
+
+def test_adam_two_steps_by_hand():
+    # beta1 = beta2 = 0.5, lr = 1, eps = 0, gradients 2 then -4 on a single parameter
+    p, m, v = O.adam_update(np.array([10.0]), np.array([2.0]), np.zeros(1), np.zeros(1), 1.0, 1, 0.5, 0.5, 0.0)
+    assert (p[0], m[0], v[0]) == (9.0, 1.0, 2.0)
+    p, m, v = O.adam_update(p, np.array([-4.0]), m, v, 1.0, 2, 0.5, 0.5, 0.0)
+    # m = 0.5 - 2 = -1.5, v = 1 + 8 = 9; m_hat = -2, v_hat = 12
+    assert (m[0], v[0]) == (-1.5, 9.0)
+    assert p[0] == pytest.approx(9.0 + 2.0 / np.sqrt(12.0), rel=1e-15)

@@ -316,6 +316,24 @@ def test_no_backprop_mode_records_nothing(F):
     assert y.creator is None and p.node.data is None and T.live_function_nodes() == 0
 
 
+def test_adam_optimiser_keeps_state_per_parameter_and_counts_steps(F):
+    rng = np.random.default_rng(13)
+    Wm, b, x, t = rnd(rng, 3, 4), rnd(rng, 3), rnd(rng, 5, 4), np.array([0, 1, 2, 1, 0])
+    layer = T.Linear(Wm.copy(), b.copy())
+    opt = T.Adam(layer.params(), lr=0.05)
+    ref = {"W": (Wm.copy(), np.zeros_like(Wm), np.zeros_like(Wm)), "b": (b.copy(), np.zeros_like(b), np.zeros_like(b))}
+    for step in (1, 2, 3):
+        opt.cleargrads()
+        T.softmax_cross_entropy(layer(T.Variable(x, False)), t).backward()
+        gW, gb = layer.W.grad.copy(), layer.b.grad.copy()
+        opt.update()
+        ref["W"] = O.adam_update(ref["W"][0], gW, ref["W"][1], ref["W"][2], 0.05, step)
+        ref["b"] = O.adam_update(ref["b"][0], gb, ref["b"][1], ref["b"][2], 0.05, step)
+        np.testing.assert_allclose(layer.W.array, ref["W"][0], rtol=1e-13)
+        np.testing.assert_allclose(layer.b.array, ref["b"][0], rtol=1e-13)
+    assert opt.t == 3 and [c for c in F.calls if c[0] == "adam"] == [("adam", 2)] * 3
+
+
 def test_gpu_backend_refuses_to_exist_without_the_library(monkeypatch):
     from paper_1908_00213_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

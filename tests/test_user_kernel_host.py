@@ -40,6 +40,10 @@ def test_oracle_reductions_are_numpy_folds():
     for axis in (0, 1, 2, -1, None):
         np.testing.assert_allclose(s(x, axis=axis), x.sum(axis=axis), rtol=1e-14, atol=1e-14)
     assert s(x, axis=1, keepdims=True).shape == (5, 1, 3)
+    y = rng.standard_normal((4, 5, 6, 7))
+    for axes in ((0, 2), (1, 3), (0, 1, 2), (1, 2), (3,)):
+        np.testing.assert_allclose(s(y, axis=axes), y.sum(axis=axes), rtol=1e-13)
+        assert s(y, axis=axes, keepdims=True).shape == y.sum(axis=axes, keepdims=True).shape
     l2 = OU.ReductionKernel("T x", "T y", "x * x", "a + b", "y = sqrt(a)", "0", "l2norm")
     np.testing.assert_allclose(l2(x, axis=None), np.linalg.norm(x.ravel()), rtol=1e-14)
     np.testing.assert_allclose(l2(x, axis=2), np.linalg.norm(x, axis=2), rtol=1e-14)
@@ -188,6 +192,14 @@ def test_reduction_declaration_shapes_and_workspace(cache):
         with pytest.raises(B.ChnError) as e:
             s.prepare(x, out, axis=axis)
         assert e.value.status == status
+    y4 = fake((4, 50, 6, 70))
+    s.prepare(y4, fake((50, 70)), axis=(0, 2))
+    s.prepare(y4, fake((4, 1, 1, 70)), axis=(1, 2), keepdims=True)
+    with pytest.raises(B.ChnError) as e:
+        s.prepare(y4, fake((50, 70)), axis=(0, 1))               # the output has the shape of another axis set
+    assert e.value.status == -4
+    L2 = B.lib()
+    assert L2.chn_reduction_kernel_prepare(s._h, 1, B._ptrs([y4]), 1, B._ptrs([fake((50, 70))]), 0x40000000 + (1 << 5), 0) == -7
     src_row = s.source(x, fake((8192,)), axis=1)
     src_col = s.source(x, fake((4096,)), axis=0)
     assert "__shared__" in src_row.split("_finish")[0] and "__shared__" not in src_col.split("_finish")[0]
