@@ -182,6 +182,27 @@ chn_status chn_lstm_bwd(const chn_array *gates, const chn_array *c_prev, const c
                         const chn_array *dh, const chn_array *dc_next, const chn_array *dz,
                         const chn_array *dc_prev, chn_stream stream);
 
+/* One time step of the recurrent layer in one launch: the recurrent product and the cell fused.
+ * Forward:  z = zx + h_prev U (+ bias), then the cell above.  zx (B,4H) F32 holds the input part
+ * x W of this step; h_prev (B,H) and Ut (4H,H) -- the TRANSPOSE of the recurrent matrix U (H,4H),
+ * so that both operands are unit-stride along the contraction -- share one dtype, F32 or BF16; h
+ * is written in that dtype; c_prev, c, gates F32.  z itself is not stored.
+ * Backward: dh <- dh + dz_next U^T (dz_next (B,4H) and U (H,4H) in dh's dtype; dz_next NULL for the
+ * last step: dh is used as it is), stored back into `dh` (the total gradient of h_t, rounded to
+ * BF16 in mixed precision -- the rounded value is what the cell sees), then the cell's backward
+ * above: dz (B,4H) in dh's dtype, dc_prev F32.
+ * Requirements beyond the unfused calls: H a multiple of 32 (pad with inert units), rows of
+ * h_prev, Ut, dz_next and U on 16-byte boundaries; otherwise CHN_ERR_SHAPE / CHN_ERR_STRIDE and
+ * the caller uses chn_gemm + chn_lstm_fwd / chn_lstm_bwd.  Sums run in fp32 on the matrix cores
+ * in an order that differs from chn_gemm's; results agree within the product tolerance. */
+chn_status chn_lstm_step_fwd(const chn_array *zx, const chn_array *h_prev, const chn_array *Ut,
+                             const chn_array *bias, const chn_array *c_prev, const chn_array *c,
+                             const chn_array *h, const chn_array *gates, chn_stream stream);
+chn_status chn_lstm_step_bwd(const chn_array *dz_next, const chn_array *U, const chn_array *dh,
+                             const chn_array *gates, const chn_array *c_prev, const chn_array *c,
+                             const chn_array *dc_next, const chn_array *dz,
+                             const chn_array *dc_prev, chn_stream stream);
+
 /* ---- softmax cross-entropy ------------------------------------------------------------------------
  * The classifier loss of the paper's MNIST example (Section "API Design"); textbook definition.
  * logits (N,C) F32 or BF16, row-major; labels (N,) I32 or I64.  Rows whose label equals

@@ -26,7 +26,7 @@ EPILOGUES = ["none", "bias", "bias_relu", "bias_gelu", "relu_bwd", "gelu_bwd", "
 EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis",
-           "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd",
+           "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan",
@@ -86,6 +86,8 @@ def lib():
     L.chn_gemm.argtypes = [AP, AP, AP, C.c_float, C.c_float, C.c_int, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_lstm_fwd.argtypes = [AP, AP, AP, AP, AP, AP, st]
     L.chn_lstm_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, st]
+    L.chn_lstm_step_fwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, AP, st]
+    L.chn_lstm_step_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, AP, AP, st]
     L.chn_softmax_ce_workspace_bytes.argtypes = [C.c_int64]
     L.chn_softmax_ce_workspace_bytes.restype = C.c_size_t
     L.chn_softmax_ce_fwd.argtypes = [AP, AP, C.c_int64, AP, AP, AP, vp, C.c_size_t, st]
@@ -243,6 +245,17 @@ def lstm_bwd(gates, c_prev, c, dh, dc_next, dz, dc_prev, stream=None):
     _check(lib().chn_lstm_bwd(_ref(desc(gates)), _ref(desc(c_prev)), _ref(desc(c)), _ref(desc(dh)),
                               _ref(desc(dc_next)), _ref(desc(dz)), _ref(desc(dc_prev)),
                               _stream() if stream is None else stream))
+
+
+def lstm_step_fwd(zx, h_prev, Ut, bias, c_prev, c, h, gates=None, stream=None):
+    _check(lib().chn_lstm_step_fwd(_ref(desc(zx)), _ref(desc(h_prev)), _ref(desc(Ut)), _ref(desc(bias)), _ref(desc(c_prev)),
+                                   _ref(desc(c)), _ref(desc(h)), _ref(desc(gates)), _stream() if stream is None else stream))
+
+
+def lstm_step_bwd(dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev, stream=None):
+    _check(lib().chn_lstm_step_bwd(_ref(desc(dz_next)), _ref(desc(U)), _ref(desc(dh)), _ref(desc(gates)), _ref(desc(c_prev)),
+                                   _ref(desc(c)), _ref(desc(dc_next)), _ref(desc(dz)), _ref(desc(dc_prev)),
+                                   _stream() if stream is None else stream))
 
 
 def softmax_ce_workspace_bytes(n_rows):

@@ -1,0 +1,294 @@
+// chn_lstm_step_fwd / chn_lstm_step_bwd: one time step of the recurrent layer in one launch.
+//
+// Unfused, a step is a small product (batch x 4H x H forward, batch x H x 4H backward), the kernel
+// that adds its partial sums, and the point-wise cell kernel: three dependent launches of a few
+// microseconds each, 35 times per direction.  The product is far too small to fill the chip, so the
+// step is bound by launch latency, not by arithmetic.  Here a workgroup owns a 32 x 32 tile of the
+// product -- 32 batch rows by 8 hidden units x 4 gates forward, 32 batch rows by 32 hidden units
+// backward -- its four waves take every fourth slice of the contraction on the matrix cores straight
+// from global memory (the operands are L2-resident: h and the recurrent matrix are re-read by every
+// tile), the partial tiles meet in LDS, and the same threads apply the cell.
+//
+// Operand layout: lane (r = lane & 31, q = lane >> 5) of a 32x32 MFMA holds row r of the tile and a
+// 16-byte piece of the contraction (8 bf16 values for one 32x32x16 instruction; 4 fp32 values for four
+// 32x32x2 instructions, which permutes the order of the sum but visits every term once).  Both
+// operands must therefore be unit-stride along the contraction: h and dz are, and so is the recurrent
+// matrix U (H, 4H) for the backward; the forward reads its transpose Ut (4H, H), which the caller
+// refreshes once per optimiser step.
+#include "common.h"
+
+namespace chn {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+
+template <typename T> struct Piece;          // what one lane contributes to one slice of the contraction
+template <> struct Piece<bf16_raw> { static constexpr int K = 16, PER_LANE = 8; };
+template <> struct Piece<float> { static constexpr int K = 8, PER_LANE = 4; };
+
+template <typename T>
+__device__ __forceinline__ void mma_piece(floatx16 &acc, const uint4 &a, const uint4 &b) {
+  if constexpr (sizeof(T) == 2) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float((&a.x)[kk]), __uint_as_float((&b.x)[kk]), acc, 0, 0, 0);
+  }
+}
+
+// acc += A[rows of this lane] . B[rows of this lane] over the slices s = wave, wave + 4, ... of a
+// contraction of `k_len` elements; ap / bp point at this lane's row, already offset by its piece.
+template <typename T>
+__device__ __forceinline__ void contract(floatx16 &acc, const T *ap, const T *bp, int64_t k_len, int wave) {
+  constexpr int K = Piece<T>::K, U = 4;
+  const int n_slices = (int)(k_len / K);
+  for (int s = wave; s < n_slices; s += kWaves * U) {
+    uint4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int su = s + u * kWaves;
+      if (su < n_slices) {                      // uniform over the wave
+        a[u] = *reinterpret_cast<const uint4 *>(ap + (int64_t)su * K);
+        b[u] = *reinterpret_cast<const uint4 *>(bp + (int64_t)su * K);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (s + u * kWaves < n_slices) mma_piece<T>(acc, a[u], b[u]);
+  }
+}
+
+// Park this wave's partial tile in LDS as tile[wave][row][col]: lane (r, q) holds column r and the
+// rows 8 * (v / 4) + 4 * q + v % 4 of its 16 accumulators.
+__device__ __forceinline__ void park(float (*tile)[32][33], const floatx16 &acc, int wave, int lane) {
+  const int r = lane & 31, q = lane >> 5;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) tile[wave][8 * (v / 4) + 4 * q + v % 4][r] = acc[v];
+}
+
+__device__ __forceinline__ float total(float (*tile)[32][33], int row, int col) {
+  return (tile[0][row][col] + tile[1][row][col]) + (tile[2][row][col] + tile[3][row][col]);
+}
+
+struct FwdArgs {
+  int64_t B, H;
+  const float *zx; int64_t zx_pitch;
+  const void *h_prev; int64_t hp_pitch;
+  const void *Ut; int64_t ut_pitch;
+  const float *bias;
+  const float *c_prev; int64_t cp_pitch;
+  float *c; int64_t c_pitch;
+  void *h; int64_t h_pitch;
+  float *gates; int64_t g_pitch;
+};
+
+// grid: (H / 8, ceil(B / 32)).  Tile column 8 * g + jj is gate g of hidden unit j0 + jj.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void lstm_step_fwd_kernel(FwdArgs a) {
+  __shared__ float tile[kWaves][32][33];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, q = lane >> 5;
+  const int64_t j0 = (int64_t)blockIdx.x * 8, b0 = (int64_t)blockIdx.y * 32;
+  const int64_t arow = b0 + r < a.B ? b0 + r : a.B - 1;            // rows past the batch repeat the last one
+  const T *ap = static_cast<const T *>(a.h_prev) + arow * a.hp_pitch + q * Piece<T>::PER_LANE;
+  const T *bp = static_cast<const T *>(a.Ut) + ((int64_t)(r >> 3) * a.H + j0 + (r & 7)) * a.ut_pitch + q * Piece<T>::PER_LANE;
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  contract<T>(acc, ap, bp, a.H, wave);
+  park(tile, acc, wave, lane);
+  __syncthreads();
+  // one (batch row, hidden unit) pair per thread
+  const int row = threadIdx.x >> 3, jj = threadIdx.x & 7;
+  const int64_t b = b0 + row, j = j0 + jj;
+  if (b >= a.B) return;
+  const float *zr = a.zx + b * a.zx_pitch;
+  float z[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    z[g] = total(tile, row, 8 * g + jj) + zr[g * a.H + j];
+    if (a.bias) z[g] += a.bias[g * a.H + j];
+  }
+  const float i = sigmoid_f(z[0]), f = sigmoid_f(z[1]), g = tanhf(z[2]), o = sigmoid_f(z[3]);
+  const float cn = f * a.c_prev[b * a.cp_pitch + j] + i * g;
+  a.c[b * a.c_pitch + j] = cn;
+  Elem<T>::store(static_cast<T *>(a.h) + b * a.h_pitch + j, o * tanhf(cn));
+  if (a.gates) {
+    float *gr = a.gates + b * a.g_pitch;
+    gr[j] = i; gr[a.H + j] = f; gr[2 * a.H + j] = g; gr[3 * a.H + j] = o;
+  }
+}
+
+struct BwdArgs {
+  int64_t B, H;
+  const void *dz_next; int64_t dzn_pitch;      // NULL: no later step
+  const void *U; int64_t u_pitch;
+  void *dh; int64_t dh_pitch;                  // in: the part from the layers above; out: the total
+  const float *gates; int64_t g_pitch;
+  const float *c_prev; int64_t cp_pitch;
+  const float *c; int64_t c_pitch;
+  const float *dc_next; int64_t dcn_pitch;
+  void *dz; int64_t dz_pitch;
+  float *dc_prev; int64_t dcp_pitch;
+};
+
+// grid: (H / 32, ceil(B / 32)).  dh[b, j] += sum_k dz_next[b, k] U[j, k], then the cell's backward.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void lstm_step_bwd_kernel(BwdArgs a) {
+  __shared__ float tile[kWaves][32][33];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, q = lane >> 5;
+  const int64_t j0 = (int64_t)blockIdx.x * 32, b0 = (int64_t)blockIdx.y * 32;
+  if (a.dz_next) {
+    const int64_t arow = b0 + r < a.B ? b0 + r : a.B - 1;
+    const T *ap = static_cast<const T *>(a.dz_next) + arow * a.dzn_pitch + q * Piece<T>::PER_LANE;
+    const T *bp = static_cast<const T *>(a.U) + (j0 + r) * a.u_pitch + q * Piece<T>::PER_LANE;
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    contract<T>(acc, ap, bp, 4 * a.H, wave);
+    park(tile, acc, wave, lane);
+    __syncthreads();
+  }
+  // four (batch row, hidden unit) pairs per thread; neighbouring threads take neighbouring units
+  const int col = threadIdx.x & 31;
+  const int64_t j = j0 + col;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int row = (threadIdx.x >> 5) + 8 * p;
+    const int64_t b = b0 + row;
+    if (b >= a.B) continue;
+    T *dhp = static_cast<T *>(a.dh) + b * a.dh_pitch + j;
+    float dh = Elem<T>::load(dhp);
+    if (a.dz_next) {
+      // the total is what the cell sees and what is stored: in mixed precision that is the bf16 value
+      dh += total(tile, row, col);
+      Elem<T>::store(dhp, dh);
+      if constexpr (sizeof(T) == 2) dh = bf16_to_f32(f32_to_bf16(dh));
+    }
+    const float *gr = a.gates + b * a.g_pitch;
+    const float i = gr[j], f = gr[a.H + j], g = gr[2 * a.H + j], o = gr[3 * a.H + j];
+    const float tc = tanhf(a.c[b * a.c_pitch + j]);
+    const float d_o = dh * tc;
+    const float dc = (a.dc_next ? a.dc_next[b * a.dcn_pitch + j] : 0.0f) + dh * o * (1.0f - tc * tc);
+    const float di = dc * g, dg = dc * i, df = dc * a.c_prev[b * a.cp_pitch + j];
+    a.dc_prev[b * a.dcp_pitch + j] = dc * f;
+    T *dr = static_cast<T *>(a.dz) + b * a.dz_pitch;
+    Elem<T>::store(dr + j, di * i * (1.0f - i));
+    Elem<T>::store(dr + a.H + j, df * f * (1.0f - f));
+    Elem<T>::store(dr + 2 * a.H + j, dg * (1.0f - g * g));
+    Elem<T>::store(dr + 3 * a.H + j, d_o * o * (1.0f - o));
+  }
+}
+
+// (rows, cols) view with unit inner stride; `t` (F32 or BF16) or F32 only; optionally rows that
+// start on 16-byte boundaries (operands of the contraction)
+chn_status view(const chn_array *x, const char *name, bool out, int64_t rows, int64_t cols, int want_dtype, bool operand,
+                int64_t *pitch) {
+  CHN_TRY(validate(x, name, out));
+  if (x->dtype != want_dtype)
+    return fail(CHN_ERR_DTYPE, "lstm_step: %s must be %s", name, want_dtype == CHN_F32 ? "F32" : "BF16");
+  int64_t r, c;
+  CHN_TRY(row_major_2d(x, name, &r, &c, pitch));
+  if (r != rows || c != cols)
+    return fail(CHN_ERR_SHAPE, "lstm_step: %s must have shape (%lld,%lld)", name, (long long)rows, (long long)cols);
+  if (operand) {
+    const int per16 = 16 / dtype_size(x->dtype);
+    if (reinterpret_cast<uintptr_t>(x->data) % 16 || (rows > 1 && *pitch % per16))
+      return fail(CHN_ERR_STRIDE, "lstm_step: rows of %s must start on 16-byte boundaries", name);
+  }
+  return CHN_OK;
+}
+
+}  // namespace
+}  // namespace chn
+
+extern "C" {
+
+chn_status chn_lstm_step_fwd(const chn_array *zx, const chn_array *h_prev, const chn_array *Ut, const chn_array *bias,
+                             const chn_array *c_prev, const chn_array *c, const chn_array *h, const chn_array *gates,
+                             chn_stream stream) {
+  using namespace chn;
+  CHN_TRY(validate(c_prev, "c_prev", false));
+  if (c_prev->ndim != 2) return fail(CHN_ERR_NDIM, "lstm_step: c_prev must be 2-d");
+  if (!h_prev) return fail(CHN_ERR_NULL, "lstm_step: h_prev is NULL");
+  FwdArgs a{};
+  a.B = c_prev->shape[0]; a.H = c_prev->shape[1];
+  if (a.H % 32) return fail(CHN_ERR_SHAPE, "lstm_step: the hidden width %lld is not a multiple of 32 (pad it, or use the unfused calls)", (long long)a.H);
+  const int t = h_prev->dtype;
+  if (t != CHN_F32 && t != CHN_BF16) return fail(CHN_ERR_DTYPE, "lstm_step: h_prev must be F32 or BF16");
+  CHN_TRY(view(c_prev, "c_prev", false, a.B, a.H, CHN_F32, false, &a.cp_pitch));
+  CHN_TRY(view(zx, "zx", false, a.B, 4 * a.H, CHN_F32, false, &a.zx_pitch));
+  CHN_TRY(view(h_prev, "h_prev", false, a.B, a.H, t, true, &a.hp_pitch));
+  CHN_TRY(view(Ut, "Ut", false, 4 * a.H, a.H, t, true, &a.ut_pitch));
+  CHN_TRY(view(c, "c", true, a.B, a.H, CHN_F32, false, &a.c_pitch));
+  CHN_TRY(view(h, "h", true, a.B, a.H, t, false, &a.h_pitch));
+  if (gates) CHN_TRY(view(gates, "gates", true, a.B, 4 * a.H, CHN_F32, false, &a.g_pitch));
+  if (bias) {
+    CHN_TRY(validate(bias, "bias", false));
+    if (bias->dtype != CHN_F32 || bias->ndim != 1 || bias->shape[0] != 4 * a.H || !is_contiguous(bias))
+      return fail(CHN_ERR_SHAPE, "lstm_step: bias must be a contiguous F32 (%lld,) array", (long long)(4 * a.H));
+  }
+  if (a.B * a.H == 0) return CHN_OK;
+  const int64_t by = (a.B + 31) / 32;
+  if (by > 65535) return fail(CHN_ERR_SHAPE, "lstm_step: batch too large");
+  a.zx = static_cast<const float *>(zx->data);
+  a.h_prev = h_prev->data; a.Ut = Ut->data;
+  a.bias = bias ? static_cast<const float *>(bias->data) : nullptr;
+  a.c_prev = static_cast<const float *>(c_prev->data);
+  a.c = static_cast<float *>(c->data);
+  a.h = h->data;
+  a.gates = gates ? static_cast<float *>(gates->data) : nullptr;
+  const dim3 grid((unsigned)(a.H / 8), (unsigned)by);
+  if (t == CHN_BF16) hipLaunchKernelGGL(lstm_step_fwd_kernel<bf16_raw>, grid, dim3(kThreads), 0, as_stream(stream), a);
+  else hipLaunchKernelGGL(lstm_step_fwd_kernel<float>, grid, dim3(kThreads), 0, as_stream(stream), a);
+  return check_launch("lstm_step_fwd");
+}
+
+chn_status chn_lstm_step_bwd(const chn_array *dz_next, const chn_array *U, const chn_array *dh, const chn_array *gates,
+                             const chn_array *c_prev, const chn_array *c, const chn_array *dc_next, const chn_array *dz,
+                             const chn_array *dc_prev, chn_stream stream) {
+  using namespace chn;
+  CHN_TRY(validate(c, "c", false));
+  if (c->ndim != 2) return fail(CHN_ERR_NDIM, "lstm_step: c must be 2-d");
+  if (!dh) return fail(CHN_ERR_NULL, "lstm_step: dh is NULL");
+  BwdArgs a{};
+  a.B = c->shape[0]; a.H = c->shape[1];
+  if (a.H % 32) return fail(CHN_ERR_SHAPE, "lstm_step: the hidden width %lld is not a multiple of 32 (pad it, or use the unfused calls)", (long long)a.H);
+  const int t = dh->dtype;
+  if (t != CHN_F32 && t != CHN_BF16) return fail(CHN_ERR_DTYPE, "lstm_step: dh must be F32 or BF16");
+  CHN_TRY(view(c, "c", false, a.B, a.H, CHN_F32, false, &a.c_pitch));
+  CHN_TRY(view(c_prev, "c_prev", false, a.B, a.H, CHN_F32, false, &a.cp_pitch));
+  CHN_TRY(view(gates, "gates", false, a.B, 4 * a.H, CHN_F32, false, &a.g_pitch));
+  CHN_TRY(view(dh, "dh", true, a.B, a.H, t, false, &a.dh_pitch));
+  if (dz_next) {
+    CHN_TRY(view(dz_next, "dz_next", false, a.B, 4 * a.H, t, true, &a.dzn_pitch));
+    CHN_TRY(view(U, "U", false, a.H, 4 * a.H, t, true, &a.u_pitch));
+  }
+  if (dc_next) CHN_TRY(view(dc_next, "dc_next", false, a.B, a.H, CHN_F32, false, &a.dcn_pitch));
+  CHN_TRY(view(dz, "dz", true, a.B, 4 * a.H, t, false, &a.dz_pitch));
+  CHN_TRY(view(dc_prev, "dc_prev", true, a.B, a.H, CHN_F32, false, &a.dcp_pitch));
+  if (a.B * a.H == 0) return CHN_OK;
+  const int64_t by = (a.B + 31) / 32;
+  if (by > 65535) return fail(CHN_ERR_SHAPE, "lstm_step: batch too large");
+  a.dz_next = dz_next ? dz_next->data : nullptr;
+  a.U = dz_next ? U->data : nullptr;
+  a.dh = dh->data;
+  a.gates = static_cast<const float *>(gates->data);
+  a.c_prev = static_cast<const float *>(c_prev->data);
+  a.c = static_cast<const float *>(c->data);
+  a.dc_next = dc_next ? static_cast<const float *>(dc_next->data) : nullptr;
+  a.dz = dz->data;
+  a.dc_prev = static_cast<float *>(dc_prev->data);
+  const dim3 grid((unsigned)(a.H / 32), (unsigned)by);
+  if (t == CHN_BF16) hipLaunchKernelGGL(lstm_step_bwd_kernel<bf16_raw>, grid, dim3(kThreads), 0, as_stream(stream), a);
+  else hipLaunchKernelGGL(lstm_step_bwd_kernel<float>, grid, dim3(kThreads), 0, as_stream(stream), a);
+  return check_launch("lstm_step_bwd");
+}
+
+}  // extern "C"

@@ -163,18 +163,21 @@ def test_config4_full_size_step_sampled():
     Hs, Cs, Z, G = (m.cpu().numpy() for m in (tr.Hs, tr.Cs, tr.Z, tr.G))
     Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
     # gate pre-activations x W + h U, sampled
+    assert tr.fused_step                       # the configuration the benchmark times: Z holds x W only
     ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
-    ref = O.gemm_entries(X, P0["W"], ms, ns) + O.gemm_entries(Hprev, P0["U"], ms, ns)
-    S = O.gemm_entries(np.abs(X), np.abs(P0["W"]), ms, ns) + O.gemm_entries(np.abs(Hprev), np.abs(P0["U"]), ms, ns)
-    check(Z[ms, ns].astype(np.float64), ref, TOL_SUM, S, "gates pre-activation")
-    # cell, every step, from the GPU's own pre-activations
+    ref = O.gemm_entries(X, P0["W"], ms, ns)
+    S = O.gemm_entries(np.abs(X), np.abs(P0["W"]), ms, ns)
+    check(Z[ms, ns].astype(np.float64), ref, TOL_SUM, S, "input part of the gate pre-activations")
+    # fused step (recurrent product + cell), whole steps, from the GPU's own inputs of that step
     for t in (0, 1, T // 2, T - 1):
         sl = slice(t * Bn, (t + 1) * Bn)
-        c, h, g = O.lstm_fwd(Z[sl], P0["b"], Cs[sl])
-        check(G[sl].astype(np.float64), g, TOL_EW, None, "gates %d" % t)
-        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H])
-        check(Cs[t * Bn + Bn:(t + 2) * Bn].astype(np.float64), c, TOL_EW, Sc, "c %d" % t)
-        check(Hall[sl].astype(np.float64), h, TOL_EW, Sc, "h %d" % t)
+        z = O.gemm(Hprev[sl], P0["U"], Z[sl], 1.0, 1.0)
+        Sz = O.gemm(np.abs(Hprev[sl]), np.abs(P0["U"])) + np.abs(Z[sl]) + np.abs(P0["b"])
+        c, h, g = O.lstm_fwd(z, P0["b"], Cs[sl])
+        check(G[sl].astype(np.float64), g, TOL_SUM, Sz, "gates %d" % t)
+        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H]) + Sz[:, :H] + Sz[:, H:2 * H] * np.abs(Cs[sl]) + Sz[:, 2 * H:3 * H]
+        check(Cs[t * Bn + Bn:(t + 2) * Bn].astype(np.float64), c, TOL_SUM, Sc, "c %d" % t)
+        check(Hall[sl].astype(np.float64), h, TOL_SUM, Sc + Sz[:, 3 * H:], "h %d" % t)
     ms, ns, ref, S = sample_gemm(Hall, P0["W_out"].T)
     check(logits[ms, ns].astype(np.float64), ref + P0["b_out"][ns], TOL_SUM, S, "logits")
     rl, _, _, nv = O.softmax_ce_fwd(logits, tgf)
@@ -235,16 +238,20 @@ def test_config4_full_size_mixed_precision_sampled():
     X, Hs, Cs, Z, G = (host(m) for m in (tr.X, tr.Hs, tr.Cs, tr.Z, tr.G))
     assert np.array_equal(X, Pl0["E"][idf])
     Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
+    assert tr.fused_step
     ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
-    ref = O.gemm_entries(X, Pl0["W"], ms, ns) + O.gemm_entries(Hprev, Pl0["U"], ms, ns)
-    S = O.gemm_entries(np.abs(X), np.abs(Pl0["W"]), ms, ns) + O.gemm_entries(np.abs(Hprev), np.abs(Pl0["U"]), ms, ns)
-    check(Z[ms, ns], ref, TOL_SUM, S, "gates pre-activation")
+    ref = O.gemm_entries(X, Pl0["W"], ms, ns)
+    S = O.gemm_entries(np.abs(X), np.abs(Pl0["W"]), ms, ns)
+    check(Z[ms, ns], ref, TOL_SUM, S, "input part of the gate pre-activations")
     for t in (0, T // 2, T - 1):
         sl = slice(t * Bn, (t + 1) * Bn)
-        c, h, g = O.lstm_fwd(Z[sl], P0["b"], Cs[sl])
-        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H])
-        check(Cs[t * Bn + Bn:(t + 2) * Bn], c, TOL_EW, Sc, "c %d" % t)
-        check(Hall[sl], h, TOL_BF16, Sc, "h %d" % t)
+        z = O.gemm(Hprev[sl], Pl0["U"], Z[sl], 1.0, 1.0)
+        Sz = O.gemm(np.abs(Hprev[sl]), np.abs(Pl0["U"])) + np.abs(Z[sl]) + np.abs(P0["b"])
+        c, h, g = O.lstm_fwd(z, P0["b"], Cs[sl])
+        check(G[sl], g, TOL_SUM, Sz, "gates %d" % t)
+        Sc = np.abs(g[:, H:2 * H] * Cs[sl]) + np.abs(g[:, :H] * g[:, 2 * H:3 * H]) + Sz[:, :H] + Sz[:, H:2 * H] * np.abs(Cs[sl]) + Sz[:, 2 * H:3 * H]
+        check(Cs[t * Bn + Bn:(t + 2) * Bn], c, TOL_SUM, Sc, "c %d" % t)
+        check(Hall[sl], h, TOL_BF16, Sc + Sz[:, 3 * H:], "h %d" % t)
     logits = host(tr.logits)
     ms, ns, ref, S = sample_gemm(Hall, Pl0["W_out"].T)
     check(logits[ms, ns], ref + P0["b_out"][ns], TOL_SUM, S, "logits")

@@ -406,3 +406,75 @@ def test_adam_update_multi_follows_the_oracle_over_several_steps():
         B.adam_update_multi(pd[:1], [dev(G[0])], md[:1], vd[:1], 0.01, 0)           # steps count from 1
     with pytest.raises(B.ChnError):
         B.adam_update_multi(pd[:1], [dev(G[0])], md[:1], vd[1:2], 0.01, 1)          # state of another shape
+
+
+# ------------------------------------------------------------------------------------ fused recurrent step
+@pytest.mark.parametrize("Bn,H,dt", [(128, 672, "f32"), (128, 672, "bf16"), (5, 32, "f32"), (33, 64, "bf16"), (70, 96, "f32")])
+def test_lstm_step_fused_product_and_cell(Bn, H, dt):
+    tol = TOL_SUM if dt == "f32" else TOL_BF16
+    q = (lambda a: a) if dt == "f32" else bf16r
+    zx, bias, cp = rnd((Bn, 4 * H), lo=-2, hi=2), rnd((4 * H,)), rnd((Bn, H), lo=-2, hi=2)
+    hp, U = q(rnd((Bn, H))), q(rnd((H, 4 * H), lo=-0.1, hi=0.1))
+    c, h, g = empty((Bn, H)), empty((Bn, H), dt), empty((Bn, 4 * H))
+    Ut = dev(np.ascontiguousarray(U.T), dt)
+    B.lstm_step_fwd(dev(zx), dev(hp, dt), Ut, dev(bias), dev(cp), c, h, g)
+    z = O.gemm(hp, U, zx, 1.0, 1.0)
+    rc, rh, rg = O.lstm_fwd(z, bias, cp)
+    Sz = O.gemm(np.abs(hp), np.abs(U)) + np.abs(zx) + np.abs(bias)
+    Sg = np.concatenate([0.25 * Sz[:, :H], 0.25 * Sz[:, H:2 * H], Sz[:, 2 * H:3 * H], 0.25 * Sz[:, 3 * H:]], axis=1)   # |d act / dz| <= 1/4, 1
+    check(host(g), rg, TOL_SUM, Sg + 1e-1, "gates")
+    Sc = np.abs(rg[:, H:2 * H] * cp) + np.abs(rg[:, :H] * rg[:, 2 * H:3 * H]) + Sg[:, :H] + Sg[:, H:2 * H] * np.abs(cp) + Sg[:, 2 * H:3 * H]
+    check(host(c), rc, TOL_SUM, Sc, "c")
+    check(host(h), rh, tol, Sc + Sg[:, 3 * H:], "h")
+    # the unfused calls on the same operands give the same step
+    z2 = dev(zx).clone()
+    B.gemm(dev(hp, dt), dev(U, dt), z2, beta=1.0)
+    c2, h2, g2 = empty((Bn, H)), empty((Bn, H), dt), empty((Bn, 4 * H))
+    B.lstm_fwd(z2, dev(bias), dev(cp), c2, h2, g2)
+    check(host(c), host(c2), TOL_SUM, Sc, "c fused vs unfused")
+    # no bias, no gates, pitched zx (a row block of a wider buffer)
+    wide = dev(np.concatenate([zx, zx], axis=1))[:, :4 * H]
+    c3, h3 = empty((Bn, H)), empty((Bn, H), dt)
+    B.lstm_step_fwd(wide, dev(hp, dt), Ut, None, dev(cp), c3, h3, None)
+    rc0, _, _ = O.lstm_fwd(z, None, cp)
+    check(host(c3), rc0, TOL_SUM, Sc, "c no bias")
+
+    # backward: dh <- dh + dz_next U^T, then the cell backward from the GPU's own retained outputs
+    dhin, dzn, dcn = q(rnd((Bn, H))), q(rnd((Bn, 4 * H), lo=-0.5, hi=0.5)), rnd((Bn, H))
+    gh, ch = host(g), host(c)
+    dh = dev(dhin, dt)
+    dz, dcp = empty((Bn, 4 * H), dt), empty((Bn, H))
+    B.lstm_step_bwd(dev(dzn, dt), dev(U, dt), dh, g, dev(cp), c, dev(dcn), dz, dcp)
+    dh_ref = O.gemm(dzn, U.T, dhin, 1.0, 1.0)
+    Sdh = O.gemm(np.abs(dzn), np.abs(U.T)) + np.abs(dhin)
+    check(host(dh), dh_ref, tol, Sdh, "dh total")
+    dh_seen = host(dh)                                          # what the cell saw (rounded in mixed precision)
+    rdz, rdcp = O.lstm_bwd(gh, cp, ch, dh_seen, dcn)
+    Sdc = np.abs(dcn) + np.abs(dh_seen)
+    Sdz = np.concatenate([Sdc, Sdc * (1 + np.abs(cp)), Sdc, np.abs(dh_seen)], axis=1)
+    check(host(dz), rdz, TOL_EW * 10 if dt == "f32" else TOL_BF16, Sdz, "dz")
+    check(host(dcp), rdcp, TOL_EW * 10, Sdc, "dc_prev")
+    # last step of the window: nothing flows back from a later step
+    dh = dev(dhin, dt)
+    B.lstm_step_bwd(None, None, dh, g, dev(cp), c, None, dz, dcp)
+    assert np.array_equal(host(dh), dhin.astype(np.float64))
+    rdz, rdcp = O.lstm_bwd(gh, cp, ch, dhin, None)
+    check(host(dz), rdz, TOL_EW * 10 if dt == "f32" else TOL_BF16, Sdz, "dz last")
+
+
+def test_lstm_step_refuses_what_it_cannot_tile():
+    Bn, H = 4, 40                                               # not a multiple of 32
+    z, cp = torch.zeros(Bn, 4 * H, device="cuda"), torch.zeros(Bn, H, device="cuda")
+    with pytest.raises(B.ChnError) as e:
+        B.lstm_step_fwd(z, cp, torch.zeros(4 * H, H, device="cuda"), None, cp, cp.clone(), cp.clone(), None)
+    assert e.value.status == -4
+    H = 64
+    z, cp = torch.zeros(Bn, 4 * H, device="cuda"), torch.zeros(Bn, H, device="cuda")
+    hb = torch.zeros(Bn, H, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.ChnError) as e:                        # operands of two dtypes
+        B.lstm_step_fwd(z, hb, torch.zeros(4 * H, H, device="cuda"), None, cp, cp.clone(), hb.clone(), None)
+    assert e.value.status == -3
+    with pytest.raises(B.ChnError) as e:                        # rows of h_prev off the 16-byte grid
+        B.lstm_step_fwd(z, torch.zeros(Bn, H + 1, device="cuda")[:, 1:], torch.zeros(4 * H, H, device="cuda"), None, cp,
+                        cp.clone(), cp.clone(), None)
+    assert e.value.status == -5
