@@ -29,6 +29,8 @@ import weakref
 __all__ = ["Variable", "Parameter", "VariableNode", "FunctionNode", "GpuBackend", "using_backend",
            "no_backprop_mode", "linear", "matmul", "relu", "gelu", "add", "softmax_cross_entropy",
            "embed_id", "lstm", "split_rows", "concat_rows", "Linear", "SGD", "Adam", "live_function_nodes",
+           "grad", "mul", "sub", "scale", "tanh", "sum_all", "sum_rows", "broadcast_to", "broadcast_rows", "transpose",
+           "relu_grad",
            "MLP", "LSTMLanguageModel"]
 
 
@@ -151,13 +153,17 @@ class VariableNode:
     """A variable's place in the backtracking graph.
 
     Holds the creator function node, the topological rank, and -- only while a function has asked
-    for it -- the array (Section "Function-wise Local Memory Usage Reduction").  The gradient that
-    back-propagation delivers lives here too, so the user handle can be dropped at any time.
+    for it -- the array (Section "Function-wise Local Memory Usage Reduction").  `grad` is a slot
+    used while a backward pass is running; when the pass ends the gradient moves to the user's
+    :class:`Variable` (Section "Interface to Access the Resulting Gradients": the reference from a
+    variable to its gradient is not part of the graph; kept on the node it would close a cycle
+    through the graph of a differentiable backward pass).  The node knows its variable weakly.
     """
     __slots__ = ("creator", "rank", "requires_grad", "data", "grad", "_grad_owned", "_retainers", "name",
-                 "__weakref__")
+                 "_variable", "__weakref__")
 
     def __init__(self, requires_grad, name=None):
+        self._variable = None
         self.creator = None
         self.rank = 0
         self.requires_grad = requires_grad
@@ -186,6 +192,16 @@ class Variable:
     def __init__(self, array, requires_grad=True, name=None):
         self.array = array
         self.node = VariableNode(requires_grad, name)
+        self.node._variable = weakref.ref(self)
+        self._grad, self._grad_owned, self.grad_var = None, False, None
+
+    @classmethod
+    def _of(cls, node, array):
+        """Another handle on an existing node (what a function's backward sees of a retained value)."""
+        v = cls.__new__(cls)
+        v.array, v.node = array, node
+        v._grad, v._grad_owned, v.grad_var = None, False, None
+        return v
 
     shape = property(lambda self: self.array.shape)
     creator = property(lambda self: self.node.creator)
@@ -193,12 +209,13 @@ class Variable:
 
     @property
     def grad(self):
-        return self.node.grad
+        """The gradient array of the last backward pass(es); `grad_var` is the same gradient as a
+        variable with its own history after ``backward(enable_double_backprop=True)``."""
+        return self._grad
 
     @grad.setter
     def grad(self, g):
-        self.node.grad = g
-        self.node._grad_owned = False
+        self._grad, self._grad_owned, self.grad_var = g, False, None
 
     def cleargrad(self):
         self.grad = None
@@ -208,8 +225,15 @@ class Variable:
         self.node.creator = None
         self.node.rank = 0
 
-    def backward(self, retain_grad=False):
-        _backward(self, retain_grad)
+    def backward(self, retain_grad=False, enable_double_backprop=False):
+        """Gradients of this variable with respect to everything it was computed from, stored in
+        the `grad` of each variable.  With `enable_double_backprop` the backward computation is
+        itself recorded (Section "Double Backpropagation"): the graph is kept, `grad_var` carries
+        the history, and what was computed from the gradients can be differentiated again."""
+        if enable_double_backprop:
+            _backward_vars([self], [None if self._grad is None else Variable(self._grad, False)], None, True, retain_grad)
+        else:
+            _backward(self, retain_grad)
 
 
 class Parameter(Variable):
@@ -266,6 +290,26 @@ class FunctionNode:
     def get_retained_outputs(self):
         return self._out_data
 
+    def get_retained_input_vars(self):
+        return tuple(Variable._of(self.inputs[i], self.inputs[i].data) for i in self._retain_in)
+
+    def get_retained_output_vars(self):
+        """Retained outputs as variables for a differentiable backward.  The function knows its
+        outputs only weakly (a strong reference would close a cycle), so an output node may be gone
+        by now: then nobody else refers to it, and a fresh node is connected in its place around the
+        array kept as a backup (Section "Output Retention for Double Backpropagation")."""
+        outs = []
+        for k, i in enumerate(self._retain_out):
+            node = self.outputs[i]()
+            if node is None:
+                node = VariableNode(True)
+                node.creator, node.rank = self, self.rank + 1
+                refs = list(self.outputs)
+                refs[i] = weakref.ref(node)
+                self.outputs = tuple(refs)
+            outs.append(Variable._of(node, self._out_data[k]))
+        return tuple(outs)
+
     def apply(self, inputs):
         """Run forward on the inputs' arrays, wrap the results, and record this node if any
         input takes part in back-propagation."""
@@ -316,8 +360,35 @@ class FunctionNode:
     def forward(self, xs):
         raise NotImplementedError
 
+    # A function gives `backward` (arrays in, arrays out: kernels called directly), or
+    # `backward_vars` (variables in, variables out, written with differentiable functions: Section
+    # "Double Backpropagation"), or both; each default is derived from the other.
     def backward(self, indexes, gys):
-        raise NotImplementedError
+        if type(self).backward_vars is FunctionNode.backward_vars:
+            raise NotImplementedError
+        with no_backprop_mode():
+            gxs = self.backward_vars(indexes, tuple(None if g is None else Variable(g, False) for g in gys))
+        return tuple(None if g is None else g.array for g in gxs)
+
+    def backward_vars(self, indexes, gys):
+        if type(self).backward is FunctionNode.backward:
+            raise NotImplementedError
+        if _record:
+            raise NotImplementedError("%s has no differentiable backward: double backprop cannot pass through it"
+                                      % type(self).__name__)
+        self.grad_slots, self.unit_seed = (None,) * len(indexes), False
+        gxs = self.backward(indexes, tuple(None if g is None else g.array for g in gys))
+        self.grad_slots = None
+        return tuple(None if g is None else Variable(g, False) for g in gxs)
+
+
+def _settle(nodes):
+    """End of a backward pass: gradients move from the nodes' slots to the users' variables."""
+    for n in nodes:
+        v = None if n._variable is None else n._variable()
+        if v is not None and n.grad is not None:
+            v._grad, v._grad_owned, v.grad_var = n.grad, n._grad_owned, None
+        n.grad, n._grad_owned = None, False
 
 
 def _accumulate(node, g, fresh):
@@ -344,6 +415,17 @@ def _backward(root, retain_grad):
     once consumed unless `retain_grad`."""
     F = backend()
     rn = root.node
+    touched = {}                          # every node whose slot this pass uses, by identity
+
+    def touch(n):
+        if id(n) not in touched:
+            touched[id(n)] = n
+            v = None if n._variable is None else n._variable()
+            if v is not None and v._grad is not None:      # gradients accumulate until cleared
+                n.grad, n._grad_owned = v._grad, v._grad_owned
+        return n
+
+    touch(rn)
     if rn.grad is None:
         n = 1
         for s in root.shape:
@@ -357,6 +439,7 @@ def _backward(root, retain_grad):
     else:
         rn_unit = False
     if rn.creator is None:
+        _settle(touched.values())
         return
     tie = itertools.count()
     heap, waiting = [], {}
@@ -384,6 +467,8 @@ def _backward(root, retain_grad):
                 if o is not None and o is not rn:
                     o.grad, o._grad_owned = None, False
         indexes = tuple(i for i, n in enumerate(f.inputs) if n.requires_grad)
+        for i in indexes:
+            touch(f.inputs[i])
         # slots a function may accumulate into directly (a product can add into its output)
         slots = f.grad_slots = tuple(f.inputs[i].grad if f.inputs[i]._grad_owned else None for i in indexes)
         gxs = f.backward(indexes, gys)
@@ -402,6 +487,94 @@ def _backward(root, retain_grad):
         del gys, gxs, outs, held
         waiting[id(f)] = None
         f.unchain()
+    _settle(touched.values())
+
+
+def _backward_vars(roots, seeds, targets, store, retain_grad=False):
+    """The same walk with gradients that are variables and backward computations that are function
+    applications (Section "Double Backpropagation").  Whether those applications are recorded is
+    the caller's business (`no_backprop_mode`).  Nothing is cut out of the graph: the gradients'
+    own history refers to it.  Returns {id(node): gradient variable} for the nodes in `targets`
+    (all leaves when None); with `store` the gradients also go to the users' variables."""
+    F = backend()
+    gvars, keep = {}, {}
+    for r, seed in zip(roots, seeds):
+        if seed is None:
+            n = 1
+            for d in r.shape:
+                n *= d
+            if n != 1:
+                raise ValueError("a non-scalar output needs a gradient to start from")
+            one = F.empty(r.shape, F.dtype(r.array))
+            F.elementwise_broadcast("fill", [], one, (1.0,))
+            seed = Variable(one, False)
+        gvars[id(r.node)] = seed
+        keep[id(r.node)] = r.node
+    want = None if targets is None else {id(t.node) for t in targets}
+    result = {}
+    tie = itertools.count()
+    heap, queued = [], set()
+
+    def push(node):
+        f = node.creator
+        if f is not None and id(f) not in queued:
+            queued.add(id(f))
+            heapq.heappush(heap, (-f.rank, next(tie), f))
+
+    for r in roots:
+        push(r.node)
+    while heap:
+        _, _, f = heapq.heappop(heap)
+        outs = [ref() for ref in f.outputs]
+        gys = []
+        for o in outs:
+            g = None if o is None else gvars.get(id(o))
+            gys.append(g)
+            if g is not None and ((want is not None and id(o) in want) or retain_grad):
+                result[id(o)] = g
+            if o is not None and not any(o is r.node for r in roots):
+                gvars.pop(id(o), None)
+        indexes = tuple(i for i, n in enumerate(f.inputs) if n.requires_grad)
+        gxs = f.backward_vars(indexes, tuple(gys))
+        if len(gxs) != len(indexes):
+            raise RuntimeError("%s.backward_vars returned %d gradients for %d inputs" % (type(f).__name__, len(gxs), len(indexes)))
+        for i, gx in zip(indexes, gxs):
+            if gx is None:
+                continue
+            n = f.inputs[i]
+            keep[id(n)] = n
+            old = gvars.get(id(n))
+            gvars[id(n)] = gx if old is None else add(old, gx)
+            push(n)
+    for k, g in gvars.items():            # what is left belongs to leaves (and the roots)
+        if want is None or k in want:
+            result[k] = g
+    if store:
+        for k, g in result.items():
+            n = keep[k]
+            v = None if n._variable is None else n._variable()
+            if v is None:
+                continue
+            if v._grad is not None and not any(n is r.node for r in roots):   # accumulate until cleared
+                base = v.grad_var if v.grad_var is not None else Variable(v._grad, False)
+                g = add(base, g)
+            v._grad, v._grad_owned, v.grad_var = g.array, False, g
+    return result
+
+
+def grad(outputs, inputs, grad_outputs=None, enable_double_backprop=False):
+    """Gradients of `outputs` with respect to `inputs`, returned (one variable or None per input)
+    instead of stored: the interface that adds no reference between the objects involved (Section
+    "Interface to Access the Resulting Gradients").  With `enable_double_backprop` the returned
+    variables carry the history of the backward computation."""
+    seeds = list(grad_outputs) if grad_outputs is not None else [None] * len(outputs)
+    seeds = [s if (s is None or isinstance(s, Variable)) else Variable(s, False) for s in seeds]
+    if enable_double_backprop:
+        res = _backward_vars(list(outputs), seeds, list(inputs), False)
+    else:
+        with no_backprop_mode():
+            res = _backward_vars(list(outputs), seeds, list(inputs), False)
+    return [res.get(id(x.node)) for x in inputs]
 
 
 # ---- functions ----------------------------------------------------------------------------------------
@@ -468,6 +641,15 @@ class LinearFunction(FunctionNode):
         return tuple(out)
 
 
+    def backward_vars(self, indexes, gys):
+        if self.act == "gelu":
+            raise NotImplementedError("linear(act='gelu') has no differentiable backward; apply tanh / relu as functions")
+        x, W = self.get_retained_input_vars()
+        gz = gys[0] if self.act is None else relu_grad(gys[0], self.get_retained_output_vars()[0])
+        grads = {0: lambda: matmul(gz, W), 1: lambda: matmul(transpose(gz), x), 2: lambda: sum_rows(gz)}
+        return tuple(grads[i]() for i in indexes)
+
+
 class MatMul(FunctionNode):
     """y = x @ W (both 2-d); retains both inputs."""
     fresh = (0, 1)
@@ -504,6 +686,12 @@ class MatMul(FunctionNode):
         return tuple(out)
 
 
+    def backward_vars(self, indexes, gys):
+        x, W = self.get_retained_input_vars()
+        grads = {0: lambda: matmul(gys[0], transpose(W)), 1: lambda: matmul(transpose(x), gys[0])}
+        return tuple(grads[i]() for i in indexes)
+
+
 class _Activation(FunctionNode):
     fresh = (0,)
     op = None
@@ -530,6 +718,9 @@ class ReLU(_Activation):
 
     def saved(self):
         return self.get_retained_outputs()[0]
+
+    def backward_vars(self, indexes, gys):
+        return (relu_grad(gys[0], self.get_retained_output_vars()[0]),)
 
 
 class GELU(_Activation):
@@ -571,6 +762,165 @@ class Add(FunctionNode):
             else:
                 out.append(gys[0])
         return tuple(out)
+
+
+    def backward_vars(self, indexes, gys):
+        return tuple(sum_rows(gys[0]) if i == 1 and self.bias_like else gys[0] for i in indexes)
+
+
+# ---- functions whose backward is written with functions (all of them differentiable any number of times)
+class ReLUGrad(FunctionNode):
+    """gy * [y > 0]: the backward of ReLU as a function of gy.  As a function of y it is constant
+    almost everywhere, so y receives no gradient."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("relu_bwd", [xs[0], xs[1]], out)
+        self.retain_inputs((1,))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        y, = self.get_retained_input_vars()
+        return tuple(relu_grad(gys[0], y) if i == 0 else None for i in indexes)
+
+
+class Mul(FunctionNode):
+    """x * y, same shape; each factor's gradient is gy times the other factor."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("mul", [xs[0], xs[1]], out)
+        self.retain_inputs((0, 1))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        x, y = self.get_retained_input_vars()
+        return tuple(mul(gys[0], y if i == 0 else x) for i in indexes)
+
+
+class Sub(FunctionNode):
+    """x - y, same shape; retains nothing."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("sub", [xs[0], xs[1]], out)
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return tuple(gys[0] if i == 0 else scale(gys[0], -1.0) for i in indexes)
+
+
+class Scale(FunctionNode):
+    """s * x for a constant s."""
+
+    def __init__(self, s):
+        super().__init__()
+        self.s = float(s)
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("scale", [xs[0]], out, (self.s,))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return (scale(gys[0], self.s),)
+
+
+class Tanh(FunctionNode):
+    """tanh(x); differentiated from its output, gx = gy * (1 - y^2) (Section "Function-wise Local
+    Memory Usage Reduction"), and since that is written with functions of y, any number of times."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("tanh", [xs[0]], out)
+        self.retain_outputs((0,))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        y, = self.get_retained_output_vars()
+        return (sub(gys[0], mul(gys[0], mul(y, y))),)
+
+
+class SumAll(FunctionNode):
+    """Sum of every element, a 0-d result (fixed-order reduction over the flattened array)."""
+
+    def forward(self, xs):
+        F = backend()
+        x = xs[0]
+        self.shape, self.dt = tuple(x.shape), F.dtype(x)
+        out = F.empty((1,), "f32")
+        if len(x.shape) == 2:                 # any strides: rows first, then the row sums
+            rows = F.empty((x.shape[0],), "f32")
+            F.reduce_axis("sum", x, 1, rows)
+            x = rows
+        F.reduce_axis("sum", x.reshape(1, -1), 1, out)
+        return (out.reshape(()),)
+
+    def backward_vars(self, indexes, gys):
+        return (broadcast_to(gys[0], self.shape),)
+
+
+class BroadcastTo(FunctionNode):
+    """A 0-d value repeated into `shape`; its backward is the sum of everything."""
+
+    def __init__(self, shape):
+        super().__init__()
+        self.shape = tuple(shape)
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(self.shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("copy", [xs[0]], out)
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return (sum_all(gys[0]),)
+
+
+class SumRows(FunctionNode):
+    """(n, d) -> (d,): the sum over the rows (a bias gradient); backward repeats the row."""
+
+    def forward(self, xs):
+        F = backend()
+        self.n = xs[0].shape[0]
+        out = F.empty((xs[0].shape[1],), "f32")
+        F.reduce_axis("sum", xs[0], 0, out)
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return (broadcast_rows(gys[0], self.n),)
+
+
+class BroadcastRows(FunctionNode):
+    """(d,) -> (n, d): the row repeated n times; backward sums the rows."""
+
+    def __init__(self, n):
+        super().__init__()
+        self.n = n
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty((self.n, xs[0].shape[0]), F.dtype(xs[0]))
+        F.elementwise_broadcast("copy", [xs[0]], out)
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return (sum_rows(gys[0]),)
+
+
+class Transpose(FunctionNode):
+    """The transposed VIEW of a 2-d array (no copy: the kernels take any strides)."""
+
+    def forward(self, xs):
+        return (_t(xs[0]),)
+
+    def backward_vars(self, indexes, gys):
+        return (transpose(gys[0]),)
 
 
 class SoftmaxCrossEntropy(FunctionNode):
@@ -749,6 +1099,46 @@ def gelu(x):
 
 def add(x, y):
     return Add().apply((x, y))[0]
+
+
+def relu_grad(gy, y):
+    return ReLUGrad().apply((gy, y))[0]
+
+
+def mul(x, y):
+    return Mul().apply((x, y))[0]
+
+
+def sub(x, y):
+    return Sub().apply((x, y))[0]
+
+
+def scale(x, s):
+    return Scale(s).apply((x,))[0]
+
+
+def tanh(x):
+    return Tanh().apply((x,))[0]
+
+
+def sum_all(x):
+    return SumAll().apply((x,))[0]
+
+
+def broadcast_to(x, shape):
+    return BroadcastTo(shape).apply((x,))[0]
+
+
+def sum_rows(x):
+    return SumRows().apply((x,))[0]
+
+
+def broadcast_rows(x, n):
+    return BroadcastRows(n).apply((x,))[0]
+
+
+def transpose(x):
+    return Transpose().apply((x,))[0]
 
 
 def softmax_cross_entropy(logits, labels, ignore_label=-1, grad_dtype=None):

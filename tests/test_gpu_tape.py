@@ -219,3 +219,39 @@ def test_tape_returns_device_memory_while_walking_back():
         l2 = forward()
     assert torch.cuda.memory_allocated() - base - after <= 2 * act_bytes
     assert abs(float(l2.array.cpu()) - np.log(width)) < 2.0
+
+
+@pytest.mark.parametrize("first", ["tanh", "relu_fused"])
+def test_tape_double_backprop_gradient_penalty(first):
+    # the gradient of || d f / d x ||^2 needs a differentiable backward pass; the same tape code runs on
+    # the GPU and, as the reference, on the CPU with the oracle's functions as kernels
+    rng = np.random.default_rng(23)
+    n, d, hdim, k = 200, 96, 130, 24
+    W1 = (rng.standard_normal((hdim, d)) / np.sqrt(d)).astype(np.float32)
+    b1 = (rng.standard_normal(hdim) * 0.1).astype(np.float32)
+    W2 = (rng.standard_normal((k, hdim)) / np.sqrt(hdim)).astype(np.float32)
+    b2 = np.zeros(k, dtype=np.float32)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    c = rng.standard_normal((n, k)).astype(np.float32)
+
+    def run(F):
+        ps = [T.Parameter(F.from_numpy(a)) for a in (W1, b1, W2, b2)]
+        xv = T.Variable(F.from_numpy(x))
+        lin = T.linear(xv, ps[0], ps[1], act="relu") if first == "relu_fused" else T.tanh(T.linear(xv, ps[0], ps[1]))
+        f = T.sum_all(T.mul(T.linear(lin, ps[2], ps[3]), T.Variable(F.from_numpy(c), False)))
+        g, = T.grad([f], [xv], enable_double_backprop=True)
+        pen = T.sum_all(T.mul(g, g))
+        pen.backward()
+        # a parameter the penalty does not depend on (the first bias behind a ReLU) receives nothing
+        pg = [np.zeros(a.shape) if p.grad is None else F.to_numpy(p.grad) for p, a in zip(ps[:3], (W1, b1, W2))]
+        gx = np.zeros(x.shape) if xv.grad is None else F.to_numpy(xv.grad)    # piecewise linear f: no dependence on x either
+        return float(F.to_numpy(pen.array)), F.to_numpy(g.array), pg, gx
+
+    got = run(T.backend())
+    with T.using_backend(OracleBackend()) as Fo:
+        ref = run(Fo)
+    assert abs(got[0] - ref[0]) <= 1e-4 * abs(ref[0])
+    check(got[1], ref[1], 1e-4, float(np.max(np.abs(ref[1]))), "d f / d x")
+    for a, b, name in zip(got[2], ref[2], ("W1", "b1", "W2")):
+        check(a, b, 1e-4, float(np.max(np.abs(b))) + 1e-30, "d penalty / d " + name)
+    check(got[3], ref[3], 1e-4, float(np.max(np.abs(ref[3]))) + 1e-30, "d penalty / d x")

@@ -316,6 +316,123 @@ def test_no_backprop_mode_records_nothing(F):
     assert y.creator is None and p.node.data is None and T.live_function_nodes() == 0
 
 
+# ---- double backpropagation ---------------------------------------------------------------------------
+def test_gradients_of_gradients_closed_form(F):
+    # y = sum x^3: dy/dx = 3 x^2, d/dx sum(dy/dx) = 6 x, once more: 6
+    x = T.Variable(np.array([[1.0, -2.0, 0.5], [3.0, 0.25, -1.5]]))
+    y = T.sum_all(T.mul(T.mul(x, x), x))
+    g1, = T.grad([y], [x], enable_double_backprop=True)
+    np.testing.assert_allclose(g1.array, 3 * x.array ** 2, rtol=1e-14)
+    g2, = T.grad([T.sum_all(g1)], [x], enable_double_backprop=True)
+    np.testing.assert_allclose(g2.array, 6 * x.array, rtol=1e-14)
+    T.sum_all(g2).backward()
+    np.testing.assert_allclose(x.grad, 6 * np.ones((2, 3)), rtol=1e-14)
+    # grad() stores nothing, and without the flag its result has no history
+    x2 = T.Variable(np.array([[2.0, 3.0]]))
+    g, = T.grad([T.sum_all(T.mul(x2, x2))], [x2])
+    assert x2.grad is None and g.creator is None
+    np.testing.assert_allclose(g.array, 2 * x2.array, rtol=1e-14)
+
+
+@pytest.mark.parametrize("first", ["tanh", "relu_fused", "relu"])
+def test_gradient_penalty_matches_finite_differences(F, first):
+    # penalty(theta) = || d f / d x ||^2 with f a two-layer network: differentiating it needs the
+    # backward pass of f to be differentiable
+    rng = np.random.default_rng(17)
+    W1, b1, W2, b2 = rnd(rng, 5, 4), rnd(rng, 5), rnd(rng, 3, 5), rnd(rng, 3)
+    x, c = rnd(rng, 6, 4), rnd(rng, 6, 3)
+
+    def penalty(double):
+        ps = [T.Parameter(W1), T.Parameter(b1), T.Parameter(W2), T.Parameter(b2)]
+        xv = T.Variable(x)
+        if first == "tanh":
+            h = T.tanh(T.linear(xv, ps[0], ps[1]))
+        elif first == "relu":
+            h = T.relu(T.linear(xv, ps[0], ps[1]))
+        else:
+            h = T.linear(xv, ps[0], ps[1], act="relu")
+        f = T.sum_all(T.mul(T.linear(h, ps[2], ps[3]), T.Variable(c, False)))
+        g, = T.grad([f], [xv], enable_double_backprop=double)
+        return T.sum_all(T.mul(g, g)), ps, xv
+
+    pen, ps, xv = penalty(True)
+    pen.backward()
+    num = fd_grad(lambda: float(penalty(False)[0].array), [W1, b1, W2, x])
+    for v, g in zip([ps[0], ps[1], ps[2], xv], num):
+        got = np.zeros_like(g) if v.grad is None else v.grad
+        np.testing.assert_allclose(got, g, rtol=2e-5, atol=1e-7)
+    assert ps[3].grad is None or not np.any(ps[3].grad)          # the penalty does not depend on the last bias
+    if first == "tanh":
+        assert np.any(ps[1].grad)                                # ... but through tanh'' on the first one
+
+
+def test_backward_with_double_backprop_keeps_the_graph_and_gives_grad_var(F):
+    x = T.Variable(np.array([[0.5, -1.0]]))
+    y = T.sum_all(T.mul(T.tanh(x), T.tanh(x)))
+    y.backward(enable_double_backprop=True)
+    assert x.grad_var is not None and x.grad_var.creator is not None and x.grad is x.grad_var.array
+    t = np.tanh(x.array)
+    np.testing.assert_allclose(x.grad, 2 * t * (1 - t ** 2), rtol=1e-13)
+    gx = x.grad_var
+    x.cleargrad()
+    T.sum_all(gx).backward()                                     # d/dx of the gradient itself
+    np.testing.assert_allclose(x.grad, 2 * (1 - t ** 2) ** 2 - 4 * t ** 2 * (1 - t ** 2), rtol=1e-12)
+
+
+def test_a_released_output_node_is_replayed_for_the_differentiable_backward(F):
+    class TanhAndDouble(T.FunctionNode):
+        def forward(self, xs):
+            self.retain_outputs((0,))
+            return (np.tanh(xs[0]), 2.0 * xs[0])
+
+        def backward_vars(self, indexes, gys):
+            y, = self.get_retained_output_vars()
+            parts = []
+            if gys[0] is not None:
+                parts.append(T.sub(gys[0], T.mul(gys[0], T.mul(y, y))))
+            if gys[1] is not None:
+                parts.append(T.scale(gys[1], 2.0))
+                parts.append(T.scale(T.mul(y, y), 0.0))          # touches y: its node must exist
+            out = parts[0]
+            for p in parts[1:]:
+                out = T.add(out, p)
+            return (out,)
+
+    x = T.Variable(np.array([[0.3, -0.7]]))
+    f = TanhAndDouble()
+    y0, y1 = f.apply((x,))
+    backup = y0.array
+    del y0                                                       # nobody refers to the first output any more
+    assert f.outputs[0]() is None
+    g, = T.grad([T.sum_all(y1)], [x], enable_double_backprop=True)
+    np.testing.assert_allclose(g.array, 2 * np.ones((1, 2)))
+    node = f.outputs[0]()
+    assert node is not None and node.creator is f and node.rank == f.rank + 1
+    assert f.get_retained_output_vars()[0].array is backup
+
+
+def test_double_backprop_leaves_no_reference_cycles(F):
+    rng = np.random.default_rng(19)
+    gc.collect()
+    gc.disable()
+    try:
+        W = T.Parameter(rnd(rng, 4, 4))
+        x = T.Variable(rnd(rng, 3, 4))
+        h = T.tanh(T.matmul(x, W))
+        f = T.sum_all(T.mul(h, h))
+        f.backward(enable_double_backprop=True)                  # gradients with history, stored on the variables
+        refs = [weakref.ref(a) for a in (h.array, x.grad_var.array, W.grad_var.array, x.array)]
+        nodes = [weakref.ref(n) for n in (h.node, x.node, W.node, x.grad_var.node)]
+        pen = T.sum_all(T.mul(x.grad_var, x.grad_var))
+        W.cleargrad()
+        pen.backward()
+        assert W.grad is not None
+        del W, x, h, f, pen
+        assert all(r() is None for r in refs) and all(n() is None for n in nodes)    # by reference counting alone
+    finally:
+        gc.enable()
+
+
 def test_adam_optimiser_keeps_state_per_parameter_and_counts_steps(F):
     rng = np.random.default_rng(13)
     Wm, b, x, t = rnd(rng, 3, 4), rnd(rng, 3), rnd(rng, 5, 4), np.array([0, 1, 2, 1, 0])
