@@ -108,6 +108,12 @@ chn_status chn_elementwise_broadcast(int op, int n_in, const chn_array *const *i
 typedef enum { CHN_REDUCE_SUM = 0, CHN_REDUCE_MAX = 1 } chn_reduce_op;
 
 size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis);
+/* Index of the largest element along `axis` (the classification example of Section "API Design"
+ * reports accuracy: the arg-max of the logits against the labels).  `out`: I32 or I64, contiguous,
+ * shaped like chn_reduce_axis's.  Among equal maxima the smallest index wins; a NaN is never
+ * selected (a slice of nothing but NaN yields 0).  An empty axis is CHN_ERR_SHAPE.  No workspace. */
+chn_status chn_argmax_axis(const chn_array *in, int axis, int keepdims, const chn_array *out,
+                           chn_stream stream);
 chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
                            const chn_array *out, void *ws, size_t ws_bytes, chn_stream stream);
 

@@ -148,6 +148,16 @@ def reduce_axis(op, x, axis, keepdims=False):
     return out
 
 
+def argmax_axis(x, axis, keepdims=False):
+    """Index of the largest element along `axis`, the smallest such index among equals: written as
+    the definition (first position where the slice equals its maximum)."""
+    x = _f64(x)
+    m = x.max(axis=axis, keepdims=True)
+    idx = np.arange(x.shape[axis]).reshape([-1 if d == axis % x.ndim else 1 for d in range(x.ndim)])
+    first = np.where(x == m, idx, x.shape[axis]).min(axis=axis, keepdims=keepdims)
+    return first.astype(np.int64)
+
+
 def gemm(A, B, Cin=None, alpha=1.0, beta=0.0):
     """alpha * A @ B + beta * Cin for 2-d views (transposition is expressed by strides)."""
     A, B = _f64(A), _f64(B)

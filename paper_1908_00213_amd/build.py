@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchn.so")
 TOOL = os.path.join(HERE, "mfma_ceiling")
 
-SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "gemm.hip", "lstm.hip", "lstm_step.hip", "softmax_ce.hip",
+SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "argmax.hip", "gemm.hip", "lstm.hip", "lstm_step.hip", "softmax_ce.hip",
            "sgd.hip", "adam.hip", "embed.hip"]
 
 # gemm_inst.hip is compiled once per (dtype, A layout, B layout): k = unit stride along K, m = along M/N

@@ -478,3 +478,40 @@ def test_lstm_step_refuses_what_it_cannot_tile():
         B.lstm_step_fwd(z, torch.zeros(Bn, H + 1, device="cuda")[:, 1:], torch.zeros(4 * H, H, device="cuda"), None, cp,
                         cp.clone(), cp.clone(), None)
     assert e.value.status == -5
+
+
+# ------------------------------------------------------------------------------------ argmax
+@pytest.mark.parametrize("shape,axis", [((300, 1000), 1), ((300, 1000), 0), ((7, 65, 9), 1), ((7, 65, 9), -1), ((5,), 0),
+                                        ((64, 10), 1), ((2, 3, 4, 5), 2)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_argmax_axis(shape, axis, dt):
+    x = rnd(shape, dt)
+    x.reshape(-1)[::7] = np.float32(0.5)                         # ties, exact in both storage types
+    for odt in (torch.int64, torch.int32):
+        oshape = [n for d, n in enumerate(shape) if d != axis % len(shape)]
+        out = torch.empty(oshape, dtype=odt, device="cuda")
+        B.argmax_axis(dev(x, dt), axis, out)
+        assert np.array_equal(host(out), O.argmax_axis(x, axis))
+    xt = dev(x, dt)
+    if len(shape) == 2:                                          # a transposed view swaps the roles of the axes
+        out = torch.empty(shape[axis], dtype=torch.int64, device="cuda")
+        B.argmax_axis(xt.t(), axis, out)
+        assert np.array_equal(host(out), O.argmax_axis(x.T, axis))
+    kd = torch.empty([1 if d == axis % len(shape) else n for d, n in enumerate(shape)], dtype=torch.int64, device="cuda")
+    B.argmax_axis(xt, axis, kd, keepdims=True)
+    assert np.array_equal(host(kd), O.argmax_axis(x, axis, keepdims=True))
+
+
+def test_argmax_is_the_accuracy_of_a_classifier_and_its_errors():
+    logits = rnd((1024, 10))
+    labels = RNG.integers(0, 10, 1024)
+    out = torch.empty(1024, dtype=torch.int64, device="cuda")
+    B.argmax_axis(dev(logits), 1, out)
+    assert float((out.cpu().numpy() == labels).mean()) == float((O.argmax_axis(logits, 1) == labels).mean())
+    for bad_out, axis, status in ((torch.empty(1024, device="cuda"), 1, -3), (torch.empty(10, dtype=torch.int64, device="cuda"), 1, -4),
+                                  (out, 2, -7)):
+        with pytest.raises(B.ChnError) as e:
+            B.argmax_axis(dev(logits), axis, bad_out)
+        assert e.value.status == status
+    with pytest.raises(B.ChnError):
+        B.argmax_axis(torch.empty(4, 0, device="cuda"), 1, torch.empty(4, dtype=torch.int64, device="cuda"))

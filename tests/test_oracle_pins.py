@@ -385,3 +385,16 @@ def test_adam_two_steps_by_hand():
     # m = 0.5 - 2 = -1.5, v = 1 + 8 = 9; m_hat = -2, v_hat = 12
     assert (m[0], v[0]) == (-1.5, 9.0)
     assert p[0] == pytest.approx(9.0 + 2.0 / np.sqrt(12.0), rel=1e-15)
+
+
+def test_argmax_first_of_equal_maxima_by_brute_force():
+    rng = np.random.default_rng(33)
+    x = rng.integers(0, 4, (5, 6, 7)).astype(np.float64)         # many ties
+    for axis in (0, 1, 2, -1):
+        got = O.argmax_axis(x, axis)
+        assert np.array_equal(got, np.argmax(x, axis=axis))      # NumPy documents the first-occurrence rule
+        moved = np.moveaxis(x, axis, -1)
+        for pos in np.ndindex(moved.shape[:-1]):
+            row = list(moved[pos])
+            assert got[pos] == row.index(max(row))
+    assert O.argmax_axis(x, 1, keepdims=True).shape == (5, 1, 7)
