@@ -128,11 +128,18 @@ def lib():
 
 
 def desc(t):
-    """chn_array descriptor of a tensor (or None)."""
+    """chn_array descriptor of a tensor (or None).  The descriptor is kept on the tensor object: a
+    tensor's storage pointer, shape and strides do not change for the life of the object (this
+    package never calls the in-place re-shaping methods that could), and parameters, inputs and
+    gradients are described thousands of times."""
     if t is None:
         return None
     if isinstance(t, ChnArray):
         return t
+    try:
+        return t._chn_desc
+    except AttributeError:
+        pass
     a = ChnArray()
     n = t.dim()
     isz = t.element_size()
@@ -141,6 +148,7 @@ def desc(t):
     a.shape[:n] = t.shape
     a.strides[:n] = [s * isz for s in t.stride()]
     a.dtype = _DTYPES[t.dtype]
+    t._chn_desc = a
     return a
 
 
@@ -169,7 +177,15 @@ def _ptrs(descs):
     return arr
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+_raw_device = getattr(torch._C, "_cuda_getDevice", None)
+
+
 def _stream():
+    """hipStream_t of torch's current stream (the raw-handle query costs a fraction of a microsecond,
+    the Stream object several)."""
+    if _raw_stream is not None and _raw_device is not None:
+        return C.c_void_p(_raw_stream(_raw_device()))
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 

@@ -66,7 +66,7 @@ class _Program:
         self.calls.append((fn, args))
 
     def run(self, stream=None):
-        s = C.c_void_p(torch.cuda.current_stream().cuda_stream) if stream is None else stream
+        s = B._stream() if stream is None else stream
         for fn, args in self.calls:
             st = fn(*args, s)
             if st != 0:

@@ -46,10 +46,11 @@ class GpuBackend:
         self._dt = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
         self._name = {v: k for k, v in self._dt.items()}
         self._gemm_ws = None
+        self._dev = torch.device("cuda", torch.cuda.current_device())
 
     # allocation (PyTorch's caching allocator; freed by reference count, reused in stream order)
     def empty(self, shape, dtype="f32"):
-        return self.torch.empty(tuple(shape), dtype=self._dt[dtype], device="cuda")
+        return self.torch.empty(tuple(shape), dtype=self._dt[dtype], device=self._dev)
 
     def dtype(self, a):
         return self._name[a.dtype]
