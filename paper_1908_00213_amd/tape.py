@@ -30,7 +30,7 @@ __all__ = ["Variable", "Parameter", "VariableNode", "FunctionNode", "GpuBackend"
            "no_backprop_mode", "linear", "matmul", "relu", "gelu", "add", "softmax_cross_entropy",
            "embed_id", "lstm", "split_rows", "concat_rows", "Linear", "SGD", "Adam", "live_function_nodes",
            "grad", "mul", "sub", "scale", "tanh", "sum_all", "sum_rows", "broadcast_to", "broadcast_rows", "transpose",
-           "relu_grad",
+           "relu_grad", "user_elementwise",
            "MLP", "LSTMLanguageModel"]
 
 
@@ -922,6 +922,39 @@ class Transpose(FunctionNode):
 
     def backward_vars(self, indexes, gys):
         return (transpose(gys[0]),)
+
+
+class UserElementwise(FunctionNode):
+    """A differentiable element-wise operation written as two user-defined kernels (Section "Custom
+    CUDA Kernels": the array layer "is easy to extend with user-defined kernels"): `forward_kernel`
+    maps the inputs to one output, `backward_kernel` maps (inputs..., gy) to one gradient per
+    input.  Both are kernel objects called with arrays (the binding's ElementwiseKernel, or
+    anything with the same call signature); all operands share one shape.  Retains its inputs."""
+
+    def __init__(self, forward_kernel, backward_kernel):
+        super().__init__()
+        self.fk, self.bk = forward_kernel, backward_kernel
+
+    def forward(self, xs):
+        self.retain_inputs(tuple(range(len(xs))))
+        return (self.fk(*xs),)
+
+    def backward(self, indexes, gys):
+        xs = self.get_retained_inputs()
+        gxs = self.bk(*xs, gys[0])
+        if not isinstance(gxs, tuple):
+            gxs = (gxs,)
+        if len(gxs) != len(xs):
+            raise RuntimeError("the backward kernel must have one output per input")
+        return tuple(gxs[i] for i in indexes)
+
+
+def user_elementwise(forward_kernel, backward_kernel):
+    """``softplus = user_elementwise(fk, bk); y = softplus(x)``: a function of variables made from
+    two element-wise kernels."""
+    def apply(*xs):
+        return UserElementwise(forward_kernel, backward_kernel).apply(xs)[0]
+    return apply
 
 
 class SoftmaxCrossEntropy(FunctionNode):

@@ -255,3 +255,30 @@ def test_tape_double_backprop_gradient_penalty(first):
     for a, b, name in zip(got[2], ref[2], ("W1", "b1", "W2")):
         check(a, b, 1e-4, float(np.max(np.abs(b))) + 1e-30, "d penalty / d " + name)
     check(got[3], ref[3], 1e-4, float(np.max(np.abs(ref[3]))) + 1e-30, "d penalty / d x")
+
+
+def test_tape_function_made_of_two_user_kernels():
+    # a new differentiable operation from two snippets compiled at run time; reference: the same tape
+    # on the CPU with the oracle's evaluation of the same snippets
+    from oracle import user_kernel as OU
+    from paper_1908_00213_amd import binding as B
+    fwd = ("T x, T y", "T z", "z = log(1 + exp(x)) * y", "softplus_times")
+    bwd = ("T x, T y, T gz", "T gx, T gy", "gx = gz * y / (1 + exp(-x)); gy = gz * log(1 + exp(x))", "softplus_times_bwd")
+    rng = np.random.default_rng(31)
+    x, y = rng.standard_normal((300, 96)).astype(np.float32), rng.standard_normal((300, 96)).astype(np.float32)
+    Wm = (rng.standard_normal((96, 40)) * 0.1).astype(np.float32)
+    t = rng.integers(0, 40, 300)
+
+    def run(F, mk):
+        op = T.user_elementwise(mk(*fwd), mk(*bwd))
+        vs = [T.Variable(F.from_numpy(x)), T.Variable(F.from_numpy(y)), T.Parameter(F.from_numpy(Wm))]
+        l = T.softmax_cross_entropy(T.matmul(op(vs[0], vs[1]), vs[2]), F.from_numpy(t))
+        l.backward()
+        return float(F.to_numpy(l.array)), [F.to_numpy(v.grad) for v in vs]
+
+    got = run(T.backend(), B.ElementwiseKernel)
+    with T.using_backend(OracleBackend()) as Fo:
+        ref = run(Fo, OU.ElementwiseKernel)
+    assert abs(got[0] - ref[0]) <= 1e-5 * abs(ref[0])
+    for a, b in zip(got[1], ref[1]):
+        check(a, b, 1e-4, float(np.max(np.abs(b))), "gradient")

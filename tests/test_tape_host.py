@@ -433,6 +433,25 @@ def test_double_backprop_leaves_no_reference_cycles(F):
         gc.enable()
 
 
+def test_a_function_made_of_two_user_kernels_differentiates(F):
+    from oracle import user_kernel as OU
+    fk = OU.ElementwiseKernel("T x, T y", "T z", "z = log(1 + exp(x)) * y", "softplus_times")
+    bk = OU.ElementwiseKernel("T x, T y, T gz", "T gx, T gy", "gx = gz * y / (1 + exp(-x)); gy = gz * log(1 + exp(x))", "softplus_times_bwd")
+    op = T.user_elementwise(fk, bk)
+    rng = np.random.default_rng(29)
+    x, y, Wm, t = rnd(rng, 4, 3), rnd(rng, 4, 3), rnd(rng, 3, 3), np.array([0, 2, 1, 1])
+
+    def loss(record=False):
+        vs = [T.Variable(x), T.Variable(y), T.Parameter(Wm)]
+        l = T.softmax_cross_entropy(T.matmul(op(vs[0], vs[1]), vs[2]), t)
+        return (l, vs) if record else float(l.array)
+
+    l, vs = loss(True)
+    l.backward()
+    for v, g in zip(vs, fd_grad(loss, [x, y, Wm])):
+        np.testing.assert_allclose(v.grad, g, rtol=1e-6, atol=1e-8)
+
+
 def test_adam_optimiser_keeps_state_per_parameter_and_counts_steps(F):
     rng = np.random.default_rng(13)
     Wm, b, x, t = rnd(rng, 3, 4), rnd(rng, 3), rnd(rng, 5, 4), np.array([0, 1, 2, 1, 0])
