@@ -926,7 +926,7 @@ class Transpose(FunctionNode):
 
 class UserElementwise(FunctionNode):
     """A differentiable element-wise operation written as two user-defined kernels (Section "Custom
-    CUDA Kernels": the array layer "is easy to extend with user-defined kernels"): `forward_kernel`
+    CUDA Kernels": users extend the array layer with kernels of their own): `forward_kernel`
     maps the inputs to one output, `backward_kernel` maps (inputs..., gy) to one gradient per
     input.  Both are kernel objects called with arrays (the binding's ElementwiseKernel, or
     anything with the same call signature); all operands share one shape.  Retains its inputs."""
