@@ -134,6 +134,42 @@ __device__ __forceinline__ void contract(floatx16 &acc, char *const (&stages)[NS
   }
 }
 
+// The same contraction with ONE barrier per chunk, for long contractions on few tiles (the backward
+// step).  A wave that has passed the barrier of chunk ch has finished reading chunk ch - 1, so the
+// stage of chunk ch - 1 can be refilled right behind that barrier and no second barrier is needed;
+// the price is one stage that is neither being read nor in flight, i.e. NS - 1 chunks of look-ahead.
+template <typename T, int NS, class RowA, class RowB>
+__device__ __forceinline__ void contract_long(floatx16 &acc, char *const (&stages)[NS], RowA row_a, RowB row_b, int64_t k_len, int wave, int lane) {
+  static_assert(NS == 4, "the wait immediates below are written for four stages");
+  constexpr int kSliceElems = 32 / (int)sizeof(T), kChunkElems = kRowBytes / (int)sizeof(T);
+  const int n_chunks = (int)((k_len + kChunkElems - 1) / kChunkElems);
+#pragma unroll
+  for (int k = 0; k < NS - 1; ++k)
+    if (k < n_chunks) copy_chunk<T>(stages[k], row_a, row_b, k_len, k, wave, lane);
+  auto step = [&](char *cur, char *refill, int ch) {
+    // issued so far: chunks 0 .. ch + NS - 2; those behind chunk ch may stay in flight
+    const int behind = n_chunks - 1 - ch < NS - 2 ? n_chunks - 1 - ch : NS - 2;
+    if (behind == 0) __builtin_amdgcn_s_waitcnt(0x0070);        // vmcnt(0) lgkmcnt(0)
+    else if (behind == 1) __builtin_amdgcn_s_waitcnt(0x0078);   // vmcnt(8) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0x4070);                    // vmcnt(16) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (ch + NS - 1 < n_chunks) copy_chunk<T>(refill, row_a, row_b, k_len, ch + NS - 1, wave, lane);
+    const int64_t left = k_len - (int64_t)ch * kChunkElems;
+    mma_chunk<T>(acc, cur, (int)((left < kChunkElems ? left : kChunkElems) / kSliceElems), wave, lane);
+  };
+  for (int ch = 0; ch < n_chunks; ch += NS) {
+#pragma unroll
+    for (int k = 0; k < NS; ++k)
+      if (ch + k < n_chunks) step(stages[k], stages[(k + NS - 1) % NS], ch + k);
+  }
+  __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): the last fragment reads have returned
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // Park this wave's partial tile in LDS as tile[wave][row][col]: lane (r, q) holds column r and the
 // rows 8 * (v / 4) + 4 * q + v % 4 of its 16 accumulators.
 __device__ __forceinline__ void park(float (*tile)[32][33], const floatx16 &acc, int wave, int lane) {
@@ -261,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void lstm_step_bwd_kernel(BwdArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
     char *const stages[4] = {stage0, stage1, stage2, stage3};
-    contract<T, 4>(acc, stages, row_a, row_b, 4 * a.H, wave, lane);
+    contract_long<T, 4>(acc, stages, row_a, row_b, 4 * a.H, wave, lane);
     park(tile, acc, wave, lane);
     __syncthreads();
   }
