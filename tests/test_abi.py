@@ -142,3 +142,48 @@ def test_gemm_plan_picks_the_direct_copy_kernel_only_where_it_applies():
     tile, dc, splits = plan(1000, 4096, 8192, B.BF16, a_t=True, b_t=False, ws=1)
     assert (tile, dc) == (2, True) and splits > 1                         # few tiles, long K: split
     assert plan(1000, 4096, 8192, B.BF16, a_t=True, b_t=False, ws=0)[2] == 1
+
+
+def test_later_entry_points_validate_on_the_host():
+    """Adam, arg-max and the fused recurrent step reject malformed calls before anything is launched."""
+    L = B.lib()
+    f = lambda shape, dt=B.F32, p=P, strides=None: B.raw_desc(
+        p, shape, strides or [int(s) for s in _row_major(shape, {B.F32: 4, B.BF16: 2, B.I32: 4, B.I64: 8}[dt])], dt)
+    r = C.byref
+    # Adam
+    p_, g_, m_, v_ = f((8, 8)), f((8, 8)), f((8, 8)), f((8, 8))
+    adam = lambda ps, gs, ms, vs, step, b1=0.9: L.chn_adam_update_multi(
+        len(ps), B._ptrs(ps), B._ptrs(gs), B._ptrs(ms), B._ptrs(vs), 0.001, b1, 0.999, 1e-8, step, None, None)
+    assert adam([p_], [g_], [m_], [f((8, 7))], 1) == -4                       # state of another shape
+    assert adam([p_], [g_], [m_], [v_], 0) == -6                              # steps count from 1
+    assert adam([p_], [g_], [m_], [v_], 1, b1=1.0) == -6                      # beta outside [0, 1)
+    assert adam([p_], [f((8, 8), B.BF16)], [m_], [v_], 1) == -3
+    assert adam([], [], [], [], 1) == 0
+    # arg-max
+    x = f((6, 10))
+    am = lambda a, axis, out, keep=0: L.chn_argmax_axis(r(a), axis, keep, r(out), None)
+    assert am(x, 1, f((6,), B.F32)) == -3                                     # indices are integers
+    assert am(x, 1, f((10,), B.I64)) == -4
+    assert am(x, 2, f((6,), B.I64)) == -7
+    assert am(f((6, 0)), 1, f((6,), B.I64)) == -4                             # nothing to choose from
+    assert am(f((0, 10)), 1, f((0,), B.I64)) == 0
+    # fused recurrent step
+    Bn, H = 4, 64
+    zx, hp, Ut, c = f((Bn, 4 * H)), f((Bn, H)), f((4 * H, H)), f((Bn, H))
+    fwd = lambda zx, hp, Ut, c_prev, c, h: L.chn_lstm_step_fwd(r(zx), r(hp), r(Ut), None, r(c_prev), r(c), r(h), None, None)
+    assert fwd(zx, hp, f((H, 4 * H)), c, c, hp) == -4                         # U instead of its transpose
+    assert fwd(zx, f((Bn, H), B.BF16), Ut, c, c, hp) == -3                    # operands of two dtypes
+    assert fwd(zx, f((Bn, H), p=P + 4), Ut, c, c, hp) == -5                   # rows off the 16-byte grid
+    assert fwd(f((Bn, 160)), f((Bn, 40)), f((160, 40)), f((Bn, 40)), f((Bn, 40)), f((Bn, 40))) == -4   # H not a multiple of 32
+    assert b"multiple of 32" in L.chn_last_error()
+    bwd = lambda dzn, U, dh, dz: L.chn_lstm_step_bwd(r(dzn), r(U), r(dh), r(zx), r(c), r(c), None, r(dz), r(c), None)
+    assert bwd(zx, f((H, 4 * H)), hp, f((Bn, 4 * H), B.BF16)) == -3           # dz must have dh's dtype
+    assert bwd(zx, f((4 * H, H)), hp, zx) == -4                               # the transpose where U is expected
+
+
+def _row_major(shape, isz):
+    out, acc = [], isz
+    for n in reversed(shape):
+        out.insert(0, acc)
+        acc *= max(n, 1)
+    return out
