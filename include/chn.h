@@ -311,7 +311,8 @@ chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_
  * chn_*_kernel_prepare compiles (or fetches) the specialisation a call with these descriptors
  * would use without loading or launching it -- it needs no GPU once an architecture is configured.
  * chn_user_kernel_config: `cache_dir` (default $CHN_KERNEL_CACHE_DIR, else ~/.cache/libchn/kernels)
- * and `arch` (default: the current device's, e.g. "gfx950"); NULL keeps a setting.  Cache files are
+ * and `arch` (default: the current device's, e.g. "gfx950"); NULL keeps a setting, "" restores the
+ * default.  Cache files are
  * named by a digest of the generated source, the architecture, the compiler version and the library
  * version, and written atomically; an unwritable cache is not an error.
  * Errors: CHN_ERR_OP (malformed declaration, wrong argument count), CHN_ERR_DTYPE (array dtype

@@ -1112,8 +1112,8 @@ extern "C" {
 
 chn_status chn_user_kernel_config(const char *cache_dir, const char *arch) {
   std::lock_guard<std::mutex> l(g_mu);
-  if (cache_dir) g_cache_dir = cache_dir;
-  if (arch) g_arch = arch;
+  if (cache_dir) g_cache_dir = cache_dir;     // "" = back to the default
+  if (arch) g_arch = arch;                    // "" = back to asking the current device
   return CHN_OK;
 }
 
