@@ -3,9 +3,9 @@
 //
 // Forward: one wave copies one row (bit-exact), 16-byte chunks when the rows are aligned.
 // Backward is written as a gather so that it needs no atomics and no workspace and is
-// bit-reproducible: one block owns one table row v, scans the id list 256 ids at a time (wave
-// ballots give each wave's matches as a bit mask), and adds the matching rows of dout in increasing
-// token order.  Rows nobody referenced are written as zeros (or left alone when accumulating).
+// bit-reproducible: one block owns eight neighbouring table rows, scans the id list 256 ids at a time
+// (wave ballots give each wave's matches as a bit mask), and adds the matching rows of dout to the
+// table row they belong to in increasing token order.  Rows nobody referenced are written as zeros (or left alone when accumulating).
 #include "common.h"
 
 namespace chn {
@@ -31,42 +31,62 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const T *table, int64_t 
 }
 
 constexpr int kColsPerThread = 4;
+constexpr int kRowsPerBlock = 8;     // table rows one block owns: the id list is scanned once for all of them
 
 template <typename L>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const L *ids, int64_t N, const float *dout, int64_t dpitch, int64_t D,
-                                                        float *dtable, int64_t tpitch, int accumulate) {
+                                                        float *dtable, int64_t tpitch, int64_t V, int accumulate) {
   __shared__ unsigned long long masks[4];
-  const int64_t v = blockIdx.x;
+  __shared__ unsigned char which[256];           // for a matching token: which of the block's rows
+  const int64_t v0 = (int64_t)blockIdx.x * kRowsPerBlock;
   const int64_t col0 = (int64_t)blockIdx.y * (256 * kColsPerThread) + threadIdx.x;
-  float acc[kColsPerThread] = {0.0f, 0.0f, 0.0f, 0.0f};
+  float acc[kRowsPerBlock][kColsPerThread];
+#pragma unroll
+  for (int r = 0; r < kRowsPerBlock; ++r)
+#pragma unroll
+    for (int k = 0; k < kColsPerThread; ++k) acc[r][k] = 0.0f;
   for (int64_t base = 0; base < N; base += 256) {
     const int64_t n = base + threadIdx.x;
-    const bool hit = n < N && (int64_t)ids[n] == v;
+    const int64_t d = n < N ? (int64_t)ids[n] - v0 : -1;
+    const bool hit = d >= 0 && d < kRowsPerBlock;
     const unsigned long long m = __ballot(hit);
     if ((threadIdx.x & 63) == 0) masks[threadIdx.x >> 6] = m;
+    which[threadIdx.x] = (unsigned char)(hit ? d : 0);
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       unsigned long long mm = masks[w];
-      while (mm) {
+      while (mm) {                                // matches in increasing token order
         const int b = __ffsll((long long)mm) - 1;
         mm &= mm - 1;
         const float *row = dout + (base + w * 64 + b) * dpitch;
+        float x[kColsPerThread];
 #pragma unroll
         for (int k = 0; k < kColsPerThread; ++k) {
           const int64_t c = col0 + (int64_t)k * 256;
-          if (c < D) acc[k] += row[c];
+          x[k] = c < D ? row[c] : 0.0f;
         }
+        const int r_hit = which[w * 64 + b];      // uniform over the block
+#pragma unroll
+        for (int r = 0; r < kRowsPerBlock; ++r)
+          if (r == r_hit) {
+#pragma unroll
+            for (int k = 0; k < kColsPerThread; ++k) acc[r][k] += x[k];
+          }
       }
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int k = 0; k < kColsPerThread; ++k) {
-    const int64_t c = col0 + (int64_t)k * 256;
-    if (c < D) {
-      float *q = dtable + v * tpitch + c;
-      *q = accumulate ? *q + acc[k] : acc[k];
+  for (int r = 0; r < kRowsPerBlock; ++r) {
+    if (v0 + r >= V) break;
+#pragma unroll
+    for (int k = 0; k < kColsPerThread; ++k) {
+      const int64_t c = col0 + (int64_t)k * 256;
+      if (c < D) {
+        float *q = dtable + (v0 + r) * tpitch + c;
+        *q = accumulate ? *q + acc[r][k] : acc[r][k];
+      }
     }
   }
 }
@@ -129,15 +149,15 @@ chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_
   if (dn != N || dd != D) return fail(CHN_ERR_SHAPE, "embed: dout must have shape (%lld,%lld)", (long long)N, (long long)D);
   if (V == 0 || D == 0) return CHN_OK;
   if (V > 0x7fffffff) return fail(CHN_ERR_SHAPE, "embed: table too large");
-  dim3 grid((unsigned)V, (unsigned)((D + 256 * kColsPerThread - 1) / (256 * kColsPerThread)));
+  dim3 grid((unsigned)((V + kRowsPerBlock - 1) / kRowsPerBlock), (unsigned)((D + 256 * kColsPerThread - 1) / (256 * kColsPerThread)));
   if (grid.y > 65535) return fail(CHN_ERR_SHAPE, "embed: rows too wide");
   hipStream_t st = as_stream(stream);
   if (ids->dtype == CHN_I32)
     hipLaunchKernelGGL((embed_bwd_kernel<int32_t>), grid, dim3(256), 0, st, static_cast<const int32_t *>(ids->data), N,
-                       static_cast<const float *>(dout->data), dp, D, static_cast<float *>(dtable->data), tp, accumulate);
+                       static_cast<const float *>(dout->data), dp, D, static_cast<float *>(dtable->data), tp, V, accumulate);
   else
     hipLaunchKernelGGL((embed_bwd_kernel<int64_t>), grid, dim3(256), 0, st, static_cast<const int64_t *>(ids->data), N,
-                       static_cast<const float *>(dout->data), dp, D, static_cast<float *>(dtable->data), tp, accumulate);
+                       static_cast<const float *>(dout->data), dp, D, static_cast<float *>(dtable->data), tp, V, accumulate);
   return check_launch("embed_bwd");
 }
 
