@@ -277,8 +277,9 @@ __device__ __forceinline__ void sched_reads_mfma() {
 // ---- epilogue helpers ------------------------------------------------------------------------------
 // Two paths.  The fast one handles whole 4-column groups with aligned vector accesses only (the host
 // sets epi_vec when every pointer and leading dimension allows it) and keeps its code small because
-// it is replicated for every row segment a lane owns; everything else (ragged right edge, unaligned
-// views) goes through a rolled element-by-element loop.
+// it is replicated for every row segment a lane owns; a pass that crosses the last row or column of
+// aligned operands runs a rolled loop over the 4-column groups that lie in range, and unaligned views
+// go through a rolled element-by-element loop.
 struct Vec4 { float v[4]; };
 
 __device__ __forceinline__ Vec4 load4v(const void *p, int64_t idx, int is_bf16) {
@@ -519,7 +520,20 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
       case CHN_EPI_GELU_BWD: run(std::integral_constant<int, CHN_EPI_GELU_BWD>{}); break;
       default: run(std::integral_constant<int, CHN_EPI_BF16_COPY>{}); break;
     }
-  } else {                                                    // ragged right edge or unaligned views: one element at a time
+  } else if (g.epi_vec) {                                     // edge tile of aligned operands: whole 4-column groups that lie in range
+    // (the lanes are dealt out over the groups that exist, so the number of dependent iterations
+    // follows the part of the pass that is in range)
+    const int nr = max(0, min(RP, g.M - row0)), ncg = max(0, min(CPR, (g.N - col0 + 3) >> 2));   // (a pass may lie wholly outside)
+#pragma unroll 1
+    for (int c = lane; c < nr * ncg; c += 64) {
+      const int rl = c / ncg, cl = (c - rl * ncg) * 4, row = row0 + rl, col = col0 + cl;
+      if (col + 4 <= g.N) {
+        finish4(g, row, col, *reinterpret_cast<const f32x4 *>(stage + L::at(rl, cl)), epi_fetch(g, row, col));
+      } else {
+        for (int e = 0; col + e < g.N; ++e) finish1(g, row, col + e, stage[L::at(rl, cl + e)]);
+      }
+    }
+  } else {                                                    // unaligned views: one element at a time
 #pragma unroll 1
     for (int c = lane; c < RP * W; c += 64) {
       const int rl = c / W, cl = c % W;
