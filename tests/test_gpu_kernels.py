@@ -212,6 +212,55 @@ def test_reduce_nd_keepdims_bf16_out_empty_and_deterministic():
     assert abs(s0 - s1) <= 1e-4 * np.abs(big).sum()
 
 
+@pytest.mark.parametrize("dt,shape", [("f32", (1500, 2048)), ("f32", (2, 1100, 2052)), ("bf16", (3000, 4104)), ("bf16", (1027, 8192))])
+def test_reduce_wide_columns_ignore_what_the_workspace_held(dt, shape):
+    """Wide column reductions leave partial sums in the caller's workspace.  Its previous contents
+    (random bytes, all ones, the leftovers of a call of another shape or of the same call) must not
+    matter, the bits must not change from call to call, and a recorded launch must replay them."""
+    x = rnd(shape, dt)
+    d = dev(x, dt)
+    axis = len(shape) - 2
+    need = B.reduce_axis_workspace_bytes(d, axis)
+    assert need > 0
+    ref = O.reduce_axis("sum", x, axis)
+    scale = O.reduce_axis("sum", np.abs(x), axis)
+    tol = tol_for(dt, "f32", TOL_SUM)
+    y = dev(rnd((1100, 2048)))
+    w = ws(max(need, B.reduce_axis_workspace_bytes(y, 0)) + 4096)
+    results = []
+    for fill in ("random", "ones", "other", "same", "same"):
+        if fill == "random":
+            w.copy_(torch.from_numpy(RNG.integers(0, 256, size=w.numel(), dtype=np.uint8)))
+        elif fill == "ones":
+            w.fill_(255)
+        elif fill == "other":
+            B.reduce_axis("sum", y, 0, empty((2048,)), ws=w)
+        out = B.reduce_axis("sum", d, axis, empty(ref.shape), ws=w)
+        check(host(out), ref, tol, scale, "workspace " + fill)
+        results.append(out)
+    for r in results[1:]:
+        assert torch.equal(r, results[0])        # fixed summation order
+    got, refm = _reduce("max", x, d, axis)
+    assert np.array_equal(got, refm)
+    g = torch.cuda.CUDAGraph()
+    out = empty(ref.shape)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        B.reduce_axis("sum", d, axis, out, ws=w)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            B.reduce_axis("sum", d, axis, out, ws=w)
+    for _ in range(3):
+        out.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, results[0])
+        eager = B.reduce_axis("sum", d, axis, empty(ref.shape), ws=w)
+        torch.cuda.synchronize()
+        assert torch.equal(eager, results[0])
+
+
 # ------------------------------------------------------------------------------------ softmax CE
 @pytest.mark.parametrize("N,Cn,dt,lab", [(37, 10, "f32", np.int32), (300, 1000, "f32", np.int64), (70, 4100, "f32", np.int32),
                                          (129, 1000, "bf16", np.int32), (33, 2051, "bf16", np.int64), (5, 33, "f32", np.int32)])
