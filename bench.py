@@ -241,20 +241,25 @@ def bench_tape(torch, W, timer, quick):
     res["cfg3_mlp_bf16"] = mlp(W.config3(), True, 100, 10)
     res["cfg1_tiny_mlp_f32"] = mlp(W.config1(), False, 200, 20)
     w = W.config4()
-    model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()})
-    opt = T.SGD(model.params(), w.lr)
     ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
-    last = [None]
+    # step by step (a product, a sum and a cell node per time step), the recurrent layer as one node,
+    # and that with the hidden width rounded up to 672 by inert units (the width the fused step takes)
+    for name, params, n_step in (("cfg4_lstm_lm_f32", w.params, False), ("cfg4_lstm_lm_f32_n_step", w.params, True),
+                                 ("cfg4_lstm_lm_f32_n_step_padded", W.pad_lstm_params(w.params), True)):
+        model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in params.items()}, n_step=n_step)
+        opt = T.SGD(model.params(), w.lr)
+        last = [None]
 
-    def fn():
-        opt.cleargrads()
-        loss, _ = model.loss(ids, tg, w.bptt)
-        loss.backward()
-        opt.update()
-        last[0] = loss.array
-    s = timer.time(fn, 10, 2)
-    res["cfg4_lstm_lm_f32"] = {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s,
-                               "loss": float(last[0].cpu())}
+        def fn():
+            opt.cleargrads()
+            loss, _ = model.loss(ids, tg, w.bptt)
+            loss.backward()
+            opt.update()
+            last[0] = loss.array
+        s = timer.time(fn, 10, 2)
+        res[name] = {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s,
+                     "loss": float(last[0].cpu())}
+        del model, opt
     return res
 
 

@@ -87,6 +87,13 @@ class GpuBackend:
     def lstm_bwd(self, gates, c_prev, c, dh, dc_next, dz, dc_prev):
         self.B.lstm_bwd(gates, c_prev, c, dh, dc_next, dz, dc_prev)
 
+    def fuses_lstm_step(self, hidden):
+        """Whether lstm_step_fwd (recurrent product and cell in one launch) takes this hidden width."""
+        return hidden % 32 == 0
+
+    def lstm_step_fwd(self, zx, h_prev, Ut, bias, c_prev, c, h, gates):
+        self.B.lstm_step_fwd(zx, h_prev, Ut, bias, c_prev, c, h, gates)
+
     def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
         ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
         self.B.softmax_ce_fwd(logits, labels, loss_mean, None, lse, ignore_label, ws)
@@ -1067,6 +1074,96 @@ class LSTM(FunctionNode):
         return tuple(out)
 
 
+class NStepLSTM(FunctionNode):
+    """(c0, h0, zx, U, bias) -> (c_T, h_T, hs): all time steps of one LSTM layer in one function node.
+
+    zx (T*B, 4H) holds the input part of the gate pre-activations of every step (time-major: rows
+    t*B .. t*B + B - 1 belong to step t), U (H, 4H) the recurrent weights; hs (T*B, H) stacks the
+    hidden states h_1 .. h_T the same way.  Step by step the tape would record a product, a sum and
+    a cell per time step and, backwards, add T small weight-gradient products into U's gradient;
+    here the forward is one launch per step where the backend fuses product and cell (two
+    otherwise), and the backward computes U's gradient as one product over all steps once every
+    step's gate gradient is known.  The arithmetic per element is that of the step-by-step graph;
+    sums over time are taken in a different order."""
+    fresh = (0, 1, 2, 3, 4)
+
+    def __init__(self, n_steps):
+        super().__init__()
+        self.T = int(n_steps)
+
+    def forward(self, xs):
+        F = backend()
+        c0, h0, zx, U, bias = xs
+        T, Bn, H = self.T, c0.shape[0], c0.shape[1]
+        if tuple(zx.shape) != (T * Bn, 4 * H) or tuple(U.shape) != (H, 4 * H) or tuple(h0.shape) != (Bn, H):
+            raise ValueError("n_step_lstm: zx %s, U %s, c0 %s, h0 %s do not fit %d steps"
+                             % (tuple(zx.shape), tuple(U.shape), tuple(c0.shape), tuple(h0.shape), T))
+        blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
+        Hs, Cs = F.empty(((T + 1) * Bn, H), "f32"), F.empty(((T + 1) * Bn, H), "f32")   # block 0 = initial state
+        F.elementwise_broadcast("copy", [h0], blk(Hs, 0))
+        F.elementwise_broadcast("copy", [c0], blk(Cs, 0))
+        G = F.empty((T * Bn, 4 * H), "f32")
+        if F.fuses_lstm_step(H):
+            Ut = F.empty((4 * H, H), "f32")
+            F.elementwise_broadcast("copy", [_t(U)], Ut)
+            for t in range(T):
+                F.lstm_step_fwd(blk(zx, t), blk(Hs, t), Ut, bias, blk(Cs, t), blk(Cs, t + 1), blk(Hs, t + 1), blk(G, t))
+        else:
+            F.elementwise_broadcast("copy", [zx], G)                 # the pre-activations are completed in place
+            for t in range(T):
+                F.gemm(blk(Hs, t), U, blk(G, t), beta=1.0)
+                F.lstm_fwd(blk(G, t), bias, blk(Cs, t), blk(Cs, t + 1), blk(Hs, t + 1), blk(G, t))
+        self.Hs, self.Cs, self.G = Hs, Cs, G
+        self.retain_inputs((3,))
+        return (blk(Cs, T), blk(Hs, T), Hs[Bn:])
+
+    def release_locals(self):
+        self.Hs = self.Cs = self.G = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        U, = self.get_retained_inputs()
+        Hs, Cs, G, T = self.Hs, self.Cs, self.G, self.T
+        Bn, H = Hs.shape[0] // (T + 1), Hs.shape[1]
+        blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
+        gc, gh, ghs = gys
+        dHs = F.empty((T * Bn, H), "f32")                            # gradient reaching h_1 .. h_T from outside
+        if ghs is None:
+            F.elementwise_broadcast("fill", [], dHs, (0.0,))
+        else:
+            F.elementwise_broadcast("copy", [ghs], dHs)
+        if gh is not None:
+            F.elementwise_broadcast("add", [blk(dHs, T - 1), gh], blk(dHs, T - 1))
+        dZ = F.empty((T * Bn, 4 * H), "f32")
+        dc = [F.empty((Bn, H), "f32"), F.empty((Bn, H), "f32")]
+        dh0 = F.empty((Bn, H), "f32")
+        dc_next = gc
+        for t in range(T - 1, -1, -1):
+            F.lstm_bwd(blk(G, t), blk(Cs, t), blk(Cs, t + 1), blk(dHs, t), dc_next, blk(dZ, t), dc[t & 1])
+            dc_next = dc[t & 1]
+            if t > 0:
+                F.gemm(blk(dZ, t), _t(U), blk(dHs, t - 1), beta=1.0)
+            elif 1 in indexes:
+                F.gemm(blk(dZ, 0), _t(U), dh0)
+        out = []
+        for i in indexes:
+            if i == 0:
+                out.append(dc[0])
+            elif i == 1:
+                out.append(dh0)
+            elif i == 2:
+                out.append(dZ)
+            elif i == 3:
+                gU = F.empty(tuple(U.shape), "f32")
+                F.gemm(_t(Hs[:T * Bn]), dZ, gU)
+                out.append(gU)
+            else:
+                gb = F.empty((4 * H,), "f32")
+                F.reduce_axis("sum", dZ, 0, gb)
+                out.append(gb)
+        return tuple(out)
+
+
 class SplitRows(FunctionNode):
     """Cut a (n*r, d) array into n views of r rows (no copy; the views keep the buffer alive).
     The backward gathers the pieces' gradients into one array, zero where a piece was unused."""
@@ -1188,6 +1285,11 @@ def lstm(c_prev, z, bias=None):
     return LSTM().apply((c_prev, z) if bias is None else (c_prev, z, bias))
 
 
+def n_step_lstm(c0, h0, zx, U, bias, n_steps):
+    """All n_steps time steps of an LSTM layer; returns (c_T, h_T, hs) with hs (n_steps*B, H)."""
+    return NStepLSTM(n_steps).apply((c0, h0, zx, U, bias))
+
+
 def split_rows(x, n):
     return SplitRows(n).apply((x,))
 
@@ -1300,10 +1402,12 @@ class LSTMLanguageModel:
     """Embedding, one LSTM layer, output Linear layer, softmax cross-entropy over every (time,
     batch) token; time-major rows (row t*B + b).  ``P``: dict of backend arrays E (V,E), W (E,4H),
     U (H,4H), b (4H,), W_out (V,H), b_out (V,).  The forward code is ordinary Python: the number of
-    time steps is whatever the batch at hand has."""
+    time steps is whatever the batch at hand has.  ``n_step``: the recurrent layer is one
+    ``n_step_lstm`` node instead of a product, a sum and a cell per time step."""
 
-    def __init__(self, P):
+    def __init__(self, P, n_step=False):
         self.P = {k: Parameter(v, None, k) for k, v in P.items()}
+        self.n_step = n_step
 
     def params(self):
         return list(self.P.values())
@@ -1313,7 +1417,7 @@ class LSTMLanguageModel:
         carry the state into the next window (after ``unchain`` for truncated back-propagation)."""
         P, F = self.P, backend()
         X = embed_id(ids, P["E"])
-        zs = split_rows(matmul(X, P["W"]), n_steps)
+        zx = matmul(X, P["W"])
         if state is None:
             Bn, H = ids.shape[0] // n_steps, P["U"].shape[0]
             z0 = F.empty((Bn, H), "f32")
@@ -1321,6 +1425,11 @@ class LSTMLanguageModel:
             c = h = Variable(z0, requires_grad=False)
         else:
             c, h = state
+        if self.n_step:
+            c, h, hs = n_step_lstm(c, h, zx, P["U"], P["b"], n_steps)
+            logits = linear(hs, P["W_out"], P["b_out"])
+            return softmax_cross_entropy(logits, targets), (c, h)
+        zs = split_rows(zx, n_steps)
         hs = []
         for t in range(n_steps):
             c, h = lstm(c, add(zs[t], matmul(h, P["U"])), P["b"])

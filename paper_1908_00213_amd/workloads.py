@@ -157,3 +157,24 @@ def config4(seed=None, vocab=10000, embed=650, hidden=650, batch=128, bptt=35, l
     }
     name = "cfg4_lstm_lm_v%d_e%d_h%d_b%d_t%d" % (vocab, embed, hidden, batch, bptt)
     return LSTMWorkload(name, vocab, embed, hidden, batch, bptt, lr, ids, targets, P)
+
+
+def pad_lstm_params(P, multiple=32):
+    """The language model's parameters embedded in zero arrays whose embedding and hidden widths are
+    rounded up to a multiple of `multiple` (gate blocks of W, U and b stay gate blocks, now of the
+    rounded width).  The added embedding columns and hidden units are inert: with zero weights and
+    biases their cell state and hidden state stay zero and nothing real depends on them, so the loss
+    and the gradients of the real entries are those of the unpadded model."""
+    V, E = P["E"].shape
+    H = P["U"].shape[0]
+    up = lambda n: (n + multiple - 1) // multiple * multiple
+    Ep, Hp = up(E), up(H)
+    out = {"E": np.zeros((V, Ep), np.float32), "W": np.zeros((Ep, 4, Hp), np.float32), "U": np.zeros((Hp, 4, Hp), np.float32),
+           "b": np.zeros((4, Hp), np.float32), "W_out": np.zeros((V, Hp), np.float32), "b_out": P["b_out"].astype(np.float32)}
+    out["E"][:, :E] = P["E"]
+    out["W"][:E, :, :H] = P["W"].reshape(E, 4, H)
+    out["U"][:H, :, :H] = P["U"].reshape(H, 4, H)
+    out["b"][:, :H] = P["b"].reshape(4, H)
+    out["W_out"][:, :H] = P["W_out"]
+    out["W"], out["U"], out["b"] = out["W"].reshape(Ep, 4 * Hp), out["U"].reshape(Hp, 4 * Hp), out["b"].reshape(4 * Hp)
+    return out

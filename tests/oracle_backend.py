@@ -59,6 +59,16 @@ class OracleBackend:
         self.calls.append(("lstm_fwd", None))
         c[...], h[...], gates[...] = O.lstm_fwd(z, bias, c_prev)
 
+    fuse_lstm_step = False                    # tests switch it on to walk the fused-step code path
+
+    def fuses_lstm_step(self, hidden):
+        return self.fuse_lstm_step
+
+    def lstm_step_fwd(self, zx, h_prev, Ut, bias, c_prev, c, h, gates):
+        self.calls.append(("lstm_step_fwd", None))
+        z = O.gemm(h_prev, Ut.T, zx, 1.0, 1.0)
+        c[...], h[...], gates[...] = O.lstm_fwd(z, bias, c_prev)
+
     def lstm_bwd(self, gates, c_prev, c, dh, dc_next, dz, dc_prev):
         self.calls.append(("lstm_bwd", None))
         dz[...], dc_prev[...] = O.lstm_bwd(gates, c_prev, c, dh, dc_next)

@@ -110,6 +110,60 @@ def test_tape_lstm_language_model_step_matches_the_oracle(cfg):
     assert T.live_function_nodes() == 0
 
 
+@pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=96, batch=16, bptt=6),      # width the fused step takes
+                                 dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])   # product and cell apart
+def test_tape_n_step_lstm_matches_the_oracle_and_carries_state(cfg):
+    """The whole recurrent layer as one function node: the step against the oracle's, then two windows
+    with the state carried over against the step-by-step graph on the CPU oracle backend."""
+    F = T.backend()
+    w = W.config4(**cfg)
+    w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()}, n_step=True)
+    ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
+    loss, _ = model.loss(ids, tg, w.bptt)
+    assert T.live_function_nodes() == 5
+    loss.backward()
+    r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr))
+    assert abs(float(loss.array.cpu()) - r["loss"]) <= 1e-4 * abs(r["loss"])
+    for k in w.params:
+        cmp(model.P[k].grad, r["grads"][k], 1e-4, "d" + k)
+    assert T.live_function_nodes() == 0
+
+    # widths rounded up by inert units (what lets a width like 130 use the fused step): same numbers
+    padded = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in W.pad_lstm_params(w.params).items()}, n_step=True)
+    lp, _ = padded.loss(ids, tg, w.bptt)
+    lp.backward()
+    assert abs(float(lp.array.cpu()) - r["loss"]) <= 1e-4 * abs(r["loss"])
+    Hp = padded.P["U"].array.shape[0]
+    gU = host(padded.P["U"].grad).reshape(Hp, 4, Hp)[:w.hidden, :, :w.hidden].reshape(w.hidden, 4 * w.hidden)
+    check(gU, r["grads"]["U"], 1e-4, float(np.max(np.abs(r["grads"]["U"]))), "dU of the padded model")
+
+    idn, tgn = w.ids.reshape(-1).astype(np.int64), w.targets.reshape(-1).astype(np.int64)
+    Bn, cut = w.batch, w.bptt // 2
+
+    def two_windows(Fb, n_step):
+        m = T.LSTMLanguageModel({k: Fb.from_numpy(v) for k, v in w.params.items()}, n_step=n_step)
+        out, state = [], None
+        for lo, hi in ((0, cut), (cut, w.bptt)):
+            for p in m.params():
+                p.cleargrad()
+            sl = slice(lo * Bn, hi * Bn)
+            l, state = m.loss(Fb.from_numpy(idn[sl]), Fb.from_numpy(tgn[sl]), hi - lo, state)
+            l.backward()
+            for v in state:
+                v.unchain()
+            out.append((float(Fb.to_numpy(l.array)), {k: Fb.to_numpy(p.grad) for k, p in m.P.items()}))
+        return out
+
+    got = two_windows(F, True)
+    with T.using_backend(OracleBackend()) as Fo:
+        ref = two_windows(Fo, False)
+    for (lg, gg), (lr_, gr) in zip(got, ref):
+        assert abs(lg - lr_) <= 1e-4 * abs(lr_)
+        for k in gr:
+            check(gg[k], gr[k], 1e-4, float(np.max(np.abs(gr[k]))), "d" + k)
+
+
 def test_tape_window_length_changes_and_state_is_carried_across_windows():
     # truncated back-propagation over two windows of different length: the second starts from the
     # first one's final state, cut from its history.  Reference: the same tape on the CPU with the

@@ -114,6 +114,95 @@ def test_lstm_language_model_matches_finite_differences_and_oracle_step(F):
         np.testing.assert_allclose(P[k], ref["params"][k], rtol=1e-12, atol=1e-14)
 
 
+@pytest.mark.parametrize("fuse", [False, True])
+def test_n_step_lstm_equals_the_oracle_step_and_the_step_by_step_graph(F, fuse):
+    """One function node for all time steps: same loss and gradients as the hand-ordered oracle step
+    and as the graph of per-step nodes, with far fewer nodes; both forward code paths (one call per
+    step where the backend fuses product and cell, two otherwise)."""
+    F.fuse_lstm_step = fuse
+    w = W.config4(seed=7, vocab=13, embed=3, hidden=4, batch=2, bptt=4)
+    P = {k: v.astype(np.float64) for k, v in w.params.items()}
+    P["b"] = np.random.default_rng(4).standard_normal(P["b"].shape) * 0.1
+    ids, tg = w.ids.reshape(-1).astype(np.int64), w.targets.reshape(-1).astype(np.int64)
+    ref = OS.lstm_lm_step(P, w.ids, w.targets, 0.1)
+
+    model = T.LSTMLanguageModel({k: v.copy() for k, v in P.items()}, n_step=True)
+    F.calls.clear()
+    loss, (c, h) = model.loss(ids, tg, w.bptt)
+    fwd_calls = [n for n, _ in F.calls]
+    assert ("lstm_step_fwd" in fwd_calls) == fuse and fwd_calls.count("lstm_step_fwd" if fuse else "lstm_fwd") == w.bptt
+    assert T.live_function_nodes() == 5               # embedding, input product, recurrent layer, output layer, loss
+    loss.backward()
+    assert float(loss.array) == pytest.approx(ref["loss"], rel=1e-13)
+    for k, p in model.P.items():
+        np.testing.assert_allclose(p.grad, ref["grads"][k], rtol=1e-10, atol=1e-13, err_msg=k)
+    assert not T.live_function_nodes()
+
+    stepwise = T.LSTMLanguageModel({k: v.copy() for k, v in P.items()})
+    l2, (c2, h2) = stepwise.loss(ids, tg, w.bptt)
+    l2.backward()
+    np.testing.assert_allclose(c.array, c2.array, rtol=1e-13)
+    np.testing.assert_allclose(h.array, h2.array, rtol=1e-13)
+    for k in P:
+        np.testing.assert_allclose(model.P[k].grad, stepwise.P[k].grad, rtol=1e-10, atol=1e-13, err_msg=k)
+
+
+def test_padded_lstm_parameters_are_inert():
+    """Rounding the widths up with zero weights changes neither the loss nor the gradients of the real
+    entries, and the added entries get zero gradients (checked on the hand-ordered oracle step)."""
+    w = W.config4(seed=9, vocab=17, embed=5, hidden=6, batch=3, bptt=4)
+    w.params["b"] = (np.random.default_rng(5).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    Pp = W.pad_lstm_params(w.params, multiple=8)
+    assert Pp["U"].shape == (8, 32) and Pp["W"].shape == (8, 32) and Pp["E"].shape == (17, 8)
+    a = OS.lstm_lm_step(w.params, w.ids, w.targets, 0.1)
+    b = OS.lstm_lm_step(Pp, w.ids, w.targets, 0.1)
+    assert b["loss"] == pytest.approx(a["loss"], rel=1e-13)
+    E, H = 5, 6
+    real = {"E": lambda g: g[:, :E], "W": lambda g: g.reshape(8, 4, 8)[:E, :, :H].reshape(E, 4 * H),
+            "U": lambda g: g.reshape(8, 4, 8)[:H, :, :H].reshape(H, 4 * H), "b": lambda g: g.reshape(4, 8)[:, :H].reshape(4 * H),
+            "W_out": lambda g: g[:, :H], "b_out": lambda g: g}
+    for k in a["grads"]:
+        np.testing.assert_allclose(real[k](b["grads"][k]), a["grads"][k], rtol=1e-12, atol=1e-15, err_msg=k)
+        assert abs(b["grads"][k]).sum() == pytest.approx(abs(a["grads"][k]).sum(), rel=1e-12)   # nothing outside
+
+
+def test_n_step_lstm_gradients_of_state_and_every_output_by_finite_differences(F):
+    """All three outputs used, a non-zero initial state that needs gradients, and a second consumer of
+    the stacked hidden states: checked against central differences of the forward value."""
+    rng = np.random.default_rng(21)
+    Tn, Bn, H = 3, 2, 3
+    c0, h0 = rng.standard_normal((Bn, H)) * 0.5, rng.standard_normal((Bn, H)) * 0.5
+    zx, U, b = rng.standard_normal((Tn * Bn, 4 * H)), rng.standard_normal((H, 4 * H)) * 0.4, rng.standard_normal(4 * H) * 0.1
+    wc, wh, ws = rng.standard_normal((Bn, H)), rng.standard_normal((Bn, H)), rng.standard_normal((Tn * Bn, H))
+
+    def value(vs):
+        c, h, hs = T.n_step_lstm(*vs, Tn)
+        return T.add(T.add(T.sum_all(T.mul(c, T.Variable(wc, requires_grad=False))),
+                           T.sum_all(T.mul(h, T.Variable(wh, requires_grad=False)))),
+                     T.add(T.sum_all(T.mul(hs, T.Variable(ws, requires_grad=False))), T.sum_all(T.mul(hs, hs))))
+
+    vs = [T.Variable(a) for a in (c0, h0, zx, U, b)]
+    value(vs).backward()
+
+    def f():
+        with T.no_backprop_mode():
+            return float(value([T.Variable(a) for a in (c0, h0, zx, U, b)]).array)
+
+    for v, g, name in zip(vs, fd_grad(f, [c0, h0, zx, U, b]), ("c0", "h0", "zx", "U", "b")):
+        np.testing.assert_allclose(v.grad, g, rtol=2e-6, atol=1e-8, err_msg=name)
+    # only the last hidden state used: the other two gradients arrive as None
+    vs = [T.Variable(a) for a in (c0, h0, zx, U, b)]
+    T.sum_all(T.mul(T.n_step_lstm(*vs, Tn)[1], T.Variable(wh, requires_grad=False))).backward()
+
+    def f2():
+        with T.no_backprop_mode():
+            return float(T.sum_all(T.mul(T.n_step_lstm(*[T.Variable(a) for a in (c0, h0, zx, U, b)], Tn)[1],
+                                         T.Variable(wh, requires_grad=False))).array)
+
+    for v, g, name in zip(vs, fd_grad(f2, [c0, h0, zx, U, b]), ("c0", "h0", "zx", "U", "b")):
+        np.testing.assert_allclose(v.grad, g, rtol=2e-6, atol=1e-8, err_msg=name)
+
+
 @pytest.mark.parametrize("act,fused", [("relu", True), ("relu", False), ("gelu", True), ("gelu", False)])
 def test_mlp_step_equals_the_hand_ordered_oracle_step(F, act, fused):
     w = W.make_mlp("t", (7, 6, 5, 4), 9, act, seed=11)
