@@ -161,19 +161,22 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
 // classical five-term rational approximation of erf (Abramowitz & Stegun 7.1.26, absolute error
 // below 1.5e-7), whose exp(-x^2/2) factor is shared with the density phi(x); for x < 0 the form
 // 0.5 * poly * exp(-x^2/2) involves no cancellation.  One hardware exp and one hardware reciprocal.
-struct PhiParts { float Phi, e; };   // e = exp(-x^2 / 2)
+// Written so that few instructions depend on each other and none is spent on what algebra removes:
+// constants are folded into the arguments of the reciprocal and the exponential and into the
+// polynomial, and gelu(x) = x * Phi(x) = max(x, 0) - |x| * Phi(-|x|) needs no case distinction.
+struct PhiParts { float tail, e; };   // tail = Phi(-|x|), e = exp(-x^2 / 2)
 __device__ __forceinline__ PhiParts phi_parts(float x) {
-  const float y = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, y, 1.0f));
-  const float e = __expf(-y * y);
-  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f), 0.254829592f);
-  const float tail = 0.5f * poly * e;             // = Phi(-|x|)
-  return PhiParts{x < 0.0f ? tail : 1.0f - tail, e};
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, fabsf(x), 1.0f));
+  const float e = __builtin_amdgcn_exp2f(x * x * -0.72134752044448170368f);   // -log2(e) / 2
+  const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f), 0.5f * 1.421413741f),
+                                      0.5f * -0.284496736f), 0.5f * 0.254829592f);
+  return PhiParts{poly * e, e};
 }
-__device__ __forceinline__ float gelu_epi_f(float x) { return x * phi_parts(x).Phi; }
+// (|x| is capped so that an infinite x meets its zero tail as 0 * finite: gelu(+-inf) = +inf, 0)
+__device__ __forceinline__ float gelu_epi_f(float x) { return fmaf(-fminf(fabsf(x), 3.0e38f), phi_parts(x).tail, fmaxf(x, 0.0f)); }
 __device__ __forceinline__ float gelu_grad_epi_f(float x) {
   const PhiParts p = phi_parts(x);
-  return fmaf(x * 0.39894228040143267794f, p.e, p.Phi);
+  return fmaf(x * 0.39894228040143267794f, p.e, x < 0.0f ? p.tail : 1.0f - p.tail);
 }
 __device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
 
