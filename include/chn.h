@@ -131,6 +131,14 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
  *              shape as C) for the backward pass
  *   RELU_BWD   v * [aux > 0]                       aux (M,N): the retained forward output
  *   GELU_BWD   v * gelu'(aux)                      aux (M,N): the retained pre-activation
+ *              With these two, preact_out != NULL asks for a second result: an F32 array of shape
+ *              (M/128, N) whose row r receives the column sums of rows 128r .. 128r+127 of C, taken
+ *              over the values as stored (after rounding to C's dtype), in a fixed order.  C is the
+ *              gradient with respect to a layer's pre-activation, so the column sum of these few
+ *              rows is that layer's bias gradient and no second pass over C is needed.  Requires M
+ *              and N to be multiples of 256, beta == 0, 16-byte aligned rows of C, aux and the sums,
+ *              and operands whose rows allow 8-byte pieces (CHN_ERR_SHAPE / OP / STRIDE otherwise);
+ *              the product then runs on 256x256 tiles, uncut.
  *   BF16_COPY  v, and preact_out (M,N) BF16 receives v rounded to bfloat16 as well (C must be F32):
  *              with alpha = -lr, beta = 1 and C the fp32 master weights, the weight-gradient product
  *              of a layer becomes the SGD update W <- W - lr * dW of Section "Background and
@@ -145,7 +153,7 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
  * product runs uncut -- same result up to summation order, possibly slower.
  * Errors (nothing is launched): CHN_ERR_NULL / NDIM / DTYPE / SHAPE / STRIDE for malformed or
  * mismatched views (a bias or aux that the epilogue needs and that is NULL: CHN_ERR_NULL), CHN_ERR_OP
- * for an unknown epilogue or a preact_out given to an epilogue other than BIAS_GELU / BF16_COPY
+ * for an unknown epilogue or a preact_out given to the NONE / BIAS / BIAS_RELU epilogues
  * (BF16_COPY requires it), CHN_ERR_LAUNCH
  * if the launch itself is refused.  M == 0 or N == 0 is a no-op; K == 0 applies the
  * epilogue to beta * C. */

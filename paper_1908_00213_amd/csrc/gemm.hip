@@ -70,7 +70,7 @@ bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
 // compute units but a long K is cut along K: every split writes fp32 partial sums to the workspace and
 // a second kernel adds them in a fixed order and runs the epilogue (its traffic and launch are charged
 // to the split candidates).
-void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split) {
+void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big_unsplit = false) {
   // microseconds per tile step [tile][0: both operands K-contiguous, 1: one, 2: none] and per block
   static const double step_bf16[3][3] = {{0.27, 0.50, 0.56}, {0.83, 1.08, 1.00}, {1.90, 2.25, 2.70}};
   static const double step_f32[3][3] = {{0.52, 0.62, 0.65}, {1.95, 2.40, 2.10}, {6.90, 7.50, 7.90}};
@@ -117,6 +117,7 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split) {
     if (force_tile >= 0 && force_tile <= (wide ? 2 : 0)) g->tile = force_tile;
     if (force_splits >= 1 && allow_split && force_splits <= nk) g->splits = force_splits;
   }
+  if (big_unsplit) { g->tile = 2; g->splits = 1; }        // (the caller has checked that the operands allow the big tile)
   const int b = 64 << g->tile;
   g->tiles_m = (g->M + b - 1) / b;
   g->tiles_n = (g->N + b - 1) / b;
@@ -201,7 +202,21 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.aux = aux->data;
   }
   if (epilogue == CHN_EPI_BF16_COPY && !preact_out) return fail(CHN_ERR_NULL, "gemm: the BF16_COPY epilogue needs preact_out");
-  if (preact_out) {
+  bool want_colsum = false;
+  if (preact_out && needs_aux) {
+    // activation-gradient epilogues: the second output holds column sums of C over blocks of 128 rows
+    CHN_TRY(validate(preact_out, "preact_out", true));
+    if (preact_out->dtype != CHN_F32) return fail(CHN_ERR_DTYPE, "gemm: the row-block column sums must be F32");
+    int64_t pr, pc;
+    CHN_TRY(row_major_2d(preact_out, "preact_out", &pr, &pc, &g.ldcs));
+    if (M % 256 || N % 256 || pr != M / 128 || pc != N)
+      return fail(CHN_ERR_SHAPE, "gemm: row-block column sums need M and N to be multiples of 256 and an (M/128, N) array");
+    if (beta != 0.0f) return fail(CHN_ERR_OP, "gemm: row-block column sums are not produced together with beta != 0");
+    if (reinterpret_cast<uintptr_t>(preact_out->data) % 16 || g.ldcs % 4)
+      return fail(CHN_ERR_STRIDE, "gemm: the row-block column sums need 16-byte aligned rows");
+    g.colsum = static_cast<float *>(preact_out->data);
+    want_colsum = true;
+  } else if (preact_out) {
     if (epilogue != CHN_EPI_BIAS_GELU && epilogue != CHN_EPI_BF16_COPY)
       return fail(CHN_ERR_OP, "gemm: preact_out is only produced by the BIAS_GELU and BF16_COPY epilogues");
     CHN_TRY(validate(preact_out, "preact_out", true));
@@ -224,7 +239,13 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     g.epi_vec = ok(g.C, g.ldc) && ok(g.aux, g.ldaux) && ok(g.pre, g.ldpre) &&
                 (g.bias == nullptr || reinterpret_cast<uintptr_t>(g.bias) % 16 == 0);
   }
-  plan(&g, isz, a_kc, b_kc, true);
+  if (want_colsum) {
+    // the sums are taken per wave tile of the 256x256 kernels, unsplit, on the vector path of the epilogue
+    if (!g.epi_vec || g.piece < 8) return fail(CHN_ERR_STRIDE, "gemm: row-block column sums need operands with 8-byte pieces and 16-byte aligned C and aux rows");
+    plan(&g, isz, a_kc, b_kc, false, true);
+  } else {
+    plan(&g, isz, a_kc, b_kc, true);
+  }
   if (g.splits > 1) {
     // split-K is an optimisation: without (enough, aligned) workspace the product is planned unsplit
     if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);

@@ -394,8 +394,10 @@ template <bool CB> struct EpiRaw { typename Raw4<CB>::type c0, aux; };
 // Same as finish4 with the epilogue kind, C's dtype (CB: bf16) and whether old C is added (BETA) fixed
 // at compile time (the tile kernels pick them once per pass, outside their loops, which are then free
 // of branches).
+// (*stored, if not null, receives the four values as C holds them, i.e. after rounding to its dtype)
 template <int EPI, bool CB, bool BETA>
-__device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, const f32x4 a, const EpiRaw<CB> &raw, const Vec4 &b) {
+__device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, const f32x4 a, const EpiRaw<CB> &raw, const Vec4 &b,
+                                          Vec4 *stored = nullptr) {
   Vec4 x, pre;
   EpiIn in;
   if constexpr (BETA) in.c0 = cvt4(raw.c0);
@@ -417,6 +419,10 @@ __device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, c
   }
   if constexpr (EPI == CHN_EPI_BF16_COPY) store4v(g.pre, (int64_t)row * g.ldpre + col, true, x);
   store4v(g.C, (int64_t)row * g.ldc + col, CB, x);
+  if (stored) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) stored->v[e] = CB ? bf16_to_f32(f32_to_bf16(x.v[e])) : x.v[e];
+  }
 }
 
 // Where the accumulators of one wave wait in LDS between the MFMA register layout and the row-major
@@ -437,8 +443,9 @@ struct StageLayout {
 // range and all accesses aligned, so that the loop is free of per-lane conditions.  Lane l handles
 // four consecutive columns; the LDS reads and the dependent global reads (old C, aux) of U row
 // segments are in flight together.
-template <int EPI, bool CB, bool BETA, int TN, int RP>
-__device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float *stage, int row0, int col0, int lane) {
+// CS: the lane also adds what it stores to cs[0..3], the running sums of its four columns.
+template <int EPI, bool CB, bool BETA, int TN, int RP, bool CS = false>
+__device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *cs = nullptr) {
   using L = StageLayout<TN>;
   constexpr int CPR = L::W / 4, RPI = 64 / CPR;            // 16-byte chunks per row, rows per wave-wide access
   constexpr int NIT = RP / RPI, U = NIT >= 8 ? 4 : NIT / 2;
@@ -465,7 +472,16 @@ __device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float
 #pragma unroll
     for (int u = 0; u < U; ++u) a[u] = *reinterpret_cast<const f32x4 *>(stage + L::at(rl0 + (base + u) * RPI, cl));
 #pragma unroll
-    for (int u = 0; u < U; ++u) finish4_t<EPI, CB, BETA>(g, row0 + rl0 + (base + u) * RPI, col, a[u], in[u], bias);
+    for (int u = 0; u < U; ++u) {
+      if constexpr (CS) {
+        Vec4 st;
+        finish4_t<EPI, CB, BETA>(g, row0 + rl0 + (base + u) * RPI, col, a[u], in[u], bias, &st);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[e] += st.v[e];
+      } else {
+        finish4_t<EPI, CB, BETA>(g, row0 + rl0 + (base + u) * RPI, col, a[u], in[u], bias);
+      }
+    }
   };
   // Two register sets take turns (the last iteration fetches its own batch once more rather than
   // branch); the scheduling fences keep the compiler from moving the reads back next to their use.
@@ -488,7 +504,7 @@ __device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float
 // One pass of a wave's epilogue: RP rows x W columns of staged accumulators.  With K splits the raw
 // sums go to this split's slab of the workspace instead.
 template <int TN, int RP>
-__device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab) {
+__device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab, float *cs) {
   using L = StageLayout<TN>;
   constexpr int W = L::W, CPR = W / 4;
   if (slab) {                                                 // split-K: raw sums, always aligned (ldp % 4 == 0)
@@ -503,6 +519,13 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
     auto run = [&](auto epi_c) __attribute__((always_inline)) {
       constexpr int EPI = decltype(epi_c)::value;
       constexpr bool kF32Only = EPI == CHN_EPI_BF16_COPY;   // (the host refuses a bf16 C for it)
+      if constexpr (EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD) {
+        if (g.colsum) {                                     // (the host asks for column sums with beta = 0 only)
+          if (g.c_bf16) epilogue_pass_vec<EPI, true, false, TN, RP, true>(g, stage, row0, col0, lane, cs);
+          else epilogue_pass_vec<EPI, false, false, TN, RP, true>(g, stage, row0, col0, lane, cs);
+          return;
+        }
+      }
       if (g.beta != 0.0f) {
         if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, true, TN, RP>(g, stage, row0, col0, lane);
         else epilogue_pass_vec<EPI, false, true, TN, RP>(g, stage, row0, col0, lane);
@@ -621,13 +644,25 @@ __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM]
         __builtin_amdgcn_sched_barrier(0);   // one block's 16 values in flight at a time, not the whole pass
       }
   };
+  float cs[4] = {0.0f, 0.0f, 0.0f, 0.0f};               // column sums of this wave's rows (when asked for)
 #pragma unroll 1
   for (int p = 0; p < NPASS; ++p) {
     if (p == 0) put(std::integral_constant<int, 0>{});
     else put(std::integral_constant<int, NPASS - 1>{});
     __builtin_amdgcn_wave_barrier();
-    epilogue_pass<TN, RP>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab);
+    epilogue_pass<TN, RP>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab, cs);
     __builtin_amdgcn_wave_barrier();
+  }
+  if constexpr (TM == 4 && TN == 4) {
+    // The lanes of one row segment own 32 column groups; lane l and lane l + 32 walked different rows
+    // of the same columns.  One row of the sums per wave tile (128 rows of C).
+    if (g.colsum) {
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = cs[e] + __shfl_xor(cs[e], 32, 64);
+      if (lane < 32)
+        global_store<f32x4>(reinterpret_cast<uintptr_t>(g.colsum + (int64_t)((m0 >> 7) + wm) * g.ldcs + n0 + wn * 128 + lane * 4), v);
+    }
   }
 }
 

@@ -122,6 +122,11 @@ class MLPTrainer:
         self.ws_ce = torch.empty(B.softmax_ce_workspace_bytes(batch), dtype=torch.uint8, device="cuda")
         need = max([B.reduce_axis_workspace_bytes(d, 0) for d in self.dv[1:]] + [256])
         self.ws_red = torch.empty(need, dtype=torch.uint8, device="cuda")
+        # Where a hidden layer's output gradient comes out of an activation-gradient product in whole
+        # 256 x 256 tiles, that product also leaves its column sums per block of 128 rows, and the
+        # bias gradient is the sum of those few rows instead of another pass over the gradient.
+        self.rowsums = {l: mk(batch // 128, self.sizes[l]) for l in range(1, n)
+                        if batch % 256 == 0 and self.sizes[l] % 256 == 0 and self.sizes[l + 1] % 8 == 0}
         self._progs = {}
 
     def _build(self, x, t):
@@ -144,10 +149,10 @@ class MLPTrainer:
             dv = self.dv[l + 1]
             if not self.fused_update:
                 _gemm(p, L, dv.t(), hs[l], self.dW[l])
-            p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(dv), 0, 0, p.d(self.db[l]), rp, rn)
+            p.add(L.chn_reduce_axis, B.REDUCE["sum"], p.d(self.rowsums.get(l + 1, dv)), 0, 0, p.d(self.db[l]), rp, rn)
             if l > 0:
                 _gemm(p, L, dv, self.Wl[l], self.dv[l], epi=bwd_epi,
-                      aux=hs[l] if self.act == "relu" else self.z[l])
+                      aux=hs[l] if self.act == "relu" else self.z[l], pre=self.rowsums.get(l))
             if self.fused_update:     # after dx: that product still reads this layer's old weights
                 _gemm(p, L, dv.t(), hs[l], self.W[l], alpha=-self.lr, beta=1.0,
                       epi="bf16_copy" if self.lowp else "none", pre=self.Wl[l] if self.lowp else None)

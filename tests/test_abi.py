@@ -103,6 +103,12 @@ def test_reduce_gemm_and_layer_validation():
     assert g(A, Bm, Cm, 4) == -1                              # aux missing
     assert g(A, Bm, Cm, 0, None, None, Cm) == -6              # preact_out without BIAS_GELU
     assert g(A, Bm, Cm, 17) == -6
+    # row-block column sums beside an activation gradient: shapes in whole 256 x 256 tiles only
+    A2, B2, C2 = f((512, 64), (256, 4)), f((64, 256), (1024, 4)), f((512, 256), (1024, 4))
+    assert g(A, Bm, Cm, 4, None, Cm, f((1, 4), (16, 4))) == -4              # M, N not multiples of 256
+    assert g(A2, B2, C2, 4, None, C2, f((3, 256), (1024, 4))) == -4          # one row per 128 rows of C
+    assert g(A2, B2, C2, 5, None, C2, f((4, 256), (512, 2), B.BF16)) == -3   # the sums are fp32
+    assert g(A2, B2, C2, 4, None, C2, f((4, 256), (1028, 4))) == -5          # rows off the 16-byte grid
     z, c = f((4, 32), (128, 4)), f((4, 8), (32, 4))
     assert L.chn_lstm_fwd(C.byref(f((4, 31), (124, 4))), None, C.byref(c), C.byref(c), C.byref(c), None, None) == -4
     assert L.chn_lstm_fwd(C.byref(z), C.byref(f((31,), (4,))), C.byref(c), C.byref(c), C.byref(c), None, None) == -4

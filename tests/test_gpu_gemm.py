@@ -263,6 +263,44 @@ def test_gemm_direct_copy_epilogues(dt, cdt, layout):
     check(host(out), (lin + c0) * gp, tol, (S + np.abs(c0)) * (np.abs(gp) + 3e-3), "gelu_bwd beta")
 
 
+@pytest.mark.parametrize("dt,cdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
+@pytest.mark.parametrize("layout,shape", [("nn", (512, 768, 200)), ("nt", (768, 256, 1000)), ("tn", (256, 512, 72))])
+def test_gemm_activation_gradient_with_row_block_column_sums(dt, cdt, layout, shape):
+    """The activation-gradient epilogues can leave, beside C, the column sums of C over blocks of 128
+    rows (the bias gradient of the layer below is their column sum).  C is checked against the oracle
+    as without the sums; the sums against the stored C, to fp32 summation accuracy, which pins them to
+    the values as stored (rounded to bf16 where C is bf16)."""
+    M, N, K = shape
+    A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
+    tol = TOL_BF16 if cdt == "bf16" else TOL_SUM
+    aux = rnd((M, N))
+    aux = bf16r(aux) if cdt == "bf16" else aux
+    lin = O.gemm(A, Bm)
+    S = np.abs(A).astype(np.float64) @ np.abs(Bm).astype(np.float64)
+    gp = O.elementwise("gelu_bwd", [np.ones_like(aux, dtype=np.float64), aux.astype(np.float64)])
+    for epi, ref, scale in (("relu_bwd", np.where(aux > 0, lin, 0.0), S), ("gelu_bwd", lin * gp, S * np.abs(gp) + 3e-3 * S)):
+        plain = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue=epi, aux=dev(aux, cdt))
+        sums = empty((M // 128, N))
+        sums.fill_(float("nan"))
+        out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue=epi, aux=dev(aux, cdt), preact_out=sums)
+        check(host(out), ref, tol, scale, epi)
+        if B.gemm_plan(Ad, Bd, out)[0] == 2 and B.gemm_plan(Ad, Bd, out)[2] == 1:
+            assert torch.equal(out, plain)                       # same kernel, same C
+        c = host(out).reshape(M // 128, 128, N)
+        got = host(sums)
+        assert np.all(np.abs(got - c.sum(axis=1)) <= 1e-5 * np.abs(c).sum(axis=1) + 1e-30), epi
+        # and so the bias gradient: one small reduction instead of a pass over C
+        db = B.reduce_axis("sum", sums, 0, empty((N,)))
+        check(host(db), ref.sum(axis=0), tol, scale.sum(axis=0), epi + " bias gradient")
+    # what the call refuses (nothing is launched)
+    with pytest.raises(B.ChnError):
+        B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="gelu_bwd", aux=dev(aux, cdt), preact_out=empty((M // 128 + 1, N)))
+    with pytest.raises(B.ChnError):
+        B.gemm(Ad, Bd, dev(aux, cdt), beta=1.0, epilogue="gelu_bwd", aux=dev(aux, cdt), preact_out=empty((M // 128, N)))
+    with pytest.raises(B.ChnError):
+        B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias", bias=dev(rnd((N,))), preact_out=empty((M // 128, N)))
+
+
 @pytest.mark.parametrize("layout", ["nt", "tn"])
 def test_gemm_direct_copy_split_k(layout):
     # few tiles and a long K: the direct-copy kernel writes fp32 slabs, the finishing kernel adds them

@@ -59,8 +59,15 @@ def test_config3_mlp_step_fp32_and_bf16():
 
 def test_config5_scaled_wide_mlp_gelu_bf16_and_fp32():
     w = W.config5(n_batches=1, scale=8)         # 512-512-512-512-1000, batch 1024
-    run_mlp(w, True, 2e-2)
+    tr, _, _ = run_mlp(w, True, 2e-2)
+    # at these sizes (whole 256 x 256 tiles) the hidden layers' bias gradients come from the row-block
+    # column sums that the activation-gradient products leave behind
+    assert sorted(tr.rowsums) == [1, 2, 3]
     run_mlp(w, False, 1e-4)
+    wr = W.make_mlp("t", (256, 512, 256, 16), 512, "relu", 7, 1)
+    tr, _, _ = run_mlp(wr, False, 1e-4)
+    assert sorted(tr.rowsums) == [1, 2]
+    run_mlp(wr, True, 2e-2)
 
 
 def test_mlp_second_step_uses_updated_weights():
