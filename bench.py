@@ -244,9 +244,11 @@ def bench_tape(torch, W, timer, quick):
     ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
     # step by step (a product, a sum and a cell node per time step), the recurrent layer as one node,
     # and that with the hidden width rounded up to 672 by inert units (the width the fused step takes)
-    for name, params, n_step in (("cfg4_lstm_lm_f32", w.params, False), ("cfg4_lstm_lm_f32_n_step", w.params, True),
-                                 ("cfg4_lstm_lm_f32_n_step_padded", W.pad_lstm_params(w.params), True)):
-        model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in params.items()}, n_step=n_step)
+    padded = W.pad_lstm_params(w.params)
+    for name, params, n_step, lowp in (("cfg4_lstm_lm_f32", w.params, False, False), ("cfg4_lstm_lm_f32_n_step", w.params, True, False),
+                                       ("cfg4_lstm_lm_f32_n_step_padded", padded, True, False),
+                                       ("cfg4_lstm_lm_bf16_n_step_padded", padded, True, True)):
+        model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in params.items()}, n_step=n_step, lowp=lowp)
         opt = T.SGD(model.params(), w.lr)
         last = [None]
 

@@ -94,6 +94,9 @@ class GpuBackend:
     def lstm_step_fwd(self, zx, h_prev, Ut, bias, c_prev, c, h, gates):
         self.B.lstm_step_fwd(zx, h_prev, Ut, bias, c_prev, c, h, gates)
 
+    def lstm_step_bwd(self, dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev):
+        self.B.lstm_step_bwd(dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev)
+
     def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
         ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
         self.B.softmax_ce_fwd(logits, labels, loss_mean, None, lse, ignore_label, ws)
@@ -659,8 +662,13 @@ class LinearFunction(FunctionNode):
 
 
 class MatMul(FunctionNode):
-    """y = x @ W (both 2-d); retains both inputs."""
+    """y = x @ W (both 2-d); retains both inputs.  ``out_dtype`` / ``gx_dtype``: storage type of the
+    result and of the gradient with respect to x (default: x's)."""
     fresh = (0, 1)
+
+    def __init__(self, out_dtype=None, gx_dtype=None):
+        super().__init__()
+        self.out_dtype, self.gx_dtype = out_dtype, gx_dtype
 
     def _input_array(self, var):
         return var.compute_array if isinstance(var, Parameter) else var.array
@@ -669,7 +677,7 @@ class MatMul(FunctionNode):
         F = backend()
         x = xs[0]
         W = self._input_array(self.in_vars[1])
-        y = F.empty((x.shape[0], W.shape[1]), F.dtype(x))
+        y = F.empty((x.shape[0], W.shape[1]), self.out_dtype or F.dtype(x))
         F.gemm(x, W, y)
         self.retain_inputs((0, 1))
         return (y,)
@@ -681,7 +689,7 @@ class MatMul(FunctionNode):
         out = []
         for k, i in enumerate(indexes):
             if i == 0:
-                gx = F.empty(x.shape, F.dtype(x))
+                gx = F.empty(x.shape, self.gx_dtype or F.dtype(x))
                 F.gemm(gy, _t(W), gx)
             else:
                 gx = self.grad_slots[k]
@@ -1003,7 +1011,9 @@ class EmbedID(FunctionNode):
 
     def forward(self, xs):
         F = backend()
-        ids, table = xs
+        ids = xs[0]
+        var = self.in_vars[1]
+        table = var.compute_array if isinstance(var, Parameter) else var.array   # (the bf16 working copy, if any)
         self.ids, self.table_shape = ids, tuple(table.shape)
         out = F.empty((ids.shape[0], table.shape[1]), F.dtype(table))
         F.embed_fwd(table, ids, out)
@@ -1084,27 +1094,37 @@ class NStepLSTM(FunctionNode):
     here the forward is one launch per step where the backend fuses product and cell (two
     otherwise), and the backward computes U's gradient as one product over all steps once every
     step's gate gradient is known.  The arithmetic per element is that of the step-by-step graph;
-    sums over time are taken in a different order."""
+    sums over time are taken in a different order.
+
+    ``lowp``: what feeds a matrix product is stored in bfloat16 -- the hidden states, their gradients,
+    the gate gradients, and U is read from its parameter's working copy; gates, cell states and
+    parameter gradients stay fp32.  The backward step is then fused as well where the backend can."""
     fresh = (0, 1, 2, 3, 4)
 
-    def __init__(self, n_steps):
+    def __init__(self, n_steps, lowp=False):
         super().__init__()
-        self.T = int(n_steps)
+        self.T, self.lowp = int(n_steps), lowp
+
+    def _input_array(self, var):
+        return var.compute_array if isinstance(var, Parameter) else var.array
 
     def forward(self, xs):
         F = backend()
-        c0, h0, zx, U, bias = xs
+        c0, h0, zx, _, bias = xs
+        U = self._input_array(self.in_vars[3])
         T, Bn, H = self.T, c0.shape[0], c0.shape[1]
         if tuple(zx.shape) != (T * Bn, 4 * H) or tuple(U.shape) != (H, 4 * H) or tuple(h0.shape) != (Bn, H):
             raise ValueError("n_step_lstm: zx %s, U %s, c0 %s, h0 %s do not fit %d steps"
                              % (tuple(zx.shape), tuple(U.shape), tuple(c0.shape), tuple(h0.shape), T))
+        adt = "bf16" if self.lowp else "f32"
         blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
-        Hs, Cs = F.empty(((T + 1) * Bn, H), "f32"), F.empty(((T + 1) * Bn, H), "f32")   # block 0 = initial state
+        Hs, Cs = F.empty(((T + 1) * Bn, H), adt), F.empty(((T + 1) * Bn, H), "f32")   # block 0 = initial state
         F.elementwise_broadcast("copy", [h0], blk(Hs, 0))
         F.elementwise_broadcast("copy", [c0], blk(Cs, 0))
         G = F.empty((T * Bn, 4 * H), "f32")
-        if F.fuses_lstm_step(H):
-            Ut = F.empty((4 * H, H), "f32")
+        self.fused = F.fuses_lstm_step(H)
+        if self.fused:
+            Ut = F.empty((4 * H, H), adt)
             F.elementwise_broadcast("copy", [_t(U)], Ut)
             for t in range(T):
                 F.lstm_step_fwd(blk(zx, t), blk(Hs, t), Ut, bias, blk(Cs, t), blk(Cs, t + 1), blk(Hs, t + 1), blk(G, t))
@@ -1125,26 +1145,36 @@ class NStepLSTM(FunctionNode):
         U, = self.get_retained_inputs()
         Hs, Cs, G, T = self.Hs, self.Cs, self.G, self.T
         Bn, H = Hs.shape[0] // (T + 1), Hs.shape[1]
+        adt = "bf16" if self.lowp else "f32"
         blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
         gc, gh, ghs = gys
-        dHs = F.empty((T * Bn, H), "f32")                            # gradient reaching h_1 .. h_T from outside
+        dHs = F.empty((T * Bn, H), adt)                              # gradient reaching h_1 .. h_T from outside
         if ghs is None:
             F.elementwise_broadcast("fill", [], dHs, (0.0,))
         else:
             F.elementwise_broadcast("copy", [ghs], dHs)
         if gh is not None:
+            if F.dtype(gh) != F.dtype(dHs):
+                g2 = F.empty((Bn, H), adt)
+                F.elementwise_broadcast("copy", [gh], g2)
+                gh = g2
             F.elementwise_broadcast("add", [blk(dHs, T - 1), gh], blk(dHs, T - 1))
-        dZ = F.empty((T * Bn, 4 * H), "f32")
+        dZ = F.empty((T * Bn, 4 * H), adt)
         dc = [F.empty((Bn, H), "f32"), F.empty((Bn, H), "f32")]
-        dh0 = F.empty((Bn, H), "f32")
+        dh0 = F.empty((Bn, H), adt)
         dc_next = gc
+        fused_bwd = self.lowp and self.fused       # (in fp32 the three separate calls are the faster ones)
         for t in range(T - 1, -1, -1):
-            F.lstm_bwd(blk(G, t), blk(Cs, t), blk(Cs, t + 1), blk(dHs, t), dc_next, blk(dZ, t), dc[t & 1])
+            if fused_bwd:                          # dh_t += dz_{t+1} U^T, then the cell
+                F.lstm_step_bwd(None if t == T - 1 else blk(dZ, t + 1), U, blk(dHs, t), blk(G, t), blk(Cs, t), blk(Cs, t + 1),
+                                dc_next, blk(dZ, t), dc[t & 1])
+            else:
+                F.lstm_bwd(blk(G, t), blk(Cs, t), blk(Cs, t + 1), blk(dHs, t), dc_next, blk(dZ, t), dc[t & 1])
+                if t > 0:
+                    F.gemm(blk(dZ, t), _t(U), blk(dHs, t - 1), beta=1.0)
             dc_next = dc[t & 1]
-            if t > 0:
-                F.gemm(blk(dZ, t), _t(U), blk(dHs, t - 1), beta=1.0)
-            elif 1 in indexes:
-                F.gemm(blk(dZ, 0), _t(U), dh0)
+        if 1 in indexes:
+            F.gemm(blk(dZ, 0), _t(U), dh0)
         out = []
         for i in indexes:
             if i == 0:
@@ -1216,8 +1246,8 @@ def linear(x, W, b, act=None, out_dtype=None):
     return LinearFunction(act, out_dtype).apply((x, W, b))[0]
 
 
-def matmul(x, W):
-    return MatMul().apply((x, W))[0]
+def matmul(x, W, out_dtype=None, gx_dtype=None):
+    return MatMul(out_dtype, gx_dtype).apply((x, W))[0]
 
 
 def relu(x):
@@ -1285,9 +1315,9 @@ def lstm(c_prev, z, bias=None):
     return LSTM().apply((c_prev, z) if bias is None else (c_prev, z, bias))
 
 
-def n_step_lstm(c0, h0, zx, U, bias, n_steps):
+def n_step_lstm(c0, h0, zx, U, bias, n_steps, lowp=False):
     """All n_steps time steps of an LSTM layer; returns (c_T, h_T, hs) with hs (n_steps*B, H)."""
-    return NStepLSTM(n_steps).apply((c0, h0, zx, U, bias))
+    return NStepLSTM(n_steps, lowp).apply((c0, h0, zx, U, bias))
 
 
 def split_rows(x, n):
@@ -1405,9 +1435,20 @@ class LSTMLanguageModel:
     time steps is whatever the batch at hand has.  ``n_step``: the recurrent layer is one
     ``n_step_lstm`` node instead of a product, a sum and a cell per time step."""
 
-    def __init__(self, P, n_step=False):
-        self.P = {k: Parameter(v, None, k) for k, v in P.items()}
-        self.n_step = n_step
+    def __init__(self, P, n_step=False, lowp=False):
+        """lowp (with n_step): bf16 working copies of E, W, U and W_out feed the products, as do bf16
+        embeddings, hidden states and their gradients; everything else stays fp32."""
+        if lowp and not n_step:
+            raise ValueError("LSTMLanguageModel: lowp needs n_step=True")
+        F = backend()
+        self.P = {}
+        for k, v in P.items():
+            low = None
+            if lowp and k in ("E", "W", "U", "W_out"):
+                low = F.empty(tuple(v.shape), "bf16")
+                F.elementwise_broadcast("copy", [v], low)
+            self.P[k] = Parameter(v, low, k)
+        self.n_step, self.lowp = n_step, lowp
 
     def params(self):
         return list(self.P.values())
@@ -1417,7 +1458,7 @@ class LSTMLanguageModel:
         carry the state into the next window (after ``unchain`` for truncated back-propagation)."""
         P, F = self.P, backend()
         X = embed_id(ids, P["E"])
-        zx = matmul(X, P["W"])
+        zx = matmul(X, P["W"], out_dtype="f32", gx_dtype="f32")
         if state is None:
             Bn, H = ids.shape[0] // n_steps, P["U"].shape[0]
             z0 = F.empty((Bn, H), "f32")
@@ -1426,9 +1467,9 @@ class LSTMLanguageModel:
         else:
             c, h = state
         if self.n_step:
-            c, h, hs = n_step_lstm(c, h, zx, P["U"], P["b"], n_steps)
-            logits = linear(hs, P["W_out"], P["b_out"])
-            return softmax_cross_entropy(logits, targets), (c, h)
+            c, h, hs = n_step_lstm(c, h, zx, P["U"], P["b"], n_steps, self.lowp)
+            logits = linear(hs, P["W_out"], P["b_out"], out_dtype="f32")
+            return softmax_cross_entropy(logits, targets, grad_dtype="bf16" if self.lowp else None), (c, h)
         zs = split_rows(zx, n_steps)
         hs = []
         for t in range(n_steps):

@@ -69,6 +69,12 @@ class OracleBackend:
         z = O.gemm(h_prev, Ut.T, zx, 1.0, 1.0)
         c[...], h[...], gates[...] = O.lstm_fwd(z, bias, c_prev)
 
+    def lstm_step_bwd(self, dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev):
+        self.calls.append(("lstm_step_bwd", None))
+        if dz_next is not None:
+            dh[...] = O.gemm(dz_next, U.T, dh, 1.0, 1.0)
+        dz[...], dc_prev[...] = O.lstm_bwd(gates, c_prev, c, dh, dc_next)
+
     def lstm_bwd(self, gates, c_prev, c, dh, dc_next, dz, dc_prev):
         self.calls.append(("lstm_bwd", None))
         dz[...], dc_prev[...] = O.lstm_bwd(gates, c_prev, c, dh, dc_next)

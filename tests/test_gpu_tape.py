@@ -164,6 +164,29 @@ def test_tape_n_step_lstm_matches_the_oracle_and_carries_state(cfg):
             check(gg[k], gr[k], 1e-4, float(np.max(np.abs(gr[k]))), "d" + k)
 
 
+@pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=96, batch=16, bptt=6),      # both steps fused
+                                 dict(vocab=1000, embed=136, hidden=136, batch=24, bptt=4)])   # separate calls
+def test_tape_n_step_lstm_mixed_precision_matches_the_oracle(cfg):
+    """bf16 storage of everything that feeds a product, against the oracle's step with the same
+    storage points; then the optimiser refreshes the working copies from the fp32 masters."""
+    F = T.backend()
+    w = W.config4(**cfg)
+    w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
+    model = T.LSTMLanguageModel({k: F.from_numpy(v) for k, v in w.params.items()}, n_step=True, lowp=True)
+    ids, tg = F.from_numpy(w.ids.reshape(-1)), F.from_numpy(w.targets.reshape(-1))
+    loss, _ = model.loss(ids, tg, w.bptt)
+    loss.backward()
+    r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr), lowp=True)
+    assert abs(float(loss.array.cpu()) - r["loss"]) <= 2e-2 * abs(r["loss"])
+    for k in w.params:
+        assert model.P[k].grad.dtype == torch.float32
+        cmp(model.P[k].grad, r["grads"][k], 2e-2, "d" + k)
+    T.SGD(model.params(), w.lr).update()
+    for k in ("E", "W", "U", "W_out"):
+        assert np.array_equal(host(model.P[k].lowp), O.round_bf16(host(model.P[k].array))), k
+    assert T.live_function_nodes() == 0
+
+
 def test_tape_window_length_changes_and_state_is_carried_across_windows():
     # truncated back-propagation over two windows of different length: the second starts from the
     # first one's final state, cut from its history.  Reference: the same tape on the CPU with the

@@ -115,6 +115,30 @@ def test_lstm_language_model_matches_finite_differences_and_oracle_step(F):
 
 
 @pytest.mark.parametrize("fuse", [False, True])
+def test_n_step_lstm_mixed_precision_code_path(F, fuse):
+    """The bf16-storage variant walks different calls (working copies of the parameters, the fused
+    backward step).  On the oracle backend nothing is rounded, so it must reproduce the fp32 step."""
+    F.fuse_lstm_step = fuse
+    w = W.config4(seed=8, vocab=13, embed=3, hidden=4, batch=2, bptt=4)
+    P = {k: v.astype(np.float64) for k, v in w.params.items()}
+    P["b"] = np.random.default_rng(6).standard_normal(P["b"].shape) * 0.1
+    ids, tg = w.ids.reshape(-1).astype(np.int64), w.targets.reshape(-1).astype(np.int64)
+    ref = OS.lstm_lm_step(P, w.ids, w.targets, 0.1)
+    model = T.LSTMLanguageModel({k: v.copy() for k, v in P.items()}, n_step=True, lowp=True)
+    assert all((model.P[k].lowp is not None) == (k in ("E", "W", "U", "W_out")) for k in P)
+    F.calls.clear()
+    loss, _ = model.loss(ids, tg, w.bptt)
+    loss.backward()
+    names = [n for n, _ in F.calls]
+    assert (names.count("lstm_step_bwd") == w.bptt) == fuse and (names.count("lstm_bwd") == w.bptt) != fuse
+    assert float(loss.array) == pytest.approx(ref["loss"], rel=1e-13)
+    for k, p in model.P.items():
+        np.testing.assert_allclose(p.grad, ref["grads"][k], rtol=1e-10, atol=1e-13, err_msg=k)
+    with pytest.raises(ValueError):
+        T.LSTMLanguageModel(P, n_step=False, lowp=True)
+
+
+@pytest.mark.parametrize("fuse", [False, True])
 def test_n_step_lstm_equals_the_oracle_step_and_the_step_by_step_graph(F, fuse):
     """One function node for all time steps: same loss and gradients as the hand-ordered oracle step
     and as the graph of per-step nodes, with far fewer nodes; both forward code paths (one call per
