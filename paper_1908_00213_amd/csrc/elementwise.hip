@@ -367,7 +367,7 @@ struct TransArgs {
   int64_t ostr0;
   int64_t istr0[3], istr1[3];
   int transposed[3];
-  int slot[3];   // vector form: which 16 KB LDS tile a transposed input uses
+  int slot[3];   // vector form: which LDS tile a transposed input uses
   float s0;
 };
 
@@ -411,19 +411,19 @@ __global__ __launch_bounds__(256) void ew_transpose_kernel(TransArgs a, int64_t 
   }
 }
 
-// family 2, vector form: 16-byte global accesses on every operand.  A tile is 64 columns x 16 vectors
-// of rows (64 fp32 / 128 bf16 rows).  A transposed input is read along its unit-stride (row) axis,
+// family 2, vector form: 16-byte global accesses on every operand.  A tile is TC (64 or 128) columns x
+// 16 vectors of rows (64 fp32 / 128 bf16 rows).  A transposed input is read along its unit-stride (row) axis,
 // 16 bytes per lane and 256 contiguous bytes per 16 lanes, and parked in LDS as [column][row], the
 // 16-byte chunk index XORed with (column / E) so that both the 16-byte writes and the later
 // element reads along a column are free of bank conflicts.  The compute phase then walks rows:
 // each lane produces E consecutive columns of one row, gathering the transposed operands element by
 // element from LDS and everything else with 16-byte global loads, and stores 16 bytes.
-template <int OP, typename T, int NIN>
+template <int OP, typename T, int NIN, int TC>
 __global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int64_t tiles_c) {
   constexpr int E = 16 / (int)sizeof(T);
-  constexpr int TC = 64, TR = 16 * E;
+  constexpr int TR = 16 * E;
   constexpr int VPR = TC / E, RPP = 256 / VPR;
-  extern __shared__ __align__(16) char tiles[];   // one 16 KB tile per transposed input
+  extern __shared__ __align__(16) char tiles[];   // one tile of TC * 256 bytes per transposed input
   const int t = threadIdx.x;
   // Diagonal tile order: blocks that run at the same time differ in their row tile AND their column
   // tile.  With a power-of-two leading dimension, neighbours that differed in one of them only would
@@ -440,7 +440,7 @@ __global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int6
       if (!a.transposed[k]) continue;
       const T *p = static_cast<const T *>(a.in[k]);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < TC / 16; ++j) {
         const int c = cl + 16 * j;
         Vec16<T> v;
         v.raw = {};
@@ -534,7 +534,14 @@ chn_status launch_fast(const Plan &p, const chn_array *const *in, const chn_arra
         if (trv * tc > 0x7fffffff) return fail(CHN_ERR_SHAPE, "elementwise: array too large");
         int nslots = 0;
         for (int k = 0; k < NIN; ++k) a.slot[k] = a.transposed[k] ? nslots++ : 0;
-        hipLaunchKernelGGL((ew_transpose_vec_kernel<OP, Tin, NIN>), dim3((unsigned)(trv * tc)), dim3(256), nslots * 64 * 256, st, a, tc);
+        // fp32: tiles of 128 columns where the LDS tiles fit (rows of the other operands and of the output
+        // are then touched in 512-byte pieces: +4 % at 8192 x 8192; bf16 gains nothing from it)
+        if (sizeof(Tin) == 4 && nslots * 128 * 256 <= 65536) {
+          const int64_t tcw = (a.cols + 127) / 128;
+          hipLaunchKernelGGL((ew_transpose_vec_kernel<OP, Tin, NIN, 128>), dim3((unsigned)(trv * tcw)), dim3(256), nslots * 128 * 256, st, a, tcw);
+        } else {
+          hipLaunchKernelGGL((ew_transpose_vec_kernel<OP, Tin, NIN, 64>), dim3((unsigned)(trv * tc)), dim3(256), nslots * 64 * 256, st, a, tc);
+        }
         return check_launch("elementwise transpose (vector)");
       }
     }

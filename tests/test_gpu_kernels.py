@@ -121,6 +121,21 @@ def test_transposed_view(dt, shape):
     assert torch.equal(out.view(torch.int16 if dt == "bf16" else torch.int32), out2.view(torch.int16 if dt == "bf16" else torch.int32))
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("n_t", [2, 3])
+def test_several_transposed_operands(dt, n_t):
+    # every transposed operand has an LDS tile of its own; with three of them the wide tiles no
+    # longer fit and the narrow ones are used
+    r, c = 392, 264
+    stores = [rnd((c, r), dt) for _ in range(3)]
+    views = [dev(s_, dt).t() if k < n_t else dev(np.ascontiguousarray(s_.T), dt) for k, s_ in enumerate(stores)]
+    out = empty((r, c), dt)
+    assert B.elementwise_plan("mad", views, out) == 2
+    B.elementwise_broadcast("mad", views, out)
+    ref = O.elementwise("mad", [s_.T for s_ in stores])
+    check(host(out), ref, tol_for(dt, dt, TOL_EW), O.elementwise("mad", [np.abs(s_.T) for s_ in stores]), "%d transposed" % n_t)
+
+
 def test_strided_views_and_inplace():
     big = rnd((40, 50))
     d = dev(big)
