@@ -87,8 +87,9 @@ chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
     if (p->vec && groups >= 64 && p->len <= 64) p->tx = kColTXWide;   // 16 row lanes: one batch of loads per thread
     const int64_t cols_per_block = (int64_t)p->tx * (p->vec ? n : 1);
     const int64_t blocks_xy = ((p->I + cols_per_block - 1) / cols_per_block) * p->O;
-    // Measured on 8192 x 8192: many short blocks (8 rows per thread) stream best.
-    int64_t s = p->len / (8 * (256 / p->tx));
+    // Measured on 8192 x 8192: many short blocks (8 rows per thread, 16 of bf16) stream best.
+    const int rpt = isz == 2 ? 16 : 8;   // rows per thread (bf16: half the partial sums for the second pass, -5 %)
+    int64_t s = p->len / (rpt * (256 / p->tx));
     if (blocks_xy * s > 16384) s = 16384 / blocks_xy;
     if (p->len <= 64) s = 1;        // a short stack of rows (e.g. per-row-block sums): one launch, a few loads per thread
     if (s < 1) s = 1;
