@@ -142,6 +142,36 @@ def test_config5_full_size_step_sampled():
         check(bias[l].astype(np.float64), O.sgd_update(b_old[l], db[l], lr), 1e-6, np.abs(b_old[l]) + lr * np.abs(db[l]), "b%d" % l)
 
 
+def test_config5_full_size_step_as_benchmarked_update_in_the_weight_gradient_products():
+    """The trainer exactly as bench.py runs it: the weight-gradient products apply the SGD update in
+    their epilogue and refresh the bf16 working copies, the hidden layers' bias gradients come from
+    the row-block column sums.  Teacher-forced on the step's own activations and gradients: sampled
+    entries of every updated weight matrix, every working copy, every bias."""
+    w = W.config5(n_batches=1)
+    x = W.bf16_exact(w.xs[0])
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp=True, fused_update=True)
+    assert sorted(tr.rowsums) == [1, 2, 3]
+    W0 = [m.clone() for m in tr.W]
+    xd, td = torch.from_numpy(x).cuda().to(torch.bfloat16), torch.from_numpy(w.ts[0]).cuda()
+    loss = float(tr.step(xd, td).cpu())
+    torch.cuda.synchronize()
+    assert np.isfinite(loss)
+    n = len(tr.W)
+    hs = [x] + [h32(hh) for hh in tr.h[1:]]
+    lr = np.float32(w.lr)
+    for l in range(n):
+        dv = h32(tr.dv[l + 1])
+        ms, ns, ref, S = sample_gemm(dv.T, hs[l])
+        old = W0[l].cpu().numpy()[ms, ns].astype(np.float64)
+        new = tr.W[l].cpu().numpy()
+        check(new[ms, ns].astype(np.float64), old - float(lr) * ref, TOL_SUM, np.abs(old) + float(lr) * S, "W%d" % l)
+        assert np.array_equal(h32(tr.Wl[l]).astype(np.float64), O.round_bf16(new)), "working copy %d" % l
+        db = tr.db[l].cpu().numpy()
+        check(db.astype(np.float64), O.reduce_axis("sum", dv, 0), TOL_SUM, O.reduce_axis("sum", np.abs(dv), 0), "db%d" % l)
+        b_old = w.params[l][1]
+        check(tr.b[l].cpu().numpy().astype(np.float64), O.sgd_update(b_old, db, lr), 1e-6, np.abs(b_old) + lr * np.abs(db), "b%d" % l)
+
+
 def test_config4_full_size_step_sampled():
     w = W.config4()
     T, Bn, H, V = w.bptt, w.batch, w.hidden, w.vocab
