@@ -43,16 +43,38 @@ __device__ __forceinline__ MS row_scan(const T *p, int64_t C, int g) {
   if constexpr (VEC) {
     constexpr int N = Vec16<T>::N;
     const int64_t nvec = C / N;
-    for (int64_t v = g; v < nvec; v += G) {
+    // Four vectors per round: their loads are in flight together, the running sum is rescaled once
+    // per round, and the exponentials are the hardware's (exp2 of a pre-scaled argument; the arguments
+    // are <= 0 and the relative error of a term is a few 1e-7, far inside what the log of the sum
+    // needs).  With the library's expf this loop was bound by arithmetic, not by memory.
+    int64_t v = g;
+    for (; v + 3 * G < nvec; v += 4 * G) {
+      Vec16<T> x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) x[u].load(p + (v + u * G) * N);
+      float mx = x[0].get(0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < N; ++i) mx = fmaxf(mx, x[u].get(i));
+      const float m = fmaxf(acc.m, mx);
+      float s = acc.s * __expf(acc.m - m);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < N; ++i) s += __expf(x[u].get(i) - m);
+      acc = MS{m, s};
+    }
+    for (; v < nvec; v += G) {
       Vec16<T> x;
       x.load(p + v * N);
       float mx = x.get(0);
 #pragma unroll
       for (int i = 1; i < N; ++i) mx = fmaxf(mx, x.get(i));
       const float m = fmaxf(acc.m, mx);
-      float s = acc.s * expf(acc.m - m);
+      float s = acc.s * __expf(acc.m - m);
 #pragma unroll
-      for (int i = 0; i < N; ++i) s += expf(x.get(i) - m);
+      for (int i = 0; i < N; ++i) s += __expf(x.get(i) - m);
       acc = MS{m, s};
     }
     for (int64_t c = nvec * N + g; c < C; c += G) {
