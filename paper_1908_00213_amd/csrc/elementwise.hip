@@ -23,8 +23,17 @@ namespace {
 constexpr int kArity[CHN_OP_COUNT_] = {1, 2, 2, 2, 3, 3, 1, 2, 1, 2, 1, 2, 2, 2, 0, 1, 1, 1};
 constexpr int kScalars[CHN_OP_COUNT_] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 0, 0, 1, 0, 0, 0};
 
-template <int OP>
+// LOWP: the result is stored as bfloat16.  gelu and its derivative then use the compact forms of the
+// GEMM epilogues: absolute error 1.5e-7 in Phi, so |error| <= 1.5e-7 |x|; what is lost against the
+// library's erfc form is the relative accuracy far out in the negative tail, where the result is
+// below 1e-5 in magnitude.  A quarter of the instructions: with erfc these ops are bound by
+// arithmetic, not by HBM.
+template <int OP, bool LOWP = false>
 __device__ __forceinline__ float ew_apply(float x, float y, float z, float s) {
+  if constexpr (LOWP && OP == CHN_OP_GELU) return gelu_epi_f(x);
+  else if constexpr (LOWP && OP == CHN_OP_GELU_BWD) return x * gelu_grad_epi_f(y);
+  else if constexpr (LOWP && OP == CHN_OP_ADD_GELU) return gelu_epi_f(x + y);
+  else
   if constexpr (OP == CHN_OP_COPY) return x;
   else if constexpr (OP == CHN_OP_ADD) return x + y;
   else if constexpr (OP == CHN_OP_SUB) return x - y;
@@ -46,9 +55,10 @@ __device__ __forceinline__ float ew_apply(float x, float y, float z, float s) {
   else return 0.0f;
 }
 
+template <bool LOWP = false>
 __device__ __forceinline__ float ew_apply_rt(int op, float x, float y, float z, float s) {
   switch (op) {
-#define CHN_CASE(OPC) case OPC: return ew_apply<OPC>(x, y, z, s);
+#define CHN_CASE(OPC) case OPC: return ew_apply<OPC, LOWP>(x, y, z, s);
     CHN_CASE(CHN_OP_COPY) CHN_CASE(CHN_OP_ADD) CHN_CASE(CHN_OP_SUB) CHN_CASE(CHN_OP_MUL)
     CHN_CASE(CHN_OP_MAD) CHN_CASE(CHN_OP_MAD_RELU) CHN_CASE(CHN_OP_RELU) CHN_CASE(CHN_OP_RELU_BWD)
     CHN_CASE(CHN_OP_GELU) CHN_CASE(CHN_OP_GELU_BWD) CHN_CASE(CHN_OP_SCALE) CHN_CASE(CHN_OP_AXPY)
@@ -275,7 +285,7 @@ __global__ __launch_bounds__(kFlatThreads) void ew_flat_kernel(FlatArgs a) {
         float f[3] = {0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int k = 0; k < NIN; ++k) f[k] = a.mode[k] == MODE_SCALAR ? sc[k] : x[u][k].get(i);
-        r.set(i, ew_apply<OP>(f[0], f[1], f[2], a.s0));
+        r.set(i, ew_apply<OP, sizeof(Tout) == 2>(f[0], f[1], f[2], a.s0));
       }
       r.store_nt(static_cast<Tout *>(a.out) + v * E);
     }
@@ -291,7 +301,7 @@ __global__ __launch_bounds__(kFlatThreads) void ew_flat_kernel(FlatArgs a) {
         f[k] = a.mode[k] == MODE_SCALAR ? sc[k]
                : a.mode[k] == MODE_FULL ? Elem<Tin>::load(p + e) : Elem<Tin>::load(p + e % a.period[k]);
       }
-      Elem<Tout>::store(static_cast<Tout *>(a.out) + e, ew_apply<OP>(f[0], f[1], f[2], a.s0));
+      Elem<Tout>::store(static_cast<Tout *>(a.out) + e, ew_apply<OP, sizeof(Tout) == 2>(f[0], f[1], f[2], a.s0));
     }
   }
 }
@@ -336,7 +346,7 @@ __global__ __launch_bounds__(kRowsThreads) void ew_rows_kernel(StridedArgs a, in
       float f[3] = {0.0f, 0.0f, 0.0f};
       for (int k = 0; k < a.n_in; ++k)
         f[k] = Elem<Tin>::load(static_cast<const Tin *>(a.in[k]) + ioff[k] + c * a.istr[k][last]);
-      Elem<Tout>::store(o + c, ew_apply_rt(a.op, f[0], f[1], f[2], a.s0));
+      Elem<Tout>::store(o + c, ew_apply_rt<sizeof(Tout) == 2>(a.op, f[0], f[1], f[2], a.s0));
     }
   }
 }
@@ -355,7 +365,7 @@ __global__ __launch_bounds__(256) void ew_general_kernel(StridedArgs a) {
   }
   float f[3] = {0.0f, 0.0f, 0.0f};
   for (int k = 0; k < a.n_in; ++k) f[k] = Elem<Tin>::load(static_cast<const Tin *>(a.in[k]) + ioff[k]);
-  Elem<Tout>::store(static_cast<Tout *>(a.out) + ooff, ew_apply_rt(a.op, f[0], f[1], f[2], a.s0));
+  Elem<Tout>::store(static_cast<Tout *>(a.out) + ooff, ew_apply_rt<sizeof(Tout) == 2>(a.op, f[0], f[1], f[2], a.s0));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -406,7 +416,7 @@ __global__ __launch_bounds__(256) void ew_transpose_kernel(TransArgs a, int64_t 
         if (a.transposed[k]) f[k] = tile[k][tx][rl];
         else f[k] = Elem<Tin>::load(static_cast<const Tin *>(a.in[k]) + r * a.istr0[k] + c * a.istr1[k]);
       }
-      Elem<Tout>::store(static_cast<Tout *>(a.out) + r * a.ostr0 + c, ew_apply<OP>(f[0], f[1], f[2], a.s0));
+      Elem<Tout>::store(static_cast<Tout *>(a.out) + r * a.ostr0 + c, ew_apply<OP, sizeof(Tout) == 2>(f[0], f[1], f[2], a.s0));
     }
   }
 }
@@ -495,7 +505,7 @@ __global__ __launch_bounds__(256) void ew_transpose_vec_kernel(TransArgs a, int6
       Vec16<T> o;
 #pragma unroll
       for (int i = 0; i < E; ++i)
-        o.set(i, ew_apply<OP>(f[0][i], NIN > 1 ? f[1][i] : 0.0f, NIN > 2 ? f[2][i] : 0.0f, a.s0));
+        o.set(i, ew_apply<OP, sizeof(T) == 2>(f[0][i], NIN > 1 ? f[1][i] : 0.0f, NIN > 2 ? f[2][i] : 0.0f, a.s0));
       o.store_nt(static_cast<T *>(a.out) + r * a.ostr0 + c);
     }
   }
