@@ -121,6 +121,24 @@ def test_transposed_view(dt, shape):
     assert torch.equal(out.view(torch.int16 if dt == "bf16" else torch.int32), out2.view(torch.int16 if dt == "bf16" else torch.int32))
 
 
+def test_gelu_fp32_keeps_relative_accuracy_in_the_negative_tail():
+    # gelu(x) = x Phi(x) through an erfc whose relative error stays at a few 1e-6 in the tails: at
+    # x = -8 the result is 5e-15 and still has five correct digits
+    # (reference: x/2 erfc(-x/sqrt 2) by SciPy's erfc; the oracle's 1 + erf form cancels in float64
+    # out there, which the comparison at |x| <= 5 below shows to be the same function)
+    from scipy.special import erfc
+    x = np.linspace(-8.0, 8.0, 200001).astype(np.float32)
+    got = host(B.elementwise_broadcast("gelu", [dev(x)], empty(x.shape)))
+    ref = 0.5 * x.astype(np.float64) * erfc(-x.astype(np.float64) / np.sqrt(2.0))
+    assert np.all(np.abs(got - ref) <= 2e-5 * np.abs(ref) + 1e-38)
+    near = np.abs(x) <= 5
+    assert np.allclose(O.elementwise("gelu", [x])[near], ref[near], rtol=1e-9, atol=0)
+    gy = np.ones_like(x)
+    got = host(B.elementwise_broadcast("gelu_bwd", [dev(gy), dev(x)], empty(x.shape)))
+    ref = O.elementwise("gelu_bwd", [gy, x])
+    assert np.all(np.abs(got - ref) <= 1e-6)          # (the derivative cancels in the tail: absolute bound)
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("n_t", [2, 3])
 def test_several_transposed_operands(dt, n_t):
