@@ -747,7 +747,9 @@ constexpr int kAxisAll = CHN_AXIS_ALL;
 //               vector form: 16 bytes per lane along that range;
 //   per thread  one thread folds one result; neighbouring threads hold neighbouring results -- taken
 //               when a kept dimension is the contiguous one (column sums); vector form: each thread
-//               holds E neighbouring results and reads them with one 16-byte access per row.
+//               holds E neighbouring results and reads them with one 16-byte access per row, and 16
+//               such threads (row lanes) share a group of results, each walking every 16th row of
+//               the slice; they meet in LDS in lane order.
 // A long reduced range is cut into slices (grid dimension y) whose partial values a second kernel
 // folds in slice order.
 std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
@@ -854,7 +856,14 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
 
   o << "extern \"C\" __global__ __launch_bounds__(256) void " << k.name << "(const chn_slots chn_s) {\n";
   decl(o);
-  if (p.per_thread) {
+  if (p.per_thread && E > 1) {
+    // 16 groups of E neighbouring results x 16 row lanes: a lane walks every 16th element of the
+    // slice, the lanes of a group meet in LDS in a fixed order
+    o << "  const int chn_tx = threadIdx.x & 15, chn_ty = threadIdx.x >> 4;\n"
+      << "  __shared__ chn_R chn_sm[16][16 * " << E << " + 1];\n"
+      << "  long long chn_res = ((long long)blockIdx.x * 16 + chn_tx) * " << E << ";\n"
+      << "  const bool chn_live = chn_res < chn_nres;\n  if (!chn_live) chn_res = 0;   // (stays in the barrier; reads and writes nothing)\n";
+  } else if (p.per_thread) {
     o << "  const long long chn_res = ((long long)blockIdx.x * 256 + threadIdx.x) * " << E << ";\n  if (chn_res >= chn_nres) return;\n";
   } else {
     o << "  __shared__ chn_R chn_sm[256];\n  const long long chn_res = blockIdx.x;\n";
@@ -865,7 +874,7 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
   if (p.per_thread && E > 1) {
     // E neighbouring results per thread: the last kept dimension is contiguous in every input
     o << "  chn_R chn_acc[" << E << "];\n#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j) chn_acc[chn_j] = (chn_R)(" << k.identity << ");\n";
-    o << "#pragma unroll 4\n  for (long long chn_r = chn_lo; chn_r < chn_hi; ++chn_r) {\n";
+    o << "#pragma unroll 4\n  for (long long chn_r = chn_lo + chn_ty; chn_live && chn_r < chn_hi; chn_r += 16) {\n";
     reduce_offsets(o, "    ");
     for (int i = 0; i < n_in; ++i) {
       const int a = p.arr_of_in[i];
@@ -877,6 +886,11 @@ std::string rd_source(const chn_user_kernel &k, const RdPlan &p) {
       if (a >= 0) o << "      const " << compute_type(b.in_dtype[i]) << " chn_x" << i << " = chn_io<" << storage_type(b.in_dtype[i]) << ">::up(chn_k" << a << ".e[chn_j]);\n";
     }
     o << "      chn_acc[chn_j] = chn_fold(chn_acc[chn_j], chn_map(" << in_args << "(chn_res + chn_j) * chn_R_len + chn_r));\n    }\n  }\n";
+    o << "#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j) chn_sm[chn_ty][chn_tx * " << E << " + chn_j] = chn_acc[chn_j];\n"
+      << "  __syncthreads();\n  if (chn_ty != 0 || !chn_live) return;\n"
+      << "#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j) {\n    chn_R chn_a = chn_sm[0][chn_tx * " << E << " + chn_j];\n"
+      << "#pragma unroll\n    for (int chn_y = 1; chn_y < 16; ++chn_y) chn_a = chn_fold(chn_a, chn_sm[chn_y][chn_tx * " << E << " + chn_j]);\n"
+      << "    chn_acc[chn_j] = chn_a;\n  }\n";
     o << "  if (chn_slices > 1) {\n#pragma unroll\n    for (int chn_j = 0; chn_j < " << E << "; ++chn_j) chn_part[(long long)blockIdx.y * chn_nres + chn_res + chn_j] = chn_acc[chn_j];\n    return;\n  }\n";
     o << "#pragma unroll\n  for (int chn_j = 0; chn_j < " << E << "; ++chn_j)\n";
     // the E results differ only in the last kept dimension: their outputs are one stride apart
@@ -1058,10 +1072,15 @@ chn_status rd_plan(chn_user_kernel *k, int n_in, const chn_array *const *in, int
   }
   // slices of the reduced range so that the launch fills the chip; each slice at least 64 (per
   // thread) or 4096 (per block) elements long and a whole number of vectors
-  const int64_t blocks = p->per_thread ? (p->n_res / p->E + 255) / 256 : p->n_res;
+  const bool lanes = p->per_thread && p->E > 1;   // 16 result groups x 16 row lanes per block
+  const int64_t blocks = lanes ? (p->n_res / p->E + 15) / 16 : p->per_thread ? (p->n_res / p->E + 255) / 256 : p->n_res;
   const int64_t min_len = p->per_thread ? 64 : 4096;
   int64_t s = blocks >= 2048 ? 1 : (2048 + blocks - 1) / blocks;
   s = std::min<int64_t>(s, std::max<int64_t>(1, p->R / min_len));
+  if (lanes) {   // many short blocks stream best: 8 elements per lane (16 of 2-byte types), at most 16384 blocks
+    s = std::max<int64_t>(1, p->R / (16 * (p->E > 4 ? 16 : 8)));
+    if (blocks * s > 16384) s = std::max<int64_t>(1, 16384 / blocks);
+  }
   s = std::min<int64_t>(s, 1024);
   p->chunk = p->R == 0 ? 1 : (p->R + s - 1) / s;
   p->chunk = (p->chunk + p->E - 1) / p->E * p->E;
@@ -1233,7 +1252,7 @@ chn_status chn_reduction_kernel_launch(chn_user_kernel *k, int n_in, const chn_a
   CHN_TRY(function_for(k, p.key, p.src, true, &f));
   Slots s;
   rd_slots(p, n_in, in, n_out, out, scalars, p.slices > 1 ? ws : nullptr, &s);
-  const int64_t gx = p.per_thread ? (p.n_res / p.E + 255) / 256 : p.n_res;
+  const int64_t gx = p.per_thread && p.E > 1 ? (p.n_res / p.E + 15) / 16 : p.per_thread ? (p.n_res / p.E + 255) / 256 : p.n_res;
   if (gx > 0x7fffffffll || p.slices > 65535) return fail(CHN_ERR_SHAPE, "%s: too many results for one launch", k->name.c_str());
   CHN_TRY(launch(k, f.fn, (unsigned)gx, (unsigned)p.slices, 256, s, p.n_slots, stream));
   if (p.slices > 1)

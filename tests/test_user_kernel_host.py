@@ -202,8 +202,10 @@ def test_reduction_declaration_shapes_and_workspace(cache):
     assert L2.chn_reduction_kernel_prepare(s._h, 1, B._ptrs([y4]), 1, B._ptrs([fake((50, 70))]), 0x40000000 + (1 << 5), 0) == -7
     src_row = s.source(x, fake((8192,)), axis=1)
     src_col = s.source(x, fake((4096,)), axis=0)
-    assert "__shared__" in src_row.split("_finish")[0] and "__shared__" not in src_col.split("_finish")[0]
+    assert "chn_sm[256]" in src_row.split("_finish")[0]                            # a block folds a row
+    assert "chn_sm[16][16 * 4 + 1]" in src_col.split("_finish")[0]                 # 16 row lanes share 4 columns
     assert "chn_pack<float, 4>" in src_row and "chn_acc[4]" in src_col             # 16 bytes per lane in both
+    assert "__shared__" not in s.source(fake((8192, 4095)), fake((4095,)), axis=0).split("_finish")[0]   # scalar form: a thread per column
     odd = fake((8192, 4095))
     assert "chn_pack<float" not in s.source(odd, fake((8192,)), axis=1)              # rows off the vector grid
     assert "chn_pack<float" not in s.source(odd, fake((4095,)), axis=0)
