@@ -239,6 +239,16 @@ chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels,
                               const chn_array *dlogits, void *ws, size_t ws_bytes,
                               chn_stream stream);
 
+/* Both of the above in one call, for a training step, where the gradient follows the loss at once:
+ * loss_mean, lse (or NULL) and dlogits as defined there, the logits read from memory once.  dlogits
+ * may be the logits array itself (same dtype and row pitch).  A problem of at most 64 classes and
+ * 8192 rows runs as a single launch of a single workgroup and needs no workspace; otherwise the
+ * workspace is that of chn_softmax_ce_fwd.  Errors as for the two separate calls. */
+chn_status chn_softmax_ce_fwd_bwd(const chn_array *logits, const chn_array *labels,
+                                  int64_t ignore_label, const chn_array *loss_mean,
+                                  const chn_array *lse, float upstream, const chn_array *dlogits,
+                                  void *ws, size_t ws_bytes, chn_stream stream);
+
 /* ---- optimiser --------------------------------------------------------------------------------------
  * Stochastic gradient descent (Section "Background and Motivation" names it as the optimiser of the
  * run phase): param <- param - lr * grad, no momentum, decay or clipping.  param, grad: F32,

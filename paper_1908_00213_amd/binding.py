@@ -27,7 +27,7 @@ EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_argmax_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
-           "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd",
+           "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan",
            "chn_user_kernel_config", "chn_user_kernel_stats", "chn_user_kernel_destroy",
@@ -93,6 +93,7 @@ def lib():
     L.chn_softmax_ce_workspace_bytes.restype = C.c_size_t
     L.chn_softmax_ce_fwd.argtypes = [AP, AP, C.c_int64, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_softmax_ce_bwd.argtypes = [AP, AP, C.c_int64, AP, C.c_float, AP, vp, C.c_size_t, st]
+    L.chn_softmax_ce_fwd_bwd.argtypes = [AP, AP, C.c_int64, AP, AP, C.c_float, AP, vp, C.c_size_t, st]
     L.chn_sgd_update.argtypes = [AP, AP, C.c_float, AP, st]
     L.chn_sgd_update_multi.argtypes = [C.c_int, APP, APP, C.c_float, APP, st]
     L.chn_adam_update_multi.argtypes = [C.c_int, APP, APP, APP, APP, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int64, APP, st]
@@ -301,6 +302,15 @@ def softmax_ce_bwd(logits, labels, dlogits, lse=None, upstream=1.0, ignore_label
                                     _ref(desc(lse)), float(upstream), _ref(desc(dlogits)), p, n,
                                     _stream() if stream is None else stream))
     return dlogits
+
+
+def softmax_ce_fwd_bwd(logits, labels, loss_mean, dlogits, lse=None, upstream=1.0, ignore_label=-1, ws=None,
+                       stream=None):
+    p, n = _ws(ws)
+    _check(lib().chn_softmax_ce_fwd_bwd(_ref(desc(logits)), _ref(desc(labels)), int(ignore_label), _ref(desc(loss_mean)),
+                                        _ref(desc(lse)), float(upstream), _ref(desc(dlogits)), p, n,
+                                        _stream() if stream is None else stream))
+    return loss_mean
 
 
 def sgd_update(param, grad, lr, lowp_copy=None, stream=None):

@@ -150,27 +150,9 @@ __global__ __launch_bounds__(1024) void sce_scale_kernel(const L *labels, int64_
   }
 }
 
-template <typename T, typename TO, typename L, int G, bool VEC>
-__global__ __launch_bounds__(256) void sce_bwd_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
-                                                      int64_t ignore, const float *lse_in, const float *scale_ptr,
-                                                      TO *dz, int64_t dpitch) {
-  __shared__ MS smem[4];
-  const int g = threadIdx.x % G;
-  int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
-  const bool live = row < N;
-  if (!live) row = N - 1;
-  const T *p = z + row * pitch;
-  float lse;
-  if (lse_in) {
-    lse = lse_in[row];
-  } else {
-    MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
-    lse = v.m + logf(v.s);
-  }
-  if (!live) return;
-  const int64_t t = (int64_t)labels[row];
-  const float scale = t == ignore ? 0.0f : *scale_ptr;
-  TO *q = dz + row * dpitch;
+// Gradient of one row, lane g of G: dz[c] = scale * (exp(z[c] - lse) - [c == t]).
+template <typename T, typename TO, int G, bool VEC>
+__device__ __forceinline__ void row_grad(const T *p, TO *q, int64_t C, int g, int64_t t, float lse, float scale) {
   if constexpr (VEC) {
     constexpr int NI = Vec16<T>::N, NO = Vec16<TO>::N;
     constexpr int E = NI > NO ? NI : NO;  // elements per step: whole 16-byte vectors on both sides
@@ -198,6 +180,104 @@ __global__ __launch_bounds__(256) void sce_bwd_kernel(const T *z, int64_t pitch,
       float pr = scale == 0.0f ? 0.0f : expf(Elem<T>::load(p + c) - lse);
       Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
     }
+  }
+}
+
+template <typename T, typename TO, typename L, int G, bool VEC>
+__global__ __launch_bounds__(256) void sce_bwd_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
+                                                      int64_t ignore, const float *lse_in, const float *scale_ptr,
+                                                      TO *dz, int64_t dpitch) {
+  __shared__ MS smem[4];
+  const int g = threadIdx.x % G;
+  int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+  const bool live = row < N;
+  if (!live) row = N - 1;
+  const T *p = z + row * pitch;
+  float lse;
+  if (lse_in) {
+    lse = lse_in[row];
+  } else {
+    MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
+    lse = v.m + logf(v.s);
+  }
+  if (!live) return;
+  const int64_t t = (int64_t)labels[row];
+  const float scale = t == ignore ? 0.0f : *scale_ptr;
+  row_grad<T, TO, G, VEC>(p, dz + row * dpitch, C, g, t, lse, scale);
+}
+
+// Forward and backward of a row in one visit: log-sum-exp and loss first, then the gradient while the
+// row is still in the caches (the logits travel from HBM once instead of twice).  dz may be the
+// logits' own buffer: a lane overwrites only elements that it has read itself, after the whole row
+// has been scanned.
+template <typename T, typename TO, typename L, int G, bool VEC>
+__global__ __launch_bounds__(256) void sce_fused_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
+                                                        int64_t ignore, const float *scale_ptr, float *loss_rows, float *lse_out,
+                                                        TO *dz, int64_t dpitch) {
+  __shared__ MS smem[4];
+  const int g = threadIdx.x % G;
+  int64_t row = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+  const bool live = row < N;
+  if (!live) row = N - 1;
+  const T *p = z + row * pitch;
+  const MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
+  const float lse = v.m + logf(v.s);
+  const int64_t t = (int64_t)labels[row];
+  float zt = 0.0f;
+  if (g == 0 && live && t != ignore) zt = Elem<T>::load(p + t);   // (read before the row may be overwritten)
+  if constexpr (G == 256) __syncthreads();
+  else __builtin_amdgcn_wave_barrier();
+  if (!live) return;
+  if (g == 0) {
+    if (lse_out) lse_out[row] = lse;
+    loss_rows[row] = t == ignore ? 0.0f : lse - zt;
+  }
+  row_grad<T, TO, G, VEC>(p, dz + row * dpitch, C, g, t, lse, t == ignore ? 0.0f : *scale_ptr);
+}
+
+// A whole small problem (few classes, a few thousand rows) in one launch of one block: count the
+// valid rows, then every thread takes rows tid, tid + 1024, ... from log-sum-exp to gradient, then the
+// mean loss in a fixed order.  For the small MLP steps, which are bound by the number of launches.
+template <typename T, typename TO, typename L>
+__global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
+                                                         int64_t ignore, float upstream, float *loss_mean, float *lse_out,
+                                                         TO *dz, int64_t dpitch) {
+  __shared__ float ssum[16];
+  __shared__ int scnt[16];
+  int cnt = 0;
+  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += ((int64_t)labels[n] != ignore) ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if ((threadIdx.x & 63) == 0) scnt[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  int valid = 0;
+  for (int w = 0; w < 16; ++w) valid += scnt[w];
+  const float scale_all = valid > 0 ? upstream / (float)valid : 0.0f;
+  float s = 0.0f;
+  for (int64_t n = threadIdx.x; n < N; n += 1024) {
+    const T *p = z + n * pitch;
+    float m = -INFINITY;
+    for (int64_t c = 0; c < C; ++c) m = fmaxf(m, Elem<T>::load(p + c));
+    float e = 0.0f;
+    for (int64_t c = 0; c < C; ++c) e += expf(Elem<T>::load(p + c) - m);
+    const float lse = m + logf(e);
+    const int64_t t = (int64_t)labels[n];
+    if (lse_out) lse_out[n] = lse;
+    if (t != ignore) s += lse - Elem<T>::load(p + t);
+    const float scale = t == ignore ? 0.0f : scale_all;
+    TO *q = dz + n * dpitch;
+    for (int64_t c = 0; c < C; ++c) {
+      const float pr = scale == 0.0f ? 0.0f : expf(Elem<T>::load(p + c) - lse);
+      Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
+    }
+  }
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.0f;
+    for (int w = 0; w < 16; ++w) tot += ssum[w];
+    *loss_mean = valid > 0 ? tot / (float)valid : 0.0f;
   }
 }
 
@@ -255,6 +335,26 @@ void launch_bwd(const Common &c, const chn_array *logits, const chn_array *label
   else if (c.G == 64) { if (vec) CHN_BWD(64, true); else CHN_BWD(64, false); }
   else CHN_BWD(8, false);
 #undef CHN_BWD
+}
+
+template <typename T, typename TO, typename L>
+void launch_fused(const Common &c, const chn_array *logits, const chn_array *labels, int64_t ignore, const float *scale, float *rows,
+                  float *lse, const chn_array *dl, int64_t dpitch, bool vec, hipStream_t st) {
+  const T *z = static_cast<const T *>(logits->data);
+  const L *t = static_cast<const L *>(labels->data);
+  TO *d = static_cast<TO *>(dl->data);
+#define CHN_FUSED(G, V) hipLaunchKernelGGL((sce_fused_kernel<T, TO, L, G, V>), dim3((unsigned)((c.N + 256 / G - 1) / (256 / G))), dim3(256), 0, st, z, c.pitch, t, c.N, c.C, ignore, scale, rows, lse, d, dpitch)
+  if (c.G == 256) { if (vec) CHN_FUSED(256, true); else CHN_FUSED(256, false); }
+  else if (c.G == 64) { if (vec) CHN_FUSED(64, true); else CHN_FUSED(64, false); }
+  else CHN_FUSED(8, false);
+#undef CHN_FUSED
+}
+
+template <typename T, typename TO, typename L>
+void launch_small(const Common &c, const chn_array *logits, const chn_array *labels, int64_t ignore, float upstream, float *loss_mean,
+                  float *lse, const chn_array *dl, int64_t dpitch, hipStream_t st) {
+  hipLaunchKernelGGL((sce_small_kernel<T, TO, L>), dim3(1), dim3(1024), 0, st, static_cast<const T *>(logits->data), c.pitch,
+                     static_cast<const L *>(labels->data), c.N, c.C, ignore, upstream, loss_mean, lse, static_cast<TO *>(dl->data), dpitch);
 }
 
 }  // namespace
@@ -339,6 +439,65 @@ chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels, 
   else CHN_GO(bf16_raw, bf16_raw);
 #undef CHN_GO
   return check_launch("softmax_ce_bwd rows");
+}
+
+chn_status chn_softmax_ce_fwd_bwd(const chn_array *logits, const chn_array *labels, int64_t ignore_label,
+                                  const chn_array *loss_mean, const chn_array *lse, float upstream,
+                                  const chn_array *dlogits, void *ws, size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  Common c;
+  CHN_TRY(check_common(logits, labels, &c));
+  CHN_TRY(validate(loss_mean, "loss_mean", true));
+  if (loss_mean->dtype != CHN_F32 || numel(loss_mean) != 1)
+    return fail(CHN_ERR_SHAPE, "softmax_ce: loss_mean must be a single F32 value");
+  if (lse) CHN_TRY(check_rows_f32(lse, "lse", c.N));
+  CHN_TRY(validate(dlogits, "dlogits", true));
+  if (!is_float(dlogits->dtype)) return fail(CHN_ERR_DTYPE, "softmax_ce: dlogits must be F32 or BF16");
+  int64_t dn, dc, dpitch;
+  CHN_TRY(row_major_2d(dlogits, "dlogits", &dn, &dc, &dpitch));
+  if (dn != c.N || dc != c.C) return fail(CHN_ERR_SHAPE, "softmax_ce: dlogits must have the logits' shape");
+  if (c.N > 0 && dlogits->data == logits->data && (dlogits->dtype != logits->dtype || dpitch != c.pitch))
+    return fail(CHN_ERR_STRIDE, "softmax_ce: a gradient written over the logits needs their dtype and row pitch");
+  hipStream_t st = as_stream(stream);
+  float *lm = static_cast<float *>(loss_mean->data);
+  float *l = lse ? static_cast<float *>(lse->data) : nullptr;
+  const bool i32 = labels->dtype == CHN_I32;
+  const bool zin32 = logits->dtype == CHN_F32, zout32 = dlogits->dtype == CHN_F32;
+  if (c.N == 0 || (c.C <= 64 && c.N <= 8192)) {         // (no rows: the mean of nothing is written as 0)
+#define CHN_GO(T, TO)                                                                                        \
+  do {                                                                                                       \
+    if (i32) launch_small<T, TO, int32_t>(c, logits, labels, ignore_label, upstream, lm, l, dlogits, dpitch, st); \
+    else launch_small<T, TO, int64_t>(c, logits, labels, ignore_label, upstream, lm, l, dlogits, dpitch, st);     \
+  } while (0)
+    if (zin32 && zout32) CHN_GO(float, float);
+    else if (zin32 && !zout32) CHN_GO(float, bf16_raw);
+    else if (!zin32 && zout32) CHN_GO(bf16_raw, float);
+    else CHN_GO(bf16_raw, bf16_raw);
+#undef CHN_GO
+    return check_launch("softmax_ce_fwd_bwd (one block)");
+  }
+  CHN_TRY(check_ws(ws, ws_bytes, chn_softmax_ce_workspace_bytes(c.N), "softmax_ce_fwd_bwd"));
+  float *scale = static_cast<float *>(ws);
+  float *rows = reinterpret_cast<float *>(static_cast<char *>(ws) + 256);
+  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  CHN_TRY(check_launch("softmax_ce_fwd_bwd scale"));
+  const int no = 16 / dtype_size(dlogits->dtype);
+  const bool vec = c.vec && reinterpret_cast<uintptr_t>(dlogits->data) % 16 == 0 && dpitch % no == 0;
+#define CHN_GO(T, TO)                                                                                              \
+  do {                                                                                                             \
+    if (i32) launch_fused<T, TO, int32_t>(c, logits, labels, ignore_label, scale, rows, l, dlogits, dpitch, vec, st); \
+    else launch_fused<T, TO, int64_t>(c, logits, labels, ignore_label, scale, rows, l, dlogits, dpitch, vec, st);     \
+  } while (0)
+  if (zin32 && zout32) CHN_GO(float, float);
+  else if (zin32 && !zout32) CHN_GO(float, bf16_raw);
+  else if (!zin32 && zout32) CHN_GO(bf16_raw, float);
+  else CHN_GO(bf16_raw, bf16_raw);
+#undef CHN_GO
+  CHN_TRY(check_launch("softmax_ce_fwd_bwd rows"));
+  if (i32) hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, ignore_label, lm);
+  else hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, ignore_label, lm);
+  return check_launch("softmax_ce_fwd_bwd mean");
 }
 
 }  // extern "C"

@@ -141,9 +141,9 @@ class MLPTrainer:
                   epi="bias" if last else fwd_epi, bias=self.b[l],
                   pre=None if last or self.act == "relu" else self.z[l + 1])
         wp, wn = p.ws(self.ws_ce)
-        p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
+        # loss and its gradient in one call (the logits are read once; one launch for the small models)
+        p.add(L.chn_softmax_ce_fwd_bwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
         # backward, reverse order
-        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(t), -1, p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
         rp, rn = p.ws(self.ws_red)
         for l in range(n - 1, -1, -1):
             dv = self.dv[l + 1]
@@ -310,9 +310,8 @@ class LSTMTrainer:
         Hall, Hprev = self._Hs[Bn:], self._Hs[:T * Bn]
         _gemm(p, L, Hall, Pl["W_out"].t(), self.logits, epi="bias", bias=P["b_out"])
         wp, wn = p.ws(self.ws_ce)
-        p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
-        # backward (in fp32 the logit gradients overwrite the logits in place)
-        p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.lse), C.c_float(1.0), p.d(dlog), wp, wn)
+        # loss and gradient in one visit of every row (in fp32 the logit gradients overwrite the logits)
+        p.add(L.chn_softmax_ce_fwd_bwd, p.d(self.logits), p.d(tg_f), -1, p.d(self.loss), p.d(self.lse), C.c_float(1.0), p.d(dlog), wp, wn)
         rp, rn = p.ws(self.ws_red)
         if self.lowp:
             _gemm(p, L, dlog.t(), Hall, self._g["W_out"])

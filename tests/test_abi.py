@@ -118,6 +118,12 @@ def test_reduce_gemm_and_layer_validation():
     assert L.chn_softmax_ce_fwd(C.byref(c), C.byref(f((4,), (4,), B.F32)), -1, C.byref(one), None, None, None, 0, None) == -3
     assert L.chn_softmax_ce_fwd(C.byref(c), C.byref(lab), -1, C.byref(one), None, None, None, 0, None) == -8
     assert L.chn_softmax_ce_workspace_bytes(1000) >= 4256
+    fb = lambda z, t, d: L.chn_softmax_ce_fwd_bwd(C.byref(z), C.byref(t), -1, C.byref(one), None, 1.0, C.byref(d), None, 0, None)
+    big, blab = f((100, 1000), (4000, 4)), f((100,), (4,), B.I32)
+    assert fb(c, f((5,), (4,), B.I32), c) == -4                               # one label per row
+    assert fb(c, lab, f((4, 9), (36, 4))) == -4                               # the gradient has the logits' shape
+    assert fb(c, lab, f((4, 8), (32, 4), B.I32)) == -3
+    assert fb(big, blab, big) == -8                                           # many classes: workspace required
     assert L.chn_sgd_update(C.byref(c), C.byref(z), 0.1, None, None) == -4
     assert L.chn_sgd_update(C.byref(c), C.byref(f((4, 8), (64, 4))), 0.1, None, None) == -5
     assert L.chn_sgd_update(C.byref(c), C.byref(c), 0.1, C.byref(c), None) == -3

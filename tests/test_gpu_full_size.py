@@ -183,7 +183,7 @@ def test_config4_full_size_step_sampled():
     # run the recorded calls one by one; keep the logits before the gradient overwrites them in place
     logits = None
     for fn, args in prog.calls:
-        if fn is L.chn_softmax_ce_bwd and logits is None:
+        if fn is L.chn_softmax_ce_fwd_bwd and logits is None:
             logits = tr.logits.cpu().numpy()
         B._check(fn(*args, None))
     torch.cuda.synchronize()

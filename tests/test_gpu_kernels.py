@@ -330,6 +330,49 @@ def test_softmax_ce(N, Cn, dt, lab):
         check(host(zc), ref, TOL_EW * 10, 1.5 / nv, "in place")
 
 
+@pytest.mark.parametrize("N,Cn,dt,lab", [(37, 10, "f32", np.int32), (1024, 10, "f32", np.int64), (3000, 33, "bf16", np.int32),   # one block
+                                         (8193, 10, "f32", np.int32), (300, 1000, "f32", np.int64), (70, 4100, "f32", np.int32),
+                                         (129, 1000, "bf16", np.int32), (33, 2051, "bf16", np.int64), (5, 65, "f32", np.int32)])
+def test_softmax_ce_loss_and_gradient_in_one_call(N, Cn, dt, lab):
+    z = rnd((N, Cn), dt, -6, 6)
+    t = RNG.integers(0, Cn, size=(N,)).astype(lab)
+    t[::7] = -1
+    zd, td = dev(z, dt), dev(t)
+    w = ws(B.softmax_ce_workspace_bytes(N))
+    rl, _, rlse, nv = O.softmax_ce_fwd(z, t)
+    ref = O.softmax_ce_bwd(z, t, -1, 1.5)
+    for out_dt in ("f32", "bf16"):
+        loss, lse, dz = empty(()), empty((N,)), empty((N, Cn), out_dt)
+        B.softmax_ce_fwd_bwd(zd, td, loss, dz, lse, 1.5, ws=w)
+        check(host(loss), np.array(rl), TOL_SUM, None, "loss mean")
+        check(host(lse), rlse, TOL_EW * 10, None, "lse")
+        check(host(dz), ref, tol_for(dt, out_dt, TOL_EW * 10), 1.5 / nv, "dlogits")
+        assert np.all(host(dz)[t == -1] == 0)
+    # against the two separate calls (the gradient kernel is shared on the many-class path)
+    l2, lse2 = empty(()), empty((N,))
+    B.softmax_ce_fwd(zd, td, l2, None, lse2, ws=w)
+    d2 = B.softmax_ce_bwd(zd, td, empty((N, Cn)), lse2, 1.5, ws=w)
+    loss, dz = empty(()), empty((N, Cn))
+    B.softmax_ce_fwd_bwd(zd, td, loss, dz, None, 1.5, ws=w)          # lse not asked for
+    assert abs(float(loss.cpu()) - float(l2.cpu())) <= 1e-6 * abs(float(l2.cpu()))
+    assert np.max(np.abs(host(dz) - host(d2))) <= 1e-6 * 1.5 / nv
+    # written over the logits
+    zc = zd.clone()
+    loss3 = empty(())
+    B.softmax_ce_fwd_bwd(zc, td, loss3, zc, None, 1.5, ws=w)
+    check(host(zc), ref, tol_for(dt, dt, TOL_EW * 10), 1.5 / nv, "in place")
+    check(host(loss3), np.array(rl), TOL_SUM, None, "loss mean, in place")
+    with pytest.raises(B.ChnError):
+        B.softmax_ce_fwd_bwd(zd, td, loss, empty((N, Cn + 1)), None, 1.0, ws=w)
+    # every row ignored; no rows at all
+    tn = np.full(N, -1, lab)
+    B.softmax_ce_fwd_bwd(zd, dev(tn), loss, dz, None, 1.0, ws=w)
+    assert float(loss.cpu()) == 0.0 and np.all(host(dz) == 0)
+    loss.fill_(7.0)
+    B.softmax_ce_fwd_bwd(empty((0, Cn), dt), dev(np.zeros(0, lab)), loss, empty((0, Cn)), None, 1.0, ws=w)
+    assert float(loss.cpu()) == 0.0
+
+
 def test_softmax_ce_closed_forms():
     for Cn in (10, 1000, 10000):
         z = np.zeros((4, Cn), dtype=np.float32)
