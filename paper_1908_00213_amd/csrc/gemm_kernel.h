@@ -118,7 +118,7 @@ struct TileLoader {
   static constexpr int NBLK = 8 * ROWS / EPC;               // EPC x EPC transpose blocks per tile
   static constexpr int NB = (NBLK + 255) / 256;             // ... per thread
   static constexpr int NSLOT = KC ? NS : NB;
-  uint4 reg[KC ? NS : NB * EPC];
+  uint4 reg[2][KC ? NS : NB * EPC];   // two sets of staging registers (the second only where a kernel looks two tiles ahead)
   uintptr_t ptr[NSLOT];   // address of the slot's first element for k0 = 0
   int lim[NSLOT];         // KC: K - (k offset of the slot) for valid rows, else 0;  MC: rows_total - m or 0
   int64_t kstride;        // bytes between consecutive k (MC only)
@@ -159,12 +159,13 @@ struct TileLoader {
     }
   }
 
-  // issue the global loads of the tile whose first k is k0
+  // issue the global loads of the tile whose first k is k0 (into register set SET)
+  template <int SET = 0>
   __device__ __forceinline__ void issue(int k0) {
     if constexpr (KC) {
 #pragma unroll
       for (int i = 0; i < NS; ++i)
-        reg[i] = load_chunk<T, PB>(ptr[i] + (int64_t)k0 * (int64_t)sizeof(T), lim[i] - k0);
+        reg[SET][i] = load_chunk<T, PB>(ptr[i] + (int64_t)k0 * (int64_t)sizeof(T), lim[i] - k0);
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
@@ -172,7 +173,7 @@ struct TileLoader {
 #pragma unroll
         for (int j = 0; j < EPC; ++j) {
           const int k = k0 + kg * EPC + j;
-          reg[b * EPC + j] = load_chunk<T, PB>(ptr[b] + (int64_t)(k0 + j) * kstride, k < K ? lim[b] : 0);
+          reg[SET][b * EPC + j] = load_chunk<T, PB>(ptr[b] + (int64_t)(k0 + j) * kstride, k < K ? lim[b] : 0);
         }
       }
     }
@@ -186,12 +187,13 @@ struct TileLoader {
     return global_load<uint32_t>(k0 < pf_lim ? a : zero);
   }
 
+  template <int SET = 0>
   __device__ __forceinline__ void store(char *lds) const {
     if constexpr (KC) {
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
         const int s = threadIdx.x + i * 256;
-        *reinterpret_cast<uint4 *>(lds + lds_off<T>(s >> 3, s & 7)) = reg[i];
+        *reinterpret_cast<uint4 *>(lds + lds_off<T>(s >> 3, s & 7)) = reg[SET][i];
       }
     } else {
 #pragma unroll
@@ -201,7 +203,7 @@ struct TileLoader {
           if (blk >= NBLK) continue;       // big tile's loop would split its scheduling region
         }
         const int kg = blk & 7, mc = blk >> 3;
-        const uint4 *r = &reg[b * EPC];
+        const uint4 *r = &reg[SET][b * EPC];
 #pragma unroll
         for (int e = 0; e < EPC; ++e) {
           uint4 o;
@@ -720,6 +722,43 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int NR = TM + TN;                              // fragment reads per k-step
   constexpr bool kSched = TM == 4 && TN == 4;              // explicit interleaving for the big tile
 
+  // The small tiles look two tiles ahead: with few MFMAs per tile step, the two k-steps between the
+  // issue of a tile's loads and their move to LDS do not cover a trip to memory, and a workgroup that
+  // is alone on its compute unit (small products) then runs at one memory latency per tile step.  Two
+  // sets of staging registers take turns, the loop is written out for both so that each set is named
+  // at compile time: a tile's loads are issued right after the set has been emptied, a whole tile step
+  // before they are needed.
+  constexpr bool kDeep = TM * TN <= 4;
+  if constexpr (kDeep) {
+    la.template issue<0>((kt0 + 1) * BK);
+    lb.template issue<0>((kt0 + 1) * BK);
+    la.template issue<1>((kt0 + 2) * BK);
+    lb.template issue<1>((kt0 + 2) * BK);
+    auto step = [&](auto set_c, int kt) __attribute__((always_inline)) {
+      constexpr int SET = decltype(set_c)::value;
+      const char *cur = lds + ((kt - kt0) & 1) * STAGE;
+      char *nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
+      f1.read(cur + a_row, cur + b_row, koff[1]);
+      mma<T, TM, TN>(acc, f0);
+      f0.read(cur + a_row, cur + b_row, koff[2]);
+      mma<T, TM, TN>(acc, f1);
+      f1.read(cur + a_row, cur + b_row, koff[3]);
+      la.template store<SET>(nxt);                    // tile kt + 1, on its way since the step before
+      lb.template store<SET>(nxt + A_BYTES);
+      la.template issue<SET>((kt + 3) * BK);          // (past the end of K: zeros, never used)
+      lb.template issue<SET>((kt + 3) * BK);
+      mma<T, TM, TN>(acc, f0);
+      __syncthreads();
+      f0.read(nxt + a_row, nxt + b_row, koff[0]);
+      mma<T, TM, TN>(acc, f1);
+    };
+    int kt = kt0;
+    for (; kt + 1 < nk; kt += 2) {
+      step(std::integral_constant<int, 0>{}, kt);
+      step(std::integral_constant<int, 1>{}, kt + 1);
+    }
+    if (kt < nk) step(std::integral_constant<int, 0>{}, kt);
+  } else
   for (int kt = kt0; kt < nk; ++kt) {
     const char *cur = lds + ((kt - kt0) & 1) * STAGE;
     char *nxt = lds + ((kt - kt0 + 1) & 1) * STAGE;
