@@ -96,7 +96,7 @@ def _gemm(p, L, A, Bm, Cm, alpha=1.0, beta=0.0, epi="none", bias=None, aux=None,
 class MLPTrainer:
     """Forward + backward + SGD for an MLP with softmax cross-entropy (workloads 1, 3 and 5)."""
 
-    def __init__(self, params, batch, act="relu", lr=0.01, lowp=False, fused_update=False):
+    def __init__(self, params, batch, act="relu", lr=0.01, lowp=False, fused_update=False, fused_loss=True):
         """fused_update: the weight-gradient product of every layer applies the SGD update in its
         epilogue (alpha = -lr, beta = 1 on the fp32 weights, bf16 working copy refreshed in the same
         pass), so weight gradients never travel through memory and `dW` stays unwritten; the input
@@ -104,6 +104,7 @@ class MLPTrainer:
         self.L = B.lib()
         self.act, self.lr, self.lowp, self.batch = act, float(lr), lowp, batch
         self.fused_update = fused_update
+        self.fused_loss = fused_loss      # loss and its gradient in one call (else the two separate calls)
         self.W = [_dev(W) for W, _ in params]
         self.b = [_dev(b) for _, b in params]
         self.Wl = [w.to(torch.bfloat16) for w in self.W] if lowp else self.W
@@ -142,7 +143,11 @@ class MLPTrainer:
                   pre=None if last or self.act == "relu" else self.z[l + 1])
         wp, wn = p.ws(self.ws_ce)
         # loss and its gradient in one call (the logits are read once; one launch for the small models)
-        p.add(L.chn_softmax_ce_fwd_bwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
+        if self.fused_loss:
+            p.add(L.chn_softmax_ce_fwd_bwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
+        else:
+            p.add(L.chn_softmax_ce_fwd, p.d(self.logits), p.d(t), -1, p.d(self.loss), None, p.d(self.lse), wp, wn)
+            p.add(L.chn_softmax_ce_bwd, p.d(self.logits), p.d(t), -1, p.d(self.lse), C.c_float(1.0), p.d(self.dv[n]), wp, wn)
         # backward, reverse order
         rp, rn = p.ws(self.ws_red)
         for l in range(n - 1, -1, -1):

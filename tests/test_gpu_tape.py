@@ -63,10 +63,11 @@ def test_tape_mlp_steps_match_the_oracle():
 
 
 def test_tape_mlp_equals_the_recorded_step_bit_for_bit_in_fp32():
-    # same kernels on the same operands; only who decides the order of the calls differs
+    # same kernels on the same operands; only who decides the order of the calls differs (the recorded
+    # step is told to take the loss and its gradient as two calls, as a tape has to)
     w = W.config3(n_batches=1)
     model, opt, xd, td = run_mlp(w, False, 1e-4)
-    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, False)
+    tr = steps.MLPTrainer(w.params, w.batch, w.act, w.lr, False, fused_loss=False)
     tr.step(xd, td)
     for l, layer in enumerate(model.layers):
         assert torch.equal(layer.W.grad, tr.dW[l]) and torch.equal(layer.b.grad, tr.db[l])
