@@ -326,6 +326,54 @@ def sgd_update_multi(params, grads, lr, lowp_copies=None, stream=None):
                                       _stream() if stream is None else stream))
 
 
+def _row_block(t, rows):
+    """Descriptor of the first `rows` rows of a 2-d tensor and the byte distance to the next such block:
+    a sequence of calls over consecutive row blocks moves the data pointer instead of slicing."""
+    isz = t.element_size()
+    return raw_desc(t.data_ptr(), (rows, t.shape[1]), (t.stride(0) * isz, t.stride(1) * isz), _DTYPES[t.dtype]), rows * t.stride(0) * isz
+
+
+def lstm_step_fwd_seq(zx, Hs, Ut, bias, Cs, gates, n_steps, stream=None):
+    """n_steps calls of lstm_step_fwd over time-major buffers: step t reads rows t*B.. of zx, block t of
+    Hs and Cs ((n_steps+1)*B rows, block 0 = initial state) and writes block t+1 of Hs and Cs and block t
+    of gates.  Same calls as the loop over slices; only the marshalling is done once."""
+    L, st = lib(), (_stream() if stream is None else stream)
+    Bn = zx.shape[0] // n_steps
+    if zx.shape[0] != n_steps * Bn or Hs.shape[0] != (n_steps + 1) * Bn or Cs.shape[0] != (n_steps + 1) * Bn or gates.shape[0] != n_steps * Bn:
+        raise ValueError("lstm_step_fwd_seq: buffers do not hold %d steps" % n_steps)
+    (zd, zs), (hp, hs), (cp, cs), (gd, gs) = _row_block(zx, Bn), _row_block(Hs, Bn), _row_block(Cs, Bn), _row_block(gates, Bn)
+    (hn, _), (cn, _) = _row_block(Hs, Bn), _row_block(Cs, Bn)
+    hn.data += hs
+    cn.data += cs
+    ut, bd = _ref(desc(Ut)), _ref(desc(bias))
+    for _ in range(n_steps):
+        _check(L.chn_lstm_step_fwd(C.byref(zd), C.byref(hp), ut, bd, C.byref(cp), C.byref(cn), C.byref(hn), C.byref(gd), st))
+        zd.data += zs; hp.data += hs; hn.data += hs; cp.data += cs; cn.data += cs; gd.data += gs
+
+
+def lstm_step_bwd_seq(dZ, U, dHs, gates, Cs, dc_last, dc, n_steps, stream=None):
+    """The n_steps calls of lstm_step_bwd of one back-propagation through time, last step first: dZ, dHs
+    and gates hold n_steps row blocks, Cs n_steps + 1; dc_last (or None) is the gradient reaching the
+    final cell state; dc = two (B, H) buffers that take turns (the one of step 0 holds the gradient
+    of the initial cell state afterwards)."""
+    L, st = lib(), (_stream() if stream is None else stream)
+    Bn = dZ.shape[0] // n_steps
+    if dZ.shape[0] != n_steps * Bn or dHs.shape[0] != n_steps * Bn or gates.shape[0] != n_steps * Bn or Cs.shape[0] != (n_steps + 1) * Bn:
+        raise ValueError("lstm_step_bwd_seq: buffers do not hold %d steps" % n_steps)
+    (zd, zs), (zn, _), (hd, hs), (gd, gs), (cp, cs), (cn, _) = (_row_block(dZ, Bn), _row_block(dZ, Bn), _row_block(dHs, Bn),
+                                                             _row_block(gates, Bn), _row_block(Cs, Bn), _row_block(Cs, Bn))
+    last = n_steps - 1
+    zd.data += last * zs; zn.data += (last + 1) * zs; hd.data += last * hs; gd.data += last * gs; cp.data += last * cs; cn.data += (last + 1) * cs
+    ud = _ref(desc(U))
+    dcd = [C.byref(desc(dc[0])), C.byref(desc(dc[1]))]
+    dc_next = _ref(desc(dc_last))
+    for t in range(last, -1, -1):
+        _check(L.chn_lstm_step_bwd(None if t == last else C.byref(zn), ud, C.byref(hd), C.byref(gd), C.byref(cp), C.byref(cn),
+                                   dc_next, C.byref(zd), dcd[t & 1], st))
+        dc_next = dcd[t & 1]
+        zd.data -= zs; zn.data -= zs; hd.data -= hs; gd.data -= gs; cp.data -= cs; cn.data -= cs
+
+
 def adam_update_multi(params, grads, ms, vs, lr, step, beta1=0.9, beta2=0.999, eps=1e-8, lowp_copies=None, stream=None):
     ps, gs, m_, v_ = ([desc(t) for t in ts] for ts in (params, grads, ms, vs))
     ls = None if lowp_copies is None else [desc(l) for l in lowp_copies]

@@ -97,6 +97,13 @@ class GpuBackend:
     def lstm_step_bwd(self, dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev):
         self.B.lstm_step_bwd(dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev)
 
+    # a whole sequence of fused steps over time-major buffers (the marshalling is done once)
+    def lstm_steps_fwd(self, zx, Hs, Ut, bias, Cs, gates, n_steps):
+        self.B.lstm_step_fwd_seq(zx, Hs, Ut, bias, Cs, gates, n_steps)
+
+    def lstm_steps_bwd(self, dZ, U, dHs, gates, Cs, dc_last, dc, n_steps):
+        self.B.lstm_step_bwd_seq(dZ, U, dHs, gates, Cs, dc_last, dc, n_steps)
+
     def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
         ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
         self.B.softmax_ce_fwd(logits, labels, loss_mean, None, lse, ignore_label, ws)
@@ -1126,8 +1133,7 @@ class NStepLSTM(FunctionNode):
         if self.fused:
             Ut = F.empty((4 * H, H), adt)
             F.elementwise_broadcast("copy", [_t(U)], Ut)
-            for t in range(T):
-                F.lstm_step_fwd(blk(zx, t), blk(Hs, t), Ut, bias, blk(Cs, t), blk(Cs, t + 1), blk(Hs, t + 1), blk(G, t))
+            F.lstm_steps_fwd(zx, Hs, Ut, bias, Cs, G, T)
         else:
             F.elementwise_broadcast("copy", [zx], G)                 # the pre-activations are completed in place
             for t in range(T):
@@ -1164,15 +1170,14 @@ class NStepLSTM(FunctionNode):
         dh0 = F.empty((Bn, H), adt)
         dc_next = gc
         fused_bwd = self.lowp and self.fused       # (in fp32 the three separate calls are the faster ones)
-        for t in range(T - 1, -1, -1):
-            if fused_bwd:                          # dh_t += dz_{t+1} U^T, then the cell
-                F.lstm_step_bwd(None if t == T - 1 else blk(dZ, t + 1), U, blk(dHs, t), blk(G, t), blk(Cs, t), blk(Cs, t + 1),
-                                dc_next, blk(dZ, t), dc[t & 1])
-            else:
+        if fused_bwd:                              # per step: dh_t += dz_{t+1} U^T, then the cell
+            F.lstm_steps_bwd(dZ, U, dHs, G, Cs, gc, dc, T)
+        else:
+            for t in range(T - 1, -1, -1):
                 F.lstm_bwd(blk(G, t), blk(Cs, t), blk(Cs, t + 1), blk(dHs, t), dc_next, blk(dZ, t), dc[t & 1])
                 if t > 0:
                     F.gemm(blk(dZ, t), _t(U), blk(dHs, t - 1), beta=1.0)
-            dc_next = dc[t & 1]
+                dc_next = dc[t & 1]
         if 1 in indexes:
             F.gemm(blk(dZ, 0), _t(U), dh0)
         out = []

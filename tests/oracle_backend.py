@@ -69,6 +69,21 @@ class OracleBackend:
         z = O.gemm(h_prev, Ut.T, zx, 1.0, 1.0)
         c[...], h[...], gates[...] = O.lstm_fwd(z, bias, c_prev)
 
+    def lstm_steps_fwd(self, zx, Hs, Ut, bias, Cs, gates, n_steps):
+        Bn = zx.shape[0] // n_steps
+        blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
+        for t in range(n_steps):
+            self.lstm_step_fwd(blk(zx, t), blk(Hs, t), Ut, bias, blk(Cs, t), blk(Cs, t + 1), blk(Hs, t + 1), blk(gates, t))
+
+    def lstm_steps_bwd(self, dZ, U, dHs, gates, Cs, dc_last, dc, n_steps):
+        Bn = dZ.shape[0] // n_steps
+        blk = lambda a, t: a[t * Bn:(t + 1) * Bn]
+        dc_next = dc_last
+        for t in range(n_steps - 1, -1, -1):
+            self.lstm_step_bwd(None if t == n_steps - 1 else blk(dZ, t + 1), U, blk(dHs, t), blk(gates, t), blk(Cs, t), blk(Cs, t + 1),
+                               dc_next, blk(dZ, t), dc[t & 1])
+            dc_next = dc[t & 1]
+
     def lstm_step_bwd(self, dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev):
         self.calls.append(("lstm_step_bwd", None))
         if dz_next is not None:
