@@ -98,7 +98,7 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big
       // per step than the amortised figure; a lone block only `slow` times (it is not that much faster
       // alone), in between linearly.  Full rounds of 256 * conc blocks, then the remainder.
       const int conc = tile == 2 ? 1 : tile == 1 ? 2 : 4;
-      const double slow = tile == 2 ? 1.0 : tile == 1 ? 1.5 : 2.0;
+      const double slow = tile == 2 ? 1.0 : tile == 1 ? 1.5 : 1.6;   // (64x64: 2.0 before the kernel looked two tiles ahead)
       const int64_t full = blocks / (256 * conc), rem = blocks % (256 * conc);
       double t = (double)full * (fixed + steps * per_step * conc);
       if (rem > 0) {
