@@ -116,6 +116,20 @@ chn_status chn_argmax_axis(const chn_array *in, int axis, int keepdims, const ch
                            chn_stream stream);
 chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims,
                            const chn_array *out, void *ws, size_t ws_bytes, chn_stream stream);
+/* chn_reduce_axis for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results (bit for bit) as chn_reduce_axis, but the partial sums of a reduction that is cut into
+ * slices live in an array built into the library -- CHN_REDUCE_STATIC_SCRATCH_BYTES of device memory
+ * that every GPU the library runs on holds until the process ends -- and the call allocates and frees
+ * nothing (the array's device address is looked up once per device, on the first call there).
+ * A reduction whose chn_reduce_axis_workspace_bytes exceeds that size is refused with
+ * CHN_ERR_WORKSPACE and nothing is launched (the 8192 x 8192 column sums need 2 MiB).  All calls on
+ * one GPU share the one array: calls that may overlap there (different streams, different threads)
+ * race and must be ordered by the caller; calls on one stream are ordered by the stream.  Nothing in
+ * the array has to start at zero: every partial sum that is read has been written by the same call. */
+#define CHN_REDUCE_STATIC_SCRATCH_BYTES (8u << 20)
+chn_status chn_reduce_axis_static(int op, const chn_array *in, int axis, int keepdims,
+                                  const chn_array *out, chn_stream stream);
 
 /* ---- dense product ------------------------------------------------------------------------------
  * C = epilogue(alpha * A B + beta * C).  A (M,K), B (K,N), C (M,N) are 2-d views; a transposed

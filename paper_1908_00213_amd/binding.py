@@ -25,7 +25,7 @@ REDUCE = {"sum": 0, "max": 1}
 EPILOGUES = ["none", "bias", "bias_relu", "bias_gelu", "relu_bwd", "gelu_bwd", "bf16_copy"]
 EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
-EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_argmax_axis",
+EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_reduce_axis_static", "chn_argmax_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
@@ -80,6 +80,7 @@ def lib():
     L.chn_reduce_axis_workspace_bytes.argtypes = [AP, C.c_int]
     L.chn_reduce_axis_workspace_bytes.restype = C.c_size_t
     L.chn_reduce_axis.argtypes = [C.c_int, AP, C.c_int, C.c_int, AP, vp, C.c_size_t, st]
+    L.chn_reduce_axis_static.argtypes = [C.c_int, AP, C.c_int, C.c_int, AP, st]
     L.chn_argmax_axis.argtypes = [AP, C.c_int, C.c_int, AP, st]
     L.chn_gemm_workspace_bytes.argtypes = [AP, AP, AP]
     L.chn_gemm_workspace_bytes.restype = C.c_size_t
@@ -229,6 +230,14 @@ def reduce_axis(op, x, axis, out, keepdims=False, ws=None, stream=None):
     _check(lib().chn_reduce_axis(REDUCE[op] if isinstance(op, str) else op, _ref(desc(x)), axis,
                                  int(keepdims), _ref(desc(out)), p, n,
                                  _stream() if stream is None else stream))
+    return out
+
+
+def reduce_axis_static(op, x, axis, out, keepdims=False, stream=None):
+    """reduce_axis without a workspace argument and without any allocation (partial sums in the
+    library's built-in per-device array)."""
+    _check(lib().chn_reduce_axis_static(REDUCE[op] if isinstance(op, str) else op, _ref(desc(x)), axis,
+                                        int(keepdims), _ref(desc(out)), _stream() if stream is None else stream))
     return out
 
 

@@ -12,8 +12,39 @@
 // A transposed 2-d view simply swaps ROW and COL.  HBM-bound: the input is read exactly once.
 #include "common.h"
 
+#include <mutex>
+
 namespace chn {
 namespace {
+
+// Partial sums of chn_reduce_axis_static: one array per GPU for the life of the process.  In host code
+// the name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+constexpr size_t kScratchBytes = (size_t)CHN_REDUCE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+chn_status scratch_of_current_device(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(CHN_ERR_LAUNCH, "reduce (static scratch): hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(CHN_ERR_LAUNCH, "reduce (static scratch): device ordinal %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return fail(CHN_ERR_LAUNCH, "reduce (static scratch): hipGetSymbolAddress: %s", hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CHN_OK;
+}
 
 template <int OP> __device__ __forceinline__ float fold(float a, float b) {
   if constexpr (OP == CHN_REDUCE_SUM) return a + b; else return fmaxf(a, b);
@@ -310,19 +341,9 @@ chn_status launch_op(int op, const RPlan &p, const chn_array *in, const chn_arra
 }
 
 }  // namespace
-}  // namespace chn
 
-extern "C" {
-
-size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis) {
-  chn::RPlan p;
-  if (chn::make_rplan(in, axis, &p) != CHN_OK) return 0;
-  return p.kind == chn::KIND_COL ? p.ws_bytes : 0;
-}
-
-chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
-                           void *ws, size_t ws_bytes, chn_stream stream) {
-  using namespace chn;
+chn_status reduce_axis_impl(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                            void *ws, size_t ws_bytes, bool static_scratch, chn_stream stream) {
   if (op != CHN_REDUCE_SUM && op != CHN_REDUCE_MAX) return fail(CHN_ERR_OP, "reduce: unknown op %d", op);
   RPlan p;
   CHN_TRY(make_rplan(in, axis, &p));
@@ -349,11 +370,42 @@ chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims, 
     else hipLaunchKernelGGL((fill_kernel<bf16_raw>), dim3(blocks), dim3(256), 0, st, static_cast<bf16_raw *>(out->data), p.total_out, v);
     return check_launch("reduce fill");
   }
-  if (p.kind == KIND_COL) CHN_TRY(check_ws(ws, ws_bytes, p.ws_bytes, "reduce"));
+  if (p.kind == KIND_COL && p.ws_bytes > 0) {
+    if (static_scratch) {
+      // the per-device array stands in for the caller's workspace; nothing is allocated
+      if (p.ws_bytes > kScratchBytes)
+        return fail(CHN_ERR_WORKSPACE, "reduce (static scratch): this reduction needs %zu bytes of partial sums, the built-in buffer holds %zu; use chn_reduce_axis with a workspace",
+                    p.ws_bytes, kScratchBytes);
+      CHN_TRY(scratch_of_current_device(&ws));
+    } else {
+      CHN_TRY(check_ws(ws, ws_bytes, p.ws_bytes, "reduce"));
+    }
+  }
   if (in->dtype == CHN_F32 && out->dtype == CHN_F32) return launch_op<float, float>(op, p, in, out, ws, st);
   if (in->dtype == CHN_BF16 && out->dtype == CHN_F32) return launch_op<bf16_raw, float>(op, p, in, out, ws, st);
   if (in->dtype == CHN_BF16 && out->dtype == CHN_BF16) return launch_op<bf16_raw, bf16_raw>(op, p, in, out, ws, st);
   return launch_op<float, bf16_raw>(op, p, in, out, ws, st);
+}
+
+
+}  // namespace chn
+
+extern "C" {
+
+size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis) {
+  chn::RPlan p;
+  if (chn::make_rplan(in, axis, &p) != CHN_OK) return 0;
+  return p.kind == chn::KIND_COL ? p.ws_bytes : 0;
+}
+
+chn_status chn_reduce_axis(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                           void *ws, size_t ws_bytes, chn_stream stream) {
+  return chn::reduce_axis_impl(op, in, axis, keepdims, out, ws, ws_bytes, false, stream);
+}
+
+chn_status chn_reduce_axis_static(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                                  chn_stream stream) {
+  return chn::reduce_axis_impl(op, in, axis, keepdims, out, nullptr, 0, true, stream);
 }
 
 }  // extern "C"
