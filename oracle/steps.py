@@ -22,15 +22,22 @@ import numpy as np
 from . import oracle as O
 
 
+ROUND = O.round_bf16     # the storage rounding (a pin replaces it by the identity: see the tests of this module)
+
+
 def _st(x, lowp):
-    return O.round_bf16(x) if lowp else x
+    return ROUND(x) if lowp else x
 
 
 def mlp_step(params, x, t, lr, act="relu", lowp=False):
     """One forward + backward + SGD step of an MLP.
 
     params: list of (W (n_out,n_in), b (n_out,)) master parameters.
-    Returns dict(loss, logits, grads=[(dW, db)...], params=[(W', b')...], acts=[...]).
+    Returns dict(loss, logits, grads=[(dW, db)...], params=[(W', b')...], acts=[...], stored=...).
+    ``stored`` names every array the mixed-precision scheme keeps in bfloat16 (rounded when lowp):
+    working copies of the weights ``Wc``, activations ``acts``, pre-activations kept for the GELU
+    backward ``zs``, and the activation gradients ``dvs`` (index l: gradient of layer l's
+    pre-activation; the last one is the logit gradient); ``dhs`` are the unrounded input gradients.
     """
     L = len(params)
     Ws = [_st(np.asarray(W, dtype=np.float64), lowp) for W, _ in params]
@@ -46,12 +53,15 @@ def mlp_step(params, x, t, lr, act="relu", lowp=False):
     loss, _, _, _ = O.softmax_ce_fwd(logits, t)
     dv = _st(O.softmax_ce_bwd(logits, t), lowp)
     grads = [None] * L
+    dvs, dhs = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
+        dvs[l] = dv
         dW = O.gemm(dv.T, hs[l])
         db = O.reduce_axis("sum", dv, 0)
         grads[l] = (dW, db)
         if l > 0:
             dh = O.gemm(dv, Ws[l])
+            dhs[l] = dh
             if act == "relu":
                 dv = O.elementwise("relu_bwd", [dh, hs[l]])
             else:
@@ -59,7 +69,8 @@ def mlp_step(params, x, t, lr, act="relu", lowp=False):
             dv = _st(dv, lowp)
     new = [(O.sgd_update(W, dW, lr), O.sgd_update(b, db, lr))
            for (W, b), (dW, db) in zip(params, grads)]
-    return dict(loss=loss, logits=logits, grads=grads, params=new, acts=hs[1:])
+    return dict(loss=loss, logits=logits, grads=grads, params=new, acts=hs[1:],
+                stored=dict(Wc=Ws, acts=hs[1:], zs=zs, dvs=dvs), dhs=dhs)
 
 
 def mlp_loss(params, x, t, act="relu"):
@@ -100,11 +111,15 @@ def lstm_lm_forward(P, ids, targets, lowp=False):
     Hall = np.concatenate(Hs, axis=0)                         # (T*B, H)
     logits = O.elementwise("add", [O.gemm(Hall, Pl["W_out"].T), P["b_out"]])
     loss = O.softmax_ce_fwd(logits, targets.reshape(-1))[0]
-    return dict(loss=loss, logits=logits, X=X, Hall=Hall, Cs=Cs, Gs=Gs, Cprev=Cprev, Hprev=Hprev, Pl=Pl)
+    return dict(loss=loss, logits=logits, X=X, Zx=Zx, Hall=Hall, Cs=Cs, Gs=Gs, Cprev=Cprev, Hprev=Hprev, Pl=Pl)
 
 
 def lstm_lm_step(P, ids, targets, lr, lowp=False):
-    """One forward + full BPTT + SGD step.  Returns dict(loss, grads{name}, params{name}).
+    """One forward + full BPTT + SGD step.  Returns dict(loss, grads{name}, params{name}, logits,
+    stored{...}, unrounded{...}): ``stored`` holds the arrays kept in bfloat16 when lowp (working
+    copies, embeddings X, hidden states Hall, dlogits, dHall, the per-step total hidden-state
+    gradients dH and the gate gradients dZ), ``unrounded`` those that stay wide (Zx, gates, cell
+    states, cell-state gradients dC, the embedding-output gradient dX).
 
     ``lowp`` additionally stores the activation gradients that feed matrix products in bfloat16:
     the logit gradients, the gradient of every h (rounded again after the recurrent term has been
@@ -121,13 +136,16 @@ def lstm_lm_step(P, ids, targets, lr, lowp=False):
     g["b_out"] = O.reduce_axis("sum", dlogits, 0)
     dHall = _st(O.gemm(dlogits, Pl["W_out"]), lowp)          # (T*B, H)
     dZ = np.zeros((T * B, 4 * H))
+    dH_tot, dC = [None] * T, [None] * T
     dh_rec = None
     dc = None
     for t in range(T - 1, -1, -1):
         dh = dHall[t * B:(t + 1) * B]
         if dh_rec is not None:
             dh = _st(O.elementwise("add", [dh, dh_rec]), lowp)
+        dH_tot[t] = dh
         dz, dc = O.lstm_bwd(F["Gs"][t], F["Cprev"][t], F["Cs"][t], dh, dc)
+        dC[t] = dc
         dz = _st(dz, lowp)
         dZ[t * B:(t + 1) * B] = dz
         dh_rec = O.gemm(dz, Pl["U"].T)
@@ -138,4 +156,7 @@ def lstm_lm_step(P, ids, targets, lr, lowp=False):
     dX = O.gemm(dZ, Pl["W"].T)
     g["E"] = O.embed_bwd(ids.reshape(-1), dX, V)
     new = {k: O.sgd_update(P[k], g[k], lr) for k in g}
-    return dict(loss=F["loss"], grads=g, params=new, logits=F["logits"])
+    return dict(loss=F["loss"], grads=g, params=new, logits=F["logits"],
+                stored=dict(Wc={k: Pl[k] for k in ("E", "W", "U", "W_out")}, X=F["X"], Hall=F["Hall"], dlogits=dlogits,
+                            dHall=dHall, dH=dH_tot, dZ=dZ),
+                unrounded=dict(Zx=F["Zx"], Gs=F["Gs"], Cs=F["Cs"], dC=dC, dX=dX))

@@ -298,6 +298,10 @@ def test_round_bf16_matches_format_definition():
     want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
     assert np.array_equal(got, want)
     assert np.array_equal(O.round_bf16(got), got)               # idempotent
+    # ties stated by hand: 1 + 2^-8 lies midway between 1 (even mantissa) and 1 + 2^-7;
+    # 1 + 3*2^-8 midway between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    ties = O.round_bf16(np.array([1.00390625, 1.01171875, -1.00390625, -1.01171875, 1.00390625 + 2.0 ** -30, 257.0, 259.0]))
+    assert list(ties) == [1.0, 1.015625, -1.0, -1.015625, 1.0078125, 256.0, 260.0]
 
 
 # ---------------------------------------------------------------- whole steps
@@ -341,6 +345,190 @@ def test_mlp_step_lowp_rounds_only_storage():
     for a in r16["acts"]:
         assert np.array_equal(O.round_bf16(a), a)
     assert r16["loss"] != r32["loss"]
+
+
+# ---- the mixed-precision ("lowp") branches: WHERE the steps round to bfloat16 ---------------------------
+# The scheme (weights: fp32 master + bf16 working copy; activations and activation gradients bf16;
+# dW, db, logits, loss, cell state, gates and masters wide) is checked three ways: which arrays are
+# bf16-exact and which are not, the identity when the rounding is switched off, and a tiny case
+# composed here from plain NumPy / SciPy with a rounding written independently of the oracle's.
+def _is_bf16(a):
+    a = np.asarray(a, dtype=np.float64)
+    return bool(np.array_equal(O.round_bf16(a), a))
+
+
+def _rne_bf16(a):
+    """bfloat16 rounding from the format's definition, without the oracle's C routine: scale the value
+    so that eight significant bits sit left of the point, round half to even (Python's round), scale back."""
+    out = np.empty(np.shape(a), dtype=np.float64)
+    flat, src = out.reshape(-1), np.asarray(a, dtype=np.float64).reshape(-1)
+    for i, v in enumerate(src):
+        if v == 0.0:
+            flat[i] = 0.0
+            continue
+        _, e = math.frexp(v)                     # |v| = f * 2^e, f in [0.5, 1)
+        flat[i] = float(round(v * 2.0 ** (8 - e))) * 2.0 ** (e - 8)
+    return out
+
+
+def _softmax_grad(z, t):
+    p = sps.softmax(z, axis=1)
+    p[np.arange(len(t)), t] -= 1.0
+    return p / len(t)
+
+
+def _gelu(v):
+    return 0.5 * v * (1.0 + sps.erf(v / math.sqrt(2.0)))
+
+
+def _gelu_grad(v):
+    return 0.5 * (1.0 + sps.erf(v / math.sqrt(2.0))) + v * np.exp(-0.5 * v * v) / math.sqrt(2.0 * math.pi)
+
+
+@pytest.mark.parametrize("act", ["relu", "gelu"])
+def test_mlp_step_lowp_storage_points(act, monkeypatch):
+    sizes = (7, 6, 5, 4)
+    params = [(RNG.standard_normal((sizes[i + 1], sizes[i])) * 0.6, RNG.standard_normal(sizes[i + 1]) * 0.1) for i in range(3)]
+    x = O.round_bf16(RNG.standard_normal((9, 7)))
+    t = RNG.integers(0, 4, 9)
+    r = OS.mlp_step(params, x, t, 0.05, act, lowp=True)
+    st = r["stored"]
+    # bf16-stored: working copies, activations, retained pre-activations, every activation gradient
+    for name in ("Wc", "acts", "zs", "dvs"):
+        assert len(st[name]) >= 2
+        for a in st[name]:
+            assert _is_bf16(a), name
+    # kept wide: logits, weight and bias gradients, input gradients before the activation derivative, new masters
+    wide = [r["logits"]] + [g for pair in r["grads"] for g in pair] + [p for pair in r["params"] for p in pair] + [d for d in r["dhs"] if d is not None]
+    for a in wide:
+        assert not _is_bf16(a)
+    # masters are updated from the masters (not from the rounded copies) with the unrounded gradients
+    for (W, b), (dW, db), (Wn, bn) in zip(params, r["grads"], r["params"]):
+        assert np.array_equal(Wn, W - 0.05 * dW) and np.array_equal(bn, b - 0.05 * db)
+    # composed by hand from NumPy / SciPy with an independent rounding
+    Wc = [_rne_bf16(W) for W, _ in params]
+    h, hs, zs = x, [x], []
+    for l in range(2):
+        v = h @ Wc[l].T + params[l][1]
+        zs.append(_rne_bf16(v))
+        h = _rne_bf16(np.maximum(v, 0.0) if act == "relu" else _gelu(v))      # activation of the UNROUNDED v
+        hs.append(h)
+    logits = h @ Wc[2].T + params[2][1]
+    np.testing.assert_allclose(r["logits"], logits, rtol=1e-13, atol=1e-14)
+    dv = _rne_bf16(_softmax_grad(logits, t))
+    for l in (2, 1, 0):
+        np.testing.assert_allclose(r["grads"][l][0], dv.T @ hs[l], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(r["grads"][l][1], dv.sum(0), rtol=1e-12, atol=1e-15)
+        assert np.array_equal(st["dvs"][l], dv)                                 # same bf16 values, bit for bit
+        if l > 0:
+            dh = dv @ Wc[l]
+            # the derivative is taken from what was STORED: the bf16 output (ReLU) or the bf16 pre-activation (GELU)
+            dv = _rne_bf16(dh * (hs[l] > 0) if act == "relu" else dh * _gelu_grad(zs[l - 1]))
+    for l in range(2):
+        assert np.array_equal(st["acts"][l], hs[l + 1]) and np.array_equal(st["zs"][l], zs[l])
+    # with the rounding switched off the lowp step IS the fp64 step
+    monkeypatch.setattr(OS, "ROUND", lambda a: a)
+    a, b = OS.mlp_step(params, x, t, 0.05, act, lowp=True), OS.mlp_step(params, x, t, 0.05, act, lowp=False)
+    assert a["loss"] == b["loss"] and np.array_equal(a["logits"], b["logits"])
+    for (aW, ab), (bW, bb) in zip(a["grads"] + a["params"], b["grads"] + b["params"]):
+        assert np.array_equal(aW, bW) and np.array_equal(ab, bb)
+
+
+def test_mlp_step_lowp_one_layer_by_hand():
+    # 2 x 2, one layer, numbers small enough to follow: the working copy rounds 1 + 2^-8 down to 1 and
+    # 1 + 3*2^-8 up to 1 + 2^-6; logits are x Wc^T + b, unrounded
+    W = np.array([[1.00390625, 0.5], [1.01171875, -0.25]])
+    b = np.array([0.125, 0.0])
+    x = np.array([[1.0, 2.0], [3.0, -1.0]])
+    t = np.array([0, 1])
+    r = OS.mlp_step([(W, b)], x, t, 0.5, "relu", lowp=True)
+    Wc = np.array([[1.0, 0.5], [1.015625, -0.25]])
+    assert np.array_equal(r["stored"]["Wc"][0], Wc)
+    logits = np.array([[1.0 + 1.0 + 0.125, 1.015625 - 0.5], [3.0 - 0.5 + 0.125, 3.046875 + 0.25]])
+    assert np.array_equal(r["logits"], logits)
+    p = np.exp(logits) / np.exp(logits).sum(1, keepdims=True)
+    dz = (p - np.eye(2)[t]) / 2.0
+    dv = _rne_bf16(dz)
+    assert np.array_equal(r["stored"]["dvs"][0], dv) and not np.array_equal(dv, dz)
+    np.testing.assert_allclose(r["grads"][0][0], dv.T @ x, rtol=1e-15)
+    np.testing.assert_allclose(r["params"][0][0], W - 0.5 * (dv.T @ x), rtol=1e-15)     # from the master W, not from Wc
+    assert abs(r["loss"] - float(np.mean(-np.log(p[np.arange(2), t])))) < 1e-15
+
+
+def _tiny_lm(scale=0.5):
+    V, E, H, B, T = 7, 3, 4, 2, 3
+    P = {"E": RNG.standard_normal((V, E)), "W": RNG.standard_normal((E, 4 * H)) * scale,
+         "U": RNG.standard_normal((H, 4 * H)) * scale, "b": RNG.standard_normal(4 * H) * 0.1,
+         "W_out": RNG.standard_normal((V, H)) * scale, "b_out": RNG.standard_normal(V) * 0.1}
+    ids = np.array([[1, 1], [3, 1], [1, 6]])
+    return P, ids, RNG.integers(0, V, (T, B))
+
+
+def test_lstm_lm_step_lowp_storage_points(monkeypatch):
+    P, ids, tg = _tiny_lm()
+    T, B = ids.shape
+    H, V = 4, 7
+    r = OS.lstm_lm_step(P, ids, tg, 0.1, lowp=True)
+    st, un = r["stored"], r["unrounded"]
+    # bf16-stored: what feeds a product
+    for k in ("E", "W", "U", "W_out"):
+        assert _is_bf16(st["Wc"][k]) and not _is_bf16(P[k])
+    for name in ("X", "Hall", "dlogits", "dHall", "dZ"):
+        assert _is_bf16(st[name]), name
+    assert all(_is_bf16(d) for d in st["dH"])
+    # kept wide: gate pre-activations, gates, cell state and its gradient, logits, dX, parameter gradients, masters
+    for a in [un["Zx"], un["dX"], r["logits"]] + un["Gs"] + un["Cs"] + un["dC"] + list(r["grads"].values()) + list(r["params"].values()):
+        assert not _is_bf16(a)
+    for k in r["grads"]:
+        assert np.array_equal(r["params"][k], P[k] - 0.1 * r["grads"][k])
+    # composed by hand (NumPy / SciPy, independent rounding), same storage points
+    Wc = {k: _rne_bf16(P[k]) for k in ("E", "W", "U", "W_out")}
+    X = Wc["E"][ids.reshape(-1)]
+    Zx = X @ Wc["W"]
+    h, c = np.zeros((B, H)), np.zeros((B, H))
+    Hp, Cp, Cs, Gs, Hs = [], [], [], [], []
+    for s in range(T):
+        z = Zx[s * B:(s + 1) * B] + h @ Wc["U"] + P["b"]
+        i, f, g, o = sps.expit(z[:, :H]), sps.expit(z[:, H:2 * H]), np.tanh(z[:, 2 * H:3 * H]), sps.expit(z[:, 3 * H:])
+        Hp.append(h); Cp.append(c)
+        c = f * c + i * g
+        h = _rne_bf16(o * np.tanh(c))                 # h is stored in bf16, c is not
+        Cs.append(c); Gs.append((i, f, g, o)); Hs.append(h)
+    Hall = np.concatenate(Hs)
+    logits = Hall @ Wc["W_out"].T + P["b_out"]
+    np.testing.assert_allclose(r["logits"], logits, rtol=1e-12, atol=1e-14)
+    assert np.array_equal(st["Hall"], Hall)
+    dlog = _rne_bf16(_softmax_grad(logits, tg.reshape(-1)))
+    assert np.array_equal(st["dlogits"], dlog)
+    dHall = _rne_bf16(dlog @ Wc["W_out"])
+    dZ = np.zeros((T * B, 4 * H))
+    dc, rec = np.zeros((B, H)), None
+    for s in range(T - 1, -1, -1):
+        dh = dHall[s * B:(s + 1) * B]
+        if rec is not None:
+            dh = _rne_bf16(dh + rec)                  # rounded again once the recurrent part is in
+        i, f, g, o = Gs[s]
+        tc = np.tanh(Cs[s])
+        dct = dc + dh * o * (1 - tc * tc)
+        dz = np.concatenate([dct * g * i * (1 - i), dct * Cp[s] * f * (1 - f), dct * i * (1 - g * g), dh * tc * o * (1 - o)], axis=1)
+        dc = dct * f                                  # the cell-state gradient is never rounded
+        dz = _rne_bf16(dz)
+        dZ[s * B:(s + 1) * B] = dz
+        rec = dz @ Wc["U"].T
+    assert np.array_equal(st["dZ"], dZ)
+    np.testing.assert_allclose(r["grads"]["U"], np.concatenate(Hp).T @ dZ, rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(r["grads"]["W"], X.T @ dZ, rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(r["grads"]["b"], dZ.sum(0), rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(r["grads"]["W_out"], dlog.T @ Hall, rtol=1e-11, atol=1e-15)
+    dE = np.zeros((V, 3))
+    np.add.at(dE, ids.reshape(-1), dZ @ Wc["W"].T)    # dX itself is not rounded
+    np.testing.assert_allclose(r["grads"]["E"], dE, rtol=1e-11, atol=1e-15)
+    # rounding switched off: the lowp step is the fp64 step, bit for bit
+    monkeypatch.setattr(OS, "ROUND", lambda a: a)
+    a, b = OS.lstm_lm_step(P, ids, tg, 0.1, lowp=True), OS.lstm_lm_step(P, ids, tg, 0.1, lowp=False)
+    assert a["loss"] == b["loss"]
+    for k in a["grads"]:
+        assert np.array_equal(a["grads"][k], b["grads"][k]) and np.array_equal(a["params"][k], b["params"][k])
 
 
 def test_fd_lstm_lm_step_bptt():
