@@ -51,6 +51,11 @@ class Timer:
         t.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / iters       # seconds per call
 
+    def repeats(self, fn, iters, warmup, n):
+        """`n` timed regions of exactly `iters` calls each (warm-up before the first only); seconds per
+        call of every region, in run order."""
+        return [self.time(fn, iters, warmup if r == 0 else 0) for r in range(n)]
+
 
 def bench_array(torch, B, W, timer, quick):
     """Workload 2: y = relu(a*b + c) with a row-broadcast c, sums over both axes, transposed views."""
@@ -59,9 +64,9 @@ def bench_array(torch, B, W, timer, quick):
     w = W.config2(n)
     for name, tdt, isz in (("f32", torch.float32, 4), ("bf16", torch.bfloat16, 2)):
         sets = 2 if name == "f32" else 4            # rotate buffers: defeat the 256 MB Infinity Cache
-        a = [torch.from_numpy(w.a).cuda().to(tdt) for _ in range(sets)]
-        b = [torch.from_numpy(w.b).cuda().to(tdt) for _ in range(sets)]
-        c = torch.from_numpy(w.c).cuda().to(tdt)
+        a = [B.cast(torch.from_numpy(w.a).cuda(), tdt) for _ in range(sets)]
+        b = [B.cast(torch.from_numpy(w.b).cuda(), tdt) for _ in range(sets)]
+        c = B.cast(torch.from_numpy(w.c).cuda(), tdt)
         y = [torch.empty(n, n, dtype=tdt, device="cuda") for _ in range(4)]
         o = torch.empty(n, dtype=torch.float32, device="cuda")
         ws = torch.empty(max(256, B.reduce_axis_workspace_bytes(y[0], 0)), dtype=torch.uint8, device="cuda")
@@ -106,41 +111,42 @@ def bench_array(torch, B, W, timer, quick):
 
 
 class GemmProbe:
-    """Brackets every GEMM launch of a recorded step with HIP events (same stream) so that the
-    per-kernel time inside the timed region can be read back afterwards."""
+    """Brackets every GEMM launch of a recorded step with HIP events (same stream) so that the time of
+    each launch can be read back afterwards.  A measurement pass of its own, run after the timed
+    region of the step benchmark: recording two events per product costs host and device time that
+    the step itself does not have.  The events exist before the pass starts."""
 
-    def __init__(self, torch, B, prog):
+    def __init__(self, torch, B, prog, slots):
         self.torch = torch
         self.fn = B.lib().chn_gemm
         self.prog = prog
-        self.idx = [i for i, (fn, _) in enumerate(prog.calls) if fn is self.fn]
-        self.events = []
+        self.n = sum(1 for fn, _ in prog.calls if fn is self.fn)
+        mk = lambda: torch.cuda.Event(enable_timing=True)
+        self.events = [[(mk(), mk()) for _ in range(self.n)] for _ in range(slots)]
+        self.used = set()
 
-    def run(self):
-        t = self.torch
+    def run(self, slot):
         import ctypes as C
-        s = C.c_void_p(t.cuda.current_stream().cuda_stream)
-        ev = []
+        s = C.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        ev = iter(self.events[slot])
         for fn, args in self.prog.calls:
             if fn is self.fn:
-                e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+                e0, e1 = next(ev)
                 e0.record()
                 st = fn(*args, s)
                 e1.record()
-                ev.append((e0, e1))
             else:
                 st = fn(*args, s)
             if st != 0:
                 raise RuntimeError("chn call failed with status %d" % st)
-        self.events.append(ev)
+        self.used.add(slot)
 
     def per_call_seconds(self):
-        n = len(self.idx)
-        tot = [0.0] * n
-        for ev in self.events:
-            for i, (e0, e1) in enumerate(ev):
+        tot = [0.0] * self.n
+        for slot in self.used:
+            for i, (e0, e1) in enumerate(self.events[slot]):
                 tot[i] += e0.elapsed_time(e1) * 1e-3
-        return [x / max(1, len(self.events)) for x in tot]
+        return [x / max(1, len(self.used)) for x in tot]
 
 
 def gemm_shapes_mlp(sizes, batch, fused_update):
@@ -154,46 +160,54 @@ def gemm_shapes_mlp(sizes, batch, fused_update):
     return out
 
 
-def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, graph=False, fused_update=False):
-    """fused_update: the SGD update of the weights runs in the epilogue of the weight-gradient products
+def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, graph=False, fused_update=False, repeats=1,
+              probe_steps=20):
+    """Times the recorded step (`repeats` regions of exactly `steps` steps after `warmup` steps of the same
+    callable; the median region is reported, all regions are listed).
+    fused_update: the SGD update of the weights runs in the epilogue of the weight-gradient products
     (same arithmetic, the gradients do not travel through memory); still one full
-    forward + backward + update step."""
+    forward + backward + update step.
+    probe: afterwards, outside every timed region, `probe_steps` more steps run with each GEMM launch
+    bracketed by HIP events (per-product times and rates)."""
     tr = steps_mod.MLPTrainer(w.params, w.batch, w.act, w.lr, lowp, fused_update=fused_update)
     xs = [torch.from_numpy(x).cuda() for x in w.xs]
     if lowp:
-        xs = [x.to(torch.bfloat16) for x in xs]
+        xs = [B.cast(x, torch.bfloat16) for x in xs]
     ts = [torch.from_numpy(t).cuda() for t in w.ts]
     nb = len(xs)
     for i in range(nb):
         tr.step(xs[i], ts[i])                                   # builds the call lists
     res = {}
-    if probe:
-        probes = [GemmProbe(torch, B, tr._progs[(xs[i].data_ptr(), ts[i].data_ptr())]) for i in range(nb)]
-        k = [0]
+    k = [0]
 
-        def fn():
-            probes[k[0] % nb].run()
-            k[0] += 1
-        for _ in range(warmup):
-            tr.step(xs[0], ts[0])
-        s = timer.time(fn, steps, 0)
-        per = [0.0] * len(probes[0].idx)
-        used = [p for p in probes if p.events]
-        for p in used:
+    def fn():
+        tr.step(xs[k[0] % nb], ts[k[0] % nb], graph=graph)
+        k[0] += 1
+    regions = timer.repeats(fn, steps, warmup, repeats)
+    s = sorted(regions)[len(regions) // 2]
+    if repeats > 1:
+        res["ms_per_step_regions"] = [round(r * 1e3, 4) for r in regions]
+        res["ms_per_step_spread"] = [round(min(regions) * 1e3, 4), round(max(regions) * 1e3, 4)]
+    if probe:
+        per_batch = (probe_steps + nb - 1) // nb
+        probes = [GemmProbe(torch, B, tr._progs[(xs[i].data_ptr(), ts[i].data_ptr())], per_batch) for i in range(nb)]
+        for i in range(nb):                                     # warm the instrumented path (events get re-recorded)
+            probes[i].run(0)
+        torch.cuda.synchronize()
+        for slot in range(per_batch):
+            for i in range(nb):
+                probes[i].run(slot)
+        torch.cuda.synchronize()
+        per = [0.0] * probes[0].n
+        for p in probes:
             for i, v in enumerate(p.per_call_seconds()):
-                per[i] += v / len(used)
+                per[i] += v / len(probes)
         res["gemm_calls"] = [{"call": lab, "M": M, "N": N, "K": K, "us": round(t_ * 1e6, 1),
                               "TFLOP/s": round(2.0 * M * N * K / t_ / 1e12, 1)}
                              for (lab, M, N, K), t_ in zip(gemm_shapes_mlp(w.sizes, w.batch, fused_update), per)]
         res["gemm_seconds_per_step"] = sum(per)
         res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch, fused_update))
-    else:
-        k = [0]
-
-        def fn():
-            tr.step(xs[k[0] % nb], ts[k[0] % nb], graph=graph)
-            k[0] += 1
-        s = timer.time(fn, steps, warmup)
+        res["gemm_probe_steps"] = per_batch * nb
     res.update({"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(tr.loss.cpu()),
                 "TFLOP/s": w.flops_per_step() / s / 1e12, "launch_calls_per_step": tr.n_launch_calls(xs[0], ts[0])})
     return res
@@ -273,8 +287,8 @@ def traffic_driver(torch, B, W):
     writes the pre-activation (M=8192, N=4096, K=4096, bf16 in / bf16 out)."""
     w = W.config5(n_batches=1)
     bf = torch.bfloat16
-    x = torch.from_numpy(W.bf16_exact(w.xs[0])).cuda().to(bf)
-    Wm = torch.from_numpy(W.bf16_exact(w.params[0][0])).cuda().to(bf)
+    x = B.cast(torch.from_numpy(w.xs[0]).cuda(), bf)
+    Wm = B.cast(torch.from_numpy(w.params[0][0]).cuda(), bf)
     bias = torch.from_numpy(w.params[0][1]).cuda()
     out = torch.empty((w.batch, Wm.shape[0]), device="cuda", dtype=bf)
     pre = torch.empty_like(out)
@@ -290,20 +304,31 @@ def traffic_driver(torch, B, W):
     log("traffic driver: 3 x (copy 256 MiB, flush, forward GEMM 8192x4096x4096 with bias+GELU epilogue, flush) done")
 
 
-def cpu_baseline(W, rows=128):
-    """The CPU oracle, as it stands, on a bounded sample of the headline workload: `rows` of the 8192
-    batch rows through the full-width network (forward + backward + SGD), scaled to steps/s."""
+def cpu_baseline(W, rows=(32, 96)):
+    """The CPU oracle, as it stands, on a bounded sample of the headline workload.  A full step would
+    take the host about half an hour, so the figure is an EXTRAPOLATION and says so: the oracle's
+    mixed-precision step (forward + backward + SGD through the full-width network) is timed on two
+    small batches, the times are split into a part per batch row and a part that does not depend on
+    the batch (rounding the working copies of 54 M weights, the SGD update), and the step at 8192
+    rows is the fixed part once plus 8192 times the per-row part."""
     from oracle import oracle as O
     from oracle import steps as OS
     w = W.config5(n_batches=1)
-    x = W.bf16_exact(w.xs[0][:rows])
-    t0 = time.perf_counter()
-    OS.mlp_step(w.params, x, w.ts[0][:rows], np.float32(w.lr), w.act, lowp=True)
-    dt = time.perf_counter() - t0
-    scale = w.batch / rows
-    return {"value": 1.0 / (dt * scale), "unit": "steps/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": "%d of %d batch rows through the full 4096-4096-4096-4096-1000 network (one forward+backward+SGD "
-                      "step, fp64 with bf16 storage rounding) took %.1f s; scaled by %d" % (rows, w.batch, dt, scale)}
+    times = []
+    for r in rows:
+        x = W.bf16_exact(w.xs[0][:r])
+        t0 = time.perf_counter()
+        OS.mlp_step(w.params, x, w.ts[0][:r], np.float32(w.lr), w.act, lowp=True)
+        times.append(time.perf_counter() - t0)
+    per_row = (times[1] - times[0]) / (rows[1] - rows[0])
+    fixed = max(0.0, times[0] - per_row * rows[0])
+    full = fixed + per_row * w.batch
+    return {"value": 1.0 / full, "unit": "steps/s", "cores": O.num_threads(), "kind": "oracle", "extrapolated": True,
+            "rows_timed": list(rows), "seconds_timed": [round(t, 2) for t in times],
+            "fit": {"fixed_s": round(fixed, 3), "per_row_s": round(per_row, 4), "batch": w.batch, "step_s": round(full, 1)},
+            "sample": "oracle mixed-precision step (fp64 arithmetic, bf16 storage rounding) of the full 4096-4096-4096-4096-1000 "
+                      "network timed at %d and %d of the %d batch rows (%.1f s and %.1f s); extrapolated linearly in the rows "
+                      "to one full step = %.0f s" % (rows[0], rows[1], w.batch, times[0], times[1], full)}
 
 
 def main():
@@ -311,6 +336,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="timed regions of --steps steps each for the headline workload; the median region is reported")
     ap.add_argument("--quick", action="store_true", help="headline workload only, fewer repetitions of the rest")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--workloads", default="1,2,3,4,tape",
@@ -343,11 +370,12 @@ def main():
     w5 = W.config5(n_batches=4)
     torch.cuda.synchronize()
     r5 = bench_mlp(torch, B, steps_mod, w5, True, timer, args.steps, args.warmup, probe=True,
-                   fused_update=not args.separate_update)
+                   fused_update=not args.separate_update, repeats=args.repeats)
     torch.cuda.synchronize()
-    log("  %.3f ms/step  %.1f steps/s  %.1f TFLOP/s whole step; GEMMs %.3f ms/step = %.1f TFLOP/s" % (
-        r5["ms_per_step"], r5["steps_per_s"], r5["TFLOP/s"], r5["gemm_seconds_per_step"] * 1e3,
-        r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12))
+    log("  %.3f ms/step (median of %d regions of %d steps: %s)  %.1f steps/s  %.1f TFLOP/s whole step; "
+        "GEMMs (separate instrumented pass) %.3f ms/step = %.1f TFLOP/s" % (
+        r5["ms_per_step"], args.repeats, args.steps, r5.get("ms_per_step_regions"), r5["steps_per_s"], r5["TFLOP/s"],
+        r5["gemm_seconds_per_step"] * 1e3, r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12))
     # dominant kernel: the 256x256-tile bf16 GEMM, forward layout (both operands unit-stride along K)
     dom = [c for c in r5["gemm_calls"] if c["call"] in ("fwd0", "fwd1", "fwd2")]
     dom_s = sum(c["us"] for c in dom) * 1e-6 / len(dom)
@@ -411,7 +439,8 @@ def main():
 
     line = {
         "metric": "train steps/s", "value": r5["steps_per_s"], "unit": "steps/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": r5["ms_per_step"],
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": r5["ms_per_step"], "repeats": args.repeats,
+        "ms_per_step_regions": r5.get("ms_per_step_regions"),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "cfg5: wide MLP 4096-4096-4096-4096-1000, GELU, softmax cross-entropy, batch 8192, "

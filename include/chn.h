@@ -25,7 +25,9 @@
  *     reduction over an empty axis writes the fold's identity.
  *   - An output may alias an input only when both descriptors are identical (in-place update);
  *     partially overlapping views are the caller's responsibility.
- *   - Index values (labels, token ids) must be in range; the library does not check them on device.
+ *   - Index values are never used as offsets unchecked: a label outside [0, C) is treated like
+ *     `ignore_label` (no loss, no gradient, not counted), a token id outside [0, V) gathers a row of
+ *     zeros and receives no gradient.  Nothing is reported: the device cannot fail a call.
  */
 #ifndef CHN_H_
 #define CHN_H_
@@ -346,7 +348,9 @@ chn_status chn_embed_bwd(const chn_array *ids, const chn_array *dout, const chn_
  * and `arch` (default: the current device's, e.g. "gfx950"); NULL keeps a setting, "" restores the
  * default.  Cache files are
  * named by a digest of the generated source, the architecture, the compiler version and the library
- * version, and written atomically; an unwritable cache is not an error.
+ * version, and written atomically; an unwritable cache is not an error.  Without a configured
+ * directory and without $HOME there is no disk cache; directories are created with mode 0700 and a
+ * cached file is used only when it belongs to the calling user and is writable by nobody else.
  * Errors: CHN_ERR_OP (malformed declaration, wrong argument count), CHN_ERR_DTYPE (array dtype
  * against the declaration, inconsistent binding of a type parameter), CHN_ERR_SHAPE, CHN_ERR_AXIS,
  * CHN_ERR_WORKSPACE, CHN_ERR_COMPILE (chn_last_error holds the compiler's first error),
@@ -405,6 +409,13 @@ int chn_elementwise_plan(int op, int n_in, const chn_array *const *in, const chn
  * 256x256 kernel that copies operand tiles straight from global memory into LDS is taken, bits 4 and
  * up the number of K splits (1 = none; have_workspace = 0 plans as chn_gemm does without workspace). */
 int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace);
+/* Test hook: replace the planner's choice for every later chn_gemm / chn_gemm_plan of the process.
+ * tile: 0, 1, 2 as above, or -1 for the planner's own; splits: a number of K splits >= 1 (used when a
+ * workspace allows it), or -1; direct_copy: 0 keeps products off the direct-copy kernel, -1 or 1 lets
+ * the planner take it where it fits.  A forced value that the operands do not allow (the large tiles
+ * need 8-byte pieces) is ignored.  Results do not depend on the plan beyond summation order; the tests
+ * use this to run short products on the large tiles.  (-1, -1, -1) restores normal planning. */
+void chn_gemm_plan_override(int tile, int splits, int direct_copy);
 
 #ifdef __cplusplus
 }

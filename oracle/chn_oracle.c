@@ -291,8 +291,13 @@ void orc_lstm_bwd(const double *gates, const double *c_prev, const double *c, co
 /* Softmax cross-entropy, textbook form.  logits (N,C) contiguous, labels (N,).
  *   lse_n = m + log sum_c exp(z_nc - m), m = max_c z_nc ;  loss_n = lse_n - z[n, t_n]
  *   loss  = (1 / N_valid) sum over rows whose label != ignore_label
- * Rows with the ignored label have loss_n = 0.  N_valid = 0 gives loss 0.
+ * Rows with the ignored label have loss_n = 0.  N_valid = 0 gives loss 0.  A label outside [0, C)
+ * counts as ignored (the boundary's rule for stray indices: never an offset, never an error).
  * Returns N_valid.  loss_rows, lse may be NULL. */
+static int label_counts(int64_t t, int64_t ignore_label, int64_t C) {
+  return t != ignore_label && t >= 0 && t < C;
+}
+
 int64_t orc_softmax_ce_fwd(const double *logits, const int64_t *labels, int64_t N, int64_t C,
                            int64_t ignore_label, double *loss_mean, double *loss_rows,
                            double *lse) {
@@ -307,7 +312,7 @@ int64_t orc_softmax_ce_fwd(const double *logits, const int64_t *labels, int64_t 
     double l = m + log(s);
     if (lse) lse[n] = l;
     double ln = 0.0;
-    if (labels[n] != ignore_label) { ln = l - z[labels[n]]; ++n_valid; total += ln; }
+    if (label_counts(labels[n], ignore_label, C)) { ln = l - z[labels[n]]; ++n_valid; total += ln; }
     if (loss_rows) loss_rows[n] = ln;
   }
   *loss_mean = n_valid > 0 ? total / (double)n_valid : 0.0;
@@ -319,13 +324,13 @@ int64_t orc_softmax_ce_fwd(const double *logits, const int64_t *labels, int64_t 
 void orc_softmax_ce_bwd(const double *logits, const int64_t *labels, int64_t N, int64_t C,
                         int64_t ignore_label, double upstream, double *dlogits) {
   int64_t n_valid = 0;
-  for (int64_t n = 0; n < N; ++n) if (labels[n] != ignore_label) ++n_valid;
+  for (int64_t n = 0; n < N; ++n) if (label_counts(labels[n], ignore_label, C)) ++n_valid;
   double g = n_valid > 0 ? upstream / (double)n_valid : 0.0;
 #pragma omp parallel for schedule(static)
   for (int64_t n = 0; n < N; ++n) {
     const double *z = logits + n * C;
     double *d = dlogits + n * C;
-    if (labels[n] == ignore_label) { for (int64_t c = 0; c < C; ++c) d[c] = 0.0; continue; }
+    if (!label_counts(labels[n], ignore_label, C)) { for (int64_t c = 0; c < C; ++c) d[c] = 0.0; continue; }
     double m = -INFINITY;
     for (int64_t c = 0; c < C; ++c) if (z[c] > m) m = z[c];
     double s = 0.0;
@@ -343,18 +348,21 @@ void orc_sgd_update(double *p, const double *g, int64_t n, double lr) {
   for (int64_t i = 0; i < n; ++i) p[i] = p[i] - lr * g[i];
 }
 
-/* Embedding lookup out[n,:] = table[ids[n],:] and its gradient dtable[v,:] (+)= sum_{n: ids[n]=v} dout[n,:]. */
-void orc_embed_fwd(const double *table, const int64_t *ids, int64_t N, int64_t D, double *out) {
+/* Embedding lookup out[n,:] = table[ids[n],:] and its gradient dtable[v,:] (+)= sum_{n: ids[n]=v} dout[n,:].
+ * An id outside [0, V) selects no row: it gathers zeros and takes part in no sum. */
+void orc_embed_fwd(const double *table, const int64_t *ids, int64_t N, int64_t D, int64_t V, double *out) {
 #pragma omp parallel for schedule(static)
   for (int64_t n = 0; n < N; ++n)
-    for (int64_t d = 0; d < D; ++d) out[n * D + d] = table[ids[n] * D + d];
+    for (int64_t d = 0; d < D; ++d) out[n * D + d] = (ids[n] >= 0 && ids[n] < V) ? table[ids[n] * D + d] : 0.0;
 }
 
 void orc_embed_bwd(const int64_t *ids, const double *dout, int64_t N, int64_t D, int64_t V,
                    int accumulate, double *dtable) {
   if (!accumulate) for (int64_t i = 0; i < V * D; ++i) dtable[i] = 0.0;
-  for (int64_t n = 0; n < N; ++n)
+  for (int64_t n = 0; n < N; ++n) {
+    if (ids[n] < 0 || ids[n] >= V) continue;
     for (int64_t d = 0; d < D; ++d) dtable[ids[n] * D + d] += dout[n * D + d];
+  }
 }
 
 /* Round each value to the nearest bfloat16 (8 significant bits, fp32 exponent range), ties to even,

@@ -54,7 +54,7 @@ def lib():
         L.orc_softmax_ce_bwd.restype = None
         L.orc_sgd_update.argtypes = [dp, dp, C.c_int64, C.c_double]
         L.orc_sgd_update.restype = None
-        L.orc_embed_fwd.argtypes = [dp, ip, C.c_int64, C.c_int64, dp]
+        L.orc_embed_fwd.argtypes = [dp, ip, C.c_int64, C.c_int64, C.c_int64, dp]
         L.orc_embed_fwd.restype = None
         L.orc_embed_bwd.argtypes = [ip, dp, C.c_int64, C.c_int64, C.c_int64, C.c_int, dp]
         L.orc_embed_bwd.restype = None
@@ -245,7 +245,7 @@ def adam_update(p, g, m, v, lr, step, beta1=0.9, beta2=0.999, eps=1e-8):
 def embed_fwd(table, ids):
     table, ids = _c64(table), _i64(ids).reshape(-1)
     out = np.empty((ids.size, table.shape[1]))
-    lib().orc_embed_fwd(_dptr(table), _iptr(ids), ids.size, table.shape[1], _dptr(out))
+    lib().orc_embed_fwd(_dptr(table), _iptr(ids), ids.size, table.shape[1], table.shape[0], _dptr(out))
     return out
 
 

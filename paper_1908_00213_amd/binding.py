@@ -29,7 +29,7 @@ EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
-           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan",
+           "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan", "chn_gemm_plan_override",
            "chn_user_kernel_config", "chn_user_kernel_stats", "chn_user_kernel_destroy",
            "chn_elementwise_kernel_create", "chn_elementwise_kernel_prepare", "chn_elementwise_kernel_launch",
            "chn_reduction_kernel_create", "chn_reduction_kernel_workspace_bytes", "chn_reduction_kernel_prepare",
@@ -85,6 +85,8 @@ def lib():
     L.chn_gemm_workspace_bytes.argtypes = [AP, AP, AP]
     L.chn_gemm_workspace_bytes.restype = C.c_size_t
     L.chn_gemm_plan.argtypes = [AP, AP, AP, C.c_int]
+    L.chn_gemm_plan_override.argtypes = [C.c_int, C.c_int, C.c_int]
+    L.chn_gemm_plan_override.restype = None
     L.chn_gemm.argtypes = [AP, AP, AP, C.c_float, C.c_float, C.c_int, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_lstm_fwd.argtypes = [AP, AP, AP, AP, AP, AP, st]
     L.chn_lstm_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, st]
@@ -221,6 +223,14 @@ def elementwise_broadcast(op, inputs, out, scalars=(), stream=None):
     return out
 
 
+def cast(x, dtype):
+    """A copy of `x` in another storage type through the library's own kernel (CHN_OP_COPY: fp32 values
+    round to nearest even on their way to bfloat16); torch only allocates the result."""
+    if x.dtype == dtype:
+        return x
+    return elementwise_broadcast("copy", [x], torch.empty(x.shape, dtype=dtype, device=x.device))
+
+
 def reduce_axis_workspace_bytes(x, axis):
     return lib().chn_reduce_axis_workspace_bytes(_ref(desc(x)), axis)
 
@@ -257,6 +267,11 @@ def gemm_plan(A, B, Cm, have_workspace=False):
     if code < 0:
         _check(code)
     return code & 3, bool(code & 4), code >> 4
+
+
+def gemm_plan_override(tile=-1, splits=-1, direct_copy=-1):
+    """Test hook: force the macro tile / K splits / keep products off the direct-copy kernel (-1: planner's choice)."""
+    lib().chn_gemm_plan_override(int(tile), int(splits), int(direct_copy))
 
 
 def gemm(A, B, Cm, alpha=1.0, beta=0.0, epilogue="none", bias=None, aux=None, preact_out=None,

@@ -14,7 +14,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchn.so")
-TOOL = os.path.join(HERE, "mfma_ceiling")
 
 SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "argmax.hip", "gemm.hip", "lstm.hip", "lstm_step.hip", "softmax_ce.hip",
            "sgd.hip", "adam.hip", "embed.hip"]
@@ -80,11 +79,6 @@ def build(force=False, verbose=False, extra=()):
     if force or _stale(LIB, objs):
         cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lhiprtc"]
         subprocess.run(cmd, check=True)
-    # measurement aid: what the matrix cores sustain (a stand-alone program, see its header)
-    tool_src = os.path.join(CSRC, "mfma_ceiling.hip")
-    if force or _stale(TOOL, [tool_src]):
-        subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-Wno-unused-command-line-argument", tool_src, "-o", TOOL],
-                       check=True, capture_output=not verbose)
     return LIB
 
 

@@ -12,13 +12,18 @@ namespace chn {
 namespace {
 
 template <typename T, typename L, bool VEC>
-__global__ __launch_bounds__(256) void embed_fwd_kernel(const T *table, int64_t tpitch, const L *ids, int64_t N, int64_t D,
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const T *table, int64_t tpitch, int64_t V, const L *ids, int64_t N, int64_t D,
                                                         T *out, int64_t opitch) {
   const int lane = threadIdx.x & 63;
   const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= N) return;
-  const T *src = table + (int64_t)ids[n] * tpitch;
+  const int64_t id = (int64_t)ids[n];
   T *dst = out + n * opitch;
+  if ((uint64_t)id >= (uint64_t)V) {   // an id outside the table is never used as an offset: its row reads as zeros
+    for (int64_t d = lane; d < D; d += 64) dst[d] = T(0);
+    return;
+  }
+  const T *src = table + id * tpitch;
   if constexpr (VEC) {
     constexpr int NV = 16 / sizeof(T);
     const int64_t nvec = D / NV;
@@ -123,7 +128,7 @@ chn_status chn_embed_fwd(const chn_array *table, const chn_array *ids, const chn
   hipStream_t st = as_stream(stream);
   const bool i32 = ids->dtype == CHN_I32;
 #define CHN_GO(T, L, V_)                                                                                     \
-  hipLaunchKernelGGL((embed_fwd_kernel<T, L, V_>), dim3(blocks), dim3(256), 0, st, static_cast<const T *>(table->data), tp, \
+  hipLaunchKernelGGL((embed_fwd_kernel<T, L, V_>), dim3(blocks), dim3(256), 0, st, static_cast<const T *>(table->data), tp, V, \
                      static_cast<const L *>(ids->data), N, D, static_cast<T *>(out->data), op)
   if (isz == 4) {
     if (i32) { if (vec) CHN_GO(float, int32_t, true); else CHN_GO(float, int32_t, false); }

@@ -1,6 +1,6 @@
 // chn_gemm: host side of the dense product -- validation, layout classification and dispatch to the
 // kernel families in gemm_kernel.h (one object file per dtype and operand layout).
-#include <cstdlib>
+#include <atomic>
 
 #include "common.h"
 #include "gemm_args.h"
@@ -20,6 +20,9 @@ namespace chn {
 namespace {
 
 using gemm::GemmArgs;
+
+// chn_gemm_plan_override: what tests force instead of the planner's choice (-1: not forced)
+std::atomic<int> g_force_tile{-1}, g_force_splits{-1}, g_force_direct{-1};
 
 // Largest load piece (bytes) that is aligned for every row start of the operand and divides its
 // extent along the unit-stride dimension, so that a piece is never partly out of range.
@@ -54,10 +57,9 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
 
 // Whether the direct-copy 256x256 kernel can take the product: it needs 16-byte pieces (so K is a
 // multiple of the chunk length for K-contiguous operands) and 32-bit offsets inside a tile; fp32 needs
-// at least one K-contiguous operand for it.  (CHN_GEMM_DMA=0 in the environment switches it off: a
-// tuning aid.)
+// at least one K-contiguous operand for it.
 bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
-  static const bool dma_on = [] { const char *e = getenv("CHN_GEMM_DMA"); return !e || atoi(e) != 0; }();
+  const bool dma_on = g_force_direct.load(std::memory_order_relaxed) != 0;
   const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
   return dma_on && g.piece == 16 && g.K > 0 && g.lda < max_ld && g.ldb < max_ld && (isz == 2 || a_kc || b_kc);
 }
@@ -111,9 +113,8 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big
       if (t < best * 0.97) { best = t; g->tile = tile; g->splits = s; }   // prefer larger tiles / fewer splits on near-ties
     }
   }
-  {   // tuning aids: force the tile / the number of splits from the environment
-    static const int force_tile = [] { const char *e = getenv("CHN_GEMM_TILE"); return e ? atoi(e) : -1; }();
-    static const int force_splits = [] { const char *e = getenv("CHN_GEMM_SPLITS"); return e ? atoi(e) : 0; }();
+  {   // chn_gemm_plan_override
+    const int force_tile = g_force_tile.load(std::memory_order_relaxed), force_splits = g_force_splits.load(std::memory_order_relaxed);
     if (force_tile >= 0 && force_tile <= (wide ? 2 : 0)) g->tile = force_tile;
     if (force_splits >= 1 && allow_split && force_splits <= nk) g->splits = force_splits;
   }
@@ -144,6 +145,12 @@ size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const ch
   if (classify(A, B, &g, &a_kc, &b_kc) != CHN_OK) return 0;
   plan(&g, dtype_size(A->dtype), a_kc, b_kc, true);
   return split_bytes(g);
+}
+
+void chn_gemm_plan_override(int tile, int splits, int direct_copy) {
+  chn::g_force_tile.store(tile, std::memory_order_relaxed);
+  chn::g_force_splits.store(splits, std::memory_order_relaxed);
+  chn::g_force_direct.store(direct_copy, std::memory_order_relaxed);
 }
 
 int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace) {

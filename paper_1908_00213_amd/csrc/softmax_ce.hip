@@ -92,6 +92,14 @@ __device__ __forceinline__ MS row_scan(const T *p, int64_t C, int g) {
   return acc;
 }
 
+// The label of a row as the kernels use it: a value outside [0, C) is never used as an offset -- such a
+// row is treated like one that carries `ignore` (no loss, no gradient, not counted among the valid rows).
+template <typename L>
+__device__ __forceinline__ int64_t row_label(const L *labels, int64_t row, int64_t ignore, int64_t C) {
+  const int64_t t = (int64_t)labels[row];
+  return (uint64_t)t < (uint64_t)C ? t : ignore;
+}
+
 template <typename T, typename L, int G, bool VEC>
 __global__ __launch_bounds__(256) void sce_fwd_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
                                                       int64_t ignore, float *loss_rows, float *lse_out) {
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(256) void sce_fwd_kernel(const T *z, int64_t pitch,
   MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
   if (g == 0 && live) {
     const float lse = v.m + logf(v.s);
-    const int64_t t = (int64_t)labels[row];
+    const int64_t t = row_label(labels, row, ignore, C);
     if (lse_out) lse_out[row] = lse;
     loss_rows[row] = t == ignore ? 0.0f : lse - Elem<T>::load(p + t);
   }
@@ -112,14 +120,14 @@ __global__ __launch_bounds__(256) void sce_fwd_kernel(const T *z, int64_t pitch,
 
 // loss_mean = sum of loss_rows over valid rows / number of valid rows, fixed order.
 template <typename L>
-__global__ __launch_bounds__(1024) void sce_mean_kernel(const float *loss_rows, const L *labels, int64_t N, int64_t ignore,
+__global__ __launch_bounds__(1024) void sce_mean_kernel(const float *loss_rows, const L *labels, int64_t N, int64_t C, int64_t ignore,
                                                         float *loss_mean) {
   __shared__ float ssum[16];
   __shared__ int scnt[16];
   float s = 0.0f;
   int cnt = 0;
   for (int64_t n = threadIdx.x; n < N; n += 1024)
-    if ((int64_t)labels[n] != ignore) { s += loss_rows[n]; ++cnt; }
+    if (row_label(labels, n, ignore, C) != ignore) { s += loss_rows[n]; ++cnt; }
   s = wave_sum(s);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
@@ -135,10 +143,10 @@ __global__ __launch_bounds__(1024) void sce_mean_kernel(const float *loss_rows, 
 
 // scale = upstream / N_valid (0 when no row is valid)
 template <typename L>
-__global__ __launch_bounds__(1024) void sce_scale_kernel(const L *labels, int64_t N, int64_t ignore, float upstream, float *scale) {
+__global__ __launch_bounds__(1024) void sce_scale_kernel(const L *labels, int64_t N, int64_t C, int64_t ignore, float upstream, float *scale) {
   __shared__ int scnt[16];
   int cnt = 0;
-  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += ((int64_t)labels[n] != ignore) ? 1 : 0;
+  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += (row_label(labels, n, ignore, C) != ignore) ? 1 : 0;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
   if ((threadIdx.x & 63) == 0) scnt[threadIdx.x >> 6] = cnt;
@@ -201,7 +209,7 @@ __global__ __launch_bounds__(256) void sce_bwd_kernel(const T *z, int64_t pitch,
     lse = v.m + logf(v.s);
   }
   if (!live) return;
-  const int64_t t = (int64_t)labels[row];
+  const int64_t t = row_label(labels, row, ignore, C);
   const float scale = t == ignore ? 0.0f : *scale_ptr;
   row_grad<T, TO, G, VEC>(p, dz + row * dpitch, C, g, t, lse, scale);
 }
@@ -222,7 +230,7 @@ __global__ __launch_bounds__(256) void sce_fused_kernel(const T *z, int64_t pitc
   const T *p = z + row * pitch;
   const MS v = group_merge<G>(row_scan<T, G, VEC>(p, C, g), smem);
   const float lse = v.m + logf(v.s);
-  const int64_t t = (int64_t)labels[row];
+  const int64_t t = row_label(labels, row, ignore, C);
   float zt = 0.0f;
   if (g == 0 && live && t != ignore) zt = Elem<T>::load(p + t);   // (read before the row may be overwritten)
   if constexpr (G == 256) __syncthreads();
@@ -245,7 +253,7 @@ __global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pit
   __shared__ float ssum[16];
   __shared__ int scnt[16];
   int cnt = 0;
-  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += ((int64_t)labels[n] != ignore) ? 1 : 0;
+  for (int64_t n = threadIdx.x; n < N; n += 1024) cnt += (row_label(labels, n, ignore, C) != ignore) ? 1 : 0;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
   if ((threadIdx.x & 63) == 0) scnt[threadIdx.x >> 6] = cnt;
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pit
     float e = 0.0f;
     for (int64_t c = 0; c < C; ++c) e += expf(Elem<T>::load(p + c) - m);
     const float lse = m + logf(e);
-    const int64_t t = (int64_t)labels[n];
+    const int64_t t = row_label(labels, n, ignore, C);
     if (lse_out) lse_out[n] = lse;
     if (t != ignore) s += lse - Elem<T>::load(p + t);
     const float scale = t == ignore ? 0.0f : scale_all;
@@ -398,9 +406,9 @@ chn_status chn_softmax_ce_fwd(const chn_array *logits, const chn_array *labels, 
   }
   float *lm = static_cast<float *>(loss_mean->data);
   if (labels->dtype == CHN_I32)
-    hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, ignore_label, lm);
+    hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, c.C, ignore_label, lm);
   else
-    hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, ignore_label, lm);
+    hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, c.C, ignore_label, lm);
   return check_launch("softmax_ce_fwd mean");
 }
 
@@ -421,8 +429,8 @@ chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels, 
   float *scale = static_cast<float *>(ws);
   hipStream_t st = as_stream(stream);
   const bool i32 = labels->dtype == CHN_I32;
-  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, ignore_label, upstream, scale);
-  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, c.C, ignore_label, upstream, scale);
+  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, c.C, ignore_label, upstream, scale);
   CHN_TRY(check_launch("softmax_ce_bwd scale"));
   const int no = 16 / dtype_size(dlogits->dtype);
   const bool vec = c.vec && reinterpret_cast<uintptr_t>(dlogits->data) % 16 == 0 && dpitch % no == 0;
@@ -479,8 +487,8 @@ chn_status chn_softmax_ce_fwd_bwd(const chn_array *logits, const chn_array *labe
   CHN_TRY(check_ws(ws, ws_bytes, chn_softmax_ce_workspace_bytes(c.N), "softmax_ce_fwd_bwd"));
   float *scale = static_cast<float *>(ws);
   float *rows = reinterpret_cast<float *>(static_cast<char *>(ws) + 256);
-  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, ignore_label, upstream, scale);
-  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, ignore_label, upstream, scale);
+  if (i32) hipLaunchKernelGGL((sce_scale_kernel<int32_t>), dim3(1), dim3(1024), 0, st, static_cast<const int32_t *>(labels->data), c.N, c.C, ignore_label, upstream, scale);
+  else hipLaunchKernelGGL((sce_scale_kernel<int64_t>), dim3(1), dim3(1024), 0, st, static_cast<const int64_t *>(labels->data), c.N, c.C, ignore_label, upstream, scale);
   CHN_TRY(check_launch("softmax_ce_fwd_bwd scale"));
   const int no = 16 / dtype_size(dlogits->dtype);
   const bool vec = c.vec && reinterpret_cast<uintptr_t>(dlogits->data) % 16 == 0 && dpitch % no == 0;
@@ -495,8 +503,8 @@ chn_status chn_softmax_ce_fwd_bwd(const chn_array *logits, const chn_array *labe
   else CHN_GO(bf16_raw, bf16_raw);
 #undef CHN_GO
   CHN_TRY(check_launch("softmax_ce_fwd_bwd rows"));
-  if (i32) hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, ignore_label, lm);
-  else hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, ignore_label, lm);
+  if (i32) hipLaunchKernelGGL((sce_mean_kernel<int32_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int32_t *>(labels->data), c.N, c.C, ignore_label, lm);
+  else hipLaunchKernelGGL((sce_mean_kernel<int64_t>), dim3(1), dim3(1024), 0, st, rows, static_cast<const int64_t *>(labels->data), c.N, c.C, ignore_label, lm);
   return check_launch("softmax_ce_fwd_bwd mean");
 }
 

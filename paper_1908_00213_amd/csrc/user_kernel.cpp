@@ -70,7 +70,8 @@ std::string cache_dir() {
   if (!g_cache_dir.empty()) return g_cache_dir;
   if (const char *e = getenv("CHN_KERNEL_CACHE_DIR")) return e;
   const char *home = getenv("HOME");
-  return std::string(home ? home : "/tmp") + "/.cache/libchn/kernels";
+  if (!home || !*home) return std::string();   // no home and no configured directory: no disk cache (never a shared /tmp)
+  return std::string(home) + "/.cache/libchn/kernels";
 }
 
 chn_status target_arch(std::string *arch) {
@@ -86,9 +87,18 @@ chn_status target_arch(std::string *arch) {
   return CHN_OK;
 }
 
+// (directories this creates are private to the user: cached code objects are executed)
 void mkdirs(const std::string &path) {
   for (size_t i = 1; i <= path.size(); ++i)
-    if (i == path.size() || path[i] == '/') mkdir(path.substr(0, i).c_str(), 0755);
+    if (i == path.size() || path[i] == '/') mkdir(path.substr(0, i).c_str(), 0700);
+}
+
+// A cached code object is only trusted when it is a regular file that belongs to this user and that
+// nobody else may write.
+bool trusted_file(FILE *f) {
+  struct stat st;
+  if (fstat(fileno(f), &st) != 0) return false;
+  return S_ISREG(st.st_mode) && st.st_uid == geteuid() && (st.st_mode & (S_IWGRP | S_IWOTH)) == 0;
 }
 
 // 128 bits of FNV-1a (two offset bases) as hex: the file name of a cached code object
@@ -398,10 +408,14 @@ chn_status binary_for(chn_user_kernel *k, const std::string &key, const std::str
   const std::string file = dir + "/" + digest(src + "|" + arch + "|" + std::to_string(rtc_major) + "." + std::to_string(rtc_minor) +
                                               "|" + std::to_string(chn_version())) + ".hsaco";
   std::vector<char> buf;
-  if (FILE *f = fopen(file.c_str(), "rb")) {
-    fseek(f, 0, SEEK_END);
-    long n = ftell(f);
-    fseek(f, 0, SEEK_SET);
+  FILE *cached = dir.empty() ? nullptr : fopen(file.c_str(), "rb");
+  if (FILE *f = cached) {
+    long n = 0;
+    if (trusted_file(f)) {
+      fseek(f, 0, SEEK_END);
+      n = ftell(f);
+      fseek(f, 0, SEEK_SET);
+    }
     if (n > 0) { buf.resize(n); if (fread(buf.data(), 1, n, f) != (size_t)n) buf.clear(); }
     fclose(f);
     if (!buf.empty() && (buf.size() < 4 || memcmp(buf.data(), "\177ELF", 4) != 0)) buf.clear();   // not a code object
@@ -410,10 +424,11 @@ chn_status binary_for(chn_user_kernel *k, const std::string &key, const std::str
     ++g_disk_hits;
   } else {
     CHN_TRY(compile(k->name, src, arch, &buf));
-    mkdirs(dir);
+    if (!dir.empty()) mkdirs(dir);
     const std::string tmp = file + ".tmp" + std::to_string((long long)getpid());
-    if (FILE *f = fopen(tmp.c_str(), "wb")) {      // a cache that cannot be written is not an error
-      bool ok = fwrite(buf.data(), 1, buf.size(), f) == buf.size();
+    if (FILE *f = dir.empty() ? nullptr : fopen(tmp.c_str(), "wb")) {      // a cache that cannot be written is not an error
+      bool ok = fchmod(fileno(f), 0600) == 0;       // whatever the umask: writable by the owner alone
+      ok = fwrite(buf.data(), 1, buf.size(), f) == buf.size() && ok;
       ok = fclose(f) == 0 && ok;
       if (!ok || rename(tmp.c_str(), file.c_str()) != 0) unlink(tmp.c_str());
     }

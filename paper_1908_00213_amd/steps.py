@@ -23,7 +23,7 @@ from . import binding as B
 
 def _dev(a, lowp=False):
     t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    return t.to(torch.bfloat16) if lowp else t
+    return B.cast(t, torch.bfloat16) if lowp else t
 
 
 class _Program:
@@ -107,7 +107,7 @@ class MLPTrainer:
         self.fused_loss = fused_loss      # loss and its gradient in one call (else the two separate calls)
         self.W = [_dev(W) for W, _ in params]
         self.b = [_dev(b) for _, b in params]
-        self.Wl = [w.to(torch.bfloat16) for w in self.W] if lowp else self.W
+        self.Wl = [B.cast(w, torch.bfloat16) for w in self.W] if lowp else self.W
         adt = torch.bfloat16 if lowp else torch.float32
         n = len(params)
         self.sizes = [params[0][0].shape[1]] + [W.shape[0] for W, _ in params]
@@ -237,7 +237,7 @@ class LSTMTrainer:
         adt = torch.bfloat16 if lowp else torch.float32
         za = lambda *s: torch.zeros(*s, dtype=adt, device="cuda")
         # working copies the products read: bf16 in mixed precision, else the parameters themselves
-        self._Pl = {k: (v.to(torch.bfloat16) if lowp and k in ("E", "W", "U", "W_out") else v) for k, v in self._P.items()}
+        self._Pl = {k: (B.cast(v, torch.bfloat16) if lowp and k in ("E", "W", "U", "W_out") else v) for k, v in self._P.items()}
         # zero-initialised: the inert columns must hold zeros before the first step
         self._X, self._Z, self._G = za(n, Ep), z(n, 4 * Hp), z(n, 4 * Hp)
         self._Hs = za(n + Bn, Hp)  # block 0 = h_0 = 0

@@ -58,7 +58,7 @@ class GpuBackend:
     def from_numpy(self, a, dtype=None):
         import numpy as np
         t = self.torch.from_numpy(np.ascontiguousarray(a)).cuda()
-        return t if dtype is None else t.to(self._dt[dtype])
+        return t if dtype is None else self.B.cast(t, self._dt[dtype])
 
     def to_numpy(self, a):
         return a.detach().to(self.torch.float64 if a.is_floating_point() else a.dtype).cpu().numpy()

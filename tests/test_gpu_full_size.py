@@ -315,3 +315,136 @@ def test_config4_full_size_mixed_precision_sampled():
         check(new, O.sgd_update(P0[k], g[k], lr), 1e-6, np.abs(P0[k]) + lr * np.abs(g[k]), "update " + k)
         if k in ("E", "W", "U", "W_out"):
             assert np.array_equal(host(tr._unpadded(tr._Pl)[k]), O.round_bf16(new)), k
+
+
+# ---- every tile of the benchmarked launches, bit for bit --------------------------------------------------------
+# Operands are small integers (|v| <= 3): every partial sum is an integer below 2^24, so the product is exact
+# in fp32 in any summation order and the WHOLE output must equal the exact product bit for bit.  The exact
+# product is NumPy's fp64 matmul, tied to the oracle on a stratified sample: in every 256 x 256 tile of the
+# output its four corner entries and one random interior entry (so every tile and every tile-edge row and
+# column is looked at), plus the matrix's last rows and columns.
+def _int_operand(shape, transposed_storage):
+    """bf16 tensor of small integers with the given logical shape; stored transposed when asked."""
+    v = RNG.integers(-3, 4, size=shape).astype(np.float32)
+    if transposed_storage:
+        t = torch.from_numpy(np.ascontiguousarray(v.T)).cuda().to(torch.bfloat16).t()
+    else:
+        t = torch.from_numpy(v).cuda().to(torch.bfloat16)
+    return v, t
+
+
+def _tie_to_oracle(A, Bm, ref):
+    M, N = ref.shape
+    ms, ns = [], []
+    for tm in range(0, M, 256):
+        for tn in range(0, N, 256):
+            r1, c1 = min(tm + 255, M - 1), min(tn + 255, N - 1)
+            ms += [tm, tm, r1, r1, int(RNG.integers(tm, r1 + 1))]
+            ns += [tn, c1, tn, c1, int(RNG.integers(tn, c1 + 1))]
+    got = O.gemm_entries(A, Bm, ms, ns)
+    assert np.array_equal(got, ref[ms, ns])
+
+
+# the three layouts of a hidden layer of workload 5 (forward x W^T, input gradient dY W, weight gradient dY^T X)
+# and of its 1000-class output layer
+HEADLINE_PRODUCTS = [
+    ("fwd hidden", 8192, 4096, 4096, False, True),      # A (M,K) row-major, B = W^T: W (N,K) row-major
+    ("dx hidden", 8192, 4096, 4096, False, False),      # B = W (K,N) row-major
+    ("dW hidden", 4096, 4096, 8192, True, False),       # A = dY^T: dY (K,M) row-major
+    ("fwd classes", 8192, 1000, 4096, False, True),
+    ("dx classes", 8192, 4096, 1000, False, False),
+    ("dW classes", 1000, 4096, 8192, True, False),
+]
+
+
+@pytest.mark.parametrize("name,M,N,K,a_t,b_t", HEADLINE_PRODUCTS)
+def test_headline_products_whole_output_bit_exact(name, M, N, K, a_t, b_t):
+    A, Ad = _int_operand((M, K), a_t)
+    Bm, Bd = _int_operand((K, N), b_t)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    _tie_to_oracle(A, Bm, ref)
+    Cd = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    need = B.gemm_workspace_bytes(Ad, Bd, Cd)
+    ws = torch.empty(max(256, need), dtype=torch.uint8, device="cuda")
+    B.gemm(Ad, Bd, Cd, ws=ws)
+    out = Cd.cpu().numpy()
+    bad = np.argwhere(out != ref)
+    assert bad.size == 0, "%s: %d entries differ, first at %s (tile %s)" % (name, len(bad), bad[0], bad[0] // 256)
+
+
+def test_headline_forward_epilogue_whole_output():
+    """The benchmarked forward launch itself: bias + GELU, bf16 output and bf16 pre-activation.  With integer
+    operands and an integer bias v = acc + bias is exact, so the stored pre-activation must be the
+    nearest-even bf16 of the exact value everywhere; the activation is compared within the bf16 bar."""
+    M, N, K = 8192, 4096, 4096
+    A, Ad = _int_operand((M, K), False)
+    Bm, Bd = _int_operand((K, N), True)
+    bias = RNG.integers(-5, 6, size=N).astype(np.float32)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    _tie_to_oracle(A, Bm, ref)
+    v = ref + bias
+    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    pre = torch.empty_like(out)
+    B.gemm(Ad, Bd, out, epilogue="bias_gelu", bias=torch.from_numpy(bias).cuda(), preact_out=pre)
+    got_pre = pre.float().cpu().numpy()
+    rows = np.sort(RNG.choice(M, 64, replace=False))
+    assert np.array_equal(O.round_bf16(v[rows]), W.bf16_exact(v[rows].astype(np.float32)))    # host rounding helper tied to the oracle's
+    assert np.array_equal(got_pre, W.bf16_exact(v.astype(np.float32)))                         # v is an integer below 2^24: the cast is exact
+    got = out.float().cpu().numpy().astype(np.float64)
+    gref = O.elementwise("gelu", [v[rows]])
+    check(got[rows], gref, TOL_BF16, np.abs(v[rows]), "gelu rows")
+    # everywhere: SciPy's erf form over the whole output (tied to the oracle's gelu on the sampled rows above)
+    import scipy.special as sps
+    full = 0.5 * v * (1.0 + sps.erf(v / np.sqrt(2.0)))
+    assert np.max(np.abs(full[rows] - gref)) <= 1e-12 * np.max(np.abs(v))
+    check(got, full, TOL_BF16, np.abs(v), "gelu everywhere")
+
+
+def test_headline_input_gradient_epilogue_and_row_block_sums_whole_output():
+    """dx of a hidden layer as benchmarked: the activation-gradient epilogue with the per-128-row column sums.
+    With the ReLU gradient and integer data everything is exact: C = RNE_bf16(acc * [aux > 0]) and the row-block
+    sums are sums of those stored integers (below 2^24), so both outputs are compared bit for bit; the GELU
+    gradient form (the one the benchmark runs) is compared within the bf16 bar on sampled rows and its row-block
+    sums against the sums of what it stored."""
+    M, N, K = 8192, 4096, 4096
+    A, Ad = _int_operand((M, K), False)
+    Bm, Bd = _int_operand((K, N), False)
+    aux = RNG.integers(-2, 3, size=(M, N)).astype(np.float32)
+    auxd = torch.from_numpy(aux).cuda().to(torch.bfloat16)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    _tie_to_oracle(A, Bm, ref)
+    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    sums = torch.empty(M // 128, N, dtype=torch.float32, device="cuda")
+    B.gemm(Ad, Bd, out, epilogue="relu_bwd", aux=auxd, preact_out=sums)
+    want = W.bf16_exact((ref * (aux > 0)).astype(np.float32)).astype(np.float64)
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, want)
+    assert np.array_equal(sums.cpu().numpy().astype(np.float64), want.reshape(M // 128, 128, N).sum(axis=1))
+    rows = np.sort(RNG.choice(M, 48, replace=False))
+    assert np.array_equal(O.elementwise("relu_bwd", [ref[rows], aux[rows]]), ref[rows] * (aux[rows] > 0))
+    B.gemm(Ad, Bd, out, epilogue="gelu_bwd", aux=auxd, preact_out=sums)
+    got = out.float().cpu().numpy().astype(np.float64)
+    check(got[rows], O.elementwise("gelu_bwd", [ref[rows], aux[rows]]), TOL_BF16, np.abs(ref[rows]), "gelu_bwd rows")
+    blk = got.reshape(M // 128, 128, N)
+    check(sums.cpu().numpy().astype(np.float64), blk.sum(axis=1), TOL_SUM, np.abs(blk).sum(axis=1), "row-block sums")
+
+
+def test_headline_weight_gradient_with_fused_update_whole_output():
+    """dW of a hidden layer as benchmarked: alpha = -lr, beta = 1 on the fp32 master weights, bf16 copy written in
+    the same pass.  lr = 2^-7 and masters on a 2^-4 grid keep v = W - lr * dW exact in fp32, so the masters are
+    compared bit for bit and the working copy is the nearest-even bf16 of them."""
+    M, N, K = 4096, 4096, 8192
+    A, Ad = _int_operand((M, K), True)
+    Bm, Bd = _int_operand((K, N), False)
+    W0 = (RNG.integers(-32, 33, size=(M, N)) / 16.0).astype(np.float32)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64)
+    _tie_to_oracle(A, Bm, ref)
+    lr = 2.0 ** -7
+    Wd = torch.from_numpy(W0.copy()).cuda()
+    Wl = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    B.gemm(Ad, Bd, Wd, alpha=-lr, beta=1.0, epilogue="bf16_copy", preact_out=Wl)
+    want = W0.astype(np.float64) - lr * ref
+    rows = np.sort(RNG.choice(M, 16, replace=False))
+    assert np.array_equal(O.sgd_update(W0[rows], ref[rows], lr), want[rows])
+    assert np.array_equal(Wd.cpu().numpy().astype(np.float64), want)
+    assert np.array_equal(Wl.float().cpu().numpy(), W.bf16_exact(want.astype(np.float32)))

@@ -71,8 +71,8 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
 
 
 # The planner takes the 256x256 tile only when K is long enough to pay for its fixed cost; the short-K
-# cases (one, two, three tile steps: where a pipeline's prologue and tail go wrong) run in a child
-# process that forces the tile through the library's tuning variable CHN_GEMM_TILE.
+# cases (one, two, three tile steps: where a pipeline's prologue and tail go wrong) force the tile
+# through the library's test hook chn_gemm_plan_override.
 DIRECT_COPY_CASES = [("bf16", s) for s in [(3704, 3592, 1024), (3720, 3592, 1000), (3704, 3592, 1088)]] + \
                     [("f32", s) for s in [(3704, 3592, 1000), (3720, 3592, 1024), (3704, 3592, 1056)]]
 DIRECT_COPY_SHORT_K = [("bf16", s) for s in [(3704, 3592, 192), (3704, 3592, 64), (3720, 3592, 128), (3704, 3592, 200), (520, 264, 448)]] + \
@@ -102,20 +102,14 @@ def test_gemm_big_tiles_direct_copy(dt, layout, shape):
 
 
 def test_gemm_big_tiles_direct_copy_short_k_forced_tile():
-    import os, subprocess, sys
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, CHN_GEMM_TILE="2", PYTHONPATH=root)
-    code = ("import tests.test_gpu_gemm as t\n"
-            "n = 0\n"
-            "for dt, shape in t.DIRECT_COPY_SHORT_K:\n"
-            "    for layout in ('nt', 'nn', 'tn'):\n"
-            "        print(dt, layout, shape, flush=True)\n"
-            "        t.direct_copy_case(dt, layout, shape)\n"
-            "        n += 1\n"
-            "print('cases passed:', n)\n")
-    r = subprocess.run([sys.executable, "-u", "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
-    assert "cases passed: %d" % (3 * len(DIRECT_COPY_SHORT_K)) in r.stdout
+    B.gemm_plan_override(tile=2)
+    try:
+        for dt, shape in DIRECT_COPY_SHORT_K:
+            for layout in ("nt", "nn", "tn"):
+                print(dt, layout, shape, flush=True)
+                direct_copy_case(dt, layout, shape)
+    finally:
+        B.gemm_plan_override()
 
 
 def test_gemm_direct_copy_odd_k_both_transposed():

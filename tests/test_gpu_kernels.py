@@ -330,6 +330,49 @@ def test_softmax_ce(N, Cn, dt, lab):
         check(host(zc), ref, TOL_EW * 10, 1.5 / nv, "in place")
 
 
+@pytest.mark.parametrize("N,Cn,lab", [(300, 10, np.int32), (70, 1000, np.int64), (9000, 10, np.int32), (64, 4100, np.int32)])
+def test_softmax_ce_and_embedding_never_follow_a_stray_index(N, Cn, lab):
+    """Labels outside [0, C) count as ignored; ids outside [0, V) gather zeros and receive no gradient.
+    (Every kernel family: separate forward / backward, the fused call, its one-workgroup form.)"""
+    z = rnd((N, Cn), "f32", -6, 6)
+    t = RNG.integers(0, Cn, size=(N,)).astype(lab)
+    t[::7] = -1
+    t[3::11] = Cn
+    t[5::13] = -100
+    t[1] = np.iinfo(lab).max
+    zd, td = dev(z), dev(t)
+    w = ws(B.softmax_ce_workspace_bytes(N))
+    rl, rrows, rlse, nv = O.softmax_ce_fwd(z, t)
+    assert nv == int(((t >= 0) & (t < Cn)).sum())
+    loss, rows, lse = empty(()), empty((N,)), empty((N,))
+    B.softmax_ce_fwd(zd, td, loss, rows, lse, ws=w)
+    check(host(rows), rrows, TOL_SUM, np.abs(rlse), "loss rows")
+    check(host(loss), np.array(rl), TOL_SUM, None, "loss mean")
+    ref = O.softmax_ce_bwd(z, t, -1, 1.5)
+    dz = B.softmax_ce_bwd(zd, td, empty((N, Cn)), lse, 1.5, ws=w)
+    check(host(dz), ref, TOL_EW * 10, 1.5 / nv, "dlogits")
+    bad = (t < 0) | (t >= Cn)
+    assert np.all(host(dz)[bad] == 0) and np.all(host(rows)[bad] == 0)
+    loss2, dz2 = empty(()), empty((N, Cn))
+    B.softmax_ce_fwd_bwd(zd, td, loss2, dz2, None, 1.5, ws=w)
+    check(host(loss2), np.array(rl), TOL_SUM, None, "fused loss")
+    check(host(dz2), ref, TOL_EW * 10, 1.5 / nv, "fused dlogits")
+    assert np.all(host(dz2)[bad] == 0)
+    # embedding
+    V, D = 50, 72
+    E = rnd((V, D))
+    ids = RNG.integers(0, V, size=(N,)).astype(lab)
+    ids[2::9] = V
+    ids[4::10] = -3
+    ids[0] = np.iinfo(lab).max
+    out = B.embed_fwd(dev(E), dev(ids), empty((N, D)))
+    assert np.array_equal(host(out), O.embed_fwd(E, ids))
+    assert np.all(host(out)[(ids < 0) | (ids >= V)] == 0)
+    dout = rnd((N, D))
+    dt_ = B.embed_bwd(dev(ids), dev(dout), empty((V, D)))
+    check(host(dt_), O.embed_bwd(ids, dout, V), TOL_SUM, O.embed_bwd(ids, np.abs(dout), V), "embed_bwd with stray ids")
+
+
 @pytest.mark.parametrize("N,Cn,dt,lab", [(37, 10, "f32", np.int32), (1024, 10, "f32", np.int64), (3000, 33, "bf16", np.int32),   # one block
                                          (8193, 10, "f32", np.int32), (300, 1000, "f32", np.int64), (70, 4100, "f32", np.int32),
                                          (129, 1000, "bf16", np.int32), (33, 2051, "bf16", np.int64), (5, 65, "f32", np.int32)])

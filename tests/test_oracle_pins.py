@@ -347,6 +347,27 @@ def test_mlp_step_lowp_rounds_only_storage():
     assert r16["loss"] != r32["loss"]
 
 
+def test_stray_indices_are_ignored_not_followed():
+    # a label outside [0, C) behaves exactly like the ignore label; an id outside [0, V) gathers zeros and
+    # takes part in no gradient sum -- checked against the same problem with those rows marked / removed
+    z = RNG.standard_normal((9, 5))
+    t = RNG.integers(0, 5, 9)
+    stray, marked = t.copy(), t.copy()
+    stray[[1, 4, 7]] = [5, -100, 2 ** 40]
+    marked[[1, 4, 7]] = -1
+    a, b = O.softmax_ce_fwd(z, stray), O.softmax_ce_fwd(z, marked)
+    assert a[0] == b[0] and np.array_equal(a[1], b[1]) and a[3] == b[3] == 6
+    assert np.array_equal(O.softmax_ce_bwd(z, stray, -1, 2.0), O.softmax_ce_bwd(z, marked, -1, 2.0))
+    keep = [0, 2, 3, 5, 6, 8]
+    assert abs(a[0] - O.softmax_ce_fwd(z[keep], t[keep])[0]) < 1e-15
+    E = RNG.standard_normal((6, 3))
+    ids = np.array([0, 6, 5, -1, 2, 10 ** 12])
+    out = O.embed_fwd(E, ids)
+    assert np.array_equal(out[[0, 2, 4]], E[[0, 5, 2]]) and np.all(out[[1, 3, 5]] == 0)
+    w = RNG.standard_normal((6, 3))
+    assert np.array_equal(O.embed_bwd(ids, w, 6), O.embed_bwd(ids[[0, 2, 4]], w[[0, 2, 4]], 6))
+
+
 # ---- the mixed-precision ("lowp") branches: WHERE the steps round to bfloat16 ---------------------------
 # The scheme (weights: fp32 master + bf16 working copy; activations and activation gradients bf16;
 # dW, db, logits, loss, cell state, gates and masters wide) is checked three ways: which arrays are

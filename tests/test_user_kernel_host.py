@@ -166,6 +166,14 @@ def test_compile_cache_memory_then_disk_then_compiler(cache):
     k4 = B.ElementwiseKernel("float32 x, float32 y, float32 z", "float32 w", "w = x * y + z", "my_mad")
     k4.prepare(x, x, x, x)
     assert B.user_kernel_stats()[0] == c0 + 4
+    # nor is a good file that somebody else could have written (group- or world-writable)
+    assert all((os.stat(os.path.join(cache, f)).st_mode & 0o022) == 0 for f in os.listdir(cache))
+    for f in os.listdir(cache):
+        os.chmod(os.path.join(cache, f), 0o666)
+    c1, d1, _ = B.user_kernel_stats()
+    k5 = B.ElementwiseKernel("float32 x, float32 y, float32 z", "float32 w", "w = x * y + z", "my_mad")
+    k5.prepare(x, x, x, x)
+    assert B.user_kernel_stats()[:2] == (c1 + 1, d1)         # compiled again, not loaded
 
 
 def test_a_snippet_that_does_not_compile_reports_the_compilers_error(cache):
