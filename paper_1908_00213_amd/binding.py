@@ -269,6 +269,14 @@ def gemm_plan(A, B, Cm, have_workspace=False):
     return code & 3, bool(code & 4), code >> 4
 
 
+def gemm_plan_eight_waves(A, B, Cm, have_workspace=False):
+    """Whether the plain product would run on the eight-wave form of the direct-copy kernel."""
+    code = lib().chn_gemm_plan(_ref(desc(A)), _ref(desc(B)), _ref(desc(Cm)), 1 if have_workspace else 0)
+    if code < 0:
+        _check(code)
+    return bool(code & 8)
+
+
 def gemm_plan_override(tile=-1, splits=-1, direct_copy=-1):
     """Test hook: force the macro tile / K splits / keep products off the direct-copy kernel (-1: planner's choice)."""
     lib().chn_gemm_plan_override(int(tile), int(splits), int(direct_copy))

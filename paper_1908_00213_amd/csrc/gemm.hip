@@ -23,6 +23,7 @@ using gemm::GemmArgs;
 
 // chn_gemm_plan_override: what tests force instead of the planner's choice (-1: not forced)
 std::atomic<int> g_force_tile{-1}, g_force_splits{-1}, g_force_direct{-1};
+std::atomic<int> g_force_w8{-1};
 
 // Largest load piece (bytes) that is aligned for every row start of the operand and divides its
 // extent along the unit-stride dimension, so that a piece is never partly out of range.
@@ -126,6 +127,19 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big
   g->dma = g->tile == 2 && direct;
 }
 
+// Which of the two direct-copy kernels takes a bf16 product on the 256x256 tile.  Measured on the wide-MLP
+// step (both are bound by the chip's power limit on random data, within 2 % of each other on the long
+// products): the eight-wave kernel wins where a workgroup's fixed parts weigh more -- short K (its two waves
+// per SIMD overlap prologue, epilogue and barriers: 8192x4096x1000 in 100 us against 120 us) and the
+// activation-gradient epilogues (-3 %); the four-wave kernel reads a third less from LDS per MFMA and wins
+// the long plain products by 1-2 %.
+bool eight_waves(const GemmArgs &g, int isz, int epilogue) {
+  if (!g.dma || isz != 2) return false;
+  const int f = g_force_w8.load(std::memory_order_relaxed);
+  if (f >= 0) return f != 0;
+  return g.K <= 2048 || epilogue == CHN_EPI_RELU_BWD || epilogue == CHN_EPI_GELU_BWD;
+}
+
 size_t split_bytes(const GemmArgs &g) {
   return g.splits > 1 ? (size_t)g.splits * g.M * g.ldp * sizeof(float) : 0;
 }
@@ -150,7 +164,8 @@ size_t chn_gemm_workspace_bytes(const chn_array *A, const chn_array *B, const ch
 void chn_gemm_plan_override(int tile, int splits, int direct_copy) {
   chn::g_force_tile.store(tile, std::memory_order_relaxed);
   chn::g_force_splits.store(splits, std::memory_order_relaxed);
-  chn::g_force_direct.store(direct_copy, std::memory_order_relaxed);
+  chn::g_force_direct.store(direct_copy >= 2 ? 1 : direct_copy, std::memory_order_relaxed);
+  chn::g_force_w8.store(direct_copy == 2 ? 0 : direct_copy == 3 ? 1 : -1, std::memory_order_relaxed);
 }
 
 int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace) {
@@ -167,7 +182,7 @@ int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, in
   CHN_TRY(classify(A, B, &g, &a_kc, &b_kc));
   const int isz = dtype_size(A->dtype);
   plan(&g, isz, a_kc, b_kc, have_workspace != 0);
-  return g.tile | (g.dma ? 4 : 0) | (g.splits << 4);
+  return g.tile | (g.dma ? 4 : 0) | (eight_waves(g, isz, CHN_EPI_NONE) ? 8 : 0) | (g.splits << 4);
 }
 
 chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, float alpha, float beta,
@@ -258,6 +273,7 @@ chn_status chn_gemm(const chn_array *A, const chn_array *B, const chn_array *C, 
     if (ws && reinterpret_cast<uintptr_t>(ws) % 256 == 0 && ws_bytes >= split_bytes(g)) g.partial = static_cast<float *>(ws);
     else plan(&g, isz, a_kc, b_kc, false);
   }
+  g.w8 = eight_waves(g, isz, epilogue);
   hipStream_t st = as_stream(stream);
   if (A->dtype == CHN_F32) {
     if (a_kc) return b_kc ? gemm::launch_f32_kk(g, st) : gemm::launch_f32_km(g, st);

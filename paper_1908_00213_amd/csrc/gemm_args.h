@@ -27,6 +27,7 @@ struct GemmArgs {
   int64_t ldp;
   int epi_vec;            // C, aux, preact and bias allow aligned 4-element vector accesses
   int dma;                // big tile: K-contiguous operands go to LDS by direct global-to-LDS loads
+  int w8;                 // ... by the kernel that works with eight waves (bf16)
   float *colsum;          // activation-gradient epilogues, 256x256 tile only: [M / 128][N] column sums of C over
                           // blocks of 128 rows (values as stored), or NULL
   int64_t ldcs;

@@ -622,7 +622,8 @@ constexpr int kEpiRows = TM == 1 ? 32 : 64;
 template <int TM, int TN>
 constexpr int kEpiStageBytes = kEpiRows<TM, TN> * StageLayout<TN>::PITCH * 4;
 
-template <int TM, int TN>
+// WAVES_N: waves side by side along N (2 for the 2 x 2 arrangement of four waves, 4 for the 2 x 4 of eight).
+template <int TM, int TN, int WAVES_N = 2>
 __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM][TN], char *stage_bytes, int m0, int n0, int split) {
   using L = StageLayout<TN>;
   constexpr int RP = kEpiRows<TM, TN>, IPP = RP / 32, NPASS = TM / IPP;   // 32-row blocks per pass, passes
@@ -630,7 +631,7 @@ __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM]
   // the value computed before the K loop alive across it, in a kernel that has no register to spare)
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
   const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int r = lane & 31, h = lane >> 5;
   float *stage = reinterpret_cast<float *>(stage_bytes);
   float *slab = g.splits > 1 ? g.partial + (int64_t)split * g.M * g.ldp : nullptr;
@@ -655,15 +656,21 @@ __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM]
     epilogue_pass<TN, RP>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab, cs);
     __builtin_amdgcn_wave_barrier();
   }
-  if constexpr (TM == 4 && TN == 4) {
-    // The lanes of one row segment own 32 column groups; lane l and lane l + 32 walked different rows
-    // of the same columns.  One row of the sums per wave tile (128 rows of C).
+  if constexpr (TM == 4 && (TN == 4 || TN == 2)) {
+    // The lanes of one row segment own 8 * TN column groups; lanes that differ by a multiple of that
+    // walked different rows of the same columns.  One row of the sums per wave tile (128 rows of C).
     if (g.colsum) {
+      constexpr int CPR = 8 * TN;
       f32x4 v;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = cs[e] + __shfl_xor(cs[e], 32, 64);
-      if (lane < 32)
-        global_store<f32x4>(reinterpret_cast<uintptr_t>(g.colsum + (int64_t)((m0 >> 7) + wm) * g.ldcs + n0 + wn * 128 + lane * 4), v);
+      for (int e = 0; e < 4; ++e) {
+        float t = cs[e];
+#pragma unroll
+        for (int o = 32; o >= CPR; o >>= 1) t += __shfl_xor(t, o, 64);
+        v[e] = t;
+      }
+      if (lane < CPR)
+        global_store<f32x4>(reinterpret_cast<uintptr_t>(g.colsum + (int64_t)((m0 >> 7) + wm) * g.ldcs + n0 + wn * (32 * TN) + lane * 4), v);
     }
   }
 }
@@ -825,11 +832,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 // the copy may be in flight for a whole tile step.  One such instruction writes the 64 lanes' chunks
 // to 1024 consecutive LDS bytes (8 tile rows), so the swizzle is applied on the global side: the
 // lane that fills physical slot (row p, chunk c) fetches the logical chunk that lives there.
-template <typename T, int ROWS, bool RAGGED>
+template <typename T, int ROWS, bool RAGGED, int NW = 4>
 struct DmaLoader {
   static constexpr int EPC = Traits<T>::EPC;
   static constexpr int BK = 128 / (int)sizeof(T);
-  static constexpr int NS = ROWS / 32;     // instructions per wave and tile
+  static constexpr int NS = ROWS / (8 * NW);   // instructions per wave and tile (NW waves share the tile)
   const char *tile;                        // wave-uniform: first row of the tile, k = 0
   uint32_t off[NS];                        // byte offset of the slot's chunk from `tile`
   int lim[RAGGED ? NS : 1];                // RAGGED: K - (k offset of the slot's chunk)
@@ -846,7 +853,7 @@ struct DmaLoader {
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      const int slot = (i * 4 + wave) * 64 + lane;
+      const int slot = (i * NW + wave) * 64 + lane;
       const int prow = slot >> 3, pchunk = slot & 7;
       const int row = lds_row<T>(prow);                 // the row swap is its own inverse
       const int kc = (pchunk ^ ((row >> 1) & 7)) * EPC;
@@ -867,7 +874,7 @@ struct DmaLoader {
       const char *a = p + off[i];
       if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
-                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
+                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * NW + wave) * 1024),
                                        16, 0, 0);
     }
   }
@@ -877,10 +884,10 @@ struct DmaLoader {
 // memory, BK rows of k, each ROWS elements (512 bytes) of m, and is transposed on the way out of LDS
 // by the 16-bit transposing read (see TrReader).  The eight 64-byte blocks of a k-row are XORed with
 // k % 8, so that the four k-rows one group of lanes reads together sit in different banks.
-template <int ROWS, bool RAGGED>
+template <int ROWS, bool RAGGED, int NW = 4>
 struct DmaLoaderMC {
   static_assert(ROWS == 256, "one k-row must be 512 bytes");
-  static constexpr int BK = 64, NS = BK * 512 / 1024 / 4;   // instructions per wave and tile
+  static constexpr int BK = 64, NS = BK * 512 / 1024 / NW;   // instructions per wave and tile
   const char *tile;                        // wave-uniform: element (k = 0, m = row0)
   uint32_t off[NS];
   int lim[RAGGED ? NS : 1];                // RAGGED: K - (k-row of the slot)
@@ -897,7 +904,7 @@ struct DmaLoaderMC {
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      const int slot = (i * 4 + wave) * 64 + lane;
+      const int slot = (i * NW + wave) * 64 + lane;
       const int k = slot >> 5, p = slot & 31;                  // k-row, 16-byte slot inside it
       const int m = (((p >> 2) ^ (k & 7)) * 32) + (p & 3) * 8; // the 8 elements that live in that slot
       const int mc = min(m, rows_total - 8 - row0);
@@ -915,7 +922,7 @@ struct DmaLoaderMC {
       const char *a = p + off[i];
       if constexpr (RAGGED) a = k0 < lim[i] ? a : zero;   // k-rows at or past K read as zeros
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)a,
-                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * 4 + wave) * 1024),
+                                       (__attribute__((address_space(3))) void *)(lds_operand + (i * NW + wave) * 1024),
                                        16, 0, 0);
     }
   }
@@ -1149,6 +1156,151 @@ __global__ __launch_bounds__(256) void gemm_kernel_dma(GemmArgs g) {
   write_out<TM, TN>(g, acc, (wave < 2 ? stage0 : stage1) + (wave & 1) * kEpiStageBytes<TM, TN>, m0, n0, split);
 }
 
+// ---- 256 x 256 tile, eight waves ----------------------------------------------------------------------
+// The loaders of the four-wave kernel with their instructions in two parts (first and second half), so that
+// a tile's copies can be dealt out over several k-steps.
+template <typename L>
+struct TwoParts : L {
+  template <int P>
+  __device__ __forceinline__ void issue_part(int k0, char *lds_operand) const {
+    this->template issue<P * (L::NS / 2), L::NS / 2>(k0, lds_operand);
+  }
+};
+
+// bfloat16 only.  The tile of the direct-copy kernel above with the work dealt out to eight waves, two on
+// every SIMD, in a 2 (M) x 4 (N) arrangement: a wave owns 128 x 64 of C (4 x 2 MFMA blocks, 128 accumulator
+// registers), so that two waves fit the register file of a SIMD.  Whatever one wave waits for -- fragment
+// reads, the barrier of a tile step, a copy instruction that the memory pipeline does not take yet, the
+// staging and stores of its epilogue -- the other wave's MFMAs fill.
+// Operand traffic from L2 is that of the four-wave kernel (the tile is the same), LDS fragment traffic is
+// 1.5 times higher (6 fragment reads per 8 MFMAs instead of 8 per 16).
+template <bool A_KC, bool B_KC, bool RAGGED>
+__global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
+  using T = bf16_raw;
+  constexpr int TM = 4, TN = 2, BM = 256, BN = 256, NW = 8;
+  constexpr int BK = 64;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  __shared__ __align__(1024) char stage0[STAGE];
+  __shared__ __align__(1024) char stage1[STAGE];
+
+  const TilePos tp = tile_pos(g);
+  const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
+
+  TwoParts<std::conditional_t<A_KC, DmaLoader<T, BM, RAGGED, NW>, DmaLoaderMC<BM, RAGGED, NW>>> la;
+  TwoParts<std::conditional_t<B_KC, DmaLoader<T, BN, RAGGED, NW>, DmaLoaderMC<BN, RAGGED, NW>>> lb;
+  la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
+  lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
+
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  std::conditional_t<A_KC, KcReader<T>, TrReader> ra;
+  std::conditional_t<B_KC, KcReader<T>, TrReader> rb;
+  ra.init(wm * TM, lane, 0);
+  rb.init(wn * TN, lane, A_BYTES);
+  auto read_frags = [&](Frags<TM, TN> &f, const char *stage, int ks) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = ra.read(stage, ks, i);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = rb.read(stage, ks, j);
+  };
+
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int per_split = (nk_all + g.splits - 1) / g.splits;
+  const int kt0 = split * per_split;
+  const int nk = min(nk_all, kt0 + per_split);
+  auto k_of = [&](int kt) { return kt * BK; };
+
+  // prologue: first tile into stage 0; of the second tile the part that a step issues after its barrier
+  la.template issue_part<0>(k_of(kt0), stage0);
+  la.template issue_part<1>(k_of(kt0), stage0);
+  lb.template issue_part<0>(k_of(kt0), stage0 + A_BYTES);
+  lb.template issue_part<1>(k_of(kt0), stage0 + A_BYTES);
+  la.template issue_part<0>(k_of(kt0 + 1), stage1);
+  __builtin_amdgcn_sched_barrier(0);
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+  __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+  __syncthreads();
+  Frags<TM, TN> f0, f1;
+  read_frags(f0, stage0, 0);
+
+  // interleaving hint for one k-step: per fragment its LDS reads, then (for the first NV fragments) one copy
+  // instruction, then its share of the 8 MFMAs (2, 2, 1, 1, 1, 1)
+  constexpr int RPG_A = A_KC ? 1 : 2, RPG_B = B_KC ? 1 : 2;   // LDS reads per fragment
+#define CHN_W8_GROUP(S, RPG, NMF, NV)                                           \
+  __builtin_amdgcn_sched_group_barrier(SG_DS_READ, RPG, 0);                     \
+  if constexpr ((NV) > (S)) __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0); \
+  __builtin_amdgcn_sched_group_barrier(SG_MFMA, NMF, 0);
+#define CHN_W8_KSTEP(NV)                                                        \
+  CHN_W8_GROUP(0, RPG_A, 2, NV) CHN_W8_GROUP(1, RPG_A, 2, NV) CHN_W8_GROUP(2, RPG_A, 1, NV) \
+  CHN_W8_GROUP(3, RPG_A, 1, NV) CHN_W8_GROUP(4, RPG_B, 1, NV) CHN_W8_GROUP(5, RPG_B, 1, NV)
+
+  // One tile step: k-steps 0..2 out of `cur` (the fragments of the following k-step are read while a
+  // k-step multiplies); barrier -- the copy of the next tile has landed in `nxt`, and nobody reads `cur` any
+  // more; k-step 3 multiplies out of registers while the first fragments of `nxt` are read.  The copies of
+  // a tile are spread: A's first part right after the barrier that frees their stage (k-step 3), A's second
+  // and B's first part in k-step 0 of the next step, B's second part in its k-step 1; they then have two
+  // k-steps left to land, several times what a trip to L2 takes.
+  auto step = [&](char *cur, char *nxt, int kt) __attribute__((always_inline)) {
+    read_frags(f1, cur, 1);
+    la.template issue_part<1>(k_of(kt + 1), nxt);
+    lb.template issue_part<0>(k_of(kt + 1), nxt + A_BYTES);
+    mma<T, TM, TN>(acc, f0);
+    CHN_W8_KSTEP(4)
+    read_frags(f0, cur, 2);
+    lb.template issue_part<1>(k_of(kt + 1), nxt + A_BYTES);
+    mma<T, TM, TN>(acc, f1);
+    CHN_W8_KSTEP(2)
+    read_frags(f1, cur, 3);
+    mma<T, TM, TN>(acc, f0);
+    CHN_W8_KSTEP(0)
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    la.template issue_part<0>(k_of(kt + 2), cur);
+    read_frags(f0, nxt, 0);
+    mma<T, TM, TN>(acc, f1);
+    CHN_W8_KSTEP(2)
+    __builtin_amdgcn_sched_barrier(0);
+  };
+#undef CHN_W8_KSTEP
+#undef CHN_W8_GROUP
+
+  int kt = kt0;
+  for (; kt + 1 < nk; kt += 2) {
+    step(stage0, stage1, kt);
+    step(stage1, stage0, kt + 1);
+  }
+  if (kt < nk) step(stage0, stage1, kt);
+
+  // The (unused) copies that the last steps started must be over: the epilogue reuses both stages.
+  __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+  __syncthreads();
+  static_assert(4 * kEpiStageBytes<TM, TN> <= STAGE, "four waves stage their accumulators in each operand stage");
+  write_out<TM, TN, 4>(g, acc, (wave < 4 ? stage0 : stage1) + (wave & 3) * kEpiStageBytes<TM, TN>, m0, n0, split);
+}
+
+template <bool A_KC, bool B_KC>
+chn_status launch_w8(const GemmArgs &g, hipStream_t st) {
+  const dim3 grid((unsigned)(g.tiles_m * g.tiles_n * g.splits));
+  if (g.K % 64 == 0) hipLaunchKernelGGL((gemm_kernel_w8<A_KC, B_KC, false>), grid, dim3(512), 0, st, g);
+  else hipLaunchKernelGGL((gemm_kernel_w8<A_KC, B_KC, true>), grid, dim3(512), 0, st, g);
+  CHN_TRY(check_launch("gemm (eight waves)"));
+  if (g.splits > 1) {
+    const int64_t n = (int64_t)g.M * (g.ldp / 4);
+    hipLaunchKernelGGL(gemm_splitk_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, g);
+    return check_launch("gemm split-K finish");
+  }
+  return CHN_OK;
+}
+
 template <typename T, bool A_KC, bool B_KC>
 constexpr bool kHasDmaKernel = A_KC || B_KC || sizeof(T) == 2;
 
@@ -1204,6 +1356,9 @@ chn_status launch_tile(const GemmArgs &g, hipStream_t st) {
 template <typename T, bool A_KC, bool B_KC>
 chn_status launch_layout(GemmArgs &g, hipStream_t st) {
   if ((int64_t)g.tiles_m * g.tiles_n * g.splits > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
+  if constexpr (sizeof(T) == 2) {
+    if (g.tile == 2 && g.piece == 16 && g.dma && g.w8) return launch_w8<A_KC, B_KC>(g, st);
+  }
   if constexpr (kHasDmaKernel<T, A_KC, B_KC>) {
     if (g.tile == 2 && g.piece == 16 && g.dma) return launch_dma<T, A_KC, B_KC>(g, st);
   }

@@ -345,6 +345,15 @@ def _tie_to_oracle(A, Bm, ref):
     assert np.array_equal(got, ref[ms, ns])
 
 
+@pytest.fixture(params=["planned", "four waves", "eight waves"])
+def direct_kernel(request):
+    """The headline products run on the 256x256 direct-copy path, which has two kernels; the planner picks
+    one per call.  Every whole-output test runs as planned and with each kernel forced."""
+    B.gemm_plan_override(direct_copy={"planned": -1, "four waves": 2, "eight waves": 3}[request.param])
+    yield request.param
+    B.gemm_plan_override()
+
+
 # the three layouts of a hidden layer of workload 5 (forward x W^T, input gradient dY W, weight gradient dY^T X)
 # and of its 1000-class output layer
 HEADLINE_PRODUCTS = [
@@ -358,7 +367,7 @@ HEADLINE_PRODUCTS = [
 
 
 @pytest.mark.parametrize("name,M,N,K,a_t,b_t", HEADLINE_PRODUCTS)
-def test_headline_products_whole_output_bit_exact(name, M, N, K, a_t, b_t):
+def test_headline_products_whole_output_bit_exact(name, M, N, K, a_t, b_t, direct_kernel):
     A, Ad = _int_operand((M, K), a_t)
     Bm, Bd = _int_operand((K, N), b_t)
     ref = A.astype(np.float64) @ Bm.astype(np.float64)
@@ -372,7 +381,7 @@ def test_headline_products_whole_output_bit_exact(name, M, N, K, a_t, b_t):
     assert bad.size == 0, "%s: %d entries differ, first at %s (tile %s)" % (name, len(bad), bad[0], bad[0] // 256)
 
 
-def test_headline_forward_epilogue_whole_output():
+def test_headline_forward_epilogue_whole_output(direct_kernel):
     """The benchmarked forward launch itself: bias + GELU, bf16 output and bf16 pre-activation.  With integer
     operands and an integer bias v = acc + bias is exact, so the stored pre-activation must be the
     nearest-even bf16 of the exact value everywhere; the activation is compared within the bf16 bar."""
@@ -400,7 +409,7 @@ def test_headline_forward_epilogue_whole_output():
     check(got, full, TOL_BF16, np.abs(v), "gelu everywhere")
 
 
-def test_headline_input_gradient_epilogue_and_row_block_sums_whole_output():
+def test_headline_input_gradient_epilogue_and_row_block_sums_whole_output(direct_kernel):
     """dx of a hidden layer as benchmarked: the activation-gradient epilogue with the per-128-row column sums.
     With the ReLU gradient and integer data everything is exact: C = RNE_bf16(acc * [aux > 0]) and the row-block
     sums are sums of those stored integers (below 2^24), so both outputs are compared bit for bit; the GELU
@@ -429,7 +438,7 @@ def test_headline_input_gradient_epilogue_and_row_block_sums_whole_output():
     check(sums.cpu().numpy().astype(np.float64), blk.sum(axis=1), TOL_SUM, np.abs(blk).sum(axis=1), "row-block sums")
 
 
-def test_headline_weight_gradient_with_fused_update_whole_output():
+def test_headline_weight_gradient_with_fused_update_whole_output(direct_kernel):
     """dW of a hidden layer as benchmarked: alpha = -lr, beta = 1 on the fp32 master weights, bf16 copy written in
     the same pass.  lr = 2^-7 and masters on a 2^-4 grid keep v = W - lr * dW exact in fp32, so the masters are
     compared bit for bit and the working copy is the nearest-even bf16 of them."""

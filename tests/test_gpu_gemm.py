@@ -70,6 +70,15 @@ def test_gemm_big_tiles_exact_integers(dt, layout, shape):
     assert np.array_equal(out, ref)
 
 
+@pytest.fixture(params=["four waves", "eight waves"])
+def direct_kernel(request):
+    """Runs a test of the 256x256 direct-copy path once per kernel that can take a bf16 product there
+    (fp32 products have the four-wave kernel only: the other parameter value then changes nothing)."""
+    B.gemm_plan_override(direct_copy=2 if request.param == "four waves" else 3)
+    yield request.param
+    B.gemm_plan_override()
+
+
 # The planner takes the 256x256 tile only when K is long enough to pay for its fixed cost; the short-K
 # cases (one, two, three tile steps: where a pipeline's prologue and tail go wrong) force the tile
 # through the library's test hook chn_gemm_plan_override.
@@ -97,14 +106,19 @@ def direct_copy_case(dt, layout, shape):
 
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
 @pytest.mark.parametrize("dt,shape", DIRECT_COPY_CASES)
-def test_gemm_big_tiles_direct_copy(dt, layout, shape):
+def test_gemm_big_tiles_direct_copy(dt, layout, shape, direct_kernel):
+    if dt == "f32" and direct_kernel == "eight waves":
+        pytest.skip("fp32 products have the four-wave kernel only")
     direct_copy_case(dt, layout, shape)
 
 
-def test_gemm_big_tiles_direct_copy_short_k_forced_tile():
-    B.gemm_plan_override(tile=2)
+@pytest.mark.parametrize("waves", [2, 3])
+def test_gemm_big_tiles_direct_copy_short_k_forced_tile(waves):
+    B.gemm_plan_override(tile=2, direct_copy=waves)
     try:
         for dt, shape in DIRECT_COPY_SHORT_K:
+            if dt == "f32" and waves == 3:
+                continue
             for layout in ("nt", "nn", "tn"):
                 print(dt, layout, shape, flush=True)
                 direct_copy_case(dt, layout, shape)
@@ -112,7 +126,7 @@ def test_gemm_big_tiles_direct_copy_short_k_forced_tile():
         B.gemm_plan_override()
 
 
-def test_gemm_direct_copy_odd_k_both_transposed():
+def test_gemm_direct_copy_odd_k_both_transposed(direct_kernel):
     # with both operands stored along M / N, K itself needs no alignment for the direct-copy kernel
     M, N, K = 3720, 3592, 1003
     gen = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
@@ -120,6 +134,28 @@ def test_gemm_direct_copy_odd_k_both_transposed():
     assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, True)
     out = host(B.gemm(Ad, Bd, empty((M, N))))
     assert np.array_equal(out, A.astype(np.float64) @ Bm.astype(np.float64))
+
+
+def test_gemm_plan_reports_the_direct_copy_kernel():
+    M, N = 1024, 768
+    for K, want in ((512, True), (2048, True), (4096, False)):       # short products go to the eight-wave kernel
+        _, _, Ad, Bd = operands(M, N, K, "nt", "bf16")
+        B.gemm_plan_override(tile=2)
+        try:
+            assert B.gemm_plan(Ad, Bd, empty((M, N)))[:2] == (2, True)
+            assert B.gemm_plan_eight_waves(Ad, Bd, empty((M, N))) == want
+            B.gemm_plan_override(tile=2, direct_copy=2)
+            assert not B.gemm_plan_eight_waves(Ad, Bd, empty((M, N)))
+            B.gemm_plan_override(tile=2, direct_copy=3)
+            assert B.gemm_plan_eight_waves(Ad, Bd, empty((M, N)))
+        finally:
+            B.gemm_plan_override()
+    _, _, Ad, Bd = operands(M, N, 512, "nt", "f32")
+    B.gemm_plan_override(tile=2, direct_copy=3)
+    try:
+        assert not B.gemm_plan_eight_waves(Ad, Bd, empty((M, N)))    # fp32: four waves only
+    finally:
+        B.gemm_plan_override()
 
 
 def test_gemm_identity_and_ones():
@@ -214,11 +250,13 @@ def test_gemm_split_k(dt, layout, shape):
 
 @pytest.mark.parametrize("dt,cdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
-def test_gemm_direct_copy_epilogues(dt, cdt, layout):
+def test_gemm_direct_copy_epilogues(dt, cdt, layout, direct_kernel):
     # every epilogue, beta and both C dtypes on the 256x256 direct-copy kernel: an interior of full tiles
     # (vector path), a ragged last tile in M (rows past the end) and in N (element-wise path)
     if dt == "f32" and layout == "tn":
         pytest.skip("fp32 with both operands stored along M/N takes the register-staged kernel")
+    if dt == "f32" and direct_kernel == "eight waves":
+        pytest.skip("fp32 products have the four-wave kernel only")
     M, N, K = 3720, 3592, 1000      # (long enough for the planner to take the 256x256 tile)
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
     assert B.gemm_plan(Ad, Bd, empty((M, N), cdt))[:2] == (2, True)
@@ -259,11 +297,13 @@ def test_gemm_direct_copy_epilogues(dt, cdt, layout):
 
 @pytest.mark.parametrize("dt,cdt", [("bf16", "bf16"), ("bf16", "f32"), ("f32", "f32")])
 @pytest.mark.parametrize("layout,shape", [("nn", (512, 768, 200)), ("nt", (768, 256, 1000)), ("tn", (256, 512, 72))])
-def test_gemm_activation_gradient_with_row_block_column_sums(dt, cdt, layout, shape):
+def test_gemm_activation_gradient_with_row_block_column_sums(dt, cdt, layout, shape, direct_kernel):
     """The activation-gradient epilogues can leave, beside C, the column sums of C over blocks of 128
     rows (the bias gradient of the layer below is their column sum).  C is checked against the oracle
     as without the sums; the sums against the stored C, to fp32 summation accuracy, which pins them to
     the values as stored (rounded to bf16 where C is bf16)."""
+    if dt == "f32" and direct_kernel == "eight waves":
+        pytest.skip("fp32 products have the four-wave kernel only")
     M, N, K = shape
     A, Bm, Ad, Bd = operands(M, N, K, layout, dt)
     tol = TOL_BF16 if cdt == "bf16" else TOL_SUM
@@ -296,7 +336,7 @@ def test_gemm_activation_gradient_with_row_block_column_sums(dt, cdt, layout, sh
 
 
 @pytest.mark.parametrize("layout", ["nt", "tn"])
-def test_gemm_direct_copy_split_k(layout):
+def test_gemm_direct_copy_split_k(layout, direct_kernel):
     # few tiles and a long K: the direct-copy kernel writes fp32 slabs, the finishing kernel adds them
     M, N, K = 1000, 4096, 8192
     gen = lambda s, d: RNG.integers(-2, 3, size=s).astype(np.float32)
@@ -331,7 +371,7 @@ def test_gemm_degenerate_sizes():
 
 
 @pytest.mark.parametrize("shape,layout", [((150, 200, 90), "tn"), ((3720, 3592, 192), "tn"), ((1000, 4096, 8192), "tn"), ((257, 130, 100), "nt")])
-def test_gemm_bf16_copy_epilogue_is_an_sgd_update(shape, layout):
+def test_gemm_bf16_copy_epilogue_is_an_sgd_update(shape, layout, direct_kernel):
     # C (fp32 master weights) <- C - lr * A B, preact_out <- bf16(C): small tile, direct-copy kernel,
     # split-K finishing kernel, element-wise path (N not a multiple of 4)
     M, N, K = shape
