@@ -161,7 +161,10 @@ chn_status chn_reduce_axis_static(int op, const chn_array *in, int axis, int kee
  *              Motivation"'s training loop together with the refresh of the bf16 working copy, and
  *              the gradient never travels through memory
  * Unused optional arguments are NULL.  beta != 0 reads C before writing it.
- * gelu / gelu' in the epilogue use a five-term rational erf (absolute error below 1.5e-7 in Phi).
+ * gelu / gelu' in the epilogue use a five-term rational erf (absolute error below 1.5e-7 in Phi) when C
+ * is F32; when C is BF16 they are odd polynomials of the clamped argument (absolute error below 7e-5 in
+ * Phi and 1.6e-4 in gelu': under the rounding of the bfloat16 result except in the negative tail, where
+ * it is an absolute 2e-4 |x| on values smaller than 0.1).
  * Workspace: optional.  chn_gemm_workspace_bytes returns what a product with few output tiles and a
  * long K would use to be cut along K (fp32 partial sums per cut, added in a fixed order by a second
  * kernel: bit-reproducible); `ws` is device memory, 256-byte aligned, owned by the caller and free
@@ -407,8 +410,8 @@ int chn_version(void);
 int chn_elementwise_plan(int op, int n_in, const chn_array *const *in, const chn_array *out);
 /* The same for chn_gemm: bits 0-1 macro tile (0: 64x64, 1: 128x128, 2: 256x256), bit 2 set when a
  * 256x256 kernel that copies operand tiles straight from global memory into LDS is taken, bit 3 when that
- * is the kernel that works on the tile with eight waves (as planned for the plain epilogue: chn_gemm also
- * takes it for the activation-gradient epilogues), bits 4 and up the number of K splits (1 = none;
+ * is the kernel that works on the tile with eight waves (bfloat16 products), bits 4 and up the number of
+ * K splits (1 = none;
  * have_workspace = 0 plans as chn_gemm does without workspace). */
 int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace);
 /* Test hook: replace the planner's choice for every later chn_gemm / chn_gemm_plan of the process.

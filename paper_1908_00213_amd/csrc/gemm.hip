@@ -127,17 +127,18 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big
   g->dma = g->tile == 2 && direct;
 }
 
-// Which of the two direct-copy kernels takes a bf16 product on the 256x256 tile.  Measured on the wide-MLP
-// step (both are bound by the chip's power limit on random data, within 2 % of each other on the long
-// products): the eight-wave kernel wins where a workgroup's fixed parts weigh more -- short K (its two waves
-// per SIMD overlap prologue, epilogue and barriers: 8192x4096x1000 in 100 us against 120 us) and the
-// activation-gradient epilogues (-3 %); the four-wave kernel reads a third less from LDS per MFMA and wins
-// the long plain products by 1-2 %.
+// Which of the two direct-copy kernels takes a bf16 product on the 256x256 tile: the eight-wave one.  Both
+// are bound by the chip's power limit on random data and within 2 % of each other on the long products of
+// the wide-MLP step (three machines: the eight-wave kernel ahead by 1-2 % on two, behind by 1.5 % on one);
+// where a workgroup's fixed parts weigh more the eight-wave kernel wins clearly -- its two waves per SIMD
+// overlap prologue, epilogue and barriers: 8192x4096x1000 in 95-100 us against 118-120 us, the products
+// with an activation-gradient epilogue 3-5 % faster.  The four-wave kernel (a third less LDS traffic per
+// MFMA) stays for fp32 and as the forced alternative of the tests.
 bool eight_waves(const GemmArgs &g, int isz, int epilogue) {
   if (!g.dma || isz != 2) return false;
   const int f = g_force_w8.load(std::memory_order_relaxed);
-  if (f >= 0) return f != 0;
-  return g.K <= 2048 || epilogue == CHN_EPI_RELU_BWD || epilogue == CHN_EPI_GELU_BWD;
+  (void)epilogue;
+  return f < 0 || f != 0;
 }
 
 size_t split_bytes(const GemmArgs &g) {

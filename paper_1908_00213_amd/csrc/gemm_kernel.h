@@ -325,9 +325,9 @@ __device__ __forceinline__ float epi_math(const GemmArgs &g, float acc, float c0
   x += bias;
   *pre = x;
   if (g.epi == CHN_EPI_BIAS_RELU) x = fmaxf(x, 0.0f);
-  else if (g.epi == CHN_EPI_BIAS_GELU) x = gelu_epi_f(x);
+  else if (g.epi == CHN_EPI_BIAS_GELU) x = g.c_bf16 ? gelu_epi_bf16_f(x) : gelu_epi_f(x);
   else if (g.epi == CHN_EPI_RELU_BWD) x = aux > 0.0f ? x : 0.0f;
-  else if (g.epi == CHN_EPI_GELU_BWD) x *= gelu_grad_epi_f(aux);
+  else if (g.epi == CHN_EPI_GELU_BWD) x *= g.c_bf16 ? gelu_grad_epi_bf16_f(aux) : gelu_grad_epi_f(aux);
   return x;
 }
 
@@ -411,9 +411,9 @@ __device__ __forceinline__ void finish4_t(const GemmArgs &g, int row, int col, c
     t += b.v[e];
     pre.v[e] = t;
     if constexpr (EPI == CHN_EPI_BIAS_RELU) t = fmaxf(t, 0.0f);
-    else if constexpr (EPI == CHN_EPI_BIAS_GELU) t = gelu_epi_f(t);
+    else if constexpr (EPI == CHN_EPI_BIAS_GELU) t = CB ? gelu_epi_bf16_f(t) : gelu_epi_f(t);
     else if constexpr (EPI == CHN_EPI_RELU_BWD) t = in.aux.v[e] > 0.0f ? t : 0.0f;
-    else if constexpr (EPI == CHN_EPI_GELU_BWD) t *= gelu_grad_epi_f(in.aux.v[e]);
+    else if constexpr (EPI == CHN_EPI_GELU_BWD) t *= CB ? gelu_grad_epi_bf16_f(in.aux.v[e]) : gelu_grad_epi_f(in.aux.v[e]);
     x.v[e] = t;
   }
   if constexpr (EPI == CHN_EPI_BIAS_GELU) {
@@ -446,11 +446,12 @@ struct StageLayout {
 // four consecutive columns; the LDS reads and the dependent global reads (old C, aux) of U row
 // segments are in flight together.
 // CS: the lane also adds what it stores to cs[0..3], the running sums of its four columns.
-template <int EPI, bool CB, bool BETA, int TN, int RP, bool CS = false>
+// UMAX bounds the row segments in flight per lane (the eight-wave kernel has half the registers per wave).
+template <int EPI, bool CB, bool BETA, int TN, int RP, bool CS = false, int UMAX = 4>
 __device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *cs = nullptr) {
   using L = StageLayout<TN>;
   constexpr int CPR = L::W / 4, RPI = 64 / CPR;            // 16-byte chunks per row, rows per wave-wide access
-  constexpr int NIT = RP / RPI, U = NIT >= 8 ? 4 : NIT / 2;
+  constexpr int NIT = RP / RPI, U0 = NIT >= 8 ? 4 : NIT / 2, U = U0 < UMAX ? U0 : UMAX;
   constexpr bool kAux = EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD;
   // a lane keeps its four columns for the whole pass and walks down the rows
   const int cl = (lane % CPR) * 4, col = col0 + cl, rl0 = lane / CPR;
@@ -505,7 +506,7 @@ __device__ __forceinline__ void epilogue_pass_vec(const GemmArgs &g, const float
 
 // One pass of a wave's epilogue: RP rows x W columns of staged accumulators.  With K splits the raw
 // sums go to this split's slab of the workspace instead.
-template <int TN, int RP>
+template <int TN, int RP, int UMAX = 4>
 __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *stage, int row0, int col0, int lane, float *slab, float *cs) {
   using L = StageLayout<TN>;
   constexpr int W = L::W, CPR = W / 4;
@@ -523,17 +524,17 @@ __device__ __forceinline__ void epilogue_pass(const GemmArgs &g, const float *st
       constexpr bool kF32Only = EPI == CHN_EPI_BF16_COPY;   // (the host refuses a bf16 C for it)
       if constexpr (EPI == CHN_EPI_RELU_BWD || EPI == CHN_EPI_GELU_BWD) {
         if (g.colsum) {                                     // (the host asks for column sums with beta = 0 only)
-          if (g.c_bf16) epilogue_pass_vec<EPI, true, false, TN, RP, true>(g, stage, row0, col0, lane, cs);
-          else epilogue_pass_vec<EPI, false, false, TN, RP, true>(g, stage, row0, col0, lane, cs);
+          if (g.c_bf16) epilogue_pass_vec<EPI, true, false, TN, RP, true, UMAX>(g, stage, row0, col0, lane, cs);
+          else epilogue_pass_vec<EPI, false, false, TN, RP, true, UMAX>(g, stage, row0, col0, lane, cs);
           return;
         }
       }
       if (g.beta != 0.0f) {
-        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, true, TN, RP>(g, stage, row0, col0, lane);
-        else epilogue_pass_vec<EPI, false, true, TN, RP>(g, stage, row0, col0, lane);
+        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, true, TN, RP, false, UMAX>(g, stage, row0, col0, lane);
+        else epilogue_pass_vec<EPI, false, true, TN, RP, false, UMAX>(g, stage, row0, col0, lane);
       } else {
-        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, false, TN, RP>(g, stage, row0, col0, lane);
-        else epilogue_pass_vec<EPI, false, false, TN, RP>(g, stage, row0, col0, lane);
+        if (!kF32Only && g.c_bf16) epilogue_pass_vec<EPI, !kF32Only, false, TN, RP, false, UMAX>(g, stage, row0, col0, lane);
+        else epilogue_pass_vec<EPI, false, false, TN, RP, false, UMAX>(g, stage, row0, col0, lane);
       }
     };
     switch (g.epi) {
@@ -653,7 +654,7 @@ __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM]
     if (p == 0) put(std::integral_constant<int, 0>{});
     else put(std::integral_constant<int, NPASS - 1>{});
     __builtin_amdgcn_wave_barrier();
-    epilogue_pass<TN, RP>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab, cs);
+    epilogue_pass<TN, RP, WAVES_N == 4 ? 2 : 4>(g, stage, m0 + (wm * TM) * 32 + p * RP, n0 + wn * TN * 32, lane, slab, cs);
     __builtin_amdgcn_wave_barrier();
   }
   if constexpr (TM == 4 && (TN == 4 || TN == 2)) {

@@ -138,7 +138,7 @@ def test_gemm_direct_copy_odd_k_both_transposed(direct_kernel):
 
 def test_gemm_plan_reports_the_direct_copy_kernel():
     M, N = 1024, 768
-    for K, want in ((512, True), (2048, True), (4096, False)):       # short products go to the eight-wave kernel
+    for K, want in ((512, True), (2048, True), (4096, True)):        # bf16 products on the direct-copy path: eight waves
         _, _, Ad, Bd = operands(M, N, K, "nt", "bf16")
         B.gemm_plan_override(tile=2)
         try:
