@@ -279,29 +279,70 @@ def bench_tape(torch, W, timer, quick):
     return res
 
 
-def traffic_driver(torch, B, W):
-    """What `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` are pointed at: three rounds of a 256 MiB
-    fp32 copy through chn_elementwise_broadcast (the calibration launch: reads and writes exactly
-    268435456 bytes), a 256 MiB scratch add that flushes the caches, and the dominant launch of the
-    headline workload: one hidden layer's forward product x @ W.T + b with the GELU epilogue that also
-    writes the pre-activation (M=8192, N=4096, K=4096, bf16 in / bf16 out)."""
-    w = W.config5(n_batches=1)
-    bf = torch.bfloat16
-    x = B.cast(torch.from_numpy(w.xs[0]).cuda(), bf)
-    Wm = B.cast(torch.from_numpy(w.params[0][0]).cuda(), bf)
-    bias = torch.from_numpy(w.params[0][1]).cuda()
-    out = torch.empty((w.batch, Wm.shape[0]), device="cuda", dtype=bf)
-    pre = torch.empty_like(out)
+def traffic_driver(torch, B, W, what):
+    """What `rocprofv3 --pmc ...` is pointed at (counters in runs of their own).  Every variant alternates,
+    three times, a 256 MiB fp32 copy through chn_elementwise_broadcast (the calibration launch: reads and
+    writes exactly 268435456 bytes) with the launches under study, a 256 MiB scratch add after each to flush
+    the caches.
+    gemm:  the dominant launch of the headline workload, one hidden layer's forward product x @ W.T + b with
+           the GELU epilogue that also writes the pre-activation (M=8192, N=4096, K=4096, bf16 in / bf16 out).
+    array: every kernel of the array microbenchmark once (8192 x 8192, fp32 then bf16): multiply-add-ReLU
+           with a row operand, the same with a transposed first operand, sums over axis 0 and axis 1."""
     src = torch.zeros(64 * 1024 * 1024, device="cuda", dtype=torch.float32)
     dst = torch.empty_like(src)
     scratch = torch.zeros(64 * 1024 * 1024, device="cuda", dtype=torch.float32)
+    if what == "gemm":
+        w = W.config5(n_batches=1)
+        bf = torch.bfloat16
+        x = B.cast(torch.from_numpy(w.xs[0]).cuda(), bf)
+        Wm = B.cast(torch.from_numpy(w.params[0][0]).cuda(), bf)
+        bias = torch.from_numpy(w.params[0][1]).cuda()
+        out = torch.empty((w.batch, Wm.shape[0]), device="cuda", dtype=bf)
+        pre = torch.empty_like(out)
+        launches = [lambda: B.gemm(x, Wm.t(), out, epilogue="bias_gelu", bias=bias, preact_out=pre)]
+    else:
+        n = 8192
+        w = W.config2(n)
+        launches = []
+        for tdt in (torch.float32, torch.bfloat16):
+            a, b, c = (B.cast(torch.from_numpy(t).cuda(), tdt) for t in (w.a, w.b, w.c))
+            y = torch.empty(n, n, dtype=tdt, device="cuda")
+            o = torch.empty(n, dtype=torch.float32, device="cuda")
+            ws = torch.empty(max(256, B.reduce_axis_workspace_bytes(y, 0)), dtype=torch.uint8, device="cuda")
+            launches += [lambda a=a, b=b, c=c, y=y: B.elementwise_broadcast("mad_relu", [a, b, c], y),
+                         lambda a=a, b=b, c=c, y=y: B.elementwise_broadcast("mad_relu", [a.t(), b, c], y),
+                         lambda y=y, o=o, ws=ws: B.reduce_axis("sum", y, 0, o, ws=ws),
+                         lambda y=y, o=o, ws=ws: B.reduce_axis("sum", y, 1, o, ws=ws)]
     for _ in range(3):
         B.elementwise_broadcast("copy", [src], dst)
         scratch.add_(1.0)
-        B.gemm(x, Wm.t(), out, epilogue="bias_gelu", bias=bias, preact_out=pre)
-        scratch.add_(1.0)
+        for fn in launches:
+            fn()
+            scratch.add_(1.0)
     torch.cuda.synchronize()
-    log("traffic driver: 3 x (copy 256 MiB, flush, forward GEMM 8192x4096x4096 with bias+GELU epilogue, flush) done")
+    log("traffic driver (%s): 3 x (copy 256 MiB, flush, %d launches with a flush after each) done" % (what, len(launches)))
+
+
+def power_probe(torch, B, W, timer):
+    """The dominant product (8192 x 4096 x 4096, bf16, plain epilogue) on operands of different bit activity:
+    the instruction stream is identical, only the data differs.  What the times show is how far the chip's
+    power management, not the kernel's schedule, sets the rate on data that looks like a training step's."""
+    M, N, K = 8192, 4096, 4096
+    bf = torch.bfloat16
+    rng = np.random.default_rng(190800213)
+    out = torch.empty(M, N, dtype=bf, device="cuda")
+    res = {}
+    kinds = {"zeros": lambda s: np.zeros(s, np.float32), "ones": lambda s: np.ones(s, np.float32),
+             "small integers in [-3, 3]": lambda s: rng.integers(-3, 4, size=s).astype(np.float32),
+             "standard normal": lambda s: rng.standard_normal(s, dtype=np.float32)}
+    for rep in range(2):
+        for kind, gen in kinds.items():
+            a = B.cast(torch.from_numpy(gen((M, K))).cuda(), bf)
+            wt = B.cast(torch.from_numpy(gen((N, K))).cuda(), bf)
+            s = timer.time(lambda: B.gemm(a, wt.t(), out), 30, 5)
+            res.setdefault(kind, []).append(round(s * 1e6, 1))
+            log("  power probe  %-28s %7.1f us  %7.1f TFLOP/s" % (kind, s * 1e6, 2.0 * M * N * K / s / 1e12))
+    return {k: {"us": v, "TFLOP/s": [round(2.0 * M * N * K / (u * 1e-6) / 1e12, 1) for u in v]} for k, v in res.items()}
 
 
 def cpu_baseline(W, rows=(32, 96)):
@@ -345,8 +386,11 @@ def main():
     ap.add_argument("--separate-update", action="store_true",
                     help="headline workload: write the weight gradients and update in a separate SGD launch "
                          "instead of updating in the epilogue of the weight-gradient products (about 1 %% slower)")
-    ap.add_argument("--traffic-driver", action="store_true",
-                    help="run only the calibration copy + dominant GEMM launches (for rocprofv3 --pmc) and exit")
+    ap.add_argument("--traffic-driver", nargs="?", const="gemm", choices=["gemm", "array"],
+                    help="run only a calibration copy + the dominant GEMM launch (gemm) or the array microbenchmark's "
+                         "kernels (array), for rocprofv3 --pmc, and exit")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="run only the dominant product on operands of different bit activity and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -362,7 +406,10 @@ def main():
     timer = Timer(torch)
     extra = {}
     if args.traffic_driver:
-        traffic_driver(torch, B, W)
+        traffic_driver(torch, B, W, args.traffic_driver)
+        return
+    if args.power_probe:
+        print(json.dumps({"power_probe": power_probe(torch, B, W, timer)}))
         return
 
     # ---- headline: workload 5, wide MLP, bf16 storage / fp32 accumulate
