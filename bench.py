@@ -23,9 +23,9 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # HBM-side bytes per launch of the dominant kernel (L2 misses fetched + bytes written), from the two
-# counter runs recorded in profiles/gemm_bf16_forward_8192x4096x4096_hbm_traffic.txt (made with
-# `bench.py --traffic-driver` under rocprofv3 --pmc); 403.2 MB fetched + 134.2 MB written.
-DOMINANT_KERNEL_TRAFFIC_BYTES = 537.4e6
+# counter runs recorded in profiles/gemm_bf16_forward_8192x4096x4096_counters.txt (made with
+# `bench.py --traffic-driver gemm` under rocprofv3 --pmc); 403.3 MB fetched + 134.2 MB written.
+DOMINANT_KERNEL_TRAFFIC_BYTES = 537.5e6
 
 
 def log(*a):
@@ -423,11 +423,11 @@ def main():
         "GEMMs (separate instrumented pass) %.3f ms/step = %.1f TFLOP/s" % (
         r5["ms_per_step"], args.repeats, args.steps, r5.get("ms_per_step_regions"), r5["steps_per_s"], r5["TFLOP/s"],
         r5["gemm_seconds_per_step"] * 1e3, r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12))
-    # dominant kernel: the 256x256-tile bf16 GEMM, forward layout (both operands unit-stride along K)
+    # dominant kernel: the 256x256-tile eight-wave bf16 GEMM, forward layout (both operands unit-stride along K)
     dom = [c for c in r5["gemm_calls"] if c["call"] in ("fwd0", "fwd1", "fwd2")]
     dom_s = sum(c["us"] for c in dom) * 1e-6 / len(dom)
     dom_flops = 2.0 * dom[0]["M"] * dom[0]["N"] * dom[0]["K"]
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel_dma<bf16, A and B unit-stride along K> (256x256 tile, direct global-to-LDS copies; "
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel_w8<A and B unit-stride along K> (bf16, 256x256 tile, eight waves, direct global-to-LDS copies; "
                                            "hidden-layer forward x @ W.T + b with GELU, M=8192 N=4096 K=4096)",
                 "achieved": dom_flops / dom_s / 1e12, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
                 "frac": dom_flops / dom_s / 1e12 / MFMA_PEAK_TFLOPS["bf16"], "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES,

@@ -101,12 +101,16 @@ chn_status chn_elementwise_broadcast(int op, int n_in, const chn_array *const *i
                                      const chn_array *out, const float *scalars, int n_scalars,
                                      chn_stream stream);
 
-/* ---- reduction over one axis ------------------------------------------------------------------
+/* ---- reduction over one axis or several ---------------------------------------------------------
  * Section "Custom CUDA Kernels": a reduction kernel folds elements by a binary operator (sum folds
- * by +).  `axis` may be negative (NumPy style).  `out` has the input's shape without the axis
- * (keepdims = 0) or with it set to 1 (keepdims != 0).  Input F32 or BF16, any byte strides;
- * accumulation is fp32 in a fixed order (bit-reproducible run to run); `out` F32 or BF16.
- * An empty axis writes 0 (sum) or -inf (max). */
+ * by +).  `axis` may be negative (NumPy style), CHN_AXES(mask) for several axes at once (bit d set =
+ * dimension d is folded) or CHN_AXIS_ALL (both defined with the user-defined kernels below).  `out`
+ * has the input's shape without the folded axes (keepdims = 0) or with them set to 1 (keepdims != 0).
+ * Input F32 or BF16, any byte strides; accumulation is fp32 in a fixed order (bit-reproducible run
+ * to run); `out` F32 or BF16.  An empty axis writes 0 (sum) or -inf (max).
+ * Several axes are folded one after the other, last first, over fp32 intermediates in the workspace
+ * (neighbouring axes of a contiguous array count as one; so does a sum over everything):
+ * chn_reduce_axis_workspace_bytes takes the same axis code. */
 typedef enum { CHN_REDUCE_SUM = 0, CHN_REDUCE_MAX = 1 } chn_reduce_op;
 
 size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis);

@@ -232,11 +232,14 @@ def cast(x, dtype):
 
 
 def reduce_axis_workspace_bytes(x, axis):
-    return lib().chn_reduce_axis_workspace_bytes(_ref(desc(x)), axis)
+    d = desc(x)
+    return lib().chn_reduce_axis_workspace_bytes(_ref(d), _axis_code(axis, d.ndim))
 
 
 def reduce_axis(op, x, axis, out, keepdims=False, ws=None, stream=None):
+    """axis: an int, a tuple of ints (several axes at once) or None (all of them)."""
     p, n = _ws(ws)
+    axis = _axis_code(axis, desc(x).ndim)
     _check(lib().chn_reduce_axis(REDUCE[op] if isinstance(op, str) else op, _ref(desc(x)), axis,
                                  int(keepdims), _ref(desc(out)), p, n,
                                  _stream() if stream is None else stream))
@@ -246,6 +249,7 @@ def reduce_axis(op, x, axis, out, keepdims=False, ws=None, stream=None):
 def reduce_axis_static(op, x, axis, out, keepdims=False, stream=None):
     """reduce_axis without a workspace argument and without any allocation (partial sums in the
     library's built-in per-device array)."""
+    axis = _axis_code(axis, desc(x).ndim)
     _check(lib().chn_reduce_axis_static(REDUCE[op] if isinstance(op, str) else op, _ref(desc(x)), axis,
                                         int(keepdims), _ref(desc(out)), _stream() if stream is None else stream))
     return out

@@ -342,8 +342,8 @@ chn_status launch_op(int op, const RPlan &p, const chn_array *in, const chn_arra
 
 }  // namespace
 
-chn_status reduce_axis_impl(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
-                            void *ws, size_t ws_bytes, bool static_scratch, chn_stream stream) {
+chn_status reduce_one_axis(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                           void *ws, size_t ws_bytes, bool static_scratch, chn_stream stream) {
   if (op != CHN_REDUCE_SUM && op != CHN_REDUCE_MAX) return fail(CHN_ERR_OP, "reduce: unknown op %d", op);
   RPlan p;
   CHN_TRY(make_rplan(in, axis, &p));
@@ -387,12 +387,155 @@ chn_status reduce_axis_impl(int op, const chn_array *in, int axis, int keepdims,
   return launch_op<float, bf16_raw>(op, p, in, out, ws, st);
 }
 
+// ---- several axes at once ---------------------------------------------------------------------------------
+// CHN_AXES(mask) / CHN_AXIS_ALL are carried out as a sequence of single-axis reductions, last axis first,
+// over fp32 intermediates in the caller's workspace: neighbouring reduced dimensions that are jointly
+// contiguous are merged into one axis first (a full sum of a contiguous array is one axis), and an axis that
+// is folded into very few results is cut in two (length = r x c: c elements per row first, then the r row
+// results), because a single-axis reduction gives every result to one workgroup.
+struct Pass {
+  chn_array in, out;     // out: contiguous fp32 intermediate, or the caller's out for the last pass
+  int axis;
+  size_t ws_need;        // partial sums of the column kernel for this pass
+};
+struct MultiPlan {
+  Pass pass[2 * CHN_MAX_NDIM];
+  int n = 0;
+  size_t tmp_bytes[2] = {0, 0};   // two intermediates that take turns
+  size_t partial_bytes = 0;
+  size_t total() const { return ((tmp_bytes[0] + 255) & ~size_t(255)) + ((tmp_bytes[1] + 255) & ~size_t(255)) + partial_bytes; }
+};
+
+void set_contiguous(chn_array *a, int dtype) {
+  int64_t st = dtype_size(dtype);
+  a->dtype = dtype;
+  for (int d = a->ndim - 1; d >= 0; --d) { a->strides[d] = st; st *= a->shape[d] > 0 ? a->shape[d] : 1; }
+}
+
+chn_status make_multi(const chn_array *in, int axis_code, MultiPlan *mp) {
+  CHN_TRY(validate(in, "in", false));
+  if (!is_float(in->dtype)) return fail(CHN_ERR_DTYPE, "reduce: input must be F32 or BF16");
+  const int nd = in->ndim;
+  if (nd < 1) return fail(CHN_ERR_NDIM, "reduce: input needs at least one dimension");
+  int mask;
+  if (axis_code == CHN_AXIS_ALL) mask = (1 << nd) - 1;
+  else {
+    mask = axis_code - CHN_AXES(0);
+    if (mask <= 0 || (mask >> nd) != 0) return fail(CHN_ERR_AXIS, "reduce: axis set 0x%x out of range for %d dimensions", mask, nd);
+  }
+  // working copy of the view; reduced flag per dimension
+  chn_array cur = *in;
+  bool red[CHN_MAX_NDIM];
+  for (int d = 0; d < nd; ++d) red[d] = (mask >> d) & 1;
+  // merge neighbouring reduced dimensions that are jointly contiguous (or of length 1)
+  for (int d = cur.ndim - 2; d >= 0; --d) {
+    if (!(red[d] && red[d + 1])) continue;
+    const bool joint = cur.shape[d + 1] == 1 || cur.shape[d] == 1 || cur.strides[d] == cur.strides[d + 1] * cur.shape[d + 1];
+    if (!joint) continue;
+    if (cur.shape[d + 1] == 1) cur.strides[d + 1] = cur.strides[d];     // keep the stride that matters
+    cur.shape[d + 1] *= cur.shape[d];
+    for (int e = d; e + 1 < cur.ndim; ++e) { cur.shape[e] = cur.shape[e + 1]; cur.strides[e] = cur.strides[e + 1]; red[e] = red[e + 1]; }
+    --cur.ndim;
+  }
+  int64_t kept = 1;
+  for (int d = 0; d < cur.ndim; ++d) if (!red[d]) kept *= cur.shape[d];
+  // cut a long axis with few results in two: (.., L, ..) -> (.., r, c, ..), both reduced
+  for (int d = 0; d < cur.ndim && cur.ndim < CHN_MAX_NDIM; ++d) {
+    if (!red[d] || cur.shape[d] < (1 << 20) || kept >= 512) continue;
+    int64_t c = 0;
+    for (int64_t t = 8192; t >= 1024; t -= 4) if (cur.shape[d] % t == 0) { c = t; break; }
+    if (!c) continue;
+    for (int e = cur.ndim; e > d + 1; --e) { cur.shape[e] = cur.shape[e - 1]; cur.strides[e] = cur.strides[e - 1]; red[e] = red[e - 1]; }
+    ++cur.ndim;
+    cur.shape[d + 1] = c; cur.strides[d + 1] = cur.strides[d]; red[d + 1] = true;
+    cur.shape[d] /= c; cur.strides[d] = cur.strides[d + 1] * c;
+    ++d;
+  }
+  // one pass per remaining reduced dimension, last first
+  int which = 0;
+  for (int d = cur.ndim - 1; d >= 0; --d) {
+    if (!red[d]) continue;
+    Pass &ps = mp->pass[mp->n++];
+    ps.in = cur;
+    ps.axis = d;
+    chn_array nxt = cur;
+    for (int e = d; e + 1 < nxt.ndim; ++e) { nxt.shape[e] = nxt.shape[e + 1]; red[e] = red[e + 1]; }
+    --nxt.ndim;
+    set_contiguous(&nxt, CHN_F32);
+    nxt.data = nullptr;                      // filled in when the workspace is known
+    ps.out = nxt;
+    RPlan rp;
+    chn_array probe = ps.in;
+    if (!probe.data) probe.data = reinterpret_cast<void *>(uintptr_t(256));   // (planning only looks at alignment)
+    CHN_TRY(make_rplan(&probe, d, &rp));
+    ps.ws_need = rp.kind == KIND_COL ? rp.ws_bytes : 0;
+    if (ps.ws_need > mp->partial_bytes) mp->partial_bytes = ps.ws_need;
+    const size_t ob = (size_t)numel(&nxt) * sizeof(float);
+    if (ob > mp->tmp_bytes[which]) mp->tmp_bytes[which] = ob;
+    which ^= 1;
+    cur = nxt;
+  }
+  return CHN_OK;
+}
+
+chn_status reduce_axis_impl(int op, const chn_array *in, int axis, int keepdims, const chn_array *out,
+                            void *ws, size_t ws_bytes, bool static_scratch, chn_stream stream) {
+  if (axis != CHN_AXIS_ALL && axis < CHN_AXES(0)) return reduce_one_axis(op, in, axis, keepdims, out, ws, ws_bytes, static_scratch, stream);
+  if (op != CHN_REDUCE_SUM && op != CHN_REDUCE_MAX) return fail(CHN_ERR_OP, "reduce: unknown op %d", op);
+  MultiPlan mp;
+  CHN_TRY(make_multi(in, axis, &mp));
+  CHN_TRY(validate(out, "out", true));
+  if (!is_float(out->dtype)) return fail(CHN_ERR_DTYPE, "reduce: out must be F32 or BF16");
+  if (!is_contiguous(out)) return fail(CHN_ERR_STRIDE, "reduce: out must be contiguous");
+  // expected shape of out
+  const int nd = in->ndim;
+  const int mask = axis == CHN_AXIS_ALL ? (1 << nd) - 1 : axis - CHN_AXES(0);
+  int od = 0;
+  for (int d = 0; d < nd; ++d) {
+    const bool r = (mask >> d) & 1;
+    if (r && !keepdims) continue;
+    if (od >= out->ndim || out->shape[od] != (r ? 1 : in->shape[d]))
+      return fail(CHN_ERR_SHAPE, "reduce: out dimension %d does not match the reduced shape", od);
+    ++od;
+  }
+  if (od != out->ndim) return fail(CHN_ERR_SHAPE, "reduce: out has ndim %d, expected %d", out->ndim, od);
+  if (numel(out) == 0) return CHN_OK;
+  const size_t need = static_scratch ? 0 : mp.total();
+  if (static_scratch) {
+    if (mp.total() > kScratchBytes)
+      return fail(CHN_ERR_WORKSPACE, "reduce (static scratch): this reduction needs %zu bytes of intermediates, the built-in buffer holds %zu; use chn_reduce_axis with a workspace",
+                  mp.total(), kScratchBytes);
+    if (mp.total() > 0) CHN_TRY(scratch_of_current_device(&ws));
+  } else {
+    CHN_TRY(check_ws(ws, ws_bytes, need, "reduce"));
+  }
+  char *base = static_cast<char *>(ws);
+  char *tmp[2] = {base, base ? base + ((mp.tmp_bytes[0] + 255) & ~size_t(255)) : nullptr};
+  char *partial = base ? tmp[1] + ((mp.tmp_bytes[1] + 255) & ~size_t(255)) : nullptr;
+  const void *src = in->data;
+  for (int i = 0; i < mp.n; ++i) {
+    Pass &ps = mp.pass[i];
+    ps.in.data = const_cast<void *>(src);
+    const bool last = i == mp.n - 1;
+    if (last) { ps.out.data = out->data; set_contiguous(&ps.out, out->dtype); }
+    else ps.out.data = tmp[i & 1];
+    CHN_TRY(reduce_one_axis(op, &ps.in, ps.axis, 0, &ps.out, partial, mp.partial_bytes, false, stream));
+    src = ps.out.data;
+  }
+  return CHN_OK;
+}
+
 
 }  // namespace chn
 
 extern "C" {
 
 size_t chn_reduce_axis_workspace_bytes(const chn_array *in, int axis) {
+  if (axis == CHN_AXIS_ALL || axis >= CHN_AXES(0)) {
+    chn::MultiPlan mp;
+    if (!in || chn::make_multi(in, axis, &mp) != CHN_OK) return 0;
+    return mp.total();
+  }
   chn::RPlan p;
   if (chn::make_rplan(in, axis, &p) != CHN_OK) return 0;
   return p.kind == chn::KIND_COL ? p.ws_bytes : 0;

@@ -245,6 +245,55 @@ def test_reduce_nd_keepdims_bf16_out_empty_and_deterministic():
     assert abs(s0 - s1) <= 1e-4 * np.abs(big).sum()
 
 
+def _np_fold(op, x, axes, keep):
+    """Several axes folded one at a time by the oracle (its single-axis call is pinned against NumPy)."""
+    out = np.asarray(x, dtype=np.float64)
+    for a in sorted((a % out.ndim for a in axes), reverse=True):
+        out = O.reduce_axis(op, out, a, True)
+    return out if keep else out.reshape([n for d, n in enumerate(out.shape) if d not in [a % out.ndim for a in axes]])
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_reduce_several_axes_at_once(dt):
+    tol = tol_for(dt, "f32", TOL_SUM)
+    cases = [((6, 70, 40), (0, 2)), ((6, 70, 40), (0, 1)), ((6, 70, 40), (1, 2)), ((6, 70, 40), None), ((5, 3, 33, 65), (1, 3)),
+             ((5, 3, 33, 65), (0, 2, 3)), ((300, 1100), None), ((2, 1200, 1024), None), ((1 << 21,), None), ((4, 1 << 20), (1,)),
+             ((2, 3, 0, 5), (1, 3)), ((7, 1, 9), (0, 1))]
+    for shape, axes in cases:
+        x = rnd(shape, dt)
+        d = dev(x, dt)
+        ax = tuple(range(len(shape))) if axes is None else axes
+        for keep in (False, True):
+            ref = _np_fold("sum", x, ax, keep)
+            need = B.reduce_axis_workspace_bytes(d, axes)
+            out = B.reduce_axis("sum", d, axes, empty(ref.shape), keepdims=keep, ws=ws(need))
+            check(host(out), ref, tol, _np_fold("sum", np.abs(x), ax, keep), "sum %s over %s" % (shape, axes))
+            if x.size:
+                got = B.reduce_axis("max", d, axes, empty(ref.shape), keepdims=keep, ws=ws(need))
+                assert np.array_equal(host(got), _np_fold("max", x, ax, keep))
+        if x.size:
+            again = B.reduce_axis("sum", d, axes, empty(ref.shape), keepdims=True, ws=ws(need))
+            assert torch.equal(again, out)                            # fixed order
+    # a transposed / sliced view, a bf16 result, exact integers, and the no-allocation entry point
+    x = rnd((40, 50, 64), dt)
+    v = dev(x, dt).permute(2, 0, 1)[1:63]
+    xv = np.transpose(x, (2, 0, 1))[1:63]
+    out = B.reduce_axis("sum", v, (0, 2), empty((40,)), ws=ws(B.reduce_axis_workspace_bytes(v, (0, 2))))
+    check(host(out), _np_fold("sum", xv, (0, 2), False), tol, _np_fold("sum", np.abs(xv), (0, 2), False), "view")
+    xi = RNG.integers(-4, 5, size=(33, 40, 130)).astype(np.float32)
+    di = dev(xi, dt)
+    need = B.reduce_axis_workspace_bytes(di, (0, 2))
+    assert np.array_equal(host(B.reduce_axis("sum", di, (0, 2), empty((40,)), ws=ws(need))), xi.sum(axis=(0, 2), dtype=np.float64))
+    assert np.array_equal(host(B.reduce_axis("sum", di, None, empty(()), ws=ws(B.reduce_axis_workspace_bytes(di, None)))), xi.sum(dtype=np.float64))
+    assert torch.equal(B.reduce_axis_static("sum", di, (0, 2), empty((40,))), B.reduce_axis("sum", di, (0, 2), empty((40,)), ws=ws(need)))
+    ob = B.reduce_axis("sum", di, (0, 2), empty((40,), "bf16"), ws=ws(need))
+    check(host(ob), xi.sum(axis=(0, 2), dtype=np.float64), TOL_BF16, None, "bf16 result")
+    with pytest.raises(B.ChnError):
+        B.reduce_axis("sum", di, (0, 2), empty((40,)))                # workspace required
+    with pytest.raises(B.ChnError):
+        B.reduce_axis("sum", di, (0, 2), empty((41,)), ws=ws(need))   # wrong shape
+
+
 @pytest.mark.parametrize("dt,shape", [("f32", (1500, 2048)), ("f32", (2, 1100, 2052)), ("bf16", (3000, 4104)), ("bf16", (1027, 8192))])
 def test_reduce_wide_columns_ignore_what_the_workspace_held(dt, shape):
     """Wide column reductions leave partial sums in the caller's workspace.  Its previous contents
