@@ -94,6 +94,9 @@ typedef enum {
   CHN_OP_SIGMOID,   /* 1 / (1 + exp(-x))                                                         */
   CHN_OP_TANH,      /* tanh(x)                                                                   */
   CHN_OP_SQRT,      /* sqrt(x)                                                                   */
+  CHN_OP_EXP,       /* exp(x)                                                                    */
+  CHN_OP_GELU_BWD2, /* g * phi(z) (2 - z^2)         (inputs g, z: gelu''(z) = phi(z)(2 - z^2), what a
+                       differentiable backward of GELU needs -- Section "Double Backpropagation")  */
   CHN_OP_COUNT_
 } chn_op;
 
@@ -261,6 +264,18 @@ chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels,
                               int64_t ignore_label, const chn_array *lse, float upstream,
                               const chn_array *dlogits, void *ws, size_t ws_bytes,
                               chn_stream stream);
+
+/* The derivative of chn_softmax_ce_bwd, for gradients of gradients (Section "Double Backpropagation":
+ * a backward pass that is itself differentiated).  With G = chn_softmax_ce_bwd(logits, labels, upstream)
+ * and gg (N,C) the gradient that reaches G:
+ *   dlogits[n,c] = (upstream / N_valid) p[n,c] (gg[n,c] - sum_k p[n,k] gg[n,k])   (0 on ignored rows)
+ *   dupstream    = (1 / N_valid) sum over valid n, all c of gg[n,c] (p[n,c] - [c == label_n])
+ * p = softmax(logits); dupstream: a single F32 value or NULL.  F32 only; `lse` as above; workspace:
+ * chn_softmax_ce_workspace_bytes(N). */
+chn_status chn_softmax_ce_bwd2(const chn_array *logits, const chn_array *labels, int64_t ignore_label,
+                               const chn_array *lse, float upstream, const chn_array *gg,
+                               const chn_array *dlogits, const chn_array *dupstream, void *ws,
+                               size_t ws_bytes, chn_stream stream);
 
 /* Both of the above in one call, for a training step, where the gradient follows the loss at once:
  * loss_mean, lse (or NULL) and dlogits as defined there, the logits read from memory once.  dlogits

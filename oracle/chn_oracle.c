@@ -63,10 +63,12 @@ enum {
   ORC_SIGMOID,
   ORC_TANH,
   ORC_SQRT,
+  ORC_EXP,
+  ORC_GELU_BWD2, /* g * gelu''(z), gelu''(z) = phi(z) (2 - z^2): the derivative of Phi(z) + z phi(z) */
   ORC_N_OPS
 };
 
-static const int orc_arity[ORC_N_OPS] = {1, 2, 2, 2, 3, 3, 1, 2, 1, 2, 1, 2, 2, 2, 0, 1, 1, 1};
+static const int orc_arity[ORC_N_OPS] = {1, 2, 2, 2, 3, 3, 1, 2, 1, 2, 1, 2, 2, 2, 0, 1, 1, 1, 1, 2};
 
 static double orc_gelu(double x) { return 0.5 * x * (1.0 + erf(x / sqrt(2.0))); }
 
@@ -99,6 +101,8 @@ static double orc_apply(int op, const double *x, const double *s) {
     case ORC_SIGMOID: return orc_sigmoid(x[0]);
     case ORC_TANH: return tanh(x[0]);
     case ORC_SQRT: return sqrt(x[0]);
+    case ORC_EXP: return exp(x[0]);
+    case ORC_GELU_BWD2: return x[0] * (exp(-0.5 * x[1] * x[1]) / sqrt(2.0 * 3.14159265358979323846)) * (2.0 - x[1] * x[1]);
   }
   return NAN;
 }
@@ -340,6 +344,34 @@ void orc_softmax_ce_bwd(const double *logits, const int64_t *labels, int64_t N, 
       d[c] = g * (p - (c == labels[n] ? 1.0 : 0.0));
     }
   }
+}
+
+/* The derivative of orc_softmax_ce_bwd (for a backward pass that is differentiated again): with
+ * G[n,c] = s_n (p[n,c] - [c == t_n]), s_n = upstream / N_valid on valid rows, and u the gradient reaching G,
+ *   dlogits[n,c] = s_n p[n,c] (u[n,c] - sum_k p[n,k] u[n,k]),
+ *   *dupstream   = (1 / N_valid) sum over valid n, all c of u[n,c] (p[n,c] - [c == t_n]).
+ * (d p_k / d z_c = p_k ([k == c] - p_c), the textbook softmax Jacobian.) */
+void orc_softmax_ce_bwd2(const double *logits, const int64_t *labels, int64_t N, int64_t C,
+                         int64_t ignore_label, double upstream, const double *u, double *dlogits,
+                         double *dupstream) {
+  int64_t n_valid = 0;
+  for (int64_t n = 0; n < N; ++n) if (label_counts(labels[n], ignore_label, C)) ++n_valid;
+  double s = n_valid > 0 ? upstream / (double)n_valid : 0.0;
+  double du = 0.0;
+  for (int64_t n = 0; n < N; ++n) {
+    const double *z = logits + n * C, *un = u + n * C;
+    double *d = dlogits + n * C;
+    if (!label_counts(labels[n], ignore_label, C)) { for (int64_t c = 0; c < C; ++c) d[c] = 0.0; continue; }
+    double m = -INFINITY;
+    for (int64_t c = 0; c < C; ++c) if (z[c] > m) m = z[c];
+    double sum = 0.0;
+    for (int64_t c = 0; c < C; ++c) sum += exp(z[c] - m);
+    double pu = 0.0;
+    for (int64_t c = 0; c < C; ++c) pu += exp(z[c] - m) / sum * un[c];
+    for (int64_t c = 0; c < C; ++c) d[c] = s * (exp(z[c] - m) / sum) * (un[c] - pu);
+    du += pu - un[labels[n]];
+  }
+  if (dupstream) *dupstream = n_valid > 0 ? du / (double)n_valid : 0.0;
 }
 
 /* Plain stochastic gradient descent, p <- p - lr * g (no momentum, decay or clipping). */

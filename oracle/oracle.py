@@ -21,7 +21,7 @@ class _View(C.Structure):
 
 
 _OPS = ["copy", "add", "sub", "mul", "mad", "mad_relu", "relu", "relu_bwd", "gelu", "gelu_bwd",
-        "scale", "axpy", "add_relu", "add_gelu", "fill", "sigmoid", "tanh", "sqrt"]
+        "scale", "axpy", "add_relu", "add_gelu", "fill", "sigmoid", "tanh", "sqrt", "exp", "gelu_bwd2"]
 _OP_CODE = {name: i for i, name in enumerate(_OPS)}
 
 _lib = None
@@ -52,6 +52,8 @@ def lib():
         L.orc_softmax_ce_fwd.restype = C.c_int64
         L.orc_softmax_ce_bwd.argtypes = [dp, ip, C.c_int64, C.c_int64, C.c_int64, C.c_double, dp]
         L.orc_softmax_ce_bwd.restype = None
+        L.orc_softmax_ce_bwd2.argtypes = [dp, ip, C.c_int64, C.c_int64, C.c_int64, C.c_double, dp, dp, dp]
+        L.orc_softmax_ce_bwd2.restype = None
         L.orc_sgd_update.argtypes = [dp, dp, C.c_int64, C.c_double]
         L.orc_sgd_update.restype = None
         L.orc_embed_fwd.argtypes = [dp, ip, C.c_int64, C.c_int64, C.c_int64, dp]
@@ -221,6 +223,16 @@ def softmax_ce_bwd(logits, labels, ignore_label=-1, upstream=1.0):
     dz = np.empty((N, Cn))
     lib().orc_softmax_ce_bwd(_dptr(z), _iptr(t), N, Cn, int(ignore_label), float(upstream), _dptr(dz))
     return dz
+
+
+def softmax_ce_bwd2(logits, labels, gg, ignore_label=-1, upstream=1.0):
+    """Derivative of softmax_ce_bwd: returns (dlogits, dupstream) for the gradient gg reaching its result."""
+    z, t, u = _c64(logits), _i64(labels), _c64(gg)
+    N, Cn = z.shape
+    dz = np.empty((N, Cn))
+    du = C.c_double(0.0)
+    lib().orc_softmax_ce_bwd2(_dptr(z), _iptr(t), N, Cn, int(ignore_label), float(upstream), _dptr(u), _dptr(dz), C.byref(du))
+    return dz, float(du.value)
 
 
 def sgd_update(p, g, lr):

@@ -19,7 +19,7 @@ F32, BF16, I32, I64 = 0, 1, 2, 3
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.int32: I32, torch.int64: I64}
 
 OPS = ["copy", "add", "sub", "mul", "mad", "mad_relu", "relu", "relu_bwd", "gelu", "gelu_bwd",
-       "scale", "axpy", "add_relu", "add_gelu", "fill", "sigmoid", "tanh", "sqrt"]
+       "scale", "axpy", "add_relu", "add_gelu", "fill", "sigmoid", "tanh", "sqrt", "exp", "gelu_bwd2"]
 OP = {n: i for i, n in enumerate(OPS)}
 REDUCE = {"sum": 0, "max": 1}
 EPILOGUES = ["none", "bias", "bias_relu", "bias_gelu", "relu_bwd", "gelu_bwd", "bf16_copy"]
@@ -27,7 +27,7 @@ EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_reduce_axis_static", "chn_argmax_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
-           "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_fwd_bwd",
+           "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_bwd2", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan", "chn_gemm_plan_override",
            "chn_user_kernel_config", "chn_user_kernel_stats", "chn_user_kernel_destroy",
@@ -97,6 +97,7 @@ def lib():
     L.chn_softmax_ce_fwd.argtypes = [AP, AP, C.c_int64, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_softmax_ce_bwd.argtypes = [AP, AP, C.c_int64, AP, C.c_float, AP, vp, C.c_size_t, st]
     L.chn_softmax_ce_fwd_bwd.argtypes = [AP, AP, C.c_int64, AP, AP, C.c_float, AP, vp, C.c_size_t, st]
+    L.chn_softmax_ce_bwd2.argtypes = [AP, AP, C.c_int64, AP, C.c_float, AP, AP, AP, vp, C.c_size_t, st]
     L.chn_sgd_update.argtypes = [AP, AP, C.c_float, AP, st]
     L.chn_sgd_update_multi.argtypes = [C.c_int, APP, APP, C.c_float, APP, st]
     L.chn_adam_update_multi.argtypes = [C.c_int, APP, APP, APP, APP, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int64, APP, st]
@@ -337,6 +338,14 @@ def softmax_ce_bwd(logits, labels, dlogits, lse=None, upstream=1.0, ignore_label
     _check(lib().chn_softmax_ce_bwd(_ref(desc(logits)), _ref(desc(labels)), int(ignore_label),
                                     _ref(desc(lse)), float(upstream), _ref(desc(dlogits)), p, n,
                                     _stream() if stream is None else stream))
+    return dlogits
+
+
+def softmax_ce_bwd2(logits, labels, gg, dlogits, dupstream=None, lse=None, upstream=1.0, ignore_label=-1, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().chn_softmax_ce_bwd2(_ref(desc(logits)), _ref(desc(labels)), int(ignore_label), _ref(desc(lse)), float(upstream),
+                                     _ref(desc(gg)), _ref(desc(dlogits)), _ref(desc(dupstream)), p, n,
+                                     _stream() if stream is None else stream))
     return dlogits
 
 

@@ -20,8 +20,8 @@
 namespace chn {
 namespace {
 
-constexpr int kArity[CHN_OP_COUNT_] = {1, 2, 2, 2, 3, 3, 1, 2, 1, 2, 1, 2, 2, 2, 0, 1, 1, 1};
-constexpr int kScalars[CHN_OP_COUNT_] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 0, 0, 1, 0, 0, 0};
+constexpr int kArity[CHN_OP_COUNT_] = {1, 2, 2, 2, 3, 3, 1, 2, 1, 2, 1, 2, 2, 2, 0, 1, 1, 1, 1, 2};
+constexpr int kScalars[CHN_OP_COUNT_] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 1, 1, 0, 0, 1, 0, 0, 0, 0, 0};
 
 // LOWP: the result is stored as bfloat16.  gelu and its derivative then use the compact forms of the
 // GEMM epilogues: absolute error 1.5e-7 in Phi, so |error| <= 1.5e-7 |x|; what is lost against the
@@ -52,6 +52,8 @@ __device__ __forceinline__ float ew_apply(float x, float y, float z, float s) {
   else if constexpr (OP == CHN_OP_SIGMOID) return sigmoid_f(x);
   else if constexpr (OP == CHN_OP_TANH) return tanhf(x);
   else if constexpr (OP == CHN_OP_SQRT) return sqrtf(x);
+  else if constexpr (OP == CHN_OP_EXP) return expf(x);
+  else if constexpr (OP == CHN_OP_GELU_BWD2) return x * (0.39894228040143267794f * expf(-0.5f * y * y)) * (2.0f - y * y);
   else return 0.0f;
 }
 
@@ -63,7 +65,7 @@ __device__ __forceinline__ float ew_apply_rt(int op, float x, float y, float z, 
     CHN_CASE(CHN_OP_MAD) CHN_CASE(CHN_OP_MAD_RELU) CHN_CASE(CHN_OP_RELU) CHN_CASE(CHN_OP_RELU_BWD)
     CHN_CASE(CHN_OP_GELU) CHN_CASE(CHN_OP_GELU_BWD) CHN_CASE(CHN_OP_SCALE) CHN_CASE(CHN_OP_AXPY)
     CHN_CASE(CHN_OP_ADD_RELU) CHN_CASE(CHN_OP_ADD_GELU) CHN_CASE(CHN_OP_FILL)
-    CHN_CASE(CHN_OP_SIGMOID) CHN_CASE(CHN_OP_TANH) CHN_CASE(CHN_OP_SQRT)
+    CHN_CASE(CHN_OP_SIGMOID) CHN_CASE(CHN_OP_TANH) CHN_CASE(CHN_OP_SQRT) CHN_CASE(CHN_OP_EXP) CHN_CASE(CHN_OP_GELU_BWD2)
 #undef CHN_CASE
   }
   return 0.0f;
@@ -569,7 +571,7 @@ chn_status launch_dtype(int op, const Plan &p, const chn_array *const *in, const
       CHN_CASE(CHN_OP_MAD) CHN_CASE(CHN_OP_MAD_RELU) CHN_CASE(CHN_OP_RELU) CHN_CASE(CHN_OP_RELU_BWD)
       CHN_CASE(CHN_OP_GELU) CHN_CASE(CHN_OP_GELU_BWD) CHN_CASE(CHN_OP_SCALE) CHN_CASE(CHN_OP_AXPY)
       CHN_CASE(CHN_OP_ADD_RELU) CHN_CASE(CHN_OP_ADD_GELU) CHN_CASE(CHN_OP_FILL)
-      CHN_CASE(CHN_OP_SIGMOID) CHN_CASE(CHN_OP_TANH) CHN_CASE(CHN_OP_SQRT)
+      CHN_CASE(CHN_OP_SIGMOID) CHN_CASE(CHN_OP_TANH) CHN_CASE(CHN_OP_SQRT) CHN_CASE(CHN_OP_EXP) CHN_CASE(CHN_OP_GELU_BWD2)
 #undef CHN_CASE
     }
     return fail(CHN_ERR_OP, "elementwise: unknown op %d", op);

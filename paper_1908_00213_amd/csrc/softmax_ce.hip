@@ -289,6 +289,43 @@ __global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pit
   }
 }
 
+// The derivative of the gradient (what differentiating a backward pass needs): with
+// G[n,c] = s_n (p[n,c] - [c == t_n]), s_n = upstream / N_valid on valid rows and 0 elsewhere, and u the
+// gradient that reaches G,
+//   dz[n,c]   = s_n p[n,c] (u[n,c] - sum_k p[n,k] u[n,k])        (G's dependence on the logits)
+//   rows[n]   = sum_c u[n,c] (p[n,c] - [c == t_n])                (summed over valid rows / N_valid: d upstream)
+// One wave per row, three sweeps (log-sum-exp unless given, the two row sums, the result): this path is
+// taken by second-order derivatives only.  F32 throughout.
+template <typename L>
+__global__ __launch_bounds__(256) void sce_bwd2_kernel(const float *z, int64_t pitch, const L *labels, int64_t N, int64_t C, int64_t ignore,
+                                                       const float *lse_in, const float *scale_ptr, const float *u, int64_t upitch,
+                                                       float *dz, int64_t dpitch, float *rows) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= N) return;
+  const float *p = z + row * pitch, *ur = u + row * upitch;
+  float lse;
+  if (lse_in) {
+    lse = lse_in[row];
+  } else {
+    float m = -INFINITY;
+    for (int64_t c = lane; c < C; c += 64) m = fmaxf(m, p[c]);
+    m = wave_max(m);
+    float e = 0.0f;
+    for (int64_t c = lane; c < C; c += 64) e += expf(p[c] - m);
+    lse = m + logf(wave_sum(e));
+  }
+  const int64_t t = row_label(labels, row, ignore, C);
+  float pu = 0.0f;
+  for (int64_t c = lane; c < C; c += 64) pu += expf(p[c] - lse) * ur[c];
+  pu = wave_sum(pu);
+  const bool valid = t != ignore;
+  if (rows && lane == 0) rows[row] = valid ? pu - ur[t] : 0.0f;
+  const float s = valid ? *scale_ptr : 0.0f;
+  float *q = dz + row * dpitch;
+  for (int64_t c = lane; c < C; c += 64) q[c] = s == 0.0f ? 0.0f : s * expf(p[c] - lse) * (ur[c] - pu);
+}
+
 struct Common {
   int64_t N = 0, C = 0, pitch = 0;
   int G = 256;
@@ -447,6 +484,47 @@ chn_status chn_softmax_ce_bwd(const chn_array *logits, const chn_array *labels, 
   else CHN_GO(bf16_raw, bf16_raw);
 #undef CHN_GO
   return check_launch("softmax_ce_bwd rows");
+}
+
+chn_status chn_softmax_ce_bwd2(const chn_array *logits, const chn_array *labels, int64_t ignore_label,
+                               const chn_array *lse, float upstream, const chn_array *gg, const chn_array *dlogits,
+                               const chn_array *dupstream, void *ws, size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  Common c;
+  CHN_TRY(check_common(logits, labels, &c));
+  CHN_TRY(validate(gg, "gg", false));
+  CHN_TRY(validate(dlogits, "dlogits", true));
+  if (logits->dtype != CHN_F32 || gg->dtype != CHN_F32 || dlogits->dtype != CHN_F32)
+    return fail(CHN_ERR_DTYPE, "softmax_ce_bwd2: logits, gg and dlogits must be F32");
+  int64_t un, uc, upitch, dn, dc, dpitch;
+  CHN_TRY(row_major_2d(gg, "gg", &un, &uc, &upitch));
+  CHN_TRY(row_major_2d(dlogits, "dlogits", &dn, &dc, &dpitch));
+  if (un != c.N || uc != c.C || dn != c.N || dc != c.C) return fail(CHN_ERR_SHAPE, "softmax_ce_bwd2: gg and dlogits must have the logits' shape");
+  if (lse) CHN_TRY(check_rows_f32(lse, "lse", c.N));
+  if (dupstream) {
+    CHN_TRY(validate(dupstream, "dupstream", true));
+    if (dupstream->dtype != CHN_F32 || numel(dupstream) != 1) return fail(CHN_ERR_SHAPE, "softmax_ce_bwd2: dupstream must be a single F32 value");
+  }
+  if (c.N == 0) return CHN_OK;
+  CHN_TRY(check_ws(ws, ws_bytes, chn_softmax_ce_workspace_bytes(c.N), "softmax_ce_bwd2"));
+  float *scale = static_cast<float *>(ws);
+  float *rows = dupstream ? reinterpret_cast<float *>(static_cast<char *>(ws) + 256) : nullptr;
+  hipStream_t st = as_stream(stream);
+  const float *l = lse ? static_cast<const float *>(lse->data) : nullptr;
+  const unsigned blocks = (unsigned)((c.N + 3) / 4);
+#define CHN_GO(L)                                                                                                              \
+  do {                                                                                                                         \
+    const L *t = static_cast<const L *>(labels->data);                                                                         \
+    hipLaunchKernelGGL((sce_scale_kernel<L>), dim3(1), dim3(1024), 0, st, t, c.N, c.C, ignore_label, upstream, scale);          \
+    hipLaunchKernelGGL((sce_bwd2_kernel<L>), dim3(blocks), dim3(256), 0, st, static_cast<const float *>(logits->data), c.pitch, t, \
+                       c.N, c.C, ignore_label, l, scale, static_cast<const float *>(gg->data), upitch,                          \
+                       static_cast<float *>(dlogits->data), dpitch, rows);                                                     \
+    if (dupstream) hipLaunchKernelGGL((sce_mean_kernel<L>), dim3(1), dim3(1024), 0, st, rows, t, c.N, c.C, ignore_label,        \
+                                      static_cast<float *>(dupstream->data));                                                  \
+  } while (0)
+  if (labels->dtype == CHN_I32) CHN_GO(int32_t); else CHN_GO(int64_t);
+#undef CHN_GO
+  return check_launch("softmax_ce_bwd2");
 }
 
 chn_status chn_softmax_ce_fwd_bwd(const chn_array *logits, const chn_array *labels, int64_t ignore_label,

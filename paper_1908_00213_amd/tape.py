@@ -112,6 +112,10 @@ class GpuBackend:
         ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
         self.B.softmax_ce_bwd(logits, labels, dlogits, lse, upstream, ignore_label, ws)
 
+    def softmax_ce_bwd2(self, logits, labels, gg, dlogits, dupstream, lse, upstream, ignore_label):
+        ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
+        self.B.softmax_ce_bwd2(logits, labels, gg, dlogits, dupstream, lse, upstream, ignore_label, ws)
+
     def embed_fwd(self, table, ids, out):
         self.B.embed_fwd(table, ids, out)
 
@@ -623,7 +627,7 @@ class LinearFunction(FunctionNode):
             self.z = F.empty(y.shape, dt)
         epi = {None: "bias", "relu": "bias_relu", "gelu": "bias_gelu"}[self.act]
         F.gemm(x, _t(W), y, epilogue=epi, bias=b, preact_out=self.z)
-        self.retain_inputs((0, 1))
+        self.retain_inputs((0, 1, 2) if self.act == "gelu" else (0, 1))   # (the bias: a differentiable backward rebuilds z)
         if self.act == "relu":
             self.retain_outputs((0,))
         return (y,)
@@ -633,7 +637,7 @@ class LinearFunction(FunctionNode):
 
     def backward(self, indexes, gys):
         F = backend()
-        x, W = self.get_retained_inputs()
+        x, W = self.get_retained_inputs()[:2]
         gy, = gys
         if self.act is not None:
             ref = self.get_retained_outputs()[0] if self.act == "relu" else self.z
@@ -660,10 +664,14 @@ class LinearFunction(FunctionNode):
 
 
     def backward_vars(self, indexes, gys):
+        x, W = self.get_retained_input_vars()[:2]
         if self.act == "gelu":
-            raise NotImplementedError("linear(act='gelu') has no differentiable backward; apply tanh / relu as functions")
-        x, W = self.get_retained_input_vars()
-        gz = gys[0] if self.act is None else relu_grad(gys[0], self.get_retained_output_vars()[0])
+            # the pre-activation the epilogue stored is an array without history: as a function of x, W and
+            # b it is computed once more, by a recorded linear function
+            z = linear(x, W, self.get_retained_input_vars()[2])
+            gz = gelu_grad(gys[0], z)
+        else:
+            gz = gys[0] if self.act is None else relu_grad(gys[0], self.get_retained_output_vars()[0])
         grads = {0: lambda: matmul(gz, W), 1: lambda: matmul(transpose(gz), x), 2: lambda: sum_rows(gz)}
         return tuple(grads[i]() for i in indexes)
 
@@ -759,6 +767,95 @@ class GELU(_Activation):
 
     def saved(self):
         return self.get_retained_inputs()[0]
+
+    def backward_vars(self, indexes, gys):
+        return (gelu_grad(gys[0], self.get_retained_input_vars()[0]),)
+
+
+class GELUGrad(FunctionNode):
+    """gy * gelu'(z): the backward of GELU as a function of both its operands.  Its own derivative with
+    respect to z needs gelu''(z) = phi(z) (2 - z^2)."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("gelu_bwd", [xs[0], xs[1]], out)
+        self.retain_inputs((0, 1))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        gy, z = self.get_retained_input_vars()
+        return tuple(gelu_grad(gys[0], z) if i == 0 else gelu_grad2(mul(gys[0], gy), z) for i in indexes)
+
+
+class GELUGrad2(FunctionNode):
+    """a * gelu''(z).  Linear in a; the derivative with respect to z (a third derivative of GELU) is not
+    provided."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("gelu_bwd2", [xs[0], xs[1]], out)
+        self.retain_inputs((1,))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        z, = self.get_retained_input_vars()
+        if 1 in indexes and z.node.requires_grad:
+            raise NotImplementedError("the third derivative of gelu is not provided")
+        return tuple(gelu_grad2(gys[0], z) if i == 0 else None for i in indexes)
+
+
+class Sigmoid(FunctionNode):
+    """1 / (1 + exp(-x)); differentiated from its output: gx = gy y (1 - y)."""
+
+    def forward(self, xs):
+        F = backend()
+        out = F.empty(xs[0].shape, F.dtype(xs[0]))
+        F.elementwise_broadcast("sigmoid", [xs[0]], out)
+        self.retain_outputs((0,))
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        y, = self.get_retained_output_vars()
+        gyy = mul(gys[0], y)
+        return (sub(gyy, mul(gyy, y)),)
+
+
+class SliceCols(FunctionNode):
+    """Columns lo .. hi - 1 of a 2-d array, as a VIEW (the kernels take any strides); the backward places
+    the gradient into a zero array of the full width."""
+
+    def __init__(self, lo, hi):
+        super().__init__()
+        self.lo, self.hi = lo, hi
+
+    def forward(self, xs):
+        self.width = xs[0].shape[1]
+        return (xs[0][:, self.lo:self.hi],)
+
+    def backward_vars(self, indexes, gys):
+        return (PadCols(self.lo, self.width).apply((gys[0],))[0],)
+
+
+class PadCols(FunctionNode):
+    """(n, w) -> (n, width): the array placed at column `lo` of zeros; the backward slices it out again."""
+
+    def __init__(self, lo, width):
+        super().__init__()
+        self.lo, self.width = lo, width
+
+    def forward(self, xs):
+        F = backend()
+        x = xs[0]
+        out = F.empty((x.shape[0], self.width), F.dtype(x))
+        F.elementwise_broadcast("fill", [], out, (0.0,))
+        F.elementwise_broadcast("copy", [x], out[:, self.lo:self.lo + x.shape[1]])
+        self.w = x.shape[1]
+        return (out,)
+
+    def backward_vars(self, indexes, gys):
+        return (slice_cols(gys[0], self.lo, self.lo + self.w),)
 
 
 class Add(FunctionNode):
@@ -1010,6 +1107,51 @@ class SoftmaxCrossEntropy(FunctionNode):
             F.elementwise_broadcast("mul", [g, gys[0]], g)
         return tuple(g if i == 0 else None for i in indexes)
 
+    def backward_vars(self, indexes, gys):
+        if not _record:
+            return FunctionNode.backward_vars(self, indexes, gys)
+        logits, = self.get_retained_input_vars()
+        g = SoftmaxCEGrad(self.labels, self.lse, self.ignore_label).apply((logits, gys[0]))[0]
+        return tuple(g if i == 0 else None for i in indexes)
+
+
+class SoftmaxCEGrad(FunctionNode):
+    """(logits, gy) -> gy * (softmax(logits) - onehot) / N_valid: the backward of the mean softmax
+    cross-entropy as a function, so that it can be differentiated in turn (gradient penalties on a
+    classifier's loss).  Its own backward is one kernel (the softmax Jacobian applied to the incoming
+    gradient); a third derivative is not provided.  fp32."""
+
+    def __init__(self, labels, lse, ignore_label):
+        super().__init__()
+        self.labels, self.lse, self.ignore_label = labels, lse, ignore_label
+
+    def forward(self, xs):
+        F = backend()
+        logits, gy = xs
+        g = F.empty(logits.shape, "f32")
+        F.softmax_ce_bwd(logits, self.labels, g, self.lse, 1.0, self.ignore_label)
+        F.elementwise_broadcast("mul", [g, gy], g)
+        self.retain_inputs((0, 1))
+        return (g,)
+
+    def release_locals(self):
+        self.labels = self.lse = None
+
+    def backward(self, indexes, gys):
+        F = backend()
+        logits, gy = self.get_retained_inputs()
+        dz = F.empty(logits.shape, "f32")
+        dup = F.empty((), "f32")
+        F.softmax_ce_bwd2(logits, self.labels, gys[0], dz, dup, self.lse, 1.0, self.ignore_label)
+        out = []
+        for i in indexes:
+            if i == 0:
+                F.elementwise_broadcast("mul", [dz, gy], dz)
+                out.append(dz)
+            else:
+                out.append(dup.reshape(gy.shape))
+        return tuple(out)
+
 
 class EmbedID(FunctionNode):
     """out[n] = table[ids[n]]; the backward scatters rows back (a dense gradient of the table,
@@ -1045,12 +1187,42 @@ class EmbedID(FunctionNode):
             out.append(g)
         return tuple(out)
 
+    def backward_vars(self, indexes, gys):
+        if not _record:
+            return FunctionNode.backward_vars(self, indexes, gys)
+        return tuple(EmbedGrad(self.ids, self.table_shape).apply((gys[0],))[0] if i == 1 else None for i in indexes)
+
+
+class EmbedGrad(FunctionNode):
+    """dout (N, D) -> dtable (V, D): rows summed into the table rows their ids name (the backward of the
+    lookup as a function).  Linear, so its own backward is the lookup again."""
+
+    def __init__(self, ids, table_shape):
+        super().__init__()
+        self.ids, self.table_shape = ids, table_shape
+
+    def forward(self, xs):
+        F = backend()
+        g = F.empty(self.table_shape, "f32")
+        F.embed_bwd(self.ids, xs[0], g, False)
+        return (g,)
+
+    def backward_vars(self, indexes, gys):
+        return (embed_id(self.ids, gys[0]),)
+
 
 class LSTM(FunctionNode):
     """(c_prev, z[, bias]) -> (c, h): the cell of the recurrent language model; z holds the four
     gate pre-activations.  Backward works from retained outputs: the activated gates the forward
     kernel stored, c_prev and c."""
     fresh = (0, 1, 2)
+
+    def __init__(self, twice_differentiable=False):
+        """twice_differentiable: also retain the gate pre-activations z (and the bias), which the fused
+        backward does not need but a differentiable backward does: it rebuilds the cell from element-wise
+        functions of c_prev and z and differentiates that."""
+        super().__init__()
+        self.twice = twice_differentiable
 
     def forward(self, xs):
         F = backend()
@@ -1060,16 +1232,34 @@ class LSTM(FunctionNode):
         h = F.empty(c_prev.shape, "f32")
         self.gates = F.empty(z.shape, "f32")
         F.lstm_fwd(z, bias, c_prev, c, h, self.gates)
-        self.retain_inputs((0,))
+        self.retain_inputs(tuple(range(len(xs))) if self.twice else (0,))
         self.retain_outputs((0,))
         return (c, h)
+
+    def backward_vars(self, indexes, gys):
+        if not _record:
+            return FunctionNode.backward_vars(self, indexes, gys)
+        if not self.twice:
+            raise NotImplementedError("lstm(..., twice_differentiable=True) is needed for a differentiable backward "
+                                      "(the fused cell does not retain its pre-activations)")
+        ins = self.get_retained_input_vars()
+        c_prev, z = ins[0], ins[1]
+        H = c_prev.shape[1]
+        zb = z if len(ins) < 3 else add(z, ins[2])
+        i, f, o = (sigmoid(slice_cols(zb, k * H, (k + 1) * H)) for k in (0, 1, 3))
+        g = tanh(slice_cols(zb, 2 * H, 3 * H))
+        c = add(mul(f, c_prev), mul(i, g))
+        h = mul(o, tanh(c))
+        pairs = [(y, gy) for y, gy in zip((c, h), gys) if gy is not None]
+        res = _backward_vars([y for y, _ in pairs], [gy for _, gy in pairs], [ins[k] for k in indexes], False)
+        return tuple(res.get(id(ins[k].node)) for k in indexes)
 
     def release_locals(self):
         self.gates = None
 
     def backward(self, indexes, gys):
         F = backend()
-        c_prev, = self.get_retained_inputs()
+        c_prev = self.get_retained_inputs()[0]
         c, = self.get_retained_outputs()
         gc, gh = gys
         if gh is None:
@@ -1263,6 +1453,22 @@ def gelu(x):
     return GELU().apply((x,))[0]
 
 
+def gelu_grad(gy, z):
+    return GELUGrad().apply((gy, z))[0]
+
+
+def gelu_grad2(a, z):
+    return GELUGrad2().apply((a, z))[0]
+
+
+def sigmoid(x):
+    return Sigmoid().apply((x,))[0]
+
+
+def slice_cols(x, lo, hi):
+    return SliceCols(lo, hi).apply((x,))[0]
+
+
 def add(x, y):
     return Add().apply((x, y))[0]
 
@@ -1315,9 +1521,9 @@ def embed_id(ids, table):
     return EmbedID().apply((ids, table))[0]
 
 
-def lstm(c_prev, z, bias=None):
+def lstm(c_prev, z, bias=None, twice_differentiable=False):
     """Returns (c, h)."""
-    return LSTM().apply((c_prev, z) if bias is None else (c_prev, z, bias))
+    return LSTM(twice_differentiable).apply((c_prev, z) if bias is None else (c_prev, z, bias))
 
 
 def n_step_lstm(c0, h0, zx, U, bias, n_steps, lowp=False):

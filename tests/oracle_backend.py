@@ -104,6 +104,13 @@ class OracleBackend:
         self.calls.append(("softmax_ce_bwd", None))
         dlogits[...] = O.softmax_ce_bwd(logits, labels, ignore_label, upstream)
 
+    def softmax_ce_bwd2(self, logits, labels, gg, dlogits, dupstream, lse, upstream, ignore_label):
+        self.calls.append(("softmax_ce_bwd2", None))
+        dz, du = O.softmax_ce_bwd2(logits, labels, gg, ignore_label, upstream)
+        dlogits[...] = dz
+        if dupstream is not None:
+            dupstream[...] = du
+
     def embed_fwd(self, table, ids, out):
         self.calls.append(("embed_fwd", None))
         out[...] = O.embed_fwd(table, ids)

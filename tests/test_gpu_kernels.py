@@ -37,8 +37,8 @@ def test_mad_relu_row_broadcast(dt_in, dt_out, shape):
         assert np.max(np.abs(host(out) - ref)) <= 2.0 ** -23 * 2
 
 
-OPS1 = ["copy", "relu", "gelu", "sigmoid", "tanh"]
-OPS2 = ["add", "sub", "mul", "relu_bwd", "gelu_bwd", "add_relu", "add_gelu"]
+OPS1 = ["copy", "relu", "gelu", "sigmoid", "tanh", "exp"]
+OPS2 = ["add", "sub", "mul", "relu_bwd", "gelu_bwd", "add_relu", "add_gelu", "gelu_bwd2"]
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
@@ -53,7 +53,7 @@ def test_every_op_flat(dt):
     for op in OPS2:
         out = B.elementwise_broadcast(op, [dev(x, dt), dev(y, dt)], empty(shape, dt))
         S = {"add": np.abs(x) + np.abs(y), "sub": np.abs(x) + np.abs(y), "add_relu": np.abs(x) + np.abs(y),
-             "add_gelu": np.abs(x) + np.abs(y), "gelu_bwd": np.abs(x) * (1 + np.abs(y))}.get(op)
+             "add_gelu": np.abs(x) + np.abs(y), "gelu_bwd": np.abs(x) * (1 + np.abs(y)), "gelu_bwd2": np.abs(x)}.get(op)
         check(host(out), O.elementwise(op, [x, y]), tol, S, op)
     out = B.elementwise_broadcast("mad", [dev(x, dt), dev(y, dt), dev(z, dt)], empty(shape, dt))
     check(host(out), O.elementwise("mad", [x, y, z]), tol, np.abs(x * y) + np.abs(z), "mad")
@@ -377,6 +377,29 @@ def test_softmax_ce(N, Cn, dt, lab):
         zc = zd.clone()
         B.softmax_ce_bwd(zc, td, zc, None, 1.5, ws=w)
         check(host(zc), ref, TOL_EW * 10, 1.5 / nv, "in place")
+
+
+@pytest.mark.parametrize("N,Cn,lab", [(37, 10, np.int32), (301, 1000, np.int64), (5, 65, np.int32), (130, 4100, np.int32)])
+def test_softmax_ce_second_order(N, Cn, lab):
+    z = rnd((N, Cn), "f32", -5, 5)
+    u = rnd((N, Cn), "f32", -2, 2)
+    t = RNG.integers(0, Cn, size=(N,)).astype(lab)
+    t[::6] = -1
+    t[3] = Cn + 5                                                  # a stray label counts as ignored
+    zd, ud, td = dev(z), dev(u), dev(t)
+    w = ws(B.softmax_ce_workspace_bytes(N))
+    ref_dz, ref_du = O.softmax_ce_bwd2(z, t, u, -1, 1.5)
+    nv = int(((t >= 0) & (t < Cn)).sum())
+    lse = empty((N,))
+    B.softmax_ce_fwd(zd, td, empty(()), None, lse, ws=w)
+    for use_lse in (False, True):
+        dz, du = empty((N, Cn)), empty(())
+        B.softmax_ce_bwd2(zd, td, ud, dz, du, lse if use_lse else None, 1.5, ws=w)
+        check(host(dz), ref_dz, TOL_EW * 10, 1.5 / nv * np.abs(u).max(), "second-order dlogits")
+        assert abs(float(du.cpu()) - ref_du) <= 1e-5 * (np.abs(u).sum() / nv)
+        assert np.all(host(dz)[(t < 0) | (t >= Cn)] == 0)
+    dz2 = B.softmax_ce_bwd2(zd, td, ud, empty((N, Cn)), None, lse, 1.5, ws=w)   # without the scalar output
+    assert torch.equal(dz2, dz)
 
 
 @pytest.mark.parametrize("N,Cn,lab", [(300, 10, np.int32), (70, 1000, np.int64), (9000, 10, np.int32), (64, 4100, np.int32)])

@@ -335,6 +335,60 @@ def test_tape_double_backprop_gradient_penalty(first):
     check(got[3], ref[3], 1e-4, float(np.max(np.abs(ref[3]))) + 1e-30, "d penalty / d x")
 
 
+@pytest.mark.parametrize("what", ["gelu_fused", "softmax_ce", "embedding", "lstm"])
+def test_tape_double_backprop_through_the_remaining_functions(what):
+    """The gradient of || d loss / d input ||^2 through the fused-GELU linear layer, the softmax cross-entropy, the
+    embedding lookup and the LSTM cell: the same tape code on the GPU and, as the reference, on the CPU with the
+    oracle's functions as kernels (whose second-order pieces are pinned by finite differences on the CPU)."""
+    rng = np.random.default_rng(29)
+    n, d, hdim, k, V = 200, 96, 128, 24, 50
+    f32 = lambda a: a.astype(np.float32)
+    W1, b1 = f32(rng.standard_normal((hdim, d)) / np.sqrt(d)), f32(rng.standard_normal(hdim) * 0.1)
+    W2, b2 = f32(rng.standard_normal((k, hdim)) / np.sqrt(hdim)), np.zeros(k, np.float32)
+    Wz, bz = f32(rng.standard_normal((4 * hdim, d)) / np.sqrt(d)), f32(rng.standard_normal(4 * hdim) * 0.1)
+    x, c, cp = f32(rng.standard_normal((n, d))), f32(rng.standard_normal((n, k))), f32(rng.standard_normal((n, hdim)))
+    E = f32(rng.standard_normal((V, d)))
+    ids = rng.integers(0, V, n)
+    t = rng.integers(0, k, n)
+    t[::9] = -1
+
+    def run(F):
+        P = lambda a: T.Parameter(F.from_numpy(a))
+        const = lambda a: T.Variable(F.from_numpy(a), False)
+        if what == "gelu_fused":
+            vs = [P(W1), P(b1), P(W2), P(x)]
+            f = T.sum_all(T.mul(T.linear(T.linear(vs[3], vs[0], vs[1], act="gelu"), vs[2], const(b2)), const(c)))
+            wrt = vs[3]
+        elif what == "softmax_ce":
+            vs = [P(W1), P(b1), P(W2), P(b2), P(x)]
+            f = T.softmax_cross_entropy(T.linear(T.tanh(T.linear(vs[4], vs[0], vs[1])), vs[2], vs[3]), F.from_numpy(t))
+            wrt = vs[4]
+        elif what == "embedding":
+            vs = [P(E), P(W1), P(b1), P(W2)]
+            f = T.sum_all(T.mul(T.linear(T.tanh(T.linear(T.embed_id(F.from_numpy(ids), vs[0]), vs[1], vs[2])), vs[3], const(b2)), const(c)))
+            wrt = vs[0]
+        else:
+            vs = [P(Wz), P(bz), P(cp), P(x), P(W2)]
+            cn, hn = T.lstm(vs[2], T.linear(vs[3], vs[0], const(np.zeros(4 * hdim, np.float32))), vs[1], twice_differentiable=True)
+            f = T.add(T.sum_all(T.mul(T.linear(hn, vs[4], const(b2)), const(c))), T.sum_all(T.mul(cn, cn)))
+            wrt = vs[3]
+        g, = T.grad([f], [wrt], enable_double_backprop=True)
+        pen = T.sum_all(T.mul(g, g))
+        pen.backward()
+        return float(F.to_numpy(pen.array)), F.to_numpy(g.array), [None if v.grad is None else F.to_numpy(v.grad) for v in vs]
+
+    got = run(T.backend())
+    with T.using_backend(OracleBackend()) as Fo:
+        ref = run(Fo)
+    assert abs(got[0] - ref[0]) <= 2e-4 * abs(ref[0])
+    check(got[1], ref[1], 2e-4, float(np.max(np.abs(ref[1]))), "first-order gradient")
+    assert any(b is not None and np.any(b) for b in ref[2])
+    for i, (a, b) in enumerate(zip(got[2], ref[2])):
+        assert (a is None) == (b is None)
+        if b is not None:
+            check(a, b, 3e-4, float(np.max(np.abs(b))) + 1e-30, "d penalty / d input %d" % i)
+
+
 def test_tape_function_made_of_two_user_kernels():
     # a new differentiable operation from two snippets compiled at run time; reference: the same tape
     # on the CPU with the oracle's evaluation of the same snippets

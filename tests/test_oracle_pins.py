@@ -347,6 +347,41 @@ def test_mlp_step_lowp_rounds_only_storage():
     assert r16["loss"] != r32["loss"]
 
 
+def test_exp_and_second_derivative_of_gelu():
+    x = np.linspace(-5, 5, 401)
+    assert np.allclose(O.elementwise("exp", [x]), np.exp(x), rtol=1e-15)
+    g = RNG.standard_normal(401)
+    got = O.elementwise("gelu_bwd2", [g, x])
+    # closed form phi(z)(2 - z^2), and the central difference of the pinned first derivative
+    phi = np.exp(-0.5 * x * x) / math.sqrt(2 * math.pi)
+    assert np.allclose(got, g * phi * (2 - x * x), rtol=1e-13, atol=1e-16)
+    one = np.ones_like(x)
+    h = 1e-5
+    fd = (O.elementwise("gelu_bwd", [one, x + h]) - O.elementwise("gelu_bwd", [one, x - h])) / (2 * h)
+    assert np.max(np.abs(got - g * fd)) < 1e-8
+    assert O.elementwise("gelu_bwd2", [np.ones(1), np.zeros(1)])[0] == pytest.approx(2 / math.sqrt(2 * math.pi), rel=1e-15)
+
+
+def test_fd_softmax_ce_second_order():
+    # <u, G(z, g)> with G the (pinned) first-order gradient: its derivatives by central differences
+    z = RNG.standard_normal((6, 5))
+    t = RNG.integers(0, 5, 6)
+    t[2] = -1
+    u = RNG.standard_normal((6, 5))
+    g0 = 1.7
+    dz, dg = O.softmax_ce_bwd2(z, t, u, -1, g0)
+    _close(dz, _fd(lambda v: float((u * O.softmax_ce_bwd(v, t, -1, g0)).sum()), z), 2e-6)
+    h = 1e-5
+    fd = ((u * O.softmax_ce_bwd(z, t, -1, g0 + h)).sum() - (u * O.softmax_ce_bwd(z, t, -1, g0 - h)).sum()) / (2 * h)
+    assert abs(dg - fd) < 1e-8
+    assert np.all(dz[2] == 0) and np.max(np.abs(dz.sum(axis=1))) < 1e-15      # rows of p (u - p.u) sum to zero
+    # zero logits: p = 1/C, so dz = (g / N_valid) (u - mean(u)) / C
+    dz0, _ = O.softmax_ce_bwd2(np.zeros((6, 5)), t, u, -1, g0)
+    want = g0 / 5 * (u - u.mean(axis=1, keepdims=True)) / 5
+    want[2] = 0
+    assert np.allclose(dz0, want, rtol=1e-13, atol=1e-16)
+
+
 def test_stray_indices_are_ignored_not_followed():
     # a label outside [0, C) behaves exactly like the ignore label; an id outside [0, V) gathers zeros and
     # takes part in no gradient sum -- checked against the same problem with those rows marked / removed

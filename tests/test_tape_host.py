@@ -479,6 +479,65 @@ def test_gradient_penalty_matches_finite_differences(F, first):
         assert np.any(ps[1].grad)                                # ... but through tanh'' on the first one
 
 
+@pytest.mark.parametrize("what", ["gelu_fused", "gelu", "softmax_ce", "embedding", "lstm"])
+def test_gradient_penalty_through_the_remaining_functions(F, what):
+    """|| d loss / d input ||^2 differentiated through the fused-GELU linear layer, the GELU function, the softmax
+    cross-entropy, the embedding lookup and the LSTM cell: each needs a differentiable backward of its own."""
+    rng = np.random.default_rng(41)
+    n, d, hdim, k, V = 6, 4, 5, 3, 7
+    W1, b1, W2, b2 = rnd(rng, hdim, d), rnd(rng, hdim), rnd(rng, k, hdim), rnd(rng, k)
+    x, c = rnd(rng, n, d), rnd(rng, n, k)
+    t = rng.integers(0, k, n)
+    t[1] = -1
+    E = rnd(rng, V, d)
+    ids = np.array([1, 1, 3, 0, 6, 3])
+    Wz, bz, cp = rnd(rng, 4 * hdim, d), rnd(rng, 4 * hdim), rnd(rng, n, hdim)
+    arrays = {"gelu_fused": [W1, b1, W2, x], "gelu": [W1, b1, W2, x], "softmax_ce": [W1, b1, W2, b2, x], "embedding": [E, W1, b1, W2],
+              "lstm": [Wz, bz, cp, x, W2]}[what]
+
+    def penalty(double):
+        vs = [T.Parameter(a) for a in arrays]
+        if what in ("gelu_fused", "gelu"):
+            Wa, ba, Wb, xv = vs
+            h = T.linear(xv, Wa, ba, act="gelu") if what == "gelu_fused" else T.gelu(T.linear(xv, Wa, ba))
+            f = T.sum_all(T.mul(T.linear(h, Wb, T.Variable(b2, False)), T.Variable(c, False)))
+            wrt = xv
+        elif what == "softmax_ce":
+            Wa, ba, Wb, bb, xv = vs
+            f = T.softmax_cross_entropy(T.linear(T.tanh(T.linear(xv, Wa, ba)), Wb, bb), t)
+            wrt = xv
+        elif what == "embedding":
+            Ev, Wa, ba, Wb = vs
+            h = T.tanh(T.linear(T.embed_id(ids, Ev), Wa, ba))
+            f = T.sum_all(T.mul(T.linear(h, Wb, T.Variable(b2, False)), T.Variable(c, False)))
+            wrt = Ev
+        else:
+            Wa, ba, cv, xv, Wb = vs
+            cn, hn = T.lstm(cv, T.linear(xv, Wa, T.Variable(np.zeros(4 * hdim), False)), ba, twice_differentiable=True)
+            f = T.add(T.sum_all(T.mul(T.linear(hn, Wb, T.Variable(b2, False)), T.Variable(c, False))), T.sum_all(T.mul(cn, cn)))
+            wrt = xv
+        g, = T.grad([f], [wrt], enable_double_backprop=double)
+        return T.sum_all(T.mul(g, g)), vs
+
+    pen, vs = penalty(True)
+    pen.backward()
+    num = fd_grad(lambda: float(penalty(False)[0].array), arrays)
+    for v, g in zip(vs, num):
+        got = np.zeros_like(g) if v.grad is None else v.grad
+        np.testing.assert_allclose(got, g, rtol=5e-5, atol=2e-7)
+    assert any(np.any(v.grad) for v in vs if v.grad is not None)
+
+
+def test_lstm_without_the_flag_says_what_a_differentiable_backward_needs(F):
+    rng = np.random.default_rng(43)
+    cv, zv = T.Variable(rnd(rng, 2, 3)), T.Variable(rnd(rng, 2, 12))
+    _, h = T.lstm(cv, zv)
+    with pytest.raises(NotImplementedError, match="twice_differentiable"):
+        T.grad([T.sum_all(h)], [zv], enable_double_backprop=True)
+    g, = T.grad([T.sum_all(h)], [zv])                            # first order needs no flag
+    assert g.array.shape == (2, 12)
+
+
 def test_backward_with_double_backprop_keeps_the_graph_and_gives_grad_var(F):
     x = T.Variable(np.array([[0.5, -1.0]]))
     y = T.sum_all(T.mul(T.tanh(x), T.tanh(x)))
