@@ -243,6 +243,37 @@ chn_status chn_lstm_step_bwd(const chn_array *dz_next, const chn_array *U, const
                              const chn_array *dc_next, const chn_array *dz,
                              const chn_array *dc_prev, chn_stream stream);
 
+/* The forward pass of the recurrent layer over a whole sequence in ONE launch (Sec. 2.2's loop over time,
+ * Sec. 3.2's NStepLSTM): for t = 0 .. n_steps-1,
+ *   block t+1 of Hs, Cs = cell(zx block t + block t of Hs . Ut^T + bias, block t of Cs),  block t of gates.
+ * zx (n_steps*B, 4H) F32; Ut (4H, H) F32 or BF16; bias (4H) F32 or NULL; Hs ((n_steps+1)*B, H) of Ut's type
+ * and Cs ((n_steps+1)*B, H) F32 with block 0 holding the initial state (read) and blocks 1.. written;
+ * gates (n_steps*B, 4H) F32 or NULL.  All device, row-major with unit inner stride, rows of Hs and Ut on
+ * 16-byte boundaries.  Same arithmetic as n_steps calls of chn_lstm_step_fwd (fp32 sums on the matrix cores,
+ * the contraction cut in four; agrees with them within the product tolerance).
+ *
+ * The grid stays on the device for the whole sequence - (H/8) x ceil(B/64) workgroups, each holding its rows
+ * of Ut in LDS - and exchanges h between steps through device memory, so every workgroup must be resident at
+ * once: H % 8 == 0 (BF16: % 16), a row of h of at most 3072 bytes (H <= 768 F32, 1536 BF16) and no more
+ * workgroups than the device has compute units; otherwise CHN_ERR_SHAPE and the caller uses the per-step
+ * calls.  ws: chn_lstm_seq_workspace_bytes(B) bytes, 256-byte aligned, the library's until the work on
+ * `stream` is done.  A workgroup waits for the others a bounded number of polls (chn_lstm_seq_spin_limit;
+ * the default is worth seconds).  If a wait runs out - another kernel holds compute units the grid needs -
+ * every workgroup leaves, the outputs are incomplete, and the first 4 bytes of ws read 1 instead of 0 once
+ * the stream is synchronised: the caller checks that word and repeats the work with the per-step calls.
+ * Launch it on one stream at a time per device. */
+size_t chn_lstm_seq_workspace_bytes(int64_t batch);
+/* CHN_OK if chn_lstm_seq_fwd takes a batch of `batch` rows and `hidden` units of `dtype` (CHN_F32 / CHN_BF16)
+ * on the current device, else the status it would return (chn_last_error says why): ask before planning. */
+chn_status chn_lstm_seq_supported(int64_t batch, int64_t hidden, int dtype);
+chn_status chn_lstm_seq_fwd(const chn_array *zx, const chn_array *Ut, const chn_array *bias, const chn_array *Hs,
+                            const chn_array *Cs, const chn_array *gates, int64_t n_steps, void *ws, size_t ws_bytes,
+                            chn_stream stream);
+/* Number of polls after which a waiting workgroup of chn_lstm_seq_fwd gives up (process-wide, >= 0; the
+ * default is 2^20).  With 0 the first wait gives up without looking: tests use it to see the status word
+ * raised and the kernel end after its first step. */
+void chn_lstm_seq_spin_limit(int64_t polls);
+
 /* ---- softmax cross-entropy ------------------------------------------------------------------------
  * The classifier loss of the paper's MNIST example (Section "API Design"); textbook definition.
  * logits (N,C) F32 or BF16, row-major; labels (N,) I32 or I64.  Rows whose label equals

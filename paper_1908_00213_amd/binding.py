@@ -27,6 +27,7 @@ EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_reduce_axis_static", "chn_argmax_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
+           "chn_lstm_seq_workspace_bytes", "chn_lstm_seq_supported", "chn_lstm_seq_fwd", "chn_lstm_seq_spin_limit",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_bwd2", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan", "chn_gemm_plan_override",
@@ -92,6 +93,12 @@ def lib():
     L.chn_lstm_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, st]
     L.chn_lstm_step_fwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, AP, st]
     L.chn_lstm_step_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, AP, AP, st]
+    L.chn_lstm_seq_workspace_bytes.argtypes = [C.c_int64]
+    L.chn_lstm_seq_workspace_bytes.restype = C.c_size_t
+    L.chn_lstm_seq_supported.argtypes = [C.c_int64, C.c_int64, C.c_int]
+    L.chn_lstm_seq_fwd.argtypes = [AP, AP, AP, AP, AP, AP, C.c_int64, C.c_void_p, C.c_size_t, st]
+    L.chn_lstm_seq_spin_limit.argtypes = [C.c_int64]
+    L.chn_lstm_seq_spin_limit.restype = None
     L.chn_softmax_ce_workspace_bytes.argtypes = [C.c_int64]
     L.chn_softmax_ce_workspace_bytes.restype = C.c_size_t
     L.chn_softmax_ce_fwd.argtypes = [AP, AP, C.c_int64, AP, AP, AP, vp, C.c_size_t, st]
@@ -317,6 +324,31 @@ def lstm_step_bwd(dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev, stream
     _check(lib().chn_lstm_step_bwd(_ref(desc(dz_next)), _ref(desc(U)), _ref(desc(dh)), _ref(desc(gates)), _ref(desc(c_prev)),
                                    _ref(desc(c)), _ref(desc(dc_next)), _ref(desc(dz)), _ref(desc(dc_prev)),
                                    _stream() if stream is None else stream))
+
+
+def lstm_seq_workspace_bytes(batch):
+    return lib().chn_lstm_seq_workspace_bytes(int(batch))
+
+
+def lstm_seq_supported(batch, hidden, dtype):
+    """Whether lstm_seq_fwd takes this batch and hidden width (torch dtype) on the current device."""
+    return lib().chn_lstm_seq_supported(int(batch), int(hidden), _DTYPES[dtype]) == 0
+
+
+def lstm_seq_status(ws):
+    """The status word lstm_seq_fwd left in its workspace (synchronises): 0 = complete, 1 = a wait ran out."""
+    return int(ws[:4].view(torch.int32).item())
+
+
+def lstm_seq_fwd(zx, Ut, bias, Hs, Cs, gates, n_steps, ws, stream=None):
+    """All n_steps forward steps in one launch.  ws[0:4] reads 1 after synchronisation if a wait ran out."""
+    p, n = _ws(ws)
+    _check(lib().chn_lstm_seq_fwd(_ref(desc(zx)), _ref(desc(Ut)), _ref(desc(bias)), _ref(desc(Hs)), _ref(desc(Cs)),
+                                  _ref(desc(gates)), int(n_steps), p, n, _stream() if stream is None else stream))
+
+
+def lstm_seq_spin_limit(polls):
+    lib().chn_lstm_seq_spin_limit(int(polls))
 
 
 def softmax_ce_workspace_bytes(n_rows):

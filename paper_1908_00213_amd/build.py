@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libchn.so")
 
-SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "argmax.hip", "gemm.hip", "lstm.hip", "lstm_step.hip", "softmax_ce.hip",
+SOURCES = ["host.cpp", "user_kernel.cpp", "elementwise.hip", "reduce.hip", "argmax.hip", "gemm.hip", "lstm.hip", "lstm_step.hip", "lstm_seq.hip", "softmax_ce.hip",
            "sgd.hip", "adam.hip", "embed.hip"]
 
 # gemm_inst.hip is compiled once per (dtype, A layout, B layout): k = unit stride along K, m = along M/N

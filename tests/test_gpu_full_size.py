@@ -193,7 +193,7 @@ def test_config4_full_size_step_sampled():
     Hs, Cs, Z, G = (m.cpu().numpy() for m in (tr.Hs, tr.Cs, tr.Z, tr.G))
     Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
     # gate pre-activations x W + h U, sampled
-    assert tr.fused_step                       # the configuration the benchmark times: Z holds x W only
+    assert tr.fused_step and tr.whole_sequence and tr.sequence_complete()   # the configuration the benchmark times: Z holds x W only, one launch for the 35 forward steps
     ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
     ref = O.gemm_entries(X, P0["W"], ms, ns)
     S = O.gemm_entries(np.abs(X), np.abs(P0["W"]), ms, ns)
@@ -268,7 +268,7 @@ def test_config4_full_size_mixed_precision_sampled():
     X, Hs, Cs, Z, G = (host(m) for m in (tr.X, tr.Hs, tr.Cs, tr.Z, tr.G))
     assert np.array_equal(X, Pl0["E"][idf])
     Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
-    assert tr.fused_step
+    assert tr.fused_step and tr.whole_sequence and tr.sequence_complete()
     ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
     ref = O.gemm_entries(X, Pl0["W"], ms, ns)
     S = O.gemm_entries(np.abs(X), np.abs(Pl0["W"]), ms, ns)
