@@ -220,7 +220,7 @@ def bench_lstm(torch, B, steps_mod, w, timer, steps, warmup, graph=False, lowp=F
     if not tr.sequence_complete():
         raise SystemExit("bench.py: a wait of the whole-sequence recurrent kernel ran out; the timing of workload 4 is void")
     return {"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "tokens_per_s": w.bptt * w.batch / s, "loss": float(tr.loss.cpu()),
-            "forward_steps_in_one_launch": bool(tr.whole_sequence),
+            "forward_steps_in_one_launch": bool(tr.whole_sequence), "backward_steps_in_one_launch": bool(tr.whole_sequence_bwd),
             "TFLOP/s": w.flops_per_step() / s / 1e12, "frac_mfma_peak_f32": w.flops_per_step() / s / 1e12 / MFMA_PEAK_TFLOPS["f32"],
             "launch_calls_per_step": tr.n_launch_calls(ids, tg)}
 

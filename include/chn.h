@@ -269,7 +269,29 @@ chn_status chn_lstm_seq_supported(int64_t batch, int64_t hidden, int dtype);
 chn_status chn_lstm_seq_fwd(const chn_array *zx, const chn_array *Ut, const chn_array *bias, const chn_array *Hs,
                             const chn_array *Cs, const chn_array *gates, int64_t n_steps, void *ws, size_t ws_bytes,
                             chn_stream stream);
-/* Number of polls after which a waiting workgroup of chn_lstm_seq_fwd gives up (process-wide, >= 0; the
+/* Back-propagation through time over the whole sequence in ONE launch (Sec. 2.2: the backward walk over the
+ * graph the loop over time built), last step first: for t = n_steps-1 .. 0,
+ *   block t of dHs <- block t of dHs + (block t+1 of dZ) . U^T        (nothing added for the last step)
+ *   block t of dZ, dc <- cell backward(block t of gates, blocks t and t+1 of Cs, block t of dHs, dc)
+ * starting from dc = dc_last (or 0 if NULL); dc0 receives the gradient of the initial cell state.
+ * U (H, 4H) F32 or BF16; dHs (n_steps*B, H) and dZ (n_steps*B, 4H) of U's type (dHs in: the gradient reaching
+ * each h_t from above; out: the total); gates (n_steps*B, 4H), Cs ((n_steps+1)*B, H), dc_last, dc0 (B, H) F32.
+ * All device, row-major, unit inner stride; rows of U on 16-byte, of dZ on 8-byte boundaries.  Same arithmetic
+ * as the chain of chn_lstm_step_bwd calls: in mixed precision the cell sees the bf16-rounded total dh and the
+ * product reads the bf16-rounded dz; the fp32 sums run in another order (64 gate columns per workgroup on the
+ * matrix cores, then the H/16 partial sums in workgroup order).
+ *
+ * Resident grid of (H/16) x ceil(B/32) workgroups, each with its columns of U in registers: H % 16 == 0,
+ * H <= 768 (F32) / 1536 (BF16), no more workgroups than compute units; otherwise CHN_ERR_SHAPE
+ * (chn_lstm_seq_bwd_supported asks beforehand).  ws: chn_lstm_seq_bwd_workspace_bytes(B, H) bytes (the partial
+ * sums the workgroups exchange: 2 * ceil(B/32) * (H/16)^2 * 2 KiB), 256-byte aligned.  Waits, the status word
+ * in the first 4 bytes of ws and chn_lstm_seq_spin_limit as for chn_lstm_seq_fwd. */
+chn_status chn_lstm_seq_bwd_supported(int64_t batch, int64_t hidden, int dtype);
+size_t chn_lstm_seq_bwd_workspace_bytes(int64_t batch, int64_t hidden);
+chn_status chn_lstm_seq_bwd(const chn_array *U, const chn_array *dHs, const chn_array *gates, const chn_array *Cs,
+                            const chn_array *dc_last, const chn_array *dZ, const chn_array *dc0, int64_t n_steps,
+                            void *ws, size_t ws_bytes, chn_stream stream);
+/* Number of polls after which a waiting workgroup of chn_lstm_seq_fwd / _bwd gives up (process-wide, >= 0; the
  * default is 2^20).  With 0 the first wait gives up without looking: tests use it to see the status word
  * raised and the kernel end after its first step. */
 void chn_lstm_seq_spin_limit(int64_t polls);

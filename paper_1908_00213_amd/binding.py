@@ -27,7 +27,8 @@ EPI = {n: i for i, n in enumerate(EPILOGUES)}
 
 EXPORTS = ["chn_elementwise_broadcast", "chn_reduce_axis_workspace_bytes", "chn_reduce_axis", "chn_reduce_axis_static", "chn_argmax_axis",
            "chn_gemm_workspace_bytes", "chn_gemm", "chn_lstm_fwd", "chn_lstm_bwd", "chn_lstm_step_fwd", "chn_lstm_step_bwd",
-           "chn_lstm_seq_workspace_bytes", "chn_lstm_seq_supported", "chn_lstm_seq_fwd", "chn_lstm_seq_spin_limit",
+           "chn_lstm_seq_workspace_bytes", "chn_lstm_seq_supported", "chn_lstm_seq_fwd",
+           "chn_lstm_seq_bwd_supported", "chn_lstm_seq_bwd_workspace_bytes", "chn_lstm_seq_bwd", "chn_lstm_seq_spin_limit",
            "chn_softmax_ce_workspace_bytes", "chn_softmax_ce_fwd", "chn_softmax_ce_bwd", "chn_softmax_ce_bwd2", "chn_softmax_ce_fwd_bwd",
            "chn_sgd_update", "chn_sgd_update_multi", "chn_adam_update_multi", "chn_embed_fwd", "chn_embed_bwd",
            "chn_status_string", "chn_last_error", "chn_version", "chn_elementwise_plan", "chn_gemm_plan", "chn_gemm_plan_override",
@@ -97,6 +98,10 @@ def lib():
     L.chn_lstm_seq_workspace_bytes.restype = C.c_size_t
     L.chn_lstm_seq_supported.argtypes = [C.c_int64, C.c_int64, C.c_int]
     L.chn_lstm_seq_fwd.argtypes = [AP, AP, AP, AP, AP, AP, C.c_int64, C.c_void_p, C.c_size_t, st]
+    L.chn_lstm_seq_bwd_supported.argtypes = [C.c_int64, C.c_int64, C.c_int]
+    L.chn_lstm_seq_bwd_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
+    L.chn_lstm_seq_bwd_workspace_bytes.restype = C.c_size_t
+    L.chn_lstm_seq_bwd.argtypes = [AP, AP, AP, AP, AP, AP, AP, C.c_int64, C.c_void_p, C.c_size_t, st]
     L.chn_lstm_seq_spin_limit.argtypes = [C.c_int64]
     L.chn_lstm_seq_spin_limit.restype = None
     L.chn_softmax_ce_workspace_bytes.argtypes = [C.c_int64]
@@ -345,6 +350,21 @@ def lstm_seq_fwd(zx, Ut, bias, Hs, Cs, gates, n_steps, ws, stream=None):
     p, n = _ws(ws)
     _check(lib().chn_lstm_seq_fwd(_ref(desc(zx)), _ref(desc(Ut)), _ref(desc(bias)), _ref(desc(Hs)), _ref(desc(Cs)),
                                   _ref(desc(gates)), int(n_steps), p, n, _stream() if stream is None else stream))
+
+
+def lstm_seq_bwd_supported(batch, hidden, dtype):
+    return lib().chn_lstm_seq_bwd_supported(int(batch), int(hidden), _DTYPES[dtype]) == 0
+
+
+def lstm_seq_bwd_workspace_bytes(batch, hidden):
+    return lib().chn_lstm_seq_bwd_workspace_bytes(int(batch), int(hidden))
+
+
+def lstm_seq_bwd(U, dHs, gates, Cs, dc_last, dZ, dc0, n_steps, ws, stream=None):
+    """Back-propagation through all n_steps steps in one launch; status word in ws as for lstm_seq_fwd."""
+    p, n = _ws(ws)
+    _check(lib().chn_lstm_seq_bwd(_ref(desc(U)), _ref(desc(dHs)), _ref(desc(gates)), _ref(desc(Cs)), _ref(desc(dc_last)),
+                                  _ref(desc(dZ)), _ref(desc(dc0)), int(n_steps), p, n, _stream() if stream is None else stream))
 
 
 def lstm_seq_spin_limit(polls):

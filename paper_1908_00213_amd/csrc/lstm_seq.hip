@@ -19,6 +19,7 @@
 // sees the status word in its next poll and leaves too.  The kernel always ends; the caller checks the status
 // word after synchronising (chn_lstm_seq_status) and falls back to the per-step calls if it is set.
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 
@@ -251,6 +252,213 @@ __global__ __launch_bounds__(kThreads) void lstm_seq_fwd_kernel(SeqArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Back-propagation through time in one launch.  dh_t = (gradient from above) + dz_{t+1} U^T is a contraction over
+// the 4H gate columns; cut along THAT axis, a workgroup that owns 16 hidden units (64 gate columns) for 32 batch
+// rows multiplies the dz it has just produced itself - no operand to fetch - with its 64 columns of U, which it
+// keeps in REGISTERS for the whole sequence (the matrix cores take them from there: nothing of U is read again
+// after the first step, not even from LDS).  What comes out is a partial dh for all H units; the H / 16
+// workgroups of a batch block exchange those through device memory (each writes one 2 KB block per receiver,
+// each receiver reads its H / 16 blocks back to back and adds them in a fixed order) with the same agent-scope
+// stores, arrival counter and bounded wait as the forward kernel, then run the cell's backward on their own units.
+struct SeqBwdArgs {
+  int64_t B, H;
+  int n_steps, nub, spin_limit;
+  const void *U; int64_t u_pitch;
+  void *dHs; int64_t dh_pitch;
+  const float *gates; int64_t g_pitch;
+  const float *Cs; int64_t c_pitch;
+  const float *dc_last; int64_t dcl_pitch;
+  void *dZ; int64_t dz_pitch;
+  float *dc0; int64_t dc0_pitch;
+  float *xbuf;               // [2][batch blocks][receiver][sender][2][32 rows][8 units]
+  unsigned *counters, *status;
+};
+
+constexpr int kBwdRows = 32, kBwdUnits = 16, kBwdCols = 4 * kBwdUnits;
+constexpr int kBlockFloats = kBwdRows * kBwdUnits;     // one sender -> receiver block
+constexpr int kBatchLoads = 48;                        // blocks a thread has in flight at once
+
+// grid: (H / 16, ceil(B / 32)).  MT: the most 32-unit row tiles of U a wave holds (tiles wave, wave + 4, ...).
+template <typename T, int MT>
+__global__ __launch_bounds__(kThreads) void lstm_seq_bwd_kernel(SeqBwdArgs a) {
+  constexpr int NI = sizeof(T) == 2 ? 4 : 8;           // 16-byte pieces along the 64 gate columns per lane half
+  constexpr int kTileRow = kBwdCols * (int)sizeof(T);  // bytes of one row of the dz tile
+  constexpr int kSwz = kTileRow / 16 - 1;
+  __shared__ __attribute__((aligned(16))) char tile[kBwdRows * kTileRow];
+  __shared__ int give_up;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int r = lane & 31, q = lane >> 5;
+  const int64_t j0 = (int64_t)blockIdx.x * kBwdUnits, b0 = (int64_t)blockIdx.y * kBwdRows;
+  const int n_mt = (int)((a.H + 31) / 32);
+  const int T_ = a.n_steps;
+
+  // ---- this wave's rows of U (all H units, this workgroup's 64 gate columns), once, into registers
+  uint4 ua[MT][NI];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const int mt = wave + 4 * m;
+    int64_t row = (int64_t)mt * 32 + r;
+    if (row >= a.H) row = a.H - 1;
+    const T *ur = static_cast<const T *>(a.U) + row * a.u_pitch;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      // piece i of lane half q covers gate columns c = (16 / sizeof(T)) * (2 i + q) ..: gate c / 16, unit c % 16
+      const int c = (16 / (int)sizeof(T)) * (2 * i + q);
+      ua[m][i] = *reinterpret_cast<const uint4 *>(ur + (int64_t)(c >> 4) * a.H + j0 + (c & 15));   // tiles past the last repeat its last row; never used
+    }
+  }
+  // nothing of this is in flight when the step loop starts: no wait on these registers inside it
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  asm volatile("" ::: "memory");
+
+  // ---- this thread's part of the cell: one batch row, two neighbouring hidden units
+  const int crow = threadIdx.x >> 3, cp2 = threadIdx.x & 7;
+  const int64_t b = b0 + crow, j = j0 + 2 * cp2;
+  const bool live = b < a.B;
+  float dc[2] = {0.0f, 0.0f};
+  if (live && a.dc_last) { dc[0] = a.dc_last[b * a.dcl_pitch + j]; dc[1] = a.dc_last[b * a.dcl_pitch + j + 1]; }
+  const int64_t blocks_per_bb = (int64_t)a.nub * a.nub;
+  // the exchange buffer as a buffer resource: stores carry a cache policy and are range-checked by the hardware
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(a.xbuf, 0, (int)(2 * gridDim.y * blocks_per_bb * kBlockFloats * 4), 0x00020000);
+  if (threadIdx.x == 0) give_up = 0;
+
+#pragma unroll 1
+  for (int step = 0; step < T_; ++step) {
+    const int t = T_ - 1 - step;
+    // what the cell's backward reads, fetched before the exchange
+    // (raw bits: nothing here is looked at before the exchange is over, so nothing waits for it earlier)
+    float gt[4][2], cc[2], cprev[2], d[2];
+    typedef typename std::conditional<sizeof(T) == 2, unsigned, float2>::type Pair;
+    Pair d_raw{};
+#pragma unroll
+    for (int e = 0; e < 2; ++e) { cc[e] = cprev[e] = 0.0f; gt[0][e] = gt[1][e] = gt[2][e] = gt[3][e] = 0.0f; }
+    T *dhr = static_cast<T *>(a.dHs) + ((int64_t)t * a.B + b) * a.dh_pitch + j;
+    if (live) {
+      const float *gr = a.gates + ((int64_t)t * a.B + b) * a.g_pitch;
+      const float *cr = a.Cs + ((int64_t)(t + 1) * a.B + b) * a.c_pitch + j, *pr = a.Cs + ((int64_t)t * a.B + b) * a.c_pitch + j;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) gt[g][e] = gr[g * a.H + j + e];
+        cc[e] = cr[e]; cprev[e] = pr[e];
+      }
+      d_raw = *reinterpret_cast<const Pair *>(dhr);
+    }
+    d[0] = d[1] = 0.0f;
+    if (step > 0) {
+      const int xoff = (int)(((int64_t)(step & 1) * gridDim.y + blockIdx.y) * blocks_per_bb * kBlockFloats * 4);   // bytes; the exchange stays under 2 GiB
+      const float *xb = a.xbuf + xoff / 4;
+      // ---- partial dh of all units from this workgroup's dz of step t + 1 (in the LDS tile)
+      uint4 bf[NI];
+#pragma unroll
+      for (int i = 0; i < NI; ++i) bf[i] = *reinterpret_cast<const uint4 *>(tile + r * kTileRow + (((2 * i + q) ^ (r & kSwz)) << 4));
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        const int mt = wave + 4 * m;
+        if (mt < n_mt) {
+          floatx16 acc;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+          for (int i = 0; i < NI; ++i) mma_piece<T>(acc, ua[m][i], bf[i]);
+          // rows of the result = units 32 mt + 8 (v / 4) + 4 q + v % 4, columns = batch rows r
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const int dest = 2 * mt + (vg >> 1);
+            if (dest < a.nub) {
+              // 16 bytes per lane, 1 KB back to back per instruction, written through to device memory (sc0 sc1)
+              const int off = xoff + (dest * a.nub + (int)blockIdx.x) * (kBlockFloats * 4) + (vg & 1) * (kBwdRows * 32) + r * 32 + q * 16;
+              const chn_f32x4 val = {acc[4 * vg], acc[4 * vg + 1], acc[4 * vg + 2], acc[4 * vg + 3]};
+              __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(chn_u32x4, val), xres, off, 0, kCpolAgent);
+            }
+          }
+        }
+      }
+      // ---- publish, then wait for the other workgroups of this batch block
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (threadIdx.x == 0) __hip_atomic_fetch_add(a.counters + blockIdx.y, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (wave == 0) {
+        const unsigned want = (unsigned)step * (unsigned)a.nub;
+        bool ok = false;
+#pragma unroll 1
+        for (int spins = 0; spins < a.spin_limit; ++spins) {
+          const unsigned seen = __hip_atomic_load(a.counters + blockIdx.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const unsigned st = __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = seen >= want;
+          if (ok || st != 0u) break;
+          __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok && lane == 0) {
+          give_up = 1;
+          __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+      __syncthreads();
+      if (give_up) break;
+      // ---- the partial sums addressed to this workgroup, one block per sender, added in sender order
+      const float *mine = xb + (int64_t)blockIdx.x * a.nub * kBlockFloats + (cp2 >> 2) * (kBwdRows * 8) + crow * 8 + 2 * (cp2 & 3);
+      float rec0 = 0.0f, rec1 = 0.0f;
+#pragma unroll 1
+      for (int s0 = 0; s0 < a.nub; s0 += kBatchLoads) {
+        unsigned long long v[kBatchLoads];
+#pragma unroll
+        for (int s = 0; s < kBatchLoads; ++s)
+          v[s] = s0 + s < a.nub ? __hip_atomic_load(reinterpret_cast<const unsigned long long *>(mine + (int64_t)(s0 + s) * kBlockFloats),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                : 0ull;
+#pragma unroll
+        for (int s = 0; s < kBatchLoads; ++s) {
+          rec0 += __uint_as_float((unsigned)v[s]);
+          rec1 += __uint_as_float((unsigned)(v[s] >> 32));
+        }
+      }
+      d[0] = rec0; d[1] = rec1;
+    }
+    if constexpr (sizeof(T) == 2) { d[0] += bf16_to_f32((bf16_raw)(d_raw & 0xFFFFu)); d[1] += bf16_to_f32((bf16_raw)(d_raw >> 16)); }
+    else { d[0] += d_raw.x; d[1] += d_raw.y; }
+    if (step > 0) {
+      // the total is what the cell sees and what is stored: in mixed precision that is the bf16 value
+      if (live) { Elem<T>::store(dhr, d[0]); Elem<T>::store(dhr + 1, d[1]); }
+      if constexpr (sizeof(T) == 2) { d[0] = bf16_to_f32(f32_to_bf16(d[0])); d[1] = bf16_to_f32(f32_to_bf16(d[1])); }
+    }
+    // ---- the cell's backward; dz goes to memory and, as the operand of the next step's product, into the tile
+    float dzv[4][2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const float i = gt[0][e], f = gt[1][e], g = gt[2][e], o = gt[3][e];
+      const float tc = tanhf(cc[e]);
+      const float d_o = d[e] * tc;
+      const float dcv = dc[e] + d[e] * o * (1.0f - tc * tc);
+      const float di = dcv * g, dg = dcv * i, df = dcv * cprev[e];
+      dc[e] = dcv * f;
+      dzv[0][e] = di * i * (1.0f - i);
+      dzv[1][e] = df * f * (1.0f - f);
+      dzv[2][e] = dg * (1.0f - g * g);
+      dzv[3][e] = d_o * o * (1.0f - o);
+    }
+    T *dzr = static_cast<T *>(a.dZ) + ((int64_t)t * a.B + b) * a.dz_pitch + j;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int c = g * kBwdUnits + 2 * cp2;               // column of the tile; c and c + 1 share a 16-byte piece
+      constexpr int per = 16 / (int)sizeof(T);
+      char *pt = tile + crow * kTileRow + (((c / per) ^ (crow & kSwz)) << 4) + (c % per) * (int)sizeof(T);
+      if constexpr (sizeof(T) == 2) {
+        const unsigned bits = live ? (unsigned)f32_to_bf16(dzv[g][0]) | ((unsigned)f32_to_bf16(dzv[g][1]) << 16) : 0u;
+        *reinterpret_cast<unsigned *>(pt) = bits;
+        if (live) *reinterpret_cast<unsigned *>(dzr + g * a.H) = bits;
+      } else {
+        const float2 v = live ? float2{dzv[g][0], dzv[g][1]} : float2{0.0f, 0.0f};
+        *reinterpret_cast<float2 *>(pt) = v;
+        if (live) *reinterpret_cast<float2 *>(dzr + g * a.H) = v;
+      }
+    }
+    __syncthreads();
+  }
+  if (live && !give_up) { a.dc0[b * a.dc0_pitch + j] = dc[0]; a.dc0[b * a.dc0_pitch + j + 1] = dc[1]; }
+}
+
 std::atomic<int> g_spin_limit{1 << 20};
 
 chn_status view2(const chn_array *x, const char *name, bool out, int64_t rows, int64_t cols, int want_dtype, bool operand, int64_t *pitch) {
@@ -284,6 +492,29 @@ chn_status fits(int64_t B, int64_t H, int dtype) {
     return fail(CHN_ERR_SHAPE, "lstm_seq: %lld workgroups needed, the device has %d compute units (use the per-step calls)", (long long)need, cus);
   return CHN_OK;
 }
+
+// What the backward grid can hold: the tiles of U in registers, every workgroup resident.
+chn_status fits_bwd(int64_t B, int64_t H, int dtype) {
+  if (dtype != CHN_F32 && dtype != CHN_BF16) return fail(CHN_ERR_DTYPE, "lstm_seq_bwd: U and the gradients must be F32 or BF16");
+  if (B < 0 || H < 0) return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: negative extent");
+  if (H % kBwdUnits) return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: the hidden width %lld is not a multiple of %d", (long long)H, kBwdUnits);
+  const int64_t widest = dtype == CHN_F32 ? 768 : 1536;
+  if (H > widest)
+    return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: hidden width %lld; the registers hold the rows of U up to %lld (use the per-step calls)", (long long)H, (long long)widest);
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return fail(CHN_ERR_LAUNCH, "lstm_seq_bwd: cannot ask the device for its number of compute units");
+  const int64_t need = ((B + kBwdRows - 1) / kBwdRows) * (H / kBwdUnits);
+  if (need > cus)
+    return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: %lld workgroups needed, the device has %d compute units (use the per-step calls)", (long long)need, cus);
+  return CHN_OK;
+}
+
+size_t bwd_exchange_bytes(int64_t B, int64_t H) {
+  const int64_t nbb = (B + kBwdRows - 1) / kBwdRows, nub = H / kBwdUnits;
+  return (size_t)(2 * nbb * nub * nub) * kBlockFloats * sizeof(float);
+}
+size_t bwd_counter_bytes(int64_t B) { return (size_t)((((B + kBwdRows - 1) / kBwdRows) * sizeof(unsigned) + 255) / 256 * 256); }
 
 }  // namespace
 }  // namespace chn
@@ -344,6 +575,63 @@ chn_status chn_lstm_seq_fwd(const chn_array *zx, const chn_array *Ut, const chn_
   if (t == CHN_BF16) hipLaunchKernelGGL(lstm_seq_fwd_kernel<bf16_raw>, grid, dim3(kThreads), 0, st, a);
   else hipLaunchKernelGGL(lstm_seq_fwd_kernel<float>, grid, dim3(kThreads), 0, st, a);
   return check_launch("lstm_seq_fwd");
+}
+
+chn_status chn_lstm_seq_bwd_supported(int64_t batch, int64_t hidden, int dtype) { return chn::fits_bwd(batch, hidden, dtype); }
+
+size_t chn_lstm_seq_bwd_workspace_bytes(int64_t batch, int64_t hidden) {
+  if (batch <= 0 || hidden <= 0 || hidden % chn::kBwdUnits) return 0;
+  return 256 + chn::bwd_counter_bytes(batch) + chn::bwd_exchange_bytes(batch, hidden);
+}
+
+chn_status chn_lstm_seq_bwd(const chn_array *U, const chn_array *dHs, const chn_array *gates, const chn_array *Cs,
+                            const chn_array *dc_last, const chn_array *dZ, const chn_array *dc0, int64_t n_steps, void *ws,
+                            size_t ws_bytes, chn_stream stream) {
+  using namespace chn;
+  CHN_TRY(validate(Cs, "Cs", false));
+  if (Cs->ndim != 2) return fail(CHN_ERR_NDIM, "lstm_seq_bwd: Cs must be 2-d");
+  if (!U || !dHs || !dZ) return fail(CHN_ERR_NULL, "lstm_seq_bwd: U, dHs or dZ is NULL");
+  if (n_steps < 0 || n_steps > (1 << 20)) return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: bad number of steps %lld", (long long)n_steps);
+  SeqBwdArgs a{};
+  a.H = Cs->shape[1];
+  const int64_t rows = Cs->shape[0];
+  if (rows % (n_steps + 1)) return fail(CHN_ERR_SHAPE, "lstm_seq_bwd: Cs has %lld rows, not a multiple of steps + 1 = %lld", (long long)rows, (long long)(n_steps + 1));
+  a.B = rows / (n_steps + 1);
+  const int t = U->dtype;
+  CHN_TRY(fits_bwd(a.B, a.H, t));
+  const int64_t n = n_steps * a.B;
+  CHN_TRY(view2(Cs, "Cs", false, rows, a.H, CHN_F32, false, &a.c_pitch));
+  CHN_TRY(view2(U, "U", false, a.H, 4 * a.H, t, true, &a.u_pitch));
+  CHN_TRY(view2(dHs, "dHs", true, n, a.H, t, false, &a.dh_pitch));
+  CHN_TRY(view2(gates, "gates", false, n, 4 * a.H, CHN_F32, false, &a.g_pitch));
+  CHN_TRY(view2(dZ, "dZ", true, n, 4 * a.H, t, false, &a.dz_pitch));
+  CHN_TRY(view2(dc0, "dc0", true, a.B, a.H, CHN_F32, false, &a.dc0_pitch));
+  if (dc_last) CHN_TRY(view2(dc_last, "dc_last", false, a.B, a.H, CHN_F32, false, &a.dcl_pitch));
+  if (n_steps == 0 || a.B * a.H == 0) return CHN_OK;
+  // dz leaves in pairs of neighbouring units (8 bytes F32, 4 bytes BF16)
+  if (reinterpret_cast<uintptr_t>(dZ->data) % 8 || (a.dz_pitch * dtype_size(t)) % 8)
+    return fail(CHN_ERR_STRIDE, "lstm_seq_bwd: rows of dZ must start on 8-byte boundaries");
+  const size_t need = chn_lstm_seq_bwd_workspace_bytes(a.B, a.H);
+  CHN_TRY(check_ws(ws, ws_bytes, need, "lstm_seq_bwd"));
+  const int64_t nbb = (a.B + kBwdRows - 1) / kBwdRows, nub = a.H / kBwdUnits;
+  a.n_steps = (int)n_steps; a.nub = (int)nub; a.spin_limit = g_spin_limit.load();
+  a.U = U->data;
+  a.dHs = dHs->data;
+  a.gates = static_cast<const float *>(gates->data);
+  a.Cs = static_cast<const float *>(Cs->data);
+  a.dc_last = dc_last ? static_cast<const float *>(dc_last->data) : nullptr;
+  a.dZ = dZ->data;
+  a.dc0 = static_cast<float *>(dc0->data);
+  a.status = static_cast<unsigned *>(ws);
+  a.counters = reinterpret_cast<unsigned *>(static_cast<char *>(ws) + 256);
+  a.xbuf = reinterpret_cast<float *>(static_cast<char *>(ws) + 256 + bwd_counter_bytes(a.B));
+  hipStream_t st = as_stream(stream);
+  hipLaunchKernelGGL(seq_clear_kernel, dim3(1), dim3(64), 0, st, a.status, (int)(64 + nbb));
+  CHN_TRY(check_launch("lstm_seq_bwd clear"));
+  const dim3 grid((unsigned)nub, (unsigned)nbb);
+  if (t == CHN_BF16) hipLaunchKernelGGL((lstm_seq_bwd_kernel<bf16_raw, 12>), grid, dim3(kThreads), 0, st, a);
+  else hipLaunchKernelGGL((lstm_seq_bwd_kernel<float, 6>), grid, dim3(kThreads), 0, st, a);
+  return check_launch("lstm_seq_bwd");
 }
 
 }  // extern "C"

@@ -214,13 +214,17 @@ class LSTMTrainer:
     every product accumulates in fp32.
     """
 
-    def __init__(self, P, T, Bn, lr=0.01, lowp=False, fused_step=True, whole_sequence=None):
+    def __init__(self, P, T, Bn, lr=0.01, lowp=False, fused_step=True, whole_sequence=None, whole_sequence_bwd=None):
         """whole_sequence: the T forward steps are ONE launch (chn_lstm_seq_fwd: the grid stays on the device,
         each workgroup keeps its rows of the recurrent matrix in LDS and the workgroups exchange h through
         device memory between steps).  None = wherever the library takes the shape (fused_step only).
         Measured on workload 4: 12.9 us instead of 14.3 us per step in fp32, 6.7 instead of 8.0 us in
-        mixed precision.  The kernel's waits are bounded; `sequence_complete()` tells whether one ran out
-        (then the step's results and the parameters it updated are invalid).
+        mixed precision.  In fp32 the T backward steps are one launch too (chn_lstm_seq_bwd: 14.4 us per
+        step instead of the 41 us of product, partial-sum kernel and cell kernel); in mixed precision the
+        per-step fused call (11.6 us) is as fast as the resident grid's exchange of partial sums (11.9 us)
+        and stays.  `whole_sequence_bwd` overrides that choice.  The kernels' waits are bounded;
+        `sequence_complete()` tells whether one ran out (then the step's results and the parameters it
+        updated are invalid).
 
         fused_step: a time step is one launch (chn_lstm_step_fwd / _bwd: recurrent product and cell
         together) instead of product, partial-sum kernel and cell kernel; `Z` then holds the input part
@@ -259,6 +263,11 @@ class LSTMTrainer:
             raise ValueError("LSTMTrainer: the whole-sequence kernel does not take batch %d, hidden %d: %s" % (Bn, Hp, B.lib().chn_last_error().decode()))
         self.whole_sequence = fits if whole_sequence is None else bool(whole_sequence)
         self.ws_seq = torch.zeros(B.lstm_seq_workspace_bytes(Bn), dtype=torch.uint8, device="cuda") if self.whole_sequence else None
+        fits = fused_step and B.lstm_seq_bwd_supported(Bn, Hp, adt)
+        if whole_sequence_bwd and not fits:
+            raise ValueError("LSTMTrainer: the whole-sequence backward kernel does not take batch %d, hidden %d: %s" % (Bn, Hp, B.lib().chn_last_error().decode()))
+        self.whole_sequence_bwd = (fits and not lowp and self.whole_sequence) if whole_sequence_bwd is None else bool(whole_sequence_bwd)
+        self.ws_seq_bwd = torch.zeros(B.lstm_seq_bwd_workspace_bytes(Bn, Hp), dtype=torch.uint8, device="cuda") if self.whole_sequence_bwd else None
         # fp32: the two backward products of the output layer read one operand along its strided
         # dimension, which for fp32 goes through registers instead of straight to LDS; a transposed
         # copy of that operand (10-12 us each) saves 50-60 us per product
@@ -344,7 +353,10 @@ class LSTMTrainer:
         else:
             p.add(L.chn_elementwise_broadcast, B.OP["copy"], 1, p.ptrs([Pl["W_out"].t()]), p.d(self._WoT), None, 0)
             _gemm(p, L, dlog, self._WoT.t(), self._dHs)
-        for t in range(T - 1, -1, -1):
+        if self.whole_sequence_bwd:                                             # all T steps, one resident grid
+            sp, sn = p.ws(self.ws_seq_bwd)
+            p.add(L.chn_lstm_seq_bwd, p.d(Pl["U"]), p.d(self._dHs), p.d(self._G), p.d(self._Cs), None, p.d(self._dZ), p.d(self._dc[0]), T, sp, sn)
+        for t in range(-1 if self.whole_sequence_bwd else T - 1, -1, -1):
             dc_next = None if t == T - 1 else self._dc[(t + 1) & 1]
             if self.fused_step and self.lowp:                     # dh_t += dz_{t+1} U^T, then the cell backward
                 dz_next = None if t == T - 1 else blk(self._dZ, t + 1)
@@ -378,7 +390,7 @@ class LSTMTrainer:
 
     def sequence_complete(self):
         """Synchronises; False if a bounded wait of the whole-sequence kernel ran out in the last step."""
-        return self.ws_seq is None or B.lstm_seq_status(self.ws_seq) == 0
+        return all(w is None or B.lstm_seq_status(w) == 0 for w in (self.ws_seq, self.ws_seq_bwd))
 
     def n_launch_calls(self, ids, targets):
         self.step(ids, targets)

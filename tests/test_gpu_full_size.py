@@ -193,7 +193,8 @@ def test_config4_full_size_step_sampled():
     Hs, Cs, Z, G = (m.cpu().numpy() for m in (tr.Hs, tr.Cs, tr.Z, tr.G))
     Hprev, Hall = Hs[:T * Bn], Hs[Bn:]
     # gate pre-activations x W + h U, sampled
-    assert tr.fused_step and tr.whole_sequence and tr.sequence_complete()   # the configuration the benchmark times: Z holds x W only, one launch for the 35 forward steps
+    # the configuration the benchmark times: Z holds x W only, one launch for the 35 forward steps, one for the 35 backward steps
+    assert tr.fused_step and tr.whole_sequence and tr.whole_sequence_bwd and tr.sequence_complete()
     ms, ns = RNG.integers(0, T * Bn, 256), RNG.integers(0, 4 * H, 256)
     ref = O.gemm_entries(X, P0["W"], ms, ns)
     S = O.gemm_entries(np.abs(X), np.abs(P0["W"]), ms, ns)

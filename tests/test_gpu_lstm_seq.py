@@ -6,7 +6,7 @@ import torch
 
 from oracle import oracle as O
 from paper_1908_00213_amd import binding as B
-from tests.util import TOL_BF16, TOL_SUM, bf16r, check, dev, empty, host, ws
+from tests.util import TOL_BF16, TOL_EW, TOL_SUM, bf16r, check, dev, empty, host, ws
 
 pytestmark = pytest.mark.gpu
 
@@ -129,3 +129,101 @@ def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_status_word():
     Hs, Cs, gates, work = run(zx, bias, h0, c0, U, T, dt, Hs, Cs, gates, work)
     assert status_word(work) == 0
     check_against_oracle(zx, bias, U, T, dt, Hs, Cs, gates)
+
+
+# ------------------------------------------------------------------------------------ backward through time
+BWD_CASES = [(128, 672, 35, "f32"), (128, 672, 35, "bf16"),  # the language-model workload: 42 x 4 workgroups
+             (40, 48, 4, "f32"), (5, 16, 3, "f32"),          # ragged batch block, a partial 32-unit tile; one workgroup
+             (33, 144, 5, "bf16"), (200, 256, 3, "f32"),
+             (96, 768, 2, "f32"), (32, 1536, 2, "bf16")]     # the widest U the registers hold (bf16: two batches of partial sums)
+
+
+def bwd_inputs(Bn, H, T, dt, seed):
+    rng = np.random.default_rng(seed)
+    q = (lambda a: a) if dt == "f32" else bf16r
+    u = lambda shape, lo, hi: rng.uniform(lo, hi, size=shape).astype(np.float32)
+    s = 1.5 / np.sqrt(H)
+    gates = np.concatenate([u((T * Bn, 2 * H), 0.05, 0.95), u((T * Bn, H), -0.95, 0.95), u((T * Bn, H), 0.05, 0.95)], axis=1)
+    return q(u((H, 4 * H), -s, s)), q(u((T * Bn, H), -1, 1)), gates, u(((T + 1) * Bn, H), -1.5, 1.5), u((Bn, H), -1, 1)
+
+
+def run_bwd(U, dh_in, gates, Cs, dc_last, T, dt, bufs=None):
+    Bn, H = Cs.shape[0] // (T + 1), Cs.shape[1]
+    dHs, dZ, dc0, work = bufs or (empty((T * Bn, H), dt), empty((T * Bn, 4 * H), dt), empty((Bn, H)),
+                                  ws(B.lstm_seq_bwd_workspace_bytes(Bn, H)))
+    dHs.copy_(dev(dh_in, dt))
+    print("lstm_seq_bwd B=%d H=%d T=%d %s" % (Bn, H, T, dt), flush=True)
+    B.lstm_seq_bwd(dev(U, dt), dHs, dev(gates), dev(Cs), None if dc_last is None else dev(dc_last), dZ, dc0, T, work)
+    torch.cuda.synchronize()
+    return dHs, dZ, dc0, work
+
+
+def check_bwd_against_oracle(U, dh_in, gates, Cs, dc_last, T, dt, dHs, dZ, dc0):
+    """Last step first; the product of every step from the dz the GPU itself stored for the step after it, the
+    cell from the dh the GPU stored; only dc is carried along by the oracle."""
+    Bn, H = Cs.shape[0] // (T + 1), Cs.shape[1]
+    dH, dz_gpu = host(dHs), host(dZ)
+    tol = TOL_SUM if dt == "f32" else TOL_BF16
+    dc = None if dc_last is None else dc_last.astype(np.float64)
+    for t in range(T - 1, -1, -1):
+        sl = slice(t * Bn, (t + 1) * Bn)
+        if t == T - 1:
+            assert np.array_equal(dH[sl], dh_in[sl].astype(np.float64))
+        else:
+            nx = slice((t + 1) * Bn, (t + 2) * Bn)
+            check(dH[sl], O.gemm(dz_gpu[nx], U.T, dh_in[sl], 1.0, 1.0), tol, O.gemm(np.abs(dz_gpu[nx]), np.abs(U.T)) + np.abs(dh_in[sl]), "dh total %d" % t)
+        cp, c = Cs[sl].astype(np.float64), Cs[(t + 1) * Bn:(t + 2) * Bn].astype(np.float64)
+        rdz, dc = O.lstm_bwd(gates[sl], cp, c, dH[sl], dc)
+        Sdc = np.abs(dc) + np.abs(dH[sl]) + 1e-3
+        Sdz = np.concatenate([Sdc, Sdc * (1 + np.abs(cp)), Sdc, np.abs(dH[sl])], axis=1)
+        check(dz_gpu[sl], rdz, TOL_EW * 10 * (T - t) if dt == "f32" else TOL_BF16, Sdz, "dz %d" % t)
+    check(host(dc0), dc, TOL_EW * 10 * T, 1.0, "dc0")
+
+
+@pytest.mark.parametrize("Bn,H,T,dt", BWD_CASES)
+def test_whole_sequence_backward(Bn, H, T, dt):
+    U, dh_in, gates, Cs, dc_last = bwd_inputs(Bn, H, T, dt, 21)
+    dHs, dZ, dc0, work = run_bwd(U, dh_in, gates, Cs, dc_last, T, dt)
+    assert status_word(work) == 0
+    check_bwd_against_oracle(U, dh_in, gates, Cs, dc_last, T, dt, dHs, dZ, dc0)
+    if H % 32 == 0:      # the chain of per-step calls walks the same trajectory
+        d2, z2, dcs = dev(dh_in, dt), empty((T * Bn, 4 * H), dt), [empty((Bn, H)), empty((Bn, H))]
+        B.lstm_step_bwd_seq(z2, dev(U, dt), d2, dev(gates), dev(Cs), dev(dc_last), dcs, T)
+        loose = (1e-4 if dt == "f32" else 4e-2) * max(1, T // 4)
+        check(host(dZ), host(z2), loose, 1.0, "dz whole sequence vs per step")
+        check(host(dc0), host(dcs[0]), loose, 1.0, "dc0 whole sequence vs per step")
+    # the same buffers and workspace again with other values, no gradient into the last cell state
+    U, dh_in, gates, Cs, _ = bwd_inputs(Bn, H, T, dt, 22)
+    run_bwd(U, dh_in, gates, Cs, None, T, dt, (dHs, dZ, dc0, work))
+    assert status_word(work) == 0
+    check_bwd_against_oracle(U, dh_in, gates, Cs, None, T, dt, dHs, dZ, dc0)
+
+
+def test_whole_sequence_backward_refusals_and_give_up():
+    def call(Bn, H, T, dt="f32", work=None):
+        tdt = torch.float32 if dt == "f32" else torch.bfloat16
+        z = lambda *s: torch.zeros(*s, device="cuda")
+        B.lstm_seq_bwd(torch.zeros(H, 4 * H, dtype=tdt, device="cuda"), torch.zeros(T * Bn, H, dtype=tdt, device="cuda"), z(T * Bn, 4 * H),
+                       z((T + 1) * Bn, H), None, torch.zeros(T * Bn, 4 * H, dtype=tdt, device="cuda"), z(Bn, H), T,
+                       ws(B.lstm_seq_bwd_workspace_bytes(Bn, H)) if work is None else work)
+    for args in [(4, 40, 2), (4, 784, 2), (4, 1552, 2, "bf16"), (288, 512, 2)]:      # width not a multiple of 16; too wide; 9 x 32 workgroups
+        with pytest.raises(B.ChnError) as e:
+            call(*args)
+        assert e.value.status == -4, args
+        assert not B.lstm_seq_bwd_supported(args[0], args[1], torch.float32 if len(args) < 4 else torch.bfloat16)
+    with pytest.raises(B.ChnError):
+        call(4, 64, 2, work=torch.empty(4096, dtype=torch.uint8, device="cuda"))
+    call(4, 64, 0)
+    torch.cuda.synchronize()
+    # spin limit 0: the first exchange gives up without looking; the kernel ends, the status word says so
+    Bn, H, T, dt = 128, 672, 35, "f32"
+    U, dh_in, gates, Cs, dc_last = bwd_inputs(Bn, H, T, dt, 23)
+    B.lstm_seq_spin_limit(0)
+    try:
+        bufs = run_bwd(U, dh_in, gates, Cs, dc_last, T, dt)
+    finally:
+        B.lstm_seq_spin_limit(1 << 20)
+    assert status_word(bufs[3]) == 1
+    dHs, dZ, dc0, work = run_bwd(U, dh_in, gates, Cs, dc_last, T, dt, bufs)
+    assert status_word(work) == 0
+    check_bwd_against_oracle(U, dh_in, gates, Cs, dc_last, T, dt, dHs, dZ, dc0)

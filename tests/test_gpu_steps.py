@@ -94,16 +94,16 @@ def test_gradient_on_batch_is_mean_of_halves():
         check(full, 0.5 * (a + b), 1e-4, float(np.max(np.abs(full))), "halves")
 
 
-@pytest.mark.parametrize("mode", ["sequence", "step", "unfused"])   # one launch for all forward steps / one per step / product and cell apart
+@pytest.mark.parametrize("mode", ["sequence", "step", "unfused"])   # one launch for all steps of a pass / one per step / product and cell apart
 @pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=72, batch=16, bptt=6),
                                  dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])
 def test_config4_scaled_lstm_lm_step(cfg, mode):
     w = W.config4(**cfg)
     w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
-    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, fused_step=mode != "unfused", whole_sequence=mode == "sequence")
+    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, fused_step=mode != "unfused", whole_sequence=mode == "sequence", whole_sequence_bwd=mode == "sequence")
     ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
     loss = tr.step(ids, tg)
-    assert tr.sequence_complete() and tr.whole_sequence == (mode == "sequence")
+    assert tr.sequence_complete() and tr.whole_sequence == tr.whole_sequence_bwd == (mode == "sequence")
     r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr))
     assert abs(float(loss.cpu()) - r["loss"]) <= 1e-4 * abs(r["loss"])
     lr = np.float32(w.lr)
@@ -125,16 +125,16 @@ def test_config4_scaled_lstm_lm_step(cfg, mode):
     cmp(tr2.g["U"], r2["grads"]["U"], 1e-4, "dU T=2")
 
 
-@pytest.mark.parametrize("mode", ["sequence", "step", "unfused"])   # one launch for all forward steps / one per step / product and cell apart
+@pytest.mark.parametrize("mode", ["sequence", "step", "unfused"])   # one launch for all steps of a pass / one per step / product and cell apart
 @pytest.mark.parametrize("cfg", [dict(vocab=300, embed=72, hidden=72, batch=16, bptt=6),
                                  dict(vocab=1000, embed=130, hidden=130, batch=24, bptt=4)])
 def test_config4_scaled_lstm_lm_step_mixed_precision(cfg, mode):
     w = W.config4(**cfg)
     w.params["b"] = (np.random.default_rng(3).standard_normal(w.params["b"].shape) * 0.1).astype(np.float32)
-    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, lowp=True, fused_step=mode != "unfused", whole_sequence=mode == "sequence")
+    tr = steps.LSTMTrainer(w.params, w.bptt, w.batch, w.lr, lowp=True, fused_step=mode != "unfused", whole_sequence=mode == "sequence", whole_sequence_bwd=mode == "sequence")
     ids, tg = torch.from_numpy(w.ids).cuda(), torch.from_numpy(w.targets).cuda()
     loss = tr.step(ids, tg)
-    assert tr.sequence_complete() and tr.whole_sequence == (mode == "sequence")
+    assert tr.sequence_complete() and tr.whole_sequence == tr.whole_sequence_bwd == (mode == "sequence")
     r = OS.lstm_lm_step(w.params, w.ids, w.targets, np.float32(w.lr), lowp=True)
     assert abs(float(loss.cpu()) - r["loss"]) <= 2e-2 * abs(r["loss"])
     assert tr.Hs.dtype == torch.bfloat16 and tr.dZ.dtype == torch.bfloat16 and tr.Z.dtype == torch.float32
