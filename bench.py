@@ -10,6 +10,11 @@ kernel that dominates it (the bf16 MFMA GEMM), the CPU oracle timed on a bounded
 workload, and -- under "workloads" -- the other benchmark configurations: the array microbenchmark
 (element-wise / reduction GB/s against the HBM peak), the fp32/bf16 MLP and the LSTM language-model
 step.  All inputs are seeded synthetic tensors already resident in HBM when timing starts.
+Protocol of the headline: W warm-up steps of the very callable that is timed (the recorded step, no
+instrumentation), then `--repeats` (5) regions of exactly K steps each between HIP events on the launch
+stream; the median region is `value`, all regions are listed.  Per-product times (and the roofline
+figure built from them) come from a separate pass afterwards in which every GEMM call sits between two
+events created beforehand.
 One GPU only: this build has no multi-GPU path, and --gpus N > 1 exits with a message.
 """
 import argparse
@@ -141,6 +146,18 @@ class GemmProbe:
                 raise RuntimeError("chn call failed with status %d" % st)
         self.used.add(slot)
 
+    def empty_pair_seconds(self, n=40):
+        """Median time between two events recorded back to back with nothing between them: what a bracket
+        reads beyond the kernel it encloses (the kernel trace of the profiler does not contain it)."""
+        t = self.torch
+        pairs = [(t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)) for _ in range(n)]
+        t.cuda.synchronize()
+        for e0, e1 in pairs:
+            e0.record()
+            e1.record()
+        t.cuda.synchronize()
+        return sorted(e0.elapsed_time(e1) for e0, e1 in pairs)[n // 2] * 1e-3
+
     def per_call_seconds(self):
         tot = [0.0] * self.n
         for slot in self.used:
@@ -208,6 +225,7 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, g
         res["gemm_seconds_per_step"] = sum(per)
         res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch, fused_update))
         res["gemm_probe_steps"] = per_batch * nb
+        res["event_pair_empty_us"] = round(probes[0].empty_pair_seconds() * 1e6, 2)
     res.update({"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(tr.loss.cpu()),
                 "TFLOP/s": w.flops_per_step() / s / 1e12, "launch_calls_per_step": tr.n_launch_calls(xs[0], ts[0])})
     return res
@@ -434,7 +452,7 @@ def main():
                                            "hidden-layer forward x @ W.T + b with GELU, M=8192 N=4096 K=4096)",
                 "achieved": dom_flops / dom_s / 1e12, "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s",
                 "frac": dom_flops / dom_s / 1e12 / MFMA_PEAK_TFLOPS["bf16"], "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES,
-                "avg_launch_us": dom_s * 1e6, "flops_per_launch": dom_flops,
+                "avg_launch_us": dom_s * 1e6, "event_pair_empty_us": r5["event_pair_empty_us"], "flops_per_launch": dom_flops,
                 "all_gemms_achieved": r5["gemm_flops_per_step"] / r5["gemm_seconds_per_step"] / 1e12}
     extra["cfg5_wide_mlp_bf16"] = r5
     del w5

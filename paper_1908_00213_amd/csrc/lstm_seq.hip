@@ -75,11 +75,20 @@ __device__ __forceinline__ void store_h2(bf16_raw *p, float v0, float v1) {
 }
 
 // grid: (H / 8, ceil(B / 64)).  Tile column 8 * g + jj is gate g of hidden unit j0 + jj.
-template <typename T>
+// UC: 512-byte chunks of a row of Ut the resident slice holds; NS: stages the rows of h stream through.  What the
+// slice leaves free of the 160 KB goes to stages: with rows of three chunks (H <= 384 F32, 768 BF16) all of h_{t-1}
+// is in flight at once and a step pays the latency of device memory once instead of once per chunk.
+template <typename T, int UC, int NS>
 __global__ __launch_bounds__(kThreads) void lstm_seq_fwd_kernel(SeqArgs a) {
-  __shared__ __attribute__((aligned(1024))) char uslice[kMaxChunks * kUChunkBytes];
+  static_assert(UC * kUChunkBytes + NS * kHStageBytes <= 160 * 1024 && NS >= 2 && NS <= 4, "LDS budget");
+  __shared__ __attribute__((aligned(1024))) char uslice[UC * kUChunkBytes];
   __shared__ __attribute__((aligned(1024))) char stage0[kHStageBytes];
   __shared__ __attribute__((aligned(1024))) char stage1[kHStageBytes];
+  __shared__ __attribute__((aligned(1024))) char stage2_[kHStageBytes];     // allocated only where referenced
+  __shared__ __attribute__((aligned(1024))) char stage3_[kHStageBytes];
+  char *stage2 = stage0, *stage3 = stage0;
+  if constexpr (NS > 2) stage2 = stage2_;
+  if constexpr (NS > 3) stage3 = stage3_;
   // the word in which wave 0 tells the others that a wait ran out: the tail of a stage, free between two steps
   volatile int &give_up = *reinterpret_cast<volatile int *>(stage1 + kHStageBytes - 4);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -190,24 +199,40 @@ __global__ __launch_bounds__(kThreads) void lstm_seq_fwd_kernel(SeqArgs a) {
     for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.0f;
     copy_h(stage0, hblk, 0);
     if (n_chunks > 1) copy_h(stage1, hblk, 1);
+    if (NS > 2 && n_chunks > 2) copy_h(stage2, hblk, 2);
+    if (NS > 3 && n_chunks > 3) copy_h(stage3, hblk, 3);
     auto step = [&](char *cur, int ch) {
-      // the copies of chunk ch are older than those of chunk ch + 1, which may stay in flight (8 per wave and chunk)
-      if (ch + 1 < n_chunks) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F70);
+      // the copies of chunk ch are older than those of the up to NS - 1 chunks after it, which may stay in flight
+      // (8 copies per wave and chunk)
+      const int newer = n_chunks - 1 - ch < NS - 1 ? n_chunks - 1 - ch : NS - 1;
+      if (newer == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
+      else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F78);
+      else if (newer == 2) __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16)
+      else __builtin_amdgcn_s_waitcnt(0x4F78);                       // vmcnt(24)
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
       mma_chunk(acc0, acc1, cur, ch);
-      __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): the fragment reads have returned
-      asm volatile("" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-      if (ch + 2 < n_chunks) copy_h(cur, hblk, ch + 2);
+      if (ch + NS < n_chunks) {                    // the stage is written again: every wave's fragment reads first
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        copy_h(cur, hblk, ch + NS);
+      }
     };
 #pragma unroll 1
-    for (int ch = 0; ch < n_chunks; ch += 2) {
+    for (int ch = 0; ch < n_chunks; ch += NS) {
       step(stage0, ch);
       if (ch + 1 < n_chunks) step(stage1, ch + 1);
+      if (NS > 2 && ch + 2 < n_chunks) step(stage2, ch + 2);
+      if (NS > 3 && ch + 3 < n_chunks) step(stage3, ch + 3);
     }
+    // every wave is done with the stages before the partial tiles overwrite them
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     // ---- partial tiles meet in LDS; the cell
     {
       const int r = lane & 31, q = lane >> 5;
@@ -572,8 +597,17 @@ chn_status chn_lstm_seq_fwd(const chn_array *zx, const chn_array *Ut, const chn_
   hipLaunchKernelGGL(seq_clear_kernel, dim3(1), dim3(64), 0, st, a.status, (int)(64 + nbb));
   CHN_TRY(check_launch("lstm_seq clear"));
   const dim3 grid((unsigned)nub, (unsigned)nbb);
-  if (t == CHN_BF16) hipLaunchKernelGGL(lstm_seq_fwd_kernel<bf16_raw>, grid, dim3(kThreads), 0, st, a);
-  else hipLaunchKernelGGL(lstm_seq_fwd_kernel<float>, grid, dim3(kThreads), 0, st, a);
+  const int64_t chunks = (a.H * dtype_size(t) + kRowBytes - 1) / kRowBytes;
+#define CHN_SEQ_FWD(UC, NS)                                                                                            \
+  do {                                                                                                                 \
+    if (t == CHN_BF16) hipLaunchKernelGGL((lstm_seq_fwd_kernel<bf16_raw, UC, NS>), grid, dim3(kThreads), 0, st, a);    \
+    else hipLaunchKernelGGL((lstm_seq_fwd_kernel<float, UC, NS>), grid, dim3(kThreads), 0, st, a);                     \
+  } while (0)
+  if (chunks <= 2) CHN_SEQ_FWD(2, 4);
+  else if (chunks <= 3) CHN_SEQ_FWD(3, 3);
+  else if (chunks <= 4) CHN_SEQ_FWD(4, 3);
+  else CHN_SEQ_FWD(6, 2);
+#undef CHN_SEQ_FWD
   return check_launch("lstm_seq_fwd");
 }
 

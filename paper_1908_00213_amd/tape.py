@@ -46,6 +46,7 @@ class GpuBackend:
         self._dt = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
         self._name = {v: k for k, v in self._dt.items()}
         self._gemm_ws = None
+        self._seq_ws = []          # workspaces of whole-sequence recurrent launches whose status word is unread
         self._dev = torch.device("cuda", torch.cuda.current_device())
 
     # allocation (PyTorch's caching allocator; freed by reference count, reused in stream order)
@@ -61,6 +62,8 @@ class GpuBackend:
         return t if dtype is None else self.B.cast(t, self._dt[dtype])
 
     def to_numpy(self, a):
+        if self._seq_ws:
+            self.check_sequences()
         return a.detach().to(self.torch.float64 if a.is_floating_point() else a.dtype).cpu().numpy()
 
     def _bytes(self, n):
@@ -97,12 +100,40 @@ class GpuBackend:
     def lstm_step_bwd(self, dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev):
         self.B.lstm_step_bwd(dz_next, U, dh, gates, c_prev, c, dc_next, dz, dc_prev)
 
-    # a whole sequence of fused steps over time-major buffers (the marshalling is done once)
+    # A whole sequence of fused steps over time-major buffers: one launch for all steps where the library's
+    # resident-grid kernels take the shape (forward: both precisions; backward: fp32, in mixed precision the
+    # per-step call is as fast), else one launch per step (the marshalling is done once).  The resident
+    # kernels' waits are bounded; whether one ran out shows in a status word that `check_sequences` reads.
     def lstm_steps_fwd(self, zx, Hs, Ut, bias, Cs, gates, n_steps):
-        self.B.lstm_step_fwd_seq(zx, Hs, Ut, bias, Cs, gates, n_steps)
+        Bn = zx.shape[0] // max(1, n_steps)
+        if n_steps > 0 and self.B.lstm_seq_supported(Bn, Hs.shape[1], Hs.dtype):
+            ws = self._bytes(self.B.lstm_seq_workspace_bytes(Bn))
+            self.B.lstm_seq_fwd(zx, Ut, bias, Hs, Cs, gates, n_steps, ws)
+            self._pending(ws)
+        else:
+            self.B.lstm_step_fwd_seq(zx, Hs, Ut, bias, Cs, gates, n_steps)
 
     def lstm_steps_bwd(self, dZ, U, dHs, gates, Cs, dc_last, dc, n_steps):
-        self.B.lstm_step_bwd_seq(dZ, U, dHs, gates, Cs, dc_last, dc, n_steps)
+        Bn = dZ.shape[0] // max(1, n_steps)
+        if n_steps > 0 and dHs.dtype == self.torch.float32 and self.B.lstm_seq_bwd_supported(Bn, dHs.shape[1], dHs.dtype):
+            ws = self._bytes(self.B.lstm_seq_bwd_workspace_bytes(Bn, dHs.shape[1]))
+            self.B.lstm_seq_bwd(U, dHs, gates, Cs, dc_last, dZ, dc[0], n_steps, ws)
+            self._pending(ws)
+        else:
+            self.B.lstm_step_bwd_seq(dZ, U, dHs, gates, Cs, dc_last, dc, n_steps)
+
+    def _pending(self, ws):
+        self._seq_ws.append(ws)
+        if len(self._seq_ws) >= 256:
+            self.check_sequences()
+
+    def check_sequences(self):
+        """Synchronises and raises if a wait of a whole-sequence recurrent kernel ran out since the last check
+        (its outputs, and whatever was computed from them, are then invalid)."""
+        pending, self._seq_ws = self._seq_ws, []
+        if any(self.B.lstm_seq_status(w) != 0 for w in pending):
+            raise RuntimeError("a whole-sequence recurrent kernel gave up waiting for its grid (the device was shared); "
+                               "results since the last check are invalid")
 
     def softmax_ce_fwd(self, logits, labels, loss_mean, lse, ignore_label):
         ws = self._bytes(self.B.softmax_ce_workspace_bytes(logits.shape[0]))
