@@ -480,14 +480,15 @@ int chn_version(void);
  * Returns a small integer code (>= 0) or a negative chn_status.  Element-wise families:
  * 0 flat contiguous/row-broadcast, 1 pitched rows, 2 tile-transposed, 3 general strided. */
 int chn_elementwise_plan(int op, int n_in, const chn_array *const *in, const chn_array *out);
-/* The same for chn_gemm: bits 0-1 macro tile (0: 64x64, 1: 128x128, 2: 256x256), bit 2 set when a
- * 256x256 kernel that copies operand tiles straight from global memory into LDS is taken, bit 3 when that
+/* The same for chn_gemm: bits 0-1 macro tile (0: 64x64, 1: 128x128, 2: 256x256, 3: 256x128 - bfloat16
+ * products with both operands unit-stride along K whose N is too small for 256 blocks of the square tile),
+ * bit 2 set when a kernel that copies operand tiles straight from global memory into LDS is taken, bit 3 when that
  * is the kernel that works on the tile with eight waves (bfloat16 products), bits 4 and up the number of
  * K splits (1 = none;
  * have_workspace = 0 plans as chn_gemm does without workspace). */
 int chn_gemm_plan(const chn_array *A, const chn_array *B, const chn_array *C, int have_workspace);
 /* Test hook: replace the planner's choice for every later chn_gemm / chn_gemm_plan of the process.
- * tile: 0, 1, 2 as above, or -1 for the planner's own; splits: a number of K splits >= 1 (used when a
+ * tile: 0 .. 3 as above, or -1 for the planner's own; splits: a number of K splits >= 1 (used when a
  * workspace allows it), or -1; direct_copy: 0 keeps products off the direct-copy kernels, -1 or 1 lets
  * the planner take them where they fit, 2 / 3 additionally fix the four-wave / eight-wave kernel.  A forced value that the operands do not allow (the large tiles
  * need 8-byte pieces) is ignored.  Results do not depend on the plan beyond summation order; the tests

@@ -279,7 +279,7 @@ def gemm_workspace_bytes(A, B, Cm):
 
 
 def gemm_plan(A, B, Cm, have_workspace=False):
-    """(tile, direct_copy, splits) chn_gemm would use: tile 0/1/2 = 64/128/256 square."""
+    """(tile, direct_copy, splits) chn_gemm would use: tile 0/1/2 = 64/128/256 square, 3 = 256 x 128."""
     code = lib().chn_gemm_plan(_ref(desc(A)), _ref(desc(B)), _ref(desc(Cm)), 1 if have_workspace else 0)
     if code < 0:
         _check(code)

@@ -23,6 +23,7 @@ using gemm::GemmArgs;
 
 // chn_gemm_plan_override: what tests force instead of the planner's choice (-1: not forced)
 std::atomic<int> g_force_tile{-1}, g_force_splits{-1}, g_force_direct{-1};
+constexpr double kNarrowStep = 0.92, kNarrowFixed = 12.0;   // microseconds per tile step / per block of the 256 x 128 tile
 std::atomic<int> g_force_w8{-1};
 
 // Largest load piece (bytes) that is aligned for every row start of the operand and divides its
@@ -65,7 +66,7 @@ bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
   return dma_on && g.piece == 16 && g.K > 0 && g.lda < max_ld && g.ldb < max_ld && (isz == 2 || a_kc || b_kc);
 }
 
-// Macro tile (2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model
+// Macro tile (3: 256x128, 2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model
 // from measured figures: every compute unit works through its share of the blocks one after another,
 // a block costing a fixed part (launch, prologue, epilogue) plus its tile steps times the time one
 // compute unit needs per tile step of that tile and kernel (for the smaller tiles, of which several
@@ -114,17 +115,28 @@ void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big
       if (t < best * 0.97) { best = t; g->tile = tile; g->splits = s; }   // prefer larger tiles / fewer splits on near-ties
     }
   }
+  // The 256 x 128 tile of the eight-wave kernel (bf16, both operands K-contiguous): taken when it fills the chip
+  // in one round without a cut along K where the square tile cannot (N near 1000 with a long M).
+  const bool narrow_ok = direct && isz == 2 && a_kc && b_kc && !big_unsplit && g_force_w8.load(std::memory_order_relaxed) != 0;
+  if (narrow_ok) {
+    const int64_t tiles = (int64_t)((g->M + 255) / 256) * ((g->N + 127) / 128);
+    const int64_t rounds = (tiles + 255) / 256;
+    const double t = (double)rounds * (kNarrowFixed + nk * kNarrowStep) * 1e-6;
+    if (t < best * 0.97) { best = t; g->tile = 3; g->splits = 1; }
+  }
   {   // chn_gemm_plan_override
     const int force_tile = g_force_tile.load(std::memory_order_relaxed), force_splits = g_force_splits.load(std::memory_order_relaxed);
     if (force_tile >= 0 && force_tile <= (wide ? 2 : 0)) g->tile = force_tile;
+    if (force_tile == 3 && narrow_ok) g->tile = 3;
+    if (force_tile >= 0 && force_tile != 3 && g->tile == 3) g->tile = wide ? 2 : 0;
     if (force_splits >= 1 && allow_split && force_splits <= nk) g->splits = force_splits;
   }
   if (big_unsplit) { g->tile = 2; g->splits = 1; }        // (the caller has checked that the operands allow the big tile)
-  const int b = 64 << g->tile;
-  g->tiles_m = (g->M + b - 1) / b;
-  g->tiles_n = (g->N + b - 1) / b;
+  const int bm = g->tile == 3 ? 256 : 64 << g->tile, bn = g->tile == 3 ? 128 : 64 << g->tile;
+  g->tiles_m = (g->M + bm - 1) / bm;
+  g->tiles_n = (g->N + bn - 1) / bn;
   g->ldp = (g->N + 3) & ~3;
-  g->dma = g->tile == 2 && direct;
+  g->dma = (g->tile == 2 || g->tile == 3) && direct;
 }
 
 // Which of the two direct-copy kernels takes a bf16 product on the 256x256 tile: the eight-wave one.  Both

@@ -1175,10 +1175,16 @@ struct TwoParts : L {
 // staging and stores of its epilogue -- the other wave's MFMAs fill.
 // Operand traffic from L2 is that of the four-wave kernel (the tile is the same), LDS fragment traffic is
 // 1.5 times higher (6 fragment reads per 8 MFMAs instead of 8 per 16).
-template <bool A_KC, bool B_KC, bool RAGGED>
+//
+// BN = 128 is the same kernel on a 256 x 128 tile for products whose N is too small to give 256 workgroups
+// of the square tile (a classifier's logits): the waves stand 4 (M) x 2 (N), a wave owns 64 x 64 (2 x 2
+// MFMA blocks), 6 copy instructions per wave and tile instead of 8, as many fragment reads as MFMAs.
+template <bool A_KC, bool B_KC, bool RAGGED, int BN = 256>
 __global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
   using T = bf16_raw;
-  constexpr int TM = 4, TN = 2, BM = 256, BN = 256, NW = 8;
+  static_assert(BN == 256 || (BN == 128 && A_KC && B_KC), "the 256 x 128 tile exists for K-contiguous operands");
+  constexpr int BM = 256, NW = 8, WN = BN == 256 ? 4 : 2, WM = NW / WN;   // waves along N and M
+  constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   constexpr int BK = 64;
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   __shared__ __align__(1024) char stage0[STAGE];
@@ -1193,7 +1199,7 @@ __global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
   lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
 
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / WN, wn = wave % WN;
 
   std::conditional_t<A_KC, KcReader<T>, TrReader> ra;
   std::conditional_t<B_KC, KcReader<T>, TrReader> rb;
@@ -1239,8 +1245,13 @@ __global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
   if constexpr ((NV) > (S)) __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0); \
   __builtin_amdgcn_sched_group_barrier(SG_MFMA, NMF, 0);
 #define CHN_W8_KSTEP(NV)                                                        \
-  CHN_W8_GROUP(0, RPG_A, 2, NV) CHN_W8_GROUP(1, RPG_A, 2, NV) CHN_W8_GROUP(2, RPG_A, 1, NV) \
-  CHN_W8_GROUP(3, RPG_A, 1, NV) CHN_W8_GROUP(4, RPG_B, 1, NV) CHN_W8_GROUP(5, RPG_B, 1, NV)
+  if constexpr (TM == 4) {                                                      \
+    CHN_W8_GROUP(0, RPG_A, 2, NV) CHN_W8_GROUP(1, RPG_A, 2, NV) CHN_W8_GROUP(2, RPG_A, 1, NV) \
+    CHN_W8_GROUP(3, RPG_A, 1, NV) CHN_W8_GROUP(4, RPG_B, 1, NV) CHN_W8_GROUP(5, RPG_B, 1, NV) \
+  } else {                                                                      \
+    CHN_W8_GROUP(0, RPG_A, 1, NV) CHN_W8_GROUP(1, RPG_A, 1, NV) CHN_W8_GROUP(2, RPG_B, 1, NV) \
+    CHN_W8_GROUP(3, RPG_B, 1, NV)                                               \
+  }
 
   // One tile step: k-steps 0..2 out of `cur` (the fragments of the following k-step are read while a
   // k-step multiplies); barrier -- the copy of the next tile has landed in `nxt`, and nobody reads `cur` any
@@ -1253,11 +1264,11 @@ __global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
     la.template issue_part<1>(k_of(kt + 1), nxt);
     lb.template issue_part<0>(k_of(kt + 1), nxt + A_BYTES);
     mma<T, TM, TN>(acc, f0);
-    CHN_W8_KSTEP(4)
+    CHN_W8_KSTEP(BN == 256 ? 4 : 3)
     read_frags(f0, cur, 2);
     lb.template issue_part<1>(k_of(kt + 1), nxt + A_BYTES);
     mma<T, TM, TN>(acc, f1);
-    CHN_W8_KSTEP(2)
+    CHN_W8_KSTEP(BN == 256 ? 2 : 1)
     read_frags(f1, cur, 3);
     mma<T, TM, TN>(acc, f0);
     CHN_W8_KSTEP(0)
@@ -1284,14 +1295,30 @@ __global__ __launch_bounds__(512) void gemm_kernel_w8(GemmArgs g) {
   // The (unused) copies that the last steps started must be over: the epilogue reuses both stages.
   __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
   __syncthreads();
-  static_assert(4 * kEpiStageBytes<TM, TN> <= STAGE, "four waves stage their accumulators in each operand stage");
-  write_out<TM, TN, 4>(g, acc, (wave < 4 ? stage0 : stage1) + (wave & 3) * kEpiStageBytes<TM, TN>, m0, n0, split);
+  if constexpr (BN == 256) {
+    static_assert(4 * kEpiStageBytes<TM, TN> <= STAGE, "four waves stage their accumulators in each operand stage");
+    write_out<TM, TN, WN>(g, acc, (wave < 4 ? stage0 : stage1) + (wave & 3) * kEpiStageBytes<TM, TN>, m0, n0, split);
+  } else {
+    // three waves in each operand stage, two in an area of their own
+    static_assert(3 * kEpiStageBytes<TM, TN> <= STAGE, "three waves stage their accumulators in each operand stage");
+    __shared__ __align__(1024) char epi_extra[2 * kEpiStageBytes<TM, TN>];
+    char *area = wave < 3 ? stage0 + wave * kEpiStageBytes<TM, TN>
+               : wave < 6 ? stage1 + (wave - 3) * kEpiStageBytes<TM, TN> : epi_extra + (wave - 6) * kEpiStageBytes<TM, TN>;
+    write_out<TM, TN, WN>(g, acc, area, m0, n0, split);
+  }
 }
 
 template <bool A_KC, bool B_KC>
 chn_status launch_w8(const GemmArgs &g, hipStream_t st) {
   const dim3 grid((unsigned)(g.tiles_m * g.tiles_n * g.splits));
-  if (g.K % 64 == 0) hipLaunchKernelGGL((gemm_kernel_w8<A_KC, B_KC, false>), grid, dim3(512), 0, st, g);
+  if (g.tile == 3) {
+    if constexpr (A_KC && B_KC) {
+      if (g.K % 64 == 0) hipLaunchKernelGGL((gemm_kernel_w8<true, true, false, 128>), grid, dim3(512), 0, st, g);
+      else hipLaunchKernelGGL((gemm_kernel_w8<true, true, true, 128>), grid, dim3(512), 0, st, g);
+    } else {
+      return fail(CHN_ERR_LAUNCH, "gemm: the 256 x 128 tile was planned for operands it does not take");
+    }
+  } else if (g.K % 64 == 0) hipLaunchKernelGGL((gemm_kernel_w8<A_KC, B_KC, false>), grid, dim3(512), 0, st, g);
   else hipLaunchKernelGGL((gemm_kernel_w8<A_KC, B_KC, true>), grid, dim3(512), 0, st, g);
   CHN_TRY(check_launch("gemm (eight waves)"));
   if (g.splits > 1) {
@@ -1358,7 +1385,8 @@ template <typename T, bool A_KC, bool B_KC>
 chn_status launch_layout(GemmArgs &g, hipStream_t st) {
   if ((int64_t)g.tiles_m * g.tiles_n * g.splits > 0x7fffffff) return fail(CHN_ERR_SHAPE, "gemm: too many tiles");
   if constexpr (sizeof(T) == 2) {
-    if (g.tile == 2 && g.piece == 16 && g.dma && g.w8) return launch_w8<A_KC, B_KC>(g, st);
+    if ((g.tile == 2 || g.tile == 3) && g.piece == 16 && g.dma && g.w8) return launch_w8<A_KC, B_KC>(g, st);
+    if (g.tile == 3) return fail(CHN_ERR_LAUNCH, "gemm: the 256 x 128 tile needs the eight-wave direct-copy kernel");
   }
   if constexpr (kHasDmaKernel<T, A_KC, B_KC>) {
     if (g.tile == 2 && g.piece == 16 && g.dma) return launch_dma<T, A_KC, B_KC>(g, st);

@@ -350,6 +350,68 @@ def test_gemm_direct_copy_split_k(layout, direct_kernel):
     assert np.array_equal(host(out), A.astype(np.float64) @ Bm.astype(np.float64))
 
 
+@pytest.fixture
+def narrow_tile():
+    B.gemm_plan_override(tile=3)
+    yield
+    B.gemm_plan_override()
+
+
+@pytest.mark.parametrize("cdt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(300, 200, 128), (513, 129, 200), (1030, 1000, 520), (256, 128, 64), (2, 3, 8)])
+def test_gemm_256x128_tile(shape, cdt, narrow_tile):
+    # the 256 x 128 tile of the eight-wave kernel (bf16, both operands unit-stride along K): full tiles, ragged last
+    # tiles in M, N and K, every epilogue, cut along K or not; small integers must come out bit for bit
+    M, N, K = shape
+    gi = lambda s, d: RNG.integers(-3, 4, size=s).astype(np.float32)
+    A, Bm, Ad, Bd = operands(M, N, K, "nt", "bf16", gi)
+    assert B.gemm_plan(Ad, Bd, empty((M, N), cdt))[:2] == (3, True)
+    w = ws(4 * M * ((N + 3) // 4 * 4) * 4 + 256)
+    lin = O.gemm(A, Bm)
+    for splits in (1, 2):
+        B.gemm_plan_override(tile=3, splits=splits)
+        assert np.array_equal(host(B.gemm(Ad, Bd, empty((M, N), cdt), ws=w)), O.round_bf16(lin) if cdt == "bf16" else lin), splits
+    B.gemm_plan_override(tile=3)
+    A, Bm, Ad, Bd = operands(M, N, K, "nt", "bf16")
+    tol = TOL_BF16 if cdt == "bf16" else TOL_SUM
+    rd = (lambda a: bf16r(a)) if cdt == "bf16" else (lambda a: a)
+    bias, aux, c0 = rnd((N,)), rd(rnd((M, N))), rd(rnd((M, N)))
+    lin, S = O.gemm(A, Bm), O.gemm(np.abs(A), np.abs(Bm))
+    out = B.gemm(Ad, Bd, dev(c0, cdt), alpha=0.5, beta=-1.25)
+    check(host(out), 0.5 * lin - 1.25 * c0.astype(np.float64), tol, 0.5 * S + 1.25 * np.abs(c0), "alpha/beta")
+    z, Sz = lin + bias, S + np.abs(bias)
+    check(host(B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias", bias=dev(bias))), z, tol, Sz, "bias")
+    check(host(B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_relu", bias=dev(bias))), np.maximum(z, 0), tol, Sz, "bias_relu")
+    pre = empty((M, N), cdt)
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="bias_gelu", bias=dev(bias), preact_out=pre)
+    check(host(pre), z, tol, Sz, "preact")
+    check(host(out), O.elementwise("gelu", [z]), tol, Sz, "bias_gelu")
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="relu_bwd", aux=dev(aux, cdt))
+    check(host(out), np.where(aux > 0, lin, 0.0), tol, S, "relu_bwd")
+    out = B.gemm(Ad, Bd, empty((M, N), cdt), epilogue="gelu_bwd", aux=dev(aux, cdt))
+    gp = O.elementwise("gelu_bwd", [np.ones_like(aux, dtype=np.float64), aux.astype(np.float64)])
+    check(host(out), lin * gp, tol, S * np.abs(gp) + 3e-3 * S, "gelu_bwd")
+    if cdt == "f32":
+        W0, low = rnd((M, N)), empty((M, N), "bf16")
+        Wd = dev(W0)
+        B.gemm(Ad, Bd, Wd, alpha=-0.01, beta=1.0, epilogue="bf16_copy", preact_out=low)
+        check(host(Wd), W0 - 0.01 * lin, TOL_SUM, np.abs(W0) + 0.01 * S, "update")
+        assert np.array_equal(host(low), O.round_bf16(host(Wd)))
+
+
+def test_gemm_256x128_tile_is_planned_for_a_classifier_layer_only():
+    x, W3 = empty((8192, 4096), "bf16"), empty((1000, 4096), "bf16")
+    assert B.gemm_plan(x, W3.t(), empty((8192, 1000)), True) == (3, True, 1)            # logits of the wide MLP
+    assert B.gemm_plan(x, empty((4096, 4096), "bf16").t(), empty((8192, 4096), "bf16"), True)[0] == 2
+    assert B.gemm_plan(x, empty((4096, 1000), "bf16"), empty((8192, 1000)), True)[0] != 3   # B unit-stride along N
+    assert B.gemm_plan(empty((8192, 4096)), empty((1000, 4096)).t(), empty((8192, 1000)), True)[0] != 3   # fp32
+    B.gemm_plan_override(direct_copy=2)                                                  # four-wave kernel forced
+    try:
+        assert B.gemm_plan(x, W3.t(), empty((8192, 1000)), True)[0] != 3
+    finally:
+        B.gemm_plan_override()
+
+
 def test_gemm_degenerate_sizes():
     # K == 0: nothing to multiply, the epilogue still runs on beta * C;  M == 0 or N == 0: nothing to do
     c0 = rnd((70, 90))
