@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 CASES = [(128, 672, 35, "f32"), (128, 672, 35, "bf16"),      # the language-model workload: 84 x 2 workgroups
          (70, 40, 4, "f32"), (5, 8, 3, "f32"),               # ragged batch block, one partial chunk
          (33, 144, 6, "bf16"), (200, 256, 3, "f32"),         # four batch blocks, two chunks
-         (64, 1536, 2, "bf16"), (128, 768, 2, "f32"),        # the widest rows the resident slice holds
+         (64, 1536, 2, "bf16"), (128, 768, 2, "f32"),        # the widest rows: Ut in registers, five stages, six chunks
+         (64, 640, 3, "f32"),                                # ... five chunks
          (64, 512, 3, "f32"), (40, 352, 3, "f32")]           # four chunks through three stages (one reused); three, the last one partial
 
 
