@@ -47,6 +47,21 @@ __device__ __forceinline__ void mma_piece(floatx16 &acc, const uint4 &a, const u
   }
 }
 
+// two row blocks against the same piece of the other operand, the two accumulator chains taking turns
+template <typename T>
+__device__ __forceinline__ void mma_pair(floatx16 &acc0, floatx16 &acc1, const uint4 &a0, const uint4 &a1, const uint4 &b) {
+  if constexpr (sizeof(T) == 2) {
+    mma_piece<T>(acc0, a0, b);
+    mma_piece<T>(acc1, a1, b);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float((&a0.x)[kk]), __uint_as_float((&b.x)[kk]), acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float((&a1.x)[kk]), __uint_as_float((&b.x)[kk]), acc1, 0, 0, 0);
+    }
+  }
+}
+
 struct SeqArgs {
   int64_t B, H;
   int n_steps, nub, spin_limit;
@@ -137,26 +152,34 @@ __global__ __launch_bounds__(kThreads) void lstm_seq_fwd_kernel(SeqArgs a) {
                                        (__attribute__((address_space(3))) void *)(stage + 2 * pair * kRowBytes), 16, 0, kCpolAgent);
     }
   };
-  // this wave's quarter of the 32-byte slices of a staged chunk, against the resident rows of Ut
-  auto mma_chunk = [&](floatx16 &acc0, floatx16 &acc1, const char *stage, int ch) {
+  // A wave's share of a staged chunk: every fourth 32-byte slice (slices 4 u + wave: the slices of a partial last chunk
+  // are dealt out over the waves too), against the resident rows of Ut.  The fragments of chunk c + 1 are read while
+  // the matrix cores work on chunk c, into the other of two register sets.
+  struct Frag { uint4 x0[4], x1[4], y[4]; };
+  auto slices_of = [&](int ch) {
     const int64_t left = row_bytes - (int64_t)ch * kRowBytes;
-    const int n_slices = (int)((left < kRowBytes ? left : kRowBytes) / 32);
+    return (int)((left < kRowBytes ? left : kRowBytes) / 32);
+  };
+  auto read_frags = [&](Frag &f, const char *stage, int ch) __attribute__((always_inline)) {
+    const int n_slices = slices_of(ch);
     const int r = lane & 31, q = lane >> 5;
     const char *pa = stage + r * kRowBytes, *pb = uslice + ch * kUChunkBytes + r * kRowBytes;
-    uint4 x0[4], x1[4], y[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int s = wave * 4 + u;
+      const int s = 4 * u + wave;
       if (s < n_slices) {
         const int pos = ((2 * s + q) ^ (r & 15)) << 4;
-        x0[u] = *reinterpret_cast<const uint4 *>(pa + pos);
-        x1[u] = *reinterpret_cast<const uint4 *>(pa + 32 * kRowBytes + pos);
-        y[u] = *reinterpret_cast<const uint4 *>(pb + pos);
+        f.x0[u] = *reinterpret_cast<const uint4 *>(pa + pos);
+        f.x1[u] = *reinterpret_cast<const uint4 *>(pa + 32 * kRowBytes + pos);
+        f.y[u] = *reinterpret_cast<const uint4 *>(pb + pos);
       }
     }
+  };
+  auto mma_frags = [&](floatx16 &acc0, floatx16 &acc1, const Frag &f, int ch) __attribute__((always_inline)) {
+    const int n_slices = slices_of(ch);
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-      if (wave * 4 + u < n_slices) { mma_piece<T>(acc0, x0[u], y[u]); mma_piece<T>(acc1, x1[u], y[u]); }
+      if (4 * u + wave < n_slices) mma_pair<T>(acc0, acc1, f.x0[u], f.x1[u], f.y[u]);
   };
   float (*tile0)[32][33] = reinterpret_cast<float (*)[32][33]>(stage0);   // partial tiles of rows 0-31 / 32-63, per wave
   float (*tile1)[32][33] = reinterpret_cast<float (*)[32][33]>(stage1);
@@ -201,38 +224,43 @@ __global__ __launch_bounds__(kThreads) void lstm_seq_fwd_kernel(SeqArgs a) {
     if (n_chunks > 1) copy_h(stage1, hblk, 1);
     if (NS > 2 && n_chunks > 2) copy_h(stage2, hblk, 2);
     if (NS > 3 && n_chunks > 3) copy_h(stage3, hblk, 3);
-    auto step = [&](char *cur, int ch) {
-      // the copies of chunk ch are older than those of the up to NS - 1 chunks after it, which may stay in flight
-      // (8 copies per wave and chunk)
-      const int newer = n_chunks - 1 - ch < NS - 1 ? n_chunks - 1 - ch : NS - 1;
-      if (newer == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
+    // the copies of a chunk are older than those of the chunks after it, which may stay in flight (8 per wave and chunk)
+    auto wait_copies = [&](int newer) __attribute__((always_inline)) {
+      if (newer <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);
       else if (newer == 1) __builtin_amdgcn_s_waitcnt(0x0F78);
       else if (newer == 2) __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16)
       else __builtin_amdgcn_s_waitcnt(0x4F78);                       // vmcnt(24)
+    };
+    auto barrier = [&]() __attribute__((always_inline)) {
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      mma_chunk(acc0, acc1, cur, ch);
-      if (ch + NS < n_chunks) {                    // the stage is written again: every wave's fragment reads first
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        copy_h(cur, hblk, ch + NS);
-      }
     };
-#pragma unroll 1
-    for (int ch = 0; ch < n_chunks; ch += NS) {
-      step(stage0, ch);
-      if (ch + 1 < n_chunks) step(stage1, ch + 1);
-      if (NS > 2 && ch + 2 < n_chunks) step(stage2, ch + 2);
-      if (NS > 3 && ch + 3 < n_chunks) step(stage3, ch + 3);
+    char *const stages[4] = {stage0, stage1, stage2, stage3};
+    Frag fa, fb;
+    wait_copies(n_chunks - 1 < NS - 1 ? n_chunks - 1 : NS - 1);
+    barrier();
+    read_frags(fa, stage0, 0);
+    // Chunk by chunk (at most kMaxChunks; written out so that stage and register set are named at compile time):
+    // the fragments of chunk ch have been requested.  Once they are here and the copies of chunk ch + 1 have landed,
+    // one barrier says both for every wave: the stage of chunk ch may be refilled and chunk ch + 1 may be read -
+    // which then happens under the MFMAs of chunk ch.
+#pragma unroll
+    for (int ch = 0; ch < kMaxChunks; ++ch) {
+      if (ch < n_chunks) {
+        Frag &cur = ch % 2 ? fb : fa, &nxt = ch % 2 ? fa : fb;
+        if (ch + 1 < n_chunks) {
+          __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): this wave's fragment reads of chunk ch are back
+          wait_copies(n_chunks - 2 - ch < NS - 2 ? n_chunks - 2 - ch : NS - 2);
+          barrier();
+          if (ch + NS < n_chunks) copy_h(stages[ch % NS], hblk, ch + NS);
+          read_frags(nxt, stages[(ch + 1) % NS], ch + 1);
+        }
+        mma_frags(acc0, acc1, cur, ch);
+      }
     }
     // every wave is done with the stages before the partial tiles overwrite them
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    barrier();
     // ---- partial tiles meet in LDS; the cell
     {
       const int r = lane & 31, q = lane >> 5;
