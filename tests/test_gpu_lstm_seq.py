@@ -137,6 +137,7 @@ def test_a_wait_that_runs_out_ends_the_kernel_and_raises_the_status_word():
 BWD_CASES = [(128, 672, 35, "f32"), (128, 672, 35, "bf16"),  # the language-model workload: 42 x 4 workgroups
              (40, 48, 4, "f32"), (5, 16, 3, "f32"),          # ragged batch block, a partial 32-unit tile; one workgroup
              (33, 144, 5, "bf16"), (200, 256, 3, "f32"),
+             (40, 96, 4, "bf16"), (250, 512, 2, "bf16"),     # ragged batch block; 32 x 8 = 256 workgroups, every compute unit
              (96, 768, 2, "f32"), (32, 1536, 2, "bf16")]     # the widest U the registers hold (bf16: two batches of partial sums)
 
 
