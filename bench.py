@@ -344,15 +344,63 @@ def traffic_driver(torch, B, W, what):
     log("traffic driver (%s): 3 x (copy 256 MiB, flush, %d launches with a flush after each) done" % (what, len(launches)))
 
 
+class _SysfsSampler:
+    """Reads the driver's own gauges (shader clock as the starred line of pp_dpm_sclk, board power from
+    hwmon) every 20 ms on a thread of its own while a measurement runs.  Read-only; where the files are
+    missing or unreadable the probe reports no clock and power."""
+
+    def __init__(self):
+        import glob
+        self.sclk = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        self.power = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                                      glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))), None)
+
+    def _read(self):
+        mhz = watts = None
+        try:
+            for line in open(self.sclk):
+                if line.rstrip().endswith("*"):
+                    mhz = float(line.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except Exception:
+            pass
+        try:
+            watts = float(open(self.power).read()) * 1e-6
+        except Exception:
+            pass
+        return mhz, watts
+
+    def run(self, fn):
+        """fn() once (it synchronises itself); returns (its result, median MHz or None, median W or None)."""
+        import threading
+        stop, samples = threading.Event(), []
+
+        def loop():
+            while not stop.is_set():
+                samples.append(self._read())
+                stop.wait(0.02)
+        th = threading.Thread(target=loop, daemon=True)
+        th.start()
+        try:
+            out = fn()
+        finally:
+            stop.set()
+            th.join()
+        samples = samples[len(samples) // 4:]                # the first quarter: clock and power still ramping
+        med = lambda xs: (sorted(xs)[len(xs) // 2] if xs else None)
+        return out, med([m for m, _ in samples if m is not None]), med([w for _, w in samples if w is not None])
+
+
 def power_probe(torch, B, W, timer):
     """The dominant product (8192 x 4096 x 4096, bf16, plain epilogue) on operands of different bit activity:
     the instruction stream is identical, only the data differs.  What the times show is how far the chip's
-    power management, not the kernel's schedule, sets the rate on data that looks like a training step's."""
+    power management, not the kernel's schedule, sets the rate on data that looks like a training step's;
+    the shader clock and board power the driver reports while each loop runs are listed beside them."""
     M, N, K = 8192, 4096, 4096
     bf = torch.bfloat16
     rng = np.random.default_rng(190800213)
     out = torch.empty(M, N, dtype=bf, device="cuda")
     res = {}
+    sampler = _SysfsSampler()
     kinds = {"zeros": lambda s: np.zeros(s, np.float32), "ones": lambda s: np.ones(s, np.float32),
              "small integers in [-3, 3]": lambda s: rng.integers(-3, 4, size=s).astype(np.float32),
              "standard normal": lambda s: rng.standard_normal(s, dtype=np.float32)}
@@ -360,10 +408,13 @@ def power_probe(torch, B, W, timer):
         for kind, gen in kinds.items():
             a = B.cast(torch.from_numpy(gen((M, K))).cuda(), bf)
             wt = B.cast(torch.from_numpy(gen((N, K))).cuda(), bf)
-            s = timer.time(lambda: B.gemm(a, wt.t(), out), 30, 5)
-            res.setdefault(kind, []).append(round(s * 1e6, 1))
-            log("  power probe  %-28s %7.1f us  %7.1f TFLOP/s" % (kind, s * 1e6, 2.0 * M * N * K / s / 1e12))
-    return {k: {"us": v, "TFLOP/s": [round(2.0 * M * N * K / (u * 1e-6) / 1e12, 1) for u in v]} for k, v in res.items()}
+            s, mhz, watts = sampler.run(lambda: timer.time(lambda: B.gemm(a, wt.t(), out), 2000, 5))   # about half a second
+            r = res.setdefault(kind, {"us": [], "TFLOP/s": [], "sclk_MHz": [], "board_W": []})
+            r["us"].append(round(s * 1e6, 1)); r["TFLOP/s"].append(round(2.0 * M * N * K / s / 1e12, 1))
+            r["sclk_MHz"].append(mhz); r["board_W"].append(None if watts is None else round(watts))
+            log("  power probe  %-28s %7.1f us  %7.1f TFLOP/s   sclk %s MHz   board %s W" % (
+                kind, s * 1e6, 2.0 * M * N * K / s / 1e12, mhz, None if watts is None else round(watts)))
+    return res
 
 
 def cpu_baseline(W, rows=(32, 96)):
