@@ -249,8 +249,9 @@ chn_status chn_lstm_step_bwd(const chn_array *dz_next, const chn_array *U, const
  * zx (n_steps*B, 4H) F32; Ut (4H, H) F32 or BF16; bias (4H) F32 or NULL; Hs ((n_steps+1)*B, H) of Ut's type
  * and Cs ((n_steps+1)*B, H) F32 with block 0 holding the initial state (read) and blocks 1.. written;
  * gates (n_steps*B, 4H) F32 or NULL.  All device, row-major with unit inner stride, rows of Hs and Ut on
- * 16-byte boundaries.  Same arithmetic as n_steps calls of chn_lstm_step_fwd (fp32 sums on the matrix cores,
- * the contraction cut in four; agrees with them within the product tolerance).
+ * 16-byte boundaries.  Same formulas as n_steps calls of chn_lstm_step_fwd (fp32 sums on the matrix cores,
+ * the contraction cut in four; the gate activations on the hardware's exponential and reciprocal, relative
+ * error a few 1e-7; agrees with them within the product tolerance).
  *
  * The grid stays on the device for the whole sequence - (H/8) x ceil(B/64) workgroups, each holding its rows
  * of Ut in LDS - and exchanges h between steps through device memory, so every workgroup must be resident at
