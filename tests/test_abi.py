@@ -193,6 +193,35 @@ def test_later_entry_points_validate_on_the_host():
     assert bwd(zx, f((4 * H, H)), hp, zx) == -4                               # the transpose where U is expected
 
 
+def test_whole_sequence_entry_points_validate_on_the_host():
+    """What the whole-sequence recurrent kernels refuse before they ask the device anything."""
+    L = B.lib()
+    f = lambda shape, dt=B.F32, p=P: B.raw_desc(p, shape, [int(s) for s in _row_major(shape, {B.F32: 4, B.BF16: 2, B.I32: 4}[dt])], dt)
+    r = C.byref
+    Bn, H, T = 4, 64, 3
+    zx, Ut, Hs, Cs = f((T * Bn, 4 * H)), f((4 * H, H)), f(((T + 1) * Bn, H)), f(((T + 1) * Bn, H))
+    fwd = lambda zx, Ut, Hs, Cs, T_=T, ws=P, n=1 << 20: L.chn_lstm_seq_fwd(r(zx), r(Ut), None, r(Hs), r(Cs), None, T_, ws, n, None)
+    assert L.chn_lstm_seq_fwd(r(zx), r(Ut), None, None, r(Cs), None, T, P, 1 << 20, None) == -1            # Hs missing
+    assert fwd(zx, Ut, Hs, f((2, 2, 2))) == -2                                    # Cs must be 2-d
+    assert fwd(zx, Ut, Hs, Cs, T_=4) == -4                                        # 16 rows do not hold 4 + 1 blocks
+    assert fwd(zx, Ut, Hs, Cs, T_=-1) == -4
+    assert fwd(f((T * Bn, 176)), f((176, 44)), f(((T + 1) * Bn, 44)), f(((T + 1) * Bn, 44))) == -4   # H not a multiple of 8
+    assert b"multiple of 8" in L.chn_last_error()
+    assert fwd(zx, Ut, f(((T + 1) * Bn, H), B.I32), Cs) == -3                     # h must be F32 or BF16
+    assert L.chn_lstm_seq_workspace_bytes(0) == 0 and L.chn_lstm_seq_workspace_bytes(130) >= 256 + 3 * 4
+    assert L.chn_lstm_seq_supported(128, 44, B.F32) == -4 and L.chn_lstm_seq_supported(128, 776, B.F32) == -4
+    assert L.chn_lstm_seq_supported(128, 776, B.BF16) == -4                       # 776 is not a multiple of 16
+    U, dHs, G, dZ, dc0 = f((H, 4 * H)), f((T * Bn, H)), f((T * Bn, 4 * H)), f((T * Bn, 4 * H)), f((Bn, H))
+    bwd = lambda U, dHs, G, Cs, dZ, dc0, T_=T: L.chn_lstm_seq_bwd(r(U), r(dHs), r(G), r(Cs), None, r(dZ), r(dc0), T_, P, 1 << 30, None)
+    assert L.chn_lstm_seq_bwd(None, r(dHs), r(G), r(Cs), None, r(dZ), r(dc0), T, P, 1 << 30, None) == -1   # U missing
+    assert bwd(U, dHs, G, Cs, dZ, dc0, T_=4) == -4
+    assert bwd(f((40, 160)), f((T * Bn, 40)), f((T * Bn, 160)), f(((T + 1) * Bn, 40)), f((T * Bn, 160)), f((Bn, 40))) == -4   # H not a multiple of 16
+    assert b"multiple of 16" in L.chn_last_error()
+    assert L.chn_lstm_seq_bwd_supported(128, 784, B.F32) == -4 and L.chn_lstm_seq_bwd_supported(128, 1552, B.BF16) == -4   # wider than the registers hold
+    assert L.chn_lstm_seq_bwd_workspace_bytes(128, 672) == 256 + 256 + 2 * 4 * 42 * 42 * 2048
+    L.chn_lstm_seq_spin_limit(1 << 20)
+
+
 def _row_major(shape, isz):
     out, acc = [], isz
     for n in reversed(shape):
