@@ -230,3 +230,20 @@ def test_whole_sequence_backward_refusals_and_give_up():
     dHs, dZ, dc0, work = run_bwd(U, dh_in, gates, Cs, dc_last, T, dt, bufs)
     assert status_word(work) == 0
     check_bwd_against_oracle(U, dh_in, gates, Cs, dc_last, T, dt, dHs, dZ, dc0)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_whole_sequence_kernels_are_reproducible_bit_for_bit(dt):
+    """Every sum is taken in a fixed order (partial tiles in wave order, partial dh in sender order): two runs of
+    the same launch agree in every bit, whatever order the workgroups arrive in."""
+    Bn, H, T = 128, 672, 35
+    zx, bias, h0, c0, U = inputs(Bn, H, T, dt, 31)
+    first = [t.clone() for t in run(zx, bias, h0, c0, U, T, dt)[:3]]
+    for _ in range(2):
+        again = run(zx, bias, h0, c0, U, T, dt)[:3]
+        assert all(torch.equal(a, b) for a, b in zip(first, again))
+    Ub, dh_in, gates, Cs, dc_last = bwd_inputs(Bn, H, T, dt, 32)
+    first = [t.clone() for t in run_bwd(Ub, dh_in, gates, Cs, dc_last, T, dt)[:3]]
+    for _ in range(2):
+        again = run_bwd(Ub, dh_in, gates, Cs, dc_last, T, dt)[:3]
+        assert all(torch.equal(a, b) for a, b in zip(first, again))
