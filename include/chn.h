@@ -168,6 +168,12 @@ chn_status chn_reduce_axis_static(int op, const chn_array *in, int axis, int kee
  *              Motivation"'s training loop together with the refresh of the bf16 working copy, and
  *              the gradient never travels through memory
  * Unused optional arguments are NULL.  beta != 0 reads C before writing it.
+ * Operands are read in aligned pieces of up to 16 bytes.  Where the unit stride of A runs along M (of
+ * B: along N) and the rows are 8- or 16-byte aligned, the last piece of a row may reach past the row's
+ * last element, by less than the piece and never out of the piece's own aligned 16 bytes: what it
+ * brings (row padding, or the start of the next row) is multiplied into rows or columns that are not
+ * part of C and is never stored.  A short unit-stride extent that is not a multiple of 8 bytes (a
+ * gradient with 10 classes, say) is therefore best given rows padded to 16 bytes.
  * gelu / gelu' in the epilogue use a five-term rational erf (absolute error below 1.5e-7 in Phi) when C
  * is F32; when C is BF16 they are odd polynomials of the clamped argument (absolute error below 7e-5 in
  * Phi and 1.6e-4 in gelu': under the rounding of the bfloat16 result except in the negative tail, where

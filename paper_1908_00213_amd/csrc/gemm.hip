@@ -28,11 +28,16 @@ std::atomic<int> g_force_w8{-1};
 
 // Largest load piece (bytes) that is aligned for every row start of the operand and divides its
 // extent along the unit-stride dimension, so that a piece is never partly out of range.
-int piece_bytes(const void *p, int64_t ld_elems, int64_t extent_elems, int isz) {
+// overhang: the extent need not be a multiple of the piece.  The last piece of a row then also brings
+// what follows the row in memory (the padding of a pitched row, or the next row's first elements;
+// never another page: the piece is aligned to its own size).  That is harmless exactly where the
+// unit stride runs along M or N: those values become rows of A (columns of B) beyond M (N), and
+// the rows (columns) of C they feed are never stored.
+int piece_bytes(const void *p, int64_t ld_elems, int64_t extent_elems, int isz, bool overhang) {
   const uintptr_t a = reinterpret_cast<uintptr_t>(p);
   const int64_t ldb = ld_elems * isz, ext = extent_elems * isz;
-  if (a % 16 == 0 && ldb % 16 == 0 && ext % 16 == 0) return 16;
-  if (a % 8 == 0 && ldb % 8 == 0 && ext % 8 == 0) return 8;
+  if (a % 16 == 0 && ldb % 16 == 0 && (overhang || ext % 16 == 0)) return 16;
+  if (a % 8 == 0 && ldb % 8 == 0 && (overhang || ext % 8 == 0)) return 8;
   return isz;
 }
 
@@ -49,10 +54,15 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
   else return fail(CHN_ERR_STRIDE, "gemm: B needs a unit-stride dimension");
   if ((*a_kc && M > 1 && g->lda < K) || (!*a_kc && K > 1 && g->lda < M) || (*b_kc && N > 1 && g->ldb < K) || (!*b_kc && K > 1 && g->ldb < N))
     return fail(CHN_ERR_STRIDE, "gemm: overlapping (broadcast) operand rows are not supported");
-  const int pa = piece_bytes(A->data, g->lda, *a_kc ? K : M, isz);
-  const int pb = piece_bytes(B->data, g->ldb, *b_kc ? K : N, isz);
-  g->piece = pa < pb ? pa : pb;
-  if (K == 0) { *a_kc = *b_kc = true; g->piece = isz; }  // nothing to multiply: every load is redirected to zeros
+  const int pa = piece_bytes(A->data, g->lda, *a_kc ? K : M, isz, false);
+  const int pb = piece_bytes(B->data, g->ldb, *b_kc ? K : N, isz, false);
+  g->piece_exact = pa < pb ? pa : pb;
+  // the kernels that stage operands in registers take pieces that hang over the end of a row of an
+  // operand whose unit stride runs along M or N
+  const int qa = piece_bytes(A->data, g->lda, *a_kc ? K : M, isz, !*a_kc);
+  const int qb = piece_bytes(B->data, g->ldb, *b_kc ? K : N, isz, !*b_kc);
+  g->piece = qa < qb ? qa : qb;
+  if (K == 0) { *a_kc = *b_kc = true; g->piece = g->piece_exact = isz; }  // nothing to multiply: every load is redirected to zeros
   g->M = (int)M; g->N = (int)N; g->K = (int)K;
   return CHN_OK;
 }
@@ -63,7 +73,7 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
 bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
   const bool dma_on = g_force_direct.load(std::memory_order_relaxed) != 0;
   const int64_t max_ld = (int64_t)0xffffffffu / (256 * isz);
-  return dma_on && g.piece == 16 && g.K > 0 && g.lda < max_ld && g.ldb < max_ld && (isz == 2 || a_kc || b_kc);
+  return dma_on && g.piece_exact == 16 && g.K > 0 && g.lda < max_ld && g.ldb < max_ld && (isz == 2 || a_kc || b_kc);
 }
 
 // Macro tile (3: 256x128, 2: 256x256, 1: 128x128, 0: 64x64) and number of K splits, chosen by a small cost model

@@ -80,9 +80,10 @@ __device__ __forceinline__ void global_store(uintptr_t addr, V v) {
 }
 
 // Load one 16-byte chunk starting at address p in pieces of PB bytes without any branch: a piece
-// whose first element index is >= n_valid is read from the zero chunk instead.  Pieces never straddle
-// the valid range because the host only picks a piece size that divides the operand's extent along
-// its unit-stride dimension.
+// whose first element index is >= n_valid is read from the zero chunk instead.  Along K a piece never
+// straddles the valid range, because there the host only picks a piece size that divides the operand's
+// extent; along M or N the last piece of a row may bring elements from beyond the row's end, which
+// only ever reach rows or columns of C that are not stored.
 template <typename T, int PB>
 __device__ __forceinline__ uint4 load_chunk(uintptr_t p, int n_valid) {
   constexpr int PE = PB / (int)sizeof(T);   // elements per piece

@@ -74,6 +74,11 @@ struct RPlan {
 // COL kernel block shapes (column groups x row lanes = 256 threads): 16 x 16 for the large streaming
 // case (more column blocks, hence fewer row splits and a smaller second pass), 64 x 4 otherwise.
 constexpr int kColTXWide = 16, kColTXMid = 32, kColTXNarrow = 64;
+// A stack of at most kShortRows rows that fits the caches (a bias gradient: the column sums of one
+// layer's output gradient) takes a single launch instead: blocks 4 column groups wide and 64 row lanes
+// tall, every lane's loads (up to 16) in flight at once, so the launch lasts about one memory latency.
+constexpr int kColTXShort = 4;
+constexpr int64_t kShortRows = 2048, kShortBytes = 8 << 20;
 
 chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
   CHN_TRY(validate(in, "in", false));
@@ -125,6 +130,10 @@ chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
     if (p->len <= 64) s = 1;        // a short stack of rows (e.g. per-row-block sums): one launch, a few loads per thread
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
+    if (p->vec && s > 1 && p->len <= kShortRows && p->O * p->len * p->I * isz <= kShortBytes) {
+      p->tx = kColTXShort;
+      s = 1;
+    }
     p->split = (int)s;
     p->rows_per_split = (p->len + s - 1) / s;
     p->split = (int)((p->len + p->rows_per_split - 1) / p->rows_per_split);
@@ -216,7 +225,23 @@ __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *ou
   if (col < I) {
     const Tin *p = in + o * sO + col;
     int64_t r = r_begin + ty;
-    if constexpr (VEC) {
+    if constexpr (VEC && kColTX == kColTXShort) {
+      constexpr int U = 16;
+      for (; r < r_end; r += U * kColTY) {
+        Vec16<Tin> x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {          // a lane past the end re-reads its first row and drops it
+          const int64_t rr = r + u * kColTY;
+          x[u].load(p + (rr < r_end ? rr : r) * sR);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (r + u * kColTY < r_end) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[i] = fold<OP>(acc[i], x[u].get(i));
+          }
+      }
+    } else if constexpr (VEC) {
       for (; r + 3 * kColTY < r_end; r += 4 * kColTY) {
         Vec16<Tin> x[4];
 #pragma unroll
@@ -243,9 +268,23 @@ __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *ou
       for (; r < r_end; r += kColTY) acc[0] = fold<OP>(acc[0], Elem<Tin>::load(p + r * sR));
     }
   }
-  __shared__ float part[kColTY][kColTX * N + 1];
+  // The short shape folds its 16 row lanes per wave with butterflies first (lanes of one column
+  // group are 4 apart), so that only one partial per wave goes through LDS.
+  constexpr int kParts = kColTX == kColTXShort ? 4 : kColTY;
+  __shared__ float part[kParts][kColTX * N + 1];
+  if constexpr (kColTX == kColTXShort) {
 #pragma unroll
-  for (int i = 0; i < N; ++i) part[ty][tx * N + i] = acc[i];
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+      for (int off = kColTX; off < 64; off <<= 1) acc[i] = fold<OP>(acc[i], __shfl_xor(acc[i], off));
+    if (threadIdx.x % 64 < kColTX) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) part[threadIdx.x / 64][tx * N + i] = acc[i];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) part[ty][tx * N + i] = acc[i];
+  }
   __syncthreads();
   if (ty == 0 && col < I) {
     Tout *q = out + (int64_t)blockIdx.y * out_split_stride + o * I + col;
@@ -253,7 +292,7 @@ __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *ou
     for (int i = 0; i < N; ++i) {
       float a = part[0][tx * N + i];
 #pragma unroll
-      for (int y = 1; y < kColTY; ++y) a = fold<OP>(a, part[y][tx * N + i]);
+      for (int y = 1; y < kParts; ++y) a = fold<OP>(a, part[y][tx * N + i]);
       Elem<Tout>::store(q + i, a);
     }
   }
@@ -284,7 +323,8 @@ chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64
   const int64_t cpb = (int64_t)tx * n;
   dim3 grid((unsigned)((I + cpb - 1) / cpb), (unsigned)split, (unsigned)O);
   if (O > 65535) return fail(CHN_ERR_SHAPE, "reduce: outer extent %lld too large for the column kernel", (long long)O);
-  if (vec && tx == kColTXWide) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXWide>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  if (vec && tx == kColTXShort) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXShort>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else if (vec && tx == kColTXWide) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXWide>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else if (vec && tx == kColTXMid) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXMid>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);

@@ -115,7 +115,10 @@ class MLPTrainer:
         self.h = [None] + [mk(batch, self.sizes[l + 1], dt=adt) for l in range(n - 1)]
         self.z = [None] + [mk(batch, self.sizes[l + 1], dt=adt) if act == "gelu" else None for l in range(n - 1)]
         self.logits = mk(batch, self.sizes[-1])
-        self.dv = [None] + [mk(batch, self.sizes[l + 1], dt=adt) for l in range(n)]   # gradient wrt layer l's output
+        # gradient wrt layer l's output; rows padded to 16 bytes, so that a narrow one (the logits') is still
+        # read in 16-byte pieces where it is the transposed operand of the weight-gradient product
+        epr = 8 if lowp else 4
+        self.dv = [None] + [mk(batch, (self.sizes[l + 1] + epr - 1) // epr * epr, dt=adt)[:, :self.sizes[l + 1]] for l in range(n)]
         self.dW = [mk(*w.shape) for w in self.W]
         self.db = [mk(*b.shape) for b in self.b]
         self.loss = mk(())

@@ -56,6 +56,38 @@ def test_gemm_layouts(dt, layout, shape):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(10, 1000, 1024), (10, 37, 200), (77, 130, 96), (203, 5, 64), (1, 3, 40)])
+def test_gemm_transposed_operands_with_padded_rows(dt, shape):
+    """Operands whose unit stride runs along M / N, with rows padded to 16 bytes and an extent that is not
+    a multiple of the load piece: the last piece of every row also brings the padding (NaN here), which
+    must reach nothing that is stored.  (The weight-gradient product of a 10-class layer has this shape.)"""
+    M, N, K = shape
+    epr = 8 if dt == "bf16" else 4
+    pm, pn = (M + epr - 1) // epr * epr, (N + epr - 1) // epr * epr + epr
+    a, b = rnd((K, M), dt), rnd((K, N), dt)
+    abuf = np.full((K, pm), np.nan, np.float32); abuf[:, :M] = a
+    bbuf = np.full((K, pn), np.nan, np.float32); bbuf[:, :N] = b
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    Ad = torch.from_numpy(abuf).cuda().to(tdt)[:, :M].t()      # (NaN and bf16-exact values survive the cast)
+    Bd = torch.from_numpy(bbuf).cuda().to(tdt)[:, :N]
+    ref, S = O.gemm(a.T, b), O.gemm(np.abs(a.T), np.abs(b))
+    tol = TOL_BF16 if dt == "bf16" else TOL_SUM
+    for splits in (-1, 2):
+        B.gemm_plan_override(-1, splits)
+        try:
+            need = B.gemm_workspace_bytes(Ad, Bd, empty((M, N)))
+            out = B.gemm(Ad, Bd, empty((M, N)), ws=ws(need) if need else None)
+        finally:
+            B.gemm_plan_override()
+        check(host(out), ref, tol, S, "padded transposed operands %s %s splits %d" % (shape, dt, splits))
+    # the same buffer as the K-contiguous operand of another product (the input-gradient layout): along K
+    # no piece may overhang, or the padding would be summed
+    w = rnd((M, 24), dt)
+    out = B.gemm(Ad.t(), dev(w, dt), empty((K, 24)))
+    check(host(out), O.gemm(a, w), tol, O.gemm(np.abs(a), np.abs(w)), "padded rows along K %s %s" % (shape, dt))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nt", "nn", "tn"])
 @pytest.mark.parametrize("shape", [(3700, 3590, 130), (1500, 1400, 136), (300, 200, 4100)])
 def test_gemm_big_tiles_exact_integers(dt, layout, shape):

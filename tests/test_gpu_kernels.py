@@ -191,7 +191,8 @@ def _reduce(op, x_np, x_dev, axis, dt_out="f32", keep=False):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(513, 1030), (4100, 260), (32, 100), (1024, 10), (7, 4099), (1, 50), (50, 1), (2500, 3)])
+@pytest.mark.parametrize("shape", [(513, 1030), (4100, 260), (32, 100), (1024, 10), (7, 4099), (1, 50), (50, 1), (2500, 3),
+                                   (1024, 1000), (1000, 264), (2048, 72), (130, 4096), (65, 8)])
 def test_reduce_2d_both_axes(dt, shape):
     x = rnd(shape, dt)
     tol = tol_for(dt, "f32", TOL_SUM)
@@ -206,6 +207,26 @@ def test_reduce_2d_both_axes(dt, shape):
     check(got, ref, tol, O.reduce_axis("sum", np.abs(x.T), 0), "sum T axis 0")
     got, ref = _reduce("sum", x.T, xt, 1, keep=True)
     check(got, ref, tol, O.reduce_axis("sum", np.abs(x.T), 1, True), "sum T axis 1 keepdims")
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_reduce_short_cache_resident_columns_take_one_launch(dt):
+    """The column sums of a short stack of rows (a bias gradient) need no workspace, i.e. no second launch."""
+    tol = tol_for(dt, "f32", TOL_SUM)
+    for shape, axis in [((1024, 1000), 0), ((1000, 1000), 0), ((2048, 512), 0), ((3, 300, 64), 1), ((5, 1031, 24), 1)]:
+        x = rnd(shape, dt)
+        d = dev(x, dt)
+        assert B.reduce_axis_workspace_bytes(d, axis) == 0
+        got, ref = _reduce("sum", x, d, axis)
+        check(got, ref, tol, O.reduce_axis("sum", np.abs(x), axis), "short columns %s" % (shape,))
+        got, ref = _reduce("max", x, d, axis)
+        assert np.array_equal(got, ref)
+    x = RNG.integers(-4, 5, size=(1000, 1000)).astype(np.float32)
+    got, ref = _reduce("sum", x, dev(x, dt), 0)
+    assert np.array_equal(got, ref)
+    x = rnd((1024, 1000), dt)
+    got, ref = _reduce("sum", x[:, 8:968], dev(x, dt)[:, 8:968], 0)  # a pitched column slice
+    check(got, ref, tol, O.reduce_axis("sum", np.abs(x[:, 8:968]), 0), "pitched short columns")
 
 
 def test_reduce_exact_integers_bit_equal():
