@@ -130,7 +130,7 @@ chn_status make_rplan(const chn_array *in, int axis, RPlan *p) {
     if (p->len <= 64) s = 1;        // a short stack of rows (e.g. per-row-block sums): one launch, a few loads per thread
     if (s < 1) s = 1;
     if (s > 1024) s = 1024;
-    if (p->vec && s > 1 && p->len <= kShortRows && p->O * p->len * p->I * isz <= kShortBytes) {
+    if (s > 1 && p->len <= kShortRows && p->O * p->len * p->I * isz <= (p->vec ? kShortBytes : kShortBytes / 8)) {
       p->tx = kColTXShort;
       s = 1;
     }
@@ -225,20 +225,25 @@ __global__ __launch_bounds__(256) void reduce_col_kernel(const Tin *in, Tout *ou
   if (col < I) {
     const Tin *p = in + o * sO + col;
     int64_t r = r_begin + ty;
-    if constexpr (VEC && kColTX == kColTXShort) {
+    if constexpr (kColTX == kColTXShort) {
       constexpr int U = 16;
       for (; r < r_end; r += U * kColTY) {
-        Vec16<Tin> x[U];
+        std::conditional_t<VEC, Vec16<Tin>, float> x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {          // a lane past the end re-reads its first row and drops it
           const int64_t rr = r + u * kColTY;
-          x[u].load(p + (rr < r_end ? rr : r) * sR);
+          const Tin *q = p + (rr < r_end ? rr : r) * sR;
+          if constexpr (VEC) x[u].load(q); else x[u] = Elem<Tin>::load(q);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
           if (r + u * kColTY < r_end) {
+            if constexpr (VEC) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) acc[i] = fold<OP>(acc[i], x[u].get(i));
+              for (int i = 0; i < N; ++i) acc[i] = fold<OP>(acc[i], x[u].get(i));
+            } else {
+              acc[0] = fold<OP>(acc[0], x[u]);
+            }
           }
       }
     } else if constexpr (VEC) {
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(256) void reduce_gen_kernel(const Tin *in, Tout *ou
 template <int OP, typename Tin, typename Tout>
 chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64_t R, int64_t I, int64_t sO, int64_t sR,
                       int split, int64_t rps, int64_t split_stride, bool vec, int tx, hipStream_t st) {
-  if (!vec) tx = kColTXNarrow;
+  if (!vec && tx != kColTXShort) tx = kColTXNarrow;
   const int n = vec ? 16 / (int)sizeof(Tin) : 1;
   const int64_t cpb = (int64_t)tx * n;
   dim3 grid((unsigned)((I + cpb - 1) / cpb), (unsigned)split, (unsigned)O);
@@ -327,6 +332,7 @@ chn_status launch_col(const Tin *in, Tout *out, const RPlan &p, int64_t O, int64
   else if (vec && tx == kColTXWide) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXWide>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else if (vec && tx == kColTXMid) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXMid>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else if (vec) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, true, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
+  else if (tx == kColTXShort) hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false, kColTXShort>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   else hipLaunchKernelGGL((reduce_col_kernel<OP, Tin, Tout, false, kColTXNarrow>), grid, dim3(256), 0, st, in, out, R, I, sO, sR, rps, split_stride);
   (void)p;
   return check_launch("reduce col");

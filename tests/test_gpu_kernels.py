@@ -192,7 +192,7 @@ def _reduce(op, x_np, x_dev, axis, dt_out="f32", keep=False):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(513, 1030), (4100, 260), (32, 100), (1024, 10), (7, 4099), (1, 50), (50, 1), (2500, 3),
-                                   (1024, 1000), (1000, 264), (2048, 72), (130, 4096), (65, 8)])
+                                   (1024, 1000), (1000, 264), (2048, 72), (130, 4096), (65, 8), (300, 333), (2000, 5)])
 def test_reduce_2d_both_axes(dt, shape):
     x = rnd(shape, dt)
     tol = tol_for(dt, "f32", TOL_SUM)
