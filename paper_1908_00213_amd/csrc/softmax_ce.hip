@@ -315,7 +315,9 @@ __global__ __launch_bounds__(256) void sce_fused_reg_kernel(const T *z, int64_t 
 // A whole small problem (few classes, a few thousand rows) in one launch of one block: count the
 // valid rows, then every thread takes rows tid, tid + 1024, ... from log-sum-exp to gradient, then the
 // mean loss in a fixed order.  For the small MLP steps, which are bound by the number of launches.
-template <typename T, typename TO, typename L>
+// A row (at most CR classes) is held in registers: its loads are all in flight at once and it is read
+// from memory once.
+template <typename T, typename TO, typename L, int CR>
 __global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pitch, const L *labels, int64_t N, int64_t C,
                                                          int64_t ignore, float upstream, float *loss_mean, float *lse_out,
                                                          TO *dz, int64_t dpitch) {
@@ -333,19 +335,30 @@ __global__ __launch_bounds__(1024) void sce_small_kernel(const T *z, int64_t pit
   float s = 0.0f;
   for (int64_t n = threadIdx.x; n < N; n += 1024) {
     const T *p = z + n * pitch;
-    float m = -INFINITY;
-    for (int64_t c = 0; c < C; ++c) m = fmaxf(m, Elem<T>::load(p + c));
-    float e = 0.0f;
-    for (int64_t c = 0; c < C; ++c) e += expf(Elem<T>::load(p + c) - m);
-    const float lse = m + logf(e);
     const int64_t t = row_label(labels, n, ignore, C);
+    float x[CR];
+#pragma unroll
+    for (int c = 0; c < CR; ++c) x[c] = c < C ? Elem<T>::load(p + c) : -INFINITY;   // exp(-inf - m) = 0
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < CR; ++c) m = fmaxf(m, x[c]);
+    float e = 0.0f, xt = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CR; ++c) {
+      if (c < C) e += expf(x[c] - m);
+      xt = c == t ? x[c] : xt;
+    }
+    const float lse = m + logf(e);
     if (lse_out) lse_out[n] = lse;
-    if (t != ignore) s += lse - Elem<T>::load(p + t);
+    if (t != ignore) s += lse - xt;
     const float scale = t == ignore ? 0.0f : scale_all;
     TO *q = dz + n * dpitch;
-    for (int64_t c = 0; c < C; ++c) {
-      const float pr = scale == 0.0f ? 0.0f : expf(Elem<T>::load(p + c) - lse);
-      Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
+#pragma unroll
+    for (int c = 0; c < CR; ++c) {
+      if (c < C) {
+        const float pr = scale == 0.0f ? 0.0f : expf(x[c] - lse);
+        Elem<TO>::store(q + c, scale * (pr - (c == t ? 1.0f : 0.0f)));
+      }
     }
   }
   s = wave_sum(s);
@@ -474,8 +487,12 @@ void launch_fused(const Common &c, const chn_array *logits, const chn_array *lab
 template <typename T, typename TO, typename L>
 void launch_small(const Common &c, const chn_array *logits, const chn_array *labels, int64_t ignore, float upstream, float *loss_mean,
                   float *lse, const chn_array *dl, int64_t dpitch, hipStream_t st) {
-  hipLaunchKernelGGL((sce_small_kernel<T, TO, L>), dim3(1), dim3(1024), 0, st, static_cast<const T *>(logits->data), c.pitch,
-                     static_cast<const L *>(labels->data), c.N, c.C, ignore, upstream, loss_mean, lse, static_cast<TO *>(dl->data), dpitch);
+  if (c.C <= 16)
+    hipLaunchKernelGGL((sce_small_kernel<T, TO, L, 16>), dim3(1), dim3(1024), 0, st, static_cast<const T *>(logits->data), c.pitch,
+                       static_cast<const L *>(labels->data), c.N, c.C, ignore, upstream, loss_mean, lse, static_cast<TO *>(dl->data), dpitch);
+  else
+    hipLaunchKernelGGL((sce_small_kernel<T, TO, L, 64>), dim3(1), dim3(1024), 0, st, static_cast<const T *>(logits->data), c.pitch,
+                       static_cast<const L *>(labels->data), c.N, c.C, ignore, upstream, loss_mean, lse, static_cast<TO *>(dl->data), dpitch);
 }
 
 }  // namespace
