@@ -62,7 +62,8 @@ chn_status classify(const chn_array *A, const chn_array *B, GemmArgs *g, bool *a
   const int qa = piece_bytes(A->data, g->lda, *a_kc ? K : M, isz, !*a_kc);
   const int qb = piece_bytes(B->data, g->ldb, *b_kc ? K : N, isz, !*b_kc);
   g->piece = qa < qb ? qa : qb;
-  if (K == 0) { *a_kc = *b_kc = true; g->piece = g->piece_exact = isz; }  // nothing to multiply: every load is redirected to zeros
+  g->piece_a = qa; g->piece_b = qb;
+  if (K == 0) { *a_kc = *b_kc = true; g->piece = g->piece_exact = g->piece_a = g->piece_b = isz; }  // nothing to multiply: every load is redirected to zeros
   g->M = (int)M; g->N = (int)N; g->K = (int)K;
   return CHN_OK;
 }

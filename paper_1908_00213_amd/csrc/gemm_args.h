@@ -20,6 +20,7 @@ struct GemmArgs {
   void *pre;
   int64_t ldpre;
   int piece;              // bytes per global load piece (16, 8 or the item size), common to A and B
+  int piece_a, piece_b;   // what A and B would allow each (the 64x64 tile takes them apart when one is element-wise and the other whole)
   int piece_exact;        // the same when no piece may hang over the end of a row (direct-copy kernels)
   int tiles_m, tiles_n;
   int tile;               // macro tile: 2 = 256x256, 1 = 128x128, 0 = 64x64

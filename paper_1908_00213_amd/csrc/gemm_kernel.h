@@ -677,7 +677,8 @@ __device__ __forceinline__ void write_out(const GemmArgs &g, floatx16 (&acc)[TM]
   }
 }
 
-template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
+// PB / PB2: bytes per global load piece of A / of B
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB, int PB2 = PB>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int BK = 128 / sizeof(T);               // elements of k per tile step
@@ -688,7 +689,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const int split = tp.split, m0 = tp.tm * BM, n0 = tp.tn * BN;
 
   TileLoader<T, BM, A_KC, PB> la;
-  TileLoader<T, BN, B_KC, PB> lb;
+  TileLoader<T, BN, B_KC, PB2> lb;
   la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
   lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
 
@@ -1351,11 +1352,11 @@ chn_status launch_dma(const GemmArgs &g, hipStream_t st) {
   }
 }
 
-template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB>
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, int PB, int PB2 = PB>
 chn_status launch_piece(const GemmArgs &g, hipStream_t st) {
   constexpr int LDS = 2 * (64 * TM + 64 * TN) * 128;
   static_assert(4 * kEpiStageBytes<TM, TN> <= LDS, "epilogue staging must fit in the operand stages");
-  auto kern = gemm_kernel<T, TM, TN, A_KC, B_KC, PB>;
+  auto kern = gemm_kernel<T, TM, TN, A_KC, B_KC, PB, PB2>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     if (LDS > 64 * 1024) {
@@ -1376,6 +1377,11 @@ chn_status launch_piece(const GemmArgs &g, hipStream_t st) {
 
 template <typename T, int TM, int TN, bool A_KC, bool B_KC>
 chn_status launch_tile(const GemmArgs &g, hipStream_t st) {
+  if constexpr (TM == 1) {
+    // one operand that only allows element-wise loads (a K of 10, say) does not slow down the other's
+    if (g.piece_a == (int)sizeof(T) && g.piece_b == 16) return launch_piece<T, 1, 1, A_KC, B_KC, (int)sizeof(T), 16>(g, st);
+    if (g.piece_a == 16 && g.piece_b == (int)sizeof(T)) return launch_piece<T, 1, 1, A_KC, B_KC, 16, (int)sizeof(T)>(g, st);
+  }
   if (g.piece == 16) return launch_piece<T, TM, TN, A_KC, B_KC, 16>(g, st);
   if (g.piece == 8) return launch_piece<T, TM, TN, A_KC, B_KC, 8>(g, st);
   if constexpr (TM == 1) return launch_piece<T, 1, 1, A_KC, B_KC, (int)sizeof(T)>(g, st);

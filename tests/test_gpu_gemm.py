@@ -35,7 +35,7 @@ def operands(M, N, K, layout, dt, gen=rnd):
 
 
 SHAPES = [(64, 64, 64), (100, 70, 50), (257, 129, 100), (130, 300, 650), (32, 10, 100), (10, 1000, 33),
-          (600, 520, 96), (1, 1, 1), (5, 7, 3)]
+          (600, 520, 96), (1, 1, 1), (5, 7, 3), (200, 64, 10), (72, 136, 6)]
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])

@@ -467,6 +467,7 @@ def test_softmax_ce_and_embedding_never_follow_a_stray_index(N, Cn, lab):
 
 
 @pytest.mark.parametrize("N,Cn,dt,lab", [(37, 10, "f32", np.int32), (1024, 10, "f32", np.int64), (3000, 33, "bf16", np.int32),   # one block
+                                         (100, 16, "f32", np.int32), (100, 17, "f32", np.int32), (2000, 64, "f32", np.int64), (2, 1, "f32", np.int32),
                                          (8193, 10, "f32", np.int32), (300, 1000, "f32", np.int64), (70, 4100, "f32", np.int32),
                                          (129, 1000, "bf16", np.int32), (33, 2051, "bf16", np.int64), (5, 65, "f32", np.int32),
                                          # long rows: held in registers between scan and gradient up to 12288 classes, streamed twice beyond
