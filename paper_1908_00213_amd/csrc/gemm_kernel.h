@@ -126,9 +126,14 @@ struct TileLoader {
   int K;
   uintptr_t pf_ptr;       // cache-line prefetch: this thread's line of the tile at k0 = 0
   int pf_lim;             // KC: K if the thread's row exists, else 0;  MC: K - (its k row) or 0
+  int tid;                // MC: the thread's number in the dealing of transpose blocks
 
-  __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K_) {
+  // shift: a small tile has fewer transpose blocks than the workgroup has threads (64 for 64 rows of
+  // bf16: one wave's worth); rotating the dealing by `shift` threads puts the second operand's blocks
+  // on waves -- and so on SIMDs -- that the first operand's leave idle.
+  __device__ __forceinline__ void init(const T *base, int64_t ld, int rows_total, int row0, int K_, int shift = 0) {
     K = K_;
+    tid = ((int)threadIdx.x + shift) & 255;
     kstride = ld * (int64_t)sizeof(T);
     if constexpr (KC) {   // one 128-byte line per tile row: thread t takes row t
       const int row = row0 + (int)threadIdx.x;
@@ -151,7 +156,7 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        const int blk = threadIdx.x + b * 256;
+        const int blk = tid + b * 256;
         const int kg = blk & 7, mc = blk >> 3;
         const int m = row0 + mc * EPC;
         ptr[b] = reinterpret_cast<uintptr_t>(base + (int64_t)(kg * EPC) * ld + m);
@@ -170,7 +175,7 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        const int kg = (threadIdx.x + b * 256) & 7;
+        const int kg = (tid + b * 256) & 7;
 #pragma unroll
         for (int j = 0; j < EPC; ++j) {
           const int k = k0 + kg * EPC + j;
@@ -199,7 +204,7 @@ struct TileLoader {
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
-        const int blk = threadIdx.x + b * 256;
+        const int blk = tid + b * 256;
         if constexpr (NBLK % 256 != 0) {   // only small tiles have idle threads here; a branch in the
           if (blk >= NBLK) continue;       // big tile's loop would split its scheduling region
         }
@@ -691,7 +696,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   TileLoader<T, BM, A_KC, PB> la;
   TileLoader<T, BN, B_KC, PB2> lb;
   la.init(static_cast<const T *>(g.A), g.lda, g.M, m0, g.K);
-  lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K);
+  lb.init(static_cast<const T *>(g.B), g.ldb, g.N, n0, g.K, 128);
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
