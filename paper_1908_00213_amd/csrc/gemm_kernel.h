@@ -118,8 +118,16 @@ struct TileLoader {
   static constexpr int NS = ROWS / 32;                      // ROWS * 8 chunks / 256 threads
   static constexpr int NBLK = 8 * ROWS / EPC;               // EPC x EPC transpose blocks per tile
   static constexpr int NB = (NBLK + 255) / 256;             // ... per thread
+  // A 64-row tile with unit stride along M/N has fewer transpose blocks (EPC k x EPC m) than the
+  // workgroup has threads: 64 of bf16, 128 of fp32.  Every load instruction of a wave costs the memory
+  // pipeline the same whether its lanes fetch data or are parked on the zero chunk, so CP = 4 (2)
+  // threads share a block instead: each loads two of its k-rows and writes, for every m, the 4 (8)
+  // bytes -- two k -- it can form.  A wave takes all eight k-groups of 2 (4) m-chunks, which spreads
+  // its narrow LDS writes over all banks, two lanes each.
+  static constexpr bool COOP = !KC && ROWS == 64;
+  static constexpr int CP = COOP ? 256 / NBLK : 1;
   static constexpr int NSLOT = KC ? NS : NB;
-  uint4 reg[2][KC ? NS : NB * EPC];   // two sets of staging registers (the second only where a kernel looks two tiles ahead)
+  uint4 reg[2][KC ? NS : COOP ? 2 : NB * EPC];   // two sets of staging registers (the second only where a kernel looks two tiles ahead)
   uintptr_t ptr[NSLOT];   // address of the slot's first element for k0 = 0
   int lim[NSLOT];         // KC: K - (k offset of the slot) for valid rows, else 0;  MC: rows_total - m or 0
   int64_t kstride;        // bytes between consecutive k (MC only)
@@ -153,6 +161,10 @@ struct TileLoader {
         ptr[i] = reinterpret_cast<uintptr_t>(base + (int64_t)row * ld + kc);
         lim[i] = row < rows_total ? K - kc : 0;
       }
+    } else if constexpr (COOP) {
+      const int m = row0 + coop_mc() * EPC;
+      ptr[0] = reinterpret_cast<uintptr_t>(base + (int64_t)(coop_kg() * EPC + 2 * coop_part()) * ld + m);
+      lim[0] = rows_total - m;
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
@@ -164,6 +176,10 @@ struct TileLoader {
       }
     }
   }
+  // COOP: which quarter (two k-rows) of which block (k-group, m-chunk) the thread handles
+  __device__ __forceinline__ int coop_part() const { return threadIdx.x % CP; }
+  __device__ __forceinline__ int coop_kg() const { return (threadIdx.x / CP) & 7; }
+  __device__ __forceinline__ int coop_mc() const { return (8 / CP) * (threadIdx.x >> 6) + (threadIdx.x & 63) / (8 * CP); }
 
   // issue the global loads of the tile whose first k is k0 (into register set SET)
   template <int SET = 0>
@@ -172,6 +188,12 @@ struct TileLoader {
 #pragma unroll
       for (int i = 0; i < NS; ++i)
         reg[SET][i] = load_chunk<T, PB>(ptr[i] + (int64_t)k0 * (int64_t)sizeof(T), lim[i] - k0);
+    } else if constexpr (COOP) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int k = k0 + coop_kg() * EPC + 2 * coop_part() + j;
+        reg[SET][j] = load_chunk<T, PB>(ptr[0] + (int64_t)(k0 + j) * kstride, k < K ? lim[0] : 0);
+      }
     } else {
 #pragma unroll
       for (int b = 0; b < NB; ++b) {
@@ -200,6 +222,19 @@ struct TileLoader {
       for (int i = 0; i < NS; ++i) {
         const int s = threadIdx.x + i * 256;
         *reinterpret_cast<uint4 *>(lds + lds_off<T>(s >> 3, s & 7)) = reg[SET][i];
+      }
+    } else if constexpr (COOP) {
+      const int kg = coop_kg(), row0l = coop_mc() * EPC, part = coop_part();
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        // k = 2 part and 2 part + 1 of row m = e of the block
+        char *q = lds + lds_off<T>(row0l + e, kg);
+        if constexpr (sizeof(T) == 2) {
+          const uint32_t lo = (&reg[SET][0].x)[e >> 1], hi = (&reg[SET][1].x)[e >> 1];
+          *reinterpret_cast<uint32_t *>(q + part * 4) = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
+        } else {
+          *reinterpret_cast<uint2 *>(q + part * 8) = make_uint2((&reg[SET][0].x)[e], (&reg[SET][1].x)[e]);
+        }
       }
     } else {
 #pragma unroll
