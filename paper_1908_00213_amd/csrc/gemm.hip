@@ -87,7 +87,7 @@ bool direct_copy_fits(const GemmArgs &g, int isz, bool a_kc, bool b_kc) {
 // to the split candidates).
 void plan(GemmArgs *g, int isz, bool a_kc, bool b_kc, bool allow_split, bool big_unsplit = false) {
   // microseconds per tile step [tile][0: both operands K-contiguous, 1: one, 2: none] and per block
-  static const double step_bf16[3][3] = {{0.27, 0.50, 0.56}, {0.83, 1.08, 1.00}, {1.90, 2.25, 2.70}};
+  static const double step_bf16[3][3] = {{0.27, 0.33, 0.56}, {0.57, 0.68, 1.12}, {1.90, 2.25, 2.70}};
   static const double step_f32[3][3] = {{0.52, 0.62, 0.65}, {1.95, 2.40, 2.10}, {6.90, 7.50, 7.90}};
   static const double fixed_bf16[3] = {1.0, 3.0, 12.0}, fixed_f32[3] = {1.5, 4.0, 18.0};
   const double step_direct = 1.48;                        // bf16 direct-copy kernel, any layout
