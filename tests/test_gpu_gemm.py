@@ -72,14 +72,14 @@ def test_gemm_transposed_operands_with_padded_rows(dt, shape):
     Bd = torch.from_numpy(bbuf).cuda().to(tdt)[:, :N]
     ref, S = O.gemm(a.T, b), O.gemm(np.abs(a.T), np.abs(b))
     tol = TOL_BF16 if dt == "bf16" else TOL_SUM
-    for splits in (-1, 2):
-        B.gemm_plan_override(-1, splits)
+    for tile, splits in ((-1, -1), (-1, 2), (1, -1), (2, -1), (2, 2)):      # also on the larger register-staged tiles
+        B.gemm_plan_override(tile, splits, 0)
         try:
             need = B.gemm_workspace_bytes(Ad, Bd, empty((M, N)))
             out = B.gemm(Ad, Bd, empty((M, N)), ws=ws(need) if need else None)
         finally:
             B.gemm_plan_override()
-        check(host(out), ref, tol, S, "padded transposed operands %s %s splits %d" % (shape, dt, splits))
+        check(host(out), ref, tol, S, "padded transposed operands %s %s tile %d splits %d" % (shape, dt, tile, splits))
     # the same buffer as the K-contiguous operand of another product (the input-gradient layout): along K
     # no piece may overhang, or the padding would be summed
     w = rnd((M, 24), dt)
