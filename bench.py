@@ -219,13 +219,18 @@ def bench_mlp(torch, B, steps_mod, w, lowp, timer, steps, warmup, probe=False, g
         for p in probes:
             for i, v in enumerate(p.per_call_seconds()):
                 per[i] += v / len(probes)
+        empty = probes[0].empty_pair_seconds()
+        # "us": the event bracket as read; "us_net": minus what an empty bracket reads (the launch itself;
+        # for a product of a few microseconds the bracket's own cost is a large part of "us")
         res["gemm_calls"] = [{"call": lab, "M": M, "N": N, "K": K, "us": round(t_ * 1e6, 1),
-                              "TFLOP/s": round(2.0 * M * N * K / t_ / 1e12, 1)}
+                              "TFLOP/s": round(2.0 * M * N * K / t_ / 1e12, 1),
+                              "us_net": round(max(t_ - empty, 1e-7) * 1e6, 1),
+                              "TFLOP/s_net": round(2.0 * M * N * K / max(t_ - empty, 1e-7) / 1e12, 1)}
                              for (lab, M, N, K), t_ in zip(gemm_shapes_mlp(w.sizes, w.batch, fused_update), per)]
         res["gemm_seconds_per_step"] = sum(per)
         res["gemm_flops_per_step"] = sum(2.0 * M * N * K for _, M, N, K in gemm_shapes_mlp(w.sizes, w.batch, fused_update))
         res["gemm_probe_steps"] = per_batch * nb
-        res["event_pair_empty_us"] = round(probes[0].empty_pair_seconds() * 1e6, 2)
+        res["event_pair_empty_us"] = round(empty * 1e6, 2)
     res.update({"ms_per_step": s * 1e3, "steps_per_s": 1.0 / s, "loss": float(tr.loss.cpu()),
                 "TFLOP/s": w.flops_per_step() / s / 1e12, "launch_calls_per_step": tr.n_launch_calls(xs[0], ts[0])})
     return res
@@ -523,11 +528,14 @@ def main():
         w3 = W.config3()
         for lowp in (False, True):
             for graph in (False, True):
-                r = bench_mlp(torch, B, steps_mod, w3, lowp, timer, 100, 10, graph=graph)
+                r = bench_mlp(torch, B, steps_mod, w3, lowp, timer, 100, 10, graph=graph, probe=not graph)
                 tag = ("bf16" if lowp else "f32") + ("_hipgraph" if graph else "")
                 extra["cfg3_mlp_%s" % tag] = r
                 log("  %s: %.1f us/step  %.0f steps/s  %.2f TFLOP/s  (%d launches/step)" % (
                     tag, r["ms_per_step"] * 1e3, r["steps_per_s"], r["TFLOP/s"], r["launch_calls_per_step"]))
+                if "gemm_calls" in r:
+                    log("    products (us, TFLOP/s; net of the event bracket): " + "  ".join(
+                        "%s %.1f %.0f" % (c["call"], c["us_net"], c["TFLOP/s_net"]) for c in r["gemm_calls"]))
     if "1" in sel:
         log("workload 1: tiny MLP 784-100-100-10, batch 32")
         for graph in (False, True):
