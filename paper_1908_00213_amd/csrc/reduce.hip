@@ -7,7 +7,8 @@
 //   COL  the innermost kept dimension has unit stride: (outer O, reduced R, inner I).  Each thread
 //        owns one 16-byte column group, a block is 64 column groups x 4 row lanes, and R is split
 //        over S blocks whose fp32 partial sums land in the caller's workspace and are folded by a
-//        second launch of the same kernel -- no atomics, so results are bit-reproducible;
+//        second launch of the same kernel -- no atomics, so results are bit-reproducible; a short stack
+//        of rows that fits the caches (a bias gradient) is folded by one launch of tall, narrow blocks;
 //   GEN  anything else: one thread per output element.
 // A transposed 2-d view simply swaps ROW and COL.  HBM-bound: the input is read exactly once.
 #include "common.h"
