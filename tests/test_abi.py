@@ -228,3 +228,18 @@ def _row_major(shape, isz):
         out.insert(0, acc)
         acc *= max(n, 1)
     return out
+
+
+def test_benchmark_refuses_what_it_cannot_measure():
+    """bench.py measures one GPU: more are refused with a message (no collectives in this build), and
+    without a GPU it exits with an error instead of timing anything on the host."""
+    import os
+    import subprocess
+    import sys
+    import torch
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--quick", "--no-cpu"], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 3 and "no GPU" in r.stderr and r.stdout.strip() == ""
